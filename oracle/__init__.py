@@ -1,0 +1,29 @@
+"""CPU oracle for the W8A8 Mamba-mixer path (test infrastructure only).
+
+A plain, slow, numpy implementation of what the quantized mixer computes, written from
+the paper's statement of the method (Sections 3.1-3.3, 4.2, 4.3 and 5.1).  It exists to
+check the HIP library; it is NOT a fallback.  Only tests, the smoke check and the
+benchmark's ``cpu_baseline`` leg may import it, and it imports nothing from the HIP
+package.
+
+Precision policy
+  * Every value that feeds a rounding-to-integer decision is formed in fp32 with the
+    operation order written in the function, so the HIP path can take the same decision.
+  * Everything else (the fp reference mixer, the recurrence of the selective scan, the
+    dense Hadamard product) is fp64.
+
+Pins (tests/test_oracle_*.py): Hadamard orthogonality and the Sylvester closed form,
+fold identity of the output projection, quantizer error bound / saturation / idempotence,
+nearest-rank percentile vs a sort, integer GEMM vs int64 loops, conv vs an explicit
+Toeplitz product and causality, scan vs cumulative sum / unrolled sum / chunk splitting /
+the LTI error bound of Theorem 4.1.
+
+parity unpinned: the end-to-end numbers of ``q_prefill`` / ``q_decode`` (the paper prints
+no worked example of a quantized mixer); they are pinned only relatively, against the fp
+reference mixer and through the ablation behaviour of Table "quamba_ablation".
+"""
+from .hadamard import hadamard_matrix, hadamard_factor, sylvester, paley1  # noqa: F401
+from .quantizer import (rne, quantize, requant_acc, absmax_scale, percentile_max,  # noqa: F401
+                        int_matmul)
+from .mixer import (fp_forward, calibrate, q_prefill, q_decode, selective_scan,  # noqa: F401
+                    causal_conv_fp, add_rmsnorm_quant, silu, softplus)
