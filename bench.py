@@ -1,0 +1,259 @@
+#!/usr/bin/env python3
+"""Benchmark of the W8A8 Mamba-mixer hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c1|c0|c3|c4] [--no-cpu]
+
+A "step" is one pass of the whole quantized mixer (quantize -> in_proj -> conv -> x_proj ->
+dt_proj -> scan+gate -> Hadamard+quant -> out_proj) over one batch of seeded synthetic input
+already resident in HBM.  The default workload is the Mamba-2.8B layer, batch 1, L = 2048
+(prefill); the decode configuration (batch 64, 1000 consecutive steps) is timed in the same
+run and reported under "decode".  One JSON line goes to stdout.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA, published
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="c1", choices=["c0", "c1", "c3", "c4"])
+    ap.add_argument("--decode-steps", type=int, default=1000)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle (cpu_baseline) leg")
+    ap.add_argument("--no-decode", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2410_13229_amd as Q
+    import workloads as W
+
+    Q.lib()  # fail loudly if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream()
+
+    cfg = W.CONFIGS[args.workload]
+    Bt, L = cfg.batch, cfg.seqlen
+    Dm, Di, N, R = cfg.d_model, cfg.d_inner, cfg.d_state, cfg.dt_rank
+    NX = R + 2 * N
+    M = Bt * L
+
+    def to_dev(a):
+        return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+
+    # ---- set-up on the product path: calibration by the library itself
+    w = W.make_weights(cfg)
+    calib = W.make_calibration(cfg)
+    fw = {k: to_dev(v) for k, v in w.items()}
+    qd = {
+        "W_in": torch.empty((2 * Di, Dm), dtype=torch.int8, device=dev),
+        "conv_w": torch.empty((Di, 4), dtype=torch.int8, device=dev),
+        "W_x": torch.empty((NX, Di), dtype=torch.int8, device=dev),
+        "W_dt": torch.empty((Di, R), dtype=torch.int8, device=dev),
+        "A": torch.empty((Di, N), dtype=torch.int8, device=dev),
+        "D": torch.empty((Di,), dtype=torch.int8, device=dev),
+        "W_outH": torch.empty((Dm, Di), dtype=torch.int8, device=dev),
+        "conv_b": torch.empty((Di,), dtype=torch.float32, device=dev),
+        "dt_bias": torch.empty((Di,), dtype=torch.float32, device=dev),
+    }
+    nb, Lc = calib.shape[:2]
+    cws = torch.empty(Q.quamba_calibrate_workspace_bytes(cfg, nb, Lc), dtype=torch.uint8, device=dev)
+    sc = Q.quamba_calibrate(cfg, fw, to_dev(calib), nb, Lc, 99.999, qd, cws, stream)
+    del cws, fw
+    scd = Q.scales_to_dict(sc)
+    qs, dims = Q.make_qweights(qd), Q.make_dims(cfg)  # pointer structs built once
+
+    u_np = W.make_hidden(cfg)
+    u = to_dev(u_np)
+    out = torch.empty((Bt, L, Dm), dtype=torch.float16, device=dev)
+    ssm = torch.zeros((Bt, Di, N), dtype=torch.float32, device=dev)
+    cs = torch.empty((Bt, Di, 3), dtype=torch.float16, device=dev)
+    ws = torch.empty(Q.quamba_workspace_bytes(cfg, Bt, L), dtype=torch.uint8, device=dev)
+
+    def step():
+        Q.quamba_mixer_prefill(dims, qs, sc, u, Bt, L, out, None, cs, None, ws, stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    tokens_per_s = M / (dt / args.steps)
+
+    # ---- per-stage timing with events on the launch stream (stage entry points, same shapes)
+    def timed(fn, iters=50):
+        for _ in range(5):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(iters):
+            fn()
+        e1.record(stream)
+        e1.synchronize()
+        return e0.elapsed_time(e1) / iters * 1e-3  # seconds per launch
+
+    i8 = torch.int8
+    u_q = torch.empty((M, Dm), dtype=i8, device=dev)
+    xz_q = torch.empty((M, 2 * Di), dtype=i8, device=dev)
+    x_q = torch.empty((M, Di), dtype=i8, device=dev)
+    dbc_q = torch.empty((M, NX), dtype=i8, device=dev)
+    dt_q = torch.empty((M, Di), dtype=i8, device=dev)
+    g16 = torch.empty((M, Di), dtype=torch.float16, device=dev)
+    gH_q = torch.empty((M, Di), dtype=i8, device=dev)
+    sws = torch.empty(max(Q.quamba_scan_workspace_bytes(Bt, L, Di), 256), dtype=torch.uint8, device=dev)
+    # realistic operands for the stage timings: run the chain once through the stage calls
+    Q.quamba_quantize_f16(u, u_q, M * Dm, sc.inv_s_u, stream)
+    stages = {}
+
+    def s_in():
+        Q.quamba_gemm_i8(u_q, Dm, qd["W_in"], Dm, M, 2 * Di, Dm, Di, 2 * Di, [sc.m_in_x, sc.m_in_z, sc.m_in_z],
+                         xz_q, None, 2 * Di, None, stream)
+
+    def s_conv():
+        Q.quamba_conv_silu_quant(xz_q, 2 * Di, qd["conv_w"], qd["conv_b"], Bt, L, Di, sc.m_conv, sc.inv_s_x,
+                                 sc.s_xpre, x_q, cs, stream)
+
+    def s_xp():
+        Q.quamba_gemm_i8(x_q, Di, qd["W_x"], Di, M, NX, Di, R, R + N, [sc.m_x_dt, sc.m_x_B, sc.m_x_C], dbc_q, None,
+                         NX, None, stream)
+
+    def s_dt():
+        Q.quamba_gemm_i8(dbc_q, NX, qd["W_dt"], R, M, Di, R, Di, Di, [sc.m_dt] * 3, dt_q, None, Di, None, stream)
+
+    def s_scan():
+        Q.quamba_scan_prefill(x_q, dt_q, xz_q[:, Di:], 2 * Di, dbc_q[:, R:], dbc_q[:, R + N:], NX, qd["A"], qd["D"],
+                              qd["dt_bias"], sc, Bt, L, Di, g16, None, None, sws, stream)
+
+    def s_had():
+        Q.quamba_hadamard_quant(g16, M, Di, sc.inv_s_y, gH_q, None, stream)
+
+    def s_out():
+        Q.quamba_gemm_i8(gH_q, Di, qd["W_outH"], Di, M, Dm, Di, Dm, Dm, [sc.m_out] * 3, None, out, Dm, None, stream)
+
+    def s_quant():
+        Q.quamba_quantize_f16(u, u_q, M * Dm, sc.inv_s_u, stream)
+
+    # (name, fn, bound, algorithmic work per launch: bytes for hbm, ops for mfma)
+    plan = [
+        ("quantize_u", s_quant, "hbm", 3.0 * M * Dm),
+        ("in_proj_gemm", s_in, "mfma", 2.0 * M * 2 * Di * Dm),
+        ("conv_silu_quant", s_conv, "hbm", 2.0 * M * Di),
+        ("x_proj_gemm", s_xp, "hbm", 1.0 * M * Di + NX * Di + M * NX),
+        ("dt_proj_gemm", s_dt, "hbm", 1.0 * M * R + Di * R + M * Di),
+        ("selective_scan", s_scan, "hbm", 5.0 * M * Di + 2.0 * N * M),
+        ("hadamard_quant", s_had, "hbm", 3.0 * M * Di),
+        ("out_proj_gemm", s_out, "mfma", 2.0 * M * Di * Dm),
+    ]
+    for name, fn, bound, work in plan:  # run the chain once in order so every operand is real
+        fn()
+    torch.cuda.synchronize()
+    for name, fn, bound, work in plan:
+        sec = timed(fn)
+        if bound == "hbm":
+            ach, peak, unit = work / sec / 1e9, HBM_PEAK_GBS, "GB/s"
+        else:
+            ach, peak, unit = work / sec / 1e12, INT8_PEAK_TOPS, "TOP/s"
+        stages[name] = {"us": round(sec * 1e6, 2), "bound": bound, "achieved": round(ach, 1), "peak": peak,
+                        "unit": unit, "frac": round(ach / peak, 4)}
+    dom = max(stages, key=lambda k: stages[k]["us"])
+    roof = dict(stages[dom])
+    roof.pop("us")
+    roof.update({"kernel": dom, "us_per_launch": stages[dom]["us"], "traffic": None})
+
+    # ---- decode: batch 64, consecutive steps on carried state, distinct seeded inputs
+    decode = None
+    if not args.no_decode:
+        c2 = W.CONFIGS["c2"]
+        Bd = c2.batch
+        dims2 = Q.make_dims(c2)
+        nsteps = args.decode_steps
+        rng_in = W.make_hidden(c2, batch=nsteps * Bd, seqlen=1)[:, 0, :]  # [nsteps*Bd, Dm] seeded
+        ud = to_dev(rng_in).view(nsteps, Bd, Dm)
+        ssm_np, cs_np = W.make_decode_state(c2)
+        dssm, dcs = to_dev(ssm_np), to_dev(cs_np)
+        dout = torch.empty((Bd, Dm), dtype=torch.float16, device=dev)
+        dws = torch.empty(Q.quamba_workspace_bytes(c2, Bd, 1), dtype=torch.uint8, device=dev)
+        for s in range(20):
+            Q.quamba_mixer_decode(dims2, qs, sc, ud[s], Bd, dout, dssm, dcs, None, dws, stream)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s in range(nsteps):
+            Q.quamba_mixer_decode(dims2, qs, sc, ud[s], Bd, dout, dssm, dcs, None, dws, stream)
+        torch.cuda.synchronize()
+        dsec = (time.perf_counter() - t0) / nsteps
+        # algorithmic bytes per step: int8 weights once + fp32 state read and written + activations
+        wbytes = 2 * Di * Dm + NX * Di + Di * R + Dm * Di
+        sbytes = 2 * 4 * Bd * Di * N + 2 * 2 * Bd * Di * 3
+        decode = {"workload": "c2: 2.8B layer, batch 64, L=1", "steps": nsteps, "us_per_step": round(dsec * 1e6, 2),
+                  "tokens_per_s": round(Bd / dsec, 1),
+                  "hbm_frac_algorithmic": round((wbytes + sbytes) / dsec / 1e9 / HBM_PEAK_GBS, 4),
+                  "note": "one layer's weights+state (85 MB) stay in the 256 MB last-level cache across steps"}
+
+    # ---- oracle on the host cores (reported baseline, not the target)
+    cpu = None
+    if not args.no_cpu:
+        import oracle as O
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count()
+        qw_np = {k: v.cpu().numpy() for k, v in qd.items()}
+        Ls = min(L, 2048)
+        t0 = time.perf_counter()
+        O.q_prefill(qw_np, scd, u_np[:, :Ls])
+        csec = time.perf_counter() - t0
+        cpu = {"value": round(Bt * Ls / csec, 1), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+               "sample": f"one oracle q_prefill over the first {Ls} tokens of the same workload "
+                         f"({csec:.1f} s wall; BLAS matmuls threaded, the recurrence is single-threaded numpy)"}
+
+    line = {
+        "metric": "w8a8_mamba_mixer_prefill_tokens_per_s",
+        "value": round(tokens_per_s, 1),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int8",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: single Mamba mixer layer d_model={Dm} d_inner={Di} d_state={N} "
+                               f"dt_rank={R}, batch {Bt}, L={L} prefill", "global_batch": Bt, "seq_len": L,
+                   "parallelism": "1 GPU"},
+        "roofline": roof,
+        "stages": stages,
+        "decode": decode,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

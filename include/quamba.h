@@ -1,0 +1,243 @@
+/*
+ * quamba.h - C ABI of the MI355X (gfx950) W8A8 Mamba-mixer library.
+ *
+ * The library implements the quantized Mamba block of "Quamba" (arXiv 2410.13229):
+ * static per-tensor int8 projections, fused int8 causal conv + SiLU, a selective scan that
+ * dequantizes its int8 inputs in-kernel, and a fused Hadamard transform + quantization in
+ * front of an output projection whose weight has the Hadamard matrix folded in.
+ *
+ * Conventions for every entry point
+ *   - plain C; returns 0 (QUAMBA_OK) or a negative QUAMBA_E* code; the text of the last
+ *     error of the calling thread is available from quamba_last_error().
+ *   - every pointer is a DEVICE pointer unless the comment says "host"; quamba_dims,
+ *     quamba_scales and the pointer-holding structs themselves live in host memory.
+ *   - all buffers are caller-owned; the library allocates no device memory and frees none.
+ *     Scratch comes from the caller's workspace `ws` (size from the matching
+ *     *_workspace_bytes query, 256-byte aligned).
+ *   - work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default stream)
+ *     and the call returns without synchronising, except quamba_calibrate, which
+ *     synchronises the stream to hand the scales back in host memory.
+ *   - fp16 tensors are IEEE binary16 (quamba_half = raw 16-bit storage).
+ *   - tensors are dense row-major with the last index fastest; weights are [out, in].
+ *   - notation: Dm = d_model, Di = d_inner, N = d_state (16), R = dt_rank, W = d_conv (4),
+ *     Bt = batch, L = sequence length, M = Bt*L tokens.
+ */
+#ifndef QUAMBA_H
+#define QUAMBA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef uint16_t quamba_half;
+
+enum {
+  QUAMBA_OK = 0,
+  QUAMBA_EINVAL = -1,       /* null pointer, non-positive size, misaligned buffer            */
+  QUAMBA_EUNSUPPORTED = -2, /* d_state != 16, d_conv != 4, d_inner without a k*2^m Hadamard
+                               factorisation (k in 1, 12, 20; 2^m >= 16), sizes not
+                               multiples of 16                                               */
+  QUAMBA_EWORKSPACE = -3,   /* workspace smaller than the *_workspace_bytes query            */
+  QUAMBA_EHIP = -4          /* a HIP runtime call failed                                     */
+};
+
+typedef struct {
+  int32_t d_model, d_inner, d_state, dt_rank, d_conv;
+} quamba_dims;
+
+/* fp32 master weights of one mixer (Section 3.1): in_proj rows [0,Di) give x, rows [Di,2Di)
+ * give the gate z; x_proj rows are dt | B | C. */
+typedef struct {
+  const float *W_in;    /* [2*Di, Dm] */
+  const float *conv_w;  /* [Di, W]    */
+  const float *conv_b;  /* [Di]       */
+  const float *W_x;     /* [R+2N, Di] */
+  const float *W_dt;    /* [Di, R]    */
+  const float *dt_bias; /* [Di]       */
+  const float *A_log;   /* [Di, N]    A = -exp(A_log) */
+  const float *D;       /* [Di]       */
+  const float *W_out;   /* [Dm, Di]   */
+} quamba_fp_weights;
+
+/* int8 weights (Section 3.2 Eq. 2, Section 4.2): same shapes as above; A holds q(-exp(A_log));
+ * W_outH holds q(W_out^H) with row m = H_n W_out[m, :] (Section 4.2 fold).  The two bias
+ * vectors stay fp32. */
+typedef struct {
+  int8_t *W_in, *conv_w, *W_x, *W_dt, *A, *D, *W_outH;
+  float *conv_b, *dt_bias;
+} quamba_qweights;
+
+/* Static per-tensor scales (Eq. 2; the scan input x uses the percentile maximum of Section
+ * 4.2) and the fp32 multipliers the fused epilogues apply.  Host memory.  Each multiplier is
+ * the stated product evaluated in double and rounded once to fp32:
+ *   inv_s_u = 1/s_u            m_in_x = s_u s_Win / s_xpre     m_in_z = s_u s_Win / s_z
+ *   m_conv  = s_cw s_xpre      inv_s_x = 1/s_x
+ *   m_x_dt  = s_x s_Wx / s_dtl m_x_B  = s_x s_Wx / s_B         m_x_C  = s_x s_Wx / s_C
+ *   m_dt    = s_dtl s_Wdt / s_dt                inv_s_y = 1/s_y
+ *   m_out   = s_y s_WoutH / Di   (carries the 1/n of the fold identity) */
+typedef struct {
+  float s_u, s_xpre, s_z, s_x, s_dtl, s_B, s_C, s_dt, s_y;
+  float s_Win, s_cw, s_Wx, s_Wdt, s_A, s_D, s_WoutH;
+  float inv_s_u, m_in_x, m_in_z, m_conv, inv_s_x, m_x_dt, m_x_B, m_x_C, m_dt, inv_s_y, m_out;
+} quamba_scales;
+
+/* Optional copies of the intermediates, for parity tests.  Any member may be NULL; the struct
+ * pointer itself may be NULL.  All are dense [M, cols] with M = Bt*L (decode: M = Bt). */
+typedef struct {
+  int8_t *u_q;      /* [M, Dm]    quantized block input                  */
+  int32_t *acc_in;  /* [M, 2*Di]  in_proj accumulators                   */
+  int8_t *xz_q;     /* [M, 2*Di]  x_pre | z                              */
+  int8_t *x_q;      /* [M, Di]    conv + SiLU output = scan input        */
+  int32_t *acc_x;   /* [M, R+2N]  x_proj accumulators                    */
+  int8_t *dbc_q;    /* [M, R+2N]  dt_low | B | C                         */
+  int32_t *acc_dt;  /* [M, Di]    dt_proj accumulators                   */
+  int8_t *dt_q;     /* [M, Di]                                            */
+  float *y_f32;     /* [M, Di]    gated scan output before fp16 rounding */
+  quamba_half *g16; /* [M, Di]    gated scan output, fp16                */
+  float *gH_f32;    /* [M, Di]    H_n g before quantization              */
+  int8_t *gH_q;     /* [M, Di]                                            */
+  int32_t *acc_out; /* [M, Dm]    out_proj accumulators                  */
+} quamba_taps;
+
+/* Text of the last error raised on the calling thread ("" if none).  Host pointer, valid
+ * until the next failing call on the same thread. */
+const char *quamba_last_error(void);
+
+/* ---------------------------------------------------------------------------------------
+ * Whole-mixer entry points
+ * ------------------------------------------------------------------------------------- */
+
+/* Bytes of workspace quamba_mixer_prefill / quamba_mixer_decode need for `batch` sequences
+ * of length `L` (decode: L = 1).  Returns 0 for unsupported dims. */
+size_t quamba_workspace_bytes(const quamba_dims *dims, int batch, int L);
+
+/* Bytes of workspace quamba_calibrate needs for an [nb, Lc, Dm] calibration batch. */
+size_t quamba_calibrate_workspace_bytes(const quamba_dims *dims, int nb, int Lc);
+
+/* Calibration (Section 5.1 "Quantization setup"; Section 4.2): runs the unquantized mixer in
+ * fp32 on `calib_u` [nb, Lc, Dm] (fp16), takes absmax/127 as the scale of every activation
+ * and weight, except the scan input x whose scale is the nearest-rank `x_percentile`-th
+ * percentile of |x| over the whole batch divided by 127 (rank = ceil(p/100 * count));
+ * collects the scale of y^H = H_n (y SiLU(z)); forms W_out^H; quantizes all weights into
+ * `out_q` (device buffers provided by the caller); fills `out_s` (host) including the
+ * epilogue multipliers.  Synchronises `stream` once before returning. */
+int quamba_calibrate(const quamba_dims *dims, const quamba_fp_weights *w,
+                     const quamba_half *calib_u, int nb, int Lc, double x_percentile,
+                     quamba_qweights *out_q, quamba_scales *out_s /* host */,
+                     void *ws, size_t ws_bytes, void *stream);
+
+/* Quantized mixer over whole sequences, starting from an empty conv history (Sections 4.2,
+ * 4.3): quantize u -> int8 in_proj -> int8 causal conv + SiLU -> int8 x_proj, dt_proj ->
+ * selective scan (int8 in, fp32 state, SiLU(z) gate, fp16 out) -> Hadamard + quantize ->
+ * int8 out_proj with W_out^H, fp16 out.
+ *   u          [Bt, L, Dm] fp16 in
+ *   out        [Bt, L, Dm] fp16 out
+ *   ssm_state  [Bt, Di, N] fp32: holds h_0 on entry and h_L on return; NULL = start from
+ *              zeros and do not return the state
+ *   conv_state [Bt, Di, W-1] fp16 out (last W-1 dequantized conv inputs, oldest first);
+ *              may be NULL
+ * quamba_mixer_prefill_q takes the block input already quantized with s_u (what the fused
+ * add+RMSNorm+quant of the previous block produces) and skips the first step. */
+int quamba_mixer_prefill(const quamba_dims *dims, const quamba_qweights *qw,
+                         const quamba_scales *sc /* host */, const quamba_half *u, int Bt, int L,
+                         quamba_half *out, float *ssm_state, quamba_half *conv_state,
+                         const quamba_taps *taps, void *ws, size_t ws_bytes, void *stream);
+int quamba_mixer_prefill_q(const quamba_dims *dims, const quamba_qweights *qw,
+                           const quamba_scales *sc /* host */, const int8_t *u_q, int Bt, int L,
+                           quamba_half *out, float *ssm_state, quamba_half *conv_state,
+                           const quamba_taps *taps, void *ws, size_t ws_bytes, void *stream);
+
+/* One generation step (L = 1) on carried state: same chain; the conv runs in fp32 over
+ * [conv_state, s_xpre * x_pre_q] with dequantized weights and the window shifts by one; the
+ * scan is one recurrence step.  ssm_state [Bt, Di, N] fp32 and conv_state [Bt, Di, W-1] fp16
+ * are updated in place (both required).  u, out: [Bt, Dm] fp16. */
+int quamba_mixer_decode(const quamba_dims *dims, const quamba_qweights *qw,
+                        const quamba_scales *sc /* host */, const quamba_half *u, int Bt,
+                        quamba_half *out, float *ssm_state, quamba_half *conv_state,
+                        const quamba_taps *taps, void *ws, size_t ws_bytes, void *stream);
+int quamba_mixer_decode_q(const quamba_dims *dims, const quamba_qweights *qw,
+                          const quamba_scales *sc /* host */, const int8_t *u_q, int Bt,
+                          quamba_half *out, float *ssm_state, quamba_half *conv_state,
+                          const quamba_taps *taps, void *ws, size_t ws_bytes, void *stream);
+
+/* Fused residual add + RMSNorm + static quantization between blocks (Section 4.3 "Fused
+ * RMSNorm"): res <- fp16(x_out + res) in place; u_q = q(RMSNorm(res) * weight, 1/s) with
+ * the norm taken in fp32 over the stored fp16 residual.
+ *   x_out, res [M, Dm] fp16; weight [Dm] fp16; u_q [M, Dm] int8 out. */
+int quamba_add_rmsnorm_quant(const quamba_half *x_out, quamba_half *res, const quamba_half *weight,
+                             float eps, float inv_s, int8_t *u_q, int M, int Dm, void *stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Stage entry points (the kernels the mixer calls, exposed one by one)
+ * ------------------------------------------------------------------------------------- */
+
+/* Eq. 2 in fused form: q[i] = clamp(rne(float(x[i]) * inv_s), -128, 127). x fp16, count n. */
+int quamba_quantize_f16(const quamba_half *x, int8_t *q, size_t n, float inv_s, void *stream);
+
+/* int8 GEMM on the matrix cores (Section 4.3 "Projection layers"):
+ *   acc[m, j] = sum_k A[m, k] * Wt[j, k]   (int32, exact)
+ * A [M, K] with row stride lda, Wt [N, K] with row stride ldw (K, lda, ldw multiples of 16;
+ * N and ldo multiples of 4).  Column j belongs to range 0 if j < col_end0, range 1 if
+ * j < col_end1, else range 2, and is scaled by mult[range].
+ *   out_i8  != NULL: out_i8[m, j] = clamp(rne(float(acc) * mult), -128, 127), row stride ldo
+ *   out_f16 != NULL: out_f16[m, j] = fp16(float(acc) * mult), row stride ldo
+ *   acc_out != NULL: raw accumulators, dense [M, N]
+ * At least one output is required; out_i8 and out_f16 are mutually exclusive. */
+int quamba_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, int N, int K,
+                   int col_end0, int col_end1, const float mult[3] /* host */,
+                   int8_t *out_i8, quamba_half *out_f16, int ldo, int32_t *acc_out, void *stream);
+
+/* Fused int8 causal depthwise conv + SiLU + requantization (Section 4.3 "Fused causal
+ * convolution"), width 4, empty history at t < 0 of every sequence:
+ *   x_q[b,t,d] = q(SiLU(float(sum_j w_q[d,j] * xpre_q[b,t-3+j,d]) * m_conv + conv_b[d]), inv_s_x)
+ * xpre_q has row stride ldx (it is the left half of the in_proj output); x_q is dense
+ * [Bt*L, Di].  conv_state (may be NULL) [Bt, Di, 3] fp16 receives fp16(s_xpre * xpre_q) of
+ * the last three tokens, oldest first (zeros where L < 3). */
+int quamba_conv_silu_quant(const int8_t *xpre_q, int ldx, const int8_t *w_q, const float *conv_b,
+                           int Bt, int L, int Di, float m_conv, float inv_s_x, float s_xpre,
+                           int8_t *x_q, quamba_half *conv_state, void *stream);
+
+/* Decode form of the same operator: window = [conv_state (3, fp16), s_xpre * xpre_q] in fp32,
+ * weights s_cw * w_q; conv_state shifts by one in place. xpre_q [Bt, Di] with row stride ldx. */
+int quamba_conv_step(const int8_t *xpre_q, int ldx, const int8_t *w_q, const float *conv_b,
+                     int Bt, int Di, float s_cw, float s_xpre, float inv_s_x,
+                     int8_t *x_q, quamba_half *conv_state, void *stream);
+
+/* Quantized selective scan with gate (Section 3.1 Eq. 1; Section 4.2 "Quantization for
+ * Selective SSM"): all inputs int8 and dequantized inside the kernel with the static scales:
+ *   x = s_x x_q, dt = softplus(s_dt dt_q + dt_bias), A = s_A A_q, B = s_B B_q, C = s_C C_q,
+ *   D = s_D D_q, z = s_z z_q;
+ *   h_t = exp(dt_t A) h_{t-1} + dt_t B_t x_t;  y_t = C_t . h_t + D x_t;  g_t = y_t SiLU(z_t)
+ * with fp32 state.  x_q, dt_q dense [Bt*L, Di]; z_q row stride ldz; B_q and C_q row stride
+ * ldbc (columns of the x_proj output); A_q [Di, 16]; D_q [Di]; dt_bias [Di] fp32.
+ *   g16   [Bt*L, Di] fp16 out          y_f32 (may be NULL) same shape, value before rounding
+ *   ssm_state [Bt, Di, 16] fp32 in/out (NULL: zeros in, nothing out)
+ * quamba_scan_prefill runs a chunked three-pass scan over L; it needs
+ * quamba_scan_workspace_bytes(Bt, L, Di) bytes of workspace.  quamba_scan_step is L = 1. */
+size_t quamba_scan_workspace_bytes(int Bt, int L, int Di);
+int quamba_scan_prefill(const int8_t *x_q, const int8_t *dt_q, const int8_t *z_q, int ldz,
+                        const int8_t *B_q, const int8_t *C_q, int ldbc, const int8_t *A_q,
+                        const int8_t *D_q, const float *dt_bias, const quamba_scales *sc /* host */,
+                        int Bt, int L, int Di, quamba_half *g16, float *y_f32, float *ssm_state,
+                        void *ws, size_t ws_bytes, void *stream);
+int quamba_scan_step(const int8_t *x_q, const int8_t *dt_q, const int8_t *z_q, int ldz,
+                     const int8_t *B_q, const int8_t *C_q, int ldbc, const int8_t *A_q,
+                     const int8_t *D_q, const float *dt_bias, const quamba_scales *sc /* host */,
+                     int Bt, int Di, quamba_half *g16, float *y_f32, float *ssm_state,
+                     void *stream);
+
+/* Fused fast Hadamard transform + quantization (Section 4.2 "SSM outputs", Eq. 3;
+ * Section 3.3): per row, yH = H_n g with n = k*2^m (k in 1, 12, 20; H_n = H_k (x) H_{2^m},
+ * H_12 / H_20 from the first Paley construction, H_{2^m} in natural Sylvester order), then
+ * yH_q = clamp(rne(yH * inv_s_y), -128, 127).  g [M, n] fp16; yH_q [M, n] int8;
+ * yH_f32 (may be NULL) [M, n] the transform before quantization. */
+int quamba_hadamard_quant(const quamba_half *g, int M, int n, float inv_s_y, int8_t *yH_q,
+                          float *yH_f32, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QUAMBA_H */

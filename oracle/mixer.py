@@ -162,29 +162,73 @@ def _silu32(v):
     return (v / (F32(1.0) + np.exp(-v))).astype(F32)
 
 
-def _scan_and_tail(qw, sc, t, x_q, z_q, dt_q, B_q, C_q, h0):
-    """Steps shared by prefill and decode after the projections: dequantize inside the
-    scan with the static scales (Section 4.2: int8 in, scales in floating point, half
-    precision out), gate, Hadamard + quantize (Eq. 3), output projection with the folded
-    weight and its 1/n (Section 4.2, fold identity)."""
-    Di, R, N = _dims(qw)
+def q_scan(x_q, dt_q, z_q, B_q, C_q, A_q, D_q, dt_bias, sc, h0=None):
+    """Quantized selective SSM of Section 4.2: int8 x, dt, B, C, z and int8 weights A, D go in
+    with their static scales and are dequantized inside; dt gets its fp32 bias and the
+    softplus after dequantization; the output is rounded to half precision.
+    Shapes: x_q, dt_q, z_q [Bt, L, Dsub]; B_q, C_q [Bt, L, N]; A_q [Dsub, N]; D_q, dt_bias
+    [Dsub] (any subset of channels works: channels do not interact).
+    Returns (g fp64, g16 fp16, h_L fp32)."""
     f = lambda k: float(sc[k])  # noqa: E731
-    x = f("s_x") * x_q.astype(F64)
-    dt = softplus(f("s_dt") * dt_q.astype(F64) + qw["dt_bias"].astype(F64))
-    A = f("s_A") * qw["A"].astype(F64)
-    Bm = f("s_B") * B_q.astype(F64)
-    Cm = f("s_C") * C_q.astype(F64)
-    D = f("s_D") * qw["D"].astype(F64)
-    z = f("s_z") * z_q.astype(F64)
-    g, y, h = selective_scan(x, dt, A, Bm, Cm, D, z, h0)
-    g16 = g.astype(np.float16)  # half-precision scan output
-    H = hadamard_matrix(Di).astype(F64)
-    gH = g16.astype(F64) @ H.T
-    gH_q = quantize(gH.astype(F32), sc["inv_s_y"])
-    Bt, L, _ = gH_q.shape
-    acc_out = int_matmul(gH_q.reshape(Bt * L, Di), qw["W_outH"]).reshape(Bt, L, -1)
-    out = (acc_out.astype(F32) * F32(sc["m_out"])).astype(np.float16)
-    t.update(g=g, g16=g16, gH=gH, gH_q=gH_q, acc_out=acc_out, out=out, h=h.astype(F32))
+    x = f("s_x") * np.asarray(x_q).astype(F64)
+    dt = softplus(f("s_dt") * np.asarray(dt_q).astype(F64) + np.asarray(dt_bias).astype(F64))
+    A = f("s_A") * np.asarray(A_q).astype(F64)
+    Bm = f("s_B") * np.asarray(B_q).astype(F64)
+    Cm = f("s_C") * np.asarray(C_q).astype(F64)
+    D = f("s_D") * np.asarray(D_q).astype(F64)
+    z = f("s_z") * np.asarray(z_q).astype(F64)
+    g, _, h = selective_scan(x, dt, A, Bm, Cm, D, z, h0)
+    return g, g.astype(np.float16), h.astype(F32)
+
+
+def q_hadamard_quant(g16, sc):
+    """Eq. 3: y^H = H_n g (dense fp64 product over the fp16 rows), then
+    clamp(rne(fp32(y^H) * fp32(1/s_y))).  g16 [..., n].  Returns (y^H fp64, int8)."""
+    n = g16.shape[-1]
+    H = hadamard_matrix(n).astype(F64)
+    gH = np.asarray(g16).astype(F64) @ H.T
+    return gH, quantize(gH.astype(F32), sc["inv_s_y"])
+
+
+def q_out_proj(gH_q, W_outH_q, sc):
+    """Output projection with the folded weight (Section 4.2 fold identity; Section 4.3: half
+    precision out): fp16(fp32(acc) * m_out), m_out = s_y s_WoutH / n."""
+    shp = gH_q.shape
+    acc = int_matmul(gH_q.reshape(-1, shp[-1]), W_outH_q).reshape(*shp[:-1], -1)
+    return acc, (acc.astype(F32) * F32(sc["m_out"])).astype(np.float16)
+
+
+def q_conv_prefill(xpre_q, conv_w_q, conv_b, sc):
+    """Section 4.3: x_out = (1/s_out) SiLU(Conv(x_in_q, W_q, s)), s = s_w s_xin, from an empty
+    history: integer taps, then fp32 (acc * m_conv + bias), SiLU in fp32, quantize with the
+    percentile scale of x.  xpre_q [Bt, L, Dsub]; conv_w_q [Dsub, W]; conv_b [Dsub]."""
+    Dsub = xpre_q.shape[-1]
+    conv_acc = causal_conv_fp(np.asarray(xpre_q).astype(np.int32), np.asarray(conv_w_q).astype(np.int32),
+                              np.zeros(Dsub, dtype=np.int32))
+    v = conv_acc.astype(F32) * F32(sc["m_conv"]) + np.asarray(conv_b).astype(F32)
+    return quantize(_silu32(v), sc["inv_s_x"])
+
+
+def q_conv_step(xpre_q_new, conv_state, conv_w_q, conv_b, sc):
+    """Decode form: fp32 conv over [conv_state (W-1, fp16), s_xpre * x_pre_q] with weights
+    s_cw * w_q, accumulated oldest tap first on top of the bias; then the window shifts.
+    xpre_q_new [Bt, Dsub]; conv_state [Bt, Dsub, W-1].  Returns (x_q [Bt, Dsub], new state)."""
+    new = (F32(sc["s_xpre"]) * np.asarray(xpre_q_new).astype(F32)).astype(F32)
+    win = np.concatenate([np.asarray(conv_state).astype(F32), new[:, :, None]], axis=2)
+    wdq = (F32(sc["s_cw"]) * np.asarray(conv_w_q).astype(F32)).astype(F32)
+    v = np.asarray(conv_b).astype(F32)[None, :].repeat(win.shape[0], axis=0)
+    for j in range(wdq.shape[1]):
+        v = (v + (wdq[None, :, j] * win[:, :, j]).astype(F32)).astype(F32)
+    return quantize(_silu32(v), sc["inv_s_x"]), win[:, :, 1:].astype(np.float16)
+
+
+def _scan_and_tail(qw, sc, t, x_q, z_q, dt_q, B_q, C_q, h0):
+    """Steps shared by prefill and decode after the projections: scan + gate, Hadamard +
+    quantize, output projection."""
+    g, g16, h = q_scan(x_q, dt_q, z_q, B_q, C_q, qw["A"], qw["D"], qw["dt_bias"], sc, h0)
+    gH, gH_q = q_hadamard_quant(g16, sc)
+    acc_out, out = q_out_proj(gH_q, qw["W_outH"], sc)
+    t.update(g=g, g16=g16, gH=gH, gH_q=gH_q, acc_out=acc_out, out=out, h=h)
     return t
 
 
@@ -225,12 +269,8 @@ def q_prefill(qw, sc, u=None, h0=None, u_q=None):
     xpre_q, z_q = t["xpre_q"], t["z_q"]
     Bt, L, _ = xpre_q.shape
     W = qw["conv_w"].shape[1]
-    # Section 4.3: x_out = (1/s_out) SiLU(Conv(x_in_q, W_q, s)), s = s_w s_xin.
-    conv_acc = causal_conv_fp(xpre_q.astype(np.int32), qw["conv_w"].astype(np.int32),
-                              np.zeros(Di, dtype=np.int32))
-    v = conv_acc.astype(F32) * F32(sc["m_conv"]) + qw["conv_b"].astype(F32)
-    x_q = quantize(_silu32(v), sc["inv_s_x"])
-    t.update(conv_acc=conv_acc, x_q=x_q)
+    x_q = q_conv_prefill(xpre_q, qw["conv_w"], qw["conv_b"], sc)
+    t.update(x_q=x_q)
     t.update(_projections(qw, sc, x_q))
     _scan_and_tail(qw, sc, t, x_q, z_q, t["dt_q"], t["B_q"], t["C_q"], h0)
     hist = np.zeros((Bt, W - 1, Di), dtype=F32)
@@ -249,17 +289,12 @@ def q_decode(qw, sc, u, ssm_state, conv_state, u_q=None):
     t = _in_proj(qw, sc, None if u is None else np.asarray(u)[:, None, :],
                  None if u_q is None else np.asarray(u_q)[:, None, :])
     xpre_q, z_q = t["xpre_q"], t["z_q"]  # [Bt, 1, Di]
-    new = (F32(sc["s_xpre"]) * xpre_q[:, 0, :].astype(F32)).astype(F32)  # [Bt, Di]
-    win = np.concatenate([np.asarray(conv_state).astype(F32), new[:, :, None]], axis=2)  # [Bt,Di,W]
-    wdq = (F32(sc["s_cw"]) * qw["conv_w"].astype(F32)).astype(F32)  # [Di, W]
-    v = qw["conv_b"].astype(F32)[None, :].repeat(win.shape[0], axis=0)
-    for j in range(wdq.shape[1]):
-        v = (v + wdq[None, :, j] * win[:, :, j]).astype(F32)
-    x_q = quantize(_silu32(v), sc["inv_s_x"])[:, None, :]
+    x_q2, new_state = q_conv_step(xpre_q[:, 0, :], conv_state, qw["conv_w"], qw["conv_b"], sc)
+    x_q = x_q2[:, None, :]
     t.update(x_q=x_q)
     t.update(_projections(qw, sc, x_q))
     _scan_and_tail(qw, sc, t, x_q, z_q, t["dt_q"], t["B_q"], t["C_q"], ssm_state)
-    t["conv_state"] = win[:, :, 1:].astype(np.float16)
+    t["conv_state"] = new_state
     return t
 
 

@@ -1,0 +1,275 @@
+"""ctypes binding of libquamba.so: argument marshalling only.
+
+Tensors are passed as anything with ``data_ptr()`` (torch tensors on the GPU), a raw integer
+address, or None.  Every function returns nothing and raises ``QuambaError`` when the
+library reports a non-zero code.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+__all__ = [
+    "QuambaError", "Dims", "Scales", "QWeights", "FpWeights", "Taps", "lib", "lib_path",
+    "SCALE_FIELDS", "scales_from_dict", "scales_to_dict", "make_qweights", "make_dims",
+    "quamba_last_error", "quamba_workspace_bytes", "quamba_calibrate_workspace_bytes",
+    "quamba_calibrate", "quamba_mixer_prefill", "quamba_mixer_prefill_q", "quamba_mixer_decode",
+    "quamba_mixer_decode_q", "quamba_add_rmsnorm_quant", "quamba_quantize_f16", "quamba_gemm_i8",
+    "quamba_conv_silu_quant", "quamba_conv_step", "quamba_scan_workspace_bytes",
+    "quamba_scan_prefill", "quamba_scan_step", "quamba_hadamard_quant",
+]
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+
+class QuambaError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__(f"libquamba error {code}: {text}")
+        self.code = code
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libquamba.so")
+
+
+class Dims(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("d_model", "d_inner", "d_state", "dt_rank", "d_conv")]
+
+
+SCALE_FIELDS = ("s_u", "s_xpre", "s_z", "s_x", "s_dtl", "s_B", "s_C", "s_dt", "s_y",
+                "s_Win", "s_cw", "s_Wx", "s_Wdt", "s_A", "s_D", "s_WoutH",
+                "inv_s_u", "m_in_x", "m_in_z", "m_conv", "inv_s_x", "m_x_dt", "m_x_B", "m_x_C",
+                "m_dt", "inv_s_y", "m_out")
+
+
+class Scales(C.Structure):
+    _fields_ = [(n, C.c_float) for n in SCALE_FIELDS]
+
+
+class FpWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("W_in", "conv_w", "conv_b", "W_x", "W_dt", "dt_bias",
+                                          "A_log", "D", "W_out")]
+
+
+class QWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("W_in", "conv_w", "W_x", "W_dt", "A", "D", "W_outH",
+                                          "conv_b", "dt_bias")]
+
+
+class Taps(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("u_q", "acc_in", "xz_q", "x_q", "acc_x", "dbc_q", "acc_dt",
+                                          "dt_q", "y_f32", "g16", "gH_f32", "gH_q", "acc_out")]
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return C.c_void_p(t)
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream(s):
+    if s is None:
+        return None
+    if isinstance(s, int):
+        return C.c_void_p(s)
+    return C.c_void_p(s.cuda_stream)  # torch.cuda.Stream
+
+
+def _struct_of_ptrs(cls, src):
+    """Build a pointer struct from a dict / object of tensors (missing or None -> NULL)."""
+    if src is None:
+        return None
+    if isinstance(src, cls):
+        return src
+    out = cls()
+    for name, _ in cls._fields_:
+        v = src.get(name) if isinstance(src, dict) else getattr(src, name, None)
+        setattr(out, name, None if v is None else (v if isinstance(v, int) else v.data_ptr()))
+    return out
+
+
+def make_qweights(src) -> QWeights:
+    """Pointer struct built once from a dict of device tensors (keep the dict alive)."""
+    return _struct_of_ptrs(QWeights, src)
+
+
+def make_dims(d) -> Dims:
+    return _dims(d)
+
+
+def scales_from_dict(d) -> Scales:
+    if isinstance(d, Scales):
+        return d
+    s = Scales()
+    for n in SCALE_FIELDS:
+        setattr(s, n, float(d[n]))
+    return s
+
+
+def scales_to_dict(s: Scales) -> dict:
+    return {n: getattr(s, n) for n in SCALE_FIELDS}
+
+
+def _dims(d) -> Dims:
+    if isinstance(d, Dims):
+        return d
+    if not hasattr(d, "d_model"):
+        raise TypeError("dims must expose d_model, d_inner, d_state, dt_rank, d_conv")
+    return Dims(int(d.d_model), int(d.d_inner), int(d.d_state), int(d.dt_rank), int(d.d_conv))
+
+
+def lib():
+    """The loaded shared library; raises if it has not been built."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = lib_path()
+    if not os.path.exists(path):
+        raise QuambaError(-100, f"{path} not found: build it with `python -m paper_2410_13229_amd.build`")
+    L = C.CDLL(path)
+    vp, i, f, sz = C.c_void_p, C.c_int, C.c_float, C.c_size_t
+    P = C.POINTER
+    L.quamba_last_error.restype = C.c_char_p
+    L.quamba_last_error.argtypes = []
+    L.quamba_workspace_bytes.restype = sz
+    L.quamba_workspace_bytes.argtypes = [P(Dims), i, i]
+    L.quamba_calibrate_workspace_bytes.restype = sz
+    L.quamba_calibrate_workspace_bytes.argtypes = [P(Dims), i, i]
+    L.quamba_calibrate.argtypes = [P(Dims), P(FpWeights), vp, i, i, C.c_double, P(QWeights), P(Scales), vp, sz, vp]
+    mix = [P(Dims), P(QWeights), P(Scales), vp, i, i, vp, vp, vp, P(Taps), vp, sz, vp]
+    L.quamba_mixer_prefill.argtypes = mix
+    L.quamba_mixer_prefill_q.argtypes = mix
+    dec = [P(Dims), P(QWeights), P(Scales), vp, i, vp, vp, vp, P(Taps), vp, sz, vp]
+    L.quamba_mixer_decode.argtypes = dec
+    L.quamba_mixer_decode_q.argtypes = dec
+    L.quamba_add_rmsnorm_quant.argtypes = [vp, vp, vp, f, f, vp, i, i, vp]
+    L.quamba_quantize_f16.argtypes = [vp, vp, sz, f, vp]
+    L.quamba_gemm_i8.argtypes = [vp, i, vp, i, i, i, i, i, i, P(C.c_float), vp, vp, i, vp, vp]
+    L.quamba_conv_silu_quant.argtypes = [vp, i, vp, vp, i, i, i, f, f, f, vp, vp, vp]
+    L.quamba_conv_step.argtypes = [vp, i, vp, vp, i, i, f, f, f, vp, vp, vp]
+    L.quamba_scan_workspace_bytes.restype = sz
+    L.quamba_scan_workspace_bytes.argtypes = [i, i, i]
+    L.quamba_scan_prefill.argtypes = [vp, vp, vp, i, vp, vp, i, vp, vp, vp, P(Scales), i, i, i, vp, vp, vp, vp, sz, vp]
+    L.quamba_scan_step.argtypes = [vp, vp, vp, i, vp, vp, i, vp, vp, vp, P(Scales), i, i, vp, vp, vp, vp]
+    L.quamba_hadamard_quant.argtypes = [vp, i, i, f, vp, vp, vp]
+    for name in ("quamba_calibrate", "quamba_mixer_prefill", "quamba_mixer_prefill_q", "quamba_mixer_decode",
+                 "quamba_mixer_decode_q", "quamba_add_rmsnorm_quant", "quamba_quantize_f16", "quamba_gemm_i8",
+                 "quamba_conv_silu_quant", "quamba_conv_step", "quamba_scan_prefill", "quamba_scan_step",
+                 "quamba_hadamard_quant"):
+        getattr(L, name).restype = C.c_int
+    _LIB = L
+    return L
+
+
+def _check(rc):
+    if rc != 0:
+        raise QuambaError(rc, lib().quamba_last_error().decode())
+
+
+def _nbytes(ws):
+    return 0 if ws is None else ws.numel() * ws.element_size()
+
+
+def quamba_last_error() -> str:
+    return lib().quamba_last_error().decode()
+
+
+def quamba_workspace_bytes(dims, batch, L) -> int:
+    return int(lib().quamba_workspace_bytes(C.byref(_dims(dims)), batch, L))
+
+
+def quamba_calibrate_workspace_bytes(dims, nb, Lc) -> int:
+    return int(lib().quamba_calibrate_workspace_bytes(C.byref(_dims(dims)), nb, Lc))
+
+
+def quamba_calibrate(dims, fp_weights, calib_u, nb, Lc, x_percentile, out_q, ws, stream=None) -> Scales:
+    """Returns the filled Scales struct; `out_q` (dict of preallocated tensors) is written on the device."""
+    fw = _struct_of_ptrs(FpWeights, fp_weights)
+    oq = _struct_of_ptrs(QWeights, out_q)
+    sc = Scales()
+    _check(lib().quamba_calibrate(C.byref(_dims(dims)), C.byref(fw), _ptr(calib_u), nb, Lc, float(x_percentile),
+                                  C.byref(oq), C.byref(sc), _ptr(ws), _nbytes(ws), _stream(stream)))
+    return sc
+
+
+def _taps(t):
+    t = _struct_of_ptrs(Taps, t)
+    return None if t is None else C.byref(t)
+
+
+def quamba_mixer_prefill(dims, qw, sc, u, Bt, L, out, ssm_state, conv_state, taps, ws, stream=None):
+    _check(lib().quamba_mixer_prefill(C.byref(_dims(dims)), C.byref(_struct_of_ptrs(QWeights, qw)),
+                                      C.byref(scales_from_dict(sc)), _ptr(u), Bt, L, _ptr(out), _ptr(ssm_state),
+                                      _ptr(conv_state), _taps(taps), _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def quamba_mixer_prefill_q(dims, qw, sc, u_q, Bt, L, out, ssm_state, conv_state, taps, ws, stream=None):
+    _check(lib().quamba_mixer_prefill_q(C.byref(_dims(dims)), C.byref(_struct_of_ptrs(QWeights, qw)),
+                                        C.byref(scales_from_dict(sc)), _ptr(u_q), Bt, L, _ptr(out),
+                                        _ptr(ssm_state), _ptr(conv_state), _taps(taps), _ptr(ws), _nbytes(ws),
+                                        _stream(stream)))
+
+
+def quamba_mixer_decode(dims, qw, sc, u, Bt, out, ssm_state, conv_state, taps, ws, stream=None):
+    _check(lib().quamba_mixer_decode(C.byref(_dims(dims)), C.byref(_struct_of_ptrs(QWeights, qw)),
+                                     C.byref(scales_from_dict(sc)), _ptr(u), Bt, _ptr(out), _ptr(ssm_state),
+                                     _ptr(conv_state), _taps(taps), _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def quamba_mixer_decode_q(dims, qw, sc, u_q, Bt, out, ssm_state, conv_state, taps, ws, stream=None):
+    _check(lib().quamba_mixer_decode_q(C.byref(_dims(dims)), C.byref(_struct_of_ptrs(QWeights, qw)),
+                                       C.byref(scales_from_dict(sc)), _ptr(u_q), Bt, _ptr(out), _ptr(ssm_state),
+                                       _ptr(conv_state), _taps(taps), _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def quamba_add_rmsnorm_quant(x_out, res, weight, eps, inv_s, u_q, M, Dm, stream=None):
+    _check(lib().quamba_add_rmsnorm_quant(_ptr(x_out), _ptr(res), _ptr(weight), float(eps), float(inv_s),
+                                          _ptr(u_q), M, Dm, _stream(stream)))
+
+
+def quamba_quantize_f16(x, q, n, inv_s, stream=None):
+    _check(lib().quamba_quantize_f16(_ptr(x), _ptr(q), n, float(inv_s), _stream(stream)))
+
+
+def quamba_gemm_i8(A, lda, Wt, ldw, M, N, K, col_end0, col_end1, mult, out_i8, out_f16, ldo, acc_out, stream=None):
+    m = (C.c_float * 3)(*[float(v) for v in mult])
+    _check(lib().quamba_gemm_i8(_ptr(A), lda, _ptr(Wt), ldw, M, N, K, col_end0, col_end1, m, _ptr(out_i8),
+                                _ptr(out_f16), ldo, _ptr(acc_out), _stream(stream)))
+
+
+def quamba_conv_silu_quant(xpre_q, ldx, w_q, conv_b, Bt, L, Di, m_conv, inv_s_x, s_xpre, x_q, conv_state,
+                           stream=None):
+    _check(lib().quamba_conv_silu_quant(_ptr(xpre_q), ldx, _ptr(w_q), _ptr(conv_b), Bt, L, Di, float(m_conv),
+                                        float(inv_s_x), float(s_xpre), _ptr(x_q), _ptr(conv_state),
+                                        _stream(stream)))
+
+
+def quamba_conv_step(xpre_q, ldx, w_q, conv_b, Bt, Di, s_cw, s_xpre, inv_s_x, x_q, conv_state, stream=None):
+    _check(lib().quamba_conv_step(_ptr(xpre_q), ldx, _ptr(w_q), _ptr(conv_b), Bt, Di, float(s_cw), float(s_xpre),
+                                  float(inv_s_x), _ptr(x_q), _ptr(conv_state), _stream(stream)))
+
+
+def quamba_scan_workspace_bytes(Bt, L, Di) -> int:
+    return int(lib().quamba_scan_workspace_bytes(Bt, L, Di))
+
+
+def quamba_scan_prefill(x_q, dt_q, z_q, ldz, B_q, C_q, ldbc, A_q, D_q, dt_bias, sc, Bt, L, Di, g16, y_f32,
+                        ssm_state, ws, stream=None):
+    _check(lib().quamba_scan_prefill(_ptr(x_q), _ptr(dt_q), _ptr(z_q), ldz, _ptr(B_q), _ptr(C_q), ldbc, _ptr(A_q),
+                                     _ptr(D_q), _ptr(dt_bias), C.byref(scales_from_dict(sc)), Bt, L, Di,
+                                     _ptr(g16), _ptr(y_f32), _ptr(ssm_state), _ptr(ws), _nbytes(ws),
+                                     _stream(stream)))
+
+
+def quamba_scan_step(x_q, dt_q, z_q, ldz, B_q, C_q, ldbc, A_q, D_q, dt_bias, sc, Bt, Di, g16, y_f32, ssm_state,
+                     stream=None):
+    _check(lib().quamba_scan_step(_ptr(x_q), _ptr(dt_q), _ptr(z_q), ldz, _ptr(B_q), _ptr(C_q), ldbc, _ptr(A_q),
+                                  _ptr(D_q), _ptr(dt_bias), C.byref(scales_from_dict(sc)), Bt, Di, _ptr(g16),
+                                  _ptr(y_f32), _ptr(ssm_state), _stream(stream)))
+
+
+def quamba_hadamard_quant(g, M, n, inv_s_y, yH_q, yH_f32, stream=None):
+    _check(lib().quamba_hadamard_quant(_ptr(g), M, n, float(inv_s_y), _ptr(yH_q), _ptr(yH_f32), _stream(stream)))

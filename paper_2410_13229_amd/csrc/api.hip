@@ -1,0 +1,372 @@
+// C-ABI entry points: argument checks, workspace carving and the order of kernel launches of
+// the quantized mixer (Sections 4.2 and 4.3).  No arithmetic of the method lives here.
+#include <cstring>
+
+#include "common.h"
+
+namespace quamba {
+
+// calibrate.hip
+size_t calibrate_workspace_bytes(const quamba_dims *d, int nb, int Lc);
+int calibrate(const quamba_dims *d, const quamba_fp_weights *w, const __half *calib_u, int nb, int Lc,
+              double x_percentile, quamba_qweights *oq, quamba_scales *os, void *ws, size_t ws_bytes,
+              hipStream_t st);
+
+static thread_local char g_err[512] = "";
+
+int fail(int code, const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+namespace {
+
+int check_dims(const quamba_dims *d) {
+  if (!d) return fail(QUAMBA_EINVAL, "dims is NULL");
+  if (d->d_model <= 0 || d->d_inner <= 0 || d->dt_rank <= 0)
+    return fail(QUAMBA_EINVAL, "non-positive dimension");
+  if (d->d_state != 16) return fail(QUAMBA_EUNSUPPORTED, "d_state=%d (only 16 is built)", d->d_state);
+  if (d->d_conv != 4) return fail(QUAMBA_EUNSUPPORTED, "d_conv=%d (only 4 is built)", d->d_conv);
+  if (d->d_model % 16 || d->d_inner % 16 || d->dt_rank % 16)
+    return fail(QUAMBA_EUNSUPPORTED, "d_model, d_inner and dt_rank must be multiples of 16");
+  int k, m;
+  if (!hadamard_factor(d->d_inner, &k, &m) || m < 4)
+    return fail(QUAMBA_EUNSUPPORTED, "d_inner=%d is not k*2^m with k in (1,12,20), m >= 4", d->d_inner);
+  return QUAMBA_OK;
+}
+
+// Workspace carving, shared by the size query and the launches.
+struct Plan {
+  size_t u_q, xz_q, x_q, dbc_q, dt_q, g16, gH_q, scan, total;
+};
+
+Plan make_plan(const quamba_dims *d, int Bt, int L) {
+  const size_t M = (size_t)Bt * L;
+  const size_t nx = d->dt_rank + 2 * d->d_state;
+  Plan p{};
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    const size_t at = off;
+    off += align_up(bytes, 256);
+    return at;
+  };
+  p.u_q = take(M * d->d_model);
+  p.xz_q = take(M * 2 * d->d_inner);
+  p.x_q = take(M * d->d_inner);
+  p.dbc_q = take(M * nx);
+  p.dt_q = take(M * d->d_inner);
+  p.g16 = take(M * d->d_inner * sizeof(__half));
+  p.gH_q = take(M * d->d_inner);
+  p.scan = take(L > 1 ? scan_workspace_bytes(Bt, L, d->d_inner) : 0);
+  p.total = off;
+  return p;
+}
+
+int check_q(const quamba_qweights *qw, const quamba_scales *sc) {
+  if (!qw || !sc) return fail(QUAMBA_EINVAL, "qweights or scales is NULL");
+  if (!qw->W_in || !qw->conv_w || !qw->W_x || !qw->W_dt || !qw->A || !qw->D || !qw->W_outH || !qw->conv_b ||
+      !qw->dt_bias)
+    return fail(QUAMBA_EINVAL, "a quantized weight pointer is NULL");
+  return QUAMBA_OK;
+}
+
+#define QUAMBA_TRY(expr)            \
+  do {                              \
+    int rc_ = (expr);               \
+    if (rc_ != QUAMBA_OK) return rc_; \
+  } while (0)
+
+int tap_copy(void *dst, const void *src, size_t bytes, hipStream_t st) {
+  if (dst) QUAMBA_HIP(hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, st));
+  return QUAMBA_OK;
+}
+
+// Steps shared by prefill (L >= 1, fresh conv history) and decode (L == 1, carried state).
+int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scales *sc, const __half *u,
+              const int8_t *u_q_in, int Bt, int L, bool decode, __half *out, float *ssm_state,
+              __half *conv_state, const quamba_taps *taps, void *ws, size_t ws_bytes, hipStream_t st) {
+  QUAMBA_TRY(check_dims(d));
+  QUAMBA_TRY(check_q(qw, sc));
+  if ((!u && !u_q_in) || !out) return fail(QUAMBA_EINVAL, "input or output pointer is NULL");
+  if (Bt < 1 || L < 1) return fail(QUAMBA_EINVAL, "batch=%d, L=%d must be >= 1", Bt, L);
+  if (decode && (!ssm_state || !conv_state)) return fail(QUAMBA_EINVAL, "decode needs ssm_state and conv_state");
+  const Plan p = make_plan(d, Bt, L);
+  if (!ws || ws_bytes < p.total) return fail(QUAMBA_EWORKSPACE, "workspace %zu < %zu", ws_bytes, p.total);
+  if (!aligned(ws, 256) || !aligned(out, 8) || (u && !aligned(u, 16)) || (u_q_in && !aligned(u_q_in, 16)))
+    return fail(QUAMBA_EINVAL, "workspace must be 256-byte aligned, u 16-byte, out 8-byte");
+
+  const int Dm = d->d_model, Di = d->d_inner, N = d->d_state, R = d->dt_rank, NX = R + 2 * N;
+  const int M = Bt * L;
+  char *base = static_cast<char *>(ws);
+  int8_t *u_q = reinterpret_cast<int8_t *>(base + p.u_q);
+  int8_t *xz_q = reinterpret_cast<int8_t *>(base + p.xz_q);
+  int8_t *x_q = reinterpret_cast<int8_t *>(base + p.x_q);
+  int8_t *dbc_q = reinterpret_cast<int8_t *>(base + p.dbc_q);
+  int8_t *dt_q = reinterpret_cast<int8_t *>(base + p.dt_q);
+  __half *g16 = reinterpret_cast<__half *>(base + p.g16);
+  int8_t *gH_q = reinterpret_cast<int8_t *>(base + p.gH_q);
+  const quamba_taps none{};
+  const quamba_taps &t = taps ? *taps : none;
+
+  // quantize the block input (Eq. 2)
+  const int8_t *uq = u_q_in;
+  if (!uq) {
+    QUAMBA_TRY(launch_quantize_f16(u, u_q, (size_t)M * Dm, sc->inv_s_u, st));
+    uq = u_q;
+  }
+  QUAMBA_TRY(tap_copy(t.u_q, uq, (size_t)M * Dm, st));
+
+  // in_proj: columns [0, Di) -> x_pre, [Di, 2Di) -> z
+  {
+    GemmEpilogue e{xz_q, nullptr, t.acc_in, 2 * Di, Di, 2 * Di, sc->m_in_x, sc->m_in_z, sc->m_in_z};
+    QUAMBA_TRY(launch_gemm_i8(uq, Dm, qw->W_in, Dm, M, 2 * Di, Dm, e, st));
+    QUAMBA_TRY(tap_copy(t.xz_q, xz_q, (size_t)M * 2 * Di, st));
+  }
+  // causal conv + SiLU + requantization with the percentile scale of x
+  if (decode) {
+    QUAMBA_TRY(launch_conv_step(xz_q, 2 * Di, qw->conv_w, qw->conv_b, Bt, Di, sc->s_cw, sc->s_xpre,
+                                sc->inv_s_x, x_q, conv_state, st));
+  } else {
+    QUAMBA_TRY(launch_conv_prefill(xz_q, 2 * Di, qw->conv_w, qw->conv_b, Bt, L, Di, sc->m_conv, sc->inv_s_x,
+                                   sc->s_xpre, x_q, conv_state, st));
+  }
+  QUAMBA_TRY(tap_copy(t.x_q, x_q, (size_t)M * Di, st));
+  // x_proj: columns dt_low | B | C, each with its own output scale
+  {
+    GemmEpilogue e{dbc_q, nullptr, t.acc_x, NX, R, R + N, sc->m_x_dt, sc->m_x_B, sc->m_x_C};
+    QUAMBA_TRY(launch_gemm_i8(x_q, Di, qw->W_x, Di, M, NX, Di, e, st));
+    QUAMBA_TRY(tap_copy(t.dbc_q, dbc_q, (size_t)M * NX, st));
+  }
+  // dt_proj on the dt_low columns
+  {
+    GemmEpilogue e{dt_q, nullptr, t.acc_dt, Di, Di, Di, sc->m_dt, sc->m_dt, sc->m_dt};
+    QUAMBA_TRY(launch_gemm_i8(dbc_q, NX, qw->W_dt, R, M, Di, R, e, st));
+    QUAMBA_TRY(tap_copy(t.dt_q, dt_q, (size_t)M * Di, st));
+  }
+  // selective scan + gate
+  {
+    ScanArgs a{};
+    a.x_q = x_q; a.dt_q = dt_q; a.z_q = xz_q + Di; a.ldz = 2 * Di;
+    a.B_q = dbc_q + R; a.C_q = dbc_q + R + N; a.ldbc = NX;
+    a.A_q = qw->A; a.D_q = qw->D; a.dt_bias = qw->dt_bias;
+    a.s_x = sc->s_x; a.s_dt = sc->s_dt; a.s_z = sc->s_z; a.s_B = sc->s_B; a.s_C = sc->s_C;
+    a.s_A = sc->s_A; a.s_D = sc->s_D;
+    a.Bt = Bt; a.L = L; a.Di = Di; a.g16 = g16; a.y_f32 = t.y_f32; a.ssm_state = ssm_state;
+    if (decode) {
+      QUAMBA_TRY(launch_scan_step(a, st));
+    } else {
+      QUAMBA_TRY(launch_scan_prefill(a, base + p.scan, p.total - p.scan, st));
+    }
+    QUAMBA_TRY(tap_copy(t.g16, g16, (size_t)M * Di * sizeof(__half), st));
+  }
+  // Hadamard transform + quantization (Eq. 3)
+  QUAMBA_TRY(launch_hadamard_quant(g16, M, Di, sc->inv_s_y, gH_q, t.gH_f32, st));
+  QUAMBA_TRY(tap_copy(t.gH_q, gH_q, (size_t)M * Di, st));
+  // out_proj with the folded weight, fp16 out; the multiplier carries s_y s_WoutH / n
+  {
+    GemmEpilogue e{nullptr, out, t.acc_out, Dm, Dm, Dm, sc->m_out, sc->m_out, sc->m_out};
+    QUAMBA_TRY(launch_gemm_i8(gH_q, Di, qw->W_outH, Di, M, Dm, Di, e, st));
+  }
+  return QUAMBA_OK;
+}
+
+}  // namespace
+}  // namespace quamba
+
+using namespace quamba;
+
+extern "C" {
+
+const char *quamba_last_error(void) { return g_err; }
+
+size_t quamba_workspace_bytes(const quamba_dims *dims, int batch, int L) {
+  if (check_dims(dims) != QUAMBA_OK || batch < 1 || L < 1) return 0;
+  return make_plan(dims, batch, L).total;
+}
+
+size_t quamba_calibrate_workspace_bytes(const quamba_dims *dims, int nb, int Lc) {
+  if (check_dims(dims) != QUAMBA_OK || nb < 1 || Lc < 1) return 0;
+  return calibrate_workspace_bytes(dims, nb, Lc);
+}
+
+int quamba_calibrate(const quamba_dims *dims, const quamba_fp_weights *w, const quamba_half *calib_u, int nb,
+                     int Lc, double x_percentile, quamba_qweights *out_q, quamba_scales *out_s, void *ws,
+                     size_t ws_bytes, void *stream) {
+  QUAMBA_TRY(check_dims(dims));
+  if (!w || !calib_u || !out_q || !out_s || !ws) return fail(QUAMBA_EINVAL, "calibrate: NULL pointer");
+  if (!w->W_in || !w->conv_w || !w->conv_b || !w->W_x || !w->W_dt || !w->dt_bias || !w->A_log || !w->D ||
+      !w->W_out)
+    return fail(QUAMBA_EINVAL, "calibrate: a master weight pointer is NULL");
+  if (!out_q->W_in || !out_q->conv_w || !out_q->W_x || !out_q->W_dt || !out_q->A || !out_q->D ||
+      !out_q->W_outH || !out_q->conv_b || !out_q->dt_bias)
+    return fail(QUAMBA_EINVAL, "calibrate: an output weight pointer is NULL");
+  if (nb < 1 || Lc < 1) return fail(QUAMBA_EINVAL, "calibrate: nb=%d Lc=%d", nb, Lc);
+  if (!(x_percentile > 0.0 && x_percentile <= 100.0))
+    return fail(QUAMBA_EINVAL, "calibrate: percentile %g outside (0, 100]", x_percentile);
+  if (!aligned(ws, 256) || !aligned(w->W_out, 16))
+    return fail(QUAMBA_EINVAL, "calibrate: workspace must be 256-byte aligned, W_out 16-byte");
+  return calibrate(dims, w, reinterpret_cast<const __half *>(calib_u), nb, Lc, x_percentile, out_q, out_s, ws,
+                   ws_bytes, as_stream(stream));
+}
+
+int quamba_mixer_prefill(const quamba_dims *dims, const quamba_qweights *qw, const quamba_scales *sc,
+                         const quamba_half *u, int Bt, int L, quamba_half *out, float *ssm_state,
+                         quamba_half *conv_state, const quamba_taps *taps, void *ws, size_t ws_bytes,
+                         void *stream) {
+  if (!u) return fail(QUAMBA_EINVAL, "u is NULL");
+  return run_mixer(dims, qw, sc, reinterpret_cast<const __half *>(u), nullptr, Bt, L, false,
+                   reinterpret_cast<__half *>(out), ssm_state, reinterpret_cast<__half *>(conv_state), taps, ws,
+                   ws_bytes, as_stream(stream));
+}
+
+int quamba_mixer_prefill_q(const quamba_dims *dims, const quamba_qweights *qw, const quamba_scales *sc,
+                           const int8_t *u_q, int Bt, int L, quamba_half *out, float *ssm_state,
+                           quamba_half *conv_state, const quamba_taps *taps, void *ws, size_t ws_bytes,
+                           void *stream) {
+  if (!u_q) return fail(QUAMBA_EINVAL, "u_q is NULL");
+  return run_mixer(dims, qw, sc, nullptr, u_q, Bt, L, false, reinterpret_cast<__half *>(out), ssm_state,
+                   reinterpret_cast<__half *>(conv_state), taps, ws, ws_bytes, as_stream(stream));
+}
+
+int quamba_mixer_decode(const quamba_dims *dims, const quamba_qweights *qw, const quamba_scales *sc,
+                        const quamba_half *u, int Bt, quamba_half *out, float *ssm_state,
+                        quamba_half *conv_state, const quamba_taps *taps, void *ws, size_t ws_bytes,
+                        void *stream) {
+  if (!u) return fail(QUAMBA_EINVAL, "u is NULL");
+  return run_mixer(dims, qw, sc, reinterpret_cast<const __half *>(u), nullptr, Bt, 1, true,
+                   reinterpret_cast<__half *>(out), ssm_state, reinterpret_cast<__half *>(conv_state), taps, ws,
+                   ws_bytes, as_stream(stream));
+}
+
+int quamba_mixer_decode_q(const quamba_dims *dims, const quamba_qweights *qw, const quamba_scales *sc,
+                          const int8_t *u_q, int Bt, quamba_half *out, float *ssm_state,
+                          quamba_half *conv_state, const quamba_taps *taps, void *ws, size_t ws_bytes,
+                          void *stream) {
+  if (!u_q) return fail(QUAMBA_EINVAL, "u_q is NULL");
+  return run_mixer(dims, qw, sc, nullptr, u_q, Bt, 1, true, reinterpret_cast<__half *>(out), ssm_state,
+                   reinterpret_cast<__half *>(conv_state), taps, ws, ws_bytes, as_stream(stream));
+}
+
+int quamba_add_rmsnorm_quant(const quamba_half *x_out, quamba_half *res, const quamba_half *weight, float eps,
+                             float inv_s, int8_t *u_q, int M, int Dm, void *stream) {
+  if (!x_out || !res || !weight || !u_q) return fail(QUAMBA_EINVAL, "NULL pointer");
+  if (M < 0 || Dm <= 0) return fail(QUAMBA_EINVAL, "M=%d, Dm=%d", M, Dm);
+  if (M == 0) return QUAMBA_OK;
+  if (!aligned(x_out, 16) || !aligned(res, 16) || !aligned(weight, 16) || !aligned(u_q, 8))
+    return fail(QUAMBA_EINVAL, "add_rmsnorm_quant: buffers must be 16-byte aligned");
+  return launch_add_rmsnorm_quant(reinterpret_cast<const __half *>(x_out), reinterpret_cast<__half *>(res),
+                                  reinterpret_cast<const __half *>(weight), eps, inv_s, u_q, M, Dm,
+                                  as_stream(stream));
+}
+
+int quamba_quantize_f16(const quamba_half *x, int8_t *q, size_t n, float inv_s, void *stream) {
+  if (!x || !q) return fail(QUAMBA_EINVAL, "NULL pointer");
+  if (!aligned(x, 16) || !aligned(q, 8)) return fail(QUAMBA_EINVAL, "quantize: x 16-byte, q 8-byte aligned");
+  return launch_quantize_f16(reinterpret_cast<const __half *>(x), q, n, inv_s, as_stream(stream));
+}
+
+int quamba_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, int N, int K, int col_end0,
+                   int col_end1, const float mult[3], int8_t *out_i8, quamba_half *out_f16, int ldo,
+                   int32_t *acc_out, void *stream) {
+  if (!A || !Wt || !mult) return fail(QUAMBA_EINVAL, "NULL pointer");
+  if (!out_i8 && !out_f16 && !acc_out) return fail(QUAMBA_EINVAL, "gemm: no output requested");
+  if (out_i8 && out_f16) return fail(QUAMBA_EINVAL, "gemm: out_i8 and out_f16 are mutually exclusive");
+  if (M < 0 || N <= 0 || K <= 0) return fail(QUAMBA_EINVAL, "gemm: M=%d N=%d K=%d", M, N, K);
+  if (K % 16 || lda % 16 || ldw % 16 || lda < K || ldw < K)
+    return fail(QUAMBA_EUNSUPPORTED, "gemm: K, lda, ldw must be multiples of 16 with lda, ldw >= K");
+  if (N % 4 || ((out_i8 || out_f16) && (ldo % 4 || ldo < N)))
+    return fail(QUAMBA_EUNSUPPORTED, "gemm: N and ldo must be multiples of 4 with ldo >= N");
+  if (!aligned(A, 16) || !aligned(Wt, 16) || (out_i8 && !aligned(out_i8, 4)) || (out_f16 && !aligned(out_f16, 8)) ||
+      (acc_out && !aligned(acc_out, 16)))
+    return fail(QUAMBA_EINVAL, "gemm: misaligned buffer");
+  if (M == 0) return QUAMBA_OK;
+  GemmEpilogue e{out_i8, reinterpret_cast<__half *>(out_f16), acc_out, ldo, col_end0, col_end1, mult[0], mult[1],
+                 mult[2]};
+  return launch_gemm_i8(A, lda, Wt, ldw, M, N, K, e, as_stream(stream));
+}
+
+int quamba_conv_silu_quant(const int8_t *xpre_q, int ldx, const int8_t *w_q, const float *conv_b, int Bt, int L,
+                           int Di, float m_conv, float inv_s_x, float s_xpre, int8_t *x_q,
+                           quamba_half *conv_state, void *stream) {
+  if (!xpre_q || !w_q || !conv_b || !x_q) return fail(QUAMBA_EINVAL, "NULL pointer");
+  if (Bt < 1 || L < 1 || Di < 4) return fail(QUAMBA_EINVAL, "conv: Bt=%d L=%d Di=%d", Bt, L, Di);
+  if (Di % 4 || ldx % 4 || ldx < Di) return fail(QUAMBA_EUNSUPPORTED, "conv: Di and ldx must be multiples of 4");
+  if (!aligned(xpre_q, 4) || !aligned(w_q, 16) || !aligned(conv_b, 16) || !aligned(x_q, 4))
+    return fail(QUAMBA_EINVAL, "conv: misaligned buffer");
+  return launch_conv_prefill(xpre_q, ldx, w_q, conv_b, Bt, L, Di, m_conv, inv_s_x, s_xpre, x_q,
+                             reinterpret_cast<__half *>(conv_state), as_stream(stream));
+}
+
+int quamba_conv_step(const int8_t *xpre_q, int ldx, const int8_t *w_q, const float *conv_b, int Bt, int Di,
+                     float s_cw, float s_xpre, float inv_s_x, int8_t *x_q, quamba_half *conv_state,
+                     void *stream) {
+  if (!xpre_q || !w_q || !conv_b || !x_q || !conv_state) return fail(QUAMBA_EINVAL, "NULL pointer");
+  if (Bt < 1 || Di < 4) return fail(QUAMBA_EINVAL, "conv_step: Bt=%d Di=%d", Bt, Di);
+  if (Di % 4 || ldx % 4 || ldx < Di) return fail(QUAMBA_EUNSUPPORTED, "conv_step: Di and ldx multiples of 4");
+  if (!aligned(xpre_q, 4) || !aligned(w_q, 16) || !aligned(conv_b, 16) || !aligned(x_q, 4) ||
+      !aligned(conv_state, 8))
+    return fail(QUAMBA_EINVAL, "conv_step: misaligned buffer");
+  return launch_conv_step(xpre_q, ldx, w_q, conv_b, Bt, Di, s_cw, s_xpre, inv_s_x, x_q,
+                          reinterpret_cast<__half *>(conv_state), as_stream(stream));
+}
+
+size_t quamba_scan_workspace_bytes(int Bt, int L, int Di) {
+  if (Bt < 1 || L < 1 || Di < 1) return 0;
+  return scan_workspace_bytes(Bt, L, Di);
+}
+
+static int fill_scan(ScanArgs &a, const int8_t *x_q, const int8_t *dt_q, const int8_t *z_q, int ldz,
+                     const int8_t *B_q, const int8_t *C_q, int ldbc, const int8_t *A_q, const int8_t *D_q,
+                     const float *dt_bias, const quamba_scales *sc, int Bt, int L, int Di, quamba_half *g16,
+                     float *y_f32, float *ssm_state) {
+  if (!x_q || !dt_q || !z_q || !B_q || !C_q || !A_q || !D_q || !dt_bias || !sc || !g16)
+    return fail(QUAMBA_EINVAL, "scan: NULL pointer");
+  if (Bt < 1 || L < 1 || Di < 1 || ldz < Di || ldbc < 16) return fail(QUAMBA_EINVAL, "scan: bad sizes");
+  if (!aligned(A_q, 16) || (ssm_state && !aligned(ssm_state, 16)) || !aligned(B_q, 4) || !aligned(C_q, 4) ||
+      ldbc % 4)
+    return fail(QUAMBA_EINVAL, "scan: A_q / ssm_state must be 16-byte aligned, B_q / C_q / ldbc 4-byte");
+  a.x_q = x_q; a.dt_q = dt_q; a.z_q = z_q; a.ldz = ldz; a.B_q = B_q; a.C_q = C_q; a.ldbc = ldbc;
+  a.A_q = A_q; a.D_q = D_q; a.dt_bias = dt_bias;
+  a.s_x = sc->s_x; a.s_dt = sc->s_dt; a.s_z = sc->s_z; a.s_B = sc->s_B; a.s_C = sc->s_C; a.s_A = sc->s_A;
+  a.s_D = sc->s_D;
+  a.Bt = Bt; a.L = L; a.Di = Di; a.g16 = reinterpret_cast<__half *>(g16); a.y_f32 = y_f32;
+  a.ssm_state = ssm_state;
+  return QUAMBA_OK;
+}
+
+int quamba_scan_prefill(const int8_t *x_q, const int8_t *dt_q, const int8_t *z_q, int ldz, const int8_t *B_q,
+                        const int8_t *C_q, int ldbc, const int8_t *A_q, const int8_t *D_q, const float *dt_bias,
+                        const quamba_scales *sc, int Bt, int L, int Di, quamba_half *g16, float *y_f32,
+                        float *ssm_state, void *ws, size_t ws_bytes, void *stream) {
+  ScanArgs a{};
+  QUAMBA_TRY(fill_scan(a, x_q, dt_q, z_q, ldz, B_q, C_q, ldbc, A_q, D_q, dt_bias, sc, Bt, L, Di, g16, y_f32,
+                       ssm_state));
+  if (!ws || !aligned(ws, 256)) return fail(QUAMBA_EINVAL, "scan: workspace NULL or not 256-byte aligned");
+  return launch_scan_prefill(a, ws, ws_bytes, as_stream(stream));
+}
+
+int quamba_scan_step(const int8_t *x_q, const int8_t *dt_q, const int8_t *z_q, int ldz, const int8_t *B_q,
+                     const int8_t *C_q, int ldbc, const int8_t *A_q, const int8_t *D_q, const float *dt_bias,
+                     const quamba_scales *sc, int Bt, int Di, quamba_half *g16, float *y_f32, float *ssm_state,
+                     void *stream) {
+  ScanArgs a{};
+  QUAMBA_TRY(fill_scan(a, x_q, dt_q, z_q, ldz, B_q, C_q, ldbc, A_q, D_q, dt_bias, sc, Bt, 1, Di, g16, y_f32,
+                       ssm_state));
+  if (!ssm_state) return fail(QUAMBA_EINVAL, "scan_step: ssm_state is required");
+  return launch_scan_step(a, as_stream(stream));
+}
+
+int quamba_hadamard_quant(const quamba_half *g, int M, int n, float inv_s_y, int8_t *yH_q, float *yH_f32,
+                          void *stream) {
+  if (!g || !yH_q) return fail(QUAMBA_EINVAL, "NULL pointer");
+  if (M < 0 || n <= 0) return fail(QUAMBA_EINVAL, "hadamard: M=%d n=%d", M, n);
+  if (!aligned(g, 16) || !aligned(yH_q, 16) || (yH_f32 && !aligned(yH_f32, 16)))
+    return fail(QUAMBA_EINVAL, "hadamard: buffers must be 16-byte aligned");
+  return launch_hadamard_quant(reinterpret_cast<const __half *>(g), M, n, inv_s_y, yH_q, yH_f32,
+                               as_stream(stream));
+}
+
+}  // extern "C"

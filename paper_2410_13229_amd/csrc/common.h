@@ -1,0 +1,85 @@
+// Shared host-side helpers of the library: error reporting and launch checks.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+
+#include "quamba.h"
+
+namespace quamba {
+
+// Per-thread text of the last error; returns `code` so callers can `return fail(...)`.
+int fail(int code, const char *fmt, ...);
+
+inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+// (k, m) with n = k * 2^m, k in {1, 12, 20}; false if there is none.
+bool hadamard_factor(int n, int *k, int *m);
+
+}  // namespace quamba
+
+#define QUAMBA_HIP(expr)                                                                       \
+  do {                                                                                         \
+    hipError_t e_ = (expr);                                                                    \
+    if (e_ != hipSuccess)                                                                      \
+      return ::quamba::fail(QUAMBA_EHIP, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), \
+                            __FILE__, __LINE__);                                               \
+  } while (0)
+
+#define QUAMBA_LAUNCH_CHECK() QUAMBA_HIP(hipGetLastError())
+
+// ---- internal launchers (one per .hip file); all enqueue on `st` and return a QUAMBA_* code
+namespace quamba {
+
+struct GemmEpilogue {
+  int8_t *out_i8;
+  __half *out_f16;
+  int32_t *acc;
+  int ldo;
+  int e0, e1;
+  float m0, m1, m2;
+};
+
+int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, int N, int K,
+                   const GemmEpilogue &epi, hipStream_t st);
+
+int launch_quantize_f16(const __half *x, int8_t *q, size_t n, float inv_s, hipStream_t st);
+
+int launch_conv_prefill(const int8_t *xpre_q, int ldx, const int8_t *w_q, const float *conv_b,
+                        int Bt, int L, int Di, float m_conv, float inv_s_x, float s_xpre,
+                        int8_t *x_q, __half *conv_state, hipStream_t st);
+
+int launch_conv_step(const int8_t *xpre_q, int ldx, const int8_t *w_q, const float *conv_b, int Bt,
+                     int Di, float s_cw, float s_xpre, float inv_s_x, int8_t *x_q,
+                     __half *conv_state, hipStream_t st);
+
+int launch_add_rmsnorm_quant(const __half *x_out, __half *res, const __half *weight, float eps,
+                             float inv_s, int8_t *u_q, int M, int Dm, hipStream_t st);
+
+struct ScanArgs {
+  const int8_t *x_q, *dt_q, *z_q, *B_q, *C_q, *A_q, *D_q;
+  const float *dt_bias;
+  int ldz, ldbc;
+  float s_x, s_dt, s_z, s_B, s_C, s_A, s_D;
+  int Bt, L, Di;
+  __half *g16;
+  float *y_f32;
+  float *ssm_state;
+};
+
+size_t scan_workspace_bytes(int Bt, int L, int Di);
+int launch_scan_prefill(const ScanArgs &a, void *ws, size_t ws_bytes, hipStream_t st);
+int launch_scan_step(const ScanArgs &a, hipStream_t st);
+
+int launch_hadamard_quant(const __half *g, int M, int n, float inv_s_y, int8_t *yH_q, float *yH_f32,
+                          hipStream_t st);
+
+}  // namespace quamba

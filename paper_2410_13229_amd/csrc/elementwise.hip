@@ -1,0 +1,263 @@
+// Bandwidth-bound stages around the GEMMs: input quantization (Eq. 2), the fused int8 causal
+// conv + SiLU + requantization in its prefill and decode forms (Section 4.3 "Fused causal
+// convolution"), and the fused residual add + RMSNorm + quantization (Section 4.3 "Fused
+// RMSNorm").  Every kernel reads and writes each byte once, with 4- to 16-byte accesses per
+// lane that are contiguous across the wavefront.
+#include "common.h"
+
+namespace quamba {
+namespace {
+
+__device__ __forceinline__ int q8(float v) {
+  v = __builtin_rintf(v);
+  v = fminf(fmaxf(v, -128.f), 127.f);
+  return static_cast<int>(v);
+}
+
+__device__ __forceinline__ float silu_f(float v) {
+  // v / (1 + exp(-v)) with the hardware exp2
+  return v / (1.f + __builtin_amdgcn_exp2f(-v * 1.44269504088896340736f));
+}
+
+// ------------------------------------------------------------------ quantize fp16 -> int8
+__global__ __launch_bounds__(256) void quantize_f16_kernel(const __half *__restrict__ x,
+                                                           int8_t *__restrict__ q, size_t n,
+                                                           float inv_s) {
+  const size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 8;
+  if (i + 8 <= n) {
+    union {
+      uint4 u;
+      __half h[8];
+    } in;
+    in.u = *reinterpret_cast<const uint4 *>(x + i);
+    unsigned lo = 0, hi = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      lo |= (static_cast<unsigned>(q8(__half2float(in.h[e]) * inv_s)) & 0xffu) << (8 * e);
+      hi |= (static_cast<unsigned>(q8(__half2float(in.h[e + 4]) * inv_s)) & 0xffu) << (8 * e);
+    }
+    *reinterpret_cast<uint2 *>(q + i) = make_uint2(lo, hi);
+  } else {
+    for (size_t j = i; j < n; ++j) q[j] = static_cast<int8_t>(q8(__half2float(x[j]) * inv_s));
+  }
+}
+
+// ------------------------------------------------------------------ conv, prefill
+// One thread owns 4 adjacent channels (one 32-bit word per token) and walks TT consecutive
+// tokens of one sequence, keeping the three previous words in registers, so each input word
+// is read once per tile (plus a 3-token halo).
+constexpr int CONV_TT = 16;
+
+__global__ __launch_bounds__(256) void conv_prefill_kernel(
+    const int8_t *__restrict__ xpre, int ldx, const int8_t *__restrict__ wq,
+    const float *__restrict__ bias, int L, int Di, float m_conv, float inv_s_x, float s_xpre,
+    int8_t *__restrict__ xq, __half *__restrict__ conv_state) {
+  const int c4 = blockIdx.x * 256 + threadIdx.x;  // channel group
+  if (c4 * 4 >= Di) return;
+  const int d0 = c4 * 4;
+  const int b = blockIdx.z;
+  const int t0 = blockIdx.y * CONV_TT;
+  const int t1 = min(t0 + CONV_TT, L);
+
+  // weights of the 4 channels: 16 bytes, [d][j]
+  const uint4 wv = *reinterpret_cast<const uint4 *>(wq + (size_t)d0 * 4);
+  const unsigned wword[4] = {wv.x, wv.y, wv.z, wv.w};
+  int w[4][4];
+#pragma unroll
+  for (int c = 0; c < 4; ++c)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) w[c][j] = static_cast<int8_t>(wword[c] >> (8 * j));
+  const float4 bv = *reinterpret_cast<const float4 *>(bias + d0);
+  const float bb[4] = {bv.x, bv.y, bv.z, bv.w};
+
+  const int8_t *src = xpre + (size_t)b * L * ldx + d0;
+  int8_t *dst = xq + (size_t)b * L * Di + d0;
+  auto ld = [&](int t) -> unsigned {
+    return t >= 0 ? *reinterpret_cast<const unsigned *>(src + (size_t)t * ldx) : 0u;
+  };
+  unsigned h0 = ld(t0 - 3), h1 = ld(t0 - 2), h2 = ld(t0 - 1);
+  for (int t = t0; t < t1; ++t) {
+    const unsigned h3 = ld(t);
+    unsigned p = 0;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const int a = w[c][0] * static_cast<int8_t>(h0 >> (8 * c)) +
+                    w[c][1] * static_cast<int8_t>(h1 >> (8 * c)) +
+                    w[c][2] * static_cast<int8_t>(h2 >> (8 * c)) +
+                    w[c][3] * static_cast<int8_t>(h3 >> (8 * c));
+      const float v = __fadd_rn(__fmul_rn(static_cast<float>(a), m_conv), bb[c]);
+      p |= (static_cast<unsigned>(q8(silu_f(v) * inv_s_x)) & 0xffu) << (8 * c);
+    }
+    *reinterpret_cast<unsigned *>(dst + (size_t)t * Di) = p;
+    h0 = h1;
+    h1 = h2;
+    h2 = h3;
+  }
+  // the tile holding the sequence end also emits the carried window [L-3, L-2, L-1]
+  if (conv_state != nullptr && t1 == L) {
+    const unsigned hh[3] = {h0, h1, h2};
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+      for (int j = 0; j < 3; ++j) {
+        const int tj = L - 3 + j;
+        const float v = tj >= 0 ? s_xpre * static_cast<float>(static_cast<int8_t>(hh[j] >> (8 * c))) : 0.f;
+        conv_state[((size_t)b * Di + d0 + c) * 3 + j] = __float2half_rn(v);
+      }
+  }
+}
+
+// ------------------------------------------------------------------ conv, decode step
+__global__ __launch_bounds__(256) void conv_step_kernel(const int8_t *__restrict__ xpre, int ldx,
+                                                        const int8_t *__restrict__ wq,
+                                                        const float *__restrict__ bias, int Bt, int Di,
+                                                        float s_cw, float s_xpre, float inv_s_x,
+                                                        int8_t *__restrict__ xq,
+                                                        __half *__restrict__ conv_state) {
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;  // (b, channel group of 4)
+  const int groups = Di / 4;
+  if (idx >= (size_t)Bt * groups) return;
+  const int b = static_cast<int>(idx / groups);
+  const int d0 = static_cast<int>(idx % groups) * 4;
+  const unsigned xin = *reinterpret_cast<const unsigned *>(xpre + (size_t)b * ldx + d0);
+  const uint4 wv = *reinterpret_cast<const uint4 *>(wq + (size_t)d0 * 4);
+  const unsigned wword[4] = {wv.x, wv.y, wv.z, wv.w};
+  const float4 bv = *reinterpret_cast<const float4 *>(bias + d0);
+  const float bb[4] = {bv.x, bv.y, bv.z, bv.w};
+  // state of 4 channels: 12 contiguous halves = 24 bytes
+  __half *cs = conv_state + ((size_t)b * Di + d0) * 3;
+  union {
+    uint2 u[3];
+    __half h[12];
+  } st;
+  st.u[0] = reinterpret_cast<const uint2 *>(cs)[0];
+  st.u[1] = reinterpret_cast<const uint2 *>(cs)[1];
+  st.u[2] = reinterpret_cast<const uint2 *>(cs)[2];
+  unsigned p = 0;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    const float xn = __fmul_rn(s_xpre, static_cast<float>(static_cast<int8_t>(xin >> (8 * c))));
+    const float win[4] = {__half2float(st.h[3 * c]), __half2float(st.h[3 * c + 1]),
+                          __half2float(st.h[3 * c + 2]), xn};
+    float v = bb[c];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const float wj = __fmul_rn(s_cw, static_cast<float>(static_cast<int8_t>(wword[c] >> (8 * j))));
+      v = __fadd_rn(v, __fmul_rn(wj, win[j]));
+    }
+    p |= (static_cast<unsigned>(q8(silu_f(v) * inv_s_x)) & 0xffu) << (8 * c);
+    st.h[3 * c] = st.h[3 * c + 1];
+    st.h[3 * c + 1] = st.h[3 * c + 2];
+    st.h[3 * c + 2] = __float2half_rn(xn);
+  }
+  *reinterpret_cast<unsigned *>(xq + (size_t)b * Di + d0) = p;
+  reinterpret_cast<uint2 *>(cs)[0] = st.u[0];
+  reinterpret_cast<uint2 *>(cs)[1] = st.u[1];
+  reinterpret_cast<uint2 *>(cs)[2] = st.u[2];
+}
+
+// ------------------------------------------------------------------ add + RMSNorm + quant
+// One workgroup per token row; each thread keeps its share of the row in registers between
+// the reduction and the normalisation, so the row is read once.
+constexpr int RMS_MAX_PER_THREAD = 4;  // groups of 8 halves per thread: Dm <= 8192
+
+__global__ __launch_bounds__(256) void add_rmsnorm_quant_kernel(const __half *__restrict__ x_out,
+                                                                __half *__restrict__ res,
+                                                                const __half *__restrict__ weight,
+                                                                float eps, float inv_s,
+                                                                int8_t *__restrict__ u_q, int Dm) {
+  const size_t row = blockIdx.x;
+  const int ngroups = Dm / 8;
+  float vals[RMS_MAX_PER_THREAD][8];
+  float ss = 0.f;
+#pragma unroll
+  for (int i = 0; i < RMS_MAX_PER_THREAD; ++i) {
+    const int g = threadIdx.x + i * 256;
+    if (g < ngroups) {
+      union {
+        uint4 u;
+        __half h[8];
+      } a, r;
+      a.u = *reinterpret_cast<const uint4 *>(x_out + row * Dm + (size_t)g * 8);
+      r.u = *reinterpret_cast<const uint4 *>(res + row * Dm + (size_t)g * 8);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const __half s = __float2half_rn(__half2float(a.h[e]) + __half2float(r.h[e]));
+        r.h[e] = s;
+        const float f = __half2float(s);
+        vals[i][e] = f;
+        ss += f * f;
+      }
+      *reinterpret_cast<uint4 *>(res + row * Dm + (size_t)g * 8) = r.u;
+    }
+  }
+  __shared__ float part[4];
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off);
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  const float tot = part[0] + part[1] + part[2] + part[3];
+  const float rinv = 1.f / sqrtf(tot / static_cast<float>(Dm) + eps);
+#pragma unroll
+  for (int i = 0; i < RMS_MAX_PER_THREAD; ++i) {
+    const int g = threadIdx.x + i * 256;
+    if (g < ngroups) {
+      union {
+        uint4 u;
+        __half h[8];
+      } wv;
+      wv.u = *reinterpret_cast<const uint4 *>(weight + (size_t)g * 8);
+      unsigned lo = 0, hi = 0;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        lo |= (static_cast<unsigned>(q8(vals[i][e] * rinv * __half2float(wv.h[e]) * inv_s)) & 0xffu) << (8 * e);
+        hi |= (static_cast<unsigned>(q8(vals[i][e + 4] * rinv * __half2float(wv.h[e + 4]) * inv_s)) & 0xffu)
+              << (8 * e);
+      }
+      *reinterpret_cast<uint2 *>(u_q + row * Dm + (size_t)g * 8) = make_uint2(lo, hi);
+    }
+  }
+}
+
+}  // namespace
+
+int launch_quantize_f16(const __half *x, int8_t *q, size_t n, float inv_s, hipStream_t st) {
+  if (n == 0) return QUAMBA_OK;
+  const size_t blocks = (n + 2047) / 2048;
+  hipLaunchKernelGGL(quantize_f16_kernel, dim3((unsigned)blocks), dim3(256), 0, st, x, q, n, inv_s);
+  QUAMBA_LAUNCH_CHECK();
+  return QUAMBA_OK;
+}
+
+int launch_conv_prefill(const int8_t *xpre_q, int ldx, const int8_t *w_q, const float *conv_b, int Bt,
+                        int L, int Di, float m_conv, float inv_s_x, float s_xpre, int8_t *x_q,
+                        __half *conv_state, hipStream_t st) {
+  dim3 grid((Di / 4 + 255) / 256, (L + CONV_TT - 1) / CONV_TT, Bt);
+  hipLaunchKernelGGL(conv_prefill_kernel, grid, dim3(256), 0, st, xpre_q, ldx, w_q, conv_b, L, Di,
+                     m_conv, inv_s_x, s_xpre, x_q, conv_state);
+  QUAMBA_LAUNCH_CHECK();
+  return QUAMBA_OK;
+}
+
+int launch_conv_step(const int8_t *xpre_q, int ldx, const int8_t *w_q, const float *conv_b, int Bt,
+                     int Di, float s_cw, float s_xpre, float inv_s_x, int8_t *x_q, __half *conv_state,
+                     hipStream_t st) {
+  const size_t n = (size_t)Bt * (Di / 4);
+  hipLaunchKernelGGL(conv_step_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, xpre_q, ldx,
+                     w_q, conv_b, Bt, Di, s_cw, s_xpre, inv_s_x, x_q, conv_state);
+  QUAMBA_LAUNCH_CHECK();
+  return QUAMBA_OK;
+}
+
+int launch_add_rmsnorm_quant(const __half *x_out, __half *res, const __half *weight, float eps,
+                             float inv_s, int8_t *u_q, int M, int Dm, hipStream_t st) {
+  if (Dm % 8 != 0 || Dm > 8 * 256 * RMS_MAX_PER_THREAD)
+    return fail(QUAMBA_EUNSUPPORTED, "add_rmsnorm_quant: d_model=%d must be a multiple of 8 and <= %d", Dm,
+                8 * 256 * RMS_MAX_PER_THREAD);
+  hipLaunchKernelGGL(add_rmsnorm_quant_kernel, dim3(M), dim3(256), 0, st, x_out, res, weight, eps, inv_s,
+                     u_q, Dm);
+  QUAMBA_LAUNCH_CHECK();
+  return QUAMBA_OK;
+}
+
+}  // namespace quamba

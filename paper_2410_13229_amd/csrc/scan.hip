@@ -1,0 +1,314 @@
+// Quantized selective scan with SiLU(z) gate (Section 3.1 Eq. 1; Section 4.2 "Quantization
+// for Selective SSM"): int8 x, dt, B, C, z (and int8 A, D) are dequantized inside the kernel
+// with their static scales, the recurrence runs on an fp32 state, the output is fp16.
+//
+//   x = s_x x_q,  dt = softplus(s_dt dt_q + dt_bias),  z = s_z z_q
+//   h[n] <- exp(dt * s_A A_q[d,n]) * h[n] + dt * x * s_B B_q[t,n]
+//   y = sum_n s_C C_q[t,n] * h[n] + s_D D_q[d] * x,   g = y * z / (1 + exp(-z))
+//
+// Layout: activations are token-major [t, d] int8, so one wavefront = 64 adjacent channels
+// reads 64 contiguous bytes per token and tensor; every lane keeps the 16 states of its channel
+// in registers.  B_t and C_t are shared by all channels: each workgroup dequantizes them once
+// per block of tokens into LDS and the lanes read them back as broadcasts.
+//
+// Prefill parallelises over L with a three-pass chunked scan (the recurrence is linear in h):
+//   pass 1  per (chunk, channel): end state of the chunk started from h = 0, and sum of dt
+//   pass 2  per (channel, n): walk the chunks in order, h_start[c+1] = P_c h_start[c] + h_loc[c]
+//           with P_c = exp(A * sum_c dt); emits the start state of every chunk and h_L
+//   pass 3  per (chunk, channel): rerun the chunk from its true start state and emit g
+// Decode is a single recurrence step with 4 lanes per channel (float4 state access).
+#include "common.h"
+
+namespace quamba {
+namespace {
+
+constexpr float LOG2E = 1.44269504088896340736f;
+constexpr float LN2 = 0.69314718055994530942f;
+constexpr int NS = 16;       // d_state
+constexpr int TB = 32;       // tokens of B/C staged in LDS at a time
+constexpr int SCAN_THREADS = 256;
+
+__device__ __forceinline__ float exp2_fast(float v) { return __builtin_amdgcn_exp2f(v); }
+
+// softplus(v) = log(1 + exp(v)); v itself above 20.  For small exp(v) the sum 1 + e would
+// lose the low bits of e, so log1p is evaluated by its alternating series there.
+__device__ __forceinline__ float softplus_f(float v) {
+  const float e = exp2_fast(fminf(v, 20.f) * LOG2E);
+  const float big = __builtin_amdgcn_logf(1.f + e) * LN2;
+  const float small = e * (1.f + e * (-0.5f + e * (1.f / 3.f + e * (-0.25f + e * (0.2f + e * (-1.f / 6.f))))));
+  const float r = e < 0.0625f ? small : big;
+  return v > 20.f ? v : r;
+}
+
+__device__ __forceinline__ float silu_gate(float y, float z) {
+  return y * z * __builtin_amdgcn_rcpf(1.f + exp2_fast(-z * LOG2E));
+}
+
+struct Dev {
+  const int8_t *x_q, *dt_q, *z_q, *B_q, *C_q, *A_q, *D_q;
+  const float *dt_bias;
+  int ldz, ldbc;
+  float s_x, s_dt, s_z, s_B, s_C, s_A, s_D;
+  int L, Di, T, nchunks;
+  __half *g16;
+  float *y_f32;
+  float *hloc;  // [Bt, nchunks, Di, 16]
+  float *ssum;  // [Bt, nchunks, Di]
+};
+
+// Dequantize B (and C) of tokens [t, t+cnt) of sequence b into LDS as fp32 [TB][16].
+template <bool WITH_C>
+__device__ __forceinline__ void stage_bc(const Dev &p, size_t row0, int cnt, float (*sB)[NS],
+                                         float (*sC)[NS]) {
+  for (int i = threadIdx.x; i < TB * NS; i += SCAN_THREADS) {
+    const int tt = i >> 4, n = i & 15;
+    float b = 0.f, c = 0.f;
+    if (tt < cnt) {
+      b = p.s_B * static_cast<float>(p.B_q[(row0 + tt) * p.ldbc + n]);
+      if (WITH_C) c = p.s_C * static_cast<float>(p.C_q[(row0 + tt) * p.ldbc + n]);
+    }
+    sB[tt][n] = b;
+    if (WITH_C) sC[tt][n] = c;
+  }
+}
+
+// ---------------------------------------------------------------- pass 1: chunk-local state
+__global__ __launch_bounds__(SCAN_THREADS) void scan_local_kernel(Dev p) {
+  __shared__ __attribute__((aligned(16))) float sB[TB][NS];
+  const int d = blockIdx.x * SCAN_THREADS + threadIdx.x;
+  const int c = blockIdx.y, b = blockIdx.z;
+  const bool live = d < p.Di;
+  const int dd = live ? d : p.Di - 1;
+  const int t0 = c * p.T, t1 = min(t0 + p.T, p.L);
+
+  float a2[NS], h[NS];
+  {
+    const uint4 av = *reinterpret_cast<const uint4 *>(p.A_q + (size_t)dd * NS);
+    const unsigned aw[4] = {av.x, av.y, av.z, av.w};
+#pragma unroll
+    for (int n = 0; n < NS; ++n) {
+      a2[n] = static_cast<float>(static_cast<int8_t>(aw[n >> 2] >> (8 * (n & 3)))) * (p.s_A * LOG2E);
+      h[n] = 0.f;
+    }
+  }
+  const float bias = p.dt_bias[dd];
+  float sdt = 0.f;
+  const size_t seq0 = (size_t)b * p.L;
+
+  for (int tb = t0; tb < t1; tb += TB) {
+    const int cnt = min(TB, t1 - tb);
+    __syncthreads();
+    stage_bc<false>(p, seq0 + tb, cnt, sB, nullptr);
+    __syncthreads();
+    for (int tt = 0; tt < cnt; ++tt) {
+      const size_t row = seq0 + tb + tt;
+      const float xv = p.s_x * static_cast<float>(p.x_q[row * p.Di + dd]);
+      const float dt = softplus_f(p.s_dt * static_cast<float>(p.dt_q[row * p.Di + dd]) + bias);
+      const float u = dt * xv;
+      sdt += dt;
+#pragma unroll
+      for (int n = 0; n < NS; ++n) h[n] = exp2_fast(dt * a2[n]) * h[n] + u * sB[tt][n];
+    }
+  }
+  if (live) {
+    float *dst = p.hloc + (((size_t)b * p.nchunks + c) * p.Di + d) * NS;
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      reinterpret_cast<float4 *>(dst)[q] = make_float4(h[4 * q], h[4 * q + 1], h[4 * q + 2], h[4 * q + 3]);
+    p.ssum[((size_t)b * p.nchunks + c) * p.Di + d] = sdt;
+  }
+}
+
+// ---------------------------------------------------------------- pass 2: carry across chunks
+// One thread per (b, d, n).  In place: hloc[c] is replaced by the start state of chunk c.
+__global__ __launch_bounds__(256) void scan_carry_kernel(Dev p, float *__restrict__ ssm_state, int Bt) {
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t per_b = (size_t)p.Di * NS;
+  if (idx >= per_b * Bt) return;
+  const int b = static_cast<int>(idx / per_b);
+  const size_t dn = idx % per_b;
+  const int d = static_cast<int>(dn / NS);
+  const float a2 = static_cast<float>(p.A_q[dn]) * (p.s_A * LOG2E);
+  float h = ssm_state ? ssm_state[idx] : 0.f;
+  float *hl = p.hloc + (size_t)b * p.nchunks * per_b + dn;
+  const float *ss = p.ssum + (size_t)b * p.nchunks * p.Di + d;
+  float loc = hl[0], s = ss[0];
+  for (int c = 0; c < p.nchunks; ++c) {
+    float nloc = 0.f, ns = 0.f;
+    if (c + 1 < p.nchunks) {
+      nloc = hl[(size_t)(c + 1) * per_b];
+      ns = ss[(size_t)(c + 1) * p.Di];
+    }
+    hl[(size_t)c * per_b] = h;
+    h = exp2_fast(a2 * s) * h + loc;
+    loc = nloc;
+    s = ns;
+  }
+  if (ssm_state) ssm_state[idx] = h;
+}
+
+// ---------------------------------------------------------------- pass 3: outputs
+__global__ __launch_bounds__(SCAN_THREADS) void scan_output_kernel(Dev p) {
+  __shared__ __attribute__((aligned(16))) float sB[TB][NS];
+  __shared__ __attribute__((aligned(16))) float sC[TB][NS];
+  const int d = blockIdx.x * SCAN_THREADS + threadIdx.x;
+  const int c = blockIdx.y, b = blockIdx.z;
+  const bool live = d < p.Di;
+  const int dd = live ? d : p.Di - 1;
+  const int t0 = c * p.T, t1 = min(t0 + p.T, p.L);
+
+  float a2[NS], h[NS];
+  {
+    const uint4 av = *reinterpret_cast<const uint4 *>(p.A_q + (size_t)dd * NS);
+    const unsigned aw[4] = {av.x, av.y, av.z, av.w};
+    const float *src = p.hloc + (((size_t)b * p.nchunks + c) * p.Di + dd) * NS;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const float4 v = reinterpret_cast<const float4 *>(src)[q];
+      h[4 * q] = v.x;
+      h[4 * q + 1] = v.y;
+      h[4 * q + 2] = v.z;
+      h[4 * q + 3] = v.w;
+    }
+#pragma unroll
+    for (int n = 0; n < NS; ++n)
+      a2[n] = static_cast<float>(static_cast<int8_t>(aw[n >> 2] >> (8 * (n & 3)))) * (p.s_A * LOG2E);
+  }
+  const float bias = p.dt_bias[dd];
+  const float Dv = p.s_D * static_cast<float>(p.D_q[dd]);
+  const size_t seq0 = (size_t)b * p.L;
+
+  for (int tb = t0; tb < t1; tb += TB) {
+    const int cnt = min(TB, t1 - tb);
+    __syncthreads();
+    stage_bc<true>(p, seq0 + tb, cnt, sB, sC);
+    __syncthreads();
+    for (int tt = 0; tt < cnt; ++tt) {
+      const size_t row = seq0 + tb + tt;
+      const float xv = p.s_x * static_cast<float>(p.x_q[row * p.Di + dd]);
+      const float dt = softplus_f(p.s_dt * static_cast<float>(p.dt_q[row * p.Di + dd]) + bias);
+      const float zv = p.s_z * static_cast<float>(p.z_q[row * p.ldz + dd]);
+      const float u = dt * xv;
+      float y = 0.f;
+#pragma unroll
+      for (int n = 0; n < NS; ++n) {
+        h[n] = exp2_fast(dt * a2[n]) * h[n] + u * sB[tt][n];
+        y += sC[tt][n] * h[n];
+      }
+      y += Dv * xv;
+      const float g = silu_gate(y, zv);
+      if (live) {
+        p.g16[row * p.Di + d] = __float2half_rn(g);
+        if (p.y_f32) p.y_f32[row * p.Di + d] = g;
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------- decode: one step
+// 4 lanes per channel, each owning 4 of the 16 states as one float4.
+__global__ __launch_bounds__(256) void scan_step_kernel(Dev p, float *__restrict__ ssm_state, int Bt) {
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;  // (b, d, quad)
+  const size_t total = (size_t)Bt * p.Di * 4;
+  const bool live = idx < total;
+  const size_t id = live ? idx : total - 1;
+  const int q = static_cast<int>(id & 3);
+  const size_t bd = id >> 2;
+  const int b = static_cast<int>(bd / p.Di), d = static_cast<int>(bd % p.Di);
+
+  float4 hv = reinterpret_cast<const float4 *>(ssm_state)[id];
+  float h[4] = {hv.x, hv.y, hv.z, hv.w};
+  const unsigned aw = *reinterpret_cast<const unsigned *>(p.A_q + (size_t)d * NS + 4 * q);
+  const unsigned bw = *reinterpret_cast<const unsigned *>(p.B_q + (size_t)b * p.ldbc + 4 * q);
+  const unsigned cw = *reinterpret_cast<const unsigned *>(p.C_q + (size_t)b * p.ldbc + 4 * q);
+  const float xv = p.s_x * static_cast<float>(p.x_q[(size_t)b * p.Di + d]);
+  const float dt = softplus_f(p.s_dt * static_cast<float>(p.dt_q[(size_t)b * p.Di + d]) + p.dt_bias[d]);
+  const float zv = p.s_z * static_cast<float>(p.z_q[(size_t)b * p.ldz + d]);
+  const float u = dt * xv;
+  float y = 0.f;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const float a2 = static_cast<float>(static_cast<int8_t>(aw >> (8 * j))) * (p.s_A * LOG2E);
+    const float Bv = p.s_B * static_cast<float>(static_cast<int8_t>(bw >> (8 * j)));
+    const float Cv = p.s_C * static_cast<float>(static_cast<int8_t>(cw >> (8 * j)));
+    h[j] = exp2_fast(dt * a2) * h[j] + u * Bv;
+    y += Cv * h[j];
+  }
+  y += __shfl_xor(y, 1);
+  y += __shfl_xor(y, 2);
+  y += p.s_D * static_cast<float>(p.D_q[d]) * xv;
+  const float g = silu_gate(y, zv);
+  if (live) {
+    reinterpret_cast<float4 *>(ssm_state)[id] = make_float4(h[0], h[1], h[2], h[3]);
+    if (q == 0) {
+      p.g16[(size_t)b * p.Di + d] = __float2half_rn(g);
+      if (p.y_f32) p.y_f32[(size_t)b * p.Di + d] = g;
+    }
+  }
+}
+
+Dev make_dev(const ScanArgs &a) {
+  Dev p{};
+  p.x_q = a.x_q; p.dt_q = a.dt_q; p.z_q = a.z_q; p.B_q = a.B_q; p.C_q = a.C_q; p.A_q = a.A_q; p.D_q = a.D_q;
+  p.dt_bias = a.dt_bias; p.ldz = a.ldz; p.ldbc = a.ldbc;
+  p.s_x = a.s_x; p.s_dt = a.s_dt; p.s_z = a.s_z; p.s_B = a.s_B; p.s_C = a.s_C; p.s_A = a.s_A; p.s_D = a.s_D;
+  p.L = a.L; p.Di = a.Di; p.g16 = a.g16; p.y_f32 = a.y_f32;
+  return p;
+}
+
+// Chunk length: enough chunks to give the chip a few thousand wavefronts, but chunks no
+// shorter than 32 tokens so the per-chunk state traffic (128 B per channel) stays small
+// against the 7 B per (token, channel) the two sweeps read and write.
+void choose_chunks(int Bt, int L, int Di, int *T, int *nchunks) {
+  const long waves_per_chunk = (long)Bt * ((Di + 63) / 64);
+  long want = (2560 + waves_per_chunk - 1) / waves_per_chunk;
+  long maxc = (L + 31) / 32;
+  if (want > maxc) want = maxc;
+  if (want < 1) want = 1;
+  int t = (int)((L + want - 1) / want);
+  t = (t + 7) / 8 * 8;
+  *T = t;
+  *nchunks = (L + t - 1) / t;
+}
+
+}  // namespace
+
+size_t scan_workspace_bytes(int Bt, int L, int Di) {
+  int T, nc;
+  choose_chunks(Bt, L, Di, &T, &nc);
+  const size_t hloc = align_up((size_t)Bt * nc * Di * NS * sizeof(float), 256);
+  const size_t ssum = align_up((size_t)Bt * nc * Di * sizeof(float), 256);
+  return hloc + ssum;
+}
+
+int launch_scan_prefill(const ScanArgs &a, void *ws, size_t ws_bytes, hipStream_t st) {
+  if (ws_bytes < scan_workspace_bytes(a.Bt, a.L, a.Di))
+    return fail(QUAMBA_EWORKSPACE, "scan: workspace %zu < %zu", ws_bytes, scan_workspace_bytes(a.Bt, a.L, a.Di));
+  Dev p = make_dev(a);
+  choose_chunks(a.Bt, a.L, a.Di, &p.T, &p.nchunks);
+  p.hloc = static_cast<float *>(ws);
+  p.ssum = reinterpret_cast<float *>(static_cast<char *>(ws) +
+                                     align_up((size_t)a.Bt * p.nchunks * a.Di * NS * sizeof(float), 256));
+  dim3 grid((a.Di + SCAN_THREADS - 1) / SCAN_THREADS, p.nchunks, a.Bt);
+  hipLaunchKernelGGL(scan_local_kernel, grid, dim3(SCAN_THREADS), 0, st, p);
+  QUAMBA_LAUNCH_CHECK();
+  const size_t n2 = (size_t)a.Bt * a.Di * NS;
+  hipLaunchKernelGGL(scan_carry_kernel, dim3((unsigned)((n2 + 255) / 256)), dim3(256), 0, st, p, a.ssm_state,
+                     a.Bt);
+  QUAMBA_LAUNCH_CHECK();
+  hipLaunchKernelGGL(scan_output_kernel, grid, dim3(SCAN_THREADS), 0, st, p);
+  QUAMBA_LAUNCH_CHECK();
+  return QUAMBA_OK;
+}
+
+int launch_scan_step(const ScanArgs &a, hipStream_t st) {
+  Dev p = make_dev(a);
+  p.L = 1;
+  const size_t n = (size_t)a.Bt * a.Di * 4;
+  hipLaunchKernelGGL(scan_step_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, a.ssm_state,
+                     a.Bt);
+  QUAMBA_LAUNCH_CHECK();
+  return QUAMBA_OK;
+}
+
+}  // namespace quamba

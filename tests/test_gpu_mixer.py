@@ -1,0 +1,287 @@
+"""GPU parity of the whole quantized mixer through the C ABI (quamba_mixer_prefill /
+quamba_mixer_decode / quamba_calibrate).
+
+A single flipped int8 code upstream changes every accumulator downstream, so the chain is
+checked link by link: every stage of the GPU run is compared with the oracle's stage function
+applied to the GPU's own input to that stage (bit-exact for integer work, within the stated
+tolerances for the floating-point stages), and the final fp16 output is also compared end to
+end with the oracle's.  At the large shapes the same links are checked on sampled rows and
+channels, which the oracle can compute one by one."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+import paper_2410_13229_amd as Q
+import workloads as W
+from gpu_util import (assert_lsb, dev, empty, host, oracle_setup, qweights_to_dev, rel_err, run_prefill,
+                      workspace, make_taps)
+
+pytestmark = pytest.mark.gpu
+
+
+def check_chain(cfg, qw, sc, u, r, h0=None, rows=None, chans=None, decode_state=None):
+    """Verify each link of a GPU run `r` (taps as numpy, [M, cols]) against the oracle.
+    rows: sampled token rows for the GEMM / Hadamard links (None = all);
+    chans: sampled channels for the conv / scan links (None = all)."""
+    Bt, L = u.shape[:2]
+    Dm, Di, N, R = cfg.d_model, cfg.d_inner, cfg.d_state, cfg.dt_rank
+    M = Bt * L
+    rs = np.arange(M) if rows is None else np.asarray(rows)
+    cs = np.arange(Di) if chans is None else np.asarray(chans)
+    stats = {}
+    # S0 quantize
+    u_q = O.quantize(u.reshape(M, Dm)[rs].astype(np.float32), sc["inv_s_u"])
+    assert np.array_equal(r["u_q"][rs], u_q)
+    # S1 in_proj
+    acc = O.int_matmul(r["u_q"][rs], qw["W_in"])
+    assert np.array_equal(r["acc_in"][rs], acc)
+    assert np.array_equal(r["xz_q"][rs, :Di], O.requant_acc(acc[:, :Di], sc["m_in_x"]))
+    assert np.array_equal(r["xz_q"][rs, Di:], O.requant_acc(acc[:, Di:], sc["m_in_z"]))
+    # S2 conv
+    xz3 = r["xz_q"].reshape(Bt, L, 2 * Di)
+    if decode_state is None:
+        want = O.q_conv_prefill(xz3[:, :, cs], qw["conv_w"][cs], qw["conv_b"][cs], sc)
+    else:
+        want, _ = O.q_conv_step(xz3[:, 0, cs], decode_state["conv_state"][:, cs], qw["conv_w"][cs],
+                                qw["conv_b"][cs], sc)
+        want = want[:, None, :]
+    got = r["x_q"].reshape(Bt, L, Di)[:, :, cs]
+    assert_lsb(got, want, "x_q")
+    stats["x_q_flip"] = float((got != want).mean())
+    # S3 x_proj
+    acc = O.int_matmul(r["x_q"][rs], qw["W_x"])
+    assert np.array_equal(r["acc_x"][rs], acc)
+    assert np.array_equal(r["dbc_q"][rs, :R], O.requant_acc(acc[:, :R], sc["m_x_dt"]))
+    assert np.array_equal(r["dbc_q"][rs, R:R + N], O.requant_acc(acc[:, R:R + N], sc["m_x_B"]))
+    assert np.array_equal(r["dbc_q"][rs, R + N:], O.requant_acc(acc[:, R + N:], sc["m_x_C"]))
+    # S4 dt_proj
+    acc = O.int_matmul(r["dbc_q"][rs, :R], qw["W_dt"])
+    assert np.array_equal(r["acc_dt"][rs], acc)
+    assert np.array_equal(r["dt_q"][rs], O.requant_acc(acc, sc["m_dt"]))
+    # S5 scan + gate
+    dbc3 = r["dbc_q"].reshape(Bt, L, R + 2 * N)
+    hh = decode_state["ssm_state"] if decode_state is not None else h0
+    g_ref, g16_ref, h_ref = O.q_scan(r["x_q"].reshape(Bt, L, Di)[:, :, cs], r["dt_q"].reshape(Bt, L, Di)[:, :, cs],
+                                     xz3[:, :, Di + cs], dbc3[..., R:R + N], dbc3[..., R + N:], qw["A"][cs],
+                                     qw["D"][cs], qw["dt_bias"][cs], sc, None if hh is None else hh[:, cs])
+    stats["scan_err"] = rel_err(r["y_f32"].reshape(Bt, L, Di)[:, :, cs], g_ref)
+    assert stats["scan_err"] <= 1e-3
+    assert rel_err(r["g16"].reshape(Bt, L, Di)[:, :, cs].astype(np.float64), g_ref) <= 1e-3
+    if "h" in r:
+        assert rel_err(r["h"][:, cs], h_ref) <= 1e-3
+    # S6 Hadamard + quant
+    gH_ref, gHq_ref = O.q_hadamard_quant(r["g16"][rs], sc)
+    stats["had_err"] = rel_err(r["gH_f32"][rs], gH_ref)
+    assert stats["had_err"] <= 1e-5
+    assert_lsb(r["gH_q"][rs], gHq_ref, "gH_q")
+    stats["gH_q_flip"] = float((r["gH_q"][rs] != gHq_ref).mean())
+    # S7 out_proj
+    acc, out = O.q_out_proj(r["gH_q"][rs], qw["W_outH"], sc)
+    assert np.array_equal(r["acc_out"][rs], acc)
+    assert np.array_equal(r["out"].reshape(M, Dm)[rs].view(np.uint16), out.view(np.uint16))
+    return stats
+
+
+def end_to_end(r, ref, name):
+    """Final output against the oracle's own run.  The bound follows from the allowance of one
+    code on 0.1 % of a requantized tensor: a flipped code moves a few downstream sums by one
+    step of their scale, far below 2 % of the output's absmax."""
+    e = rel_err(r["out"].astype(np.float64), ref["out"].astype(np.float64))
+    assert e <= 2e-2, (name, e)
+    return e
+
+
+@pytest.mark.parametrize("Bt,L,dm,di,rk", [(2, 37, 64, 128, 16), (1, 5, 96, 192, 16), (3, 130, 160, 320, 32)])
+def test_prefill_tiny(Bt, L, dm, di, rk):
+    cfg = W.tiny_config(name=f"t{di}", d_model=dm, d_inner=di, dt_rank=rk, batch=Bt, seqlen=L, config_id=91 + di)
+    w, qw, sc = oracle_setup(cfg, randomize_bias=True, gain=10.0)
+    u = W.make_hidden(cfg)
+    rng = np.random.default_rng(5)
+    h0 = (rng.standard_normal((Bt, di, 16)) * 0.1).astype(np.float32)
+    r = run_prefill(cfg, qweights_to_dev(qw), sc, u, h0=h0)
+    ref = O.q_prefill(qw, sc, u, h0=h0)
+    check_chain(cfg, qw, sc, u, r, h0=h0)
+    end_to_end(r, ref, cfg.name)
+    assert np.array_equal(r["conv_state"].view(np.uint16), ref["conv_state"].view(np.uint16))
+    assert rel_err(r["h"], ref["h"]) <= 2e-2
+
+
+def test_prefill_q_variant_and_null_state():
+    cfg = W.tiny_config(name="tq", d_model=64, d_inner=128, dt_rank=16, batch=2, seqlen=20, config_id=95)
+    w, qw, sc = oracle_setup(cfg, randomize_bias=True, gain=10.0)
+    u = W.make_hidden(cfg)
+    qd = qweights_to_dev(qw)
+    a = run_prefill(cfg, qd, sc, u, want_state=False, taps=False)
+    u_q = O.quantize(u.astype(np.float32), sc["inv_s_u"])
+    b = run_prefill(cfg, qd, sc, None, u_q=u_q, want_state=True, taps=False)
+    assert np.array_equal(a["out"].view(np.uint16), b["out"].view(np.uint16))
+
+
+def test_prefill_c0_full():
+    cfg = W.CONFIGS["c0"]
+    w, qw, sc = oracle_setup(cfg)
+    u = W.make_hidden(cfg)
+    r = run_prefill(cfg, qweights_to_dev(qw), sc, u)
+    ref = O.q_prefill(qw, sc, u)
+    st = check_chain(cfg, qw, sc, u, r)
+    e = end_to_end(r, ref, "c0")
+    print("c0", st, "end-to-end", e)
+
+
+def test_prefill_c1_full():
+    cfg = W.CONFIGS["c1"]
+    w, qw, sc = oracle_setup(cfg)
+    u = W.make_hidden(cfg)
+    r = run_prefill(cfg, qweights_to_dev(qw), sc, u)
+    ref = O.q_prefill(qw, sc, u)
+    st = check_chain(cfg, qw, sc, u, r)
+    e = end_to_end(r, ref, "c1")
+    print("c1", st, "end-to-end", e)
+
+
+def _sampled(cfg, Bt, L, seed):
+    rng = np.random.default_rng(seed)
+    M = Bt * L
+    rows = np.unique(np.concatenate([[0, 1, M - 1, M // 2], rng.integers(0, M, 60)]))
+    chans = np.unique(np.concatenate([[0, 1, cfg.d_inner - 1], rng.integers(0, cfg.d_inner, 93)]))
+    return rows, chans
+
+
+def test_prefill_c4_full_size_sampled():
+    """Jamba-shaped layer at L = 16384 in the launch configuration the benchmark uses."""
+    cfg = W.CONFIGS["c4"]
+    w, qw, sc = oracle_setup(cfg)
+    u = W.make_hidden(cfg)
+    r = run_prefill(cfg, qweights_to_dev(qw), sc, u)
+    rows, chans = _sampled(cfg, cfg.batch, cfg.seqlen, 4)
+    st = check_chain(cfg, qw, sc, u, r, rows=rows, chans=chans)
+    print("c4", st)
+
+
+def test_prefill_c3_layer_shape_sampled():
+    """One layer of the 64-layer stack at its batch 4 x 4096 shape, with a carried-in state."""
+    cfg = W.CONFIGS["c3"]
+    w, qw, sc = oracle_setup(cfg)
+    u = W.make_hidden(cfg)
+    rng = np.random.default_rng(8)
+    h0 = (rng.standard_normal((cfg.batch, cfg.d_inner, 16)) * 0.1).astype(np.float32)
+    r = run_prefill(cfg, qweights_to_dev(qw), sc, u, h0=h0)
+    rows, chans = _sampled(cfg, cfg.batch, cfg.seqlen, 3)
+    st = check_chain(cfg, qw, sc, u, r, h0=h0, rows=rows, chans=chans)
+    print("c3-layer", st)
+
+
+def _decode_steps(cfg, Bt, steps, qw, sc, check_every=1):
+    qd = qweights_to_dev(qw)
+    ssm_np, cs_np = W.make_decode_state(cfg, batch=Bt)
+    ssm, cs = dev(ssm_np), dev(cs_np)
+    ws = workspace(Q.quamba_workspace_bytes(cfg, Bt, 1))
+    out = empty((Bt, cfg.d_model), torch.float16)
+    tp = make_taps(cfg, Bt)
+    o_ssm, o_cs = ssm_np, cs_np
+    for s in range(steps):
+        u = W.make_hidden(cfg, batch=Bt, seqlen=1, stream=100 + s)
+        state_before = {"ssm_state": host(ssm).copy(), "conv_state": host(cs).copy()}
+        Q.quamba_mixer_decode(cfg, qd, sc, dev(u[:, 0]), Bt, out, ssm, cs, tp, ws)
+        r = {k: host(v) for k, v in tp.items()}
+        r["out"] = host(out)
+        r["h"] = host(ssm)
+        if s % check_every == 0:
+            check_chain(cfg, qw, sc, u, r, decode_state=state_before)
+        # the oracle's own trajectory, for the end-to-end comparison
+        ref = O.q_decode(qw, sc, u[:, 0], o_ssm, o_cs)
+        o_ssm, o_cs = ref["h"], ref["conv_state"]
+        assert rel_err(r["out"].astype(np.float64), ref["out"][:, 0].astype(np.float64)) <= 2e-2
+        assert rel_err(host(ssm), o_ssm) <= 2e-2
+        new_cs = host(cs)
+        assert np.array_equal(new_cs[:, :, :2].view(np.uint16), state_before["conv_state"][:, :, 1:].view(np.uint16))
+        assert np.array_equal(new_cs.view(np.uint16), o_cs.view(np.uint16))
+
+
+def test_decode_tiny():
+    cfg = W.tiny_config(name="td", d_model=64, d_inner=128, dt_rank=16, batch=3, seqlen=1, config_id=96)
+    w, qw, sc = oracle_setup(cfg, randomize_bias=True, gain=10.0)
+    _decode_steps(cfg, 3, 4, qw, sc)
+
+
+def test_decode_c2_shape():
+    cfg = W.CONFIGS["c2"]
+    w, qw, sc = oracle_setup(cfg)
+    _decode_steps(cfg, cfg.batch, 3, qw, sc)
+
+
+def test_prefill_then_decode_handoff():
+    """State handed from prefill to decode: prefill(L) + one decode step tracks prefill(L+1)."""
+    cfg = W.tiny_config(name="th", d_model=64, d_inner=128, dt_rank=16, batch=2, seqlen=33, config_id=97)
+    w, qw, sc = oracle_setup(cfg, randomize_bias=True, gain=10.0)
+    qd = qweights_to_dev(qw)
+    u = W.make_hidden(cfg, seqlen=34)
+    full = run_prefill(cfg, qd, sc, u, taps=False)
+    part = run_prefill(cfg, qd, sc, u[:, :33], taps=False)
+    ssm, cs = dev(part["h"]), dev(part["conv_state"])
+    out = empty((2, cfg.d_model), torch.float16)
+    ws = workspace(Q.quamba_workspace_bytes(cfg, 2, 1))
+    Q.quamba_mixer_decode(cfg, qd, sc, dev(u[:, 33]), 2, out, ssm, cs, None, ws)
+    assert rel_err(host(out).astype(np.float64), full["out"][:, 33].astype(np.float64)) <= 3e-2
+    assert rel_err(host(ssm), full["h"]) <= 2e-2
+    assert np.array_equal(host(cs).view(np.uint16), full["conv_state"].view(np.uint16))
+
+
+def test_mixer_argument_errors():
+    cfg = W.tiny_config(name="te", d_model=64, d_inner=128, dt_rank=16, batch=1, seqlen=4, config_id=98)
+    w, qw, sc = oracle_setup(cfg)
+    qd = qweights_to_dev(qw)
+    u = dev(W.make_hidden(cfg))
+    out = empty((1, 4, 64), torch.float16)
+    small = workspace(256)
+    with pytest.raises(Q.QuambaError) as e:
+        Q.quamba_mixer_prefill(cfg, qd, sc, u, 1, 4, out, None, None, None, small)
+    assert e.value.code == -3
+    ws = workspace(Q.quamba_workspace_bytes(cfg, 1, 4))
+    with pytest.raises(Q.QuambaError) as e:
+        Q.quamba_mixer_prefill(cfg, qd, sc, u, 1, 0, out, None, None, None, ws)
+    assert e.value.code == -1
+    bad = W.tiny_config(name="tb", d_model=64, d_inner=112, dt_rank=16)  # 7 * 16: no Hadamard order
+    assert Q.quamba_workspace_bytes(bad, 1, 4) == 0
+    with pytest.raises(Q.QuambaError) as e:
+        Q.quamba_mixer_decode(cfg, qd, sc, u, 1, out, None, None, None, ws)  # decode needs its state
+    assert e.value.code == -1
+
+
+def test_determinism():
+    cfg = W.CONFIGS["c0"]
+    w, qw, sc = oracle_setup(cfg)
+    u = W.make_hidden(cfg)
+    qd = qweights_to_dev(qw)
+    a = run_prefill(cfg, qd, sc, u, taps=False)
+    b = run_prefill(cfg, qd, sc, u, taps=False)
+    assert np.array_equal(a["out"].view(np.uint16), b["out"].view(np.uint16))
+    assert np.array_equal(a["h"], b["h"])
+
+
+# ------------------------------------------------------------------ calibration on the GPU
+@pytest.mark.parametrize("name", ["tiny", "c0"])
+def test_calibrate_matches_oracle(name):
+    cfg = (W.tiny_config(name="tc", d_model=64, d_inner=192, dt_rank=16, config_id=99) if name == "tiny"
+           else W.CONFIGS[name])
+    w = W.make_weights(cfg, randomize_bias=True)
+    calib = W.make_calibration(cfg)
+    p = 99.9 if name == "tiny" else 99.999
+    qw_ref, sc_ref = O.calibrate(w, calib, p)
+    fw = {k: dev(v) for k, v in w.items()}
+    out_q = {k: torch.zeros(v.shape, dtype=torch.int8 if v.dtype == np.int8 else torch.float32, device="cuda:0")
+             for k, v in qw_ref.items()}
+    nb, Lc = calib.shape[:2]
+    ws = workspace(Q.quamba_calibrate_workspace_bytes(cfg, nb, Lc))
+    sc = Q.scales_to_dict(Q.quamba_calibrate(cfg, fw, dev(calib), nb, Lc, p, out_q, ws))
+    for k in Q.SCALE_FIELDS:
+        tol = 2e-3 if k in ("s_x", "inv_s_x", "m_x_dt", "m_x_B", "m_x_C") else 1e-4
+        assert abs(sc[k] - float(sc_ref[k])) <= tol * abs(float(sc_ref[k])), (k, sc[k], float(sc_ref[k]))
+    for k, v in qw_ref.items():
+        got = host(out_q[k])
+        if v.dtype == np.int8:
+            d = np.abs(got.astype(int) - v.astype(int))
+            assert d.max() <= 1 and (d != 0).mean() <= 1e-3, k
+        else:
+            assert np.array_equal(got, v), k

@@ -1,0 +1,229 @@
+"""GPU parity, stage by stage: each HIP kernel gets the oracle's own inputs and is compared
+element by element with the oracle's output for that stage.
+Bars: int32 accumulators and GEMM epilogues bit-exact; scan fp32 output <= 1e-3 and Hadamard
+fp32 output <= 1e-5 of the tensor's absmax; requantized int8 within 1 LSB on <= 0.1 %."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+import paper_2410_13229_amd as Q
+import workloads as W
+from gpu_util import (assert_lsb, dev, empty, host, oracle_setup, rel_err, workspace)
+
+pytestmark = pytest.mark.gpu
+
+
+# ------------------------------------------------------------------ quantize
+@pytest.mark.parametrize("n", [8, 2048, 2048 * 3 + 8, 1000003])
+def test_quantize_f16_exact(n):
+    rng = np.random.default_rng(n)
+    x = (rng.standard_normal(n) * 40).astype(np.float16)
+    x[: min(n, 6)] = np.array([0.5, 1.5, 2.5, -0.5, 300.0, -300.0], dtype=np.float16)[: min(n, 6)]
+    inv = np.float32(1.0 / 0.37)
+    q = empty((n,), torch.int8)
+    Q.quamba_quantize_f16(dev(x), q, n, inv)
+    assert np.array_equal(host(q), O.quantize(x.astype(np.float32), inv))
+
+
+# ------------------------------------------------------------------ GEMM
+GEMM_SHAPES = [
+    # M, N, K, lda_pad, label
+    (64, 64, 64, 0), (1, 4, 16, 0), (200, 192, 160, 32), (129, 260, 48, 0), (257, 80, 1536, 0),
+    (64, 10240, 2560, 0), (512, 2560, 5120, 0), (300, 5120, 160, 32), (2048, 192, 5120, 0),
+]
+
+
+@pytest.mark.parametrize("M,N,K,pad", GEMM_SHAPES)
+def test_gemm_acc_and_requant_bit_exact(M, N, K, pad):
+    rng = np.random.default_rng(M * 7 + N * 3 + K)
+    lda = K + pad
+    A = rng.integers(-128, 128, (M, lda), dtype=np.int8)
+    Wt = rng.integers(-128, 128, (N, K), dtype=np.int8)
+    A[0, :K] = -128
+    Wt[0, :] = -128  # largest possible accumulator
+    acc_ref = O.int_matmul(A[:, :K], Wt)
+    e0, e1 = (N // 4) // 4 * 4, (N // 2) // 4 * 4
+    mult = np.array([3.1e-5, 7.7e-5, 1.9e-4], dtype=np.float32) * np.float32(5120.0 / K)
+    cols = np.arange(N)
+    mcol = np.where(cols < e0, mult[0], np.where(cols < e1, mult[1], mult[2])).astype(np.float32)
+    want_i8 = np.clip(np.rint(acc_ref.astype(np.float32) * mcol[None, :]), -128, 127).astype(np.int8)
+    for k, m in ((0, mult[0]), (1, mult[1]), (2, mult[2])):  # the oracle's own requant, per range
+        sel = (cols < e0) if k == 0 else ((cols >= e0) & (cols < e1) if k == 1 else cols >= e1)
+        assert np.array_equal(want_i8[:, sel], O.requant_acc(acc_ref[:, sel], m))
+    ldo = N + 16
+    acc = empty((M, N), torch.int32)
+    out = torch.zeros((M, ldo), dtype=torch.int8, device="cuda:0")
+    dA, dW = dev(A), dev(Wt)
+    Q.quamba_gemm_i8(dA, lda, dW, K, M, N, K, e0, e1, mult, out, None, ldo, acc)
+    assert np.array_equal(host(acc), acc_ref)
+    got = host(out)
+    assert np.array_equal(got[:, :N], want_i8)
+    assert not got[:, N:].any()  # nothing written past N
+    # fp16 epilogue
+    outh = torch.zeros((M, ldo), dtype=torch.float16, device="cuda:0")
+    Q.quamba_gemm_i8(dA, lda, dW, K, M, N, K, N, N, mult, None, outh, ldo, None)
+    want_h = (acc_ref.astype(np.float32) * mult[0]).astype(np.float16)
+    goth = host(outh)
+    assert np.array_equal(goth[:, :N].view(np.uint16), want_h.view(np.uint16))
+    assert not goth[:, N:].any()
+
+
+def test_gemm_rejects_bad_arguments():
+    a = torch.zeros((16, 32), dtype=torch.int8, device="cuda:0")
+    o = torch.zeros((16, 16), dtype=torch.int8, device="cuda:0")
+    with pytest.raises(Q.QuambaError):
+        Q.quamba_gemm_i8(a, 32, a, 32, 16, 16, 24, 16, 16, [1, 1, 1], o, None, 16, None)  # K % 16
+    with pytest.raises(Q.QuambaError):
+        Q.quamba_gemm_i8(a, 32, a, 32, 16, 16, 32, 16, 16, [1, 1, 1], None, None, 16, None)  # no output
+    with pytest.raises(Q.QuambaError):
+        Q.quamba_gemm_i8(None, 32, a, 32, 16, 16, 32, 16, 16, [1, 1, 1], o, None, 16, None)  # NULL
+
+
+# ------------------------------------------------------------------ conv
+@pytest.mark.parametrize("Bt,L,Di", [(1, 1, 64), (2, 3, 128), (3, 37, 192), (1, 256, 1536), (2, 100, 5120)])
+def test_conv_prefill(Bt, L, Di):
+    rng = np.random.default_rng(Bt * 1000 + L)
+    ldx = 2 * Di
+    xz = rng.integers(-128, 128, (Bt, L, ldx), dtype=np.int8)
+    wq = rng.integers(-128, 128, (Di, 4), dtype=np.int8)
+    b = (rng.standard_normal(Di) * 0.2).astype(np.float32)
+    sc = {"m_conv": np.float32(2.3e-4), "inv_s_x": np.float32(1 / 0.011), "s_xpre": np.float32(0.031)}
+    want = O.q_conv_prefill(xz[..., :Di], wq, b, sc)
+    xq = empty((Bt, L, Di), torch.int8)
+    cs = empty((Bt, Di, 3), torch.float16)
+    Q.quamba_conv_silu_quant(dev(xz), ldx, dev(wq), dev(b), Bt, L, Di, sc["m_conv"], sc["inv_s_x"], sc["s_xpre"],
+                             xq, cs)
+    assert_lsb(host(xq), want, "x_q")
+    hist = np.zeros((Bt, 3, Di), dtype=np.float32)
+    take = min(L, 3)
+    hist[:, 3 - take:] = sc["s_xpre"] * xz[:, L - take:, :Di].astype(np.float32)
+    assert np.array_equal(host(cs), hist.transpose(0, 2, 1).astype(np.float16))
+
+
+@pytest.mark.parametrize("Bt,Di", [(1, 64), (5, 192), (64, 5120)])
+def test_conv_step(Bt, Di):
+    rng = np.random.default_rng(Bt + Di)
+    ldx = 2 * Di
+    xz = rng.integers(-128, 128, (Bt, ldx), dtype=np.int8)
+    wq = rng.integers(-128, 128, (Di, 4), dtype=np.int8)
+    b = (rng.standard_normal(Di) * 0.2).astype(np.float32)
+    st = (rng.standard_normal((Bt, Di, 3)) * 2.2).astype(np.float16)
+    sc = {"s_cw": np.float32(6e-4), "s_xpre": np.float32(0.031), "inv_s_x": np.float32(1 / 0.011)}
+    want, want_state = O.q_conv_step(xz[:, :Di], st, wq, b, sc)
+    xq = empty((Bt, Di), torch.int8)
+    dst = dev(st)
+    Q.quamba_conv_step(dev(xz), ldx, dev(wq), dev(b), Bt, Di, sc["s_cw"], sc["s_xpre"], sc["inv_s_x"], xq, dst)
+    assert_lsb(host(xq), want, "x_q")
+    assert np.array_equal(host(dst).view(np.uint16), want_state.view(np.uint16))
+
+
+# ------------------------------------------------------------------ scan
+def _scan_inputs(rng, Bt, L, Di, N=16):
+    sc = {"s_x": np.float32(0.004), "s_dt": np.float32(0.03), "s_z": np.float32(0.03), "s_B": np.float32(0.02),
+          "s_C": np.float32(0.02), "s_A": np.float32(16 / 127), "s_D": np.float32(1 / 127)}
+    x = rng.integers(-128, 128, (Bt, L, Di), dtype=np.int8)
+    dt = rng.integers(-128, 128, (Bt, L, Di), dtype=np.int8)
+    xz = rng.integers(-128, 128, (Bt, L, 2 * Di), dtype=np.int8)
+    dbc = rng.integers(-128, 128, (Bt, L, 48 + 2 * N), dtype=np.int8)
+    A = -rng.integers(1, 128, (Di, N)).astype(np.int8)
+    D = rng.integers(-128, 128, Di, dtype=np.int8)
+    u = rng.random(Di)
+    step = np.exp(u * (np.log(1e-1) - np.log(1e-3)) + np.log(1e-3))
+    bias = (step + np.log(-np.expm1(-step))).astype(np.float32)
+    return sc, x, dt, xz, dbc, A, D, bias
+
+
+@pytest.mark.parametrize("Bt,L,Di,with_h0", [(1, 1, 64, False), (2, 45, 128, True), (1, 300, 320, False),
+                                              (3, 67, 192, True), (1, 1000, 256, True), (1, 256, 1536, False)])
+def test_scan_prefill(Bt, L, Di, with_h0):
+    rng = np.random.default_rng(L * 31 + Di)
+    sc, x, dt, xz, dbc, A, D, bias = _scan_inputs(rng, Bt, L, Di)
+    R = 48
+    h0 = (rng.standard_normal((Bt, Di, 16)) * 0.1).astype(np.float32) if with_h0 else None
+    g_ref, g16_ref, h_ref = O.q_scan(x, dt, xz[..., Di:], dbc[..., R:R + 16], dbc[..., R + 16:], A, D, bias, sc, h0)
+    full = dict(sc)
+    for k in Q.SCALE_FIELDS:
+        full.setdefault(k, 1.0)
+    dxz, ddbc = dev(xz), dev(dbc)
+    g16 = empty((Bt, L, Di), torch.float16)
+    y32 = empty((Bt, L, Di), torch.float32)
+    ssm = dev(h0) if with_h0 else torch.zeros((Bt, Di, 16), dtype=torch.float32, device="cuda:0")
+    ws = workspace(Q.quamba_scan_workspace_bytes(Bt, L, Di))
+    Q.quamba_scan_prefill(dev(x), dev(dt), dxz[..., Di:], 2 * Di, ddbc[..., R:], ddbc[..., R + 16:], dbc.shape[-1],
+                          dev(A), dev(D), dev(bias), full, Bt, L, Di, g16, y32, ssm, ws)
+    assert rel_err(host(y32), g_ref) <= 1e-3
+    assert rel_err(host(g16).astype(np.float64), g_ref) <= 1e-3
+    assert rel_err(host(ssm), h_ref) <= 1e-3
+    # tighter: the fp32 path should sit near fp32 rounding of the fp64 recurrence
+    assert rel_err(host(y32), g_ref) <= 2e-5
+
+
+@pytest.mark.parametrize("Bt,Di", [(1, 64), (7, 192), (64, 5120)])
+def test_scan_step(Bt, Di):
+    rng = np.random.default_rng(Bt * 13 + Di)
+    sc, x, dt, xz, dbc, A, D, bias = _scan_inputs(rng, Bt, 1, Di)
+    R = 48
+    h0 = (rng.standard_normal((Bt, Di, 16)) * 0.1).astype(np.float32)
+    g_ref, g16_ref, h_ref = O.q_scan(x, dt, xz[..., Di:], dbc[..., R:R + 16], dbc[..., R + 16:], A, D, bias, sc, h0)
+    full = dict(sc)
+    for k in Q.SCALE_FIELDS:
+        full.setdefault(k, 1.0)
+    dxz, ddbc = dev(xz[:, 0]), dev(dbc[:, 0])
+    g16 = empty((Bt, Di), torch.float16)
+    y32 = empty((Bt, Di), torch.float32)
+    ssm = dev(h0)
+    Q.quamba_scan_step(dev(x[:, 0]), dev(dt[:, 0]), dxz[:, Di:], 2 * Di, ddbc[:, R:], ddbc[:, R + 16:],
+                       dbc.shape[-1], dev(A), dev(D), dev(bias), full, Bt, Di, g16, y32, ssm)
+    assert rel_err(host(y32), g_ref[:, 0]) <= 2e-5
+    assert rel_err(host(ssm), h_ref) <= 2e-6
+    assert rel_err(host(g16).astype(np.float64), g_ref[:, 0]) <= 1e-3
+
+
+# ------------------------------------------------------------------ Hadamard + quant
+@pytest.mark.parametrize("M,n", [(3, 16), (5, 128), (4, 192), (4, 320), (33, 1536), (17, 5120), (9, 8192),
+                                 (2, 2048), (2, 640), (1, 16384)])
+def test_hadamard_quant(M, n):
+    rng = np.random.default_rng(n + M)
+    g = rng.standard_normal((M, n)).astype(np.float16)
+    g[0, n // 3] = np.float16(300.0)  # an outlier channel
+    gH = g.astype(np.float64) @ O.hadamard_matrix(n).astype(np.float64).T
+    sc = {"inv_s_y": np.float32(127.0 / np.abs(gH).max())}
+    gH_ref, q_ref = O.q_hadamard_quant(g, sc)
+    q = empty((M, n), torch.int8)
+    f = empty((M, n), torch.float32)
+    Q.quamba_hadamard_quant(dev(g), M, n, sc["inv_s_y"], q, f)
+    assert rel_err(host(f), gH_ref) <= 1e-5
+    assert_lsb(host(q), q_ref, "gH_q")
+    # unit vectors pick out columns of H (orientation of the non-symmetric factors)
+    e = np.zeros((2, n), dtype=np.float16)
+    e[0, 1] = 1
+    e[1, n - 2] = 1
+    q2, f2 = empty((2, n), torch.int8), empty((2, n), torch.float32)
+    Q.quamba_hadamard_quant(dev(e), 2, n, 1.0, q2, f2)
+    H = O.hadamard_matrix(n)
+    assert np.array_equal(host(f2), np.stack([H[:, 1], H[:, n - 2]]).astype(np.float32))
+
+
+def test_hadamard_rejects_unsupported_order():
+    g = torch.zeros((1, 1792), dtype=torch.float16, device="cuda:0")
+    q = torch.zeros((1, 1792), dtype=torch.int8, device="cuda:0")
+    with pytest.raises(Q.QuambaError) as e:
+        Q.quamba_hadamard_quant(g, 1, 1792, 1.0, q, None)  # 7 * 256
+    assert e.value.code == -2
+
+
+# ------------------------------------------------------------------ add + RMSNorm + quant
+@pytest.mark.parametrize("M,Dm", [(1, 64), (37, 768), (256, 2560), (5, 4096)])
+def test_add_rmsnorm_quant(M, Dm):
+    rng = np.random.default_rng(M + Dm)
+    a = rng.standard_normal((M, Dm)).astype(np.float16)
+    r = (rng.standard_normal((M, Dm)) * 3).astype(np.float16)
+    wt = (1 + 0.1 * rng.standard_normal(Dm)).astype(np.float16)
+    inv = np.float32(127 / 5.0)
+    q_ref, res_ref = O.add_rmsnorm_quant(a, r, wt, inv, eps=1e-5)
+    dres = dev(r)
+    q = empty((M, Dm), torch.int8)
+    Q.quamba_add_rmsnorm_quant(dev(a), dres, dev(wt), 1e-5, inv, q, M, Dm)
+    assert np.array_equal(host(dres).view(np.uint16), res_ref.view(np.uint16))
+    assert_lsb(host(q), q_ref, "u_q")
