@@ -65,6 +65,7 @@ def check_chain(cfg, qw, sc, u, r, h0=None, rows=None, chans=None, decode_state=
     g_ref, g16_ref, h_ref = O.q_scan(r["x_q"].reshape(Bt, L, Di)[:, :, cs], r["dt_q"].reshape(Bt, L, Di)[:, :, cs],
                                      xz3[:, :, Di + cs], dbc3[..., R:R + N], dbc3[..., R + N:], qw["A"][cs],
                                      qw["D"][cs], qw["dt_bias"][cs], sc, None if hh is None else hh[:, cs])
+    assert np.isfinite(g16_ref.astype(np.float32)).all(), "workload overflows fp16: not a valid parity case"
     stats["scan_err"] = rel_err(r["y_f32"].reshape(Bt, L, Di)[:, :, cs], g_ref)
     assert stats["scan_err"] <= 1e-3
     assert rel_err(r["g16"].reshape(Bt, L, Di)[:, :, cs].astype(np.float64), g_ref) <= 1e-3
@@ -95,7 +96,7 @@ def end_to_end(r, ref, name):
 @pytest.mark.parametrize("Bt,L,dm,di,rk", [(2, 37, 64, 128, 16), (1, 5, 96, 192, 16), (3, 130, 160, 320, 32)])
 def test_prefill_tiny(Bt, L, dm, di, rk):
     cfg = W.tiny_config(name=f"t{di}", d_model=dm, d_inner=di, dt_rank=rk, batch=Bt, seqlen=L, config_id=91 + di)
-    w, qw, sc = oracle_setup(cfg, randomize_bias=True, gain=10.0)
+    w, qw, sc = oracle_setup(cfg, randomize_bias=True, gain=4.0)
     u = W.make_hidden(cfg)
     rng = np.random.default_rng(5)
     h0 = (rng.standard_normal((Bt, di, 16)) * 0.1).astype(np.float32)
@@ -109,7 +110,7 @@ def test_prefill_tiny(Bt, L, dm, di, rk):
 
 def test_prefill_q_variant_and_null_state():
     cfg = W.tiny_config(name="tq", d_model=64, d_inner=128, dt_rank=16, batch=2, seqlen=20, config_id=95)
-    w, qw, sc = oracle_setup(cfg, randomize_bias=True, gain=10.0)
+    w, qw, sc = oracle_setup(cfg, randomize_bias=True, gain=4.0)
     u = W.make_hidden(cfg)
     qd = qweights_to_dev(qw)
     a = run_prefill(cfg, qd, sc, u, want_state=False, taps=False)
@@ -201,7 +202,7 @@ def _decode_steps(cfg, Bt, steps, qw, sc, check_every=1):
 
 def test_decode_tiny():
     cfg = W.tiny_config(name="td", d_model=64, d_inner=128, dt_rank=16, batch=3, seqlen=1, config_id=96)
-    w, qw, sc = oracle_setup(cfg, randomize_bias=True, gain=10.0)
+    w, qw, sc = oracle_setup(cfg, randomize_bias=True, gain=4.0)
     _decode_steps(cfg, 3, 4, qw, sc)
 
 
@@ -214,7 +215,7 @@ def test_decode_c2_shape():
 def test_prefill_then_decode_handoff():
     """State handed from prefill to decode: prefill(L) + one decode step tracks prefill(L+1)."""
     cfg = W.tiny_config(name="th", d_model=64, d_inner=128, dt_rank=16, batch=2, seqlen=33, config_id=97)
-    w, qw, sc = oracle_setup(cfg, randomize_bias=True, gain=10.0)
+    w, qw, sc = oracle_setup(cfg, randomize_bias=True, gain=4.0)
     qd = qweights_to_dev(qw)
     u = W.make_hidden(cfg, seqlen=34)
     full = run_prefill(cfg, qd, sc, u, taps=False)
