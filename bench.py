@@ -105,8 +105,8 @@ def main():
     tokens_per_s = M / (dt / args.steps)
 
     # ---- per-stage timing with events on the launch stream (stage entry points, same shapes)
-    def timed(fn, iters=50):
-        for _ in range(5):
+    def timed(fn, iters=100):
+        for _ in range(100):  # long enough for the clocks to settle on this kernel's load
             fn()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record(stream)
@@ -125,13 +125,14 @@ def main():
     g16 = torch.empty((M, Di), dtype=torch.float16, device=dev)
     gH_q = torch.empty((M, Di), dtype=i8, device=dev)
     sws = torch.empty(max(Q.quamba_scan_workspace_bytes(Bt, L, Di), 256), dtype=torch.uint8, device=dev)
+    gws = torch.empty(max(Q.quamba_gemm_workspace_bytes(M, NX, Di), 256), dtype=torch.uint8, device=dev)
     # realistic operands for the stage timings: run the chain once through the stage calls
     Q.quamba_quantize_f16(u, u_q, M * Dm, sc.inv_s_u, stream)
     stages = {}
 
     def s_in():
         Q.quamba_gemm_i8(u_q, Dm, qd["W_in"], Dm, M, 2 * Di, Dm, Di, 2 * Di, [sc.m_in_x, sc.m_in_z, sc.m_in_z],
-                         xz_q, None, 2 * Di, None, stream)
+                         xz_q, None, 2 * Di, None, gws, stream)
 
     def s_conv():
         Q.quamba_conv_silu_quant(xz_q, 2 * Di, qd["conv_w"], qd["conv_b"], Bt, L, Di, sc.m_conv, sc.inv_s_x,
@@ -139,10 +140,10 @@ def main():
 
     def s_xp():
         Q.quamba_gemm_i8(x_q, Di, qd["W_x"], Di, M, NX, Di, R, R + N, [sc.m_x_dt, sc.m_x_B, sc.m_x_C], dbc_q, None,
-                         NX, None, stream)
+                         NX, None, gws, stream)
 
     def s_dt():
-        Q.quamba_gemm_i8(dbc_q, NX, qd["W_dt"], R, M, Di, R, Di, Di, [sc.m_dt] * 3, dt_q, None, Di, None, stream)
+        Q.quamba_gemm_i8(dbc_q, NX, qd["W_dt"], R, M, Di, R, Di, Di, [sc.m_dt] * 3, dt_q, None, Di, None, gws, stream)
 
     def s_scan():
         Q.quamba_scan_prefill(x_q, dt_q, xz_q[:, Di:], 2 * Di, dbc_q[:, R:], dbc_q[:, R + N:], NX, qd["A"], qd["D"],
@@ -152,7 +153,7 @@ def main():
         Q.quamba_hadamard_quant(g16, M, Di, sc.inv_s_y, gH_q, None, stream)
 
     def s_out():
-        Q.quamba_gemm_i8(gH_q, Di, qd["W_outH"], Di, M, Dm, Di, Dm, Dm, [sc.m_out] * 3, None, out, Dm, None, stream)
+        Q.quamba_gemm_i8(gH_q, Di, qd["W_outH"], Di, M, Dm, Di, Dm, Dm, [sc.m_out] * 3, None, out, Dm, None, gws, stream)
 
     def s_quant():
         Q.quamba_quantize_f16(u, u_q, M * Dm, sc.inv_s_u, stream)

@@ -180,15 +180,20 @@ int quamba_quantize_f16(const quamba_half *x, int8_t *q, size_t n, float inv_s, 
 /* int8 GEMM on the matrix cores (Section 4.3 "Projection layers"):
  *   acc[m, j] = sum_k A[m, k] * Wt[j, k]   (int32, exact)
  * A [M, K] with row stride lda, Wt [N, K] with row stride ldw (K, lda, ldw multiples of 16;
- * N and ldo multiples of 4).  Column j belongs to range 0 if j < col_end0, range 1 if
- * j < col_end1, else range 2, and is scaled by mult[range].
+ * N, ldo, col_end0, col_end1 multiples of 4).  Column j belongs to range 0 if j < col_end0,
+ * range 1 if j < col_end1, else range 2, and is scaled by mult[range].
  *   out_i8  != NULL: out_i8[m, j] = clamp(rne(float(acc) * mult), -128, 127), row stride ldo
  *   out_f16 != NULL: out_f16[m, j] = fp16(float(acc) * mult), row stride ldo
  *   acc_out != NULL: raw accumulators, dense [M, N]
- * At least one output is required; out_i8 and out_f16 are mutually exclusive. */
+ * At least one output is required; out_i8 and out_f16 are mutually exclusive.
+ * ws (may be NULL) is scratch of quamba_gemm_workspace_bytes(M, N, K) bytes: with it, problems
+ * with few output tiles and deep K are split along K and summed by a second kernel (integer
+ * sums: the result is the same either way). */
+size_t quamba_gemm_workspace_bytes(int M, int N, int K);
 int quamba_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, int N, int K,
                    int col_end0, int col_end1, const float mult[3] /* host */,
-                   int8_t *out_i8, quamba_half *out_f16, int ldo, int32_t *acc_out, void *stream);
+                   int8_t *out_i8, quamba_half *out_f16, int ldo, int32_t *acc_out,
+                   void *ws, size_t ws_bytes, void *stream);
 
 /* Fused int8 causal depthwise conv + SiLU + requantization (Section 4.3 "Fused causal
  * convolution"), width 4, empty history at t < 0 of every sequence:

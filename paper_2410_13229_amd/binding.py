@@ -15,7 +15,7 @@ __all__ = [
     "quamba_last_error", "quamba_workspace_bytes", "quamba_calibrate_workspace_bytes",
     "quamba_calibrate", "quamba_mixer_prefill", "quamba_mixer_prefill_q", "quamba_mixer_decode",
     "quamba_mixer_decode_q", "quamba_add_rmsnorm_quant", "quamba_quantize_f16", "quamba_gemm_i8",
-    "quamba_conv_silu_quant", "quamba_conv_step", "quamba_scan_workspace_bytes",
+    "quamba_gemm_workspace_bytes", "quamba_conv_silu_quant", "quamba_conv_step", "quamba_scan_workspace_bytes",
     "quamba_scan_prefill", "quamba_scan_step", "quamba_hadamard_quant",
 ]
 
@@ -147,7 +147,9 @@ def lib():
     L.quamba_mixer_decode_q.argtypes = dec
     L.quamba_add_rmsnorm_quant.argtypes = [vp, vp, vp, f, f, vp, i, i, vp]
     L.quamba_quantize_f16.argtypes = [vp, vp, sz, f, vp]
-    L.quamba_gemm_i8.argtypes = [vp, i, vp, i, i, i, i, i, i, P(C.c_float), vp, vp, i, vp, vp]
+    L.quamba_gemm_i8.argtypes = [vp, i, vp, i, i, i, i, i, i, P(C.c_float), vp, vp, i, vp, vp, sz, vp]
+    L.quamba_gemm_workspace_bytes.restype = sz
+    L.quamba_gemm_workspace_bytes.argtypes = [i, i, i]
     L.quamba_conv_silu_quant.argtypes = [vp, i, vp, vp, i, i, i, f, f, f, vp, vp, vp]
     L.quamba_conv_step.argtypes = [vp, i, vp, vp, i, i, f, f, f, vp, vp, vp]
     L.quamba_scan_workspace_bytes.restype = sz
@@ -234,10 +236,15 @@ def quamba_quantize_f16(x, q, n, inv_s, stream=None):
     _check(lib().quamba_quantize_f16(_ptr(x), _ptr(q), n, float(inv_s), _stream(stream)))
 
 
-def quamba_gemm_i8(A, lda, Wt, ldw, M, N, K, col_end0, col_end1, mult, out_i8, out_f16, ldo, acc_out, stream=None):
+def quamba_gemm_workspace_bytes(M, N, K) -> int:
+    return int(lib().quamba_gemm_workspace_bytes(M, N, K))
+
+
+def quamba_gemm_i8(A, lda, Wt, ldw, M, N, K, col_end0, col_end1, mult, out_i8, out_f16, ldo, acc_out, ws=None,
+                   stream=None):
     m = (C.c_float * 3)(*[float(v) for v in mult])
     _check(lib().quamba_gemm_i8(_ptr(A), lda, _ptr(Wt), ldw, M, N, K, col_end0, col_end1, m, _ptr(out_i8),
-                                _ptr(out_f16), ldo, _ptr(acc_out), _stream(stream)))
+                                _ptr(out_f16), ldo, _ptr(acc_out), _ptr(ws), _nbytes(ws), _stream(stream)))
 
 
 def quamba_conv_silu_quant(xpre_q, ldx, w_q, conv_b, Bt, L, Di, m_conv, inv_s_x, s_xpre, x_q, conv_state,

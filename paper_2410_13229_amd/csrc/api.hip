@@ -40,7 +40,7 @@ int check_dims(const quamba_dims *d) {
 
 // Workspace carving, shared by the size query and the launches.
 struct Plan {
-  size_t u_q, xz_q, x_q, dbc_q, dt_q, g16, gH_q, scan, total;
+  size_t u_q, xz_q, x_q, dbc_q, dt_q, g16, gH_q, scan, gemm, gemm_bytes, total;
 };
 
 Plan make_plan(const quamba_dims *d, int Bt, int L) {
@@ -61,6 +61,10 @@ Plan make_plan(const quamba_dims *d, int Bt, int L) {
   p.g16 = take(M * d->d_inner * sizeof(__half));
   p.gH_q = take(M * d->d_inner);
   p.scan = take(L > 1 ? scan_workspace_bytes(Bt, L, d->d_inner) : 0);
+  // split-K partial sums: x_proj always (skinny N), every projection when M is small
+  const size_t widest = M <= 64 ? (size_t)2 * d->d_inner : nx;
+  p.gemm_bytes = gemm_workspace_bytes((int)M, (int)widest);
+  p.gemm = take(p.gemm_bytes);
   p.total = off;
   return p;
 }
@@ -122,7 +126,7 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
   // in_proj: columns [0, Di) -> x_pre, [Di, 2Di) -> z
   {
     GemmEpilogue e{xz_q, nullptr, t.acc_in, 2 * Di, Di, 2 * Di, sc->m_in_x, sc->m_in_z, sc->m_in_z};
-    QUAMBA_TRY(launch_gemm_i8(uq, Dm, qw->W_in, Dm, M, 2 * Di, Dm, e, st));
+    QUAMBA_TRY(launch_gemm_i8(uq, Dm, qw->W_in, Dm, M, 2 * Di, Dm, e, base + p.gemm, p.gemm_bytes, st));
     QUAMBA_TRY(tap_copy(t.xz_q, xz_q, (size_t)M * 2 * Di, st));
   }
   // causal conv + SiLU + requantization with the percentile scale of x
@@ -137,13 +141,13 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
   // x_proj: columns dt_low | B | C, each with its own output scale
   {
     GemmEpilogue e{dbc_q, nullptr, t.acc_x, NX, R, R + N, sc->m_x_dt, sc->m_x_B, sc->m_x_C};
-    QUAMBA_TRY(launch_gemm_i8(x_q, Di, qw->W_x, Di, M, NX, Di, e, st));
+    QUAMBA_TRY(launch_gemm_i8(x_q, Di, qw->W_x, Di, M, NX, Di, e, base + p.gemm, p.gemm_bytes, st));
     QUAMBA_TRY(tap_copy(t.dbc_q, dbc_q, (size_t)M * NX, st));
   }
   // dt_proj on the dt_low columns
   {
     GemmEpilogue e{dt_q, nullptr, t.acc_dt, Di, Di, Di, sc->m_dt, sc->m_dt, sc->m_dt};
-    QUAMBA_TRY(launch_gemm_i8(dbc_q, NX, qw->W_dt, R, M, Di, R, e, st));
+    QUAMBA_TRY(launch_gemm_i8(dbc_q, NX, qw->W_dt, R, M, Di, R, e, base + p.gemm, p.gemm_bytes, st));
     QUAMBA_TRY(tap_copy(t.dt_q, dt_q, (size_t)M * Di, st));
   }
   // selective scan + gate
@@ -168,7 +172,7 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
   // out_proj with the folded weight, fp16 out; the multiplier carries s_y s_WoutH / n
   {
     GemmEpilogue e{nullptr, out, t.acc_out, Dm, Dm, Dm, sc->m_out, sc->m_out, sc->m_out};
-    QUAMBA_TRY(launch_gemm_i8(gH_q, Di, qw->W_outH, Di, M, Dm, Di, e, st));
+    QUAMBA_TRY(launch_gemm_i8(gH_q, Di, qw->W_outH, Di, M, Dm, Di, e, base + p.gemm, p.gemm_bytes, st));
   }
   return QUAMBA_OK;
 }
@@ -268,9 +272,15 @@ int quamba_quantize_f16(const quamba_half *x, int8_t *q, size_t n, float inv_s, 
   return launch_quantize_f16(reinterpret_cast<const __half *>(x), q, n, inv_s, as_stream(stream));
 }
 
+size_t quamba_gemm_workspace_bytes(int M, int N, int K) {
+  (void)K;
+  if (M < 1 || N < 1) return 0;
+  return gemm_workspace_bytes(M, N);
+}
+
 int quamba_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, int N, int K, int col_end0,
                    int col_end1, const float mult[3], int8_t *out_i8, quamba_half *out_f16, int ldo,
-                   int32_t *acc_out, void *stream) {
+                   int32_t *acc_out, void *ws, size_t ws_bytes, void *stream) {
   if (!A || !Wt || !mult) return fail(QUAMBA_EINVAL, "NULL pointer");
   if (!out_i8 && !out_f16 && !acc_out) return fail(QUAMBA_EINVAL, "gemm: no output requested");
   if (out_i8 && out_f16) return fail(QUAMBA_EINVAL, "gemm: out_i8 and out_f16 are mutually exclusive");
@@ -279,13 +289,16 @@ int quamba_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, i
     return fail(QUAMBA_EUNSUPPORTED, "gemm: K, lda, ldw must be multiples of 16 with lda, ldw >= K");
   if (N % 4 || ((out_i8 || out_f16) && (ldo % 4 || ldo < N)))
     return fail(QUAMBA_EUNSUPPORTED, "gemm: N and ldo must be multiples of 4 with ldo >= N");
+  if (col_end0 % 4 || col_end1 % 4 || col_end0 < 0 || col_end1 < col_end0)
+    return fail(QUAMBA_EUNSUPPORTED, "gemm: column ranges must end on multiples of 4, in order");
+  if (ws && !aligned(ws, 16)) return fail(QUAMBA_EINVAL, "gemm: workspace must be 16-byte aligned");
   if (!aligned(A, 16) || !aligned(Wt, 16) || (out_i8 && !aligned(out_i8, 4)) || (out_f16 && !aligned(out_f16, 8)) ||
       (acc_out && !aligned(acc_out, 16)))
     return fail(QUAMBA_EINVAL, "gemm: misaligned buffer");
   if (M == 0) return QUAMBA_OK;
   GemmEpilogue e{out_i8, reinterpret_cast<__half *>(out_f16), acc_out, ldo, col_end0, col_end1, mult[0], mult[1],
                  mult[2]};
-  return launch_gemm_i8(A, lda, Wt, ldw, M, N, K, e, as_stream(stream));
+  return launch_gemm_i8(A, lda, Wt, ldw, M, N, K, e, ws, ws ? ws_bytes : 0, as_stream(stream));
 }
 
 int quamba_conv_silu_quant(const int8_t *xpre_q, int ldx, const int8_t *w_q, const float *conv_b, int Bt, int L,

@@ -48,8 +48,10 @@ struct GemmEpilogue {
   float m0, m1, m2;
 };
 
+// `ws` (may be NULL) lets skinny problems split K; gemm_workspace_bytes is the most they use.
+size_t gemm_workspace_bytes(int M, int N);
 int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, int N, int K,
-                   const GemmEpilogue &epi, hipStream_t st);
+                   const GemmEpilogue &epi, void *ws, size_t ws_bytes, hipStream_t st);
 
 int launch_quantize_f16(const __half *x, int8_t *q, size_t n, float inv_s, hipStream_t st);
 

@@ -4,13 +4,22 @@
 //
 //   acc[m, j] = sum_k A[m, k] * Wt[j, k]          A [M, K], Wt [N, K], both K-contiguous
 //
-// One workgroup of 4 wave64s owns a BM x BN tile of the output.  K is walked in slices of 64
-// bytes: each slice of A and Wt is fetched with 16-byte global loads into registers, parked in
-// LDS (double buffered, XOR-swizzled so both the 16-byte writes and the MFMA operand reads are
-// bank-conflict free) and consumed by v_mfma_i32_32x32x32_i8.  The weight fragment is the
-// MFMA "A" operand and the activation fragment the "B" operand, so each lane ends up holding
-// four consecutive output columns of one token row and can requantize, pack and store them as
-// one 32-bit (int8) or 64-bit (fp16) word.
+// One workgroup of 4 wave64s owns a BM x BN tile of the output and walks K in slices that are
+// parked in LDS (XOR-swizzled 16-byte chunks, so the fills and the MFMA operand reads are free
+// of bank conflicts) and consumed by v_mfma_i32_32x32x32_i8.  The weight fragment is the MFMA
+// "A" operand and the activation fragment the "B" operand, so each lane ends up holding four
+// consecutive output columns of one token row and can requantize, pack and store them as one
+// 32-bit (int8) or 64-bit (fp16) word.
+//
+// Two kernels share that tiling:
+//   gemm_i8_dma_kernel   K a multiple of the slice width.  Slices travel with gfx950's 16-byte
+//                        direct-to-LDS loads (global_load_lds_dwordx4): no staging registers, no
+//                        LDS write instructions, a ring of LDS stages whose arrival is tracked
+//                        with an explicit vmcnt wait in front of one barrier per slice.
+//   gemm_i8_kernel       register-staged, zero-fills ragged K, serves small / ragged shapes.
+// Skinny problems (few output tiles, deep K) are split along K over grid.y; the int32 partial
+// sums go to a workspace and a second kernel adds them and applies the epilogue (integer
+// addition, so the result does not depend on the order).
 #include "common.h"
 
 namespace quamba {
@@ -20,27 +29,99 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 namespace {
 
-constexpr int BK = 64;  // bytes of K per LDS tile row
-
-// Byte offset of 16-byte chunk `chunk` (0..3) of tile row `row`.  Rows are 64 bytes, so four
-// rows span the 64 LDS banks once; XOR-ing the chunk index with bits 2..3 of the row spreads
-// any 16 consecutive rows read at one logical chunk over all banks.
-__device__ __forceinline__ int swz(int row, int chunk) {
-  return row * BK + ((chunk ^ ((row >> 2) & 3)) << 4);
+// Byte offset of 16-byte chunk `chunk` of tile row `row` for rows of BKB bytes.  With 64-byte
+// rows four rows span the 64 LDS banks and the chunk index is XOR-ed with bits 2..3 of the row;
+// with 128-byte rows two rows span them and bits 1..3 are used.  Either way any 16 consecutive
+// rows read at one logical chunk hit 16 different bank groups.
+template <int BKB>
+__device__ __forceinline__ int swzk(int row, int chunk) {
+  if constexpr (BKB == 64) return row * 64 + ((chunk ^ ((row >> 2) & 3)) << 4);
+  else return row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4);
 }
 
-__device__ __forceinline__ int requant1(int acc, float m) {
-  float v = __builtin_rintf(static_cast<float>(acc) * m);
-  v = fminf(fmaxf(v, -128.f), 127.f);
-  return static_cast<int>(v);
+__device__ __forceinline__ unsigned requant_pack4(const int (&a)[4], float m) {
+  unsigned p = 0;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    float v = __builtin_rintf(static_cast<float>(a[e]) * m);
+    v = __builtin_amdgcn_fmed3f(v, -128.f, 127.f);
+    p |= (static_cast<unsigned>(static_cast<int>(v)) & 0xffu) << (8 * e);
+  }
+  return p;
 }
 
+// Epilogue for four consecutive columns gn..gn+3 of row gm.  The column ranges end on multiples
+// of 4, so one multiplier serves the group.
+__device__ __forceinline__ void emit4(const GemmEpilogue &epi, int gm, int gn, int N, const int (&a)[4]) {
+  if (epi.acc) {
+    v4i v = {a[0], a[1], a[2], a[3]};
+    *reinterpret_cast<v4i *>(epi.acc + (size_t)gm * N + gn) = v;
+  }
+  const float m = gn < epi.e0 ? epi.m0 : (gn < epi.e1 ? epi.m1 : epi.m2);
+  if (epi.out_i8) {
+    *reinterpret_cast<unsigned *>(epi.out_i8 + (size_t)gm * epi.ldo + gn) = requant_pack4(a, m);
+  } else if (epi.out_f16) {
+    union {
+      __half h[4];
+      uint2 u;
+    } pk;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) pk.h[e] = __float2half_rn(static_cast<float>(a[e]) * m);
+    *reinterpret_cast<uint2 *>(epi.out_f16 + (size_t)gm * epi.ldo + gn) = pk.u;
+  }
+}
+
+// Register r of lane l in MFMA tile (i, j) holds
+//   column n = n_base + i*32 + 8*(r/4) + 4*(l/32) + r%4,   row m = m_base + j*32 + l%32.
+// `partial` != nullptr: split-K launch, raw sums go to partial[M, N].
+template <int TM, int TN>
+__device__ __forceinline__ void store_tiles(const v16i (&acc)[TN][TM], int m_base, int n_base, int lane,
+                                            int M, int N, const GemmEpilogue &epi, int32_t *partial) {
+#pragma unroll
+  for (int i = 0; i < TN; ++i) {
+#pragma unroll
+    for (int j = 0; j < TM; ++j) {
+      const int gm = m_base + j * 32 + (lane & 31);
+      if (gm >= M) continue;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int gn = n_base + i * 32 + 8 * g + 4 * (lane >> 5);
+        if (gn >= N) continue;  // N is a multiple of 4: a group is all in or all out
+        const int a[4] = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+        if (partial) {
+          v4i v = {a[0], a[1], a[2], a[3]};
+          *reinterpret_cast<v4i *>(partial + (size_t)gm * N + gn) = v;
+        } else {
+          emit4(epi, gm, gn, N, a);
+        }
+      }
+    }
+  }
+}
+
+// Workgroup ids are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of tiles
+// (same weight columns, consecutive token rows) so its L2 sees each weight slice once.
+__device__ __forceinline__ int xcd_tile_id(int wg, int nwg) {
+  const int per = nwg >> 3;
+  return (wg < (per << 3)) ? (wg & 7) * per + (wg >> 3) : wg;
+}
+
+struct KSplit {
+  int slices_per_split;  // K slices handled by one grid.y index
+  int32_t *partial;      // [splits, M, N] when splitting, else nullptr
+};
+
+// ------------------------------------------------------------------------------------------
+// Register-staged kernel: 16-byte global loads into registers, parked in a double-buffered LDS
+// tile after the MFMAs of the current slice; chunks past K are zero-filled.
+// ------------------------------------------------------------------------------------------
 template <int BM, int BN, int WGM, int WGN>
 __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t *__restrict__ A, int lda,
-                                                      const int8_t *__restrict__ Wt, int ldw,
-                                                      int M, int N, int K, GemmEpilogue epi,
-                                                      int tiles_m, int tiles_n) {
+                                                      const int8_t *__restrict__ Wt, int ldw, int M, int N,
+                                                      int K, GemmEpilogue epi, int tiles_m, int tiles_n,
+                                                      KSplit ks) {
   static_assert(WGM * WGN == 4, "four waves per workgroup");
+  constexpr int BK = 64;
   constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int TM = WM / 32, TN = WN / 32;
   static_assert(TM >= 1 && TN >= 1 && BM % 64 == 0 && BN % 64 == 0, "tile shape");
@@ -48,14 +129,11 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t *__restrict__
 
   __shared__ __attribute__((aligned(16))) int8_t lds[2][(BM + BN) * BK];
 
-  // Workgroup ids are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of
-  // tiles (same weight columns, consecutive token rows) so its L2 sees each weight slice once.
-  const int nwg = tiles_m * tiles_n;
-  const int per = nwg >> 3;
-  const int wg = blockIdx.x;
-  const int id = (wg < (per << 3)) ? (wg & 7) * per + (wg >> 3) : wg;
+  const int id = xcd_tile_id(blockIdx.x, tiles_m * tiles_n);
   const int m0 = (id % tiles_m) * BM;
   const int n0 = (id / tiles_m) * BN;
+  const int k_lo = blockIdx.y * ks.slices_per_split * BK;
+  const int k_hi = min(K, k_lo + ks.slices_per_split * BK);
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -71,7 +149,6 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t *__restrict__
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
   v4i ra[A_CH], rw[W_CH];
-
   auto fetch = [&](int k0) {
 #pragma unroll
     for (int i = 0; i < A_CH; ++i) {
@@ -79,7 +156,7 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t *__restrict__
       const int row = c >> 2, ch = c & 3;
       const int gm = m0 + row, gk = k0 + ch * 16;
       v4i v = {0, 0, 0, 0};
-      if (gm < M && gk < K) v = *reinterpret_cast<const v4i *>(A + (size_t)gm * lda + gk);
+      if (gm < M && gk < k_hi) v = *reinterpret_cast<const v4i *>(A + (size_t)gm * lda + gk);
       ra[i] = v;
     }
 #pragma unroll
@@ -88,7 +165,7 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t *__restrict__
       const int row = c >> 2, ch = c & 3;
       const int gn = n0 + row, gk = k0 + ch * 16;
       v4i v = {0, 0, 0, 0};
-      if (gn < N && gk < K) v = *reinterpret_cast<const v4i *>(Wt + (size_t)gn * ldw + gk);
+      if (gn < N && gk < k_hi) v = *reinterpret_cast<const v4i *>(Wt + (size_t)gn * ldw + gk);
       rw[i] = v;
     }
   };
@@ -98,35 +175,36 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t *__restrict__
 #pragma unroll
     for (int i = 0; i < A_CH; ++i) {
       const int c = tid + i * 256;
-      *reinterpret_cast<v4i *>(la + swz(c >> 2, c & 3)) = ra[i];
+      *reinterpret_cast<v4i *>(la + swzk<64>(c >> 2, c & 3)) = ra[i];
     }
 #pragma unroll
     for (int i = 0; i < W_CH; ++i) {
       const int c = tid + i * 256;
-      *reinterpret_cast<v4i *>(lw + swz(c >> 2, c & 3)) = rw[i];
+      *reinterpret_cast<v4i *>(lw + swzk<64>(c >> 2, c & 3)) = rw[i];
     }
   };
 
-  const int nk = (K + BK - 1) / BK;
-  fetch(0);
-  park(0);
+  const int nk = (k_hi - k_lo + BK - 1) / BK;
+  if (nk > 0) {
+    fetch(k_lo);
+    park(0);
+  }
   __syncthreads();
-
   for (int kt = 0; kt < nk; ++kt) {
     const int buf = kt & 1;
-    if (kt + 1 < nk) fetch((kt + 1) * BK);
+    if (kt + 1 < nk) fetch(k_lo + (kt + 1) * BK);
     const int8_t *la = lds[buf];
     const int8_t *lw = lds[buf] + BM * BK;
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      const int chunk = ks * 2 + (lane >> 5);
+    for (int s = 0; s < 2; ++s) {
+      const int chunk = s * 2 + (lane >> 5);
       v4i fa[TM], fw[TN];
 #pragma unroll
       for (int j = 0; j < TM; ++j)
-        fa[j] = *reinterpret_cast<const v4i *>(la + swz(wm * WM + j * 32 + (lane & 31), chunk));
+        fa[j] = *reinterpret_cast<const v4i *>(la + swzk<64>(wm * WM + j * 32 + (lane & 31), chunk));
 #pragma unroll
       for (int i = 0; i < TN; ++i)
-        fw[i] = *reinterpret_cast<const v4i *>(lw + swz(wn * WN + i * 32 + (lane & 31), chunk));
+        fw[i] = *reinterpret_cast<const v4i *>(lw + swzk<64>(wn * WN + i * 32 + (lane & 31), chunk));
 #pragma unroll
       for (int i = 0; i < TN; ++i)
 #pragma unroll
@@ -136,66 +214,227 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t *__restrict__
     if (kt + 1 < nk) park(buf ^ 1);
     __syncthreads();
   }
-
-  // Epilogue.  Register r of lane l in tile (i, j) holds
-  //   column n = n0 + wn*WN + i*32 + 8*(r/4) + 4*(l/32) + r%4,  row m = m0 + wm*WM + j*32 + l%32.
-#pragma unroll
-  for (int i = 0; i < TN; ++i) {
-#pragma unroll
-    for (int j = 0; j < TM; ++j) {
-      const int gm = m0 + wm * WM + j * 32 + (lane & 31);
-      if (gm >= M) continue;
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int gn = n0 + wn * WN + i * 32 + 8 * g + 4 * (lane >> 5);
-        if (gn >= N) continue;  // N is a multiple of 4: a group is all in or all out
-        int a[4];
-        float mlt[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          a[e] = acc[i][j][4 * g + e];
-          const int c = gn + e;
-          mlt[e] = c < epi.e0 ? epi.m0 : (c < epi.e1 ? epi.m1 : epi.m2);
-        }
-        if (epi.acc) {
-          v4i v = {a[0], a[1], a[2], a[3]};
-          *reinterpret_cast<v4i *>(epi.acc + (size_t)gm * N + gn) = v;
-        }
-        if (epi.out_i8) {
-          unsigned p = 0;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) p |= (static_cast<unsigned>(requant1(a[e], mlt[e])) & 0xffu) << (8 * e);
-          *reinterpret_cast<unsigned *>(epi.out_i8 + (size_t)gm * epi.ldo + gn) = p;
-        } else if (epi.out_f16) {
-          union {
-            __half h[4];
-            uint2 u;
-          } pk;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) pk.h[e] = __float2half_rn(static_cast<float>(a[e]) * mlt[e]);
-          *reinterpret_cast<uint2 *>(epi.out_f16 + (size_t)gm * epi.ldo + gn) = pk.u;
-        }
-      }
-    }
-  }
+  store_tiles<TM, TN>(acc, m0 + wm * WM, n0 + wn * WN, lane, M, N, epi,
+                      ks.partial ? ks.partial + (size_t)blockIdx.y * M * N : nullptr);
 }
 
-template <int BM, int BN, int WGM, int WGN>
-int run(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, int N, int K,
-        const GemmEpilogue &epi, hipStream_t st) {
+// ------------------------------------------------------------------------------------------
+// Direct-to-LDS kernel.  A wave-level global_load_lds_dwordx4 writes 64 lanes x 16 bytes to
+// LDS base (M0) + lane * 16, i.e. 1024 / BKB consecutive tile rows; the swizzle is therefore
+// applied on the global side: each lane fetches the logical chunk that belongs in its slot.
+// Ring of S stages.  Iteration k: wait until this wave's loads of slice k have landed (vmcnt <=
+// loads issued after them), barrier (everyone's part of slice k is in LDS and everyone is done
+// reading slice k-1), refill the stage slice k-1 occupied with slice k+S-1, multiply slice k.
+// Rows past M or N are clamped to the last valid row: they are loaded and multiplied but never
+// stored.
+// ------------------------------------------------------------------------------------------
+template <int BM, int BN, int WGM, int WGN, int S, int BKB, int OCC>
+__global__ __launch_bounds__(256, OCC) void gemm_i8_dma_kernel(const int8_t *__restrict__ A, int lda,
+                                                               const int8_t *__restrict__ Wt, int ldw,
+                                                               int M, int N, int K, GemmEpilogue epi,
+                                                               int tiles_m, int tiles_n, KSplit ks) {
+  static_assert(WGM * WGN == 4, "four waves per workgroup");
+  static_assert(BKB == 64 || BKB == 128, "slice width");
+  constexpr int WM = BM / WGM, WN = BN / WGN;
+  constexpr int TM = WM / 32, TN = WN / 32;
+  constexpr int RPI = 1024 / BKB;  // tile rows written by one wave-level load
+  constexpr int CPR = BKB / 16;    // 16-byte chunks per row
+  static_assert(TM >= 1 && TN >= 1 && WM % 32 == 0 && WN % 32 == 0 && BM % RPI == 0 && BN % RPI == 0, "tile");
+  constexpr int ROWS = BM + BN;
+  constexpr int NJ = ROWS / RPI;    // wave-level loads per slice
+  constexpr int NI = (NJ + 3) / 4;  // per wave (a short wave repeats the last group)
+  constexpr int STAGE = ROWS * BKB;
+  static_assert((S - 2) * NI <= 63 && S >= 2, "vmcnt is 6 bits");
+
+  extern __shared__ __attribute__((aligned(16))) int8_t ring[];
+
+  const int id = xcd_tile_id(blockIdx.x, tiles_m * tiles_n);
+  const int m0 = (id % tiles_m) * BM;
+  const int n0 = (id / tiles_m) * BN;
+  const int slice_lo = blockIdx.y * ks.slices_per_split;
+  const int nk = min(K / BKB - slice_lo, ks.slices_per_split);
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave % WGM, wn = wave / WGM;
+
+  const int8_t *src[NI];
+  int dst[NI];
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    const int j = min(wave + 4 * i, NJ - 1);
+    const int row = j * RPI + lane / CPR;
+    const int lrow = row < BM ? row : row - BM;  // the swizzle phase follows the row inside its operand
+    const int chunk = BKB == 64 ? ((lane % CPR) ^ ((lrow >> 2) & 3)) : ((lane % CPR) ^ ((lrow >> 1) & 7));
+    dst[i] = j * 1024;
+    if (row < BM)
+      src[i] = A + (size_t)min(m0 + row, M - 1) * lda + (size_t)slice_lo * BKB + chunk * 16;
+    else
+      src[i] = Wt + (size_t)min(n0 + row - BM, N - 1) * ldw + (size_t)slice_lo * BKB + chunk * 16;
+  }
+  auto issue = [&](int stage, int kslice) {
+#pragma unroll
+    for (int i = 0; i < NI; ++i)
+      __builtin_amdgcn_global_load_lds(
+          (const void __attribute__((address_space(1))) *)(src[i] + (size_t)kslice * BKB),
+          (void __attribute__((address_space(3))) *)(ring + stage * STAGE + dst[i]), 16, 0, 0);
+  };
+
+  v16i acc[TN][TM];
+#pragma unroll
+  for (int i = 0; i < TN; ++i)
+#pragma unroll
+    for (int j = 0; j < TM; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+
+  auto compute = [&](int stage) {
+    const int8_t *la = ring + stage * STAGE;
+    const int8_t *lw = la + BM * BKB;
+#pragma unroll
+    for (int s = 0; s < BKB / 32; ++s) {
+      const int chunk = s * 2 + (lane >> 5);
+      v4i fa[TM], fw[TN];
+#pragma unroll
+      for (int j = 0; j < TM; ++j)
+        fa[j] = *reinterpret_cast<const v4i *>(la + swzk<BKB>(wm * WM + j * 32 + (lane & 31), chunk));
+#pragma unroll
+      for (int i = 0; i < TN; ++i)
+        fw[i] = *reinterpret_cast<const v4i *>(lw + swzk<BKB>(wn * WN + i * 32 + (lane & 31), chunk));
+#pragma unroll
+      for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[i], fa[j], acc[i][j], 0, 0, 0);
+    }
+  };
+
+  // s_waitcnt immediate for "vmcnt <= n, nothing else waited for" (gfx9 encoding: vmcnt in
+  // bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8)
+#define QUAMBA_VMCNT(n) (((n) & 0xF) | ((((n) >> 4) & 0x3) << 14) | (0x7 << 4) | (0xF << 8))
+#pragma unroll
+  for (int s = 0; s < S - 1; ++s)
+    if (s < nk) issue(s, s);
+  int stage = 0;
+  for (int kt = 0; kt < nk; ++kt) {
+    if (kt + S - 2 < nk)
+      __builtin_amdgcn_s_waitcnt(QUAMBA_VMCNT((S - 2) * NI));  // slices kt+1 .. kt+S-2 may be in flight
+    else
+      __builtin_amdgcn_s_waitcnt(QUAMBA_VMCNT(0));             // tail: fewer slices were issued
+    __builtin_amdgcn_s_barrier();
+    if (kt + S - 1 < nk) issue(stage == 0 ? S - 1 : stage - 1, kt + S - 1);
+    compute(stage);
+    stage = (stage + 1 == S) ? 0 : stage + 1;
+  }
+#undef QUAMBA_VMCNT
+
+  store_tiles<TM, TN>(acc, m0 + wm * WM, n0 + wn * WN, lane, M, N, epi,
+                      ks.partial ? ks.partial + (size_t)blockIdx.y * M * N : nullptr);
+}
+
+// Sum of the split-K partials + epilogue; one thread per group of four columns.
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const int32_t *__restrict__ partial, int splits,
+                                                            int M, int N, GemmEpilogue epi) {
+  const size_t g = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t groups = (size_t)M * (N / 4);
+  if (g >= groups) return;
+  const int gm = static_cast<int>(g / (N / 4));
+  const int gn = static_cast<int>(g % (N / 4)) * 4;
+  int a[4] = {0, 0, 0, 0};
+  for (int s = 0; s < splits; ++s) {
+    const v4i v = *reinterpret_cast<const v4i *>(partial + ((size_t)s * M + gm) * N + gn);
+    a[0] += v[0];
+    a[1] += v[1];
+    a[2] += v[2];
+    a[3] += v[3];
+  }
+  emit4(epi, gm, gn, N, a);
+}
+
+template <int BM, int BN, int WGM, int WGN, int S, int BKB, int OCC>
+int run_dma(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, int N, int K,
+            const GemmEpilogue &epi, int splits, const KSplit &ks, hipStream_t st) {
+  constexpr size_t lds = (size_t)S * (BM + BN) * BKB;
+  static bool attr_set = false;
+  if (!attr_set) {
+    QUAMBA_HIP(hipFuncSetAttribute(
+        reinterpret_cast<const void *>(&gemm_i8_dma_kernel<BM, BN, WGM, WGN, S, BKB, OCC>),
+        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    attr_set = true;
+  }
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-  hipLaunchKernelGGL((gemm_i8_kernel<BM, BN, WGM, WGN>), dim3(tiles_m * tiles_n), dim3(256), 0, st,
-                     A, lda, Wt, ldw, M, N, K, epi, tiles_m, tiles_n);
+  hipLaunchKernelGGL((gemm_i8_dma_kernel<BM, BN, WGM, WGN, S, BKB, OCC>), dim3(tiles_m * tiles_n, splits),
+                     dim3(256), lds, st, A, lda, Wt, ldw, M, N, K, epi, tiles_m, tiles_n, ks);
   QUAMBA_LAUNCH_CHECK();
   return QUAMBA_OK;
 }
 
+template <int BM, int BN, int WGM, int WGN>
+int run_reg(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, int N, int K,
+            const GemmEpilogue &epi, int splits, const KSplit &ks, hipStream_t st) {
+  const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+  hipLaunchKernelGGL((gemm_i8_kernel<BM, BN, WGM, WGN>), dim3(tiles_m * tiles_n, splits), dim3(256), 0, st, A,
+                     lda, Wt, ldw, M, N, K, epi, tiles_m, tiles_n, ks);
+  QUAMBA_LAUNCH_CHECK();
+  return QUAMBA_OK;
+}
+
+int g_gemm_variant = -1;  // tuning hook: >= 0 forces a kernel configuration
+
 }  // namespace
 
+size_t gemm_workspace_bytes(int M, int N) {
+  // room for up to 8 int32 partial copies of a skinny output
+  return (size_t)8 * M * N * sizeof(int32_t);
+}
+
 int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, int N, int K,
-                   const GemmEpilogue &epi, hipStream_t st) {
-  if (M <= 64 || N <= 512) return run<64, 64, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, st);
-  return run<128, 128, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, st);
+                   const GemmEpilogue &epi, void *ws, size_t ws_bytes, hipStream_t st) {
+  const bool k64 = (K % 64) == 0, k128 = (K % 128) == 0;
+  // which kernel: 0 = reg 64x64, 1 = reg 128x128, 2 = dma 128x160 (128-byte slices),
+  // 3 = dma 64x64 (64-byte slices, ring of 4), 4 = dma 256x160 (64-byte slices, ring of 3)
+  int kind;
+  if (M <= 64 || N <= 512)
+    kind = k64 ? 3 : 0;
+  else if (k128 && M >= 256 && N >= 640)
+    kind = 2;
+  else
+    kind = 1;
+  if (g_gemm_variant >= 0 && (g_gemm_variant < 2 || (g_gemm_variant == 3 && k64) || (g_gemm_variant != 3 && k128)))
+    kind = g_gemm_variant;
+
+  // split K when the output has too few tiles to fill 256 CUs and K is deep
+  int splits = 1;
+  const int slice = (kind == 2) ? 128 : 64;
+  const int nslices = (K + slice - 1) / slice;
+  if ((kind == 0 || kind == 3) && ws != nullptr) {
+    const int tiles = ((M + 63) / 64) * ((N + 63) / 64);
+    int want = 512 / (tiles > 0 ? tiles : 1);
+    if (want > 8) want = 8;
+    while (want > 1 && (nslices / want < 8 || (size_t)want * M * N * sizeof(int32_t) > ws_bytes)) --want;
+    if (want > 1) splits = want;
+  }
+  KSplit ks{(nslices + splits - 1) / splits, nullptr};
+  splits = (nslices + ks.slices_per_split - 1) / ks.slices_per_split;
+  if (splits > 1) ks.partial = static_cast<int32_t *>(ws);
+
+  int rc;
+  switch (kind) {
+    case 0: rc = run_reg<64, 64, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
+    case 2: rc = run_dma<128, 160, 4, 1, 2, 128, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
+    case 3: rc = run_dma<64, 64, 2, 2, 4, 64, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
+    case 4: rc = run_dma<256, 160, 4, 1, 3, 64, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
+    default: rc = run_reg<128, 128, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
+  }
+  if (rc != QUAMBA_OK || splits == 1) return rc;
+  const size_t groups = (size_t)M * (N / 4);
+  hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, st, ks.partial,
+                     splits, M, N, epi);
+  QUAMBA_LAUNCH_CHECK();
+  return QUAMBA_OK;
 }
 
 }  // namespace quamba
+
+extern "C" void quamba_debug_set_gemm_variant(int v) { quamba::g_gemm_variant = v; }

@@ -25,7 +25,7 @@ namespace {
 constexpr float LOG2E = 1.44269504088896340736f;
 constexpr float LN2 = 0.69314718055994530942f;
 constexpr int NS = 16;       // d_state
-constexpr int TB = 32;       // tokens of B/C staged in LDS at a time
+constexpr int TB = 64;       // tokens of B/C staged in LDS at a time
 constexpr int SCAN_THREADS = 256;
 
 __device__ __forceinline__ float exp2_fast(float v) { return __builtin_amdgcn_exp2f(v); }
@@ -56,7 +56,7 @@ struct Dev {
   float *ssum;  // [Bt, nchunks, Di]
 };
 
-// Dequantize B (and C) of tokens [t, t+cnt) of sequence b into LDS as fp32 [TB][16].
+// Dequantize B (and C) of tokens [row0, row0+cnt) into LDS as fp32 [TB][16].
 template <bool WITH_C>
 __device__ __forceinline__ void stage_bc(const Dev &p, size_t row0, int cnt, float (*sB)[NS],
                                          float (*sC)[NS]) {
@@ -72,9 +72,14 @@ __device__ __forceinline__ void stage_bc(const Dev &p, size_t row0, int cnt, flo
   }
 }
 
-// ---------------------------------------------------------------- pass 1: chunk-local state
-__global__ __launch_bounds__(SCAN_THREADS) void scan_local_kernel(Dev p) {
+// One (chunk, 256-channel) tile of the scan.  OUTPUT = false: pass 1 (state from zero, sum of
+// dt).  OUTPUT = true: pass 3 (state from the carried start, gated output).
+// The int8 x / dt / z bytes of the next TS tokens are fetched into registers while the
+// current TS tokens are computed, so no load latency sits on the recurrence.
+template <bool OUTPUT>
+__global__ __launch_bounds__(SCAN_THREADS) void scan_chunk_kernel(Dev p) {
   __shared__ __attribute__((aligned(16))) float sB[TB][NS];
+  __shared__ __attribute__((aligned(16))) float sC[OUTPUT ? TB : 1][NS];
   const int d = blockIdx.x * SCAN_THREADS + threadIdx.x;
   const int c = blockIdx.y, b = blockIdx.z;
   const bool live = d < p.Di;
@@ -90,27 +95,81 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_local_kernel(Dev p) {
       a2[n] = static_cast<float>(static_cast<int8_t>(aw[n >> 2] >> (8 * (n & 3)))) * (p.s_A * LOG2E);
       h[n] = 0.f;
     }
+    if (OUTPUT) {
+      const float *src = p.hloc + (((size_t)b * p.nchunks + c) * p.Di + dd) * NS;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float4 v = reinterpret_cast<const float4 *>(src)[q];
+        h[4 * q] = v.x;
+        h[4 * q + 1] = v.y;
+        h[4 * q + 2] = v.z;
+        h[4 * q + 3] = v.w;
+      }
+    }
   }
   const float bias = p.dt_bias[dd];
+  const float Dv = OUTPUT ? p.s_D * static_cast<float>(p.D_q[dd]) : 0.f;
   float sdt = 0.f;
   const size_t seq0 = (size_t)b * p.L;
+  const int8_t *xp = p.x_q + seq0 * p.Di + dd;
+  const int8_t *dp = p.dt_q + seq0 * p.Di + dd;
+  const int8_t *zp = p.z_q + seq0 * p.ldz + dd;
+
+  constexpr int TS = 8;
+  struct Regs {
+    int x[TS], dt[TS], z[TS];
+  };
+  auto fetch = [&](Regs &r, int t) {
+#pragma unroll
+    for (int i = 0; i < TS; ++i) {
+      const int tt = min(t + i, t1 - 1);  // clamp: tokens past the chunk are loaded but never used
+      r.x[i] = xp[(size_t)tt * p.Di];
+      r.dt[i] = dp[(size_t)tt * p.Di];
+      if (OUTPUT) r.z[i] = zp[(size_t)tt * p.ldz];
+    }
+  };
+  auto compute = [&](const Regs &r, int t, int tl) {  // t: token index, tl: index inside the LDS block
+#pragma unroll
+    for (int i = 0; i < TS; ++i) {
+      if (t + i < t1) {
+        const float xv = p.s_x * static_cast<float>(r.x[i]);
+        const float dt = softplus_f(p.s_dt * static_cast<float>(r.dt[i]) + bias);
+        const float u = dt * xv;
+        if (!OUTPUT) sdt += dt;
+        float y = 0.f;
+#pragma unroll
+        for (int n = 0; n < NS; ++n) {
+          h[n] = exp2_fast(dt * a2[n]) * h[n] + u * sB[tl + i][n];
+          if (OUTPUT) y += sC[tl + i][n] * h[n];
+        }
+        if (OUTPUT) {
+          y += Dv * xv;
+          const float g = silu_gate(y, p.s_z * static_cast<float>(r.z[i]));
+          if (live) {
+            const size_t o = (seq0 + t + i) * p.Di + d;
+            p.g16[o] = __float2half_rn(g);
+            if (p.y_f32) p.y_f32[o] = g;
+          }
+        }
+      }
+    }
+  };
 
   for (int tb = t0; tb < t1; tb += TB) {
     const int cnt = min(TB, t1 - tb);
+    Regs ra, rb;
+    fetch(ra, tb);
     __syncthreads();
-    stage_bc<false>(p, seq0 + tb, cnt, sB, nullptr);
+    stage_bc<OUTPUT>(p, seq0 + tb, cnt, sB, sC);
     __syncthreads();
-    for (int tt = 0; tt < cnt; ++tt) {
-      const size_t row = seq0 + tb + tt;
-      const float xv = p.s_x * static_cast<float>(p.x_q[row * p.Di + dd]);
-      const float dt = softplus_f(p.s_dt * static_cast<float>(p.dt_q[row * p.Di + dd]) + bias);
-      const float u = dt * xv;
-      sdt += dt;
-#pragma unroll
-      for (int n = 0; n < NS; ++n) h[n] = exp2_fast(dt * a2[n]) * h[n] + u * sB[tt][n];
+    for (int ts = 0; ts < cnt; ts += 2 * TS) {
+      if (ts + TS < cnt) fetch(rb, tb + ts + TS);
+      compute(ra, tb + ts, ts);
+      if (ts + 2 * TS < cnt) fetch(ra, tb + ts + 2 * TS);
+      if (ts + TS < cnt) compute(rb, tb + ts + TS, ts + TS);
     }
   }
-  if (live) {
+  if (!OUTPUT && live) {
     float *dst = p.hloc + (((size_t)b * p.nchunks + c) * p.Di + d) * NS;
 #pragma unroll
     for (int q = 0; q < 4; ++q)
@@ -121,6 +180,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_local_kernel(Dev p) {
 
 // ---------------------------------------------------------------- pass 2: carry across chunks
 // One thread per (b, d, n).  In place: hloc[c] is replaced by the start state of chunk c.
+// The chunk states are read eight at a time so the walk is not a chain of dependent loads.
 __global__ __launch_bounds__(256) void scan_carry_kernel(Dev p, float *__restrict__ ssm_state, int Bt) {
   const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
   const size_t per_b = (size_t)p.Di * NS;
@@ -132,77 +192,24 @@ __global__ __launch_bounds__(256) void scan_carry_kernel(Dev p, float *__restric
   float h = ssm_state ? ssm_state[idx] : 0.f;
   float *hl = p.hloc + (size_t)b * p.nchunks * per_b + dn;
   const float *ss = p.ssum + (size_t)b * p.nchunks * p.Di + d;
-  float loc = hl[0], s = ss[0];
-  for (int c = 0; c < p.nchunks; ++c) {
-    float nloc = 0.f, ns = 0.f;
-    if (c + 1 < p.nchunks) {
-      nloc = hl[(size_t)(c + 1) * per_b];
-      ns = ss[(size_t)(c + 1) * p.Di];
+  constexpr int G = 8;
+  for (int c0 = 0; c0 < p.nchunks; c0 += G) {
+    float loc[G], s[G];
+#pragma unroll
+    for (int i = 0; i < G; ++i) {
+      const int c = min(c0 + i, p.nchunks - 1);
+      loc[i] = hl[(size_t)c * per_b];
+      s[i] = ss[(size_t)c * p.Di];
     }
-    hl[(size_t)c * per_b] = h;
-    h = exp2_fast(a2 * s) * h + loc;
-    loc = nloc;
-    s = ns;
+#pragma unroll
+    for (int i = 0; i < G; ++i) {
+      if (c0 + i < p.nchunks) {
+        hl[(size_t)(c0 + i) * per_b] = h;
+        h = exp2_fast(a2 * s[i]) * h + loc[i];
+      }
+    }
   }
   if (ssm_state) ssm_state[idx] = h;
-}
-
-// ---------------------------------------------------------------- pass 3: outputs
-__global__ __launch_bounds__(SCAN_THREADS) void scan_output_kernel(Dev p) {
-  __shared__ __attribute__((aligned(16))) float sB[TB][NS];
-  __shared__ __attribute__((aligned(16))) float sC[TB][NS];
-  const int d = blockIdx.x * SCAN_THREADS + threadIdx.x;
-  const int c = blockIdx.y, b = blockIdx.z;
-  const bool live = d < p.Di;
-  const int dd = live ? d : p.Di - 1;
-  const int t0 = c * p.T, t1 = min(t0 + p.T, p.L);
-
-  float a2[NS], h[NS];
-  {
-    const uint4 av = *reinterpret_cast<const uint4 *>(p.A_q + (size_t)dd * NS);
-    const unsigned aw[4] = {av.x, av.y, av.z, av.w};
-    const float *src = p.hloc + (((size_t)b * p.nchunks + c) * p.Di + dd) * NS;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const float4 v = reinterpret_cast<const float4 *>(src)[q];
-      h[4 * q] = v.x;
-      h[4 * q + 1] = v.y;
-      h[4 * q + 2] = v.z;
-      h[4 * q + 3] = v.w;
-    }
-#pragma unroll
-    for (int n = 0; n < NS; ++n)
-      a2[n] = static_cast<float>(static_cast<int8_t>(aw[n >> 2] >> (8 * (n & 3)))) * (p.s_A * LOG2E);
-  }
-  const float bias = p.dt_bias[dd];
-  const float Dv = p.s_D * static_cast<float>(p.D_q[dd]);
-  const size_t seq0 = (size_t)b * p.L;
-
-  for (int tb = t0; tb < t1; tb += TB) {
-    const int cnt = min(TB, t1 - tb);
-    __syncthreads();
-    stage_bc<true>(p, seq0 + tb, cnt, sB, sC);
-    __syncthreads();
-    for (int tt = 0; tt < cnt; ++tt) {
-      const size_t row = seq0 + tb + tt;
-      const float xv = p.s_x * static_cast<float>(p.x_q[row * p.Di + dd]);
-      const float dt = softplus_f(p.s_dt * static_cast<float>(p.dt_q[row * p.Di + dd]) + bias);
-      const float zv = p.s_z * static_cast<float>(p.z_q[row * p.ldz + dd]);
-      const float u = dt * xv;
-      float y = 0.f;
-#pragma unroll
-      for (int n = 0; n < NS; ++n) {
-        h[n] = exp2_fast(dt * a2[n]) * h[n] + u * sB[tt][n];
-        y += sC[tt][n] * h[n];
-      }
-      y += Dv * xv;
-      const float g = silu_gate(y, zv);
-      if (live) {
-        p.g16[row * p.Di + d] = __float2half_rn(g);
-        if (p.y_f32) p.y_f32[row * p.Di + d] = g;
-      }
-    }
-  }
 }
 
 // ---------------------------------------------------------------- decode: one step
@@ -290,13 +297,13 @@ int launch_scan_prefill(const ScanArgs &a, void *ws, size_t ws_bytes, hipStream_
   p.ssum = reinterpret_cast<float *>(static_cast<char *>(ws) +
                                      align_up((size_t)a.Bt * p.nchunks * a.Di * NS * sizeof(float), 256));
   dim3 grid((a.Di + SCAN_THREADS - 1) / SCAN_THREADS, p.nchunks, a.Bt);
-  hipLaunchKernelGGL(scan_local_kernel, grid, dim3(SCAN_THREADS), 0, st, p);
+  hipLaunchKernelGGL(scan_chunk_kernel<false>, grid, dim3(SCAN_THREADS), 0, st, p);
   QUAMBA_LAUNCH_CHECK();
   const size_t n2 = (size_t)a.Bt * a.Di * NS;
   hipLaunchKernelGGL(scan_carry_kernel, dim3((unsigned)((n2 + 255) / 256)), dim3(256), 0, st, p, a.ssm_state,
                      a.Bt);
   QUAMBA_LAUNCH_CHECK();
-  hipLaunchKernelGGL(scan_output_kernel, grid, dim3(SCAN_THREADS), 0, st, p);
+  hipLaunchKernelGGL(scan_chunk_kernel<true>, grid, dim3(SCAN_THREADS), 0, st, p);
   QUAMBA_LAUNCH_CHECK();
   return QUAMBA_OK;
 }

@@ -31,6 +31,7 @@ GEMM_SHAPES = [
     # M, N, K, lda_pad, label
     (64, 64, 64, 0), (1, 4, 16, 0), (200, 192, 160, 32), (129, 260, 48, 0), (257, 80, 1536, 0),
     (64, 10240, 2560, 0), (512, 2560, 5120, 0), (300, 5120, 160, 32), (2048, 192, 5120, 0),
+    (64, 2560, 5120, 0), (1000, 288, 8192, 0), (333, 1280, 1024, 0), (2048, 80, 1536, 0),
 ]
 
 
@@ -57,12 +58,19 @@ def test_gemm_acc_and_requant_bit_exact(M, N, K, pad):
     dA, dW = dev(A), dev(Wt)
     Q.quamba_gemm_i8(dA, lda, dW, K, M, N, K, e0, e1, mult, out, None, ldo, acc)
     assert np.array_equal(host(acc), acc_ref)
+    # same call with a workspace: skinny shapes take the split-K path, the result must not change
+    out2 = torch.zeros((M, ldo), dtype=torch.int8, device="cuda:0")
+    acc2 = empty((M, N), torch.int32)
+    ws = workspace(Q.quamba_gemm_workspace_bytes(M, N, K))
+    Q.quamba_gemm_i8(dA, lda, dW, K, M, N, K, e0, e1, mult, out2, None, ldo, acc2, ws)
+    assert np.array_equal(host(acc2), acc_ref)
+    assert torch.equal(out, out2)
     got = host(out)
     assert np.array_equal(got[:, :N], want_i8)
     assert not got[:, N:].any()  # nothing written past N
     # fp16 epilogue
     outh = torch.zeros((M, ldo), dtype=torch.float16, device="cuda:0")
-    Q.quamba_gemm_i8(dA, lda, dW, K, M, N, K, N, N, mult, None, outh, ldo, None)
+    Q.quamba_gemm_i8(dA, lda, dW, K, M, N, K, N, N, mult, None, outh, ldo, None, ws)
     want_h = (acc_ref.astype(np.float32) * mult[0]).astype(np.float16)
     goth = host(outh)
     assert np.array_equal(goth[:, :N].view(np.uint16), want_h.view(np.uint16))
