@@ -99,6 +99,75 @@ __device__ __forceinline__ void store_tiles(const v16i (&acc)[TN][TM], int m_bas
   }
 }
 
+// Same result, but the wave first lays its (TM*32) x (TN*32) block of finished int8 / fp16
+// values out row-major in a private LDS region and then writes it with 16 bytes per lane, so a
+// wave-level store covers whole runs of a row instead of 8-byte pieces of 32 different rows.
+// Needs N, ldo and the output base aligned to 16 bytes; `scratch` is this wave's region of
+// TM*32 * TN*32 * sizeof(element) bytes, free of other use (callers barrier before).
+template <int TM, int TN>
+__device__ __forceinline__ void store_tiles_rows(const v16i (&acc)[TN][TM], int m_base, int n_base, int lane,
+                                                 int M, int N, const GemmEpilogue &epi, int8_t *scratch) {
+  const bool f16 = epi.out_f16 != nullptr;
+  const int esz = f16 ? 2 : 1;
+  const int rowb = TN * 32 * esz;  // bytes per block row
+#pragma unroll
+  for (int i = 0; i < TN; ++i) {
+#pragma unroll
+    for (int j = 0; j < TM; ++j) {
+      const int row = j * 32 + (lane & 31);
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int col = i * 32 + 8 * g + 4 * (lane >> 5);
+        const int gn = n_base + col;
+        const int a[4] = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+        const float m = gn < epi.e0 ? epi.m0 : (gn < epi.e1 ? epi.m1 : epi.m2);
+        if (f16) {
+          union {
+            __half h[4];
+            uint2 u;
+          } pk;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) pk.h[e] = __float2half_rn(static_cast<float>(a[e]) * m);
+          *reinterpret_cast<uint2 *>(scratch + row * rowb + col * 2) = pk.u;
+        } else {
+          *reinterpret_cast<unsigned *>(scratch + row * rowb + col) = requant_pack4(a, m);
+        }
+      }
+    }
+  }
+  // the region is private to this wave: its own LDS writes are ordered before its reads
+  const int cpr = rowb / 16;  // 16-byte chunks per block row
+  const int total = TM * 32 * cpr;
+  int8_t *out = f16 ? reinterpret_cast<int8_t *>(epi.out_f16) : epi.out_i8;
+  for (int q = lane; q < total; q += 64) {
+    const int row = q / cpr, cc = q % cpr;
+    const int gm = m_base + row;
+    const int gcol = n_base + cc * (16 / esz);
+    if (gm < M && gcol < N) {
+      const v4i v = *reinterpret_cast<const v4i *>(scratch + row * rowb + cc * 16);
+      *reinterpret_cast<v4i *>(out + ((size_t)gm * epi.ldo + gcol) * esz) = v;
+    }
+  }
+}
+
+// Picks the epilogue: row-major staged stores when alignment allows and no raw accumulators are
+// requested, direct per-lane stores otherwise.
+template <int TM, int TN>
+__device__ __forceinline__ void finish(const v16i (&acc)[TN][TM], int m_base, int n_base, int lane, int wave,
+                                       int M, int N, const GemmEpilogue &epi, int32_t *partial,
+                                       int8_t *lds_base) {
+  const bool f16 = epi.out_f16 != nullptr;
+  const int per = f16 ? 8 : 16;  // elements per 16-byte store
+  const uintptr_t base = reinterpret_cast<uintptr_t>(f16 ? (const void *)epi.out_f16 : (const void *)epi.out_i8);
+  const bool rows_ok = !partial && !epi.acc && base != 0 && (N % per) == 0 && (epi.ldo % per) == 0 && (base % 16) == 0;
+  if (rows_ok) {
+    __syncthreads();  // every wave is done with the operand tiles that lived here
+    store_tiles_rows<TM, TN>(acc, m_base, n_base, lane, M, N, epi, lds_base + wave * (TM * 32 * TN * 32 * 2));
+  } else {
+    store_tiles<TM, TN>(acc, m_base, n_base, lane, M, N, epi, partial);
+  }
+}
+
 // Workgroup ids are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of tiles
 // (same weight columns, consecutive token rows) so its L2 sees each weight slice once.
 __device__ __forceinline__ int xcd_tile_id(int wg, int nwg) {
@@ -214,8 +283,9 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t *__restrict__
     if (kt + 1 < nk) park(buf ^ 1);
     __syncthreads();
   }
-  store_tiles<TM, TN>(acc, m0 + wm * WM, n0 + wn * WN, lane, M, N, epi,
-                      ks.partial ? ks.partial + (size_t)blockIdx.y * M * N : nullptr);
+  static_assert(sizeof(lds) >= 4 * WM * WN * 2, "epilogue staging fits in the operand tiles");
+  finish<TM, TN>(acc, m0 + wm * WM, n0 + wn * WN, lane, wave, M, N, epi,
+                 ks.partial ? ks.partial + (size_t)blockIdx.y * M * N : nullptr, &lds[0][0]);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -329,8 +399,9 @@ __global__ __launch_bounds__(256, OCC) void gemm_i8_dma_kernel(const int8_t *__r
   }
 #undef QUAMBA_VMCNT
 
-  store_tiles<TM, TN>(acc, m0 + wm * WM, n0 + wn * WN, lane, M, N, epi,
-                      ks.partial ? ks.partial + (size_t)blockIdx.y * M * N : nullptr);
+  static_assert(S * STAGE >= 4 * WM * WN * 2, "epilogue staging fits in the ring");
+  finish<TM, TN>(acc, m0 + wm * WM, n0 + wn * WN, lane, wave, M, N, epi,
+                 ks.partial ? ks.partial + (size_t)blockIdx.y * M * N : nullptr, ring);
 }
 
 // Sum of the split-K partials + epilogue; one thread per group of four columns.
@@ -393,7 +464,7 @@ int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, i
                    const GemmEpilogue &epi, void *ws, size_t ws_bytes, hipStream_t st) {
   const bool k64 = (K % 64) == 0, k128 = (K % 128) == 0;
   // which kernel: 0 = reg 64x64, 1 = reg 128x128, 2 = dma 128x160 (128-byte slices),
-  // 3 = dma 64x64 (64-byte slices, ring of 4), 4 = dma 256x160 (64-byte slices, ring of 3)
+  // 3 = dma 64x64 (64-byte slices, ring of 4)
   int kind;
   if (M <= 64 || N <= 512)
     kind = k64 ? 3 : 0;
@@ -401,7 +472,7 @@ int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, i
     kind = 2;
   else
     kind = 1;
-  if (g_gemm_variant >= 0 && (g_gemm_variant < 2 || (g_gemm_variant == 3 && k64) || (g_gemm_variant != 3 && k128)))
+  if (g_gemm_variant >= 0 && g_gemm_variant <= 3 && (g_gemm_variant < 2 || (g_gemm_variant == 3 && k64) || (g_gemm_variant == 2 && k128)))
     kind = g_gemm_variant;
 
   // split K when the output has too few tiles to fill 256 CUs and K is deep
@@ -424,7 +495,6 @@ int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, i
     case 0: rc = run_reg<64, 64, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
     case 2: rc = run_dma<128, 160, 4, 1, 2, 128, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
     case 3: rc = run_dma<64, 64, 2, 2, 4, 64, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
-    case 4: rc = run_dma<256, 160, 4, 1, 3, 64, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
     default: rc = run_reg<128, 128, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
   }
   if (rc != QUAMBA_OK || splits == 1) return rc;

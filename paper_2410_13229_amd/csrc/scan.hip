@@ -180,7 +180,9 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_chunk_kernel(Dev p) {
 
 // ---------------------------------------------------------------- pass 2: carry across chunks
 // One thread per (b, d, n).  In place: hloc[c] is replaced by the start state of chunk c.
-// The chunk states are read eight at a time so the walk is not a chain of dependent loads.
+// All loads of a block of up to 64 chunks are issued before the walk starts, so the memory
+// latency is paid once per block instead of once per chunk.  The kernel moves the chunk states
+// once in and once out and is bound by that traffic.
 __global__ __launch_bounds__(256) void scan_carry_kernel(Dev p, float *__restrict__ ssm_state, int Bt) {
   const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
   const size_t per_b = (size_t)p.Di * NS;
@@ -192,7 +194,7 @@ __global__ __launch_bounds__(256) void scan_carry_kernel(Dev p, float *__restric
   float h = ssm_state ? ssm_state[idx] : 0.f;
   float *hl = p.hloc + (size_t)b * p.nchunks * per_b + dn;
   const float *ss = p.ssum + (size_t)b * p.nchunks * p.Di + d;
-  constexpr int G = 8;
+  constexpr int G = 64;
   for (int c0 = 0; c0 < p.nchunks; c0 += G) {
     float loc[G], s[G];
 #pragma unroll
@@ -203,11 +205,13 @@ __global__ __launch_bounds__(256) void scan_carry_kernel(Dev p, float *__restric
     }
 #pragma unroll
     for (int i = 0; i < G; ++i) {
-      if (c0 + i < p.nchunks) {
-        hl[(size_t)(c0 + i) * per_b] = h;
-        h = exp2_fast(a2 * s[i]) * h + loc[i];
-      }
+      const float start = h;
+      if (c0 + i < p.nchunks) h = exp2_fast(a2 * s[i]) * h + loc[i];
+      loc[i] = start;
     }
+#pragma unroll
+    for (int i = 0; i < G; ++i)
+      if (c0 + i < p.nchunks) hl[(size_t)(c0 + i) * per_b] = loc[i];
   }
   if (ssm_state) ssm_state[idx] = h;
 }
@@ -263,16 +267,29 @@ Dev make_dev(const ScanArgs &a) {
   return p;
 }
 
-// Chunk length: enough chunks to give the chip a few thousand wavefronts, but chunks no
-// shorter than 32 tokens so the per-chunk state traffic (128 B per channel) stays small
-// against the 7 B per (token, channel) the two sweeps read and write.
+// Chunk length.  A (chunk, 256-channel) tile is one workgroup, i.e. one wave on each SIMD of
+// a CU.  Take the fewest chunks (least per-chunk state traffic: 128 B per channel and chunk, read
+// and written twice) that give at least 4 workgroups per CU (the recurrence needs several waves
+// per SIMD to hide its own latencies) and fill the last round of 256 CUs to 90 %; chunks are
+// never shorter than 16 tokens.
 void choose_chunks(int Bt, int L, int Di, int *T, int *nchunks) {
-  const long waves_per_chunk = (long)Bt * ((Di + 63) / 64);
-  long want = (2560 + waves_per_chunk - 1) / waves_per_chunk;
-  long maxc = (L + 31) / 32;
-  if (want > maxc) want = maxc;
-  if (want < 1) want = 1;
-  int t = (int)((L + want - 1) / want);
+  const long per_chunk = (long)Bt * ((Di + SCAN_THREADS - 1) / SCAN_THREADS);
+  const int max_chunks = (L + 15) / 16;
+  int best_n = max_chunks > 0 ? max_chunks : 1;
+  for (int n = 1; n <= max_chunks; ++n) {
+    int t = (L + n - 1) / n;
+    t = (t + 7) / 8 * 8;
+    const int real_n = (L + t - 1) / t;
+    const long wgs = per_chunk * real_n;
+    const long rounds = (wgs + 255) / 256;
+    // equal chunks when L allows (a ragged last chunk leaves SIMDs idle), unless there are many
+    const bool full = wgs >= 1024 && (double)wgs / (double)(rounds * 256) >= 0.9 && (L % t == 0 || real_n >= 16);
+    if (full) {
+      best_n = real_n;
+      break;
+    }
+  }
+  int t = (L + best_n - 1) / best_n;
   t = (t + 7) / 8 * 8;
   *T = t;
   *nchunks = (L + t - 1) / t;
