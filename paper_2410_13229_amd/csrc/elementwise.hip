@@ -10,7 +10,7 @@ namespace {
 
 __device__ __forceinline__ int q8(float v) {
   v = __builtin_rintf(v);
-  v = fminf(fmaxf(v, -128.f), 127.f);
+  v = __builtin_amdgcn_fmed3f(v, -128.f, 127.f);
   return static_cast<int>(v);
 }
 
@@ -43,10 +43,15 @@ __global__ __launch_bounds__(256) void quantize_f16_kernel(const __half *__restr
 }
 
 // ------------------------------------------------------------------ conv, prefill
-// One thread owns 4 adjacent channels (one 32-bit word per token) and walks TT consecutive
-// tokens of one sequence, keeping the three previous words in registers, so each input word
-// is read once per tile (plus a 3-token halo).
+// One thread owns 4 adjacent channels (one 32-bit word per token) and TT consecutive tokens of
+// one sequence.  All TT+3 words are requested up front; a pair of byte permutes per channel
+// turns "4 channels of one tap" into "4 taps of one channel", which v_dot4_i32_i8 multiplies
+// with that channel's packed weights.
 constexpr int CONV_TT = 16;
+
+__device__ __forceinline__ float silu_fast(float v) {
+  return v * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-v * 1.44269504088896340736f));
+}
 
 __global__ __launch_bounds__(256) void conv_prefill_kernel(
     const int8_t *__restrict__ xpre, int ldx, const int8_t *__restrict__ wq,
@@ -59,51 +64,57 @@ __global__ __launch_bounds__(256) void conv_prefill_kernel(
   const int t0 = blockIdx.y * CONV_TT;
   const int t1 = min(t0 + CONV_TT, L);
 
-  // weights of the 4 channels: 16 bytes, [d][j]
-  const uint4 wv = *reinterpret_cast<const uint4 *>(wq + (size_t)d0 * 4);
-  const unsigned wword[4] = {wv.x, wv.y, wv.z, wv.w};
-  int w[4][4];
-#pragma unroll
-  for (int c = 0; c < 4; ++c)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) w[c][j] = static_cast<int8_t>(wword[c] >> (8 * j));
+  const uint4 wv = *reinterpret_cast<const uint4 *>(wq + (size_t)d0 * 4);  // [channel][tap]
+  const int wword[4] = {(int)wv.x, (int)wv.y, (int)wv.z, (int)wv.w};
   const float4 bv = *reinterpret_cast<const float4 *>(bias + d0);
   const float bb[4] = {bv.x, bv.y, bv.z, bv.w};
 
   const int8_t *src = xpre + (size_t)b * L * ldx + d0;
   int8_t *dst = xq + (size_t)b * L * Di + d0;
-  auto ld = [&](int t) -> unsigned {
-    return t >= 0 ? *reinterpret_cast<const unsigned *>(src + (size_t)t * ldx) : 0u;
-  };
-  unsigned h0 = ld(t0 - 3), h1 = ld(t0 - 2), h2 = ld(t0 - 1);
-  for (int t = t0; t < t1; ++t) {
-    const unsigned h3 = ld(t);
-    unsigned p = 0;
+  unsigned h[CONV_TT + 3];
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      const int a = w[c][0] * static_cast<int8_t>(h0 >> (8 * c)) +
-                    w[c][1] * static_cast<int8_t>(h1 >> (8 * c)) +
-                    w[c][2] * static_cast<int8_t>(h2 >> (8 * c)) +
-                    w[c][3] * static_cast<int8_t>(h3 >> (8 * c));
-      const float v = __fadd_rn(__fmul_rn(static_cast<float>(a), m_conv), bb[c]);
-      p |= (static_cast<unsigned>(q8(silu_f(v) * inv_s_x)) & 0xffu) << (8 * c);
+  for (int i = 0; i < CONV_TT + 3; ++i) {
+    const int t = t0 - 3 + i;
+    h[i] = (t >= 0 && t < t1) ? *reinterpret_cast<const unsigned *>(src + (size_t)t * ldx) : 0u;
+  }
+#pragma unroll
+  for (int i = 0; i < CONV_TT; ++i) {
+    if (t0 + i < t1) {
+      // bytes of h[i..i+3]: taps oldest..newest, 4 channels each -> per channel its 4 taps
+      const unsigned ta = __builtin_amdgcn_perm(h[i + 1], h[i], 0x05010400u);
+      const unsigned tb = __builtin_amdgcn_perm(h[i + 1], h[i], 0x07030602u);
+      const unsigned ua = __builtin_amdgcn_perm(h[i + 3], h[i + 2], 0x05010400u);
+      const unsigned ub = __builtin_amdgcn_perm(h[i + 3], h[i + 2], 0x07030602u);
+      const unsigned taps[4] = {__builtin_amdgcn_perm(ua, ta, 0x05040100u), __builtin_amdgcn_perm(ua, ta, 0x07060302u),
+                                __builtin_amdgcn_perm(ub, tb, 0x05040100u), __builtin_amdgcn_perm(ub, tb, 0x07060302u)};
+      unsigned p = 0;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const int a = __builtin_amdgcn_sdot4((int)taps[c], wword[c], 0, false);
+        const float v = __fadd_rn(__fmul_rn(static_cast<float>(a), m_conv), bb[c]);
+        p |= (static_cast<unsigned>(q8(silu_fast(v) * inv_s_x)) & 0xffu) << (8 * c);
+      }
+      *reinterpret_cast<unsigned *>(dst + (size_t)(t0 + i) * Di) = p;
     }
-    *reinterpret_cast<unsigned *>(dst + (size_t)t * Di) = p;
-    h0 = h1;
-    h1 = h2;
-    h2 = h3;
   }
   // the tile holding the sequence end also emits the carried window [L-3, L-2, L-1]
   if (conv_state != nullptr && t1 == L) {
-    const unsigned hh[3] = {h0, h1, h2};
 #pragma unroll
-    for (int c = 0; c < 4; ++c)
+    for (int j = 0; j < 3; ++j) {
+      const int tj = L - 3 + j;
+      unsigned w = 0u;
+      if (tj >= 0) {
+        // tj >= t0 - 3 always holds for the last tile; pick the word out of the preloaded window
 #pragma unroll
-      for (int j = 0; j < 3; ++j) {
-        const int tj = L - 3 + j;
-        const float v = tj >= 0 ? s_xpre * static_cast<float>(static_cast<int8_t>(hh[j] >> (8 * c))) : 0.f;
+        for (int i = 0; i < CONV_TT + 3; ++i)
+          if (t0 - 3 + i == tj) w = h[i];
+      }
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const float v = tj >= 0 ? s_xpre * static_cast<float>(static_cast<int8_t>(w >> (8 * c))) : 0.f;
         conv_state[((size_t)b * Di + d0 + c) * 3 + j] = __float2half_rn(v);
       }
+    }
   }
 }
 
