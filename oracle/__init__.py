@@ -28,3 +28,4 @@ from .quantizer import (rne, quantize, requant_acc, absmax_scale, percentile_max
 from .mixer import (fp_forward, calibrate, q_prefill, q_decode, selective_scan,  # noqa: F401
                     causal_conv_fp, add_rmsnorm_quant, silu, softplus, q_scan, q_hadamard_quant,
                     q_out_proj, q_conv_prefill, q_conv_step)
+from .stack import calibrate_stack, q_stack_prefill, q_stack_decode  # noqa: F401

@@ -299,11 +299,12 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t *__restrict__
 // stored.
 // ------------------------------------------------------------------------------------------
 template <int BM, int BN, int WGM, int WGN, int S, int BKB, int OCC>
-__global__ __launch_bounds__(256, OCC) void gemm_i8_dma_kernel(const int8_t *__restrict__ A, int lda,
+__global__ __launch_bounds__(64 * WGM * WGN, OCC) void gemm_i8_dma_kernel(const int8_t *__restrict__ A, int lda,
                                                                const int8_t *__restrict__ Wt, int ldw,
                                                                int M, int N, int K, GemmEpilogue epi,
                                                                int tiles_m, int tiles_n, KSplit ks) {
-  static_assert(WGM * WGN == 4, "four waves per workgroup");
+  constexpr int NW = WGM * WGN;  // waves per workgroup
+  static_assert(NW == 2 || NW == 4, "two or four waves per workgroup");
   static_assert(BKB == 64 || BKB == 128, "slice width");
   constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int TM = WM / 32, TN = WN / 32;
@@ -312,7 +313,7 @@ __global__ __launch_bounds__(256, OCC) void gemm_i8_dma_kernel(const int8_t *__r
   static_assert(TM >= 1 && TN >= 1 && WM % 32 == 0 && WN % 32 == 0 && BM % RPI == 0 && BN % RPI == 0, "tile");
   constexpr int ROWS = BM + BN;
   constexpr int NJ = ROWS / RPI;    // wave-level loads per slice
-  constexpr int NI = (NJ + 3) / 4;  // per wave (a short wave repeats the last group)
+  constexpr int NI = (NJ + NW - 1) / NW;  // per wave (a short wave repeats the last group)
   constexpr int STAGE = ROWS * BKB;
   static_assert((S - 2) * NI <= 63 && S >= 2, "vmcnt is 6 bits");
 
@@ -333,7 +334,7 @@ __global__ __launch_bounds__(256, OCC) void gemm_i8_dma_kernel(const int8_t *__r
   int dst[NI];
 #pragma unroll
   for (int i = 0; i < NI; ++i) {
-    const int j = min(wave + 4 * i, NJ - 1);
+    const int j = min(wave + NW * i, NJ - 1);
     const int row = j * RPI + lane / CPR;
     const int lrow = row < BM ? row : row - BM;  // the swizzle phase follows the row inside its operand
     const int chunk = BKB == 64 ? ((lane % CPR) ^ ((lrow >> 2) & 3)) : ((lane % CPR) ^ ((lrow >> 1) & 7));
@@ -399,7 +400,7 @@ __global__ __launch_bounds__(256, OCC) void gemm_i8_dma_kernel(const int8_t *__r
   }
 #undef QUAMBA_VMCNT
 
-  static_assert(S * STAGE >= 4 * WM * WN * 2, "epilogue staging fits in the ring");
+  static_assert(S * STAGE >= NW * WM * WN * 2, "epilogue staging fits in the ring");
   finish<TM, TN>(acc, m0 + wm * WM, n0 + wn * WN, lane, wave, M, N, epi,
                  ks.partial ? ks.partial + (size_t)blockIdx.y * M * N : nullptr, ring);
 }
@@ -436,7 +437,7 @@ int run_dma(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, int N, i
   }
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   hipLaunchKernelGGL((gemm_i8_dma_kernel<BM, BN, WGM, WGN, S, BKB, OCC>), dim3(tiles_m * tiles_n, splits),
-                     dim3(256), lds, st, A, lda, Wt, ldw, M, N, K, epi, tiles_m, tiles_n, ks);
+                     dim3(64 * WGM * WGN), lds, st, A, lda, Wt, ldw, M, N, K, epi, tiles_m, tiles_n, ks);
   QUAMBA_LAUNCH_CHECK();
   return QUAMBA_OK;
 }
@@ -463,27 +464,31 @@ size_t gemm_workspace_bytes(int M, int N) {
 int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, int N, int K,
                    const GemmEpilogue &epi, void *ws, size_t ws_bytes, hipStream_t st) {
   const bool k64 = (K % 64) == 0, k128 = (K % 128) == 0;
-  // which kernel: 0 = reg 64x64, 1 = reg 128x128, 2 = dma 128x160 (128-byte slices),
-  // 3 = dma 64x64 (64-byte slices, ring of 4)
+  // which kernel: 0 = reg 64x64, 1 = reg 128x128, 2 = dma 128x160 (128-byte slices, ring of 2),
+  // 3 = dma 64x64 (64-byte slices, ring of 4), 5 = dma 64x64 (128-byte slices, ring of 3; the
+  // best weight-streaming rate measured for decode-sized M)
   int kind;
-  if (M <= 64 || N <= 512)
+  if (M <= 64)
+    kind = k128 ? 5 : (k64 ? 3 : 0);
+  else if (N <= 512)
     kind = k64 ? 3 : 0;
   else if (k128 && M >= 256 && N >= 640)
     kind = 2;
   else
     kind = 1;
-  if (g_gemm_variant >= 0 && g_gemm_variant <= 3 && (g_gemm_variant < 2 || (g_gemm_variant == 3 && k64) || (g_gemm_variant == 2 && k128)))
+  if (g_gemm_variant >= 0 && g_gemm_variant <= 5 && g_gemm_variant != 4 &&
+      (g_gemm_variant < 2 || (g_gemm_variant == 3 && k64) || (g_gemm_variant != 3 && k128)))
     kind = g_gemm_variant;
 
   // split K when the output has too few tiles to fill 256 CUs and K is deep
   int splits = 1;
-  const int slice = (kind == 2) ? 128 : 64;
+  const int slice = (kind == 2 || kind == 5) ? 128 : 64;
   const int nslices = (K + slice - 1) / slice;
-  if ((kind == 0 || kind == 3) && ws != nullptr) {
+  if ((kind == 0 || kind == 3 || kind == 5) && ws != nullptr) {
     const int tiles = ((M + 63) / 64) * ((N + 63) / 64);
     int want = 512 / (tiles > 0 ? tiles : 1);
     if (want > 8) want = 8;
-    while (want > 1 && (nslices / want < 8 || (size_t)want * M * N * sizeof(int32_t) > ws_bytes)) --want;
+    while (want > 1 && (nslices / want < 4 || (size_t)want * M * N * sizeof(int32_t) > ws_bytes)) --want;
     if (want > 1) splits = want;
   }
   KSplit ks{(nslices + splits - 1) / splits, nullptr};
@@ -495,6 +500,7 @@ int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, i
     case 0: rc = run_reg<64, 64, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
     case 2: rc = run_dma<128, 160, 4, 1, 2, 128, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
     case 3: rc = run_dma<64, 64, 2, 2, 4, 64, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
+    case 5: rc = run_dma<64, 64, 2, 2, 3, 128, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
     default: rc = run_reg<128, 128, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
   }
   if (rc != QUAMBA_OK || splits == 1) return rc;
