@@ -152,17 +152,21 @@ __device__ __forceinline__ void store_tiles_rows(const v16i (&acc)[TN][TM], int 
 
 // Picks the epilogue: row-major staged stores when alignment allows and no raw accumulators are
 // requested, direct per-lane stores otherwise.
-template <int TM, int TN>
-__device__ __forceinline__ void finish(const v16i (&acc)[TN][TM], int m_base, int n_base, int lane, int wave,
+// `scratch` is this wave's private LDS region of `scratch_bytes`; with BARRIER the workgroup
+// first agrees that the operand tiles living there are dead (every wave must then call this).
+template <int TM, int TN, bool BARRIER>
+__device__ __forceinline__ void finish(const v16i (&acc)[TN][TM], int m_base, int n_base, int lane,
                                        int M, int N, const GemmEpilogue &epi, int32_t *partial,
-                                       int8_t *lds_base) {
+                                       int8_t *scratch, int scratch_bytes) {
   const bool f16 = epi.out_f16 != nullptr;
   const int per = f16 ? 8 : 16;  // elements per 16-byte store
+  const int region = TM * 32 * TN * 32 * (f16 ? 2 : 1);  // bytes one wave stages
   const uintptr_t base = reinterpret_cast<uintptr_t>(f16 ? (const void *)epi.out_f16 : (const void *)epi.out_i8);
-  const bool rows_ok = !partial && !epi.acc && base != 0 && (N % per) == 0 && (epi.ldo % per) == 0 && (base % 16) == 0;
+  const bool rows_ok = !partial && !epi.acc && base != 0 && (N % per) == 0 && (epi.ldo % per) == 0 &&
+                       (base % 16) == 0 && region <= scratch_bytes;
   if (rows_ok) {
-    __syncthreads();  // every wave is done with the operand tiles that lived here
-    store_tiles_rows<TM, TN>(acc, m_base, n_base, lane, M, N, epi, lds_base + wave * (TM * 32 * TN * 32 * 2));
+    if (BARRIER) __syncthreads();
+    store_tiles_rows<TM, TN>(acc, m_base, n_base, lane, M, N, epi, scratch);
   } else {
     store_tiles<TM, TN>(acc, m_base, n_base, lane, M, N, epi, partial);
   }
@@ -283,9 +287,10 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t *__restrict__
     if (kt + 1 < nk) park(buf ^ 1);
     __syncthreads();
   }
-  static_assert(sizeof(lds) >= 4 * WM * WN * 2, "epilogue staging fits in the operand tiles");
-  finish<TM, TN>(acc, m0 + wm * WM, n0 + wn * WN, lane, wave, M, N, epi,
-                 ks.partial ? ks.partial + (size_t)blockIdx.y * M * N : nullptr, &lds[0][0]);
+  constexpr int REGION = (int)sizeof(lds) / 4;
+  finish<TM, TN, true>(acc, m0 + wm * WM, n0 + wn * WN, lane, M, N, epi,
+                       ks.partial ? ks.partial + (size_t)blockIdx.y * M * N : nullptr, &lds[0][0] + wave * REGION,
+                       REGION);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -298,14 +303,17 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t *__restrict__
 // Rows past M or N are clamped to the last valid row: they are loaded and multiplied but never
 // stored.
 // ------------------------------------------------------------------------------------------
-template <int BM, int BN, int WGM, int WGN, int S, int BKB, int OCC>
-__global__ __launch_bounds__(64 * WGM * WGN, OCC) void gemm_i8_dma_kernel(const int8_t *__restrict__ A, int lda,
+template <int BM, int BN, int WGM, int WGN, int S, int BKB, int OCC, int KG = 1>
+__global__ __launch_bounds__(64 * WGM * WGN * KG, OCC) void gemm_i8_dma_kernel(const int8_t *__restrict__ A, int lda,
                                                                const int8_t *__restrict__ Wt, int ldw,
                                                                int M, int N, int K, GemmEpilogue epi,
                                                                int tiles_m, int tiles_n, KSplit ks) {
-  constexpr int NW = WGM * WGN;  // waves per workgroup
-  static_assert(NW == 2 || NW == 4, "two or four waves per workgroup");
+  // KG wave groups share one output tile: group g multiplies the 32-byte sub-slices s with
+  // s % KG == g, and the groups' sums are added through LDS before the epilogue.
+  constexpr int NW = WGM * WGN * KG;  // waves per workgroup
+  static_assert(NW == 2 || NW == 4 || NW == 8, "two, four or eight waves per workgroup");
   static_assert(BKB == 64 || BKB == 128, "slice width");
+  static_assert(KG == 1 || KG == 2, "one or two K groups");
   constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int TM = WM / 32, TN = WN / 32;
   constexpr int RPI = 1024 / BKB;  // tile rows written by one wave-level load
@@ -328,7 +336,9 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC) void gemm_i8_dma_kernel(const 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave % WGM, wn = wave / WGM;
+  const int kg = wave / (WGM * WGN);
+  const int wtile = wave % (WGM * WGN);
+  const int wm = wtile % WGM, wn = wtile / WGM;
 
   const int8_t *src[NI];
   int dst[NI];
@@ -364,8 +374,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC) void gemm_i8_dma_kernel(const 
     const int8_t *la = ring + stage * STAGE;
     const int8_t *lw = la + BM * BKB;
 #pragma unroll
-    for (int s = 0; s < BKB / 32; ++s) {
-      const int chunk = s * 2 + (lane >> 5);
+    for (int s0 = 0; s0 < BKB / 32; s0 += KG) {
+      const int chunk = (s0 + kg) * 2 + (lane >> 5);
       v4i fa[TM], fw[TN];
 #pragma unroll
       for (int j = 0; j < TM; ++j)
@@ -400,9 +410,43 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC) void gemm_i8_dma_kernel(const 
   }
 #undef QUAMBA_VMCNT
 
-  static_assert(S * STAGE >= NW * WM * WN * 2, "epilogue staging fits in the ring");
-  finish<TM, TN>(acc, m0 + wm * WM, n0 + wn * WN, lane, wave, M, N, epi,
-                 ks.partial ? ks.partial + (size_t)blockIdx.y * M * N : nullptr, ring);
+  if constexpr (KG == 2) {
+    // group 1 parks its sums lane-major (16 bytes per lane and register quad: conflict-free),
+    // group 0 adds them; each wave pair owns one PART-byte region, reused below for staging
+    constexpr int PART = TM * TN * 16 * 64 * 4;
+    static_assert(S * STAGE >= WGM * WGN * PART, "K-group sums fit in the ring");
+    __syncthreads();  // operand tiles are dead
+    v4i *part = reinterpret_cast<v4i *>(ring + wtile * PART);
+    if (kg == 1) {
+#pragma unroll
+      for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+#pragma unroll
+          for (int g = 0; g < 4; ++g)
+            part[((i * TM + j) * 4 + g) * 64 + lane] =
+                v4i{acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+    }
+    __syncthreads();
+    if (kg == 1) return;
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+      for (int j = 0; j < TM; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const v4i v = part[((i * TM + j) * 4 + g) * 64 + lane];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[i][j][4 * g + e] += v[e];
+        }
+    // this wave alone read its region, so it may restage into it without another barrier
+    finish<TM, TN, false>(acc, m0 + wm * WM, n0 + wn * WN, lane, M, N, epi,
+                          ks.partial ? ks.partial + (size_t)blockIdx.y * M * N : nullptr, ring + wtile * PART, PART);
+  } else {
+    constexpr int REGION = S * STAGE / NW / 16 * 16;
+    finish<TM, TN, true>(acc, m0 + wm * WM, n0 + wn * WN, lane, M, N, epi,
+                         ks.partial ? ks.partial + (size_t)blockIdx.y * M * N : nullptr, ring + wave * REGION, REGION);
+  }
 }
 
 // Sum of the split-K partials + epilogue; one thread per group of four columns.
@@ -413,31 +457,38 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const int32_t *__res
   if (g >= groups) return;
   const int gm = static_cast<int>(g / (N / 4));
   const int gn = static_cast<int>(g % (N / 4)) * 4;
+  // at most 8 splits: request every partial before adding any, so the loads overlap
+  v4i v[8];
+#pragma unroll
+  for (int s = 0; s < 8; ++s) {
+    v[s] = v4i{0, 0, 0, 0};
+    if (s < splits) v[s] = *reinterpret_cast<const v4i *>(partial + ((size_t)s * M + gm) * N + gn);
+  }
   int a[4] = {0, 0, 0, 0};
-  for (int s = 0; s < splits; ++s) {
-    const v4i v = *reinterpret_cast<const v4i *>(partial + ((size_t)s * M + gm) * N + gn);
-    a[0] += v[0];
-    a[1] += v[1];
-    a[2] += v[2];
-    a[3] += v[3];
+#pragma unroll
+  for (int s = 0; s < 8; ++s) {
+    a[0] += v[s][0];
+    a[1] += v[s][1];
+    a[2] += v[s][2];
+    a[3] += v[s][3];
   }
   emit4(epi, gm, gn, N, a);
 }
 
-template <int BM, int BN, int WGM, int WGN, int S, int BKB, int OCC>
+template <int BM, int BN, int WGM, int WGN, int S, int BKB, int OCC, int KG = 1>
 int run_dma(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, int N, int K,
             const GemmEpilogue &epi, int splits, const KSplit &ks, hipStream_t st) {
   constexpr size_t lds = (size_t)S * (BM + BN) * BKB;
   static bool attr_set = false;
   if (!attr_set) {
     QUAMBA_HIP(hipFuncSetAttribute(
-        reinterpret_cast<const void *>(&gemm_i8_dma_kernel<BM, BN, WGM, WGN, S, BKB, OCC>),
+        reinterpret_cast<const void *>(&gemm_i8_dma_kernel<BM, BN, WGM, WGN, S, BKB, OCC, KG>),
         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     attr_set = true;
   }
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-  hipLaunchKernelGGL((gemm_i8_dma_kernel<BM, BN, WGM, WGN, S, BKB, OCC>), dim3(tiles_m * tiles_n, splits),
-                     dim3(64 * WGM * WGN), lds, st, A, lda, Wt, ldw, M, N, K, epi, tiles_m, tiles_n, ks);
+  hipLaunchKernelGGL((gemm_i8_dma_kernel<BM, BN, WGM, WGN, S, BKB, OCC, KG>), dim3(tiles_m * tiles_n, splits),
+                     dim3(64 * WGM * WGN * KG), lds, st, A, lda, Wt, ldw, M, N, K, epi, tiles_m, tiles_n, ks);
   QUAMBA_LAUNCH_CHECK();
   return QUAMBA_OK;
 }
@@ -464,25 +515,33 @@ size_t gemm_workspace_bytes(int M, int N) {
 int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, int N, int K,
                    const GemmEpilogue &epi, void *ws, size_t ws_bytes, hipStream_t st) {
   const bool k64 = (K % 64) == 0, k128 = (K % 128) == 0;
-  // which kernel: 0 = reg 64x64, 1 = reg 128x128, 2 = dma 128x160 (128-byte slices, ring of 2),
-  // 3 = dma 64x64 (64-byte slices, ring of 4), 5 = dma 64x64 (128-byte slices, ring of 3; the
-  // best weight-streaming rate measured for decode-sized M)
+  // which kernel:
+  //   0 = reg 64x64            1 = reg 128x128
+  //   2 = dma 128x160, 4 waves, 128-byte slices, ring of 2, two workgroups per CU
+  //   3 = dma 64x64, 64-byte slices, ring of 4
+  //   4 = dma 256x320, 8 waves of 64x160, 128-byte slices, ring of 2 (the least operand traffic
+  //       per MFMA; best when it still yields a tile for most CUs)
+  //   5 = dma 64x64, 128-byte slices, ring of 3 (best weight-streaming rate for decode-sized M)
+  //   6 = dma 128x160, two K groups of 4 waves (fills the SIMDs when there is only about one
+  //       128x160 tile per CU)
   int kind;
+  const long tiles_256 = (long)((M + 255) / 256) * ((N + 319) / 320);
+  const long tiles_128 = (long)((M + 127) / 128) * ((N + 159) / 160);
   if (M <= 64)
     kind = k128 ? 5 : (k64 ? 3 : 0);
   else if (N <= 512)
     kind = k64 ? 3 : 0;
   else if (k128 && M >= 256 && N >= 640)
-    kind = 2;
+    kind = tiles_256 >= 192 ? 4 : (tiles_128 <= 384 ? 6 : 2);
   else
     kind = 1;
-  if (g_gemm_variant >= 0 && g_gemm_variant <= 5 && g_gemm_variant != 4 &&
+  if (g_gemm_variant >= 0 && g_gemm_variant <= 6 &&
       (g_gemm_variant < 2 || (g_gemm_variant == 3 && k64) || (g_gemm_variant != 3 && k128)))
     kind = g_gemm_variant;
 
   // split K when the output has too few tiles to fill 256 CUs and K is deep
   int splits = 1;
-  const int slice = (kind == 2 || kind == 5) ? 128 : 64;
+  const int slice = (kind == 2 || kind >= 4) ? 128 : 64;
   const int nslices = (K + slice - 1) / slice;
   if ((kind == 0 || kind == 3 || kind == 5) && ws != nullptr) {
     const int tiles = ((M + 63) / 64) * ((N + 63) / 64);
@@ -501,6 +560,8 @@ int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, i
     case 2: rc = run_dma<128, 160, 4, 1, 2, 128, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
     case 3: rc = run_dma<64, 64, 2, 2, 4, 64, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
     case 5: rc = run_dma<64, 64, 2, 2, 3, 128, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
+    case 4: rc = run_dma<256, 320, 4, 2, 2, 128, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
+    case 6: rc = run_dma<128, 160, 4, 1, 3, 128, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
     default: rc = run_reg<128, 128, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
   }
   if (rc != QUAMBA_OK || splits == 1) return rc;

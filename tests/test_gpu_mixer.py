@@ -286,3 +286,46 @@ def test_calibrate_matches_oracle(name):
             assert d.max() <= 1 and (d != 0).mean() <= 1e-3, k
         else:
             assert np.array_equal(got, v), k
+
+
+def test_decode_steps_replayed_from_a_hip_graph():
+    """The decode call enqueues kernel launches only, so a caller may capture it.  Several replays,
+    with eager work and synchronisations in between, must each reproduce the eager result bit for bit."""
+    cfg = W.tiny_config(name="tg", d_model=64, d_inner=128, dt_rank=16, batch=3, seqlen=1, config_id=89)
+    w, qw, sc = oracle_setup(cfg, randomize_bias=True, gain=4.0)
+    qd = qweights_to_dev(qw)
+    Bt, nsteps = 3, 4
+    us = dev(np.stack([W.make_hidden(cfg, batch=Bt, seqlen=1, stream=300 + s)[:, 0] for s in range(nsteps)]))
+    ssm0_np, cs0_np = W.make_decode_state(cfg, batch=Bt)
+    ws = workspace(Q.quamba_workspace_bytes(cfg, Bt, 1))
+    outs = empty((nsteps, Bt, cfg.d_model), torch.float16)
+    ssm, cs = dev(ssm0_np), dev(cs0_np)
+    qs, scs, dims = Q.make_qweights(qd), Q.scales_from_dict(sc), Q.make_dims(cfg)
+
+    def steps():
+        for s in range(nsteps):
+            Q.quamba_mixer_decode(dims, qs, scs, us[s], Bt, outs[s], ssm, cs, None, ws, torch.cuda.current_stream())
+
+    steps()  # eager reference (also the warm-up that sets kernel attributes outside the capture)
+    ref_out, ref_ssm, ref_cs = host(outs).copy(), host(ssm).copy(), host(cs).copy()
+
+    cap = torch.cuda.Stream()
+    cap.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    ssm.copy_(dev(ssm0_np)); cs.copy_(dev(cs0_np))
+    torch.cuda.synchronize()
+    with torch.cuda.graph(g, stream=cap):
+        steps()
+    for rep in range(3):
+        ssm.copy_(dev(ssm0_np)); cs.copy_(dev(cs0_np)); outs.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(host(outs).view(np.uint16), ref_out.view(np.uint16)), rep
+        assert np.array_equal(host(ssm), ref_ssm), rep
+        assert np.array_equal(host(cs).view(np.uint16), ref_cs.view(np.uint16)), rep
+        # eager work between the replays
+        ssm.copy_(dev(ssm0_np)); cs.copy_(dev(cs0_np))
+        steps()
+        torch.cuda.synchronize()
+        assert np.array_equal(host(outs).view(np.uint16), ref_out.view(np.uint16))
