@@ -228,6 +228,19 @@ int quamba_scan_prefill(const int8_t *x_q, const int8_t *dt_q, const int8_t *z_q
                         const int8_t *D_q, const float *dt_bias, const quamba_scales *sc /* host */,
                         int Bt, int L, int Di, quamba_half *g16, float *y_f32, float *ssm_state,
                         void *ws, size_t ws_bytes, void *stream);
+/* The same scan with dt_proj fused into its first pass (Section 4.3 fuses operators to save
+ * launches and traffic): dt_q = q(W_dt_q dtlow_q, m_dt) with dtlow_q [Bt*L, lddl] (the dt_low
+ * columns of the x_proj output, row stride lddl), W_dt_q [Di, R], m_dt = s_dtlow s_Wdt / s_dt.
+ * dt_q [Bt*L, Di] is an OUTPUT here (written before the scan reads it).  Needs R and lddl
+ * multiples of 16 (R >= 16), Di a multiple of 4, dtlow_q and W_dt_q 16-byte aligned, else
+ * QUAMBA_EUNSUPPORTED; everything else as quamba_scan_prefill. */
+int quamba_scan_prefill_dtproj(const int8_t *x_q, const int8_t *dtlow_q, int lddl,
+                               const int8_t *W_dt_q, int R, float m_dt, int8_t *dt_q,
+                               const int8_t *z_q, int ldz, const int8_t *B_q, const int8_t *C_q,
+                               int ldbc, const int8_t *A_q, const int8_t *D_q, const float *dt_bias,
+                               const quamba_scales *sc /* host */, int Bt, int L, int Di,
+                               quamba_half *g16, float *y_f32, float *ssm_state,
+                               void *ws, size_t ws_bytes, void *stream);
 int quamba_scan_step(const int8_t *x_q, const int8_t *dt_q, const int8_t *z_q, int ldz,
                      const int8_t *B_q, const int8_t *C_q, int ldbc, const int8_t *A_q,
                      const int8_t *D_q, const float *dt_bias, const quamba_scales *sc /* host */,

@@ -16,7 +16,7 @@ __all__ = [
     "quamba_calibrate", "quamba_mixer_prefill", "quamba_mixer_prefill_q", "quamba_mixer_decode",
     "quamba_mixer_decode_q", "quamba_add_rmsnorm_quant", "quamba_quantize_f16", "quamba_gemm_i8",
     "quamba_gemm_workspace_bytes", "quamba_conv_silu_quant", "quamba_conv_step", "quamba_scan_workspace_bytes",
-    "quamba_scan_prefill", "quamba_scan_step", "quamba_hadamard_quant",
+    "quamba_scan_prefill", "quamba_scan_prefill_dtproj", "quamba_scan_step", "quamba_hadamard_quant",
 ]
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -155,12 +155,14 @@ def lib():
     L.quamba_scan_workspace_bytes.restype = sz
     L.quamba_scan_workspace_bytes.argtypes = [i, i, i]
     L.quamba_scan_prefill.argtypes = [vp, vp, vp, i, vp, vp, i, vp, vp, vp, P(Scales), i, i, i, vp, vp, vp, vp, sz, vp]
+    L.quamba_scan_prefill_dtproj.argtypes = [vp, vp, i, vp, i, f, vp, vp, i, vp, vp, i, vp, vp, vp, P(Scales), i, i,
+                                             i, vp, vp, vp, vp, sz, vp]
     L.quamba_scan_step.argtypes = [vp, vp, vp, i, vp, vp, i, vp, vp, vp, P(Scales), i, i, vp, vp, vp, vp]
     L.quamba_hadamard_quant.argtypes = [vp, i, i, f, vp, vp, vp]
     for name in ("quamba_calibrate", "quamba_mixer_prefill", "quamba_mixer_prefill_q", "quamba_mixer_decode",
                  "quamba_mixer_decode_q", "quamba_add_rmsnorm_quant", "quamba_quantize_f16", "quamba_gemm_i8",
                  "quamba_conv_silu_quant", "quamba_conv_step", "quamba_scan_prefill", "quamba_scan_step",
-                 "quamba_hadamard_quant"):
+                 "quamba_scan_prefill_dtproj", "quamba_hadamard_quant"):
         getattr(L, name).restype = C.c_int
     _LIB = L
     return L
@@ -269,6 +271,14 @@ def quamba_scan_prefill(x_q, dt_q, z_q, ldz, B_q, C_q, ldbc, A_q, D_q, dt_bias, 
                                      _ptr(D_q), _ptr(dt_bias), C.byref(scales_from_dict(sc)), Bt, L, Di,
                                      _ptr(g16), _ptr(y_f32), _ptr(ssm_state), _ptr(ws), _nbytes(ws),
                                      _stream(stream)))
+
+
+def quamba_scan_prefill_dtproj(x_q, dtlow_q, lddl, W_dt_q, R, m_dt, dt_q, z_q, ldz, B_q, C_q, ldbc, A_q, D_q, dt_bias,
+                               sc, Bt, L, Di, g16, y_f32, ssm_state, ws, stream=None):
+    _check(lib().quamba_scan_prefill_dtproj(_ptr(x_q), _ptr(dtlow_q), lddl, _ptr(W_dt_q), R, float(m_dt), _ptr(dt_q),
+                                            _ptr(z_q), ldz, _ptr(B_q), _ptr(C_q), ldbc, _ptr(A_q), _ptr(D_q),
+                                            _ptr(dt_bias), C.byref(scales_from_dict(sc)), Bt, L, Di, _ptr(g16),
+                                            _ptr(y_f32), _ptr(ssm_state), _ptr(ws), _nbytes(ws), _stream(stream)))
 
 
 def quamba_scan_step(x_q, dt_q, z_q, ldz, B_q, C_q, ldbc, A_q, D_q, dt_bias, sc, Bt, Di, g16, y_f32, ssm_state,

@@ -15,15 +15,42 @@ SOURCES = ["api.hip", "gemm_i8.hip", "elementwise.hip", "scan.hip", "hadamard.hi
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + os.path.join(ROOT, "include"),
          "-I" + CSRC, "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wno-unused-command-line-argument"]
+         "-Wno-unused-command-line-argument", "-Rpass-analysis=kernel-resource-usage"]
+# Kernels that count their own outstanding loads (explicit vmcnt waits) must not spill: scratch
+# accesses share that counter and would make the waits release too early.
+NO_SPILL = ("gemm_i8_dma_kernel",)
+
+
+def _check_spills(stderr: str) -> None:
+    """Read the compiler's per-kernel resource remarks; refuse spills in the NO_SPILL kernels."""
+    name = None
+    for line in stderr.splitlines():
+        if "remark: Function Name:" in line:
+            name = line.split("Function Name:")[1].split()[0]
+        elif name and ("ScratchSize [bytes/lane]:" in line or "VGPRs Spill:" in line or "SGPRs Spill:" in line):
+            val = int(line.split(":")[-1].split()[0])
+            if val != 0 and any(k in name for k in NO_SPILL):
+                raise RuntimeError("kernel %s spills (%s): its explicit vmcnt waits would be wrong"
+                                   % (name, line.split("remark:")[1].strip()))
 
 
 def _run(cmd):
     r = subprocess.run(cmd, capture_output=True, text=True)
-    err = "\n".join(l for l in r.stderr.splitlines() if "is not a recognized feature" not in l)
     if r.returncode != 0:
-        raise RuntimeError("command failed: %s\n%s\n%s" % (" ".join(cmd), r.stdout, err))
-    return err
+        raise RuntimeError("command failed: %s\n%s\n%s" % (" ".join(cmd), r.stdout, r.stderr))
+    _check_spills(r.stderr)
+    keep, skip = [], 0
+    for l in r.stderr.splitlines():  # drop the resource remarks and the harmless feature warning
+        if "is not a recognized feature" in l:
+            continue
+        if "kernel-resource-usage" in l:
+            skip = 2  # the remark is followed by a source line and a caret line
+            continue
+        if skip:
+            skip -= 1
+            continue
+        keep.append(l)
+    return "\n".join(keep)
 
 
 def build(verbose: bool = False) -> str:

@@ -144,8 +144,11 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
     QUAMBA_TRY(launch_gemm_i8(x_q, Di, qw->W_x, Di, M, NX, Di, e, base + p.gemm, p.gemm_bytes, st));
     QUAMBA_TRY(tap_copy(t.dbc_q, dbc_q, (size_t)M * NX, st));
   }
-  // dt_proj on the dt_low columns
-  {
+  // dt_proj on the dt_low columns.  In prefill the scan's first pass computes dt_q itself when
+  // the shapes allow and the raw dt_proj sums are not asked for; otherwise it is a GEMM.
+  const bool fuse_dt = !decode && L > 1 && !t.acc_dt && R >= 16 && R % 16 == 0 && NX % 16 == 0 && Di % 4 == 0 &&
+                       aligned(qw->W_dt, 16);
+  if (!fuse_dt) {
     GemmEpilogue e{dt_q, nullptr, t.acc_dt, Di, Di, Di, sc->m_dt, sc->m_dt, sc->m_dt};
     QUAMBA_TRY(launch_gemm_i8(dbc_q, NX, qw->W_dt, R, M, Di, R, e, base + p.gemm, p.gemm_bytes, st));
     QUAMBA_TRY(tap_copy(t.dt_q, dt_q, (size_t)M * Di, st));
@@ -159,11 +162,15 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
     a.s_x = sc->s_x; a.s_dt = sc->s_dt; a.s_z = sc->s_z; a.s_B = sc->s_B; a.s_C = sc->s_C;
     a.s_A = sc->s_A; a.s_D = sc->s_D;
     a.Bt = Bt; a.L = L; a.Di = Di; a.g16 = g16; a.y_f32 = t.y_f32; a.ssm_state = ssm_state;
+    if (fuse_dt) {
+      a.dtlow_q = dbc_q; a.lddl = NX; a.W_dt = qw->W_dt; a.R = R; a.m_dt = sc->m_dt; a.dt_out = dt_q;
+    }
     if (decode) {
       QUAMBA_TRY(launch_scan_step(a, st));
     } else {
       QUAMBA_TRY(launch_scan_prefill(a, base + p.scan, p.total - p.scan, st));
     }
+    if (fuse_dt) QUAMBA_TRY(tap_copy(t.dt_q, dt_q, (size_t)M * Di, st));
     QUAMBA_TRY(tap_copy(t.g16, g16, (size_t)M * Di * sizeof(__half), st));
   }
   // Hadamard transform + quantization (Eq. 3)
@@ -358,6 +365,21 @@ int quamba_scan_prefill(const int8_t *x_q, const int8_t *dt_q, const int8_t *z_q
   QUAMBA_TRY(fill_scan(a, x_q, dt_q, z_q, ldz, B_q, C_q, ldbc, A_q, D_q, dt_bias, sc, Bt, L, Di, g16, y_f32,
                        ssm_state));
   if (!ws || !aligned(ws, 256)) return fail(QUAMBA_EINVAL, "scan: workspace NULL or not 256-byte aligned");
+  return launch_scan_prefill(a, ws, ws_bytes, as_stream(stream));
+}
+
+int quamba_scan_prefill_dtproj(const int8_t *x_q, const int8_t *dtlow_q, int lddl, const int8_t *W_dt_q, int R,
+                               float m_dt, int8_t *dt_q, const int8_t *z_q, int ldz, const int8_t *B_q,
+                               const int8_t *C_q, int ldbc, const int8_t *A_q, const int8_t *D_q,
+                               const float *dt_bias, const quamba_scales *sc, int Bt, int L, int Di,
+                               quamba_half *g16, float *y_f32, float *ssm_state, void *ws, size_t ws_bytes,
+                               void *stream) {
+  ScanArgs a{};
+  if (!dtlow_q || !W_dt_q || !dt_q) return fail(QUAMBA_EINVAL, "scan: NULL pointer");
+  QUAMBA_TRY(fill_scan(a, x_q, dt_q, z_q, ldz, B_q, C_q, ldbc, A_q, D_q, dt_bias, sc, Bt, L, Di, g16, y_f32,
+                       ssm_state));
+  if (!ws || !aligned(ws, 256)) return fail(QUAMBA_EINVAL, "scan: workspace NULL or not 256-byte aligned");
+  a.dtlow_q = dtlow_q; a.lddl = lddl; a.W_dt = W_dt_q; a.R = R; a.m_dt = m_dt; a.dt_out = dt_q;
   return launch_scan_prefill(a, ws, ws_bytes, as_stream(stream));
 }
 

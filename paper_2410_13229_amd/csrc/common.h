@@ -75,6 +75,12 @@ struct ScanArgs {
   __half *g16;
   float *y_f32;
   float *ssm_state;
+  // prefill only, optional: dt_q = q(W_dt dt_low, m_dt) is computed by the scan itself from the
+  // dt_low codes [Bt*L, lddl] and W_dt [Di, R] and written to dt_out [Bt*L, Di]; dt_q is ignored
+  const int8_t *dtlow_q, *W_dt;
+  int lddl, R;
+  float m_dt;
+  int8_t *dt_out;
 };
 
 size_t scan_workspace_bytes(int Bt, int L, int Di);

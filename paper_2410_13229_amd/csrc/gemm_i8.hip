@@ -21,11 +21,9 @@
 // sums go to a workspace and a second kernel adds them and applies the epilogue (integer
 // addition, so the result does not depend on the order).
 #include "common.h"
+#include "device_util.h"
 
 namespace quamba {
-
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v16i __attribute__((ext_vector_type(16)));
 
 namespace {
 
@@ -37,17 +35,6 @@ template <int BKB>
 __device__ __forceinline__ int swzk(int row, int chunk) {
   if constexpr (BKB == 64) return row * 64 + ((chunk ^ ((row >> 2) & 3)) << 4);
   else return row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4);
-}
-
-__device__ __forceinline__ unsigned requant_pack4(const int (&a)[4], float m) {
-  unsigned p = 0;
-#pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    float v = __builtin_rintf(static_cast<float>(a[e]) * m);
-    v = __builtin_amdgcn_fmed3f(v, -128.f, 127.f);
-    p |= (static_cast<unsigned>(static_cast<int>(v)) & 0xffu) << (8 * e);
-  }
-  return p;
 }
 
 // Epilogue for four consecutive columns gn..gn+3 of row gm.  The column ranges end on multiples

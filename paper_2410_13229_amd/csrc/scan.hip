@@ -17,7 +17,13 @@
 //           with P_c = exp(A * sum_c dt); emits the start state of every chunk and h_L
 //   pass 3  per (chunk, channel): rerun the chunk from its true start state and emit g
 // Decode is a single recurrence step with 4 lanes per channel (float4 state access).
+//
+// Pass 1 can also produce dt_q itself (Section 4.3 fuses operators to save memory traffic and
+// launches): dt_q = q(W_dt dt_low) is a K = dt_rank contraction, a handful of MFMAs per
+// (32-token, 64-channel) tile, which each wave runs for its own channels before it walks the
+// tokens.  The codes go through a wave-private LDS tile to the lanes and to dt_q for pass 3.
 #include "common.h"
+#include "device_util.h"
 
 namespace quamba {
 namespace {
@@ -27,6 +33,7 @@ constexpr float LN2 = 0.69314718055994530942f;
 constexpr int NS = 16;       // d_state
 constexpr int TB = 64;       // tokens of B/C staged in LDS at a time
 constexpr int SCAN_THREADS = 256;
+constexpr int DT_LD = 68;    // row pitch (bytes) of the LDS tile of dt codes: 17 words, odd
 
 __device__ __forceinline__ float exp2_fast(float v) { return __builtin_amdgcn_exp2f(v); }
 
@@ -54,6 +61,11 @@ struct Dev {
   float *y_f32;
   float *hloc;  // [Bt, nchunks, Di, 16]
   float *ssum;  // [Bt, nchunks, Di]
+  // fused dt_proj (pass 1): dt_low codes [Bt*L, lddl], W_dt [Di, R], multiplier, dt_q to write
+  const int8_t *dtlow_q, *W_dt;
+  int lddl, R;
+  float m_dt;
+  int8_t *dt_out;
 };
 
 // Dequantize B (and C) of tokens [row0, row0+cnt) into LDS as fp32 [TB][16].
@@ -76,10 +88,13 @@ __device__ __forceinline__ void stage_bc(const Dev &p, size_t row0, int cnt, flo
 // dt).  OUTPUT = true: pass 3 (state from the carried start, gated output).
 // The int8 x / dt / z bytes of the next TS tokens are fetched into registers while the
 // current TS tokens are computed, so no load latency sits on the recurrence.
-template <bool OUTPUT>
+// FUSE_DT (pass 1 only): dt_q is not read but computed from dt_low and W_dt, and written out.
+template <bool OUTPUT, bool FUSE_DT>
 __global__ __launch_bounds__(SCAN_THREADS) void scan_chunk_kernel(Dev p) {
+  static_assert(!(OUTPUT && FUSE_DT), "dt_q is produced by pass 1");
   __shared__ __attribute__((aligned(16))) float sB[TB][NS];
   __shared__ __attribute__((aligned(16))) float sC[OUTPUT ? TB : 1][NS];
+  __shared__ __attribute__((aligned(16))) int8_t sDT[FUSE_DT ? SCAN_THREADS / 64 : 1][FUSE_DT ? TB : 1][DT_LD];
   const int d = blockIdx.x * SCAN_THREADS + threadIdx.x;
   const int c = blockIdx.y, b = blockIdx.z;
   const bool live = d < p.Di;
@@ -115,6 +130,58 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_chunk_kernel(Dev p) {
   const int8_t *dp = p.dt_q + seq0 * p.Di + dd;
   const int8_t *zp = p.z_q + seq0 * p.ldz + dd;
 
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  // dt codes of tokens [tok0, tok0 + 32) for this wave's 64 channels -> rows [row0, row0 + 32) of
+  // its LDS tile.  MFMA operands come straight from global memory (every fragment is used once):
+  // lane l supplies 16 bytes of k at offset 32 s + 16 (l / 32) of weight row / token row l % 32;
+  // register r of tile i then holds channel 32 i + 8 (r / 4) + 4 (l / 32) + r % 4 of token l % 32.
+  auto dt_tile = [&](int tok0, int row0) {
+    const int dw0 = blockIdx.x * SCAN_THREADS + wave * 64;
+    const int8_t *arow = p.dtlow_q + (seq0 + min(tok0 + (lane & 31), t1 - 1)) * p.lddl;
+    const int8_t *w0 = p.W_dt + (size_t)min(dw0 + (lane & 31), p.Di - 1) * p.R;
+    const int8_t *w1 = p.W_dt + (size_t)min(dw0 + 32 + (lane & 31), p.Di - 1) * p.R;
+    const int koff = 16 * (lane >> 5);
+    v16i acc[2];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[0][r] = acc[1][r] = 0;
+    constexpr int PH = 3;  // k steps whose operands are in flight together
+    for (int s0 = 0; s0 * 32 < p.R; s0 += PH) {
+      v4i fa[PH], fw0[PH], fw1[PH];
+#pragma unroll
+      for (int j = 0; j < PH; ++j) {
+        const int kc = 32 * (s0 + j) + koff;
+        fa[j] = fw0[j] = fw1[j] = v4i{0, 0, 0, 0};
+        if (kc < p.R) {  // R is a multiple of 16: a 16-byte piece is all in or all out
+          fa[j] = *reinterpret_cast<const v4i *>(arow + kc);
+          fw0[j] = *reinterpret_cast<const v4i *>(w0 + kc);
+          fw1[j] = *reinterpret_cast<const v4i *>(w1 + kc);
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < PH; ++j) {
+        acc[0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw0[j], fa[j], acc[0], 0, 0, 0);
+        acc[1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw1[j], fa[j], acc[1], 0, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int a[4] = {acc[i][4 * g], acc[i][4 * g + 1], acc[i][4 * g + 2], acc[i][4 * g + 3]};
+        *reinterpret_cast<unsigned *>(&sDT[wave][row0 + (lane & 31)][32 * i + 8 * g + 4 * (lane >> 5)]) =
+            requant_pack4(a, p.m_dt);
+      }
+  };
+  // rows [0, cnt) of the wave's tile -> dt_q (64 contiguous bytes per token)
+  auto dt_store = [&](int tb, int cnt) {
+    const int ch = blockIdx.x * SCAN_THREADS + wave * 64 + 4 * (lane & 15);
+    for (int tt = lane >> 4; tt < cnt; tt += 4)
+      if (ch < p.Di)  // Di is a multiple of 4
+        *reinterpret_cast<unsigned *>(p.dt_out + (seq0 + tb + tt) * p.Di + ch) =
+            *reinterpret_cast<const unsigned *>(&sDT[wave][tt][4 * (lane & 15)]);
+  };
+
   constexpr int TS = 8;
   struct Regs {
     int x[TS], dt[TS], z[TS];
@@ -124,7 +191,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_chunk_kernel(Dev p) {
     for (int i = 0; i < TS; ++i) {
       const int tt = min(t + i, t1 - 1);  // clamp: tokens past the chunk are loaded but never used
       r.x[i] = xp[(size_t)tt * p.Di];
-      r.dt[i] = dp[(size_t)tt * p.Di];
+      if (!FUSE_DT) r.dt[i] = dp[(size_t)tt * p.Di];  // fused: read from the LDS tile when needed
       if (OUTPUT) r.z[i] = zp[(size_t)tt * p.ldz];
     }
   };
@@ -133,7 +200,8 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_chunk_kernel(Dev p) {
     for (int i = 0; i < TS; ++i) {
       if (t + i < t1) {
         const float xv = p.s_x * static_cast<float>(r.x[i]);
-        const float dt = softplus_f(p.s_dt * static_cast<float>(r.dt[i]) + bias);
+        const int dtq = FUSE_DT ? static_cast<int>(sDT[wave][tl + i][lane]) : r.dt[i];
+        const float dt = softplus_f(p.s_dt * static_cast<float>(dtq) + bias);
         const float u = dt * xv;
         if (!OUTPUT) sdt += dt;
         float y = 0.f;
@@ -158,6 +226,11 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_chunk_kernel(Dev p) {
   for (int tb = t0; tb < t1; tb += TB) {
     const int cnt = min(TB, t1 - tb);
     Regs ra, rb;
+    if (FUSE_DT) {  // the tile is private to the wave: its LDS accesses execute in order
+      dt_tile(tb, 0);
+      if (cnt > 32) dt_tile(tb + 32, 32);
+      dt_store(tb, cnt);
+    }
     fetch(ra, tb);
     __syncthreads();
     stage_bc<OUTPUT>(p, seq0 + tb, cnt, sB, sC);
@@ -264,6 +337,8 @@ Dev make_dev(const ScanArgs &a) {
   p.dt_bias = a.dt_bias; p.ldz = a.ldz; p.ldbc = a.ldbc;
   p.s_x = a.s_x; p.s_dt = a.s_dt; p.s_z = a.s_z; p.s_B = a.s_B; p.s_C = a.s_C; p.s_A = a.s_A; p.s_D = a.s_D;
   p.L = a.L; p.Di = a.Di; p.g16 = a.g16; p.y_f32 = a.y_f32;
+  p.dtlow_q = a.dtlow_q; p.W_dt = a.W_dt; p.lddl = a.lddl; p.R = a.R; p.m_dt = a.m_dt; p.dt_out = a.dt_out;
+  if (a.dtlow_q) p.dt_q = a.dt_out;
   return p;
 }
 
@@ -314,13 +389,21 @@ int launch_scan_prefill(const ScanArgs &a, void *ws, size_t ws_bytes, hipStream_
   p.ssum = reinterpret_cast<float *>(static_cast<char *>(ws) +
                                      align_up((size_t)a.Bt * p.nchunks * a.Di * NS * sizeof(float), 256));
   dim3 grid((a.Di + SCAN_THREADS - 1) / SCAN_THREADS, p.nchunks, a.Bt);
-  hipLaunchKernelGGL(scan_chunk_kernel<false>, grid, dim3(SCAN_THREADS), 0, st, p);
+  if (a.dtlow_q) {
+    if (!a.W_dt || !a.dt_out || a.R < 16 || a.R % 16 || a.lddl % 16 || a.lddl < a.R || a.Di % 4 ||
+        !aligned(a.dtlow_q, 16) || !aligned(a.W_dt, 16) || !aligned(a.dt_out, 4))
+      return fail(QUAMBA_EUNSUPPORTED, "scan: fused dt_proj needs dt_rank and lddl multiples of 16, Di a multiple "
+                                       "of 4, 16-byte aligned dt_low and W_dt");
+    hipLaunchKernelGGL((scan_chunk_kernel<false, true>), grid, dim3(SCAN_THREADS), 0, st, p);
+  } else {
+    hipLaunchKernelGGL((scan_chunk_kernel<false, false>), grid, dim3(SCAN_THREADS), 0, st, p);
+  }
   QUAMBA_LAUNCH_CHECK();
   const size_t n2 = (size_t)a.Bt * a.Di * NS;
   hipLaunchKernelGGL(scan_carry_kernel, dim3((unsigned)((n2 + 255) / 256)), dim3(256), 0, st, p, a.ssm_state,
                      a.Bt);
   QUAMBA_LAUNCH_CHECK();
-  hipLaunchKernelGGL(scan_chunk_kernel<true>, grid, dim3(SCAN_THREADS), 0, st, p);
+  hipLaunchKernelGGL((scan_chunk_kernel<true, false>), grid, dim3(SCAN_THREADS), 0, st, p);
   QUAMBA_LAUNCH_CHECK();
   return QUAMBA_OK;
 }

@@ -167,6 +167,55 @@ def test_scan_prefill(Bt, L, Di, with_h0):
     assert rel_err(host(y32), g_ref) <= 2e-5
 
 
+@pytest.mark.parametrize("Bt,L,Di,R,with_h0", [(1, 1, 64, 16, False), (2, 45, 128, 48, True), (1, 300, 320, 160, False),
+                                                (3, 67, 192, 32, True), (1, 1000, 256, 256, True),
+                                                (1, 256, 1536, 48, False), (1, 130, 100, 80, False)])
+def test_scan_prefill_with_fused_dt_proj(Bt, L, Di, R, with_h0):
+    """dt_q computed inside the scan's first pass: bit-exact codes, same scan tolerances."""
+    rng = np.random.default_rng(L * 17 + Di + R)
+    sc, x, _, xz, _, A, D, bias = _scan_inputs(rng, Bt, L, Di)
+    NX = R + 32
+    dbc = rng.integers(-128, 128, (Bt, L, NX), dtype=np.int8)
+    W_dt = rng.integers(-128, 128, (Di, R), dtype=np.int8)
+    m_dt = np.float32(127.0 / (64.0 * 74.0 * np.sqrt(R) * 3.0))
+    acc = O.int_matmul(dbc[..., :R].reshape(-1, R), W_dt)
+    dt = O.requant_acc(acc, m_dt).reshape(Bt, L, Di)
+    h0 = (rng.standard_normal((Bt, Di, 16)) * 0.1).astype(np.float32) if with_h0 else None
+    g_ref, g16_ref, h_ref = O.q_scan(x, dt, xz[..., Di:], dbc[..., R:R + 16], dbc[..., R + 16:], A, D, bias, sc, h0)
+    full = dict(sc)
+    for k in Q.SCALE_FIELDS:
+        full.setdefault(k, 1.0)
+    dxz, ddbc = dev(xz), dev(dbc)
+    g16 = empty((Bt, L, Di), torch.float16)
+    y32 = empty((Bt, L, Di), torch.float32)
+    dt_q = torch.full((Bt, L, Di), 99, dtype=torch.int8, device="cuda:0")
+    ssm = dev(h0) if with_h0 else torch.zeros((Bt, Di, 16), dtype=torch.float32, device="cuda:0")
+    ws = workspace(Q.quamba_scan_workspace_bytes(Bt, L, Di))
+    Q.quamba_scan_prefill_dtproj(dev(x), ddbc, NX, dev(W_dt), R, m_dt, dt_q, dxz[..., Di:], 2 * Di, ddbc[..., R:],
+                                 ddbc[..., R + 16:], NX, dev(A), dev(D), dev(bias), full, Bt, L, Di, g16, y32, ssm,
+                                 ws)
+    assert np.array_equal(host(dt_q), dt)
+    assert rel_err(host(y32), g_ref) <= 2e-5
+    assert rel_err(host(g16).astype(np.float64), g_ref) <= 1e-3
+    assert rel_err(host(ssm), h_ref) <= 1e-3
+
+
+def test_scan_prefill_with_fused_dt_proj_rejects_odd_rank():
+    rng = np.random.default_rng(5)
+    Bt, L, Di, R = 1, 8, 64, 24
+    sc, x, _, xz, _, A, D, bias = _scan_inputs(rng, Bt, L, Di)
+    full = dict(sc)
+    for k in Q.SCALE_FIELDS:
+        full.setdefault(k, 1.0)
+    dbc = dev(rng.integers(-128, 128, (Bt, L, 64), dtype=np.int8))
+    ws = workspace(Q.quamba_scan_workspace_bytes(Bt, L, Di))
+    with pytest.raises(Q.QuambaError):
+        Q.quamba_scan_prefill_dtproj(dev(x), dbc, 64, dev(rng.integers(-128, 128, (Di, R), dtype=np.int8)), R, 1e-3,
+                                     empty((Bt, L, Di), torch.int8), dev(xz)[..., Di:], 2 * Di, dbc[..., 32:],
+                                     dbc[..., 48:], 64, dev(A), dev(D), dev(bias), full, Bt, L, Di,
+                                     empty((Bt, L, Di), torch.float16), None, None, ws)
+
+
 @pytest.mark.parametrize("Bt,Di", [(1, 64), (7, 192), (64, 5120)])
 def test_scan_step(Bt, Di):
     rng = np.random.default_rng(Bt * 13 + Di)
