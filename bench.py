@@ -35,8 +35,8 @@ MEASURED_TRAFFIC_BYTES = {"c1": 137.3e6}
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--workload", default="c1", choices=["c0", "c1", "c3", "c4"])
     ap.add_argument("--decode-steps", type=int, default=1000)
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle (cpu_baseline) leg")
@@ -163,12 +163,19 @@ def main():
         Q.quamba_gemm_i8(x_q, Di, qd["W_x"], Di, M, NX, Di, R, R + N, [sc.m_x_dt, sc.m_x_B, sc.m_x_C], dbc_q, None,
                          NX, None, gws, stream)
 
-    def s_dt():
+    fused_dt = R >= 16 and R % 16 == 0 and NX % 16 == 0  # what the mixer entry point does for this shape
+
+    def s_dt():  # only on the path when the scan cannot take dt_proj in
         Q.quamba_gemm_i8(dbc_q, NX, qd["W_dt"], R, M, Di, R, Di, Di, [sc.m_dt] * 3, dt_q, None, Di, None, gws, stream)
 
     def s_scan():
-        Q.quamba_scan_prefill(x_q, dt_q, xz_q[:, Di:], 2 * Di, dbc_q[:, R:], dbc_q[:, R + N:], NX, qd["A"], qd["D"],
-                              qd["dt_bias"], sc, Bt, L, Di, g16, None, None, sws, stream)
+        if fused_dt:
+            Q.quamba_scan_prefill_dtproj(x_q, dbc_q, NX, qd["W_dt"], R, sc.m_dt, dt_q, xz_q[:, Di:], 2 * Di,
+                                         dbc_q[:, R:], dbc_q[:, R + N:], NX, qd["A"], qd["D"], qd["dt_bias"], sc, Bt,
+                                         L, Di, g16, None, None, sws, stream)
+        else:
+            Q.quamba_scan_prefill(x_q, dt_q, xz_q[:, Di:], 2 * Di, dbc_q[:, R:], dbc_q[:, R + N:], NX, qd["A"],
+                                  qd["D"], qd["dt_bias"], sc, Bt, L, Di, g16, None, None, sws, stream)
 
     def s_had():
         Q.quamba_hadamard_quant(g16, M, Di, sc.inv_s_y, gH_q, None, stream)
@@ -185,8 +192,12 @@ def main():
         ("in_proj_gemm", s_in, "mfma", 2.0 * M * 2 * Di * Dm),
         ("conv_silu_quant", s_conv, "hbm", 2.0 * M * Di),
         ("x_proj_gemm", s_xp, "hbm", 1.0 * M * Di + NX * Di + M * NX),
-        ("dt_proj_gemm", s_dt, "hbm", 1.0 * M * R + Di * R + M * Di),
-        ("selective_scan", s_scan, "alu", SCAN_FLOP_PER_TD * M * Di),
+    ]
+    if not fused_dt:
+        plan.append(("dt_proj_gemm", s_dt, "hbm", 1.0 * M * R + Di * R + M * Di))
+    plan += [
+        ("dt_proj+selective_scan" if fused_dt else "selective_scan", s_scan, "alu",
+         SCAN_FLOP_PER_TD * M * Di),  # fp32 work of the recurrence only; the fused int8 dt_proj is not counted
         ("hadamard_quant", s_had, "hbm", 3.0 * M * Di),
         ("out_proj_gemm", s_out, "mfma", 2.0 * M * Di * Dm),
     ]
@@ -203,13 +214,13 @@ def main():
             ach, peak, unit = work / sec / 1e12, INT8_PEAK_TOPS, "TOP/s"
         stages[name] = {"us": round(sec * 1e6, 2), "bound": bound, "achieved": round(ach, 1), "peak": peak,
                         "unit": unit, "frac": round(ach / peak, 4)}
-        if name == "selective_scan":  # three kernels; also quote it against HBM as the benchmark spec asks
+        if name.endswith("selective_scan"):  # three kernels; also quote it against HBM as the benchmark spec asks
             hb = (5.0 * M * Di + 2.0 * N * M) / sec / 1e9
             stages[name].update({"kernels": 3, "hbm_achieved_GBs": round(hb, 1),
                                  "hbm_frac": round(hb / HBM_PEAK_GBS, 4)})
     # the dominant kernel is the slowest single kernel: every stage but the scan is one kernel
     # (x_proj adds a small reduce); the scan's three kernels are each shorter than the in_proj GEMM
-    single = {k: v for k, v in stages.items() if k != "selective_scan"}
+    single = {k: v for k, v in stages.items() if not k.endswith("selective_scan")}
     dom = max(single, key=lambda k: single[k]["us"])
     roof = {k: stages[dom][k] for k in ("bound", "achieved", "peak", "unit", "frac")}
     roof.update({"kernel": dom, "us_per_launch": stages[dom]["us"],

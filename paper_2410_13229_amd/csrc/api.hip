@@ -69,6 +69,8 @@ Plan make_plan(const quamba_dims *d, int Bt, int L) {
   return p;
 }
 
+int g_fuse_dt = 1;  // tuning hook
+
 int check_q(const quamba_qweights *qw, const quamba_scales *sc) {
   if (!qw || !sc) return fail(QUAMBA_EINVAL, "qweights or scales is NULL");
   if (!qw->W_in || !qw->conv_w || !qw->W_x || !qw->W_dt || !qw->A || !qw->D || !qw->W_outH || !qw->conv_b ||
@@ -146,7 +148,7 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
   }
   // dt_proj on the dt_low columns.  In prefill the scan's first pass computes dt_q itself when
   // the shapes allow and the raw dt_proj sums are not asked for; otherwise it is a GEMM.
-  const bool fuse_dt = !decode && L > 1 && !t.acc_dt && R >= 16 && R % 16 == 0 && NX % 16 == 0 && Di % 4 == 0 &&
+  const bool fuse_dt = g_fuse_dt && !decode && L > 1 && !t.acc_dt && R >= 16 && R % 16 == 0 && NX % 16 == 0 && Di % 4 == 0 &&
                        aligned(qw->W_dt, 16);
   if (!fuse_dt) {
     GemmEpilogue e{dt_q, nullptr, t.acc_dt, Di, Di, Di, sc->m_dt, sc->m_dt, sc->m_dt};
@@ -405,3 +407,5 @@ int quamba_hadamard_quant(const quamba_half *g, int M, int n, float inv_s_y, int
 }
 
 }  // extern "C"
+
+extern "C" void quamba_debug_set_fuse_dt(int v) { quamba::g_fuse_dt = v; }
