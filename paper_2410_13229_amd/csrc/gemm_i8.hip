@@ -90,13 +90,14 @@ __device__ __forceinline__ void store_tiles(const v16i (&acc)[TN][TM], int m_bas
 // values out row-major in a private LDS region and then writes it with 16 bytes per lane, so a
 // wave-level store covers whole runs of a row instead of 8-byte pieces of 32 different rows.
 // Needs N, ldo and the output base aligned to 16 bytes; `scratch` is this wave's region of
-// TM*32 * TN*32 * sizeof(element) bytes, free of other use (callers barrier before).
+// TM*32 * (TN*32 * sizeof(element) + 16) bytes, free of other use (callers barrier before).
 template <int TM, int TN>
 __device__ __forceinline__ void store_tiles_rows(const v16i (&acc)[TN][TM], int m_base, int n_base, int lane,
                                                  int M, int N, const GemmEpilogue &epi, int8_t *scratch) {
   const bool f16 = epi.out_f16 != nullptr;
   const int esz = f16 ? 2 : 1;
   const int rowb = TN * 32 * esz;  // bytes per block row
+  const int pitch = rowb + 16;     // staged rows sit 16 bytes further apart: fewer lanes per LDS bank
 #pragma unroll
   for (int i = 0; i < TN; ++i) {
 #pragma unroll
@@ -115,9 +116,9 @@ __device__ __forceinline__ void store_tiles_rows(const v16i (&acc)[TN][TM], int 
           } pk;
 #pragma unroll
           for (int e = 0; e < 4; ++e) pk.h[e] = __float2half_rn(static_cast<float>(a[e]) * m);
-          *reinterpret_cast<uint2 *>(scratch + row * rowb + col * 2) = pk.u;
+          *reinterpret_cast<uint2 *>(scratch + row * pitch + col * 2) = pk.u;
         } else {
-          *reinterpret_cast<unsigned *>(scratch + row * rowb + col) = requant_pack4(a, m);
+          *reinterpret_cast<unsigned *>(scratch + row * pitch + col) = requant_pack4(a, m);
         }
       }
     }
@@ -131,7 +132,7 @@ __device__ __forceinline__ void store_tiles_rows(const v16i (&acc)[TN][TM], int 
     const int gm = m_base + row;
     const int gcol = n_base + cc * (16 / esz);
     if (gm < M && gcol < N) {
-      const v4i v = *reinterpret_cast<const v4i *>(scratch + row * rowb + cc * 16);
+      const v4i v = *reinterpret_cast<const v4i *>(scratch + row * pitch + cc * 16);
       *reinterpret_cast<v4i *>(out + ((size_t)gm * epi.ldo + gcol) * esz) = v;
     }
   }
@@ -147,7 +148,7 @@ __device__ __forceinline__ void finish(const v16i (&acc)[TN][TM], int m_base, in
                                        int8_t *scratch, int scratch_bytes) {
   const bool f16 = epi.out_f16 != nullptr;
   const int per = f16 ? 8 : 16;  // elements per 16-byte store
-  const int region = TM * 32 * TN * 32 * (f16 ? 2 : 1);  // bytes one wave stages
+  const int region = TM * 32 * (TN * 32 * (f16 ? 2 : 1) + 16);  // bytes one wave stages (padded rows)
   const uintptr_t base = reinterpret_cast<uintptr_t>(f16 ? (const void *)epi.out_f16 : (const void *)epi.out_i8);
   const bool rows_ok = !partial && !epi.acc && base != 0 && (N % per) == 0 && (epi.ldo % per) == 0 &&
                        (base % 16) == 0 && region <= scratch_bytes;

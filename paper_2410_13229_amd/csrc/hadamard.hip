@@ -6,6 +6,11 @@
 // k part (Section 3.3: a known Hadamard matrix of non-power-of-two order) is the first Paley
 // construction for q = k - 1 prime, applied as a dense +-1 product of order k.
 //
+// For fp16 input the order-k factor runs on the matrix cores: y[a, w] = sum_b H_k[a, b] x[b, w]
+// is a (k x k) by (k x 2^m) product whose operands (+-1 and fp16 values) are exact in fp16 and
+// whose sums accumulate in fp32, so only the order of the fp32 additions differs from the
+// scalar form.  H_k is zero-padded to 32 x 32.
+//
 // One workgroup per row.  The row sits in LDS as fp32; each pass gathers 2^r (or k) elements
 // per work item at a power-of-two stride, transforms them in registers and scatters them back.
 // The last pass covers the lowest four index bits, so every work item ends with 16 adjacent
@@ -16,7 +21,9 @@
 namespace quamba {
 namespace {
 
-constexpr int HT = 256;  // threads per row
+// Threads per row: one per 16 elements (every pass then gives each thread one work item), in
+// whole waves, at most 1024.
+constexpr int threads_for(int n) { return n / 16 >= 1024 ? 1024 : (n / 16 + 63) / 64 * 64; }
 
 __device__ __forceinline__ int pad(int i) { return i + ((i >> 4) << 2); }
 
@@ -48,7 +55,21 @@ struct Paley {
   }
 };
 
+// H_k as fp16 bit patterns (+1 = 0x3C00, -1 = 0xBC00), zero-padded to 32 x 32: the A operand of
+// the MFMA form, read 16 bytes per lane.
 template <int K>
+struct PaleyHalf {
+  uint16_t h[32][32];
+  constexpr PaleyHalf() : h{} {
+    constexpr Paley<K - 1> tab{};
+    for (int a = 0; a < K; ++a)
+      for (int b = 0; b < K; ++b) h[a][b] = ((tab.neg[a] >> b) & 1u) ? 0xBC00 : 0x3C00;
+  }
+};
+template <int K>
+__device__ const PaleyHalf<K> g_paley_half{};
+
+template <int K, int HT>
 __device__ __forceinline__ void order_k_pass(float *row, int logm) {
   if constexpr (K > 1) {
     constexpr Paley<K - 1> tab{};
@@ -71,6 +92,64 @@ __device__ __forceinline__ void order_k_pass(float *row, int logm) {
   }
 }
 
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// fp16 row in global memory -> order-k transform -> fp32 row in LDS (padded layout), using
+// v_mfma_f32_32x32x16_f16.  The row is first staged as fp16 [K][2^LOGM + 8] in the same LDS
+// bytes (the pitch keeps the two half-waves of a fragment read on different banks).  Operand
+// element e of lane l at k step s is b = 16 s + 8 (l / 32) + e for both operands: H_k[l % 32, b]
+// on the A side, x[b, 32 t + l % 32] on the B side; register r of the result is row
+// a = 8 (r / 4) + 4 (l / 32) + r % 4, column 32 t + l % 32.
+template <int K, int LOGM, int HT>
+__device__ __forceinline__ void order_k_load_mfma(const __half *__restrict__ src, float *row) {
+  static_assert(K > 1 && K <= 32 && LOGM >= 5, "one 32-row tile of H_k, whole 32-column tiles");
+  constexpr int W = 1 << LOGM, PITCH = W + 8, n = K << LOGM;
+  _Float16 *hx = reinterpret_cast<_Float16 *>(row);
+  for (int i = threadIdx.x * 8; i < n; i += HT * 8)
+    *reinterpret_cast<uint4 *>(hx + (i >> LOGM) * PITCH + (i & (W - 1))) = *reinterpret_cast<const uint4 *>(src + i);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int a = lane & 31, bhalf = 8 * (lane >> 5);
+  h8 ha[2];
+#pragma unroll
+  for (int s = 0; s < 2; ++s) ha[s] = *reinterpret_cast<const h8 *>(&g_paley_half<K>.h[a][16 * s + bhalf]);
+  __syncthreads();
+  constexpr int NWAVE = HT / 64, TILES = W / 32, TPW = (TILES + NWAVE - 1) / NWAVE;  // column tiles, per wave
+  f32x16 acc[TPW];
+#pragma unroll
+  for (int q = 0; q < TPW; ++q) {
+    const int t = wave + NWAVE * q;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[q][r] = 0.f;
+    if (t < TILES) {
+#pragma unroll
+      for (int s = 0; s < 2; ++s) {
+        if (16 * s >= K) continue;
+        h8 hb;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int b = 16 * s + bhalf + e;
+          hb[e] = b < K ? hx[b * PITCH + 32 * t + a] : static_cast<_Float16>(0.f);
+        }
+        acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ha[s], hb, acc[q], 0, 0, 0);
+      }
+    }
+  }
+  __syncthreads();  // every fragment is in registers: the fp16 staging may be overwritten
+#pragma unroll
+  for (int q = 0; q < TPW; ++q) {
+    const int t = wave + NWAVE * q;
+    if (t < TILES) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int oa = 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        if (oa < K) row[pad((oa << LOGM) | (32 * t + a))] = acc[q][r];
+      }
+    }
+  }
+  __syncthreads();
+}
+
 template <int R>
 __device__ __forceinline__ void butterflies(float (&v)[1 << R]) {
 #pragma unroll
@@ -85,7 +164,7 @@ __device__ __forceinline__ void butterflies(float (&v)[1 << R]) {
 }
 
 // Butterflies over index bits [s, s+R) of the whole row.
-template <int R>
+template <int R, int HT>
 __device__ __forceinline__ void radix_pass(float *row, int n, int s) {
   if constexpr (R > 0) {
     const int items = n >> R;
@@ -103,42 +182,51 @@ __device__ __forceinline__ void radix_pass(float *row, int n, int s) {
   }
 }
 
-__device__ __forceinline__ unsigned q8u(float v) {
-  v = __builtin_rintf(v);
-  v = fminf(fmaxf(v, -128.f), 127.f);
-  return static_cast<unsigned>(static_cast<int>(v)) & 0xffu;
+// Four values -> four int8 codes (Eq. 2): clamp to [-128, 127], then add 1.5 * 2^23 so that the
+// low mantissa byte is the round-to-nearest-even integer (the sum has unit spacing and the
+// constant is even, so ties break as rintf would).
+__device__ __forceinline__ unsigned q8x4(float v0, float v1, float v2, float v3, float inv_s) {
+  const unsigned b0 = __float_as_uint(__builtin_amdgcn_fmed3f(v0 * inv_s, -128.f, 127.f) + 12582912.f);
+  const unsigned b1 = __float_as_uint(__builtin_amdgcn_fmed3f(v1 * inv_s, -128.f, 127.f) + 12582912.f);
+  const unsigned b2 = __float_as_uint(__builtin_amdgcn_fmed3f(v2 * inv_s, -128.f, 127.f) + 12582912.f);
+  const unsigned b3 = __float_as_uint(__builtin_amdgcn_fmed3f(v3 * inv_s, -128.f, 127.f) + 12582912.f);
+  return __builtin_amdgcn_perm(b1, b0, 0x0c0c0400u) | __builtin_amdgcn_perm(b3, b2, 0x04000c0cu);
 }
 
 template <int K, int LOGM, typename TIn>
-__global__ __launch_bounds__(HT) void hadamard_quant_kernel(const TIn *__restrict__ g, float inv_s,
+__global__ __launch_bounds__(threads_for(K << LOGM)) void hadamard_quant_kernel(const TIn *__restrict__ g, float inv_s,
                                                             int8_t *__restrict__ out,
                                                             float *__restrict__ out_f32) {
   static_assert(LOGM >= 4, "the last pass owns the low four index bits");
   constexpr int n = K << LOGM;
+  constexpr int HT = threads_for(n);
   extern __shared__ __attribute__((aligned(16))) float row[];
   const size_t r = blockIdx.x;
   const TIn *src = g + r * n;
 
-  for (int i = threadIdx.x * 8; i < n; i += HT * 8) {
-    float *dst = row + pad(i);
-    if constexpr (sizeof(TIn) == 2) {
-      union {
-        uint4 u;
-        __half h[8];
-      } in;
-      in.u = *reinterpret_cast<const uint4 *>(src + i);
-      *reinterpret_cast<float4 *>(dst) = make_float4(__half2float(in.h[0]), __half2float(in.h[1]),
-                                                     __half2float(in.h[2]), __half2float(in.h[3]));
-      *reinterpret_cast<float4 *>(dst + 4) = make_float4(__half2float(in.h[4]), __half2float(in.h[5]),
-                                                         __half2float(in.h[6]), __half2float(in.h[7]));
-    } else {
-      *reinterpret_cast<float4 *>(dst) = *reinterpret_cast<const float4 *>(src + i);
-      *reinterpret_cast<float4 *>(dst + 4) = *reinterpret_cast<const float4 *>(src + i + 4);
+  if constexpr (sizeof(TIn) == 2 && K > 1 && LOGM >= 5) {
+    order_k_load_mfma<K, LOGM, HT>(src, row);
+  } else {
+    for (int i = threadIdx.x * 8; i < n; i += HT * 8) {
+      float *dst = row + pad(i);
+      if constexpr (sizeof(TIn) == 2) {
+        union {
+          uint4 u;
+          __half h[8];
+        } in;
+        in.u = *reinterpret_cast<const uint4 *>(src + i);
+        *reinterpret_cast<float4 *>(dst) = make_float4(__half2float(in.h[0]), __half2float(in.h[1]),
+                                                       __half2float(in.h[2]), __half2float(in.h[3]));
+        *reinterpret_cast<float4 *>(dst + 4) = make_float4(__half2float(in.h[4]), __half2float(in.h[5]),
+                                                           __half2float(in.h[6]), __half2float(in.h[7]));
+      } else {
+        *reinterpret_cast<float4 *>(dst) = *reinterpret_cast<const float4 *>(src + i);
+        *reinterpret_cast<float4 *>(dst + 4) = *reinterpret_cast<const float4 *>(src + i + 4);
+      }
     }
+    __syncthreads();
+    order_k_pass<K, HT>(row, LOGM);
   }
-  __syncthreads();
-
-  order_k_pass<K>(row, LOGM);
 
   // index bits [4, LOGM) in up to three passes of at most 5 bits, high bits first
   constexpr int HI = LOGM - 4;
@@ -147,9 +235,9 @@ __global__ __launch_bounds__(HT) void hadamard_quant_kernel(const TIn *__restric
   constexpr int R1 = NP > 1 ? (HI - R0 + NP - 2) / (NP - 1) : 0;
   constexpr int R2 = NP > 2 ? HI - R0 - R1 : 0;
   static_assert(R0 + R1 + R2 == HI && NP <= 3, "pass schedule");
-  radix_pass<R0>(row, n, LOGM - R0);
-  radix_pass<R1>(row, n, LOGM - R0 - R1);
-  radix_pass<R2>(row, n, 4);
+  radix_pass<R0, HT>(row, n, LOGM - R0);
+  radix_pass<R1, HT>(row, n, LOGM - R0 - R1);
+  radix_pass<R2, HT>(row, n, 4);
 
   // last pass: bits [0, 4), fused with scale / round / clamp / pack
   for (int w = threadIdx.x; w < n / 16; w += HT) {
@@ -168,8 +256,7 @@ __global__ __launch_bounds__(HT) void hadamard_quant_kernel(const TIn *__restric
       unsigned pk[4];
 #pragma unroll
       for (int q = 0; q < 4; ++q)
-        pk[q] = q8u(v[4 * q] * inv_s) | (q8u(v[4 * q + 1] * inv_s) << 8) | (q8u(v[4 * q + 2] * inv_s) << 16) |
-                (q8u(v[4 * q + 3] * inv_s) << 24);
+        pk[q] = q8x4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3], inv_s);
       *reinterpret_cast<uint4 *>(out + r * n + (size_t)w * 16) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
     }
     if (out_f32) {
@@ -191,7 +278,7 @@ int run(const TIn *g, int M, float inv_s, int8_t *out, float *out_f32, hipStream
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     attr_set = true;
   }
-  hipLaunchKernelGGL((hadamard_quant_kernel<K, LOGM, TIn>), dim3(M), dim3(HT), lds, st, g, inv_s, out, out_f32);
+  hipLaunchKernelGGL((hadamard_quant_kernel<K, LOGM, TIn>), dim3(M), dim3(threads_for(n)), lds, st, g, inv_s, out, out_f32);
   QUAMBA_LAUNCH_CHECK();
   return QUAMBA_OK;
 }
