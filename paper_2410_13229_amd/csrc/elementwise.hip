@@ -4,6 +4,7 @@
 // RMSNorm").  Every kernel reads and writes each byte once, with 4- to 16-byte accesses per
 // lane that are contiguous across the wavefront.
 #include "common.h"
+#include "device_util.h"
 
 namespace quamba {
 namespace {
@@ -30,13 +31,10 @@ __global__ __launch_bounds__(256) void quantize_f16_kernel(const __half *__restr
       __half h[8];
     } in;
     in.u = *reinterpret_cast<const uint4 *>(x + i);
-    unsigned lo = 0, hi = 0;
+    float v[8];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      lo |= (static_cast<unsigned>(q8(__half2float(in.h[e]) * inv_s)) & 0xffu) << (8 * e);
-      hi |= (static_cast<unsigned>(q8(__half2float(in.h[e + 4]) * inv_s)) & 0xffu) << (8 * e);
-    }
-    *reinterpret_cast<uint2 *>(q + i) = make_uint2(lo, hi);
+    for (int e = 0; e < 8; ++e) v[e] = __half2float(in.h[e]) * inv_s;
+    *reinterpret_cast<uint2 *>(q + i) = make_uint2(pack_q8x4(v[0], v[1], v[2], v[3]), pack_q8x4(v[4], v[5], v[6], v[7]));
   } else {
     for (size_t j = i; j < n; ++j) q[j] = static_cast<int8_t>(q8(__half2float(x[j]) * inv_s));
   }
@@ -47,7 +45,7 @@ __global__ __launch_bounds__(256) void quantize_f16_kernel(const __half *__restr
 // one sequence.  All TT+3 words are requested up front; a pair of byte permutes per channel
 // turns "4 channels of one tap" into "4 taps of one channel", which v_dot4_i32_i8 multiplies
 // with that channel's packed weights.
-constexpr int CONV_TT = 16;
+constexpr int CONV_TT = 8;
 
 __device__ __forceinline__ float silu_fast(float v) {
   return v * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-v * 1.44269504088896340736f));
@@ -87,14 +85,14 @@ __global__ __launch_bounds__(256) void conv_prefill_kernel(
       const unsigned ub = __builtin_amdgcn_perm(h[i + 3], h[i + 2], 0x07030602u);
       const unsigned taps[4] = {__builtin_amdgcn_perm(ua, ta, 0x05040100u), __builtin_amdgcn_perm(ua, ta, 0x07060302u),
                                 __builtin_amdgcn_perm(ub, tb, 0x05040100u), __builtin_amdgcn_perm(ub, tb, 0x07060302u)};
-      unsigned p = 0;
+      float sv[4];
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         const int a = __builtin_amdgcn_sdot4((int)taps[c], wword[c], 0, false);
         const float v = __fadd_rn(__fmul_rn(static_cast<float>(a), m_conv), bb[c]);
-        p |= (static_cast<unsigned>(q8(silu_fast(v) * inv_s_x)) & 0xffu) << (8 * c);
+        sv[c] = silu_fast(v) * inv_s_x;
       }
-      *reinterpret_cast<unsigned *>(dst + (size_t)(t0 + i) * Di) = p;
+      *reinterpret_cast<unsigned *>(dst + (size_t)(t0 + i) * Di) = pack_q8x4(sv[0], sv[1], sv[2], sv[3]);
     }
   }
   // the tile holding the sequence end also emits the carried window [L-3, L-2, L-1]

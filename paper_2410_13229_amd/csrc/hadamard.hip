@@ -17,6 +17,7 @@
 // outputs, which it scales, rounds, clamps and stores as one 16-byte word.  The LDS row is
 // padded by 4 floats every 16 so that this 16-byte-per-lane pass is bank-conflict free.
 #include "common.h"
+#include "device_util.h"
 
 namespace quamba {
 namespace {
@@ -182,17 +183,6 @@ __device__ __forceinline__ void radix_pass(float *row, int n, int s) {
   }
 }
 
-// Four values -> four int8 codes (Eq. 2): clamp to [-128, 127], then add 1.5 * 2^23 so that the
-// low mantissa byte is the round-to-nearest-even integer (the sum has unit spacing and the
-// constant is even, so ties break as rintf would).
-__device__ __forceinline__ unsigned q8x4(float v0, float v1, float v2, float v3, float inv_s) {
-  const unsigned b0 = __float_as_uint(__builtin_amdgcn_fmed3f(v0 * inv_s, -128.f, 127.f) + 12582912.f);
-  const unsigned b1 = __float_as_uint(__builtin_amdgcn_fmed3f(v1 * inv_s, -128.f, 127.f) + 12582912.f);
-  const unsigned b2 = __float_as_uint(__builtin_amdgcn_fmed3f(v2 * inv_s, -128.f, 127.f) + 12582912.f);
-  const unsigned b3 = __float_as_uint(__builtin_amdgcn_fmed3f(v3 * inv_s, -128.f, 127.f) + 12582912.f);
-  return __builtin_amdgcn_perm(b1, b0, 0x0c0c0400u) | __builtin_amdgcn_perm(b3, b2, 0x04000c0cu);
-}
-
 template <int K, int LOGM, typename TIn>
 __global__ __launch_bounds__(threads_for(K << LOGM)) void hadamard_quant_kernel(const TIn *__restrict__ g, float inv_s,
                                                             int8_t *__restrict__ out,
@@ -256,7 +246,7 @@ __global__ __launch_bounds__(threads_for(K << LOGM)) void hadamard_quant_kernel(
       unsigned pk[4];
 #pragma unroll
       for (int q = 0; q < 4; ++q)
-        pk[q] = q8x4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3], inv_s);
+        pk[q] = pack_q8x4(v[4 * q] * inv_s, v[4 * q + 1] * inv_s, v[4 * q + 2] * inv_s, v[4 * q + 3] * inv_s);
       *reinterpret_cast<uint4 *>(out + r * n + (size_t)w * 16) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
     }
     if (out_f32) {
