@@ -32,6 +32,8 @@ GEMM_SHAPES = [
     (64, 64, 64, 0), (1, 4, 16, 0), (200, 192, 160, 32), (129, 260, 48, 0), (257, 80, 1536, 0),
     (64, 10240, 2560, 0), (512, 2560, 5120, 0), (300, 5120, 160, 32), (2048, 192, 5120, 0),
     (64, 2560, 5120, 0), (1000, 288, 8192, 0), (333, 1280, 1024, 0), (2048, 80, 1536, 0),
+    # the widest tiles (256 x 320, eight waves) and the two-workgroups-per-CU 128 x 160 tiles, ragged in M and N
+    (1100, 14000, 256, 0), (1500, 5408, 128, 0),
 ]
 
 
@@ -68,6 +70,10 @@ def test_gemm_acc_and_requant_bit_exact(M, N, K, pad):
     got = host(out)
     assert np.array_equal(got[:, :N], want_i8)
     assert not got[:, N:].any()  # nothing written past N
+    # without the raw sums the epilogue may restage rows through LDS: same codes
+    out3 = torch.zeros((M, ldo), dtype=torch.int8, device="cuda:0")
+    Q.quamba_gemm_i8(dA, lda, dW, K, M, N, K, e0, e1, mult, out3, None, ldo, None, ws)
+    assert torch.equal(out, out3)
     # fp16 epilogue
     outh = torch.zeros((M, ldo), dtype=torch.float16, device="cuda:0")
     Q.quamba_gemm_i8(dA, lda, dW, K, M, N, K, N, N, mult, None, outh, ldo, None, ws)
