@@ -29,7 +29,7 @@ SCAN_FLOP_PER_TD = 123.0     # 16 x (exp + 2 mul + 2 fma) + D*x + softplus + gat
 # HBM bytes per launch of the dominant kernel (in_proj GEMM, c1) from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE runs of `bench.py --probe`, scaled by a plain device copy in the same run
 # (profiles/in_proj_gemm_c1_hbm_traffic.txt).  None until measured for a workload.
-MEASURED_TRAFFIC_BYTES = {"c1": 137.3e6}
+MEASURED_TRAFFIC_BYTES = {"c1": 90.7e6}
 
 
 def main():

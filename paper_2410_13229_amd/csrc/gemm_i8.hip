@@ -518,7 +518,7 @@ int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, i
   if (M <= 64)
     kind = k128 ? 5 : (k64 ? 3 : 0);
   else if (N <= 512)
-    kind = k64 ? 3 : 0;
+    kind = k128 ? 5 : (k64 ? 3 : 0);
   else if (k128 && M >= 256 && N >= 640)
     kind = tiles_256 >= 192 ? 4 : (tiles_128 <= 384 ? 6 : 2);
   else
