@@ -16,7 +16,8 @@ Pins (tests/test_oracle_*.py): Hadamard orthogonality and the Sylvester closed f
 fold identity of the output projection, quantizer error bound / saturation / idempotence,
 nearest-rank percentile vs a sort, integer GEMM vs int64 loops, conv vs an explicit
 Toeplitz product and causality, scan vs cumulative sum / unrolled sum / chunk splitting /
-the LTI error bound of Theorem 4.1.
+the LTI error bound of Theorem 4.1; the model shell: final norm closed form, head of a one-hot
+vector, and generation by carried state against re-running the prefill on the grown sequence.
 
 parity unpinned: the end-to-end numbers of ``q_prefill`` / ``q_decode`` (the paper prints
 no worked example of a quantized mixer); they are pinned only relatively, against the fp
@@ -29,3 +30,5 @@ from .mixer import (fp_forward, calibrate, q_prefill, q_decode, selective_scan, 
                     causal_conv_fp, add_rmsnorm_quant, silu, softplus, q_scan, q_hadamard_quant,
                     q_out_proj, q_conv_prefill, q_conv_step)
 from .stack import calibrate_stack, q_stack_prefill, q_stack_decode  # noqa: F401
+from .model import (embed, final_norm, lm_head, greedy, model_prefill, model_decode,  # noqa: F401
+                    model_generate)

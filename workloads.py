@@ -57,6 +57,7 @@ CONFIGS = {
 _T_W_IN, _T_CONV_W, _T_W_X, _T_W_DT, _T_W_OUT, _T_DT_BIAS = 1, 2, 3, 4, 5, 6
 _T_OUTLIER_IDX, _T_CALIB, _T_HIDDEN, _T_SSM_STATE, _T_CONV_STATE = 10, 11, 12, 13, 14
 _T_CONV_B, _T_D = 15, 16
+_T_EMBED, _T_NORM, _T_TOKENS = 20, 21, 22
 
 
 def tiny_config(name="tiny", d_model=64, d_inner=128, dt_rank=16, batch=2, seqlen=37,
@@ -144,3 +145,25 @@ def make_decode_state(cfg: MixerConfig, batch=None, layer: int = 0):
     conv = _rng(cfg, _T_CONV_STATE, layer).standard_normal((b, cfg.d_inner, cfg.d_conv - 1),
                                                            dtype=np.float32) * np.float32(2.2)
     return ssm, conv.astype(np.float16)
+
+
+# ------------------------------------------------------------------ whole-model shell inputs
+def make_embedding(cfg: MixerConfig, vocab: int):
+    """fp16 token embedding [vocab, Dm] ~ N(0, 0.02^2) (also the output head: tied)."""
+    e = _rng(cfg, _T_EMBED).standard_normal((vocab, cfg.d_model), dtype=np.float32) * np.float32(0.02)
+    return e.astype(np.float16)
+
+
+def make_norm_weights(cfg: MixerConfig, n_layers: int):
+    """RMSNorm weights: n_layers block norms and the final norm, fp16 [Dm] ~ 1 + 0.1 N(0,1)."""
+    rng = _rng(cfg, _T_NORM)
+    ws = [(1.0 + 0.1 * rng.standard_normal(cfg.d_model, dtype=np.float32)).astype(np.float16)
+          for _ in range(n_layers + 1)]
+    return ws[:-1], ws[-1]
+
+
+def make_tokens(cfg: MixerConfig, vocab: int, batch=None, seqlen=None, stream: int = 0):
+    """int32 token ids [batch, seqlen], uniform over the vocabulary."""
+    b = cfg.batch if batch is None else batch
+    l = cfg.seqlen if seqlen is None else seqlen
+    return _rng(cfg, _T_TOKENS, 0, stream).integers(0, vocab, (b, l), dtype=np.int32)
