@@ -255,6 +255,78 @@ int quamba_scan_step(const int8_t *x_q, const int8_t *dt_q, const int8_t *z_q, i
 int quamba_hadamard_quant(const quamba_half *g, int M, int n, float inv_s_y, int8_t *yH_q,
                           float *yH_f32, void *stream);
 
+/* ---- Whole-model shell.  Section 5.2 reports time to first token (prefill), time per output
+ * token (one generation step) and time to last token of the full language model; this is that
+ * loop around the quantized blocks:
+ *   res = E[token] (fp16), out = 0;
+ *   block l: (u_q, res) = add_rmsnorm_quant(out, res; norm_w_l, 1/s_u,l); out = mixer_l(u_q)
+ *   y = fp16(RMSNorm(out + res) * norm_f); logits = y E^T (fp32 sums); next = argmax
+ * The embedding and the head are one fp16 matrix and are not quantized (Section 4.3 quantizes
+ * the blocks).  `layers` is a HOST array of n_layers entries whose weight pointers are device
+ * memory and whose scales are host values; embedding [vocab, d_model] and the norm weights
+ * [d_model] are fp16 device memory, 16-byte aligned; d_model <= 8192. */
+typedef struct quamba_layer {
+  quamba_qweights q;
+  quamba_scales s;
+  const quamba_half *norm_w;
+} quamba_layer;
+
+typedef struct quamba_model {
+  quamba_dims dims;
+  int n_layers;
+  int vocab;
+  float eps;
+  const quamba_half *embedding;
+  const quamba_half *norm_f;
+  const quamba_layer *layers;
+} quamba_model;
+
+/* The shell's own stages, one entry point each (all buffers device memory, 16-byte aligned):
+ *   quamba_embed       res[m, :] = embedding[clamp(tokens[m], 0, vocab-1), :], out[m, :] = 0; fp16 [M, Dm]
+ *   quamba_final_norm  y[b, :] = fp16(RMSNorm(fp16(out[r] + res[r])) * weight), r = b*L + L-1: the last
+ *                      position of each of Bt sequences of L rows; y fp16 [Bt, Dm]; Dm <= 8192
+ *   quamba_lm_head     logits[b, v] = sum_k y[b, k] embedding[v, k], fp32 sums of fp16 products; [Bt, vocab]
+ *   quamba_argmax      next_token[b] = lowest index of the largest logit of row b
+ * Dm a multiple of 8. */
+int quamba_embed(const quamba_half *embedding, const int32_t *tokens, int M, int Dm, int vocab,
+                 quamba_half *res, quamba_half *out, void *stream);
+int quamba_final_norm(const quamba_half *out, const quamba_half *res, const quamba_half *weight,
+                      float eps, int Bt, int L, int Dm, quamba_half *y, void *stream);
+int quamba_lm_head(const quamba_half *y, const quamba_half *embedding, int Bt, int vocab, int Dm,
+                   float *logits, void *stream);
+int quamba_argmax(const float *logits, int Bt, int vocab, int32_t *next_token, void *stream);
+
+/* Bytes of workspace for batch sequences of L tokens (generation: L = 1); 0 on bad arguments. */
+size_t quamba_model_workspace_bytes(const quamba_model *model, int batch, int L);
+
+/* Prefill of fresh sequences: tokens int32 [Bt, L] (device; ids outside [0, vocab) are clamped).
+ *   logits      fp32 [Bt, vocab] of the last position, 16-byte aligned (may be NULL)
+ *   next_token  int32 [Bt]: argmax of those logits, lowest index among equal maxima (may be NULL)
+ *   ssm_states  fp32 [n_layers, Bt, d_inner, 16], conv_states fp16 [n_layers, Bt, d_inner, 3]:
+ *               OUTPUTS here (the recurrent state starts from zero), inputs of the decode calls
+ * Enqueued on `stream`, not synchronised. */
+int quamba_model_prefill(const quamba_model *model, const int32_t *tokens, int Bt, int L,
+                         float *logits, int32_t *next_token, float *ssm_states,
+                         quamba_half *conv_states, void *ws, size_t ws_bytes, void *stream);
+
+/* One generation step on the carried states (in/out): tokens int32 [Bt]. */
+int quamba_model_decode(const quamba_model *model, const int32_t *tokens, int Bt, float *logits,
+                        int32_t *next_token, float *ssm_states, quamba_half *conv_states,
+                        void *ws, size_t ws_bytes, void *stream);
+
+/* Greedy generation of n_new tokens per sequence from first_tokens [Bt] (device; typically the
+ * next_token of the prefill): step i feeds the token chosen by step i - 1.  tokens_out int32
+ * [n_new, Bt] receives the chosen tokens.  The current token, the step counter and the log stay
+ * on the device, so a step is a fixed sequence of launches: with use_graph != 0 the first step
+ * runs eagerly, the second is captured from `stream` (which must not be the default stream)
+ * into a HIP graph, and the graph is replayed for the rest; the call then returns after the last
+ * replay has finished.  With use_graph == 0 every step is enqueued eagerly and the call does not
+ * synchronise. */
+int quamba_model_generate(const quamba_model *model, const int32_t *first_tokens, int Bt,
+                          int n_new, int32_t *tokens_out, float *ssm_states,
+                          quamba_half *conv_states, void *ws, size_t ws_bytes, int use_graph,
+                          void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -17,6 +17,8 @@ __all__ = [
     "quamba_mixer_decode_q", "quamba_add_rmsnorm_quant", "quamba_quantize_f16", "quamba_gemm_i8",
     "quamba_gemm_workspace_bytes", "quamba_conv_silu_quant", "quamba_conv_step", "quamba_scan_workspace_bytes",
     "quamba_scan_prefill", "quamba_scan_prefill_dtproj", "quamba_scan_step", "quamba_hadamard_quant",
+    "Layer", "Model", "make_model", "quamba_model_workspace_bytes", "quamba_model_prefill", "quamba_model_decode",
+    "quamba_model_generate", "quamba_embed", "quamba_final_norm", "quamba_lm_head", "quamba_argmax",
 ]
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -62,6 +64,15 @@ class Taps(C.Structure):
                                           "dt_q", "y_f32", "g16", "gH_f32", "gH_q", "acc_out")]
 
 
+class Layer(C.Structure):
+    _fields_ = [("q", QWeights), ("s", Scales), ("norm_w", C.c_void_p)]
+
+
+class Model(C.Structure):
+    _fields_ = [("dims", Dims), ("n_layers", C.c_int), ("vocab", C.c_int), ("eps", C.c_float),
+                ("embedding", C.c_void_p), ("norm_f", C.c_void_p), ("layers", C.POINTER(Layer))]
+
+
 def _ptr(t):
     if t is None:
         return None
@@ -98,6 +109,23 @@ def make_qweights(src) -> QWeights:
 
 def make_dims(d) -> Dims:
     return _dims(d)
+
+
+def make_model(dims, embedding, norm_f, layers, eps=1e-5) -> Model:
+    """Model struct from device tensors: embedding fp16 [vocab, Dm], norm_f fp16 [Dm], layers a list of
+    (qweights dict / QWeights, scales dict / Scales, norm_w fp16 [Dm]).  The struct keeps the layer array and
+    the tensors alive through attributes of its own."""
+    arr = (Layer * len(layers))()
+    keep = [embedding, norm_f]
+    for i, (qw, sc, nw) in enumerate(layers):
+        arr[i].q = _struct_of_ptrs(QWeights, qw)
+        arr[i].s = scales_from_dict(sc)
+        arr[i].norm_w = nw.data_ptr()
+        keep += [qw, nw]
+    m = Model(_dims(dims), len(layers), int(embedding.shape[0]), float(eps), embedding.data_ptr(), norm_f.data_ptr(),
+              C.cast(arr, C.POINTER(Layer)))
+    m._keep = (arr, keep)
+    return m
 
 
 def scales_from_dict(d) -> Scales:
@@ -159,6 +187,18 @@ def lib():
                                              i, vp, vp, vp, vp, sz, vp]
     L.quamba_scan_step.argtypes = [vp, vp, vp, i, vp, vp, i, vp, vp, vp, P(Scales), i, i, vp, vp, vp, vp]
     L.quamba_hadamard_quant.argtypes = [vp, i, i, f, vp, vp, vp]
+    L.quamba_model_workspace_bytes.restype = sz
+    L.quamba_model_workspace_bytes.argtypes = [P(Model), i, i]
+    L.quamba_model_prefill.argtypes = [P(Model), vp, i, i, vp, vp, vp, vp, vp, sz, vp]
+    L.quamba_model_decode.argtypes = [P(Model), vp, i, vp, vp, vp, vp, vp, sz, vp]
+    L.quamba_model_generate.argtypes = [P(Model), vp, i, i, vp, vp, vp, vp, sz, i, vp]
+    L.quamba_embed.argtypes = [vp, vp, i, i, i, vp, vp, vp]
+    L.quamba_final_norm.argtypes = [vp, vp, vp, f, i, i, i, vp, vp]
+    L.quamba_lm_head.argtypes = [vp, vp, i, i, i, vp, vp]
+    L.quamba_argmax.argtypes = [vp, i, i, vp, vp]
+    for name in ("quamba_model_prefill", "quamba_model_decode", "quamba_model_generate", "quamba_embed",
+                 "quamba_final_norm", "quamba_lm_head", "quamba_argmax"):
+        getattr(L, name).restype = C.c_int
     for name in ("quamba_calibrate", "quamba_mixer_prefill", "quamba_mixer_prefill_q", "quamba_mixer_decode",
                  "quamba_mixer_decode_q", "quamba_add_rmsnorm_quant", "quamba_quantize_f16", "quamba_gemm_i8",
                  "quamba_conv_silu_quant", "quamba_conv_step", "quamba_scan_prefill", "quamba_scan_step",
@@ -290,3 +330,41 @@ def quamba_scan_step(x_q, dt_q, z_q, ldz, B_q, C_q, ldbc, A_q, D_q, dt_bias, sc,
 
 def quamba_hadamard_quant(g, M, n, inv_s_y, yH_q, yH_f32, stream=None):
     _check(lib().quamba_hadamard_quant(_ptr(g), M, n, float(inv_s_y), _ptr(yH_q), _ptr(yH_f32), _stream(stream)))
+
+
+def quamba_model_workspace_bytes(model, batch, L) -> int:
+    return int(lib().quamba_model_workspace_bytes(C.byref(model), batch, L))
+
+
+def quamba_model_prefill(model, tokens, Bt, L, logits, next_token, ssm_states, conv_states, ws, stream=None):
+    _check(lib().quamba_model_prefill(C.byref(model), _ptr(tokens), Bt, L, _ptr(logits), _ptr(next_token),
+                                      _ptr(ssm_states), _ptr(conv_states), _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def quamba_model_decode(model, tokens, Bt, logits, next_token, ssm_states, conv_states, ws, stream=None):
+    _check(lib().quamba_model_decode(C.byref(model), _ptr(tokens), Bt, _ptr(logits), _ptr(next_token),
+                                     _ptr(ssm_states), _ptr(conv_states), _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def quamba_model_generate(model, first_tokens, Bt, n_new, tokens_out, ssm_states, conv_states, ws, use_graph=False,
+                          stream=None):
+    _check(lib().quamba_model_generate(C.byref(model), _ptr(first_tokens), Bt, n_new, _ptr(tokens_out),
+                                       _ptr(ssm_states), _ptr(conv_states), _ptr(ws), _nbytes(ws),
+                                       1 if use_graph else 0, _stream(stream)))
+
+
+def quamba_embed(embedding, tokens, M, Dm, vocab, res, out, stream=None):
+    _check(lib().quamba_embed(_ptr(embedding), _ptr(tokens), M, Dm, vocab, _ptr(res), _ptr(out), _stream(stream)))
+
+
+def quamba_final_norm(out, res, weight, eps, Bt, L, Dm, y, stream=None):
+    _check(lib().quamba_final_norm(_ptr(out), _ptr(res), _ptr(weight), float(eps), Bt, L, Dm, _ptr(y),
+                                   _stream(stream)))
+
+
+def quamba_lm_head(y, embedding, Bt, vocab, Dm, logits, stream=None):
+    _check(lib().quamba_lm_head(_ptr(y), _ptr(embedding), Bt, vocab, Dm, _ptr(logits), _stream(stream)))
+
+
+def quamba_argmax(logits, Bt, vocab, next_token, stream=None):
+    _check(lib().quamba_argmax(_ptr(logits), Bt, vocab, _ptr(next_token), _stream(stream)))

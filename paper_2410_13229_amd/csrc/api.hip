@@ -60,7 +60,7 @@ Plan make_plan(const quamba_dims *d, int Bt, int L) {
   p.dt_q = take(M * d->d_inner);
   p.g16 = take(M * d->d_inner * sizeof(__half));
   p.gH_q = take(M * d->d_inner);
-  p.scan = take(L > 1 ? scan_workspace_bytes(Bt, L, d->d_inner) : 0);
+  p.scan = take(scan_workspace_bytes(Bt, L, d->d_inner));  // a one-token prefill still runs the chunked scan
   // split-K partial sums: x_proj always (skinny N), every projection when M is small
   const size_t widest = M <= 64 ? (size_t)2 * d->d_inner : nx;
   p.gemm_bytes = gemm_workspace_bytes((int)M, (int)widest);
@@ -187,6 +187,17 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
 }
 
 }  // namespace
+
+size_t mixer_workspace_bytes(const quamba_dims *d, int Bt, int L) { return make_plan(d, Bt, L).total; }
+
+int mixer_run_q(const quamba_dims *d, const quamba_qweights *qw, const quamba_scales *sc, const int8_t *u_q, int Bt,
+                int L, bool decode, __half *out, float *ssm_state, __half *conv_state, void *ws, size_t ws_bytes,
+                hipStream_t st) {
+  return run_mixer(d, qw, sc, nullptr, u_q, Bt, L, decode, out, ssm_state, conv_state, nullptr, ws, ws_bytes, st);
+}
+
+int check_model_dims(const quamba_dims *d) { return check_dims(d); }
+
 }  // namespace quamba
 
 using namespace quamba;

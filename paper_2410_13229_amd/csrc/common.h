@@ -90,4 +90,12 @@ int launch_scan_step(const ScanArgs &a, hipStream_t st);
 int launch_hadamard_quant(const __half *g, int M, int n, float inv_s_y, int8_t *yH_q, float *yH_f32,
                           hipStream_t st);
 
+// one quantized mixer on already quantized input (prefill: fresh conv history; decode: L == 1 on
+// carried states), its workspace size, and the dimension check of the entry points
+size_t mixer_workspace_bytes(const quamba_dims *d, int Bt, int L);
+int mixer_run_q(const quamba_dims *d, const quamba_qweights *qw, const quamba_scales *sc, const int8_t *u_q, int Bt,
+                int L, bool decode, __half *out, float *ssm_state, __half *conv_state, void *ws, size_t ws_bytes,
+                hipStream_t st);
+int check_model_dims(const quamba_dims *d);
+
 }  // namespace quamba

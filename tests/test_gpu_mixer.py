@@ -93,7 +93,8 @@ def end_to_end(r, ref, name):
     return e
 
 
-@pytest.mark.parametrize("Bt,L,dm,di,rk", [(2, 37, 64, 128, 16), (1, 5, 96, 192, 16), (3, 130, 160, 320, 32)])
+@pytest.mark.parametrize("Bt,L,dm,di,rk", [(2, 37, 64, 128, 16), (1, 5, 96, 192, 16), (3, 130, 160, 320, 32),
+                                            (2, 1, 64, 128, 16)])  # the last: a prefill of one token
 def test_prefill_tiny(Bt, L, dm, di, rk):
     cfg = W.tiny_config(name=f"t{di}", d_model=dm, d_inner=di, dt_rank=rk, batch=Bt, seqlen=L, config_id=91 + di)
     w, qw, sc = oracle_setup(cfg, randomize_bias=True, gain=4.0)
