@@ -32,6 +32,77 @@ SCAN_FLOP_PER_TD = 123.0     # 16 x (exp + 2 mul + 2 fma) + D*x + softplus + gat
 MEASURED_TRAFFIC_BYTES = {"c1": 90.7e6}
 
 
+def bench_model(args, Q, W, torch, np, dev, to_dev):
+    """Time to first token, time per output token (eager and HIP-graph replay) and time to last token of
+    the Mamba-2.8B-shaped model: 64 quantized blocks, vocabulary 50280, random-init weights."""
+    cfg = W.CONFIGS["c1"]
+    Dm, Di, N, R = cfg.d_model, cfg.d_inner, cfg.d_state, cfg.dt_rank
+    NX = R + 2 * N
+    vocab, nl = 50280, args.model_layers
+    stream = torch.cuda.Stream()
+    calib = to_dev(W.make_calibration(cfg))
+    nb, Lc = calib.shape[:2]
+    cws = torch.empty(Q.quamba_calibrate_workspace_bytes(cfg, nb, Lc), dtype=torch.uint8, device=dev)
+    distinct = []
+    for l in range(max(1, min(args.model_distinct, nl))):
+        fw = {k: to_dev(v) for k, v in W.make_weights(cfg, layer=l).items()}
+        qd = {"W_in": (2 * Di, Dm), "conv_w": (Di, 4), "W_x": (NX, Di), "W_dt": (Di, R), "A": (Di, N), "D": (Di,),
+              "W_outH": (Dm, Di)}
+        qd = {k: torch.empty(v, dtype=torch.int8, device=dev) for k, v in qd.items()}
+        qd["conv_b"] = torch.empty((Di,), dtype=torch.float32, device=dev)
+        qd["dt_bias"] = torch.empty((Di,), dtype=torch.float32, device=dev)
+        sc = Q.quamba_calibrate(cfg, fw, calib, nb, Lc, 99.999, qd, cws, torch.cuda.current_stream())
+        distinct.append((qd, sc))
+    del cws, fw
+    norm_w, norm_f = W.make_norm_weights(cfg, nl)
+    layers = []
+    for l in range(nl):
+        qd, sc = distinct[l % len(distinct)]
+        layers.append(({k: v.clone() for k, v in qd.items()}, sc, to_dev(norm_w[l])))  # own memory per layer
+    E = to_dev(W.make_embedding(cfg, vocab))
+    m = Q.make_model(cfg, E, to_dev(norm_f), layers)
+    torch.cuda.synchronize()
+
+    def wall(fn, iters):
+        fn()
+        stream.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(iters):
+            fn()
+        stream.synchronize()
+        return (time.perf_counter() - t0) / iters
+
+    out = {"workload": f"Mamba-2.8B shape: {nl} quantized blocks (d_model {Dm}), fp16 tied embedding/head, vocab "
+                       f"{vocab}; {len(distinct)} distinct random-init layers cycled, each layer in its own memory",
+           "ttft_ms": {}}
+    first = torch.empty((64,), dtype=torch.int32, device=dev)
+    ssm = torch.empty((nl, 64, Di, N), dtype=torch.float32, device=dev)
+    cs = torch.empty((nl, 64, Di, 3), dtype=torch.float16, device=dev)
+    with torch.cuda.stream(stream):
+        for L in (512, 1024, 2048):
+            tok = to_dev(W.make_tokens(cfg, vocab, batch=1, seqlen=L))
+            ws = torch.empty(Q.quamba_model_workspace_bytes(m, 1, L), dtype=torch.uint8, device=dev)
+            sec = wall(lambda: Q.quamba_model_prefill(m, tok, 1, L, None, first, ssm, cs, ws, stream), 10)
+            out["ttft_ms"][f"L{L}"] = round(sec * 1e3, 3)
+            del ws
+        n_new = 64
+        for Bd in (1, 64):
+            tok = to_dev(W.make_tokens(cfg, vocab, batch=Bd, seqlen=16, stream=1))
+            wsp = torch.empty(Q.quamba_model_workspace_bytes(m, Bd, 16), dtype=torch.uint8, device=dev)
+            Q.quamba_model_prefill(m, tok, Bd, 16, None, first, ssm, cs, wsp, stream)  # real states to step on
+            del wsp
+            wsd = torch.empty(Q.quamba_model_workspace_bytes(m, Bd, 1), dtype=torch.uint8, device=dev)
+            toks = torch.empty((n_new, Bd), dtype=torch.int32, device=dev)
+            for name, g in (("eager", False), ("graph", True)):
+                sec = wall(lambda: Q.quamba_model_generate(m, first, Bd, n_new, toks, ssm, cs, wsd, g, stream), 3)
+                out[f"tpot_ms_b{Bd}_{name}"] = round(sec / n_new * 1e3, 4)
+            del wsd
+    tp = min(out["tpot_ms_b1_eager"], out["tpot_ms_b1_graph"])
+    out["ttlt_ms_L2048_gen64"] = round(out["ttft_ms"]["L2048"] + 64 * tp, 2)
+    out["decode_tokens_per_s_b64"] = round(64 / (min(out["tpot_ms_b64_eager"], out["tpot_ms_b64_graph"]) * 1e-3), 1)
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -41,6 +112,11 @@ def main():
     ap.add_argument("--decode-steps", type=int, default=1000)
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle (cpu_baseline) leg")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-model", action="store_true", help="skip the whole-model shell (64-layer 2.8B) timings")
+    ap.add_argument("--model-layers", type=int, default=64)
+    ap.add_argument("--model-distinct", type=int, default=4,
+                    help="distinct random-init layers generated on the host; the stack cycles through copies of "
+                         "them, every layer in device memory of its own")
     ap.add_argument("--probe", action="store_true",
                     help="counter-collection mode: a plain 256 MiB device copy (calibration) and 20 launches "
                          "of each stage, nothing else")
@@ -278,6 +354,11 @@ def main():
                   "hbm_frac_algorithmic": round((wbytes + sbytes) / dsec / 1e9 / HBM_PEAK_GBS, 4),
                   "note": "one layer's weights+state (85 MB) stay in the 256 MB last-level cache across steps"}
 
+    # ---- whole-model shell: the 2.8B stack with embedding, final norm, tied head, greedy selection
+    model = None
+    if not args.no_model and args.workload == "c1":
+        model = bench_model(args, Q, W, torch, np, dev, to_dev)
+
     # ---- oracle on the host cores (reported baseline, not the target)
     cpu = None
     if not args.no_cpu:
@@ -315,6 +396,7 @@ def main():
         "roofline": roof,
         "stages": stages,
         "decode": decode,
+        "model": model,
         "cpu_baseline": cpu,
     }
     print(json.dumps(line))
