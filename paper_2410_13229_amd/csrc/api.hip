@@ -148,7 +148,7 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
   }
   // dt_proj on the dt_low columns.  In prefill the scan's first pass computes dt_q itself when
   // the shapes allow and the raw dt_proj sums are not asked for; otherwise it is a GEMM.
-  const bool fuse_dt = g_fuse_dt && !decode && L > 1 && !t.acc_dt && R >= 16 && R % 16 == 0 && NX % 16 == 0 && Di % 4 == 0 &&
+  const bool fuse_dt = g_fuse_dt && (decode || L > 1) && !t.acc_dt && R >= 16 && R % 16 == 0 && NX % 16 == 0 && Di % 4 == 0 &&
                        aligned(qw->W_dt, 16);
   if (!fuse_dt) {
     GemmEpilogue e{dt_q, nullptr, t.acc_dt, Di, Di, Di, sc->m_dt, sc->m_dt, sc->m_dt};
@@ -164,8 +164,9 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
     a.s_x = sc->s_x; a.s_dt = sc->s_dt; a.s_z = sc->s_z; a.s_B = sc->s_B; a.s_C = sc->s_C;
     a.s_A = sc->s_A; a.s_D = sc->s_D;
     a.Bt = Bt; a.L = L; a.Di = Di; a.g16 = g16; a.y_f32 = t.y_f32; a.ssm_state = ssm_state;
-    if (fuse_dt) {
-      a.dtlow_q = dbc_q; a.lddl = NX; a.W_dt = qw->W_dt; a.R = R; a.m_dt = sc->m_dt; a.dt_out = dt_q;
+    if (fuse_dt) {  // decode writes the dt codes only when they are asked for as a tap
+      a.dtlow_q = dbc_q; a.lddl = NX; a.W_dt = qw->W_dt; a.R = R; a.m_dt = sc->m_dt;
+      a.dt_out = (decode && !t.dt_q) ? nullptr : dt_q;
     }
     if (decode) {
       QUAMBA_TRY(launch_scan_step(a, st));

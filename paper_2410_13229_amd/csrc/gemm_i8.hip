@@ -437,6 +437,68 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG, OCC) void gemm_i8_dma_kernel(c
   }
 }
 
+// ------------------------------------------------------------------------------------------
+// Few-row kernel (generation with a handful of sequences: M <= 8).  A matrix tile would be
+// nearly empty, and the job is to stream W once: a workgroup owns four adjacent output columns,
+// its 256 threads split K in 16-byte pieces (one wave-level load covers 1 KB of a weight row),
+// multiply with v_dot4_i32_i8 against the activation rows held in LDS, and reduce across lanes
+// and waves.  No K split over the grid, so no second kernel.
+// ------------------------------------------------------------------------------------------
+template <int MB>
+__global__ __launch_bounds__(256) void gemv_i8_kernel(const int8_t *__restrict__ A, int lda,
+                                                      const int8_t *__restrict__ Wt, int ldw, int M, int N,
+                                                      int K, GemmEpilogue epi) {
+  extern __shared__ __attribute__((aligned(16))) int8_t sA[];  // [MB][K], rows past M zero
+  __shared__ int red[4][MB * 4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n0 = blockIdx.x * 4;
+  const int nchunks = K / 16;
+  for (int c = tid; c < MB * nchunks; c += 256) {
+    const int m = c / nchunks, ch = c % nchunks;
+    v4i v = {0, 0, 0, 0};
+    if (m < M) v = *reinterpret_cast<const v4i *>(A + (size_t)m * lda + ch * 16);
+    *reinterpret_cast<v4i *>(sA + (size_t)m * K + ch * 16) = v;
+  }
+  __syncthreads();
+  int acc[MB][4];
+#pragma unroll
+  for (int m = 0; m < MB; ++m)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[m][j] = 0;
+  for (int ch = tid; ch < nchunks; ch += 256) {
+    v4i w[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int n = min(n0 + j, N - 1);  // N is a multiple of 4: the clamp never acts, it only bounds the address
+      w[j] = *reinterpret_cast<const v4i *>(Wt + (size_t)n * ldw + ch * 16);
+    }
+#pragma unroll
+    for (int m = 0; m < MB; ++m) {
+      const v4i a = *reinterpret_cast<const v4i *>(sA + (size_t)m * K + ch * 16);
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[m][j] = __builtin_amdgcn_sdot4(a[e], w[j][e], acc[m][j], false);
+    }
+  }
+#pragma unroll
+  for (int m = 0; m < MB; ++m)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      int v = acc[m][j];
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+      if (lane == 0) red[wave][m * 4 + j] = v;
+    }
+  __syncthreads();
+  if (tid < M) {
+    int a[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) a[j] = red[0][tid * 4 + j] + red[1][tid * 4 + j] + red[2][tid * 4 + j] + red[3][tid * 4 + j];
+    emit4(epi, tid, n0, N, a);
+  }
+}
+
 // Sum of the split-K partials + epilogue; one thread per group of four columns.
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const int32_t *__restrict__ partial, int splits,
                                                             int M, int N, GemmEpilogue epi) {
@@ -512,6 +574,17 @@ int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, i
   //   5 = dma 64x64, 128-byte slices, ring of 3 (best weight-streaming rate for decode-sized M)
   //   6 = dma 128x160, two K groups of 4 waves (fills the SIMDs when there is only about one
   //       128x160 tile per CU)
+  if (M <= 8 && g_gemm_variant < 0 && (size_t)8 * K <= 64 * 1024) {
+    const size_t lds = (size_t)(M <= 1 ? 1 : (M <= 4 ? 4 : 8)) * K;
+    if (M <= 1)
+      hipLaunchKernelGGL(gemv_i8_kernel<1>, dim3(N / 4), dim3(256), lds, st, A, lda, Wt, ldw, M, N, K, epi);
+    else if (M <= 4)
+      hipLaunchKernelGGL(gemv_i8_kernel<4>, dim3(N / 4), dim3(256), lds, st, A, lda, Wt, ldw, M, N, K, epi);
+    else
+      hipLaunchKernelGGL(gemv_i8_kernel<8>, dim3(N / 4), dim3(256), lds, st, A, lda, Wt, ldw, M, N, K, epi);
+    QUAMBA_LAUNCH_CHECK();
+    return QUAMBA_OK;
+  }
   int kind;
   const long tiles_256 = (long)((M + 255) / 256) * ((N + 319) / 320);
   const long tiles_128 = (long)((M + 127) / 128) * ((N + 159) / 160);

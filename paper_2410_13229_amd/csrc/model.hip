@@ -95,8 +95,12 @@ __global__ __launch_bounds__(256) void final_norm_kernel(const __half *__restric
 // are zero.
 __device__ __forceinline__ int swz128(int row, int chunk) { return row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4); }
 
+// With `pmax` / `pidx` ([gridDim.x, Bt]) every workgroup also leaves, per token, the largest of its 64
+// logits and that entry's index (lowest index among equals), so that the selection does not have to
+// read the logits again.
 __global__ __launch_bounds__(256) void head_kernel(const __half *__restrict__ y, const __half *__restrict__ E, int Bt,
-                                                   int V, int K, float *__restrict__ logits) {
+                                                   int V, int K, float *__restrict__ logits,
+                                                   float *__restrict__ pmax, int32_t *__restrict__ pidx) {
   constexpr int BKB = 128;  // bytes of K per slice
   __shared__ __attribute__((aligned(16))) int8_t lds[2][128 * BKB];  // rows 0..63 tokens, 64..127 vocabulary
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -155,18 +159,94 @@ __global__ __launch_bounds__(256) void head_kernel(const __half *__restrict__ y,
   }
   // register r: vocabulary entry v0 + wn*32 + 8 (r/4) + 4 (lane/32) + r%4, token b0 + wm*32 + lane%32
   const int b = b0 + wm * 32 + (lane & 31);
-  if (b >= Bt) return;
+  if (logits && b < Bt) {
 #pragma unroll
-  for (int g = 0; g < 4; ++g) {
-    const int v = v0 + wn * 32 + 8 * g + 4 * (lane >> 5);
-    float *dst = logits + (size_t)b * V + v;
-    if ((V & 3) == 0) {
-      if (v < V) *reinterpret_cast<float4 *>(dst) = make_float4(acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]);
-    } else {
+    for (int g = 0; g < 4; ++g) {
+      const int v = v0 + wn * 32 + 8 * g + 4 * (lane >> 5);
+      float *dst = logits + (size_t)b * V + v;
+      if ((V & 3) == 0) {
+        if (v < V) *reinterpret_cast<float4 *>(dst) = make_float4(acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]);
+      } else {
 #pragma unroll
-      for (int e = 0; e < 4; ++e)
-        if (v + e < V) dst[e] = acc[4 * g + e];
+        for (int e = 0; e < 4; ++e)
+          if (v + e < V) dst[e] = acc[4 * g + e];
+      }
     }
+  }
+  if (pmax) {
+    // per lane over its 16 entries (ascending index), then the other half-wave, then the other wn wave
+    float best = -INFINITY;
+    int bi = 0x7fffffff;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int v = v0 + wn * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+      if (v < V && (acc[r] > best || (acc[r] == best && v < bi))) {
+        best = acc[r];
+        bi = v;
+      }
+    }
+    const float ob = __shfl_xor(best, 32);
+    const int oi = __shfl_xor(bi, 32);
+    if (ob > best || (ob == best && oi < bi)) {
+      best = ob;
+      bi = oi;
+    }
+    __shared__ float sbest[2][64];
+    __shared__ int sidx[2][64];
+    if (lane < 32) {
+      sbest[wn][wm * 32 + lane] = best;
+      sidx[wn][wm * 32 + lane] = bi;
+    }
+    __syncthreads();
+    if (tid < 64 && b0 + tid < Bt) {
+      float x = sbest[0][tid];
+      int xi = sidx[0][tid];
+      if (sbest[1][tid] > x || (sbest[1][tid] == x && sidx[1][tid] < xi)) {
+        x = sbest[1][tid];
+        xi = sidx[1][tid];
+      }
+      pmax[(size_t)blockIdx.x * Bt + b0 + tid] = x;
+      pidx[(size_t)blockIdx.x * Bt + b0 + tid] = xi;
+    }
+  }
+}
+
+// Selection from the head's per-workgroup partials [P, Bt]: one workgroup per token.
+__global__ __launch_bounds__(256) void argmax_partials_kernel(const float *__restrict__ pmax,
+                                                              const int32_t *__restrict__ pidx, int P, int Bt,
+                                                              int32_t *__restrict__ next, int32_t *__restrict__ log,
+                                                              const int32_t *__restrict__ step) {
+  const int b = blockIdx.x;
+  float best = -INFINITY;
+  int bi = 0x7fffffff;
+  for (int p = threadIdx.x; p < P; p += 256) {
+    const float x = pmax[(size_t)p * Bt + b];
+    const int xi = pidx[(size_t)p * Bt + b];
+    if (x > best || (x == best && xi < bi)) {
+      best = x;
+      bi = xi;
+    }
+  }
+  __shared__ float sb[256];
+  __shared__ int si[256];
+  sb[threadIdx.x] = best;
+  si[threadIdx.x] = bi;
+  __syncthreads();
+  for (int off = 128; off > 0; off >>= 1) {
+    if (threadIdx.x < off) {
+      const float ob = sb[threadIdx.x + off];
+      const int oi = si[threadIdx.x + off];
+      if (ob > sb[threadIdx.x] || (ob == sb[threadIdx.x] && oi < si[threadIdx.x])) {
+        sb[threadIdx.x] = ob;
+        si[threadIdx.x] = oi;
+      }
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    const int r = si[0] == 0x7fffffff ? 0 : si[0];  // a row of NaNs selects token 0
+    next[b] = r;
+    if (log) log[(size_t)(*step) * Bt + b] = r;
   }
 }
 
@@ -220,7 +300,7 @@ __global__ void bump_kernel(int32_t *step) { *step += 1; }
 
 // ------------------------------------------------------------------ host side
 struct Carve {
-  size_t res, out, u_q, y, logits, cur, step, mixer, mixer_bytes, total;
+  size_t res, out, u_q, y, pmax, pidx, cur, step, mixer, mixer_bytes, total;
 };
 
 Carve carve(const quamba_model *m, int Bt, int L) {
@@ -236,7 +316,8 @@ Carve carve(const quamba_model *m, int Bt, int L) {
   c.out = take(M * Dm * sizeof(__half));
   c.u_q = take(M * Dm);
   c.y = take((size_t)Bt * Dm * sizeof(__half));
-  c.logits = take((size_t)Bt * m->vocab * sizeof(float));
+  c.pmax = take((size_t)((m->vocab + 63) / 64) * Bt * sizeof(float));
+  c.pidx = take((size_t)((m->vocab + 63) / 64) * Bt * sizeof(int32_t));
   c.cur = take((size_t)Bt * sizeof(int32_t));
   c.step = take(sizeof(int32_t));
   c.mixer_bytes = mixer_workspace_bytes(&m->dims, Bt, L);
@@ -270,7 +351,9 @@ int run_model(const quamba_model *m, const int32_t *tokens, int Bt, int L, bool 
   __half *out = reinterpret_cast<__half *>(base + c.out);
   int8_t *u_q = reinterpret_cast<int8_t *>(base + c.u_q);
   __half *y = reinterpret_cast<__half *>(base + c.y);
-  float *logits = logits_out ? logits_out : reinterpret_cast<float *>(base + c.logits);
+  float *logits = logits_out;  // the logits are written only when the caller wants them
+  float *pmax = next ? reinterpret_cast<float *>(base + c.pmax) : nullptr;
+  int32_t *pidx = next ? reinterpret_cast<int32_t *>(base + c.pidx) : nullptr;
   int32_t *step = reinterpret_cast<int32_t *>(base + c.step);
 
   const size_t pieces = (size_t)M * (Dm / 8);
@@ -291,11 +374,13 @@ int run_model(const quamba_model *m, const int32_t *tokens, int Bt, int L, bool 
   hipLaunchKernelGGL(final_norm_kernel, dim3(Bt), dim3(256), 0, st, out, res,
                      reinterpret_cast<const __half *>(m->norm_f), m->eps, L, Dm, y);
   QUAMBA_LAUNCH_CHECK();
-  hipLaunchKernelGGL(head_kernel, dim3((m->vocab + 63) / 64, (Bt + 63) / 64), dim3(256), 0, st, y,
-                     reinterpret_cast<const __half *>(m->embedding), Bt, m->vocab, Dm, logits);
+  if (!logits && !next) return QUAMBA_OK;
+  const int P = (m->vocab + 63) / 64;
+  hipLaunchKernelGGL(head_kernel, dim3(P, (Bt + 63) / 64), dim3(256), 0, st, y,
+                     reinterpret_cast<const __half *>(m->embedding), Bt, m->vocab, Dm, logits, pmax, pidx);
   QUAMBA_LAUNCH_CHECK();
   if (next) {
-    hipLaunchKernelGGL(argmax_kernel, dim3(Bt), dim3(256), 0, st, logits, m->vocab, Bt, next, log, step);
+    hipLaunchKernelGGL(argmax_partials_kernel, dim3(Bt), dim3(256), 0, st, pmax, pidx, P, Bt, next, log, step);
     QUAMBA_LAUNCH_CHECK();
   }
   return QUAMBA_OK;
@@ -365,7 +450,7 @@ int quamba_lm_head(const quamba_half *y, const quamba_half *embedding, int Bt, i
     return fail(QUAMBA_EINVAL, "lm_head: buffers must be 16-byte aligned");
   hipLaunchKernelGGL(head_kernel, dim3((vocab + 63) / 64, (Bt + 63) / 64), dim3(256), 0, as_stream(stream),
                      reinterpret_cast<const __half *>(y), reinterpret_cast<const __half *>(embedding), Bt, vocab, Dm,
-                     logits);
+                     logits, static_cast<float *>(nullptr), static_cast<int32_t *>(nullptr));
   QUAMBA_LAUNCH_CHECK();
   return QUAMBA_OK;
 }

@@ -290,7 +290,10 @@ __global__ __launch_bounds__(256) void scan_carry_kernel(Dev p, float *__restric
 }
 
 // ---------------------------------------------------------------- decode: one step
-// 4 lanes per channel, each owning 4 of the 16 states as one float4.
+// 4 lanes per channel, each owning 4 of the 16 states as one float4.  FUSE_DT: the step also forms
+// its own dt code, dt_q = q(W_dt[d, :] . dt_low[b, :], m_dt) (dt_proj, K = dt_rank): the four lanes of
+// a channel share the 16-byte pieces of the two rows and add their parts with two shuffles.
+template <bool FUSE_DT>
 __global__ __launch_bounds__(256) void scan_step_kernel(Dev p, float *__restrict__ ssm_state, int Bt) {
   const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;  // (b, d, quad)
   const size_t total = (size_t)Bt * p.Di * 4;
@@ -306,7 +309,26 @@ __global__ __launch_bounds__(256) void scan_step_kernel(Dev p, float *__restrict
   const unsigned bw = *reinterpret_cast<const unsigned *>(p.B_q + (size_t)b * p.ldbc + 4 * q);
   const unsigned cw = *reinterpret_cast<const unsigned *>(p.C_q + (size_t)b * p.ldbc + 4 * q);
   const float xv = p.s_x * static_cast<float>(p.x_q[(size_t)b * p.Di + d]);
-  const float dt = softplus_f(p.s_dt * static_cast<float>(p.dt_q[(size_t)b * p.Di + d]) + p.dt_bias[d]);
+  int dtq;
+  if (FUSE_DT) {
+    const int8_t *wrow = p.W_dt + (size_t)d * p.R;
+    const int8_t *arow = p.dtlow_q + (size_t)b * p.lddl;
+    int acc = 0;
+    for (int kc = 16 * q; kc < p.R; kc += 64) {
+      const v4i w = *reinterpret_cast<const v4i *>(wrow + kc);
+      const v4i a = *reinterpret_cast<const v4i *>(arow + kc);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc = __builtin_amdgcn_sdot4(a[e], w[e], acc, false);
+    }
+    acc += __shfl_xor(acc, 1);
+    acc += __shfl_xor(acc, 2);
+    const float v = __builtin_amdgcn_fmed3f(static_cast<float>(acc) * p.m_dt, -128.f, 127.f);
+    dtq = static_cast<int>(__builtin_rintf(v));
+    if (live && q == 0 && p.dt_out) p.dt_out[(size_t)b * p.Di + d] = static_cast<int8_t>(dtq);
+  } else {
+    dtq = p.dt_q[(size_t)b * p.Di + d];
+  }
+  const float dt = softplus_f(p.s_dt * static_cast<float>(dtq) + p.dt_bias[d]);
   const float zv = p.s_z * static_cast<float>(p.z_q[(size_t)b * p.ldz + d]);
   const float u = dt * xv;
   float y = 0.f;
@@ -338,7 +360,7 @@ Dev make_dev(const ScanArgs &a) {
   p.s_x = a.s_x; p.s_dt = a.s_dt; p.s_z = a.s_z; p.s_B = a.s_B; p.s_C = a.s_C; p.s_A = a.s_A; p.s_D = a.s_D;
   p.L = a.L; p.Di = a.Di; p.g16 = a.g16; p.y_f32 = a.y_f32;
   p.dtlow_q = a.dtlow_q; p.W_dt = a.W_dt; p.lddl = a.lddl; p.R = a.R; p.m_dt = a.m_dt; p.dt_out = a.dt_out;
-  if (a.dtlow_q) p.dt_q = a.dt_out;
+  if (a.dtlow_q && a.dt_out) p.dt_q = a.dt_out;
   return p;
 }
 
@@ -412,8 +434,16 @@ int launch_scan_step(const ScanArgs &a, hipStream_t st) {
   Dev p = make_dev(a);
   p.L = 1;
   const size_t n = (size_t)a.Bt * a.Di * 4;
-  hipLaunchKernelGGL(scan_step_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, a.ssm_state,
-                     a.Bt);
+  if (a.dtlow_q) {
+    if (!a.W_dt || a.R < 16 || a.R % 16 || a.lddl % 16 || a.lddl < a.R || !aligned(a.dtlow_q, 16) || !aligned(a.W_dt, 16))
+      return fail(QUAMBA_EUNSUPPORTED, "scan_step: fused dt_proj needs dt_rank and lddl multiples of 16 and 16-byte "
+                                       "aligned dt_low and W_dt");
+    hipLaunchKernelGGL(scan_step_kernel<true>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, a.ssm_state,
+                       a.Bt);
+  } else {
+    hipLaunchKernelGGL(scan_step_kernel<false>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, a.ssm_state,
+                       a.Bt);
+  }
   QUAMBA_LAUNCH_CHECK();
   return QUAMBA_OK;
 }

@@ -85,7 +85,7 @@ def make_taps(cfg, M, names=None):
     return {n: empty((M, cols[TAP_SHAPES[n][0]]), TAP_SHAPES[n][1]) for n in names}
 
 
-def run_prefill(cfg, qw_d, sc, u, h0=None, want_state=True, taps=True, u_q=None):
+def run_prefill(cfg, qw_d, sc, u, h0=None, want_state=True, taps=True, u_q=None, tap_names=None):
     """Call quamba_mixer_prefill(_q); returns dict(out, h, conv_state, taps...) as numpy."""
     Bt, L = (u if u is not None else u_q).shape[:2]
     M = Bt * L
@@ -96,7 +96,7 @@ def run_prefill(cfg, qw_d, sc, u, h0=None, want_state=True, taps=True, u_q=None)
         ssm = dev(h0) if h0 is not None else torch.zeros((Bt, cfg.d_inner, cfg.d_state), dtype=torch.float32,
                                                          device=DEV)
     cs = empty((Bt, cfg.d_inner, cfg.d_conv - 1), torch.float16)
-    tp = make_taps(cfg, M) if taps else None
+    tp = make_taps(cfg, M, tap_names) if taps else None
     if u_q is None:
         Q.quamba_mixer_prefill(cfg, qw_d, sc, dev(u), Bt, L, out, ssm, cs, tp, ws)
     else:

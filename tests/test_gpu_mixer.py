@@ -57,7 +57,8 @@ def check_chain(cfg, qw, sc, u, r, h0=None, rows=None, chans=None, decode_state=
     assert np.array_equal(r["dbc_q"][rs, R + N:], O.requant_acc(acc[:, R + N:], sc["m_x_C"]))
     # S4 dt_proj
     acc = O.int_matmul(r["dbc_q"][rs, :R], qw["W_dt"])
-    assert np.array_equal(r["acc_dt"][rs], acc)
+    if "acc_dt" in r:  # absent when dt_proj ran inside the scan kernel (no raw sums to tap)
+        assert np.array_equal(r["acc_dt"][rs], acc)
     assert np.array_equal(r["dt_q"][rs], O.requant_acc(acc, sc["m_dt"]))
     # S5 scan + gate
     dbc3 = r["dbc_q"].reshape(Bt, L, R + 2 * N)
@@ -107,6 +108,12 @@ def test_prefill_tiny(Bt, L, dm, di, rk):
     end_to_end(r, ref, cfg.name)
     assert np.array_equal(r["conv_state"].view(np.uint16), ref["conv_state"].view(np.uint16))
     assert rel_err(r["h"], ref["h"]) <= 2e-2
+    # without the raw dt_proj sums among the taps the scan computes dt_q itself: same chain, same output
+    from gpu_util import TAP_SHAPES
+    r2 = run_prefill(cfg, qweights_to_dev(qw), sc, u, h0=h0, tap_names=[n for n in TAP_SHAPES if n != "acc_dt"])
+    check_chain(cfg, qw, sc, u, r2, h0=h0)
+    assert np.array_equal(r2["dt_q"], r["dt_q"])
+    assert np.array_equal(r2["out"].view(np.uint16), r["out"].view(np.uint16))
 
 
 def test_prefill_q_variant_and_null_state():
@@ -174,13 +181,15 @@ def test_prefill_c3_layer_shape_sampled():
     print("c3-layer", st)
 
 
-def _decode_steps(cfg, Bt, steps, qw, sc, check_every=1):
+def _decode_steps(cfg, Bt, steps, qw, sc, check_every=1, fused_dt=False):
     qd = qweights_to_dev(qw)
     ssm_np, cs_np = W.make_decode_state(cfg, batch=Bt)
     ssm, cs = dev(ssm_np), dev(cs_np)
     ws = workspace(Q.quamba_workspace_bytes(cfg, Bt, 1))
     out = empty((Bt, cfg.d_model), torch.float16)
-    tp = make_taps(cfg, Bt)
+    from gpu_util import TAP_SHAPES
+    # without the raw dt_proj sums among the taps the scan step computes dt_q itself
+    tp = make_taps(cfg, Bt, [n for n in TAP_SHAPES if n != "acc_dt"] if fused_dt else None)
     o_ssm, o_cs = ssm_np, cs_np
     for s in range(steps):
         u = W.make_hidden(cfg, batch=Bt, seqlen=1, stream=100 + s)
@@ -201,16 +210,26 @@ def _decode_steps(cfg, Bt, steps, qw, sc, check_every=1):
         assert np.array_equal(new_cs.view(np.uint16), o_cs.view(np.uint16))
 
 
-def test_decode_tiny():
+@pytest.mark.parametrize("fused_dt", [False, True])
+def test_decode_tiny(fused_dt):
     cfg = W.tiny_config(name="td", d_model=64, d_inner=128, dt_rank=16, batch=3, seqlen=1, config_id=96)
     w, qw, sc = oracle_setup(cfg, randomize_bias=True, gain=4.0)
-    _decode_steps(cfg, 3, 4, qw, sc)
+    _decode_steps(cfg, 3, 4, qw, sc, fused_dt=fused_dt)
 
 
-def test_decode_c2_shape():
+@pytest.mark.parametrize("fused_dt", [False, True])
+def test_decode_c2_shape(fused_dt):
     cfg = W.CONFIGS["c2"]
     w, qw, sc = oracle_setup(cfg)
-    _decode_steps(cfg, cfg.batch, 3, qw, sc)
+    _decode_steps(cfg, cfg.batch, 3, qw, sc, fused_dt=fused_dt)
+
+
+@pytest.mark.parametrize("Bt", [1, 2, 5, 8])
+def test_decode_few_sequences_2p8b_width(Bt):
+    """Generation with a handful of sequences takes the streaming (no matrix tile) projections."""
+    cfg = W.CONFIGS["c2"]
+    w, qw, sc = oracle_setup(cfg)
+    _decode_steps(cfg, Bt, 2, qw, sc, fused_dt=(Bt % 2 == 1))
 
 
 def test_prefill_then_decode_handoff():
