@@ -69,7 +69,8 @@ Plan make_plan(const quamba_dims *d, int Bt, int L) {
   return p;
 }
 
-int g_fuse_dt = 1;  // tuning hook
+int g_fuse_dt = 1;      // tuning hook
+int g_fuse_decode = 1;  // tuning hook
 
 int check_q(const quamba_qweights *qw, const quamba_scales *sc) {
   if (!qw || !sc) return fail(QUAMBA_EINVAL, "qweights or scales is NULL");
@@ -91,12 +92,16 @@ int tap_copy(void *dst, const void *src, size_t bytes, hipStream_t st) {
 }
 
 // Steps shared by prefill (L >= 1, fresh conv history) and decode (L == 1, carried state).
+// `norm` (generation with at most 8 sequences only): the block input is not given but formed inside
+// the first kernel from the previous block's output and the residual stream.
 int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scales *sc, const __half *u,
               const int8_t *u_q_in, int Bt, int L, bool decode, __half *out, float *ssm_state,
-              __half *conv_state, const quamba_taps *taps, void *ws, size_t ws_bytes, hipStream_t st) {
+              __half *conv_state, const quamba_taps *taps, void *ws, size_t ws_bytes, hipStream_t st,
+              const NormIn *norm = nullptr) {
   QUAMBA_TRY(check_dims(d));
   QUAMBA_TRY(check_q(qw, sc));
-  if ((!u && !u_q_in) || !out) return fail(QUAMBA_EINVAL, "input or output pointer is NULL");
+  if ((!u && !u_q_in && !norm) || !out) return fail(QUAMBA_EINVAL, "input or output pointer is NULL");
+  if (norm && !(decode && Bt <= 8)) return fail(QUAMBA_EINVAL, "fused block input needs decode with batch <= 8");
   if (Bt < 1 || L < 1) return fail(QUAMBA_EINVAL, "batch=%d, L=%d must be >= 1", Bt, L);
   if (decode && (!ssm_state || !conv_state)) return fail(QUAMBA_EINVAL, "decode needs ssm_state and conv_state");
   const Plan p = make_plan(d, Bt, L);
@@ -117,27 +122,44 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
   const quamba_taps none{};
   const quamba_taps &t = taps ? *taps : none;
 
+  // Generation with a handful of sequences: [norm +] in_proj + conv step in one streaming kernel.
+  const bool few = decode && M <= 8 && Dm <= 8192 && g_fuse_decode;
   // quantize the block input (Eq. 2)
   const int8_t *uq = u_q_in;
-  if (!uq) {
+  if (!uq && !norm) {
     QUAMBA_TRY(launch_quantize_f16(u, u_q, (size_t)M * Dm, sc->inv_s_u, st));
     uq = u_q;
   }
-  QUAMBA_TRY(tap_copy(t.u_q, uq, (size_t)M * Dm, st));
+  if (uq) QUAMBA_TRY(tap_copy(t.u_q, uq, (size_t)M * Dm, st));
 
-  // in_proj: columns [0, Di) -> x_pre, [Di, 2Di) -> z
-  {
-    GemmEpilogue e{xz_q, nullptr, t.acc_in, 2 * Di, Di, 2 * Di, sc->m_in_x, sc->m_in_z, sc->m_in_z};
-    QUAMBA_TRY(launch_gemm_i8(uq, Dm, qw->W_in, Dm, M, 2 * Di, Dm, e, base + p.gemm, p.gemm_bytes, st));
+  if (few) {
+    DecodeInArgs a{};
+    if (norm) {
+      a.out_prev = norm->out_prev; a.res_in = norm->res_in; a.res_out = norm->res_out; a.norm_w = norm->norm_w;
+      a.eps = norm->eps; a.inv_s_u = sc->inv_s_u;
+    } else {
+      a.u_q = uq;
+    }
+    a.W_in = qw->W_in; a.Dm = Dm; a.Di = Di; a.M = M; a.m_in_x = sc->m_in_x; a.m_in_z = sc->m_in_z;
+    a.conv_w = qw->conv_w; a.conv_b = qw->conv_b; a.s_cw = sc->s_cw; a.s_xpre = sc->s_xpre; a.inv_s_x = sc->inv_s_x;
+    a.x_q = x_q; a.xz_q = xz_q; a.acc_in = t.acc_in; a.conv_state = conv_state;
+    QUAMBA_TRY(launch_decode_in(a, st));
     QUAMBA_TRY(tap_copy(t.xz_q, xz_q, (size_t)M * 2 * Di, st));
-  }
-  // causal conv + SiLU + requantization with the percentile scale of x
-  if (decode) {
-    QUAMBA_TRY(launch_conv_step(xz_q, 2 * Di, qw->conv_w, qw->conv_b, Bt, Di, sc->s_cw, sc->s_xpre,
-                                sc->inv_s_x, x_q, conv_state, st));
   } else {
-    QUAMBA_TRY(launch_conv_prefill(xz_q, 2 * Di, qw->conv_w, qw->conv_b, Bt, L, Di, sc->m_conv, sc->inv_s_x,
-                                   sc->s_xpre, x_q, conv_state, st));
+    // in_proj: columns [0, Di) -> x_pre, [Di, 2Di) -> z
+    {
+      GemmEpilogue e{xz_q, nullptr, t.acc_in, 2 * Di, Di, 2 * Di, sc->m_in_x, sc->m_in_z, sc->m_in_z};
+      QUAMBA_TRY(launch_gemm_i8(uq, Dm, qw->W_in, Dm, M, 2 * Di, Dm, e, base + p.gemm, p.gemm_bytes, st));
+      QUAMBA_TRY(tap_copy(t.xz_q, xz_q, (size_t)M * 2 * Di, st));
+    }
+    // causal conv + SiLU + requantization with the percentile scale of x
+    if (decode) {
+      QUAMBA_TRY(launch_conv_step(xz_q, 2 * Di, qw->conv_w, qw->conv_b, Bt, Di, sc->s_cw, sc->s_xpre,
+                                  sc->inv_s_x, x_q, conv_state, st));
+    } else {
+      QUAMBA_TRY(launch_conv_prefill(xz_q, 2 * Di, qw->conv_w, qw->conv_b, Bt, L, Di, sc->m_conv, sc->inv_s_x,
+                                     sc->s_xpre, x_q, conv_state, st));
+    }
   }
   QUAMBA_TRY(tap_copy(t.x_q, x_q, (size_t)M * Di, st));
   // x_proj: columns dt_low | B | C, each with its own output scale
@@ -196,6 +218,15 @@ int mixer_run_q(const quamba_dims *d, const quamba_qweights *qw, const quamba_sc
                 hipStream_t st) {
   return run_mixer(d, qw, sc, nullptr, u_q, Bt, L, decode, out, ssm_state, conv_state, nullptr, ws, ws_bytes, st);
 }
+
+int mixer_decode_norm(const quamba_dims *d, const quamba_qweights *qw, const quamba_scales *sc, const NormIn &norm,
+                      int Bt, __half *out, float *ssm_state, __half *conv_state, void *ws, size_t ws_bytes,
+                      hipStream_t st) {
+  return run_mixer(d, qw, sc, nullptr, nullptr, Bt, 1, true, out, ssm_state, conv_state, nullptr, ws, ws_bytes, st,
+                   &norm);
+}
+
+bool mixer_decode_norm_available(const quamba_dims *d, int Bt) { return g_fuse_decode && Bt <= 8 && d->d_model <= 8192; }
 
 int check_model_dims(const quamba_dims *d) { return check_dims(d); }
 
@@ -421,3 +452,4 @@ int quamba_hadamard_quant(const quamba_half *g, int M, int n, float inv_s_y, int
 }  // extern "C"
 
 extern "C" void quamba_debug_set_fuse_dt(int v) { quamba::g_fuse_dt = v; }
+extern "C" void quamba_debug_set_fuse_decode(int v) { quamba::g_fuse_decode = v; }

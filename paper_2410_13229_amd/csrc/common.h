@@ -90,6 +90,28 @@ int launch_scan_step(const ScanArgs &a, hipStream_t st);
 int launch_hadamard_quant(const __half *g, int M, int n, float inv_s_y, int8_t *yH_q, float *yH_f32,
                           hipStream_t st);
 
+// generation with M <= 8 rows: [add + RMSNorm + quant] -> in_proj -> conv step in one kernel.
+// Either u_q (already quantized input [M, Dm]) or out_prev / res_in / res_out / norm_w (res_out must
+// not alias res_in: every workgroup reads res_in while workgroup 0 writes res_out).
+struct DecodeInArgs {
+  const __half *out_prev, *res_in;
+  __half *res_out;
+  const __half *norm_w;
+  float eps, inv_s_u;
+  const int8_t *u_q;
+  const int8_t *W_in;
+  int Dm, Di, M;
+  float m_in_x, m_in_z;
+  const int8_t *conv_w;
+  const float *conv_b;
+  float s_cw, s_xpre, inv_s_x;
+  int8_t *x_q;        // [M, Di]
+  int8_t *xz_q;       // [M, 2 Di]: x_pre codes | z codes
+  int32_t *acc_in;    // [M, 2 Di] raw sums, may be NULL
+  __half *conv_state; // [M, Di, 3], in/out
+};
+int launch_decode_in(const DecodeInArgs &a, hipStream_t st);
+
 // one quantized mixer on already quantized input (prefill: fresh conv history; decode: L == 1 on
 // carried states), its workspace size, and the dimension check of the entry points
 size_t mixer_workspace_bytes(const quamba_dims *d, int Bt, int L);
@@ -97,5 +119,18 @@ int mixer_run_q(const quamba_dims *d, const quamba_qweights *qw, const quamba_sc
                 int L, bool decode, __half *out, float *ssm_state, __half *conv_state, void *ws, size_t ws_bytes,
                 hipStream_t st);
 int check_model_dims(const quamba_dims *d);
+
+// generation with at most 8 sequences: the block's own residual add + RMSNorm + quantization runs
+// inside the mixer's first kernel.  res_out must not alias res_in.
+struct NormIn {
+  const __half *out_prev, *res_in;
+  __half *res_out;
+  const __half *norm_w;
+  float eps;
+};
+bool mixer_decode_norm_available(const quamba_dims *d, int Bt);
+int mixer_decode_norm(const quamba_dims *d, const quamba_qweights *qw, const quamba_scales *sc, const NormIn &norm,
+                      int Bt, __half *out, float *ssm_state, __half *conv_state, void *ws, size_t ws_bytes,
+                      hipStream_t st);
 
 }  // namespace quamba

@@ -3,6 +3,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
 
 #include <cstdint>
 
@@ -27,6 +28,46 @@ __device__ __forceinline__ unsigned pack_q8x4(float v0, float v1, float v2, floa
 __device__ __forceinline__ unsigned requant_pack4(const int (&a)[4], float m) {
   return pack_q8x4(static_cast<float>(a[0]) * m, static_cast<float>(a[1]) * m, static_cast<float>(a[2]) * m,
                    static_cast<float>(a[3]) * m);
+}
+
+// One generation step of the causal conv + SiLU + requantization (Section 4.3 "Fused causal
+// convolution") for four adjacent channels of one sequence: window = [state (3, fp16),
+// s_xpre * xpre_q] in fp32, weights s_cw * w_q, products and sums rounded one by one in tap order;
+// the window then shifts by one.  `xin`: the four new int8 codes; `cs`: 12 fp16 of state
+// (channel-major, oldest first), updated in place.  Returns the four int8 output codes.
+__device__ __forceinline__ unsigned conv_step4(unsigned xin, const int8_t *wq4, const float *bias4, __half *cs,
+                                               float s_cw, float s_xpre, float inv_s_x) {
+  const uint4 wv = *reinterpret_cast<const uint4 *>(wq4);
+  const unsigned wword[4] = {wv.x, wv.y, wv.z, wv.w};
+  const float4 bv = *reinterpret_cast<const float4 *>(bias4);
+  const float bb[4] = {bv.x, bv.y, bv.z, bv.w};
+  union {
+    uint2 u[3];
+    __half h[12];
+  } st;
+  st.u[0] = reinterpret_cast<const uint2 *>(cs)[0];
+  st.u[1] = reinterpret_cast<const uint2 *>(cs)[1];
+  st.u[2] = reinterpret_cast<const uint2 *>(cs)[2];
+  float sv[4];
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    const float xn = __fmul_rn(s_xpre, static_cast<float>(static_cast<int8_t>(xin >> (8 * c))));
+    const float win[4] = {__half2float(st.h[3 * c]), __half2float(st.h[3 * c + 1]), __half2float(st.h[3 * c + 2]), xn};
+    float v = bb[c];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const float wj = __fmul_rn(s_cw, static_cast<float>(static_cast<int8_t>(wword[c] >> (8 * j))));
+      v = __fadd_rn(v, __fmul_rn(wj, win[j]));
+    }
+    sv[c] = v / (1.f + __builtin_amdgcn_exp2f(-v * 1.44269504088896340736f)) * inv_s_x;
+    st.h[3 * c] = st.h[3 * c + 1];
+    st.h[3 * c + 1] = st.h[3 * c + 2];
+    st.h[3 * c + 2] = __float2half_rn(xn);
+  }
+  reinterpret_cast<uint2 *>(cs)[0] = st.u[0];
+  reinterpret_cast<uint2 *>(cs)[1] = st.u[1];
+  reinterpret_cast<uint2 *>(cs)[2] = st.u[2];
+  return pack_q8x4(sv[0], sv[1], sv[2], sv[3]);
 }
 
 }  // namespace quamba

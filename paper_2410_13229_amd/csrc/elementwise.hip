@@ -129,40 +129,8 @@ __global__ __launch_bounds__(256) void conv_step_kernel(const int8_t *__restrict
   const int b = static_cast<int>(idx / groups);
   const int d0 = static_cast<int>(idx % groups) * 4;
   const unsigned xin = *reinterpret_cast<const unsigned *>(xpre + (size_t)b * ldx + d0);
-  const uint4 wv = *reinterpret_cast<const uint4 *>(wq + (size_t)d0 * 4);
-  const unsigned wword[4] = {wv.x, wv.y, wv.z, wv.w};
-  const float4 bv = *reinterpret_cast<const float4 *>(bias + d0);
-  const float bb[4] = {bv.x, bv.y, bv.z, bv.w};
-  // state of 4 channels: 12 contiguous halves = 24 bytes
-  __half *cs = conv_state + ((size_t)b * Di + d0) * 3;
-  union {
-    uint2 u[3];
-    __half h[12];
-  } st;
-  st.u[0] = reinterpret_cast<const uint2 *>(cs)[0];
-  st.u[1] = reinterpret_cast<const uint2 *>(cs)[1];
-  st.u[2] = reinterpret_cast<const uint2 *>(cs)[2];
-  unsigned p = 0;
-#pragma unroll
-  for (int c = 0; c < 4; ++c) {
-    const float xn = __fmul_rn(s_xpre, static_cast<float>(static_cast<int8_t>(xin >> (8 * c))));
-    const float win[4] = {__half2float(st.h[3 * c]), __half2float(st.h[3 * c + 1]),
-                          __half2float(st.h[3 * c + 2]), xn};
-    float v = bb[c];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const float wj = __fmul_rn(s_cw, static_cast<float>(static_cast<int8_t>(wword[c] >> (8 * j))));
-      v = __fadd_rn(v, __fmul_rn(wj, win[j]));
-    }
-    p |= (static_cast<unsigned>(q8(silu_f(v) * inv_s_x)) & 0xffu) << (8 * c);
-    st.h[3 * c] = st.h[3 * c + 1];
-    st.h[3 * c + 1] = st.h[3 * c + 2];
-    st.h[3 * c + 2] = __float2half_rn(xn);
-  }
-  *reinterpret_cast<unsigned *>(xq + (size_t)b * Di + d0) = p;
-  reinterpret_cast<uint2 *>(cs)[0] = st.u[0];
-  reinterpret_cast<uint2 *>(cs)[1] = st.u[1];
-  reinterpret_cast<uint2 *>(cs)[2] = st.u[2];
+  *reinterpret_cast<unsigned *>(xq + (size_t)b * Di + d0) =
+      conv_step4(xin, wq + (size_t)d0 * 4, bias + d0, conv_state + ((size_t)b * Di + d0) * 3, s_cw, s_xpre, inv_s_x);
 }
 
 // ------------------------------------------------------------------ add + RMSNorm + quant

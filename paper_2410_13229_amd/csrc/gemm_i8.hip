@@ -453,6 +453,14 @@ __global__ __launch_bounds__(256) void gemv_i8_kernel(const int8_t *__restrict__
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n0 = blockIdx.x * 4;
   const int nchunks = K / 16;
+  // the first weight pieces are requested before the activations are staged: their latency
+  // overlaps the staging and its barrier
+  v4i w[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int n = min(n0 + j, N - 1);  // N is a multiple of 4: the clamp never acts, it only bounds the address
+    w[j] = *reinterpret_cast<const v4i *>(Wt + (size_t)n * ldw + min(tid, nchunks - 1) * 16);
+  }
   for (int c = tid; c < MB * nchunks; c += 256) {
     const int m = c / nchunks, ch = c % nchunks;
     v4i v = {0, 0, 0, 0};
@@ -466,11 +474,14 @@ __global__ __launch_bounds__(256) void gemv_i8_kernel(const int8_t *__restrict__
 #pragma unroll
     for (int j = 0; j < 4; ++j) acc[m][j] = 0;
   for (int ch = tid; ch < nchunks; ch += 256) {
-    v4i w[4];
+    v4i wn[4];
+    const bool more = ch + 256 < nchunks;
+    if (more) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int n = min(n0 + j, N - 1);  // N is a multiple of 4: the clamp never acts, it only bounds the address
-      w[j] = *reinterpret_cast<const v4i *>(Wt + (size_t)n * ldw + ch * 16);
+      for (int j = 0; j < 4; ++j) {
+        const int n = min(n0 + j, N - 1);
+        wn[j] = *reinterpret_cast<const v4i *>(Wt + (size_t)n * ldw + (ch + 256) * 16);
+      }
     }
 #pragma unroll
     for (int m = 0; m < MB; ++m) {
@@ -479,6 +490,10 @@ __global__ __launch_bounds__(256) void gemv_i8_kernel(const int8_t *__restrict__
       for (int j = 0; j < 4; ++j)
 #pragma unroll
         for (int e = 0; e < 4; ++e) acc[m][j] = __builtin_amdgcn_sdot4(a[e], w[j][e], acc[m][j], false);
+    }
+    if (more) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) w[j] = wn[j];
     }
   }
 #pragma unroll

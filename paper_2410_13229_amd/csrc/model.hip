@@ -300,7 +300,7 @@ __global__ void bump_kernel(int32_t *step) { *step += 1; }
 
 // ------------------------------------------------------------------ host side
 struct Carve {
-  size_t res, out, u_q, y, pmax, pidx, cur, step, mixer, mixer_bytes, total;
+  size_t res, res2, out, u_q, y, pmax, pidx, cur, step, mixer, mixer_bytes, total;
 };
 
 Carve carve(const quamba_model *m, int Bt, int L) {
@@ -313,6 +313,7 @@ Carve carve(const quamba_model *m, int Bt, int L) {
     return at;
   };
   c.res = take(M * Dm * sizeof(__half));
+  c.res2 = take(L == 1 ? M * Dm * sizeof(__half) : 0);  // second residual buffer of the fused generation path
   c.out = take(M * Dm * sizeof(__half));
   c.u_q = take(M * Dm);
   c.y = take((size_t)Bt * Dm * sizeof(__half));
@@ -361,14 +362,27 @@ int run_model(const quamba_model *m, const int32_t *tokens, int Bt, int L, bool 
                      reinterpret_cast<const __half *>(m->embedding), tokens, M,
                      Dm, m->vocab, res, out);
   QUAMBA_LAUNCH_CHECK();
+  // generation with at most 8 sequences: the add + norm + quantization runs inside each block's first
+  // kernel, which reads one residual buffer and writes the other
+  const bool fused = decode && mixer_decode_norm_available(&m->dims, Bt);
+  __half *res_other = reinterpret_cast<__half *>(base + c.res2);
   for (int l = 0; l < m->n_layers; ++l) {
     const quamba_layer &ly = m->layers[l];
-    int rc = launch_add_rmsnorm_quant(out, res, reinterpret_cast<const __half *>(ly.norm_w), m->eps, ly.s.inv_s_u,
-                                      u_q, M, Dm, st);
-    if (rc != QUAMBA_OK) return rc;
     float *ssm = ssm_states + (size_t)l * Bt * Di * N;
     __half *cs = conv_states + (size_t)l * Bt * Di * 3;
-    rc = mixer_run_q(&m->dims, &ly.q, &ly.s, u_q, Bt, L, decode, out, ssm, cs, base + c.mixer, c.mixer_bytes, st);
+    int rc;
+    if (fused) {
+      const NormIn norm{out, res, res_other, reinterpret_cast<const __half *>(ly.norm_w), m->eps};
+      rc = mixer_decode_norm(&m->dims, &ly.q, &ly.s, norm, Bt, out, ssm, cs, base + c.mixer, c.mixer_bytes, st);
+      __half *tmp = res;
+      res = res_other;
+      res_other = tmp;
+    } else {
+      rc = launch_add_rmsnorm_quant(out, res, reinterpret_cast<const __half *>(ly.norm_w), m->eps, ly.s.inv_s_u,
+                                    u_q, M, Dm, st);
+      if (rc != QUAMBA_OK) return rc;
+      rc = mixer_run_q(&m->dims, &ly.q, &ly.s, u_q, Bt, L, decode, out, ssm, cs, base + c.mixer, c.mixer_bytes, st);
+    }
     if (rc != QUAMBA_OK) return rc;
   }
   hipLaunchKernelGGL(final_norm_kernel, dim3(Bt), dim3(256), 0, st, out, res,
