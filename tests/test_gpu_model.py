@@ -172,6 +172,37 @@ def test_model_generate_eager_and_graph_agree_with_each_other_and_track_the_orac
         tok = toks_gpu[i]
 
 
+@pytest.mark.parametrize("Bt", [1, 3, 8])
+def test_few_sequence_generation_kernels_match_the_general_path(Bt):
+    """With at most 8 sequences a block's norm, in_proj and conv step run in one kernel; the general path
+    (separate kernels, matrix tiles) must give the same step up to the odd code that flips because the two
+    sum the squares of a row in a different order."""
+    nlayers, vocab = 2, 256
+    cfg, om, gm = _tiny_model(nlayers, 101, vocab, d_model=96, d_inner=192)
+    prompt = W.make_tokens(cfg, vocab, batch=Bt, seqlen=9)
+    wsp = workspace(Q.quamba_model_workspace_bytes(gm, Bt, 9))
+    wsd = workspace(Q.quamba_model_workspace_bytes(gm, Bt, 1))
+    res = []
+    try:
+        for fuse in (1, 0):
+            Q.lib().quamba_debug_set_fuse_decode(fuse)
+            ssm, cs = _states(cfg, nlayers, Bt)
+            nxt = empty((Bt,), torch.int32)
+            Q.quamba_model_prefill(gm, dev(prompt), Bt, 9, None, nxt, ssm, cs, wsp)
+            logits = empty((Bt, vocab), torch.float32)
+            steps = []
+            for _ in range(3):
+                Q.quamba_model_decode(gm, nxt, Bt, logits, nxt, ssm, cs, wsd)
+                steps.append((host(logits).copy(), host(ssm).copy(), host(cs).copy()))
+            res.append(steps)
+    finally:
+        Q.lib().quamba_debug_set_fuse_decode(1)
+    for (la, sa, ca), (lb, sb, cb) in zip(*res):
+        assert rel_err(la, lb) <= 2e-2
+        assert rel_err(sa, sb) <= 2e-2
+        assert (ca.view(np.uint16) != cb.view(np.uint16)).mean() <= 2e-3
+
+
 def test_model_rejects_bad_arguments():
     cfg, om, gm = _tiny_model(1, 100, 97)
     ws = workspace(Q.quamba_model_workspace_bytes(gm, 1, 4))
