@@ -608,7 +608,7 @@ int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, i
   else if (N <= 512)
     kind = k128 ? 5 : (k64 ? 3 : 0);
   else if (k128 && M >= 256 && N >= 640)
-    kind = tiles_256 >= 192 ? 4 : (tiles_128 <= 384 ? 6 : 2);
+    kind = tiles_256 >= 192 ? 4 : (tiles_128 < 192 ? 5 : (tiles_128 <= 384 ? 6 : 2));  // few big tiles: 64x64 ones
   else
     kind = 1;
   if (g_gemm_variant >= 0 && g_gemm_variant <= 6 &&
