@@ -255,6 +255,17 @@ int quamba_scan_step(const int8_t *x_q, const int8_t *dt_q, const int8_t *z_q, i
 int quamba_hadamard_quant(const quamba_half *g, int M, int n, float inv_s_y, int8_t *yH_q,
                           float *yH_f32, void *stream);
 
+/* Calibration of one block of a stack (Section 5.1: per-layer static scales; Section 4.3 for the
+ * norm between blocks).  The caller carries the UNQUANTIZED residual stream in fp32:
+ *   res [nb*Lc, d_model] in/out, out [nb*Lc, d_model] in/out (start: res = hidden, out = 0).
+ * The call forms res += out, u = RMSNorm(res) * norm_w (fp16 [d_model]), calibrates the block on u
+ * exactly as quamba_calibrate does on its calib_u, and leaves this block's unquantized output in
+ * out for the next call.  Same workspace size as quamba_calibrate; synchronises the stream. */
+int quamba_calibrate_block(const quamba_dims *dims, const quamba_fp_weights *w,
+                           const quamba_half *norm_w, float eps, float *res, float *out, int nb,
+                           int Lc, double x_percentile, quamba_qweights *out_q,
+                           quamba_scales *out_s /* host */, void *ws, size_t ws_bytes, void *stream);
+
 /* ---- Whole-model shell.  Section 5.2 reports time to first token (prefill), time per output
  * token (one generation step) and time to last token of the full language model; this is that
  * loop around the quantized blocks:

@@ -18,7 +18,7 @@ __all__ = [
     "quamba_gemm_workspace_bytes", "quamba_conv_silu_quant", "quamba_conv_step", "quamba_scan_workspace_bytes",
     "quamba_scan_prefill", "quamba_scan_prefill_dtproj", "quamba_scan_step", "quamba_hadamard_quant",
     "Layer", "Model", "make_model", "quamba_model_workspace_bytes", "quamba_model_prefill", "quamba_model_decode",
-    "quamba_model_generate", "quamba_embed", "quamba_final_norm", "quamba_lm_head", "quamba_argmax",
+    "quamba_model_generate", "quamba_calibrate_block", "quamba_embed", "quamba_final_norm", "quamba_lm_head", "quamba_argmax",
 ]
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -187,6 +187,9 @@ def lib():
                                              i, vp, vp, vp, vp, sz, vp]
     L.quamba_scan_step.argtypes = [vp, vp, vp, i, vp, vp, i, vp, vp, vp, P(Scales), i, i, vp, vp, vp, vp]
     L.quamba_hadamard_quant.argtypes = [vp, i, i, f, vp, vp, vp]
+    L.quamba_calibrate_block.argtypes = [P(Dims), P(FpWeights), vp, f, vp, vp, i, i, C.c_double, P(QWeights), P(Scales),
+                                         vp, sz, vp]
+    L.quamba_calibrate_block.restype = C.c_int
     L.quamba_model_workspace_bytes.restype = sz
     L.quamba_model_workspace_bytes.argtypes = [P(Model), i, i]
     L.quamba_model_prefill.argtypes = [P(Model), vp, i, i, vp, vp, vp, vp, vp, sz, vp]
@@ -368,3 +371,14 @@ def quamba_lm_head(y, embedding, Bt, vocab, Dm, logits, stream=None):
 
 def quamba_argmax(logits, Bt, vocab, next_token, stream=None):
     _check(lib().quamba_argmax(_ptr(logits), Bt, vocab, _ptr(next_token), _stream(stream)))
+
+
+def quamba_calibrate_block(dims, fp_weights, norm_w, eps, res, out, nb, Lc, x_percentile, out_q, ws, stream=None) -> Scales:
+    """One block of a stack: advances the fp32 residual stream (res, out) and returns the block's Scales."""
+    fw = _struct_of_ptrs(FpWeights, fp_weights)
+    oq = _struct_of_ptrs(QWeights, out_q)
+    sc = Scales()
+    _check(lib().quamba_calibrate_block(C.byref(_dims(dims)), C.byref(fw), _ptr(norm_w), float(eps), _ptr(res), _ptr(out),
+                                        nb, Lc, float(x_percentile), C.byref(oq), C.byref(sc), _ptr(ws), _nbytes(ws),
+                                        _stream(stream)))
+    return sc

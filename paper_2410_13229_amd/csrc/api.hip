@@ -10,7 +10,10 @@ namespace quamba {
 size_t calibrate_workspace_bytes(const quamba_dims *d, int nb, int Lc);
 int calibrate(const quamba_dims *d, const quamba_fp_weights *w, const __half *calib_u, int nb, int Lc,
               double x_percentile, quamba_qweights *oq, quamba_scales *os, void *ws, size_t ws_bytes,
-              hipStream_t st);
+              hipStream_t st, float *out_f32);
+int calibrate_block(const quamba_dims *d, const quamba_fp_weights *w, const __half *norm_w, float eps, float *res,
+                    float *out, int nb, int Lc, double x_percentile, quamba_qweights *oq, quamba_scales *os, void *ws,
+                    size_t ws_bytes, hipStream_t st);
 
 static thread_local char g_err[512] = "";
 
@@ -265,7 +268,27 @@ int quamba_calibrate(const quamba_dims *dims, const quamba_fp_weights *w, const 
   if (!aligned(ws, 256) || !aligned(w->W_out, 16))
     return fail(QUAMBA_EINVAL, "calibrate: workspace must be 256-byte aligned, W_out 16-byte");
   return calibrate(dims, w, reinterpret_cast<const __half *>(calib_u), nb, Lc, x_percentile, out_q, out_s, ws,
-                   ws_bytes, as_stream(stream));
+                   ws_bytes, as_stream(stream), nullptr);
+}
+
+int quamba_calibrate_block(const quamba_dims *dims, const quamba_fp_weights *w, const quamba_half *norm_w, float eps,
+                           float *res, float *out, int nb, int Lc, double x_percentile, quamba_qweights *out_q,
+                           quamba_scales *out_s, void *ws, size_t ws_bytes, void *stream) {
+  QUAMBA_TRY(check_dims(dims));
+  if (!w || !norm_w || !res || !out || !out_q || !out_s || !ws) return fail(QUAMBA_EINVAL, "calibrate: NULL pointer");
+  if (!w->W_in || !w->conv_w || !w->conv_b || !w->W_x || !w->W_dt || !w->dt_bias || !w->A_log || !w->D ||
+      !w->W_out)
+    return fail(QUAMBA_EINVAL, "calibrate: a master weight pointer is NULL");
+  if (!out_q->W_in || !out_q->conv_w || !out_q->W_x || !out_q->W_dt || !out_q->A || !out_q->D ||
+      !out_q->W_outH || !out_q->conv_b || !out_q->dt_bias)
+    return fail(QUAMBA_EINVAL, "calibrate: an output weight pointer is NULL");
+  if (nb < 1 || Lc < 1) return fail(QUAMBA_EINVAL, "calibrate: nb=%d Lc=%d", nb, Lc);
+  if (!(x_percentile > 0.0 && x_percentile <= 100.0))
+    return fail(QUAMBA_EINVAL, "calibrate: percentile %g outside (0, 100]", x_percentile);
+  if (!aligned(ws, 256) || !aligned(w->W_out, 16) || !aligned(res, 16) || !aligned(out, 16))
+    return fail(QUAMBA_EINVAL, "calibrate: workspace must be 256-byte aligned, W_out, res and out 16-byte");
+  return calibrate_block(dims, w, reinterpret_cast<const __half *>(norm_w), eps, res, out, nb, Lc, x_percentile, out_q,
+                         out_s, ws, ws_bytes, as_stream(stream));
 }
 
 int quamba_mixer_prefill(const quamba_dims *dims, const quamba_qweights *qw, const quamba_scales *sc,

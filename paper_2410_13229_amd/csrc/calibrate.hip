@@ -223,7 +223,50 @@ size_t calibrate_workspace_bytes(const quamba_dims *d, int nb, int Lc) { return 
 
 int calibrate(const quamba_dims *d, const quamba_fp_weights *w, const __half *calib_u, int nb, int Lc,
               double x_percentile, quamba_qweights *oq, quamba_scales *os, void *ws, size_t ws_bytes,
-              hipStream_t st) {
+              hipStream_t st, float *out_f32);
+
+namespace {
+// res[row] += out[row]; u[row] = res[row] / sqrt(mean(res[row]^2) + eps) * w   (fp32; one workgroup per row)
+__global__ __launch_bounds__(256) void add_rmsnorm_f32_kernel(float *__restrict__ res, const float *__restrict__ out,
+                                                              const __half *__restrict__ w, float eps, int Dm,
+                                                              float *__restrict__ u) {
+  const size_t row = blockIdx.x;
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < Dm; i += 256) {
+    const float r = res[row * Dm + i] + out[row * Dm + i];
+    res[row * Dm + i] = r;
+    ss += r * r;
+  }
+  __shared__ float part[4];
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off);
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  const float rinv = 1.f / sqrtf((part[0] + part[1] + part[2] + part[3]) / static_cast<float>(Dm) + eps);
+  for (int i = threadIdx.x; i < Dm; i += 256) u[row * Dm + i] = res[row * Dm + i] * rinv * __half2float(w[i]);
+}
+}  // namespace
+
+// One block of a stack (Section 5.1: every layer gets its own static scales): the block input is
+// the RMSNorm of the unquantized residual stream, which the call advances.
+int calibrate_block(const quamba_dims *d, const quamba_fp_weights *w, const __half *norm_w, float eps, float *res,
+                    float *out, int nb, int Lc, double x_percentile, quamba_qweights *oq, quamba_scales *os, void *ws,
+                    size_t ws_bytes, hipStream_t st) {
+  const CalPlan p = cal_plan(d, nb, Lc);
+  if (ws_bytes < p.total) return fail(QUAMBA_EWORKSPACE, "calibrate: workspace %zu < %zu", ws_bytes, p.total);
+  float *u32 = reinterpret_cast<float *>(static_cast<char *>(ws) + p.u32);
+  hipLaunchKernelGGL(add_rmsnorm_f32_kernel, dim3((unsigned)((size_t)nb * Lc)), dim3(256), 0, st, res, out, norm_w, eps,
+                     d->d_model, u32);
+  QUAMBA_LAUNCH_CHECK();
+  return calibrate(d, w, nullptr, nb, Lc, x_percentile, oq, os, ws, ws_bytes, st, out);
+}
+
+// calib_u == nullptr: the fp32 block input is already in the workspace's own input buffer
+// (calibrate_block puts it there).  out_f32 != nullptr: also receives the unquantized block output
+// g W_out^T, which feeds the next block of a stack.
+int calibrate(const quamba_dims *d, const quamba_fp_weights *w, const __half *calib_u, int nb, int Lc,
+              double x_percentile, quamba_qweights *oq, quamba_scales *os, void *ws, size_t ws_bytes,
+              hipStream_t st, float *out_f32) {
   const CalPlan p = cal_plan(d, nb, Lc);
   if (ws_bytes < p.total) return fail(QUAMBA_EWORKSPACE, "calibrate: workspace %zu < %zu", ws_bytes, p.total);
   const int Dm = d->d_model, Di = d->d_inner, N = d->d_state, R = d->dt_rank, NX = R + 2 * N;
@@ -238,7 +281,7 @@ int calibrate(const quamba_dims *d, const quamba_fp_weights *w, const __half *ca
   unsigned long long *hist = reinterpret_cast<unsigned long long *>(base + p.hist);
 
   hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(256), 0, st, slots, (size_t)32, 0u);
-  hipLaunchKernelGGL(half_to_float_kernel, dim3(nblk(M * Dm)), dim3(256), 0, st, calib_u, u32, M * Dm);
+  if (calib_u) hipLaunchKernelGGL(half_to_float_kernel, dim3(nblk(M * Dm)), dim3(256), 0, st, calib_u, u32, M * Dm);
   hipLaunchKernelGGL(neg_exp_kernel, dim3(nblk((size_t)Di * N)), dim3(256), 0, st, w->A_log, A, (size_t)Di * N);
   QUAMBA_LAUNCH_CHECK();
 
@@ -255,6 +298,7 @@ int calibrate(const quamba_dims *d, const quamba_fp_weights *w, const __half *ca
   QUAMBA_LAUNCH_CHECK();
   if ((rc = launch_hadamard_f32(g, (int)M, Di, gH, st))) return rc;      // y^H = H_n g
   if ((rc = launch_hadamard_f32(w->W_out, Dm, Di, woh, st))) return rc;  // rows of W_out^H
+  if (out_f32 && (rc = sgemm(g, Di, w->W_out, Di, out_f32, Dm, (int)M, Dm, Di, st))) return rc;
 
   // observers
   struct Obs { const float *p; size_t rows; int ld, c0, c1, slot; };

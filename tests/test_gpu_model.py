@@ -215,3 +215,39 @@ def test_model_rejects_bad_arguments():
     with pytest.raises(Q.QuambaError):
         Q.quamba_model_generate(gm, tok, 1, 3, empty((3, 1), torch.int32), ssm, cs, ws, use_graph=True, stream=0)
     assert Q.quamba_model_workspace_bytes(gm, 0, 4) == 0
+
+
+# ------------------------------------------------------------------ per-layer calibration of a stack
+def test_calibrate_block_chain_matches_oracle_stack_calibration():
+    nlayers = 3
+    cfg = W.tiny_config(name="gc", d_model=64, d_inner=128, dt_rank=16, batch=2, seqlen=12, config_id=102,
+                        n_outlier=1, outlier_gain=8.0)
+    ws_np = []
+    for l in range(nlayers):
+        w = W.make_weights(cfg, layer=l, randomize_bias=True)
+        for k in ("W_in", "conv_w", "W_x", "W_dt", "W_out"):
+            w[k] = w[k] * np.float32(4.0)
+        ws_np.append(w)
+    norm_w, _ = W.make_norm_weights(cfg, nlayers)
+    hidden = W.make_calibration(cfg)
+    nb, Lc = hidden.shape[:2]
+    ref = O.calibrate_stack(ws_np, norm_w, hidden)
+    res = dev(hidden.astype(np.float32).reshape(nb * Lc, -1))
+    out = torch.zeros_like(res)
+    wsb = workspace(Q.quamba_calibrate_workspace_bytes(cfg, nb, Lc))
+    for l in range(nlayers):
+        qw_ref, sc_ref = ref[l]
+        out_q = {k: torch.zeros(v.shape, dtype=torch.int8 if v.dtype == np.int8 else torch.float32, device="cuda:0")
+                 for k, v in qw_ref.items()}
+        sc = Q.scales_to_dict(Q.quamba_calibrate_block(cfg, {k: dev(v) for k, v in ws_np[l].items()}, dev(norm_w[l]),
+                                                       1e-5, res, out, nb, Lc, 99.999, out_q, wsb))
+        for k in Q.SCALE_FIELDS:
+            tol = 2e-3 if k in ("s_x", "inv_s_x", "m_x_dt", "m_x_B", "m_x_C") else 2e-4
+            assert abs(sc[k] - float(sc_ref[k])) <= tol * abs(float(sc_ref[k])), (l, k, sc[k], float(sc_ref[k]))
+        for k, v in qw_ref.items():
+            got = host(out_q[k])
+            if v.dtype == np.int8:
+                d = np.abs(got.astype(int) - v.astype(int))
+                assert d.max() <= 1 and (d != 0).mean() <= 1e-3, (l, k)
+            else:
+                assert np.array_equal(got, v), (l, k)
