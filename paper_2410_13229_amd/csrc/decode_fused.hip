@@ -46,27 +46,72 @@ __global__ __launch_bounds__(256) void decode_in_kernel(DecodeInArgs p) {
       *reinterpret_cast<v4i *>(sA + (size_t)m * Dm + ch * 16) = v;
     }
   } else {
+    // One sweep: the fp16 sums s = fp16(out + res) stay in registers (8 halves per 16-byte word) between
+    // the reduction and the scaling; a thread owns at most SW words per row (d_model <= 4096 with 2).
+    constexpr int SW = 2;
+    const bool one_sweep = groups <= SW * 256;
+    uint4 keep[MB][SW];
     float ss[MB];
 #pragma unroll
     for (int m = 0; m < MB; ++m) ss[m] = 0.f;
-    for (int g = tid; g < groups; g += 256) {
+    auto load_sum = [&](int m, int g) -> uint4 {
+      union {
+        uint4 u;
+        __half h[8];
+      } a, r;
+      a.u = *reinterpret_cast<const uint4 *>(p.out_prev + (size_t)m * Dm + (size_t)g * 8);
+      r.u = *reinterpret_cast<const uint4 *>(p.res_in + (size_t)m * Dm + (size_t)g * 8);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) r.h[e] = __float2half_rn(__half2float(a.h[e]) + __half2float(r.h[e]));
+      return r.u;
+    };
+#pragma unroll
+    for (int it = 0; it < (SW > 1 ? SW : 1); ++it) {
+      const int g = tid + it * 256;
 #pragma unroll
       for (int m = 0; m < MB; ++m) {
-        if (m < M) {
-          union {
-            uint4 u;
-            __half h[8];
-          } a, r;
-          a.u = *reinterpret_cast<const uint4 *>(p.out_prev + (size_t)m * Dm + (size_t)g * 8);
-          r.u = *reinterpret_cast<const uint4 *>(p.res_in + (size_t)m * Dm + (size_t)g * 8);
+        keep[m][it] = make_uint4(0u, 0u, 0u, 0u);
+        if (one_sweep && m < M && g < groups) keep[m][it] = load_sum(m, g);
+      }
+    }
+    if (one_sweep) {
 #pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            const __half s = __float2half_rn(__half2float(a.h[e]) + __half2float(r.h[e]));
-            r.h[e] = s;
-            const float f = __half2float(s);
-            ss[m] += f * f;
+      for (int it = 0; it < SW; ++it) {
+        const int g = tid + it * 256;
+#pragma unroll
+        for (int m = 0; m < MB; ++m) {
+          if (m < M && g < groups) {
+            union {
+              uint4 u;
+              __half h[8];
+            } r;
+            r.u = keep[m][it];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+              const float f = __half2float(r.h[e]);
+              ss[m] += f * f;
+            }
+            if (blockIdx.x == 0) *reinterpret_cast<uint4 *>(p.res_out + (size_t)m * Dm + (size_t)g * 8) = r.u;
           }
-          if (blockIdx.x == 0) *reinterpret_cast<uint4 *>(p.res_out + (size_t)m * Dm + (size_t)g * 8) = r.u;
+        }
+      }
+    } else {
+      for (int g = tid; g < groups; g += 256) {
+#pragma unroll
+        for (int m = 0; m < MB; ++m) {
+          if (m < M) {
+            union {
+              uint4 u;
+              __half h[8];
+            } r;
+            r.u = load_sum(m, g);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+              const float f = __half2float(r.h[e]);
+              ss[m] += f * f;
+            }
+            if (blockIdx.x == 0) *reinterpret_cast<uint4 *>(p.res_out + (size_t)m * Dm + (size_t)g * 8) = r.u;
+          }
         }
       }
     }
@@ -82,32 +127,41 @@ __global__ __launch_bounds__(256) void decode_in_kernel(DecodeInArgs p) {
 #pragma unroll
     for (int m = 0; m < MB; ++m)
       rinv[m] = 1.f / sqrtf((part[0][m] + part[1][m] + part[2][m] + part[3][m]) / static_cast<float>(Dm) + p.eps);
-    // second sweep over the same (cache-resident) rows: normalise, scale, quantize into LDS
-    for (int g = tid; g < groups; g += 256) {
+    // normalise, scale, quantize into LDS (rows past M: zero codes)
+    auto emit = [&](int m, int g, uint4 sum, const uint4 &wword) {
       union {
         uint4 u;
         __half h[8];
-      } wv;
-      wv.u = *reinterpret_cast<const uint4 *>(p.norm_w + (size_t)g * 8);
+      } r, wv;
+      r.u = sum;
+      wv.u = wword;
+      float v[8];
 #pragma unroll
-      for (int m = 0; m < MB; ++m) {
-        uint2 codes = make_uint2(0u, 0u);
-        if (m < M) {
-          union {
-            uint4 u;
-            __half h[8];
-          } a, r;
-          a.u = *reinterpret_cast<const uint4 *>(p.out_prev + (size_t)m * Dm + (size_t)g * 8);
-          r.u = *reinterpret_cast<const uint4 *>(p.res_in + (size_t)m * Dm + (size_t)g * 8);
-          float v[8];
+      for (int e = 0; e < 8; ++e) v[e] = __half2float(r.h[e]) * rinv[m] * __half2float(wv.h[e]) * p.inv_s_u;
+      *reinterpret_cast<uint2 *>(sA + (size_t)m * Dm + (size_t)g * 8) =
+          make_uint2(pack_q8x4(v[0], v[1], v[2], v[3]), pack_q8x4(v[4], v[5], v[6], v[7]));
+    };
+    if (one_sweep) {
 #pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            const float f = __half2float(__float2half_rn(__half2float(a.h[e]) + __half2float(r.h[e])));
-            v[e] = f * rinv[m] * __half2float(wv.h[e]) * p.inv_s_u;
+      for (int it = 0; it < SW; ++it) {
+        const int g = tid + it * 256;
+        if (g < groups) {
+          const uint4 wword = *reinterpret_cast<const uint4 *>(p.norm_w + (size_t)g * 8);
+#pragma unroll
+          for (int m = 0; m < MB; ++m) {
+            if (m < M) emit(m, g, keep[m][it], wword);
+            else *reinterpret_cast<uint2 *>(sA + (size_t)m * Dm + (size_t)g * 8) = make_uint2(0u, 0u);
           }
-          codes = make_uint2(pack_q8x4(v[0], v[1], v[2], v[3]), pack_q8x4(v[4], v[5], v[6], v[7]));
         }
-        *reinterpret_cast<uint2 *>(sA + (size_t)m * Dm + (size_t)g * 8) = codes;
+      }
+    } else {  // second sweep over the same (cache-resident) rows
+      for (int g = tid; g < groups; g += 256) {
+        const uint4 wword = *reinterpret_cast<const uint4 *>(p.norm_w + (size_t)g * 8);
+#pragma unroll
+        for (int m = 0; m < MB; ++m) {
+          if (m < M) emit(m, g, load_sum(m, g), wword);
+          else *reinterpret_cast<uint2 *>(sA + (size_t)m * Dm + (size_t)g * 8) = make_uint2(0u, 0u);
+        }
       }
     }
   }
