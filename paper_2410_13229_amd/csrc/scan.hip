@@ -272,9 +272,12 @@ __global__ __launch_bounds__(256) void scan_carry_kernel(Dev p, float *__restric
     float loc[G], s[G];
 #pragma unroll
     for (int i = 0; i < G; ++i) {
-      const int c = min(c0 + i, p.nchunks - 1);
-      loc[i] = hl[(size_t)c * per_b];
-      s[i] = ss[(size_t)c * p.Di];
+      loc[i] = 0.f;
+      s[i] = 0.f;
+      if (c0 + i < p.nchunks) {
+        loc[i] = hl[(size_t)(c0 + i) * per_b];
+        s[i] = ss[(size_t)(c0 + i) * p.Di];
+      }
     }
 #pragma unroll
     for (int i = 0; i < G; ++i) {
