@@ -301,7 +301,8 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG, OCC) void gemm_i8_dma_kernel(c
   constexpr int NW = WGM * WGN * KG;  // waves per workgroup
   static_assert(NW == 2 || NW == 4 || NW == 8, "two, four or eight waves per workgroup");
   static_assert(BKB == 64 || BKB == 128, "slice width");
-  static_assert(KG == 1 || KG == 2, "one or two K groups");
+  static_assert(KG == 1 || KG == 2 || KG == 4, "one, two or four K groups");
+  static_assert(BKB / 32 % KG == 0, "every K group gets whole sub-slices");
   constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int TM = WM / 32, TN = WN / 32;
   constexpr int RPI = 1024 / BKB;  // tile rows written by one wave-level load
@@ -398,14 +399,16 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG, OCC) void gemm_i8_dma_kernel(c
   }
 #undef QUAMBA_VMCNT
 
-  if constexpr (KG == 2) {
-    // group 1 parks its sums lane-major (16 bytes per lane and register quad: conflict-free),
-    // group 0 adds them; each wave pair owns one PART-byte region, reused below for staging
+  if constexpr (KG > 1) {
+    // groups 1 .. KG-1 park their sums lane-major (16 bytes per lane and register quad:
+    // conflict-free), group 0 adds them; region (g - 1, tile) is PART bytes, and group 0 reuses
+    // region (0, tile), which it alone reads, for staging its output
     constexpr int PART = TM * TN * 16 * 64 * 4;
-    static_assert(S * STAGE >= WGM * WGN * PART, "K-group sums fit in the ring");
+    constexpr int TILES = WGM * WGN;
+    static_assert(S * STAGE >= (KG - 1) * TILES * PART, "K-group sums fit in the ring");
     __syncthreads();  // operand tiles are dead
-    v4i *part = reinterpret_cast<v4i *>(ring + wtile * PART);
-    if (kg == 1) {
+    if (kg >= 1) {
+      v4i *part = reinterpret_cast<v4i *>(ring + ((kg - 1) * TILES + wtile) * PART);
 #pragma unroll
       for (int i = 0; i < TN; ++i)
 #pragma unroll
@@ -416,18 +419,21 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG, OCC) void gemm_i8_dma_kernel(c
                 v4i{acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
     }
     __syncthreads();
-    if (kg == 1) return;
+    if (kg >= 1) return;
 #pragma unroll
-    for (int i = 0; i < TN; ++i)
+    for (int o = 0; o < KG - 1; ++o) {
+      const v4i *part = reinterpret_cast<const v4i *>(ring + (o * TILES + wtile) * PART);
 #pragma unroll
-      for (int j = 0; j < TM; ++j)
+      for (int i = 0; i < TN; ++i)
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const v4i v = part[((i * TM + j) * 4 + g) * 64 + lane];
+        for (int j = 0; j < TM; ++j)
 #pragma unroll
-          for (int e = 0; e < 4; ++e) acc[i][j][4 * g + e] += v[e];
-        }
-    // this wave alone read its region, so it may restage into it without another barrier
+          for (int g = 0; g < 4; ++g) {
+            const v4i v = part[((i * TM + j) * 4 + g) * 64 + lane];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[i][j][4 * g + e] += v[e];
+          }
+    }
     finish<TM, TN, false>(acc, m0 + wm * WM, n0 + wn * WN, lane, M, N, epi,
                           ks.partial ? ks.partial + (size_t)blockIdx.y * M * N : nullptr, ring + wtile * PART, PART);
   } else {
@@ -589,6 +595,8 @@ int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, i
   //   5 = dma 64x64, 128-byte slices, ring of 3 (best weight-streaming rate for decode-sized M)
   //   6 = dma 128x160, two K groups of 4 waves (fills the SIMDs when there is only about one
   //       128x160 tile per CU)
+  //   7 = dma 64x32, two K groups of 2 waves, ring of 4: decode-sized M with a wide output gets a
+  //       tile per CU without splitting K over the grid (no second kernel)
   if (M <= 8 && g_gemm_variant < 0 && (size_t)8 * K <= 64 * 1024) {
     const size_t lds = (size_t)(M <= 1 ? 1 : (M <= 4 ? 4 : 8)) * K;
     if (M <= 1)
@@ -604,14 +612,14 @@ int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, i
   const long tiles_256 = (long)((M + 255) / 256) * ((N + 319) / 320);
   const long tiles_128 = (long)((M + 127) / 128) * ((N + 159) / 160);
   if (M <= 64)
-    kind = k128 ? 5 : (k64 ? 3 : 0);
+    kind = k128 ? ((N + 31) / 32 >= 256 ? 7 : 5) : (k64 ? 3 : 0);
   else if (N <= 512)
     kind = k128 ? 5 : (k64 ? 3 : 0);
   else if (k128 && M >= 256 && N >= 640)
     kind = tiles_256 >= 192 ? 4 : (tiles_128 < 192 ? 5 : (tiles_128 <= 384 ? 6 : 2));  // few big tiles: 64x64 ones
   else
     kind = 1;
-  if (g_gemm_variant >= 0 && g_gemm_variant <= 6 &&
+  if (g_gemm_variant >= 0 && g_gemm_variant <= 7 &&
       (g_gemm_variant < 2 || (g_gemm_variant == 3 && k64) || (g_gemm_variant != 3 && k128)))
     kind = g_gemm_variant;
 
@@ -638,6 +646,7 @@ int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, i
     case 5: rc = run_dma<64, 64, 2, 2, 3, 128, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
     case 4: rc = run_dma<256, 320, 4, 2, 2, 128, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
     case 6: rc = run_dma<128, 160, 4, 1, 3, 128, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
+    case 7: rc = run_dma<64, 32, 2, 1, 4, 128, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
     default: rc = run_reg<128, 128, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
   }
   if (rc != QUAMBA_OK || splits == 1) return rc;
