@@ -251,3 +251,41 @@ def test_calibrate_block_chain_matches_oracle_stack_calibration():
                 assert d.max() <= 1 and (d != 0).mean() <= 1e-3, (l, k)
             else:
                 assert np.array_equal(got, v), (l, k)
+
+
+def test_model_two_blocks_at_2p8b_width_and_full_vocabulary():
+    """The 64-block configuration's width (d_model 2560, d_inner 5120, dt_rank 160) and vocabulary (50280) with two
+    blocks, batch 4: prefill, then generation steps on the few-sequence kernels, against the oracle."""
+    cfg = W.CONFIGS["c3"]
+    nlayers, Bt, L, vocab = 2, 4, 48, 50280
+    ws_np = [W.make_weights(cfg, layer=l) for l in range(nlayers)]
+    norm_w, norm_f = W.make_norm_weights(cfg, nlayers)
+    E = W.make_embedding(cfg, vocab)
+    calib = O.embed(E, W.make_tokens(cfg, vocab, batch=2, seqlen=128, stream=7))
+    layers = O.calibrate_stack(ws_np, norm_w, calib)
+    om = dict(E=E, norm_f=norm_f, norm_w=norm_w, layers=layers, eps=1e-5)
+    gm = Q.make_model(cfg, dev(E), dev(norm_f),
+                      [(qweights_to_dev(qw), sc, dev(nw)) for (qw, sc), nw in zip(layers, norm_w)], eps=1e-5)
+    prompt = W.make_tokens(cfg, vocab, batch=Bt, seqlen=L)
+    ssm, cs = _states(cfg, nlayers, Bt)
+    logits = empty((Bt, vocab), torch.float32)
+    nxt = empty((Bt,), torch.int32)
+    Q.quamba_model_prefill(gm, dev(prompt), Bt, L, logits, nxt, ssm, cs,
+                           workspace(Q.quamba_model_workspace_bytes(gm, Bt, L)))
+    ref_logits, ref_next, ref_states = O.model_prefill(om, prompt)
+    assert rel_err(host(logits), ref_logits) <= 5e-2
+    assert np.array_equal(host(nxt), O.greedy(host(logits)))
+    _check_choice(host(nxt), ref_logits, 0.1 * np.abs(ref_logits).max())
+    for l in range(nlayers):
+        assert rel_err(host(ssm[l]), ref_states[l][0]) <= 5e-2
+    wsd = workspace(Q.quamba_model_workspace_bytes(gm, Bt, 1))
+    tok = ref_next
+    for step in range(2):
+        st_in = [(host(ssm[l]).copy(), host(cs[l]).copy()) for l in range(nlayers)]
+        Q.quamba_model_decode(gm, dev(tok), Bt, logits, nxt, ssm, cs, wsd)
+        ref_logits, ref_next, ref_states = O.model_decode(om, tok, st_in)
+        assert rel_err(host(logits), ref_logits) <= 5e-2, step
+        _check_choice(host(nxt), ref_logits, 0.1 * np.abs(ref_logits).max())
+        for l in range(nlayers):
+            assert rel_err(host(ssm[l]), ref_states[l][0]) <= 5e-2
+        tok = ref_next
