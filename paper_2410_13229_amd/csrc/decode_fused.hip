@@ -39,12 +39,13 @@ __global__ __launch_bounds__(256) void decode_in_kernel(DecodeInArgs p) {
     }
 
   if (p.u_q) {  // already quantized input
-    for (int c = tid; c < MB * (Dm / 16); c += 256) {
-      const int m = c / (Dm / 16), ch = c % (Dm / 16);
-      v4i v = {0, 0, 0, 0};
-      if (m < M) v = *reinterpret_cast<const v4i *>(p.u_q + (size_t)m * Dm + ch * 16);
-      *reinterpret_cast<v4i *>(sA + (size_t)m * Dm + ch * 16) = v;
-    }
+#pragma unroll
+    for (int m = 0; m < MB; ++m)
+      for (int ch = tid; ch < Dm / 16; ch += 256) {
+        v4i v = {0, 0, 0, 0};
+        if (m < M) v = *reinterpret_cast<const v4i *>(p.u_q + (size_t)m * Dm + ch * 16);
+        *reinterpret_cast<v4i *>(sA + (size_t)m * Dm + ch * 16) = v;
+      }
   } else {
     // One sweep: the fp16 sums s = fp16(out + res) stay in registers (8 halves per 16-byte word) between
     // the reduction and the scaling; a thread owns at most SW words per row (d_model <= 4096 with 2).
@@ -197,12 +198,7 @@ __global__ __launch_bounds__(256) void decode_in_kernel(DecodeInArgs p) {
 #pragma unroll
   for (int m = 0; m < MB; ++m)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      int v = acc[m][j];
-#pragma unroll
-      for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
-      acc[m][j] = v;  // every lane holds the sum
-    }
+    for (int j = 0; j < 4; ++j) acc[m][j] = wave_sum(acc[m][j]);  // every lane holds the sum
   // lane m finishes row m of this wave's four columns
   if (n0 < N && lane < M) {
     int a[4] = {0, 0, 0, 0};

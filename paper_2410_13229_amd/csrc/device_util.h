@@ -12,6 +12,18 @@ namespace quamba {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
+// Sum of an int over the 64 lanes of the wave, the same value returned to every lane.  Four DPP steps
+// (inside quads, half rows, rows of 16: plain VALU operand swizzles, no LDS round trip as a shuffle
+// would take) and the four row sums read out as scalars.
+__device__ __forceinline__ int wave_sum(int v) {
+  v += __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xf, 0xf, true);   // quad_perm [1, 0, 3, 2]
+  v += __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xf, 0xf, true);   // quad_perm [2, 3, 0, 1]
+  v += __builtin_amdgcn_update_dpp(0, v, 0x141, 0xf, 0xf, true);  // row_half_mirror
+  v += __builtin_amdgcn_update_dpp(0, v, 0x140, 0xf, 0xf, true);  // row_mirror
+  return __builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16) + __builtin_amdgcn_readlane(v, 32) +
+         __builtin_amdgcn_readlane(v, 48);
+}
+
 // Four already scaled values -> four int8 codes (Eq. 2) in one word, first value in the low
 // byte.  Clamping to [-128, 127] first and then adding 1.5 * 2^23 leaves the rounded integer in
 // the low mantissa bits (the sum's unit in the last place is 1 and the constant is even, so ties

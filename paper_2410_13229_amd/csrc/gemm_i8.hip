@@ -467,12 +467,13 @@ __global__ __launch_bounds__(256) void gemv_i8_kernel(const int8_t *__restrict__
     const int n = min(n0 + j, N - 1);  // N is a multiple of 4: the clamp never acts, it only bounds the address
     w[j] = *reinterpret_cast<const v4i *>(Wt + (size_t)n * ldw + min(tid, nchunks - 1) * 16);
   }
-  for (int c = tid; c < MB * nchunks; c += 256) {
-    const int m = c / nchunks, ch = c % nchunks;
-    v4i v = {0, 0, 0, 0};
-    if (m < M) v = *reinterpret_cast<const v4i *>(A + (size_t)m * lda + ch * 16);
-    *reinterpret_cast<v4i *>(sA + (size_t)m * K + ch * 16) = v;
-  }
+#pragma unroll
+  for (int m = 0; m < MB; ++m)
+    for (int ch = tid; ch < nchunks; ch += 256) {
+      v4i v = {0, 0, 0, 0};
+      if (m < M) v = *reinterpret_cast<const v4i *>(A + (size_t)m * lda + ch * 16);
+      *reinterpret_cast<v4i *>(sA + (size_t)m * K + ch * 16) = v;
+    }
   __syncthreads();
   int acc[MB][4];
 #pragma unroll
@@ -506,9 +507,7 @@ __global__ __launch_bounds__(256) void gemv_i8_kernel(const int8_t *__restrict__
   for (int m = 0; m < MB; ++m)
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      int v = acc[m][j];
-#pragma unroll
-      for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+      const int v = wave_sum(acc[m][j]);
       if (lane == 0) red[wave][m * 4 + j] = v;
     }
   __syncthreads();
