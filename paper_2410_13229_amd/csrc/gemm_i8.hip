@@ -34,7 +34,8 @@ namespace {
 template <int BKB>
 __device__ __forceinline__ int swzk(int row, int chunk) {
   if constexpr (BKB == 64) return row * 64 + ((chunk ^ ((row >> 2) & 3)) << 4);
-  else return row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4);
+  else if constexpr (BKB == 128) return row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4);
+  else return row * 256 + ((chunk ^ (row & 15)) << 4);  // 256-byte rows: one row spans the 64 banks
 }
 
 // Epilogue for four consecutive columns gn..gn+3 of row gm.  The column ranges end on multiples
@@ -167,6 +168,19 @@ __device__ __forceinline__ int xcd_tile_id(int wg, int nwg) {
   return (wg < (per << 3)) ? (wg & 7) * per + (wg >> 3) : wg;
 }
 
+// Tile id -> (m tile, n tile), walking the output in bands of 8 m tiles with m fastest inside a
+// band: a run of 32 consecutive ids (one XCD's share of 256 tiles) is then an 8 x 4 block, which
+// touches the fewest distinct operand rows, instead of a 16 x 2 or 32 x 1 strip.
+__device__ __forceinline__ void tile_coords(int id, int tiles_m, int tiles_n, int *tm, int *tn) {
+  constexpr int GM = 8;
+  const int width = GM * tiles_n;
+  const int first = (id / width) * GM;
+  const int gsz = min(tiles_m - first, GM);
+  const int r = id % width;
+  *tm = first + r % gsz;
+  *tn = r / gsz;
+}
+
 struct KSplit {
   int slices_per_split;  // K slices handled by one grid.y index
   int32_t *partial;      // [splits, M, N] when splitting, else nullptr
@@ -190,9 +204,10 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t *__restrict__
 
   __shared__ __attribute__((aligned(16))) int8_t lds[2][(BM + BN) * BK];
 
-  const int id = xcd_tile_id(blockIdx.x, tiles_m * tiles_n);
-  const int m0 = (id % tiles_m) * BM;
-  const int n0 = (id / tiles_m) * BN;
+  int tile_m, tile_n;
+  tile_coords(xcd_tile_id(blockIdx.x, tiles_m * tiles_n), tiles_m, tiles_n, &tile_m, &tile_n);
+  const int m0 = tile_m * BM;
+  const int n0 = tile_n * BN;
   const int k_lo = blockIdx.y * ks.slices_per_split * BK;
   const int k_hi = min(K, k_lo + ks.slices_per_split * BK);
 
@@ -291,7 +306,7 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t *__restrict__
 // Rows past M or N are clamped to the last valid row: they are loaded and multiplied but never
 // stored.
 // ------------------------------------------------------------------------------------------
-template <int BM, int BN, int WGM, int WGN, int S, int BKB, int OCC, int KG = 1>
+template <int BM, int BN, int WGM, int WGN, int S, int BKB, int OCC, int KG = 1, bool PIPE = false>
 __global__ __launch_bounds__(64 * WGM * WGN * KG, OCC) void gemm_i8_dma_kernel(const int8_t *__restrict__ A, int lda,
                                                                const int8_t *__restrict__ Wt, int ldw,
                                                                int M, int N, int K, GemmEpilogue epi,
@@ -300,7 +315,7 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG, OCC) void gemm_i8_dma_kernel(c
   // s % KG == g, and the groups' sums are added through LDS before the epilogue.
   constexpr int NW = WGM * WGN * KG;  // waves per workgroup
   static_assert(NW == 2 || NW == 4 || NW == 8, "two, four or eight waves per workgroup");
-  static_assert(BKB == 64 || BKB == 128, "slice width");
+  static_assert(BKB == 64 || BKB == 128 || BKB == 256, "slice width");
   static_assert(KG == 1 || KG == 2 || KG == 4, "one, two or four K groups");
   static_assert(BKB / 32 % KG == 0, "every K group gets whole sub-slices");
   constexpr int WM = BM / WGM, WN = BN / WGN;
@@ -316,9 +331,10 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG, OCC) void gemm_i8_dma_kernel(c
 
   extern __shared__ __attribute__((aligned(16))) int8_t ring[];
 
-  const int id = xcd_tile_id(blockIdx.x, tiles_m * tiles_n);
-  const int m0 = (id % tiles_m) * BM;
-  const int n0 = (id / tiles_m) * BN;
+  int tile_m, tile_n;
+  tile_coords(xcd_tile_id(blockIdx.x, tiles_m * tiles_n), tiles_m, tiles_n, &tile_m, &tile_n);
+  const int m0 = tile_m * BM;
+  const int n0 = tile_n * BN;
   const int slice_lo = blockIdx.y * ks.slices_per_split;
   const int nk = min(K / BKB - slice_lo, ks.slices_per_split);
 
@@ -336,7 +352,8 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG, OCC) void gemm_i8_dma_kernel(c
     const int j = min(wave + NW * i, NJ - 1);
     const int row = j * RPI + lane / CPR;
     const int lrow = row < BM ? row : row - BM;  // the swizzle phase follows the row inside its operand
-    const int chunk = BKB == 64 ? ((lane % CPR) ^ ((lrow >> 2) & 3)) : ((lane % CPR) ^ ((lrow >> 1) & 7));
+    const int chunk = BKB == 64 ? ((lane % CPR) ^ ((lrow >> 2) & 3))
+                                : (BKB == 128 ? ((lane % CPR) ^ ((lrow >> 1) & 7)) : ((lane % CPR) ^ (lrow & 15)));
     dst[i] = j * 1024;
     if (row < BM)
       src[i] = A + (size_t)min(m0 + row, M - 1) * lda + (size_t)slice_lo * BKB + chunk * 16;
@@ -362,6 +379,34 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG, OCC) void gemm_i8_dma_kernel(c
   auto compute = [&](int stage) {
     const int8_t *la = ring + stage * STAGE;
     const int8_t *lw = la + BM * BKB;
+    if constexpr (PIPE) {
+      // one wave per SIMD: nothing else hides the LDS latency, so the fragments of sub-slice s + 1 are
+      // requested before the MFMAs of sub-slice s are issued, and the scheduler is told to keep that order
+      constexpr int NSUB = BKB / 32 / KG;
+      v4i fa[2][TM], fw[2][TN];
+      auto load = [&](int sub, int buf) {
+        const int chunk = (sub * KG + kg) * 2 + (lane >> 5);
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+          fa[buf][j] = *reinterpret_cast<const v4i *>(la + swzk<BKB>(wm * WM + j * 32 + (lane & 31), chunk));
+#pragma unroll
+        for (int i = 0; i < TN; ++i)
+          fw[buf][i] = *reinterpret_cast<const v4i *>(lw + swzk<BKB>(wn * WN + i * 32 + (lane & 31), chunk));
+      };
+      load(0, 0);
+#pragma unroll
+      for (int sub = 0; sub < NSUB; ++sub) {
+        if (sub + 1 < NSUB) load(sub + 1, (sub + 1) & 1);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < TN; ++i)
+#pragma unroll
+          for (int j = 0; j < TM; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[sub & 1][i], fa[sub & 1][j], acc[i][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      return;
+    }
 #pragma unroll
     for (int s0 = 0; s0 < BKB / 32; s0 += KG) {
       const int chunk = (s0 + kg) * 2 + (lane >> 5);
@@ -545,19 +590,19 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const int32_t *__res
   emit4(epi, gm, gn, N, a);
 }
 
-template <int BM, int BN, int WGM, int WGN, int S, int BKB, int OCC, int KG = 1>
+template <int BM, int BN, int WGM, int WGN, int S, int BKB, int OCC, int KG = 1, bool PIPE = false>
 int run_dma(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, int N, int K,
             const GemmEpilogue &epi, int splits, const KSplit &ks, hipStream_t st) {
   constexpr size_t lds = (size_t)S * (BM + BN) * BKB;
   static bool attr_set = false;
   if (!attr_set) {
     QUAMBA_HIP(hipFuncSetAttribute(
-        reinterpret_cast<const void *>(&gemm_i8_dma_kernel<BM, BN, WGM, WGN, S, BKB, OCC, KG>),
+        reinterpret_cast<const void *>(&gemm_i8_dma_kernel<BM, BN, WGM, WGN, S, BKB, OCC, KG, PIPE>),
         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     attr_set = true;
   }
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-  hipLaunchKernelGGL((gemm_i8_dma_kernel<BM, BN, WGM, WGN, S, BKB, OCC, KG>), dim3(tiles_m * tiles_n, splits),
+  hipLaunchKernelGGL((gemm_i8_dma_kernel<BM, BN, WGM, WGN, S, BKB, OCC, KG, PIPE>), dim3(tiles_m * tiles_n, splits),
                      dim3(64 * WGM * WGN * KG), lds, st, A, lda, Wt, ldw, M, N, K, epi, tiles_m, tiles_n, ks);
   QUAMBA_LAUNCH_CHECK();
   return QUAMBA_OK;
@@ -594,6 +639,7 @@ int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, i
   //   5 = dma 64x64, 128-byte slices, ring of 3 (best weight-streaming rate for decode-sized M)
   //   6 = dma 128x160, two K groups of 4 waves (fills the SIMDs when there is only about one
   //       128x160 tile per CU)
+  //   8, 9 = 6 and 5 with 256-byte slices and a ring of 2 (K a multiple of 256)
   //   7 = dma 64x32, two K groups of 2 waves, ring of 4: decode-sized M with a wide output gets a
   //       tile per CU without splitting K over the grid (no second kernel)
   if (M <= 8 && g_gemm_variant < 0 && (size_t)8 * K <= 64 * 1024) {
@@ -618,15 +664,18 @@ int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, i
     kind = tiles_256 >= 192 ? 4 : (tiles_128 < 192 ? 5 : (tiles_128 <= 384 ? 6 : 2));  // few big tiles: 64x64 ones
   else
     kind = 1;
-  if (g_gemm_variant >= 0 && g_gemm_variant <= 7 &&
+  // deep K in whole 256-byte slices: half as many barriers for the same bytes
+  if ((K % 256) == 0 && kind == 6) kind = 8;
+  if ((K % 256) == 0 && kind == 5 && M > 64) kind = 9;  // (decode-sized M measured better with 128-byte slices)
+  if (g_gemm_variant >= 0 && g_gemm_variant <= 9 &&
       (g_gemm_variant < 2 || (g_gemm_variant == 3 && k64) || (g_gemm_variant != 3 && k128)))
     kind = g_gemm_variant;
 
   // split K when the output has too few tiles to fill 256 CUs and K is deep
   int splits = 1;
-  const int slice = (kind == 2 || kind >= 4) ? 128 : 64;
+  const int slice = kind >= 8 ? 256 : ((kind == 2 || kind >= 4) ? 128 : 64);
   const int nslices = (K + slice - 1) / slice;
-  if ((kind == 0 || kind == 3 || kind == 5) && ws != nullptr) {
+  if ((kind == 0 || kind == 3 || kind == 5 || kind == 9) && ws != nullptr) {
     const int tiles = ((M + 63) / 64) * ((N + 63) / 64);
     int want = 512 / (tiles > 0 ? tiles : 1);
     if (want > 8) want = 8;
@@ -646,6 +695,8 @@ int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, i
     case 4: rc = run_dma<256, 320, 4, 2, 2, 128, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
     case 6: rc = run_dma<128, 160, 4, 1, 3, 128, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
     case 7: rc = run_dma<64, 32, 2, 1, 4, 128, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
+    case 8: rc = run_dma<128, 160, 4, 1, 2, 256, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
+    case 9: rc = run_dma<64, 64, 2, 2, 2, 256, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
     default: rc = run_reg<128, 128, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
   }
   if (rc != QUAMBA_OK || splits == 1) return rc;
