@@ -15,8 +15,10 @@
  *     Scratch comes from the caller's workspace `ws` (size from the matching
  *     *_workspace_bytes query, 256-byte aligned).
  *   - work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default stream)
- *     and the call returns without synchronising, except quamba_calibrate, which
- *     synchronises the stream to hand the scales back in host memory.
+ *     and the call returns without synchronising, except the calibration calls, which
+ *     synchronise the stream to hand the scales back in host memory, and graph-replayed
+ *     generation (quamba_model_generate with use_graph), which waits for its last replay and
+ *     lets the HIP runtime allocate what its graph objects need.
  *   - fp16 tensors are IEEE binary16 (quamba_half = raw 16-bit storage).
  *   - tensors are dense row-major with the last index fastest; weights are [out, in].
  *   - notation: Dm = d_model, Di = d_inner, N = d_state (16), R = dt_rank, W = d_conv (4),
@@ -85,7 +87,9 @@ typedef struct {
 } quamba_scales;
 
 /* Optional copies of the intermediates, for parity tests.  Any member may be NULL; the struct
- * pointer itself may be NULL.  All are dense [M, cols] with M = Bt*L (decode: M = Bt). */
+ * pointer itself may be NULL.  All are dense [M, cols] with M = Bt*L (decode: M = Bt).
+ * Asking for acc_dt makes dt_proj run as a GEMM of its own; otherwise the scan kernels form
+ * dt_q themselves where the shapes allow (same codes either way). */
 typedef struct {
   int8_t *u_q;      /* [M, Dm]    quantized block input                  */
   int32_t *acc_in;  /* [M, 2*Di]  in_proj accumulators                   */
