@@ -640,6 +640,7 @@ int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, i
   //   6 = dma 128x160, two K groups of 4 waves (fills the SIMDs when there is only about one
   //       128x160 tile per CU)
   //   8, 9 = 6 and 5 with 256-byte slices and a ring of 2 (K a multiple of 256)
+  //   10 = 4 with 256 x 256 tiles (eight waves of 64 x 128), for N that 320-wide tiles fit badly
   //   7 = dma 64x32, two K groups of 2 waves, ring of 4: decode-sized M with a wide output gets a
   //       tile per CU without splitting K over the grid (no second kernel)
   if (M <= 8 && g_gemm_variant < 0 && (size_t)8 * K <= 64 * 1024) {
@@ -664,16 +665,24 @@ int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, i
     kind = tiles_256 >= 192 ? 4 : (tiles_128 < 192 ? 5 : (tiles_128 <= 384 ? 6 : 2));  // few big tiles: 64x64 ones
   else
     kind = 1;
+  if (kind == 4) {
+    // 256 x 256 tiles instead when they fill the rounds of 256 CUs (and the N edge) clearly better
+    auto fill = [&](int bn) {
+      const long tn = (N + bn - 1) / bn, t = (long)((M + 255) / 256) * tn;
+      return (double)t / (double)((t + 255) / 256 * 256) * (double)N / (double)(tn * bn);
+    };
+    if (fill(256) > fill(320) + 0.05) kind = 10;
+  }
   // deep K in whole 256-byte slices: half as many barriers for the same bytes
   if ((K % 256) == 0 && kind == 6) kind = 8;
   if ((K % 256) == 0 && kind == 5 && M > 64) kind = 9;  // (decode-sized M measured better with 128-byte slices)
-  if (g_gemm_variant >= 0 && g_gemm_variant <= 9 &&
+  if (g_gemm_variant >= 0 && g_gemm_variant <= 10 &&
       (g_gemm_variant < 2 || (g_gemm_variant == 3 && k64) || (g_gemm_variant != 3 && k128)))
     kind = g_gemm_variant;
 
   // split K when the output has too few tiles to fill 256 CUs and K is deep
   int splits = 1;
-  const int slice = kind >= 8 ? 256 : ((kind == 2 || kind >= 4) ? 128 : 64);
+  const int slice = (kind == 8 || kind == 9) ? 256 : ((kind == 2 || kind >= 4) ? 128 : 64);
   const int nslices = (K + slice - 1) / slice;
   if ((kind == 0 || kind == 3 || kind == 5 || kind == 9) && ws != nullptr) {
     const int tiles = ((M + 63) / 64) * ((N + 63) / 64);
@@ -697,6 +706,7 @@ int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, i
     case 7: rc = run_dma<64, 32, 2, 1, 4, 128, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
     case 8: rc = run_dma<128, 160, 4, 1, 2, 256, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
     case 9: rc = run_dma<64, 64, 2, 2, 2, 256, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
+    case 10: rc = run_dma<256, 256, 4, 2, 2, 128, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
     default: rc = run_reg<128, 128, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
   }
   if (rc != QUAMBA_OK || splits == 1) return rc;

@@ -33,7 +33,7 @@ GEMM_SHAPES = [
     (64, 10240, 2560, 0), (512, 2560, 5120, 0), (300, 5120, 160, 32), (2048, 192, 5120, 0),
     (64, 2560, 5120, 0), (1000, 288, 8192, 0), (333, 1280, 1024, 0), (2048, 80, 1536, 0),
     # the widest tiles (256 x 320, eight waves) and the two-workgroups-per-CU 128 x 160 tiles, ragged in M and N
-    (1100, 14000, 256, 0), (1500, 5408, 128, 0),
+    (1100, 14000, 256, 0), (1500, 5408, 128, 0), (4000, 4096, 128, 0),  # the last: 256 x 256 tiles
     # few rows (generation): the streaming kernel without matrix tiles
     (1, 10240, 2560, 0), (4, 2560, 5120, 0), (8, 192, 5120, 0), (3, 5120, 160, 32), (2, 12, 48, 0), (7, 768, 1536, 0),
 ]
