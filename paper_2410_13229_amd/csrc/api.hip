@@ -95,7 +95,7 @@ int tap_copy(void *dst, const void *src, size_t bytes, hipStream_t st) {
 }
 
 // Steps shared by prefill (L >= 1, fresh conv history) and decode (L == 1, carried state).
-// `norm` (generation with at most 8 sequences only): the block input is not given but formed inside
+// `norm` (generation with at most 4 sequences only): the block input is not given but formed inside
 // the first kernel from the previous block's output and the residual stream.
 int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scales *sc, const __half *u,
               const int8_t *u_q_in, int Bt, int L, bool decode, __half *out, float *ssm_state,
@@ -104,7 +104,7 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
   QUAMBA_TRY(check_dims(d));
   QUAMBA_TRY(check_q(qw, sc));
   if ((!u && !u_q_in && !norm) || !out) return fail(QUAMBA_EINVAL, "input or output pointer is NULL");
-  if (norm && !(decode && Bt <= 8)) return fail(QUAMBA_EINVAL, "fused block input needs decode with batch <= 8");
+  if (norm && !(decode && Bt <= 4)) return fail(QUAMBA_EINVAL, "fused block input needs decode with batch <= 4");
   if (Bt < 1 || L < 1) return fail(QUAMBA_EINVAL, "batch=%d, L=%d must be >= 1", Bt, L);
   if (decode && (!ssm_state || !conv_state)) return fail(QUAMBA_EINVAL, "decode needs ssm_state and conv_state");
   const Plan p = make_plan(d, Bt, L);
@@ -126,7 +126,7 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
   const quamba_taps &t = taps ? *taps : none;
 
   // Generation with a handful of sequences: [norm +] in_proj + conv step in one streaming kernel.
-  const bool few = decode && M <= 8 && Dm <= 8192 && g_fuse_decode;
+  const bool few = decode && M <= 4 && Dm <= 8192 && g_fuse_decode;
   // quantize the block input (Eq. 2)
   const int8_t *uq = u_q_in;
   if (!uq && !norm) {
@@ -230,7 +230,7 @@ int mixer_decode_norm(const quamba_dims *d, const quamba_qweights *qw, const qua
                    &norm);
 }
 
-bool mixer_decode_norm_available(const quamba_dims *d, int Bt) { return g_fuse_decode && Bt <= 8 && d->d_model <= 8192; }
+bool mixer_decode_norm_available(const quamba_dims *d, int Bt) { return g_fuse_decode && Bt <= 4 && d->d_model <= 8192; }
 
 int check_model_dims(const quamba_dims *d) { return check_dims(d); }
 

@@ -90,7 +90,7 @@ int launch_scan_step(const ScanArgs &a, hipStream_t st);
 int launch_hadamard_quant(const __half *g, int M, int n, float inv_s_y, int8_t *yH_q, float *yH_f32,
                           hipStream_t st);
 
-// generation with M <= 8 rows: [add + RMSNorm + quant] -> in_proj -> conv step in one kernel.
+// generation with M <= 4 rows: [add + RMSNorm + quant] -> in_proj -> conv step in one kernel.
 // Either u_q (already quantized input [M, Dm]) or out_prev / res_in / res_out / norm_w (res_out must
 // not alias res_in: every workgroup reads res_in while workgroup 0 writes res_out).
 struct DecodeInArgs {
@@ -120,7 +120,7 @@ int mixer_run_q(const quamba_dims *d, const quamba_qweights *qw, const quamba_sc
                 hipStream_t st);
 int check_model_dims(const quamba_dims *d);
 
-// generation with at most 8 sequences: the block's own residual add + RMSNorm + quantization runs
+// generation with at most 4 sequences: the block's own residual add + RMSNorm + quantization runs
 // inside the mixer's first kernel.  res_out must not alias res_in.
 struct NormIn {
   const __half *out_prev, *res_in;

@@ -1,4 +1,4 @@
-// First kernel of a block in generation with few sequences (M <= 8): residual add + RMSNorm +
+// First kernel of a block in generation with few sequences (M <= 4): residual add + RMSNorm +
 // quantization (Section 4.3 "Fused RMSNorm"), the int8 input projection, and the causal conv step
 // with SiLU and requantization (Section 4.3 "Fused causal convolution") in one launch.  With a
 // handful of rows every one of these is a few microseconds of launch latency and almost no work,
@@ -227,18 +227,17 @@ __global__ __launch_bounds__(256) void decode_in_kernel(DecodeInArgs p) {
 }  // namespace
 
 int launch_decode_in(const DecodeInArgs &a, hipStream_t st) {
-  if (a.M < 1 || a.M > 8) return fail(QUAMBA_EUNSUPPORTED, "decode_in: M=%d outside 1..8", a.M);
-  if (a.Dm % 16 || a.Di % 4 || (size_t)8 * a.Dm > 64 * 1024)
+  if (a.M < 1 || a.M > 4) return fail(QUAMBA_EUNSUPPORTED, "decode_in: M=%d outside 1..4", a.M);
+  if (a.Dm % 16 || a.Di % 4 || a.Dm > 8192)
     return fail(QUAMBA_EUNSUPPORTED, "decode_in: d_model=%d must be a multiple of 16 and <= 8192, d_inner a multiple of 4",
                 a.Dm);
-  const int mb = a.M <= 1 ? 1 : (a.M <= 2 ? 2 : (a.M <= 4 ? 4 : 8));
+  const int mb = a.M <= 1 ? 1 : (a.M <= 2 ? 2 : 4);
   const size_t lds = (size_t)mb * a.Dm;
   const dim3 grid((2 * a.Di + 15) / 16), block(256);
   switch (mb) {
     case 1: hipLaunchKernelGGL(decode_in_kernel<1>, grid, block, lds, st, a); break;
     case 2: hipLaunchKernelGGL(decode_in_kernel<2>, grid, block, lds, st, a); break;
-    case 4: hipLaunchKernelGGL(decode_in_kernel<4>, grid, block, lds, st, a); break;
-    default: hipLaunchKernelGGL(decode_in_kernel<8>, grid, block, lds, st, a); break;
+    default: hipLaunchKernelGGL(decode_in_kernel<4>, grid, block, lds, st, a); break;
   }
   QUAMBA_LAUNCH_CHECK();
   return QUAMBA_OK;

@@ -489,7 +489,8 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG, OCC) void gemm_i8_dma_kernel(c
 }
 
 // ------------------------------------------------------------------------------------------
-// Few-row kernel (generation with a handful of sequences: M <= 8).  A matrix tile would be
+// Few-row kernel (generation with a handful of sequences: M <= 4; from about 8 rows on the
+// matrix-tile kernels are faster again).  A matrix tile would be
 // nearly empty, and the job is to stream W once: a workgroup owns four adjacent output columns,
 // its 256 threads split K in 16-byte pieces (one wave-level load covers 1 KB of a weight row),
 // multiply with v_dot4_i32_i8 against the activation rows held in LDS, and reduce across lanes
@@ -619,6 +620,7 @@ int run_reg(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, int N, i
 }
 
 int g_gemm_variant = -1;  // tuning hook: >= 0 forces a kernel configuration
+int g_gemv_max_rows = 4;  // the few-row streaming kernel serves M up to this (tuning hook; at most 4)
 
 }  // namespace
 
@@ -643,14 +645,14 @@ int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, i
   //   10 = 4 with 256 x 256 tiles (eight waves of 64 x 128), for N that 320-wide tiles fit badly
   //   7 = dma 64x32, two K groups of 2 waves, ring of 4: decode-sized M with a wide output gets a
   //       tile per CU without splitting K over the grid (no second kernel)
-  if (M <= 8 && g_gemm_variant < 0 && (size_t)8 * K <= 64 * 1024) {
-    const size_t lds = (size_t)(M <= 1 ? 1 : (M <= 4 ? 4 : 8)) * K;
+  if (M <= g_gemv_max_rows && g_gemm_variant < 0 && (size_t)4 * K <= 64 * 1024) {
+    const size_t lds = (size_t)(M <= 1 ? 1 : (M <= 2 ? 2 : 4)) * K;
     if (M <= 1)
       hipLaunchKernelGGL(gemv_i8_kernel<1>, dim3(N / 4), dim3(256), lds, st, A, lda, Wt, ldw, M, N, K, epi);
-    else if (M <= 4)
-      hipLaunchKernelGGL(gemv_i8_kernel<4>, dim3(N / 4), dim3(256), lds, st, A, lda, Wt, ldw, M, N, K, epi);
+    else if (M <= 2)
+      hipLaunchKernelGGL(gemv_i8_kernel<2>, dim3(N / 4), dim3(256), lds, st, A, lda, Wt, ldw, M, N, K, epi);
     else
-      hipLaunchKernelGGL(gemv_i8_kernel<8>, dim3(N / 4), dim3(256), lds, st, A, lda, Wt, ldw, M, N, K, epi);
+      hipLaunchKernelGGL(gemv_i8_kernel<4>, dim3(N / 4), dim3(256), lds, st, A, lda, Wt, ldw, M, N, K, epi);
     QUAMBA_LAUNCH_CHECK();
     return QUAMBA_OK;
   }
@@ -720,3 +722,4 @@ int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, i
 }  // namespace quamba
 
 extern "C" void quamba_debug_set_gemm_variant(int v) { quamba::g_gemm_variant = v; }
+extern "C" void quamba_debug_set_gemv_max_rows(int v) { quamba::g_gemv_max_rows = v < 4 ? v : 4; }

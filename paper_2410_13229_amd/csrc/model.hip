@@ -362,7 +362,7 @@ int run_model(const quamba_model *m, const int32_t *tokens, int Bt, int L, bool 
                      reinterpret_cast<const __half *>(m->embedding), tokens, M,
                      Dm, m->vocab, res, out);
   QUAMBA_LAUNCH_CHECK();
-  // generation with at most 8 sequences: the add + norm + quantization runs inside each block's first
+  // generation with at most 4 sequences: the add + norm + quantization runs inside each block's first
   // kernel, which reads one residual buffer and writes the other
   const bool fused = decode && mixer_decode_norm_available(&m->dims, Bt);
   __half *res_other = reinterpret_cast<__half *>(base + c.res2);
