@@ -82,4 +82,18 @@ __device__ __forceinline__ unsigned conv_step4(unsigned xin, const int8_t *wq4, 
   return pack_q8x4(sv[0], sv[1], sv[2], sv[3]);
 }
 
+// Buffer descriptor over [base, base + bytes).  An access takes a scalar byte offset plus a 32-bit
+// lane offset, so its address costs no vector arithmetic (a 64-bit vector address is a quarter-rate
+// multiply-add per access); bytes past the end read as zero and are not written.  `base` must be
+// wave-uniform and bytes < 2^31.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t buffer_over(const void *base, int bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, bytes, 0x00020000);
+}
+__device__ __forceinline__ int buffer_load_i8(__amdgpu_buffer_rsrc_t r, unsigned lane_off, int wave_off) {
+  return static_cast<int>(static_cast<int8_t>(__builtin_amdgcn_raw_buffer_load_b8(r, lane_off, wave_off, 0)));
+}
+__device__ __forceinline__ void buffer_store_f16(__amdgpu_buffer_rsrc_t r, unsigned lane_off, int wave_off, float v) {
+  __builtin_amdgcn_raw_buffer_store_b16(__half_as_ushort(__float2half_rn(v)), r, lane_off, wave_off, 0);
+}
+
 }  // namespace quamba

@@ -126,9 +126,15 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_chunk_kernel(Dev p) {
   const float Dv = OUTPUT ? p.s_D * static_cast<float>(p.D_q[dd]) : 0.f;
   float sdt = 0.f;
   const size_t seq0 = (size_t)b * p.L;
-  const int8_t *xp = p.x_q + seq0 * p.Di + dd;
-  const int8_t *dp = p.dt_q + seq0 * p.Di + dd;
-  const int8_t *zp = p.z_q + seq0 * p.ldz + dd;
+  // x / dt / z / g of this chunk behind buffer descriptors: row offsets are scalar, the lane adds
+  // its channel (the launcher checks that a chunk's rows span less than 2^31 bytes)
+  const unsigned ud = static_cast<unsigned>(dd);
+  const size_t tok0 = seq0 + t0;
+  const int nt = t1 - t0;
+  const auto rx = buffer_over(p.x_q + tok0 * p.Di, nt * p.Di);
+  const auto rdt = FUSE_DT ? rx : buffer_over(p.dt_q + tok0 * p.Di, nt * p.Di);
+  const auto rz = OUTPUT ? buffer_over(p.z_q + tok0 * p.ldz, (nt - 1) * p.ldz + p.Di) : rx;
+  const auto rg = OUTPUT ? buffer_over(p.g16 + tok0 * p.Di, nt * p.Di * 2) : rx;
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -189,10 +195,11 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_chunk_kernel(Dev p) {
   auto fetch = [&](Regs &r, int t) {
 #pragma unroll
     for (int i = 0; i < TS; ++i) {
-      const int tt = min(t + i, t1 - 1);  // clamp: tokens past the chunk are loaded but never used
-      r.x[i] = xp[(size_t)tt * p.Di];
-      if (!FUSE_DT) r.dt[i] = dp[(size_t)tt * p.Di];  // fused: read from the LDS tile when needed
-      if (OUTPUT) r.z[i] = zp[(size_t)tt * p.ldz];
+      // clamp: tokens past the chunk are loaded but never used
+      const int row = min(t + i, t1 - 1) - t0;
+      r.x[i] = buffer_load_i8(rx, ud, row * p.Di);
+      if (!FUSE_DT) r.dt[i] = buffer_load_i8(rdt, ud, row * p.Di);  // fused: read from the LDS tile
+      if (OUTPUT) r.z[i] = buffer_load_i8(rz, ud, row * p.ldz);
     }
   };
   auto compute = [&](const Regs &r, int t, int tl) {  // t: token index, tl: index inside the LDS block
@@ -214,9 +221,8 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_chunk_kernel(Dev p) {
           y += Dv * xv;
           const float g = silu_gate(y, p.s_z * static_cast<float>(r.z[i]));
           if (live) {
-            const size_t o = (seq0 + t + i) * p.Di + d;
-            p.g16[o] = __float2half_rn(g);
-            if (p.y_f32) p.y_f32[o] = g;
+            buffer_store_f16(rg, 2 * ud, (t + i - t0) * p.Di * 2, g);
+            if (p.y_f32) p.y_f32[(seq0 + t + i) * p.Di + d] = g;
           }
         }
       }
@@ -410,6 +416,8 @@ int launch_scan_prefill(const ScanArgs &a, void *ws, size_t ws_bytes, hipStream_
     return fail(QUAMBA_EWORKSPACE, "scan: workspace %zu < %zu", ws_bytes, scan_workspace_bytes(a.Bt, a.L, a.Di));
   Dev p = make_dev(a);
   choose_chunks(a.Bt, a.L, a.Di, &p.T, &p.nchunks);
+  if ((long long)p.T * std::max(a.ldz, 2 * a.Di) > 0x7fffffffLL)  // the kernels' 32-bit offsets inside a chunk
+    return fail(QUAMBA_EUNSUPPORTED, "scan: a chunk of %d tokens x %d channels exceeds 2^31 bytes", p.T, a.Di);
   p.hloc = static_cast<float *>(ws);
   p.ssum = reinterpret_cast<float *>(static_cast<char *>(ws) +
                                      align_up((size_t)a.Bt * p.nchunks * a.Di * NS * sizeof(float), 256));
