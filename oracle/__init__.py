@@ -25,7 +25,7 @@ reference mixer and through the ablation behaviour of Table "quamba_ablation".
 """
 from .hadamard import hadamard_matrix, hadamard_factor, sylvester, paley1  # noqa: F401
 from .quantizer import (rne, quantize, requant_acc, absmax_scale, percentile_max,  # noqa: F401
-                        int_matmul)
+                        int_matmul, optimal_clip, clip_mse_model)
 from .mixer import (fp_forward, calibrate, q_prefill, q_decode, selective_scan,  # noqa: F401
                     causal_conv_fp, add_rmsnorm_quant, silu, softplus, q_scan, q_hadamard_quant,
                     q_out_proj, q_conv_prefill, q_conv_step)

@@ -13,7 +13,7 @@ from __future__ import annotations
 import numpy as np
 
 from .hadamard import hadamard_matrix
-from .quantizer import absmax_scale, int_matmul, percentile_max, quantize, requant_acc
+from .quantizer import absmax_scale, int_matmul, optimal_clip, percentile_max, quantize, requant_acc
 
 F64 = np.float64
 F32 = np.float32
@@ -92,12 +92,16 @@ def fp_forward(w, u, h0=None, conv_history=None):
 
 
 # ----------------------------------------------------------------------------- calibration
-def calibrate(w, calib_u, x_percentile=99.999):
+def calibrate(w, calib_u, x_percentile=99.999, x_clip="percentile"):
     """Static per-tensor scales and int8 weights (Section 5.1 "Quantization setup",
     Section 4.2): run the fp mixer on the calibration batch; every activation scale is
     absmax/127 except the scan input x, which takes the percentile maximum; the scale of
     y^H is collected after applying H_n to the gated scan output; W_out is replaced by
     W_out^H (each row transformed by the same H_n) before it is quantized.
+
+    x_clip = "mse" replaces the percentile by the model-optimal clipping scalar
+    (`quantizer.optimal_clip`), the enhanced variant Section 5.1 mentions; the paper does not say
+    which tensors it clips, this reading applies it where the percentile was.
 
     Returns (qw, sc): int8 weights (+ fp32 conv_b, dt_bias) and a dict of fp32 scales
     and fp32 epilogue multipliers (products of scales evaluated in double, rounded once)."""
@@ -108,10 +112,16 @@ def calibrate(w, calib_u, x_percentile=99.999):
     gH = t["g"] @ H.T  # y^H = H_n g for every token row
     W_outH = np.asarray(w["W_out"], dtype=F64) @ H.T  # row m: H_n W_out[m, :]
     A = t["A"]
+    if x_clip == "percentile":
+        x_clip_value = percentile_max(t["x"], x_percentile)
+    elif x_clip == "mse":
+        x_clip_value = optimal_clip(np.asarray(t["x"], dtype=F64).astype(F32))
+    else:
+        raise ValueError("x_clip must be 'percentile' or 'mse'")
 
     sc = {
         "s_u": absmax_scale(t["u"]), "s_xpre": absmax_scale(t["x_pre"]), "s_z": absmax_scale(t["z"]),
-        "s_x": F32(percentile_max(t["x"], x_percentile) / 127.0),
+        "s_x": F32(x_clip_value / 127.0),
         "s_dtl": absmax_scale(t["dt_low"]), "s_B": absmax_scale(t["B"]), "s_C": absmax_scale(t["C"]),
         "s_dt": absmax_scale(t["dt_raw"]), "s_y": absmax_scale(gH),
         "s_Win": absmax_scale(w["W_in"]), "s_cw": absmax_scale(w["conv_w"]),

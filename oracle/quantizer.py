@@ -49,6 +49,43 @@ def percentile_max(X, p: float) -> float:
     return float(a[rank - 1])
 
 
+def clip_mse_model(X, s: float, bits: int = 8) -> float:
+    """Modelled squared error of quantizing X with clipping scalar s: uniform rounding noise
+    s^2 4^-bits / 3 on every nonzero element inside [-s, s] (step 2s / 2^bits, variance
+    step^2 / 12), plus the clipping error (|x| - s)^2 of every element outside."""
+    a = np.abs(np.asarray(X, dtype=np.float64)).ravel()
+    inside = (a > 0.0) & (a <= s)
+    outside = a > s
+    return float(4.0 ** (-bits) / 3.0 * s * s * np.count_nonzero(inside) + np.sum((a[outside] - s) ** 2))
+
+
+def optimal_clip(X, bits: int = 8, max_iters: int = 32) -> float:
+    """Clipping scalar that minimises `clip_mse_model` (the clipping optimisation named in
+    Section 5.1 "Quantization setup" for the enhanced variant; the paper cites the algorithm and
+    prints none of it, so this is the cited method's fixed-point form of d(model)/ds = 0):
+
+        s <- sum(|x| : |x| > s) / (4^-bits / 3 * count(0 < |x| <= s) + count(|x| > s))
+
+    started at s = mean|x| and repeated until s stops changing, nothing lies outside s, or
+    `max_iters` updates were made.  Returns 0 for an all-zero tensor."""
+    a = np.abs(np.asarray(X, dtype=np.float64)).ravel()
+    if a.size == 0:
+        return 0.0
+    c = 4.0 ** (-bits) / 3.0
+    s = float(np.sum(a) / a.size)
+    for _ in range(max_iters):
+        outside = a > s
+        n_out = int(np.count_nonzero(outside))
+        if n_out == 0:
+            break
+        n_in = int(np.count_nonzero((a > 0.0) & (a <= s)))
+        nxt = float(np.sum(a[outside]) / (c * n_in + n_out))
+        if nxt == s:
+            break
+        s = nxt
+    return s
+
+
 def int_matmul(a_q, w_q) -> np.ndarray:
     """Integer GEMM acc[m, j] = sum_k a_q[m, k] * w_q[j, k] (weights stored [out, in]).
 

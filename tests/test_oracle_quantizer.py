@@ -111,3 +111,81 @@ def test_int_matmul_extreme_values_exact():
     a = rng.integers(-128, 128, (64, K), dtype=np.int8)
     w = rng.integers(-128, 128, (32, K), dtype=np.int8)
     assert np.array_equal(int_matmul(a, w).astype(np.int64), a.astype(np.int64) @ w.astype(np.int64).T)
+
+
+# ---------------------------------------------------------------- optimal clipping scalar
+def _heavy_tailed(seed, n=60000, n_big=40, gain=9.0):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal(n)
+    x[rng.choice(n, n_big, replace=False)] *= gain
+    return x.astype(np.float32)
+
+
+def test_clip_model_matches_measured_rounding_and_clipping_error():
+    """The noise model behind the clipping optimisation (Section 5.1, enhanced variant): rounding
+    noise of a 2^bits-level grid over [-s, s] plus the squared overshoot of clipped values,
+    against the error of actually rounding and clipping."""
+    from oracle import clip_mse_model
+    rng = np.random.default_rng(5)
+    for bits, s in ((8, 2.0), (6, 3.5), (4, 1.0)):
+        x = rng.uniform(-1.4 * s, 1.4 * s, 400000)
+        step = 2.0 * s / 2 ** bits
+        xq = np.clip(np.rint(x / step) * step, -s, s)
+        measured = float(np.sum((x - xq) ** 2))
+        assert clip_mse_model(x, s, bits) == pytest.approx(measured, rel=0.02)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_optimal_clip_minimises_the_model(seed):
+    from oracle import clip_mse_model, optimal_clip
+    x = _heavy_tailed(seed)
+    s = optimal_clip(x)
+    a = np.abs(x.astype(np.float64))
+    assert a.mean() < s < a.max()
+    grid = np.linspace(0.05 * a.max(), a.max(), 3000)
+    j = np.array([clip_mse_model(x, g) for g in grid])
+    best = grid[np.argmin(j)]
+    assert abs(s - best) <= 2 * (grid[1] - grid[0])
+    assert clip_mse_model(x, s) <= j.min() * (1 + 1e-9)
+    # every percentile of the paper's sweep (Table "percentiles") is a clip the model rates no better
+    for p in (99.0, 99.9, 99.99, 99.999, 100.0):
+        assert clip_mse_model(x, s) <= clip_mse_model(x, percentile_max(x, p)) * (1 + 1e-9)
+
+
+def test_optimal_clip_two_level_closed_form():
+    """n_in values of magnitude 1 and one value of magnitude M: the stationary point is
+    M / (4^-bits / 3 * n_in + 1), reached from the mean in a few updates."""
+    from oracle import optimal_clip
+    n_in, M = 1000, 100.0
+    x = np.concatenate([np.ones(n_in), [-M]])
+    for bits in (8, 4):
+        c = 4.0 ** (-bits) / 3.0
+        assert optimal_clip(x, bits=bits) == pytest.approx(M / (c * n_in + 1.0), rel=1e-12)
+
+
+def test_optimal_clip_degenerate_inputs():
+    from oracle import optimal_clip
+    assert optimal_clip(np.zeros(17)) == 0.0
+    assert optimal_clip(np.array([])) == 0.0
+    assert optimal_clip(np.full(33, -2.5)) == 2.5       # nothing lies outside the mean
+    x = _heavy_tailed(3)
+    assert optimal_clip(x, max_iters=64) == optimal_clip(x, max_iters=32)  # converged well before
+
+
+def test_calibrate_with_optimal_clip_changes_only_the_x_scale():
+    from oracle import calibrate, fp_forward, optimal_clip
+    import workloads
+    cfg = workloads.tiny_config()
+    w = workloads.make_weights(cfg)
+    cu = workloads.make_calibration(cfg)
+    _, sp = calibrate(w, cu)
+    _, sm = calibrate(w, cu, x_clip="mse")
+    x = fp_forward(w, cu)["x"]
+    assert float(sm["s_x"]) == pytest.approx(optimal_clip(np.asarray(x, np.float64).astype(np.float32)) / 127.0, rel=1e-6)
+    for k in sp:
+        if k in ("s_x", "inv_s_x", "m_x_dt", "m_x_B", "m_x_C"):
+            assert sp[k] != sm[k]
+        else:
+            assert sp[k] == sm[k]
+    with pytest.raises(ValueError):
+        calibrate(w, cu, x_clip="other")
