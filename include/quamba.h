@@ -133,6 +133,34 @@ int quamba_calibrate(const quamba_dims *dims, const quamba_fp_weights *w,
                      quamba_qweights *out_q, quamba_scales *out_s /* host */,
                      void *ws, size_t ws_bytes, void *stream);
 
+/* Calibration with a choice of rule for the scale of the scan input x.  Section 5.1 mentions,
+ * next to the percentile, a clipping optimisation as the enhanced variant and Table "percentiles"
+ * sets the two side by side; the paper cites the algorithm without printing it and does not say
+ * which tensors it clips, so here it replaces the percentile for x only:
+ *   QUAMBA_X_PERCENTILE  s_x = percentile maximum / 127 (what quamba_calibrate does)
+ *   QUAMBA_X_MSE_CLIP    s_x = c / 127 with c the scalar minimising
+ *                        (4^-8 / 3) c^2 #{0 < |x| <= c} + sum_{|x| > c} (|x| - c)^2
+ *                        (rounding noise inside the clip + overshoot outside), see quamba_clip_search;
+ *                        x_percentile is checked but not used.
+ * Everything else is as in quamba_calibrate. */
+#define QUAMBA_X_PERCENTILE 0
+#define QUAMBA_X_MSE_CLIP 1
+int quamba_calibrate_x_rule(const quamba_dims *dims, const quamba_fp_weights *w,
+                            const quamba_half *calib_u, int nb, int Lc, int x_rule, double x_percentile,
+                            quamba_qweights *out_q, quamba_scales *out_s /* host */,
+                            void *ws, size_t ws_bytes, void *stream);
+
+/* The clipping scalar of QUAMBA_X_MSE_CLIP for any fp32 device array x[0, n), for a quantizer of
+ * `bits` bits (2..16): starting from c = mean|x|, repeat
+ *   c <- sum(|x| : |x| > c) / (4^-bits / 3 * #{0 < |x| <= c} + #{|x| > c})
+ * until c stops changing, nothing lies outside c, or max_iters (1..1024) updates were made; sums
+ * in fp64, added in a fixed order (same result on every run).  Writes c (0 for an all-zero
+ * array) and, if iters_out is not NULL, the number of updates made, both HOST memory;
+ * synchronises the stream.  Workspace: quamba_clip_search_workspace_bytes(), 256-byte aligned. */
+size_t quamba_clip_search_workspace_bytes(void);
+int quamba_clip_search(const float *x, size_t n, int bits, int max_iters, double *clip_out /* host */,
+                       int *iters_out /* host, may be NULL */, void *ws, size_t ws_bytes, void *stream);
+
 /* Quantized mixer over whole sequences, starting from an empty conv history (Sections 4.2,
  * 4.3): quantize u -> int8 in_proj -> int8 causal conv + SiLU -> int8 x_proj, dt_proj ->
  * selective scan (int8 in, fp32 state, SiLU(z) gate, fp16 out) -> Hadamard + quantize ->

@@ -19,7 +19,10 @@ __all__ = [
     "quamba_scan_prefill", "quamba_scan_prefill_dtproj", "quamba_scan_step", "quamba_hadamard_quant",
     "Layer", "Model", "make_model", "quamba_model_workspace_bytes", "quamba_model_prefill", "quamba_model_decode",
     "quamba_model_generate", "quamba_calibrate_block", "quamba_embed", "quamba_final_norm", "quamba_lm_head", "quamba_argmax",
+    "X_PERCENTILE", "X_MSE_CLIP", "quamba_calibrate_x_rule", "quamba_clip_search_workspace_bytes", "quamba_clip_search",
 ]
+
+X_PERCENTILE, X_MSE_CLIP = 0, 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
@@ -202,6 +205,13 @@ def lib():
     for name in ("quamba_model_prefill", "quamba_model_decode", "quamba_model_generate", "quamba_embed",
                  "quamba_final_norm", "quamba_lm_head", "quamba_argmax"):
         getattr(L, name).restype = C.c_int
+    L.quamba_calibrate_x_rule.argtypes = [P(Dims), P(FpWeights), vp, i, i, i, C.c_double, P(QWeights), P(Scales), vp,
+                                          sz, vp]
+    L.quamba_clip_search_workspace_bytes.restype = sz
+    L.quamba_clip_search_workspace_bytes.argtypes = []
+    L.quamba_clip_search.argtypes = [vp, sz, i, i, P(C.c_double), P(C.c_int), vp, sz, vp]
+    for name in ("quamba_calibrate_x_rule", "quamba_clip_search"):
+        getattr(L, name).restype = C.c_int
     for name in ("quamba_calibrate", "quamba_mixer_prefill", "quamba_mixer_prefill_q", "quamba_mixer_decode",
                  "quamba_mixer_decode_q", "quamba_add_rmsnorm_quant", "quamba_quantize_f16", "quamba_gemm_i8",
                  "quamba_conv_silu_quant", "quamba_conv_step", "quamba_scan_prefill", "quamba_scan_step",
@@ -240,6 +250,28 @@ def quamba_calibrate(dims, fp_weights, calib_u, nb, Lc, x_percentile, out_q, ws,
     _check(lib().quamba_calibrate(C.byref(_dims(dims)), C.byref(fw), _ptr(calib_u), nb, Lc, float(x_percentile),
                                   C.byref(oq), C.byref(sc), _ptr(ws), _nbytes(ws), _stream(stream)))
     return sc
+
+
+def quamba_calibrate_x_rule(dims, fp_weights, calib_u, nb, Lc, x_rule, x_percentile, out_q, ws, stream=None) -> Scales:
+    fw = _struct_of_ptrs(FpWeights, fp_weights)
+    oq = _struct_of_ptrs(QWeights, out_q)
+    sc = Scales()
+    _check(lib().quamba_calibrate_x_rule(C.byref(_dims(dims)), C.byref(fw), _ptr(calib_u), nb, Lc, int(x_rule),
+                                         float(x_percentile), C.byref(oq), C.byref(sc), _ptr(ws), _nbytes(ws),
+                                         _stream(stream)))
+    return sc
+
+
+def quamba_clip_search_workspace_bytes() -> int:
+    return int(lib().quamba_clip_search_workspace_bytes())
+
+
+def quamba_clip_search(x, n, bits, max_iters, ws, stream=None):
+    """Returns (clip, updates made)."""
+    clip, iters = C.c_double(0.0), C.c_int(0)
+    _check(lib().quamba_clip_search(_ptr(x), n, bits, max_iters, C.byref(clip), C.byref(iters), _ptr(ws), _nbytes(ws),
+                                    _stream(stream)))
+    return clip.value, iters.value
 
 
 def _taps(t):

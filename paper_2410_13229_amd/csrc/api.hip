@@ -9,8 +9,11 @@ namespace quamba {
 // calibrate.hip
 size_t calibrate_workspace_bytes(const quamba_dims *d, int nb, int Lc);
 int calibrate(const quamba_dims *d, const quamba_fp_weights *w, const __half *calib_u, int nb, int Lc,
-              double x_percentile, quamba_qweights *oq, quamba_scales *os, void *ws, size_t ws_bytes,
+              int x_rule, double x_percentile, quamba_qweights *oq, quamba_scales *os, void *ws, size_t ws_bytes,
               hipStream_t st, float *out_f32);
+size_t clip_search_workspace_bytes();
+int clip_search(const float *x, size_t n, int bits, int max_iters, double *clip_out, int *iters_out, void *ws,
+                size_t ws_bytes, hipStream_t st);
 int calibrate_block(const quamba_dims *d, const quamba_fp_weights *w, const __half *norm_w, float eps, float *res,
                     float *out, int nb, int Lc, double x_percentile, quamba_qweights *oq, quamba_scales *os, void *ws,
                     size_t ws_bytes, hipStream_t st);
@@ -213,6 +216,24 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
   return QUAMBA_OK;
 }
 
+int check_calibrate_args(const quamba_dims *dims, const quamba_fp_weights *w, const quamba_qweights *out_q,
+                         const quamba_scales *out_s, const void *ws, int nb, int Lc, double x_percentile) {
+  QUAMBA_TRY(check_dims(dims));
+  if (!w || !out_q || !out_s || !ws) return fail(QUAMBA_EINVAL, "calibrate: NULL pointer");
+  if (!w->W_in || !w->conv_w || !w->conv_b || !w->W_x || !w->W_dt || !w->dt_bias || !w->A_log || !w->D ||
+      !w->W_out)
+    return fail(QUAMBA_EINVAL, "calibrate: a master weight pointer is NULL");
+  if (!out_q->W_in || !out_q->conv_w || !out_q->W_x || !out_q->W_dt || !out_q->A || !out_q->D ||
+      !out_q->W_outH || !out_q->conv_b || !out_q->dt_bias)
+    return fail(QUAMBA_EINVAL, "calibrate: an output weight pointer is NULL");
+  if (nb < 1 || Lc < 1) return fail(QUAMBA_EINVAL, "calibrate: nb=%d Lc=%d", nb, Lc);
+  if (!(x_percentile > 0.0 && x_percentile <= 100.0))
+    return fail(QUAMBA_EINVAL, "calibrate: percentile %g outside (0, 100]", x_percentile);
+  if (!aligned(ws, 256) || !aligned(w->W_out, 16))
+    return fail(QUAMBA_EINVAL, "calibrate: workspace must be 256-byte aligned, W_out 16-byte");
+  return QUAMBA_OK;
+}
+
 }  // namespace
 
 size_t mixer_workspace_bytes(const quamba_dims *d, int Bt, int L) { return make_plan(d, Bt, L).total; }
@@ -252,42 +273,41 @@ size_t quamba_calibrate_workspace_bytes(const quamba_dims *dims, int nb, int Lc)
   return calibrate_workspace_bytes(dims, nb, Lc);
 }
 
+int quamba_calibrate_x_rule(const quamba_dims *dims, const quamba_fp_weights *w, const quamba_half *calib_u, int nb,
+                            int Lc, int x_rule, double x_percentile, quamba_qweights *out_q, quamba_scales *out_s,
+                            void *ws, size_t ws_bytes, void *stream) {
+  QUAMBA_TRY(check_calibrate_args(dims, w, out_q, out_s, ws, nb, Lc, x_percentile));
+  if (!calib_u) return fail(QUAMBA_EINVAL, "calibrate: NULL pointer");
+  if (x_rule != QUAMBA_X_PERCENTILE && x_rule != QUAMBA_X_MSE_CLIP)
+    return fail(QUAMBA_EINVAL, "calibrate: unknown x_rule %d", x_rule);
+  return calibrate(dims, w, reinterpret_cast<const __half *>(calib_u), nb, Lc, x_rule, x_percentile, out_q, out_s, ws,
+                   ws_bytes, as_stream(stream), nullptr);
+}
+
 int quamba_calibrate(const quamba_dims *dims, const quamba_fp_weights *w, const quamba_half *calib_u, int nb,
                      int Lc, double x_percentile, quamba_qweights *out_q, quamba_scales *out_s, void *ws,
                      size_t ws_bytes, void *stream) {
-  QUAMBA_TRY(check_dims(dims));
-  if (!w || !calib_u || !out_q || !out_s || !ws) return fail(QUAMBA_EINVAL, "calibrate: NULL pointer");
-  if (!w->W_in || !w->conv_w || !w->conv_b || !w->W_x || !w->W_dt || !w->dt_bias || !w->A_log || !w->D ||
-      !w->W_out)
-    return fail(QUAMBA_EINVAL, "calibrate: a master weight pointer is NULL");
-  if (!out_q->W_in || !out_q->conv_w || !out_q->W_x || !out_q->W_dt || !out_q->A || !out_q->D ||
-      !out_q->W_outH || !out_q->conv_b || !out_q->dt_bias)
-    return fail(QUAMBA_EINVAL, "calibrate: an output weight pointer is NULL");
-  if (nb < 1 || Lc < 1) return fail(QUAMBA_EINVAL, "calibrate: nb=%d Lc=%d", nb, Lc);
-  if (!(x_percentile > 0.0 && x_percentile <= 100.0))
-    return fail(QUAMBA_EINVAL, "calibrate: percentile %g outside (0, 100]", x_percentile);
-  if (!aligned(ws, 256) || !aligned(w->W_out, 16))
-    return fail(QUAMBA_EINVAL, "calibrate: workspace must be 256-byte aligned, W_out 16-byte");
-  return calibrate(dims, w, reinterpret_cast<const __half *>(calib_u), nb, Lc, x_percentile, out_q, out_s, ws,
-                   ws_bytes, as_stream(stream), nullptr);
+  return quamba_calibrate_x_rule(dims, w, calib_u, nb, Lc, QUAMBA_X_PERCENTILE, x_percentile, out_q, out_s, ws,
+                                 ws_bytes, stream);
+}
+
+size_t quamba_clip_search_workspace_bytes(void) { return clip_search_workspace_bytes(); }
+
+int quamba_clip_search(const float *x, size_t n, int bits, int max_iters, double *clip_out, int *iters_out, void *ws,
+                       size_t ws_bytes, void *stream) {
+  if (!x || !clip_out || !ws) return fail(QUAMBA_EINVAL, "clip_search: NULL pointer");
+  if (n < 1 || bits < 2 || bits > 16 || max_iters < 1 || max_iters > 1024)
+    return fail(QUAMBA_EINVAL, "clip_search: n=%zu bits=%d max_iters=%d", n, bits, max_iters);
+  if (!aligned(ws, 256)) return fail(QUAMBA_EINVAL, "clip_search: workspace must be 256-byte aligned");
+  return clip_search(x, n, bits, max_iters, clip_out, iters_out, ws, ws_bytes, as_stream(stream));
 }
 
 int quamba_calibrate_block(const quamba_dims *dims, const quamba_fp_weights *w, const quamba_half *norm_w, float eps,
                            float *res, float *out, int nb, int Lc, double x_percentile, quamba_qweights *out_q,
                            quamba_scales *out_s, void *ws, size_t ws_bytes, void *stream) {
-  QUAMBA_TRY(check_dims(dims));
-  if (!w || !norm_w || !res || !out || !out_q || !out_s || !ws) return fail(QUAMBA_EINVAL, "calibrate: NULL pointer");
-  if (!w->W_in || !w->conv_w || !w->conv_b || !w->W_x || !w->W_dt || !w->dt_bias || !w->A_log || !w->D ||
-      !w->W_out)
-    return fail(QUAMBA_EINVAL, "calibrate: a master weight pointer is NULL");
-  if (!out_q->W_in || !out_q->conv_w || !out_q->W_x || !out_q->W_dt || !out_q->A || !out_q->D ||
-      !out_q->W_outH || !out_q->conv_b || !out_q->dt_bias)
-    return fail(QUAMBA_EINVAL, "calibrate: an output weight pointer is NULL");
-  if (nb < 1 || Lc < 1) return fail(QUAMBA_EINVAL, "calibrate: nb=%d Lc=%d", nb, Lc);
-  if (!(x_percentile > 0.0 && x_percentile <= 100.0))
-    return fail(QUAMBA_EINVAL, "calibrate: percentile %g outside (0, 100]", x_percentile);
-  if (!aligned(ws, 256) || !aligned(w->W_out, 16) || !aligned(res, 16) || !aligned(out, 16))
-    return fail(QUAMBA_EINVAL, "calibrate: workspace must be 256-byte aligned, W_out, res and out 16-byte");
+  QUAMBA_TRY(check_calibrate_args(dims, w, out_q, out_s, ws, nb, Lc, x_percentile));
+  if (!norm_w || !res || !out) return fail(QUAMBA_EINVAL, "calibrate: NULL pointer");
+  if (!aligned(res, 16) || !aligned(out, 16)) return fail(QUAMBA_EINVAL, "calibrate: res and out must be 16-byte aligned");
   return calibrate_block(dims, w, reinterpret_cast<const __half *>(norm_w), eps, res, out, nb, Lc, x_percentile, out_q,
                          out_s, ws, ws_bytes, as_stream(stream));
 }

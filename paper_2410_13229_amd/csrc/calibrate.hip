@@ -172,6 +172,94 @@ __global__ void select_hist_kernel(const float *__restrict__ x, size_t n, unsign
   if (local[threadIdx.x]) atomicAdd(&hist[threadIdx.x], (unsigned long long)local[threadIdx.x]);
 }
 
+// ---------------------------------------------------------------- model-optimal clipping scalar
+// Section 5.1 names a clipping optimisation as the enhanced variant; the rule is the stationary
+// point of (4^-bits / 3) s^2 #{0 < |x| <= s} + sum_{|x| > s} (|x| - s)^2, iterated as
+//   s <- sum(|x| : |x| > s) / (4^-bits / 3 * #{0 < |x| <= s} + #{|x| > s}).
+// One pass gathers the three sums per workgroup, a one-workgroup pass adds them in a fixed order
+// (same result on every run) and moves s.  state[0] = s, state[1] = updates made, state[2] = done.
+struct ClipPart {
+  double sum_out;
+  unsigned long long n_out, n_in;
+};
+constexpr int CLIP_BLOCKS = 1024;
+
+__global__ __launch_bounds__(256) void clip_stats_kernel(const float *__restrict__ x, size_t n,
+                                                         const double *__restrict__ state, ClipPart *parts) {
+  const double s = state[0];
+  double sum = 0.0;
+  unsigned long long n_out = 0, n_in = 0;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+    const double a = static_cast<double>(fabsf(x[i]));
+    if (a > s) {
+      sum += a;
+      ++n_out;
+    } else if (a > 0.0) {
+      ++n_in;
+    }
+  }
+  __shared__ ClipPart part[256];
+  part[threadIdx.x] = ClipPart{sum, n_out, n_in};
+  __syncthreads();
+  for (int off = 128; off > 0; off >>= 1) {
+    if ((int)threadIdx.x < off) {
+      part[threadIdx.x].sum_out += part[threadIdx.x + off].sum_out;
+      part[threadIdx.x].n_out += part[threadIdx.x + off].n_out;
+      part[threadIdx.x].n_in += part[threadIdx.x + off].n_in;
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) parts[blockIdx.x] = part[0];
+}
+
+__global__ __launch_bounds__(256) void clip_update_kernel(const ClipPart *__restrict__ parts, int nparts, double c,
+                                                          int first, double *state) {
+  __shared__ ClipPart part[256];
+  ClipPart acc{0.0, 0, 0};
+  for (int i = threadIdx.x; i < nparts; i += 256) {
+    acc.sum_out += parts[i].sum_out;
+    acc.n_out += parts[i].n_out;
+    acc.n_in += parts[i].n_in;
+  }
+  part[threadIdx.x] = acc;
+  __syncthreads();
+  for (int off = 128; off > 0; off >>= 1) {
+    if ((int)threadIdx.x < off) {
+      part[threadIdx.x].sum_out += part[threadIdx.x + off].sum_out;
+      part[threadIdx.x].n_out += part[threadIdx.x + off].n_out;
+      part[threadIdx.x].n_in += part[threadIdx.x + off].n_in;
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x != 0 || state[2] != 0.0) return;
+  const ClipPart t = part[0];
+  if (first) {  // the start value: every element counts as outside, which makes the quotient mean |x|
+    state[0] = t.n_out ? t.sum_out / static_cast<double>(t.n_out) : 0.0;
+    return;
+  }
+  if (t.n_out == 0) {
+    state[2] = 1.0;
+    return;
+  }
+  const double nxt = t.sum_out / (c * static_cast<double>(t.n_in) + static_cast<double>(t.n_out));
+  if (nxt == state[0]) {
+    state[2] = 1.0;
+    return;
+  }
+  state[0] = nxt;
+  state[1] += 1.0;
+}
+
+__global__ void clip_init_kernel(double *state) {
+  if (threadIdx.x == 0) {
+    state[0] = -1.0;  // below every |x|
+    state[1] = 0.0;
+    state[2] = 0.0;
+  }
+}
+
+constexpr size_t CLIP_WS_BYTES = 256 + CLIP_BLOCKS * sizeof(ClipPart);
+
 __global__ void quantize_f32_kernel(const float *__restrict__ x, int8_t *__restrict__ q, size_t n, float inv_s) {
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= n) return;
@@ -188,7 +276,7 @@ __global__ void copy_f32_kernel(const float *x, float *y, size_t n) {
 inline unsigned nblk(size_t n) { return (unsigned)((n + 255) / 256); }
 
 struct CalPlan {
-  size_t u32, xz, x, dbc, dtr, g, gH, woh, a, slots, hist, total;
+  size_t u32, xz, x, dbc, dtr, g, gH, woh, a, slots, hist, clip, total;
 };
 
 CalPlan cal_plan(const quamba_dims *d, int nb, int Lc) {
@@ -211,6 +299,7 @@ CalPlan cal_plan(const quamba_dims *d, int nb, int Lc) {
   p.a = take(Di * d->d_state * 4);
   p.slots = take(32 * 4);
   p.hist = take(256 * 8);
+  p.clip = take(CLIP_WS_BYTES);
   p.total = off;
   return p;
 }
@@ -221,8 +310,33 @@ enum Slot { S_U, S_XPRE, S_Z, S_DTL, S_B, S_C, S_DT, S_Y, S_WIN, S_CW, S_WX, S_W
 
 size_t calibrate_workspace_bytes(const quamba_dims *d, int nb, int Lc) { return cal_plan(d, nb, Lc).total; }
 
+size_t clip_search_workspace_bytes() { return CLIP_WS_BYTES; }
+
+// Runs the fixed-point iteration above on x[0, n) and returns the scalar and the number of updates
+// on the host (synchronises the stream).
+int clip_search(const float *x, size_t n, int bits, int max_iters, double *clip_out, int *iters_out, void *ws,
+                size_t ws_bytes, hipStream_t st) {
+  if (ws_bytes < CLIP_WS_BYTES) return fail(QUAMBA_EWORKSPACE, "clip_search: workspace %zu < %zu", ws_bytes, CLIP_WS_BYTES);
+  double *state = static_cast<double *>(ws);
+  ClipPart *parts = reinterpret_cast<ClipPart *>(static_cast<char *>(ws) + 256);
+  const double c = std::pow(4.0, -static_cast<double>(bits)) / 3.0;
+  const int blocks = (int)std::min<size_t>(std::max<size_t>((n + 255) / 256, 1), CLIP_BLOCKS);
+  hipLaunchKernelGGL(clip_init_kernel, dim3(1), dim3(64), 0, st, state);
+  for (int it = 0; it <= max_iters; ++it) {  // pass 0 produces the start value
+    hipLaunchKernelGGL(clip_stats_kernel, dim3(blocks), dim3(256), 0, st, x, n, state, parts);
+    hipLaunchKernelGGL(clip_update_kernel, dim3(1), dim3(256), 0, st, parts, blocks, c, it == 0 ? 1 : 0, state);
+    QUAMBA_LAUNCH_CHECK();
+  }
+  double h[3];
+  QUAMBA_HIP(hipMemcpyAsync(h, state, sizeof(h), hipMemcpyDeviceToHost, st));
+  QUAMBA_HIP(hipStreamSynchronize(st));
+  *clip_out = h[0];
+  if (iters_out) *iters_out = static_cast<int>(h[1]);
+  return QUAMBA_OK;
+}
+
 int calibrate(const quamba_dims *d, const quamba_fp_weights *w, const __half *calib_u, int nb, int Lc,
-              double x_percentile, quamba_qweights *oq, quamba_scales *os, void *ws, size_t ws_bytes,
+              int x_rule, double x_percentile, quamba_qweights *oq, quamba_scales *os, void *ws, size_t ws_bytes,
               hipStream_t st, float *out_f32);
 
 namespace {
@@ -258,14 +372,14 @@ int calibrate_block(const quamba_dims *d, const quamba_fp_weights *w, const __ha
   hipLaunchKernelGGL(add_rmsnorm_f32_kernel, dim3((unsigned)((size_t)nb * Lc)), dim3(256), 0, st, res, out, norm_w, eps,
                      d->d_model, u32);
   QUAMBA_LAUNCH_CHECK();
-  return calibrate(d, w, nullptr, nb, Lc, x_percentile, oq, os, ws, ws_bytes, st, out);
+  return calibrate(d, w, nullptr, nb, Lc, QUAMBA_X_PERCENTILE, x_percentile, oq, os, ws, ws_bytes, st, out);
 }
 
 // calib_u == nullptr: the fp32 block input is already in the workspace's own input buffer
 // (calibrate_block puts it there).  out_f32 != nullptr: also receives the unquantized block output
 // g W_out^T, which feeds the next block of a stack.
 int calibrate(const quamba_dims *d, const quamba_fp_weights *w, const __half *calib_u, int nb, int Lc,
-              double x_percentile, quamba_qweights *oq, quamba_scales *os, void *ws, size_t ws_bytes,
+              int x_rule, double x_percentile, quamba_qweights *oq, quamba_scales *os, void *ws, size_t ws_bytes,
               hipStream_t st, float *out_f32) {
   const CalPlan p = cal_plan(d, nb, Lc);
   if (ws_bytes < p.total) return fail(QUAMBA_EWORKSPACE, "calibrate: workspace %zu < %zu", ws_bytes, p.total);
@@ -316,9 +430,15 @@ int calibrate(const quamba_dims *d, const quamba_fp_weights *w, const __half *ca
   QUAMBA_HIP(hipMemcpyAsync(mx, slots, sizeof(mx), hipMemcpyDeviceToHost, st));
   QUAMBA_HIP(hipStreamSynchronize(st));
 
+  const size_t nx = M * Di;
+  float xp;
+  if (x_rule == QUAMBA_X_MSE_CLIP) {
+    double clip;
+    if ((rc = clip_search(x, nx, 8, 32, &clip, nullptr, base + p.clip, CLIP_WS_BYTES, st))) return rc;
+    xp = static_cast<float>(clip);
+  } else {
   // percentile maximum of |x| (Section 4.2): value of 1-based rank ceil(p/100 * n), found by a
   // most-significant-byte-first radix select on the bit patterns
-  const size_t nx = M * Di;
   size_t rank = (size_t)std::ceil(x_percentile * (double)nx / 100.0);
   if (rank < 1) rank = 1;
   if (rank > nx) rank = nx;
@@ -343,8 +463,8 @@ int calibrate(const quamba_dims *d, const quamba_fp_weights *w, const __half *ca
     prefix |= (unsigned)byte << shift;
     mask |= 0xffu << shift;
   }
-  float xp;
   std::memcpy(&xp, &prefix, 4);
+  }
 
   auto sc_of = [](float m) { return m > 0.f ? (float)((double)m / 127.0) : 1.0f; };
   quamba_scales s{};

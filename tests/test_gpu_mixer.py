@@ -308,6 +308,29 @@ def test_calibrate_matches_oracle(name):
             assert np.array_equal(got, v), k
 
 
+def test_calibrate_with_mse_clip_matches_oracle():
+    """Section 5.1, enhanced variant: the scale of the scan input from the model-optimal clipping
+    scalar instead of the percentile; every other scale is the one the percentile run gives."""
+    cfg = W.tiny_config(name="tc", d_model=64, d_inner=192, dt_rank=16, config_id=99)
+    w = W.make_weights(cfg, randomize_bias=True)
+    calib = W.make_calibration(cfg)
+    qw_ref, sc_ref = O.calibrate(w, calib, x_clip="mse")
+    _, sc_pct = O.calibrate(w, calib)
+    assert float(sc_ref["s_x"]) != float(sc_pct["s_x"])
+    fw = {k: dev(v) for k, v in w.items()}
+    out_q = {k: torch.zeros(v.shape, dtype=torch.int8 if v.dtype == np.int8 else torch.float32, device="cuda:0")
+             for k, v in qw_ref.items()}
+    nb, Lc = calib.shape[:2]
+    ws = workspace(Q.quamba_calibrate_workspace_bytes(cfg, nb, Lc))
+    sc = Q.scales_to_dict(Q.quamba_calibrate_x_rule(cfg, fw, dev(calib), nb, Lc, Q.X_MSE_CLIP, 99.999, out_q, ws))
+    for k in Q.SCALE_FIELDS:
+        # x on the GPU is an fp32 forward, the oracle's an fp64 one: the clip moves with the few values near it
+        tol = 2e-3 if k in ("s_x", "inv_s_x", "m_x_dt", "m_x_B", "m_x_C") else 1e-4
+        assert abs(sc[k] - float(sc_ref[k])) <= tol * abs(float(sc_ref[k])), (k, sc[k], float(sc_ref[k]))
+    with pytest.raises(Q.QuambaError):
+        Q.quamba_calibrate_x_rule(cfg, fw, dev(calib), nb, Lc, 7, 99.999, out_q, ws)
+
+
 def test_decode_steps_replayed_from_a_hip_graph():
     """The decode call enqueues kernel launches only, so a caller may capture it.  Several replays,
     with eager work and synchronisations in between, must each reproduce the eager result bit for bit."""

@@ -292,3 +292,37 @@ def test_add_rmsnorm_quant(M, Dm):
     Q.quamba_add_rmsnorm_quant(dev(a), dres, dev(wt), 1e-5, inv, q, M, Dm)
     assert np.array_equal(host(dres).view(np.uint16), res_ref.view(np.uint16))
     assert_lsb(host(q), q_ref, "u_q")
+
+
+# ------------------------------------------------------------------ clipping scalar search
+@pytest.mark.parametrize("n,bits", [(1, 8), (255, 8), (70001, 8), (1 << 20, 8), (300007, 4)])
+def test_clip_search_matches_oracle(n, bits):
+    """Section 5.1 (enhanced variant): the fixed point of the clipping-scalar iteration, against
+    the oracle on heavy-tailed data, at sizes below one workgroup, ragged, and beyond the grid."""
+    rng = np.random.default_rng(n + bits)
+    x = rng.standard_normal(n).astype(np.float32)
+    if n > 100:
+        x[rng.choice(n, max(n // 2000, 1), replace=False)] *= np.float32(11.0)
+    want = O.optimal_clip(x, bits=bits)
+    ws = workspace(Q.quamba_clip_search_workspace_bytes())
+    got, iters = Q.quamba_clip_search(dev(x), n, bits, 32, ws)
+    assert got == pytest.approx(want, rel=1e-12), (got, want)
+    assert 0 <= iters <= 32
+    again, _ = Q.quamba_clip_search(dev(x), n, bits, 32, ws)
+    assert again == got  # fixed summation order
+
+
+def test_clip_search_degenerate_and_errors():
+    ws = workspace(Q.quamba_clip_search_workspace_bytes())
+    z = torch.zeros(1000, dtype=torch.float32, device="cuda:0")
+    assert Q.quamba_clip_search(z, 1000, 8, 32, ws) == (0.0, 0)
+    c = torch.full((777,), -2.5, dtype=torch.float32, device="cuda:0")
+    assert Q.quamba_clip_search(c, 777, 8, 32, ws) == (2.5, 0)
+    x = dev(np.arange(1, 50001, dtype=np.float32))
+    one, it1 = Q.quamba_clip_search(x, 50000, 8, 1, ws)
+    assert it1 == 1 and one == pytest.approx(O.optimal_clip(host(x), max_iters=1), rel=1e-12)
+    for bad in (dict(n=0), dict(bits=1), dict(bits=17), dict(iters=0)):
+        with pytest.raises(Q.QuambaError):
+            Q.quamba_clip_search(x, bad.get("n", 10), bad.get("bits", 8), bad.get("iters", 4), ws)
+    with pytest.raises(Q.QuambaError):
+        Q.quamba_clip_search(x, 10, 8, 4, workspace(256))
