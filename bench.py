@@ -119,6 +119,46 @@ def bench_model(args, Q, W, torch, np, dev, to_dev):
     return out
 
 
+def bench_x_scale_rules(Q, W, torch, np, dev, to_dev, stream):
+    """Table "percentiles" on synthetic weights: relative error of the quantized mixer against the
+    unquantized fp32 one (both on the GPU) for the percentile sweep and the clipping optimisation
+    (Section 5.1), at the 2.8B layer shape with a few far-reaching scan-input channels and no
+    outlier channels in the hidden input, so the scale of x decides the error."""
+    import dataclasses
+    cfg = dataclasses.replace(W.CONFIGS["c1"], name="c1x", config_id=78, outlier_gain=1.0)
+    Dm, Di, N, R = cfg.d_model, cfg.d_inner, cfg.d_state, cfg.dt_rank
+    NX, L = R + 2 * N, 1024
+    w = W.make_weights(cfg, x_outlier_rows=8, x_outlier_gain=8.0)
+    fw = {k: to_dev(v) for k, v in w.items()}
+    calib = to_dev(W.make_calibration(cfg))
+    nb, Lc = calib.shape[:2]
+    u = to_dev(W.make_hidden(cfg, batch=1, seqlen=L, stream=5))
+    shapes = {"W_in": (2 * Di, Dm), "conv_w": (Di, 4), "W_x": (NX, Di), "W_dt": (Di, R), "A": (Di, N), "D": (Di,),
+              "W_outH": (Dm, Di)}
+    qd = {k: torch.empty(v, dtype=torch.int8, device=dev) for k, v in shapes.items()}
+    qd["conv_b"] = torch.empty((Di,), dtype=torch.float32, device=dev)
+    qd["dt_bias"] = torch.empty((Di,), dtype=torch.float32, device=dev)
+    cws = torch.empty(max(Q.quamba_calibrate_workspace_bytes(cfg, nb, Lc), Q.quamba_calibrate_workspace_bytes(cfg, 1, L)),
+                      dtype=torch.uint8, device=dev)
+    ref = torch.empty((L, Dm), dtype=torch.float32, device=dev)
+    Q.quamba_mixer_fp32(cfg, fw, u, 1, L, ref, cws, stream)
+    out = torch.empty((1, L, Dm), dtype=torch.float16, device=dev)
+    ws = torch.empty(Q.quamba_workspace_bytes(cfg, 1, L), dtype=torch.uint8, device=dev)
+    res = {}
+    for name, rule, p in (("p99", Q.X_PERCENTILE, 99.0), ("p99.9", Q.X_PERCENTILE, 99.9),
+                          ("p99.99", Q.X_PERCENTILE, 99.99), ("p99.999", Q.X_PERCENTILE, 99.999),
+                          ("max", Q.X_PERCENTILE, 100.0), ("mse_clip", Q.X_MSE_CLIP, 99.999)):
+        sc = Q.quamba_calibrate_x_rule(cfg, fw, calib, nb, Lc, rule, p, qd, cws, stream)
+        Q.quamba_mixer_prefill(cfg, qd, sc, u, 1, L, out, None, None, None, ws, stream)
+        torch.cuda.synchronize()
+        err = (torch.linalg.vector_norm(out.reshape(L, Dm).double() - ref.double())
+               / torch.linalg.vector_norm(ref.double())).item()
+        res[name] = {"x_clip": round(sc.s_x * 127.0, 4), "rel_err": round(err, 5)}
+    return {"workload": "c1 shape, hidden input without outlier channels, 8 rows of the x half of W_in scaled by 8; "
+                        "calibrated on a seeded 4x256 batch, error over a fresh 1024-token sequence",
+            "rules": res}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -399,6 +439,11 @@ def main():
     if not args.no_model and args.workload == "c1":
         model = bench_model(args, Q, W, torch, np, dev, to_dev)
 
+    # ---- choice of the clipping rule for the scan input (percentile sweep, clipping optimisation)
+    x_rules = None
+    if not args.no_model and args.workload == "c1":
+        x_rules = bench_x_scale_rules(Q, W, torch, np, dev, to_dev, stream)
+
     # ---- oracle on the host cores (reported baseline, not the target)
     cpu = None
     if not args.no_cpu:
@@ -442,6 +487,7 @@ def main():
         "stages": stages,
         "decode": decode,
         "model": model,
+        "x_scale_rules": x_rules,
         "cpu_baseline": cpu,
     }
     print(json.dumps(line))

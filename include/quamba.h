@@ -150,6 +150,14 @@ int quamba_calibrate_x_rule(const quamba_dims *dims, const quamba_fp_weights *w,
                             quamba_qweights *out_q, quamba_scales *out_s /* host */,
                             void *ws, size_t ws_bytes, void *stream);
 
+/* The unquantized mixer (Section 3.1: in_proj, causal conv + SiLU, selection, selective scan,
+ * gate, out_proj) in fp32 from the fp32 master weights, each of the nb sequences of length L from
+ * an empty history: u [nb, L, Dm] fp16 in, out [nb * L, Dm] fp32.  It is what calibration observes
+ * and the reference the quantized mixer's error is measured against; plain untuned kernels.
+ * Workspace: quamba_calibrate_workspace_bytes(dims, nb, L), 256-byte aligned.  Enqueues only. */
+int quamba_mixer_fp32(const quamba_dims *dims, const quamba_fp_weights *w, const quamba_half *u, int nb,
+                      int L, float *out, void *ws, size_t ws_bytes, void *stream);
+
 /* The clipping scalar of QUAMBA_X_MSE_CLIP for any fp32 device array x[0, n), for a quantizer of
  * `bits` bits (2..16): starting from c = mean|x|, repeat
  *   c <- sum(|x| : |x| > c) / (4^-bits / 3 * #{0 < |x| <= c} + #{|x| > c})

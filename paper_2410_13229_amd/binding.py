@@ -19,7 +19,7 @@ __all__ = [
     "quamba_scan_prefill", "quamba_scan_prefill_dtproj", "quamba_scan_step", "quamba_hadamard_quant",
     "Layer", "Model", "make_model", "quamba_model_workspace_bytes", "quamba_model_prefill", "quamba_model_decode",
     "quamba_model_generate", "quamba_calibrate_block", "quamba_embed", "quamba_final_norm", "quamba_lm_head", "quamba_argmax",
-    "X_PERCENTILE", "X_MSE_CLIP", "quamba_calibrate_x_rule", "quamba_clip_search_workspace_bytes", "quamba_clip_search",
+    "X_PERCENTILE", "X_MSE_CLIP", "quamba_calibrate_x_rule", "quamba_clip_search_workspace_bytes", "quamba_clip_search", "quamba_mixer_fp32",
 ]
 
 X_PERCENTILE, X_MSE_CLIP = 0, 1
@@ -210,7 +210,8 @@ def lib():
     L.quamba_clip_search_workspace_bytes.restype = sz
     L.quamba_clip_search_workspace_bytes.argtypes = []
     L.quamba_clip_search.argtypes = [vp, sz, i, i, P(C.c_double), P(C.c_int), vp, sz, vp]
-    for name in ("quamba_calibrate_x_rule", "quamba_clip_search"):
+    L.quamba_mixer_fp32.argtypes = [P(Dims), P(FpWeights), vp, i, i, vp, vp, sz, vp]
+    for name in ("quamba_calibrate_x_rule", "quamba_clip_search", "quamba_mixer_fp32"):
         getattr(L, name).restype = C.c_int
     for name in ("quamba_calibrate", "quamba_mixer_prefill", "quamba_mixer_prefill_q", "quamba_mixer_decode",
                  "quamba_mixer_decode_q", "quamba_add_rmsnorm_quant", "quamba_quantize_f16", "quamba_gemm_i8",
@@ -260,6 +261,12 @@ def quamba_calibrate_x_rule(dims, fp_weights, calib_u, nb, Lc, x_rule, x_percent
                                          float(x_percentile), C.byref(oq), C.byref(sc), _ptr(ws), _nbytes(ws),
                                          _stream(stream)))
     return sc
+
+
+def quamba_mixer_fp32(dims, fp_weights, u, nb, L, out, ws, stream=None):
+    fw = _struct_of_ptrs(FpWeights, fp_weights)
+    _check(lib().quamba_mixer_fp32(C.byref(_dims(dims)), C.byref(fw), _ptr(u), nb, L, _ptr(out), _ptr(ws), _nbytes(ws),
+                                   _stream(stream)))
 
 
 def quamba_clip_search_workspace_bytes() -> int:

@@ -11,6 +11,8 @@ size_t calibrate_workspace_bytes(const quamba_dims *d, int nb, int Lc);
 int calibrate(const quamba_dims *d, const quamba_fp_weights *w, const __half *calib_u, int nb, int Lc,
               int x_rule, double x_percentile, quamba_qweights *oq, quamba_scales *os, void *ws, size_t ws_bytes,
               hipStream_t st, float *out_f32);
+int fp_mixer(const quamba_dims *d, const quamba_fp_weights *w, const __half *u, int nb, int Lc, float *out,
+             void *ws, size_t ws_bytes, hipStream_t st);
 size_t clip_search_workspace_bytes();
 int clip_search(const float *x, size_t n, int bits, int max_iters, double *clip_out, int *iters_out, void *ws,
                 size_t ws_bytes, hipStream_t st);
@@ -289,6 +291,18 @@ int quamba_calibrate(const quamba_dims *dims, const quamba_fp_weights *w, const 
                      size_t ws_bytes, void *stream) {
   return quamba_calibrate_x_rule(dims, w, calib_u, nb, Lc, QUAMBA_X_PERCENTILE, x_percentile, out_q, out_s, ws,
                                  ws_bytes, stream);
+}
+
+int quamba_mixer_fp32(const quamba_dims *dims, const quamba_fp_weights *w, const quamba_half *u, int nb, int L,
+                      float *out, void *ws, size_t ws_bytes, void *stream) {
+  QUAMBA_TRY(check_dims(dims));
+  if (!w || !u || !out || !ws) return fail(QUAMBA_EINVAL, "fp mixer: NULL pointer");
+  if (!w->W_in || !w->conv_w || !w->conv_b || !w->W_x || !w->W_dt || !w->dt_bias || !w->A_log || !w->D ||
+      !w->W_out)
+    return fail(QUAMBA_EINVAL, "fp mixer: a master weight pointer is NULL");
+  if (nb < 1 || L < 1) return fail(QUAMBA_EINVAL, "fp mixer: nb=%d L=%d", nb, L);
+  if (!aligned(ws, 256)) return fail(QUAMBA_EINVAL, "fp mixer: workspace must be 256-byte aligned");
+  return fp_mixer(dims, w, reinterpret_cast<const __half *>(u), nb, L, out, ws, ws_bytes, as_stream(stream));
 }
 
 size_t quamba_clip_search_workspace_bytes(void) { return clip_search_workspace_bytes(); }

@@ -306,6 +306,41 @@ CalPlan cal_plan(const quamba_dims *d, int nb, int Lc) {
 
 enum Slot { S_U, S_XPRE, S_Z, S_DTL, S_B, S_C, S_DT, S_Y, S_WIN, S_CW, S_WX, S_WDT, S_A, S_D, S_WOH, S_COUNT };
 
+struct CalBufs {
+  float *u32, *xz, *x, *dbc, *dtr, *g, *gH, *woh, *A;
+  unsigned *slots;
+  unsigned long long *hist;
+};
+
+CalBufs carve(const CalPlan &p, void *ws) {
+  char *base = static_cast<char *>(ws);
+  auto f = [&](size_t off) { return reinterpret_cast<float *>(base + off); };
+  return CalBufs{f(p.u32), f(p.xz), f(p.x), f(p.dbc), f(p.dtr), f(p.g), f(p.gH), f(p.woh), f(p.a),
+                 reinterpret_cast<unsigned *>(base + p.slots), reinterpret_cast<unsigned long long *>(base + p.hist)};
+}
+
+// The unquantized mixer up to the gated scan output (Section 3.1), fp32: leaves x_pre | z, x,
+// dt_low | B | C, dt_raw and g in the workspace.  calib_u == nullptr: the input is already in b.u32.
+int fp_forward(const quamba_dims *d, const quamba_fp_weights *w, const __half *calib_u, int nb, int Lc,
+               const CalBufs &b, hipStream_t st) {
+  const int Dm = d->d_model, Di = d->d_inner, N = d->d_state, R = d->dt_rank, NX = R + 2 * N;
+  const size_t M = (size_t)nb * Lc;
+  if (calib_u) hipLaunchKernelGGL(half_to_float_kernel, dim3(nblk(M * Dm)), dim3(256), 0, st, calib_u, b.u32, M * Dm);
+  hipLaunchKernelGGL(neg_exp_kernel, dim3(nblk((size_t)Di * N)), dim3(256), 0, st, w->A_log, b.A, (size_t)Di * N);
+  QUAMBA_LAUNCH_CHECK();
+  int rc;
+  if ((rc = sgemm(b.u32, Dm, w->W_in, Dm, b.xz, 2 * Di, (int)M, 2 * Di, Dm, st))) return rc;
+  hipLaunchKernelGGL(conv_silu_f32_kernel, dim3(nblk(M * Di)), dim3(256), 0, st, b.xz, 2 * Di, w->conv_w,
+                     w->conv_b, Lc, Di, b.x, M * Di);
+  QUAMBA_LAUNCH_CHECK();
+  if ((rc = sgemm(b.x, Di, w->W_x, Di, b.dbc, NX, (int)M, NX, Di, st))) return rc;
+  if ((rc = sgemm(b.dbc, NX, w->W_dt, R, b.dtr, Di, (int)M, Di, R, st))) return rc;
+  hipLaunchKernelGGL(scan_f32_kernel, dim3(nblk((size_t)nb * Di)), dim3(256), 0, st, b.x, b.dtr, w->dt_bias, b.A,
+                     b.dbc, NX, R, w->D, b.xz, nb, Lc, Di, b.g);
+  QUAMBA_LAUNCH_CHECK();
+  return QUAMBA_OK;
+}
+
 }  // namespace
 
 size_t calibrate_workspace_bytes(const quamba_dims *d, int nb, int Lc) { return cal_plan(d, nb, Lc).total; }
@@ -333,6 +368,18 @@ int clip_search(const float *x, size_t n, int bits, int max_iters, double *clip_
   *clip_out = h[0];
   if (iters_out) *iters_out = static_cast<int>(h[1]);
   return QUAMBA_OK;
+}
+
+// The unquantized mixer of Section 3.1 in fp32 on u [nb, Lc, Dm] (fp16), each sequence from an
+// empty history: out [nb * Lc, Dm] fp32.  The reference the quantized path is compared with.
+int fp_mixer(const quamba_dims *d, const quamba_fp_weights *w, const __half *u, int nb, int Lc, float *out,
+             void *ws, size_t ws_bytes, hipStream_t st) {
+  const CalPlan p = cal_plan(d, nb, Lc);
+  if (ws_bytes < p.total) return fail(QUAMBA_EWORKSPACE, "fp mixer: workspace %zu < %zu", ws_bytes, p.total);
+  const CalBufs b = carve(p, ws);
+  int rc;
+  if ((rc = fp_forward(d, w, u, nb, Lc, b, st))) return rc;
+  return sgemm(b.g, d->d_inner, w->W_out, d->d_inner, out, d->d_model, nb * Lc, d->d_model, d->d_inner, st);
 }
 
 int calibrate(const quamba_dims *d, const quamba_fp_weights *w, const __half *calib_u, int nb, int Lc,
@@ -386,30 +433,15 @@ int calibrate(const quamba_dims *d, const quamba_fp_weights *w, const __half *ca
   const int Dm = d->d_model, Di = d->d_inner, N = d->d_state, R = d->dt_rank, NX = R + 2 * N;
   const size_t M = (size_t)nb * Lc;
   char *base = static_cast<char *>(ws);
-  float *u32 = reinterpret_cast<float *>(base + p.u32), *xz = reinterpret_cast<float *>(base + p.xz);
-  float *x = reinterpret_cast<float *>(base + p.x), *dbc = reinterpret_cast<float *>(base + p.dbc);
-  float *dtr = reinterpret_cast<float *>(base + p.dtr), *g = reinterpret_cast<float *>(base + p.g);
-  float *gH = reinterpret_cast<float *>(base + p.gH), *woh = reinterpret_cast<float *>(base + p.woh);
-  float *A = reinterpret_cast<float *>(base + p.a);
-  unsigned *slots = reinterpret_cast<unsigned *>(base + p.slots);
-  unsigned long long *hist = reinterpret_cast<unsigned long long *>(base + p.hist);
+  const CalBufs b = carve(p, ws);
+  float *u32 = b.u32, *xz = b.xz, *x = b.x, *dbc = b.dbc, *dtr = b.dtr, *g = b.g, *gH = b.gH, *woh = b.woh, *A = b.A;
+  unsigned *slots = b.slots;
+  unsigned long long *hist = b.hist;
 
   hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(256), 0, st, slots, (size_t)32, 0u);
-  if (calib_u) hipLaunchKernelGGL(half_to_float_kernel, dim3(nblk(M * Dm)), dim3(256), 0, st, calib_u, u32, M * Dm);
-  hipLaunchKernelGGL(neg_exp_kernel, dim3(nblk((size_t)Di * N)), dim3(256), 0, st, w->A_log, A, (size_t)Di * N);
   QUAMBA_LAUNCH_CHECK();
-
-  // fp forward (Section 3.1)
   int rc;
-  if ((rc = sgemm(u32, Dm, w->W_in, Dm, xz, 2 * Di, (int)M, 2 * Di, Dm, st))) return rc;
-  hipLaunchKernelGGL(conv_silu_f32_kernel, dim3(nblk(M * Di)), dim3(256), 0, st, xz, 2 * Di, w->conv_w,
-                     w->conv_b, Lc, Di, x, M * Di);
-  QUAMBA_LAUNCH_CHECK();
-  if ((rc = sgemm(x, Di, w->W_x, Di, dbc, NX, (int)M, NX, Di, st))) return rc;
-  if ((rc = sgemm(dbc, NX, w->W_dt, R, dtr, Di, (int)M, Di, R, st))) return rc;
-  hipLaunchKernelGGL(scan_f32_kernel, dim3(nblk((size_t)nb * Di)), dim3(256), 0, st, x, dtr, w->dt_bias, A, dbc,
-                     NX, R, w->D, xz, nb, Lc, Di, g);
-  QUAMBA_LAUNCH_CHECK();
+  if ((rc = fp_forward(d, w, calib_u, nb, Lc, b, st))) return rc;
   if ((rc = launch_hadamard_f32(g, (int)M, Di, gH, st))) return rc;      // y^H = H_n g
   if ((rc = launch_hadamard_f32(w->W_out, Dm, Di, woh, st))) return rc;  // rows of W_out^H
   if (out_f32 && (rc = sgemm(g, Di, w->W_out, Di, out_f32, Dm, (int)M, Dm, Di, st))) return rc;

@@ -331,6 +331,59 @@ def test_calibrate_with_mse_clip_matches_oracle():
         Q.quamba_calibrate_x_rule(cfg, fw, dev(calib), nb, Lc, 7, 99.999, out_q, ws)
 
 
+@pytest.mark.parametrize("name", ["tiny", "c0"])
+def test_fp32_mixer_matches_oracle(name):
+    """The unquantized mixer of Section 3.1 on the GPU (fp32) against the oracle's fp64 one."""
+    cfg = W.tiny_config(name="tf", d_model=64, d_inner=192, dt_rank=16, config_id=98) if name == "tiny" else W.CONFIGS[name]
+    w = W.make_weights(cfg, randomize_bias=True)
+    nb, L = (3, 37) if name == "tiny" else (2, 130)
+    u = W.make_hidden(cfg, batch=nb, seqlen=L, stream=11)
+    want = O.fp_forward(w, u)["out"].reshape(nb * L, cfg.d_model)
+    fw = {k: dev(v) for k, v in w.items()}
+    out = empty((nb * L, cfg.d_model), torch.float32)
+    Q.quamba_mixer_fp32(cfg, fw, dev(u), nb, L, out, workspace(Q.quamba_calibrate_workspace_bytes(cfg, nb, L)))
+    assert rel_err(host(out), want) <= 1e-4
+    with pytest.raises(Q.QuambaError):
+        Q.quamba_mixer_fp32(cfg, fw, dev(u), nb, L, out, workspace(1024))
+
+
+def test_x_scale_rules_rank_as_in_the_oracle():
+    """Table "percentiles": error of the quantized mixer against the unquantized one for the
+    percentile sweep and the clipping optimisation, on weights whose scan input has a few
+    far-reaching channels (no outlier channels in the hidden input, so x decides the error).
+    The whole GPU pipeline (calibration, quantized prefill, fp32 reference) must reproduce the
+    oracle's error for every rule, and with it the shape of the sweep."""
+    import dataclasses
+    cfg = dataclasses.replace(W.CONFIGS["c0"], name="c0x", config_id=77, outlier_gain=1.0)
+    w = W.make_weights(cfg, x_outlier_rows=8, x_outlier_gain=8.0)
+    calib = W.make_calibration(cfg)
+    nb, Lc = calib.shape[:2]
+    L = 128
+    u = W.make_hidden(cfg, batch=1, seqlen=L, stream=5)
+    ref_o = O.fp_forward(w, u)["out"].reshape(L, cfg.d_model)
+    fw = {k: dev(v) for k, v in w.items()}
+    ref_g = empty((L, cfg.d_model), torch.float32)
+    Q.quamba_mixer_fp32(cfg, fw, dev(u), 1, L, ref_g, workspace(Q.quamba_calibrate_workspace_bytes(cfg, 1, L)))
+    ref_g = host(ref_g).astype(np.float64)
+    ws = workspace(Q.quamba_calibrate_workspace_bytes(cfg, nb, Lc))
+    err_o, err_g = {}, {}
+    for rule in (99.0, 99.99, 100.0, "mse"):
+        qw_o, sc_o = (O.calibrate(w, calib, x_clip="mse") if rule == "mse" else O.calibrate(w, calib, rule))
+        out_o = O.q_prefill(qw_o, sc_o, u)["out"].reshape(L, cfg.d_model).astype(np.float64)
+        err_o[rule] = np.linalg.norm(out_o - ref_o) / np.linalg.norm(ref_o)
+        out_q = {k: torch.zeros(v.shape, dtype=torch.int8 if v.dtype == np.int8 else torch.float32, device="cuda:0")
+                 for k, v in qw_o.items()}
+        sc_g = Q.scales_to_dict(Q.quamba_calibrate_x_rule(
+            cfg, fw, dev(calib), nb, Lc, Q.X_MSE_CLIP if rule == "mse" else Q.X_PERCENTILE,
+            99.999 if rule == "mse" else rule, out_q, ws))
+        got = run_prefill(cfg, out_q, sc_g, u, taps=False)["out"].reshape(L, cfg.d_model).astype(np.float64)
+        err_g[rule] = np.linalg.norm(got - ref_g) / np.linalg.norm(ref_g)
+    for rule in err_o:
+        assert err_g[rule] == pytest.approx(err_o[rule], rel=0.03), (rule, err_g, err_o)
+    assert err_g[99.0] > 1.5 * err_g[99.99] and err_g[100.0] > 1.1 * err_g[99.99]
+    assert err_g["mse"] <= 1.05 * min(err_g[99.0], err_g[99.99], err_g[100.0])
+
+
 def test_decode_steps_replayed_from_a_hip_graph():
     """The decode call enqueues kernel launches only, so a caller may capture it.  Several replays,
     with eager work and synchronisations in between, must each reproduce the eager result bit for bit."""

@@ -58,6 +58,7 @@ _T_W_IN, _T_CONV_W, _T_W_X, _T_W_DT, _T_W_OUT, _T_DT_BIAS = 1, 2, 3, 4, 5, 6
 _T_OUTLIER_IDX, _T_CALIB, _T_HIDDEN, _T_SSM_STATE, _T_CONV_STATE = 10, 11, 12, 13, 14
 _T_CONV_B, _T_D = 15, 16
 _T_EMBED, _T_NORM, _T_TOKENS = 20, 21, 22
+_T_X_ROWS = 23
 
 
 def tiny_config(name="tiny", d_model=64, d_inner=128, dt_rank=16, batch=2, seqlen=37,
@@ -72,7 +73,8 @@ def _rng(cfg: MixerConfig, tensor_id: int, layer: int = 0, stream: int = 0):
     return np.random.Generator(np.random.Philox(key=key))
 
 
-def make_weights(cfg: MixerConfig, layer: int = 0, randomize_bias: bool = False):
+def make_weights(cfg: MixerConfig, layer: int = 0, randomize_bias: bool = False,
+                 x_outlier_rows: int = 0, x_outlier_gain: float = 1.0):
     """fp32 master weights of one mixer.
 
     W_in [2*Di, Dm] (rows [0,Di) produce x, rows [Di,2Di) produce z), conv_w [Di, W],
@@ -82,6 +84,11 @@ def make_weights(cfg: MixerConfig, layer: int = 0, randomize_bias: bool = False)
     Dense and conv weights are N(0, 0.02^2); A_log[d, n] = log(n+1); D = 1 and
     conv_b = 0 unless ``randomize_bias`` (unit tests) draws them; dt_bias is the
     inverse softplus of a log-uniform time step in [1e-3, 1e-1].
+
+    ``x_outlier_rows`` > 0 multiplies that many seeded rows of the x half of W_in by
+    ``x_outlier_gain``: a few channels of the scan input then reach well beyond the rest, the
+    situation Section 4.2 describes for x (rare, moderately large values), which is what the
+    choice of clipping rule for x is evaluated on.
     """
     Dm, Di, N, R, W = cfg.d_model, cfg.d_inner, cfg.d_state, cfg.dt_rank, cfg.d_conv
     std = 0.02
@@ -96,6 +103,9 @@ def make_weights(cfg: MixerConfig, layer: int = 0, randomize_bias: bool = False)
         "W_dt": normal(_T_W_DT, (Di, R)),
         "W_out": normal(_T_W_OUT, (Dm, Di)),
     }
+    if x_outlier_rows > 0:
+        rows = _rng(cfg, _T_X_ROWS, layer).choice(Di, size=x_outlier_rows, replace=False)
+        w["W_in"][np.sort(rows)] *= np.float32(x_outlier_gain)
     u = _rng(cfg, _T_DT_BIAS, layer).random(Di)
     dt = np.exp(u * (np.log(1e-1) - np.log(1e-3)) + np.log(1e-3))
     w["dt_bias"] = (dt + np.log(-np.expm1(-dt))).astype(np.float32)
