@@ -32,3 +32,5 @@ from .mixer import (fp_forward, calibrate, q_prefill, q_decode, selective_scan, 
 from .stack import calibrate_stack, q_stack_prefill, q_stack_decode  # noqa: F401
 from .model import (embed, final_norm, lm_head, greedy, model_prefill, model_decode,  # noqa: F401
                     model_generate)
+from .mamba_had import (calibrate_hadx, q_prefill_hadx, q_decode_hadx,  # noqa: F401
+                        hadamard_inverse_dequant)

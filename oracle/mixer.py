@@ -172,15 +172,17 @@ def _silu32(v):
     return (v / (F32(1.0) + np.exp(-v))).astype(F32)
 
 
-def q_scan(x_q, dt_q, z_q, B_q, C_q, A_q, D_q, dt_bias, sc, h0=None):
+def q_scan(x_q, dt_q, z_q, B_q, C_q, A_q, D_q, dt_bias, sc, h0=None, x_values=None):
     """Quantized selective SSM of Section 4.2: int8 x, dt, B, C, z and int8 weights A, D go in
     with their static scales and are dequantized inside; dt gets its fp32 bias and the
     softplus after dequantization; the output is rounded to half precision.
     Shapes: x_q, dt_q, z_q [Bt, L, Dsub]; B_q, C_q [Bt, L, N]; A_q [Dsub, N]; D_q, dt_bias
     [Dsub] (any subset of channels works: channels do not interact).
+    ``x_values`` (a half-precision x given directly) replaces s_x * x_q: the comparison
+    variant of Appendix H feeds the scan an x that went through a transform pair instead.
     Returns (g fp64, g16 fp16, h_L fp32)."""
     f = lambda k: float(sc[k])  # noqa: E731
-    x = f("s_x") * np.asarray(x_q).astype(F64)
+    x = f("s_x") * np.asarray(x_q).astype(F64) if x_values is None else np.asarray(x_values).astype(F64)
     dt = softplus(f("s_dt") * np.asarray(dt_q).astype(F64) + np.asarray(dt_bias).astype(F64))
     A = f("s_A") * np.asarray(A_q).astype(F64)
     Bm = f("s_B") * np.asarray(B_q).astype(F64)
@@ -208,28 +210,42 @@ def q_out_proj(gH_q, W_outH_q, sc):
     return acc, (acc.astype(F32) * F32(sc["m_out"])).astype(np.float16)
 
 
-def q_conv_prefill(xpre_q, conv_w_q, conv_b, sc):
-    """Section 4.3: x_out = (1/s_out) SiLU(Conv(x_in_q, W_q, s)), s = s_w s_xin, from an empty
-    history: integer taps, then fp32 (acc * m_conv + bias), SiLU in fp32, quantize with the
-    percentile scale of x.  xpre_q [Bt, L, Dsub]; conv_w_q [Dsub, W]; conv_b [Dsub]."""
+def conv_prefill_silu(xpre_q, conv_w_q, conv_b, sc):
+    """SiLU(Conv(x_in_q, W_q, s)), s = s_w s_xin, from an empty history (Section 4.3 before the
+    output quantizer): integer taps, then fp32 (acc * m_conv + bias), SiLU in fp32.
+    xpre_q [Bt, L, Dsub]; conv_w_q [Dsub, W]; conv_b [Dsub]."""
     Dsub = xpre_q.shape[-1]
     conv_acc = causal_conv_fp(np.asarray(xpre_q).astype(np.int32), np.asarray(conv_w_q).astype(np.int32),
                               np.zeros(Dsub, dtype=np.int32))
     v = conv_acc.astype(F32) * F32(sc["m_conv"]) + np.asarray(conv_b).astype(F32)
-    return quantize(_silu32(v), sc["inv_s_x"])
+    return _silu32(v)
 
 
-def q_conv_step(xpre_q_new, conv_state, conv_w_q, conv_b, sc):
-    """Decode form: fp32 conv over [conv_state (W-1, fp16), s_xpre * x_pre_q] with weights
-    s_cw * w_q, accumulated oldest tap first on top of the bias; then the window shifts.
-    xpre_q_new [Bt, Dsub]; conv_state [Bt, Dsub, W-1].  Returns (x_q [Bt, Dsub], new state)."""
+def q_conv_prefill(xpre_q, conv_w_q, conv_b, sc):
+    """Section 4.3: x_out = (1/s_out) SiLU(Conv(x_in_q, W_q, s)): `conv_prefill_silu`, then the
+    quantizer with the percentile scale of x."""
+    return quantize(conv_prefill_silu(xpre_q, conv_w_q, conv_b, sc), sc["inv_s_x"])
+
+
+def conv_step_silu(xpre_q_new, conv_state, conv_w_q, conv_b, sc):
+    """Decode form before the output quantizer: fp32 conv over [conv_state (W-1, fp16),
+    s_xpre * x_pre_q] with weights s_cw * w_q, accumulated oldest tap first on top of the
+    bias, SiLU in fp32; then the window shifts.
+    xpre_q_new [Bt, Dsub]; conv_state [Bt, Dsub, W-1].  Returns (x fp32 [Bt, Dsub], new state)."""
     new = (F32(sc["s_xpre"]) * np.asarray(xpre_q_new).astype(F32)).astype(F32)
     win = np.concatenate([np.asarray(conv_state).astype(F32), new[:, :, None]], axis=2)
     wdq = (F32(sc["s_cw"]) * np.asarray(conv_w_q).astype(F32)).astype(F32)
     v = np.asarray(conv_b).astype(F32)[None, :].repeat(win.shape[0], axis=0)
     for j in range(wdq.shape[1]):
         v = (v + (wdq[None, :, j] * win[:, :, j]).astype(F32)).astype(F32)
-    return quantize(_silu32(v), sc["inv_s_x"]), win[:, :, 1:].astype(np.float16)
+    return _silu32(v), win[:, :, 1:].astype(np.float16)
+
+
+def q_conv_step(xpre_q_new, conv_state, conv_w_q, conv_b, sc):
+    """`conv_step_silu`, then the quantizer with the percentile scale of x.
+    Returns (x_q [Bt, Dsub], new state)."""
+    x, new_state = conv_step_silu(xpre_q_new, conv_state, conv_w_q, conv_b, sc)
+    return quantize(x, sc["inv_s_x"]), new_state
 
 
 def _scan_and_tail(qw, sc, t, x_q, z_q, dt_q, B_q, C_q, h0):
