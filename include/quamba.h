@@ -150,6 +150,56 @@ int quamba_calibrate_x_rule(const quamba_dims *dims, const quamba_fp_weights *w,
                             quamba_qweights *out_q, quamba_scales *out_s /* host */,
                             void *ws, size_t ws_bytes, void *stream);
 
+/* ---- The comparison variant of Appendix H (the rotation recipe for Transformers moved onto the
+ * Mamba block), on the scan-input path.  The paper measures it to show what its own recipe
+ * avoids: forward Hadamard & quantize and a backward Hadamard between the conv and the scan,
+ * with the Hadamard matrix folded into the linear layer that reads x.  The wiring (the figure is
+ * not in the text, so this is a reading):
+ *   x16   = fp16(SiLU(conv(x_pre_q)))                         (conv output, not quantized)
+ *   xH_q  = q(H_n x16, s_xH), s_xH = max|H_n x| / 127          (forward transform + quantize)
+ *   x_proj reads xH_q with W_xH = q(rows of W_x transformed by H_n), 1/n in the multipliers
+ *   x_hat = fp16((s_xH / n) H_n^T xH_q)                       (backward transform)
+ *   the scan takes x_hat in half precision in place of s_x x_q
+ * and everything else is the Quamba path.  The layout transposes the paper lists come from the
+ * kernels it reused; this library is token-major throughout and has none.
+ * quamba_hadx: the variant's extra calibration results; W_xH [dt_rank + 2 d_state, d_inner] is
+ * device memory provided by the caller, the scalars are host values. */
+typedef struct quamba_hadx {
+  int8_t *W_xH;
+  float s_xH, s_WxH, inv_s_xH, m_xh_dt, m_xh_B, m_xh_C, xhat_scale /* s_xH / n */;
+} quamba_hadx;
+
+/* optional taps of the variant, device pointers, any may be NULL: x16, x_hat [M, d_inner] fp16,
+ * xH_q [M, d_inner] int8 */
+typedef struct quamba_hadx_taps {
+  quamba_half *x16;
+  int8_t *xH_q;
+  quamba_half *xhat16;
+} quamba_hadx_taps;
+
+/* quamba_calibrate plus the variant's extras (fills *out_h on the host, writes out_h->W_xH on
+ * the device); same workspace as quamba_calibrate. */
+int quamba_calibrate_hadx(const quamba_dims *dims, const quamba_fp_weights *w, const quamba_half *calib_u,
+                          int nb, int Lc, double x_percentile, quamba_qweights *out_q,
+                          quamba_scales *out_s /* host */, quamba_hadx *out_h /* host */, void *ws,
+                          size_t ws_bytes, void *stream);
+
+/* The variant's mixer: arguments as quamba_mixer_prefill / quamba_mixer_decode plus `hx`; `taps->x_q`,
+ * if given, receives xH_q.  Workspace: quamba_hadx_workspace_bytes (decode: L = 1). */
+size_t quamba_hadx_workspace_bytes(const quamba_dims *dims, int batch, int L);
+int quamba_mixer_prefill_hadx(const quamba_dims *dims, const quamba_qweights *qw, const quamba_scales *sc,
+                              const quamba_hadx *hx, const quamba_half *u, int Bt, int L, quamba_half *out,
+                              float *ssm_state, quamba_half *conv_state, const quamba_taps *taps,
+                              const quamba_hadx_taps *hx_taps, void *ws, size_t ws_bytes, void *stream);
+int quamba_mixer_decode_hadx(const quamba_dims *dims, const quamba_qweights *qw, const quamba_scales *sc,
+                             const quamba_hadx *hx, const quamba_half *u, int Bt, quamba_half *out,
+                             float *ssm_state, quamba_half *conv_state, const quamba_taps *taps,
+                             const quamba_hadx_taps *hx_taps, void *ws, size_t ws_bytes, void *stream);
+
+/* Stage of the variant: x_hat [M, n] = fp16(scale * H_n^T xH_q [M, n]) (the integer sums are exact);
+ * n = k 2^m as for quamba_hadamard_quant; pointers 16-byte aligned. */
+int quamba_hadamard_inverse(const int8_t *xH_q, int M, int n, float scale, quamba_half *x_hat, void *stream);
+
 /* The unquantized mixer (Section 3.1: in_proj, causal conv + SiLU, selection, selective scan,
  * gate, out_proj) in fp32 from the fp32 master weights, each of the nb sequences of length L from
  * an empty history: u [nb, L, Dm] fp16 in, out [nb * L, Dm] fp32.  It is what calibration observes

@@ -20,6 +20,8 @@ __all__ = [
     "Layer", "Model", "make_model", "quamba_model_workspace_bytes", "quamba_model_prefill", "quamba_model_decode",
     "quamba_model_generate", "quamba_calibrate_block", "quamba_embed", "quamba_final_norm", "quamba_lm_head", "quamba_argmax",
     "X_PERCENTILE", "X_MSE_CLIP", "quamba_calibrate_x_rule", "quamba_clip_search_workspace_bytes", "quamba_clip_search", "quamba_mixer_fp32",
+    "Hadx", "HadxTaps", "HADX_FIELDS", "make_hadx", "hadx_to_dict", "quamba_calibrate_hadx", "quamba_hadx_workspace_bytes",
+    "quamba_mixer_prefill_hadx", "quamba_mixer_decode_hadx", "quamba_hadamard_inverse",
 ]
 
 X_PERCENTILE, X_MSE_CLIP = 0, 1
@@ -67,6 +69,17 @@ class Taps(C.Structure):
                                           "dt_q", "y_f32", "g16", "gH_f32", "gH_q", "acc_out")]
 
 
+HADX_FIELDS = ("s_xH", "s_WxH", "inv_s_xH", "m_xh_dt", "m_xh_B", "m_xh_C", "xhat_scale")
+
+
+class Hadx(C.Structure):
+    _fields_ = [("W_xH", C.c_void_p)] + [(n, C.c_float) for n in HADX_FIELDS]
+
+
+class HadxTaps(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("x16", "xH_q", "xhat16")]
+
+
 class Layer(C.Structure):
     _fields_ = [("q", QWeights), ("s", Scales), ("norm_w", C.c_void_p)]
 
@@ -103,6 +116,20 @@ def _struct_of_ptrs(cls, src):
         v = src.get(name) if isinstance(src, dict) else getattr(src, name, None)
         setattr(out, name, None if v is None else (v if isinstance(v, int) else v.data_ptr()))
     return out
+
+
+def make_hadx(W_xH, values=None) -> Hadx:
+    """Hadx struct over a device tensor W_xH (keep it alive) and, optionally, a dict of the scalars."""
+    h = Hadx()
+    h.W_xH = W_xH.data_ptr()
+    for n in HADX_FIELDS:
+        if values is not None:
+            setattr(h, n, float(values[n]))
+    return h
+
+
+def hadx_to_dict(h: Hadx) -> dict:
+    return {n: float(getattr(h, n)) for n in HADX_FIELDS}
 
 
 def make_qweights(src) -> QWeights:
@@ -210,6 +237,18 @@ def lib():
     L.quamba_clip_search_workspace_bytes.restype = sz
     L.quamba_clip_search_workspace_bytes.argtypes = []
     L.quamba_clip_search.argtypes = [vp, sz, i, i, P(C.c_double), P(C.c_int), vp, sz, vp]
+    L.quamba_calibrate_hadx.argtypes = [P(Dims), P(FpWeights), vp, i, i, C.c_double, P(QWeights), P(Scales), P(Hadx), vp,
+                                        sz, vp]
+    L.quamba_hadx_workspace_bytes.restype = sz
+    L.quamba_hadx_workspace_bytes.argtypes = [P(Dims), i, i]
+    L.quamba_mixer_prefill_hadx.argtypes = [P(Dims), P(QWeights), P(Scales), P(Hadx), vp, i, i, vp, vp, vp, P(Taps),
+                                            P(HadxTaps), vp, sz, vp]
+    L.quamba_mixer_decode_hadx.argtypes = [P(Dims), P(QWeights), P(Scales), P(Hadx), vp, i, vp, vp, vp, P(Taps),
+                                           P(HadxTaps), vp, sz, vp]
+    L.quamba_hadamard_inverse.argtypes = [vp, i, i, f, vp, vp]
+    for name in ("quamba_calibrate_hadx", "quamba_mixer_prefill_hadx", "quamba_mixer_decode_hadx",
+                 "quamba_hadamard_inverse"):
+        getattr(L, name).restype = C.c_int
     L.quamba_mixer_fp32.argtypes = [P(Dims), P(FpWeights), vp, i, i, vp, vp, sz, vp]
     for name in ("quamba_calibrate_x_rule", "quamba_clip_search", "quamba_mixer_fp32"):
         getattr(L, name).restype = C.c_int
@@ -267,6 +306,43 @@ def quamba_mixer_fp32(dims, fp_weights, u, nb, L, out, ws, stream=None):
     fw = _struct_of_ptrs(FpWeights, fp_weights)
     _check(lib().quamba_mixer_fp32(C.byref(_dims(dims)), C.byref(fw), _ptr(u), nb, L, _ptr(out), _ptr(ws), _nbytes(ws),
                                    _stream(stream)))
+
+
+def quamba_calibrate_hadx(dims, fp_weights, calib_u, nb, Lc, x_percentile, out_q, W_xH, ws, stream=None):
+    """Returns (Scales, Hadx); `out_q` and `W_xH` (preallocated device tensors) are written on the device."""
+    fw = _struct_of_ptrs(FpWeights, fp_weights)
+    oq = _struct_of_ptrs(QWeights, out_q)
+    sc, hx = Scales(), make_hadx(W_xH)
+    _check(lib().quamba_calibrate_hadx(C.byref(_dims(dims)), C.byref(fw), _ptr(calib_u), nb, Lc, float(x_percentile),
+                                       C.byref(oq), C.byref(sc), C.byref(hx), _ptr(ws), _nbytes(ws), _stream(stream)))
+    return sc, hx
+
+
+def quamba_hadx_workspace_bytes(dims, batch, L) -> int:
+    return int(lib().quamba_hadx_workspace_bytes(C.byref(_dims(dims)), batch, L))
+
+
+def _hadx_taps(t):
+    t = _struct_of_ptrs(HadxTaps, t)
+    return None if t is None else C.byref(t)
+
+
+def quamba_mixer_prefill_hadx(dims, qw, sc, hx, u, Bt, L, out, ssm_state, conv_state, taps, hx_taps, ws, stream=None):
+    _check(lib().quamba_mixer_prefill_hadx(C.byref(_dims(dims)), C.byref(_struct_of_ptrs(QWeights, qw)),
+                                           C.byref(scales_from_dict(sc)), C.byref(hx), _ptr(u), Bt, L, _ptr(out),
+                                           _ptr(ssm_state), _ptr(conv_state), _taps(taps), _hadx_taps(hx_taps),
+                                           _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def quamba_mixer_decode_hadx(dims, qw, sc, hx, u, Bt, out, ssm_state, conv_state, taps, hx_taps, ws, stream=None):
+    _check(lib().quamba_mixer_decode_hadx(C.byref(_dims(dims)), C.byref(_struct_of_ptrs(QWeights, qw)),
+                                          C.byref(scales_from_dict(sc)), C.byref(hx), _ptr(u), Bt, _ptr(out),
+                                          _ptr(ssm_state), _ptr(conv_state), _taps(taps), _hadx_taps(hx_taps),
+                                          _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def quamba_hadamard_inverse(xH_q, M, n, scale, x_hat, stream=None):
+    _check(lib().quamba_hadamard_inverse(_ptr(xH_q), M, n, float(scale), _ptr(x_hat), _stream(stream)))
 
 
 def quamba_clip_search_workspace_bytes() -> int:

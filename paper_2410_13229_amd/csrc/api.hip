@@ -13,6 +13,9 @@ int calibrate(const quamba_dims *d, const quamba_fp_weights *w, const __half *ca
               hipStream_t st, float *out_f32);
 int fp_mixer(const quamba_dims *d, const quamba_fp_weights *w, const __half *u, int nb, int Lc, float *out,
              void *ws, size_t ws_bytes, hipStream_t st);
+int calibrate_hadx(const quamba_dims *d, const quamba_fp_weights *w, const __half *calib_u, int nb, int Lc,
+                   double x_percentile, quamba_qweights *oq, quamba_scales *os, quamba_hadx *oh, void *ws,
+                   size_t ws_bytes, hipStream_t st);
 size_t clip_search_workspace_bytes();
 int clip_search(const float *x, size_t n, int bits, int max_iters, double *clip_out, int *iters_out, void *ws,
                 size_t ws_bytes, hipStream_t st);
@@ -48,10 +51,11 @@ int check_dims(const quamba_dims *d) {
 
 // Workspace carving, shared by the size query and the launches.
 struct Plan {
-  size_t u_q, xz_q, x_q, dbc_q, dt_q, g16, gH_q, scan, gemm, gemm_bytes, total;
+  size_t u_q, xz_q, x_q, dbc_q, dt_q, g16, gH_q, scan, gemm, gemm_bytes, x16, total;
 };
 
-Plan make_plan(const quamba_dims *d, int Bt, int L) {
+// hadx: the Appendix H comparison variant also keeps the scan input in half precision
+Plan make_plan(const quamba_dims *d, int Bt, int L, bool hadx = false) {
   const size_t M = (size_t)Bt * L;
   const size_t nx = d->dt_rank + 2 * d->d_state;
   Plan p{};
@@ -73,6 +77,7 @@ Plan make_plan(const quamba_dims *d, int Bt, int L) {
   const size_t widest = M <= 64 ? (size_t)2 * d->d_inner : nx;
   p.gemm_bytes = gemm_workspace_bytes((int)M, (int)widest);
   p.gemm = take(p.gemm_bytes);
+  p.x16 = take(hadx ? M * d->d_inner * sizeof(__half) : 0);
   p.total = off;
   return p;
 }
@@ -105,14 +110,15 @@ int tap_copy(void *dst, const void *src, size_t bytes, hipStream_t st) {
 int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scales *sc, const __half *u,
               const int8_t *u_q_in, int Bt, int L, bool decode, __half *out, float *ssm_state,
               __half *conv_state, const quamba_taps *taps, void *ws, size_t ws_bytes, hipStream_t st,
-              const NormIn *norm = nullptr) {
+              const NormIn *norm = nullptr, const quamba_hadx *hx = nullptr, const quamba_hadx_taps *hx_taps = nullptr) {
   QUAMBA_TRY(check_dims(d));
   QUAMBA_TRY(check_q(qw, sc));
   if ((!u && !u_q_in && !norm) || !out) return fail(QUAMBA_EINVAL, "input or output pointer is NULL");
   if (norm && !(decode && Bt <= 4)) return fail(QUAMBA_EINVAL, "fused block input needs decode with batch <= 4");
   if (Bt < 1 || L < 1) return fail(QUAMBA_EINVAL, "batch=%d, L=%d must be >= 1", Bt, L);
   if (decode && (!ssm_state || !conv_state)) return fail(QUAMBA_EINVAL, "decode needs ssm_state and conv_state");
-  const Plan p = make_plan(d, Bt, L);
+  if (hx && (!hx->W_xH || norm)) return fail(QUAMBA_EINVAL, "variant: W_xH is NULL");
+  const Plan p = make_plan(d, Bt, L, hx != nullptr);
   if (!ws || ws_bytes < p.total) return fail(QUAMBA_EWORKSPACE, "workspace %zu < %zu", ws_bytes, p.total);
   if (!aligned(ws, 256) || !aligned(out, 8) || (u && !aligned(u, 16)) || (u_q_in && !aligned(u_q_in, 16)))
     return fail(QUAMBA_EINVAL, "workspace must be 256-byte aligned, u 16-byte, out 8-byte");
@@ -127,11 +133,14 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
   int8_t *dt_q = reinterpret_cast<int8_t *>(base + p.dt_q);
   __half *g16 = reinterpret_cast<__half *>(base + p.g16);
   int8_t *gH_q = reinterpret_cast<int8_t *>(base + p.gH_q);
+  __half *x16 = hx ? reinterpret_cast<__half *>(base + p.x16) : nullptr;
+  const quamba_hadx_taps hnone{};
+  const quamba_hadx_taps &ht = hx_taps ? *hx_taps : hnone;
   const quamba_taps none{};
   const quamba_taps &t = taps ? *taps : none;
 
   // Generation with a handful of sequences: [norm +] in_proj + conv step in one streaming kernel.
-  const bool few = decode && M <= 4 && Dm <= 8192 && g_fuse_decode;
+  const bool few = decode && M <= 4 && Dm <= 8192 && g_fuse_decode && !hx;
   // quantize the block input (Eq. 2)
   const int8_t *uq = u_q_in;
   if (!uq && !norm) {
@@ -163,18 +172,28 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
     // causal conv + SiLU + requantization with the percentile scale of x
     if (decode) {
       QUAMBA_TRY(launch_conv_step(xz_q, 2 * Di, qw->conv_w, qw->conv_b, Bt, Di, sc->s_cw, sc->s_xpre,
-                                  sc->inv_s_x, x_q, conv_state, st));
+                                  sc->inv_s_x, x_q, conv_state, st, x16));
     } else {
       QUAMBA_TRY(launch_conv_prefill(xz_q, 2 * Di, qw->conv_w, qw->conv_b, Bt, L, Di, sc->m_conv, sc->inv_s_x,
-                                     sc->s_xpre, x_q, conv_state, st));
+                                     sc->s_xpre, x_q, conv_state, st, x16));
     }
+  }
+  if (hx) {  // forward Hadamard & quantize: x_q now holds the codes of H_n x
+    QUAMBA_TRY(tap_copy(ht.x16, x16, (size_t)M * Di * sizeof(__half), st));
+    QUAMBA_TRY(launch_hadamard_quant(x16, M, Di, hx->inv_s_xH, x_q, nullptr, st));
+    QUAMBA_TRY(tap_copy(ht.xH_q, x_q, (size_t)M * Di, st));
   }
   QUAMBA_TRY(tap_copy(t.x_q, x_q, (size_t)M * Di, st));
   // x_proj: columns dt_low | B | C, each with its own output scale
   {
-    GemmEpilogue e{dbc_q, nullptr, t.acc_x, NX, R, R + N, sc->m_x_dt, sc->m_x_B, sc->m_x_C};
-    QUAMBA_TRY(launch_gemm_i8(x_q, Di, qw->W_x, Di, M, NX, Di, e, base + p.gemm, p.gemm_bytes, st));
+    GemmEpilogue e{dbc_q, nullptr, t.acc_x, NX, R, R + N, hx ? hx->m_xh_dt : sc->m_x_dt, hx ? hx->m_xh_B : sc->m_x_B,
+                   hx ? hx->m_xh_C : sc->m_x_C};
+    QUAMBA_TRY(launch_gemm_i8(x_q, Di, hx ? hx->W_xH : qw->W_x, Di, M, NX, Di, e, base + p.gemm, p.gemm_bytes, st));
     QUAMBA_TRY(tap_copy(t.dbc_q, dbc_q, (size_t)M * NX, st));
+  }
+  if (hx) {  // backward Hadamard: the scan's x, half precision, over the conv output that is no longer needed
+    QUAMBA_TRY(launch_hadamard_inverse(x_q, M, Di, hx->xhat_scale, x16, st));
+    QUAMBA_TRY(tap_copy(ht.xhat16, x16, (size_t)M * Di * sizeof(__half), st));
   }
   // dt_proj on the dt_low columns.  In prefill the scan's first pass computes dt_q itself when
   // the shapes allow and the raw dt_proj sums are not asked for; otherwise it is a GEMM.
@@ -195,6 +214,7 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
     a.s_x = sc->s_x; a.s_dt = sc->s_dt; a.s_z = sc->s_z; a.s_B = sc->s_B; a.s_C = sc->s_C;
     a.s_A = sc->s_A; a.s_D = sc->s_D;
     a.Bt = Bt; a.L = L; a.Di = Di; a.g16 = g16; a.y_f32 = t.y_f32; a.ssm_state = ssm_state;
+    a.x_f16 = x16;
     if (fuse_dt) {  // decode writes the dt codes only when they are asked for as a tap
       a.dtlow_q = dbc_q; a.lddl = NX; a.W_dt = qw->W_dt; a.R = R; a.m_dt = sc->m_dt;
       a.dt_out = (decode && !t.dt_q) ? nullptr : dt_q;
@@ -505,6 +525,47 @@ int quamba_hadamard_quant(const quamba_half *g, int M, int n, float inv_s_y, int
     return fail(QUAMBA_EINVAL, "hadamard: buffers must be 16-byte aligned");
   return launch_hadamard_quant(reinterpret_cast<const __half *>(g), M, n, inv_s_y, yH_q, yH_f32,
                                as_stream(stream));
+}
+
+int quamba_hadamard_inverse(const int8_t *xH_q, int M, int n, float scale, quamba_half *x_hat, void *stream) {
+  if (!xH_q || !x_hat) return fail(QUAMBA_EINVAL, "NULL pointer");
+  if (M < 0 || n <= 0) return fail(QUAMBA_EINVAL, "hadamard: M=%d n=%d", M, n);
+  if (!aligned(xH_q, 16) || !aligned(x_hat, 16)) return fail(QUAMBA_EINVAL, "hadamard: buffers must be 16-byte aligned");
+  return launch_hadamard_inverse(xH_q, M, n, scale, reinterpret_cast<__half *>(x_hat), as_stream(stream));
+}
+
+int quamba_calibrate_hadx(const quamba_dims *dims, const quamba_fp_weights *w, const quamba_half *calib_u, int nb,
+                          int Lc, double x_percentile, quamba_qweights *out_q, quamba_scales *out_s, quamba_hadx *out_h,
+                          void *ws, size_t ws_bytes, void *stream) {
+  QUAMBA_TRY(check_calibrate_args(dims, w, out_q, out_s, ws, nb, Lc, x_percentile));
+  if (!calib_u || !out_h || !out_h->W_xH) return fail(QUAMBA_EINVAL, "calibrate: NULL pointer");
+  return calibrate_hadx(dims, w, reinterpret_cast<const __half *>(calib_u), nb, Lc, x_percentile, out_q, out_s, out_h,
+                        ws, ws_bytes, as_stream(stream));
+}
+
+size_t quamba_hadx_workspace_bytes(const quamba_dims *dims, int batch, int L) {
+  if (check_dims(dims) != QUAMBA_OK || batch < 1 || L < 1) return 0;
+  return make_plan(dims, batch, L, true).total;
+}
+
+int quamba_mixer_prefill_hadx(const quamba_dims *dims, const quamba_qweights *qw, const quamba_scales *sc,
+                              const quamba_hadx *hx, const quamba_half *u, int Bt, int L, quamba_half *out,
+                              float *ssm_state, quamba_half *conv_state, const quamba_taps *taps,
+                              const quamba_hadx_taps *hx_taps, void *ws, size_t ws_bytes, void *stream) {
+  if (!u || !hx) return fail(QUAMBA_EINVAL, "u or hx is NULL");
+  return run_mixer(dims, qw, sc, reinterpret_cast<const __half *>(u), nullptr, Bt, L, false,
+                   reinterpret_cast<__half *>(out), ssm_state, reinterpret_cast<__half *>(conv_state), taps, ws, ws_bytes,
+                   as_stream(stream), nullptr, hx, hx_taps);
+}
+
+int quamba_mixer_decode_hadx(const quamba_dims *dims, const quamba_qweights *qw, const quamba_scales *sc,
+                             const quamba_hadx *hx, const quamba_half *u, int Bt, quamba_half *out, float *ssm_state,
+                             quamba_half *conv_state, const quamba_taps *taps, const quamba_hadx_taps *hx_taps, void *ws,
+                             size_t ws_bytes, void *stream) {
+  if (!u || !hx) return fail(QUAMBA_EINVAL, "u or hx is NULL");
+  return run_mixer(dims, qw, sc, reinterpret_cast<const __half *>(u), nullptr, Bt, 1, true,
+                   reinterpret_cast<__half *>(out), ssm_state, reinterpret_cast<__half *>(conv_state), taps, ws, ws_bytes,
+                   as_stream(stream), nullptr, hx, hx_taps);
 }
 
 }  // extern "C"

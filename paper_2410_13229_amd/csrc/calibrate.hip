@@ -538,4 +538,44 @@ int calibrate(const quamba_dims *d, const quamba_fp_weights *w, const __half *ca
   return QUAMBA_OK;
 }
 
+// Calibration of the Appendix H comparison variant: Quamba's calibration, then the scale of H_n x
+// (absmax over the calibration batch) and the x_proj weight with every row transformed by the same
+// H_n, quantized per tensor; (H w) . (H x) = n (w . x) puts 1/n into the multipliers.
+int calibrate_hadx(const quamba_dims *d, const quamba_fp_weights *w, const __half *calib_u, int nb, int Lc,
+                   double x_percentile, quamba_qweights *oq, quamba_scales *os, quamba_hadx *oh, void *ws,
+                   size_t ws_bytes, hipStream_t st) {
+  int rc;
+  if ((rc = calibrate(d, w, calib_u, nb, Lc, QUAMBA_X_PERCENTILE, x_percentile, oq, os, ws, ws_bytes, st, nullptr)))
+    return rc;
+  const CalPlan p = cal_plan(d, nb, Lc);
+  const CalBufs b = carve(p, ws);
+  const int Di = d->d_inner, Dm = d->d_model, NX = d->dt_rank + 2 * d->d_state;
+  const size_t M = (size_t)nb * Lc;
+  if (NX > Dm) return fail(QUAMBA_EUNSUPPORTED, "calibrate: dt_rank + 2 d_state = %d exceeds d_model = %d", NX, Dm);
+  // the forward pass left x in the workspace; gH and woh are free again
+  hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(256), 0, st, b.slots, (size_t)32, 0u);
+  QUAMBA_LAUNCH_CHECK();
+  if ((rc = launch_hadamard_f32(b.x, (int)M, Di, b.gH, st))) return rc;
+  if ((rc = launch_hadamard_f32(w->W_x, NX, Di, b.woh, st))) return rc;
+  if ((rc = absmax(b.gH, M, Di, 0, Di, b.slots + 0, st))) return rc;
+  if ((rc = absmax(b.woh, (size_t)NX, Di, 0, Di, b.slots + 1, st))) return rc;
+  float mx[2];
+  QUAMBA_HIP(hipMemcpyAsync(mx, b.slots, sizeof(mx), hipMemcpyDeviceToHost, st));
+  QUAMBA_HIP(hipStreamSynchronize(st));
+  auto sc_of = [](float m) { return m > 0.f ? (float)((double)m / 127.0) : 1.0f; };
+  oh->s_xH = sc_of(mx[0]);
+  oh->s_WxH = sc_of(mx[1]);
+  const double a = oh->s_xH, c = oh->s_WxH;
+  oh->inv_s_xH = (float)(1.0 / a);
+  oh->m_xh_dt = (float)(a * c / ((double)Di * (double)os->s_dtl));
+  oh->m_xh_B = (float)(a * c / ((double)Di * (double)os->s_B));
+  oh->m_xh_C = (float)(a * c / ((double)Di * (double)os->s_C));
+  oh->xhat_scale = (float)(a / (double)Di);
+  const size_t nw = (size_t)NX * Di;
+  hipLaunchKernelGGL(quantize_f32_kernel, dim3(nblk(nw)), dim3(256), 0, st, b.woh, oh->W_xH, nw, (float)(1.0 / c));
+  QUAMBA_LAUNCH_CHECK();
+  QUAMBA_HIP(hipStreamSynchronize(st));
+  return QUAMBA_OK;
+}
+
 }  // namespace quamba

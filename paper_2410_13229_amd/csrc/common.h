@@ -57,11 +57,11 @@ int launch_quantize_f16(const __half *x, int8_t *q, size_t n, float inv_s, hipSt
 
 int launch_conv_prefill(const int8_t *xpre_q, int ldx, const int8_t *w_q, const float *conv_b,
                         int Bt, int L, int Di, float m_conv, float inv_s_x, float s_xpre,
-                        int8_t *x_q, __half *conv_state, hipStream_t st);
+                        int8_t *x_q, __half *conv_state, hipStream_t st, __half *x16 = nullptr);
 
 int launch_conv_step(const int8_t *xpre_q, int ldx, const int8_t *w_q, const float *conv_b, int Bt,
                      int Di, float s_cw, float s_xpre, float inv_s_x, int8_t *x_q,
-                     __half *conv_state, hipStream_t st);
+                     __half *conv_state, hipStream_t st, __half *x16 = nullptr);
 
 int launch_add_rmsnorm_quant(const __half *x_out, __half *res, const __half *weight, float eps,
                              float inv_s, int8_t *u_q, int M, int Dm, hipStream_t st);
@@ -81,6 +81,9 @@ struct ScanArgs {
   int lddl, R;
   float m_dt;
   int8_t *dt_out;
+  // optional: the scan input given in half precision [Bt*L, Di] instead of s_x * x_q
+  // (the Appendix H comparison variant); x_q and s_x are then ignored
+  const __half *x_f16;
 };
 
 size_t scan_workspace_bytes(int Bt, int L, int Di);
@@ -89,6 +92,8 @@ int launch_scan_step(const ScanArgs &a, hipStream_t st);
 
 int launch_hadamard_quant(const __half *g, int M, int n, float inv_s_y, int8_t *yH_q, float *yH_f32,
                           hipStream_t st);
+// x_hat = fp16(scale * H_n^T xH_q): the backward transform of the Appendix H comparison variant
+int launch_hadamard_inverse(const int8_t *xH_q, int M, int n, float scale, __half *x_hat, hipStream_t st);
 
 // generation with M <= 4 rows: [add + RMSNorm + quant] -> in_proj -> conv step in one kernel.
 // Either u_q (already quantized input [M, Dm]) or out_prev / res_in / res_out / norm_w (res_out must

@@ -47,8 +47,9 @@ __device__ __forceinline__ unsigned requant_pack4(const int (&a)[4], float m) {
 // s_xpre * xpre_q] in fp32, weights s_cw * w_q, products and sums rounded one by one in tap order;
 // the window then shifts by one.  `xin`: the four new int8 codes; `cs`: 12 fp16 of state
 // (channel-major, oldest first), updated in place.  Returns the four int8 output codes.
-__device__ __forceinline__ unsigned conv_step4(unsigned xin, const int8_t *wq4, const float *bias4, __half *cs,
-                                               float s_cw, float s_xpre, float inv_s_x) {
+// conv_step4_values leaves SiLU(conv) of the four channels in sv; conv_step4 quantizes them.
+__device__ __forceinline__ void conv_step4_values(unsigned xin, const int8_t *wq4, const float *bias4, __half *cs,
+                                                  float s_cw, float s_xpre, float (&sv)[4]) {
   const uint4 wv = *reinterpret_cast<const uint4 *>(wq4);
   const unsigned wword[4] = {wv.x, wv.y, wv.z, wv.w};
   const float4 bv = *reinterpret_cast<const float4 *>(bias4);
@@ -60,7 +61,6 @@ __device__ __forceinline__ unsigned conv_step4(unsigned xin, const int8_t *wq4, 
   st.u[0] = reinterpret_cast<const uint2 *>(cs)[0];
   st.u[1] = reinterpret_cast<const uint2 *>(cs)[1];
   st.u[2] = reinterpret_cast<const uint2 *>(cs)[2];
-  float sv[4];
 #pragma unroll
   for (int c = 0; c < 4; ++c) {
     const float xn = __fmul_rn(s_xpre, static_cast<float>(static_cast<int8_t>(xin >> (8 * c))));
@@ -71,7 +71,7 @@ __device__ __forceinline__ unsigned conv_step4(unsigned xin, const int8_t *wq4, 
       const float wj = __fmul_rn(s_cw, static_cast<float>(static_cast<int8_t>(wword[c] >> (8 * j))));
       v = __fadd_rn(v, __fmul_rn(wj, win[j]));
     }
-    sv[c] = v / (1.f + __builtin_amdgcn_exp2f(-v * 1.44269504088896340736f)) * inv_s_x;
+    sv[c] = v / (1.f + __builtin_amdgcn_exp2f(-v * 1.44269504088896340736f));
     st.h[3 * c] = st.h[3 * c + 1];
     st.h[3 * c + 1] = st.h[3 * c + 2];
     st.h[3 * c + 2] = __float2half_rn(xn);
@@ -79,7 +79,26 @@ __device__ __forceinline__ unsigned conv_step4(unsigned xin, const int8_t *wq4, 
   reinterpret_cast<uint2 *>(cs)[0] = st.u[0];
   reinterpret_cast<uint2 *>(cs)[1] = st.u[1];
   reinterpret_cast<uint2 *>(cs)[2] = st.u[2];
-  return pack_q8x4(sv[0], sv[1], sv[2], sv[3]);
+}
+
+__device__ __forceinline__ unsigned conv_step4(unsigned xin, const int8_t *wq4, const float *bias4, __half *cs,
+                                               float s_cw, float s_xpre, float inv_s_x) {
+  float sv[4];
+  conv_step4_values(xin, wq4, bias4, cs, s_cw, s_xpre, sv);
+  return pack_q8x4(sv[0] * inv_s_x, sv[1] * inv_s_x, sv[2] * inv_s_x, sv[3] * inv_s_x);
+}
+
+// four floats -> four fp16 in one 8-byte word
+__device__ __forceinline__ uint2 pack_f16x4(float v0, float v1, float v2, float v3) {
+  union {
+    uint2 u;
+    __half h[4];
+  } o;
+  o.h[0] = __float2half_rn(v0);
+  o.h[1] = __float2half_rn(v1);
+  o.h[2] = __float2half_rn(v2);
+  o.h[3] = __float2half_rn(v3);
+  return o.u;
 }
 
 // Buffer descriptor over [base, base + bytes).  An access takes a scalar byte offset plus a 32-bit
@@ -91,6 +110,9 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t buffer_over(const void *base, 
 }
 __device__ __forceinline__ int buffer_load_i8(__amdgpu_buffer_rsrc_t r, unsigned lane_off, int wave_off) {
   return static_cast<int>(static_cast<int8_t>(__builtin_amdgcn_raw_buffer_load_b8(r, lane_off, wave_off, 0)));
+}
+__device__ __forceinline__ unsigned buffer_load_u16(__amdgpu_buffer_rsrc_t r, unsigned lane_off, int wave_off) {
+  return __builtin_amdgcn_raw_buffer_load_b16(r, lane_off, wave_off, 0);
 }
 __device__ __forceinline__ void buffer_store_f16(__amdgpu_buffer_rsrc_t r, unsigned lane_off, int wave_off, float v) {
   __builtin_amdgcn_raw_buffer_store_b16(__half_as_ushort(__float2half_rn(v)), r, lane_off, wave_off, 0);

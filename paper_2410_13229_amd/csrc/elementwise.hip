@@ -51,10 +51,13 @@ __device__ __forceinline__ float silu_fast(float v) {
   return v * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-v * 1.44269504088896340736f));
 }
 
+// F16OUT (the Appendix H comparison variant): the SiLU output is stored in half precision into
+// x16 instead of being quantized into xq.
+template <bool F16OUT>
 __global__ __launch_bounds__(256) void conv_prefill_kernel(
     const int8_t *__restrict__ xpre, int ldx, const int8_t *__restrict__ wq,
     const float *__restrict__ bias, int L, int Di, float m_conv, float inv_s_x, float s_xpre,
-    int8_t *__restrict__ xq, __half *__restrict__ conv_state) {
+    int8_t *__restrict__ xq, __half *__restrict__ x16, __half *__restrict__ conv_state) {
   const int c4 = blockIdx.x * 256 + threadIdx.x;  // channel group
   if (c4 * 4 >= Di) return;
   const int d0 = c4 * 4;
@@ -90,9 +93,12 @@ __global__ __launch_bounds__(256) void conv_prefill_kernel(
       for (int c = 0; c < 4; ++c) {
         const int a = __builtin_amdgcn_sdot4((int)taps[c], wword[c], 0, false);
         const float v = __fadd_rn(__fmul_rn(static_cast<float>(a), m_conv), bb[c]);
-        sv[c] = silu_fast(v) * inv_s_x;
+        sv[c] = F16OUT ? silu_fast(v) : silu_fast(v) * inv_s_x;
       }
-      *reinterpret_cast<unsigned *>(dst + (size_t)(t0 + i) * Di) = pack_q8x4(sv[0], sv[1], sv[2], sv[3]);
+      if constexpr (F16OUT)
+        *reinterpret_cast<uint2 *>(x16 + ((size_t)b * L + t0 + i) * Di + d0) = pack_f16x4(sv[0], sv[1], sv[2], sv[3]);
+      else
+        *reinterpret_cast<unsigned *>(dst + (size_t)(t0 + i) * Di) = pack_q8x4(sv[0], sv[1], sv[2], sv[3]);
     }
   }
   // the tile holding the sequence end also emits the carried window [L-3, L-2, L-1]
@@ -121,7 +127,7 @@ __global__ __launch_bounds__(256) void conv_step_kernel(const int8_t *__restrict
                                                         const int8_t *__restrict__ wq,
                                                         const float *__restrict__ bias, int Bt, int Di,
                                                         float s_cw, float s_xpre, float inv_s_x,
-                                                        int8_t *__restrict__ xq,
+                                                        int8_t *__restrict__ xq, __half *__restrict__ x16,
                                                         __half *__restrict__ conv_state) {
   const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;  // (b, channel group of 4)
   const int groups = Di / 4;
@@ -129,8 +135,15 @@ __global__ __launch_bounds__(256) void conv_step_kernel(const int8_t *__restrict
   const int b = static_cast<int>(idx / groups);
   const int d0 = static_cast<int>(idx % groups) * 4;
   const unsigned xin = *reinterpret_cast<const unsigned *>(xpre + (size_t)b * ldx + d0);
-  *reinterpret_cast<unsigned *>(xq + (size_t)b * Di + d0) =
-      conv_step4(xin, wq + (size_t)d0 * 4, bias + d0, conv_state + ((size_t)b * Di + d0) * 3, s_cw, s_xpre, inv_s_x);
+  __half *cs = conv_state + ((size_t)b * Di + d0) * 3;
+  if (x16) {  // half-precision output, no quantizer
+    float sv[4];
+    conv_step4_values(xin, wq + (size_t)d0 * 4, bias + d0, cs, s_cw, s_xpre, sv);
+    *reinterpret_cast<uint2 *>(x16 + (size_t)b * Di + d0) = pack_f16x4(sv[0], sv[1], sv[2], sv[3]);
+  } else {
+    *reinterpret_cast<unsigned *>(xq + (size_t)b * Di + d0) =
+        conv_step4(xin, wq + (size_t)d0 * 4, bias + d0, cs, s_cw, s_xpre, inv_s_x);
+  }
 }
 
 // ------------------------------------------------------------------ add + RMSNorm + quant
@@ -208,20 +221,24 @@ int launch_quantize_f16(const __half *x, int8_t *q, size_t n, float inv_s, hipSt
 
 int launch_conv_prefill(const int8_t *xpre_q, int ldx, const int8_t *w_q, const float *conv_b, int Bt,
                         int L, int Di, float m_conv, float inv_s_x, float s_xpre, int8_t *x_q,
-                        __half *conv_state, hipStream_t st) {
+                        __half *conv_state, hipStream_t st, __half *x16) {
   dim3 grid((Di / 4 + 255) / 256, (L + CONV_TT - 1) / CONV_TT, Bt);
-  hipLaunchKernelGGL(conv_prefill_kernel, grid, dim3(256), 0, st, xpre_q, ldx, w_q, conv_b, L, Di,
-                     m_conv, inv_s_x, s_xpre, x_q, conv_state);
+  if (x16)
+    hipLaunchKernelGGL(conv_prefill_kernel<true>, grid, dim3(256), 0, st, xpre_q, ldx, w_q, conv_b, L, Di,
+                       m_conv, inv_s_x, s_xpre, x_q, x16, conv_state);
+  else
+    hipLaunchKernelGGL(conv_prefill_kernel<false>, grid, dim3(256), 0, st, xpre_q, ldx, w_q, conv_b, L, Di,
+                       m_conv, inv_s_x, s_xpre, x_q, x16, conv_state);
   QUAMBA_LAUNCH_CHECK();
   return QUAMBA_OK;
 }
 
 int launch_conv_step(const int8_t *xpre_q, int ldx, const int8_t *w_q, const float *conv_b, int Bt,
                      int Di, float s_cw, float s_xpre, float inv_s_x, int8_t *x_q, __half *conv_state,
-                     hipStream_t st) {
+                     hipStream_t st, __half *x16) {
   const size_t n = (size_t)Bt * (Di / 4);
   hipLaunchKernelGGL(conv_step_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, xpre_q, ldx,
-                     w_q, conv_b, Bt, Di, s_cw, s_xpre, inv_s_x, x_q, conv_state);
+                     w_q, conv_b, Bt, Di, s_cw, s_xpre, inv_s_x, x_q, x16, conv_state);
   QUAMBA_LAUNCH_CHECK();
   return QUAMBA_OK;
 }

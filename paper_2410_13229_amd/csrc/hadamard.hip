@@ -58,19 +58,23 @@ struct Paley {
 
 // H_k as fp16 bit patterns (+1 = 0x3C00, -1 = 0xBC00), zero-padded to 32 x 32: the A operand of
 // the MFMA form, read 16 bytes per lane.
-template <int K>
+// TR: the table of H_k^T (the Paley matrices are not symmetric; the backward transform needs it).
+template <int K, bool TR>
 struct PaleyHalf {
   uint16_t h[32][32];
   constexpr PaleyHalf() : h{} {
     constexpr Paley<K - 1> tab{};
     for (int a = 0; a < K; ++a)
-      for (int b = 0; b < K; ++b) h[a][b] = ((tab.neg[a] >> b) & 1u) ? 0xBC00 : 0x3C00;
+      for (int b = 0; b < K; ++b) {
+        const bool minus = TR ? ((tab.neg[b] >> a) & 1u) : ((tab.neg[a] >> b) & 1u);
+        h[a][b] = minus ? 0xBC00 : 0x3C00;
+      }
   }
 };
-template <int K>
-__device__ const PaleyHalf<K> g_paley_half{};
+template <int K, bool TR>
+__device__ const PaleyHalf<K, TR> g_paley_half{};
 
-template <int K, int HT>
+template <int K, int HT, bool TR>
 __device__ __forceinline__ void order_k_pass(float *row, int logm) {
   if constexpr (K > 1) {
     constexpr Paley<K - 1> tab{};
@@ -83,7 +87,7 @@ __device__ __forceinline__ void order_k_pass(float *row, int logm) {
       for (int a = 0; a < K; ++a) {
         float s = 0.f;
 #pragma unroll
-        for (int b = 0; b < K; ++b) s += ((tab.neg[a] >> b) & 1u) ? -v[b] : v[b];
+        for (int b = 0; b < K; ++b) s += (TR ? ((tab.neg[b] >> a) & 1u) : ((tab.neg[a] >> b) & 1u)) ? -v[b] : v[b];
         o[a] = s;
       }
 #pragma unroll
@@ -102,18 +106,34 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 // element e of lane l at k step s is b = 16 s + 8 (l / 32) + e for both operands: H_k[l % 32, b]
 // on the A side, x[b, 32 t + l % 32] on the B side; register r of the result is row
 // a = 8 (r / 4) + 4 (l / 32) + r % 4, column 32 t + l % 32.
-template <int K, int LOGM, int HT>
-__device__ __forceinline__ void order_k_load_mfma(const __half *__restrict__ src, float *row) {
+// int8 input (the backward transform of quantized codes) is widened to fp16 while staging, which is exact.
+template <int K, int LOGM, int HT, typename TIn, bool TR>
+__device__ __forceinline__ void order_k_load_mfma(const TIn *__restrict__ src, float *row) {
   static_assert(K > 1 && K <= 32 && LOGM >= 5, "one 32-row tile of H_k, whole 32-column tiles");
+  static_assert(sizeof(TIn) <= 2, "fp16 or int8 rows");
   constexpr int W = 1 << LOGM, PITCH = W + 8, n = K << LOGM;
   _Float16 *hx = reinterpret_cast<_Float16 *>(row);
-  for (int i = threadIdx.x * 8; i < n; i += HT * 8)
-    *reinterpret_cast<uint4 *>(hx + (i >> LOGM) * PITCH + (i & (W - 1))) = *reinterpret_cast<const uint4 *>(src + i);
+  for (int i = threadIdx.x * 8; i < n; i += HT * 8) {
+    uint4 *dst = reinterpret_cast<uint4 *>(hx + (i >> LOGM) * PITCH + (i & (W - 1)));
+    if constexpr (sizeof(TIn) == 2) {
+      *dst = *reinterpret_cast<const uint4 *>(src + i);
+    } else {
+      const uint2 in = *reinterpret_cast<const uint2 *>(src + i);
+      union {
+        uint4 u;
+        _Float16 h[8];
+      } w;
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        w.h[e] = static_cast<_Float16>(static_cast<int>(static_cast<int8_t>((e < 4 ? in.x : in.y) >> (8 * (e & 3)))));
+      *dst = w.u;
+    }
+  }
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int a = lane & 31, bhalf = 8 * (lane >> 5);
   h8 ha[2];
 #pragma unroll
-  for (int s = 0; s < 2; ++s) ha[s] = *reinterpret_cast<const h8 *>(&g_paley_half<K>.h[a][16 * s + bhalf]);
+  for (int s = 0; s < 2; ++s) ha[s] = *reinterpret_cast<const h8 *>(&g_paley_half<K, TR>.h[a][16 * s + bhalf]);
   __syncthreads();
   constexpr int NWAVE = HT / 64, TILES = W / 32, TPW = (TILES + NWAVE - 1) / NWAVE;  // column tiles, per wave
   f32x16 acc[TPW];
@@ -183,10 +203,13 @@ __device__ __forceinline__ void radix_pass(float *row, int n, int s) {
   }
 }
 
-template <int K, int LOGM, typename TIn>
+// Outputs (any may be null): out = int8 codes of scale * y; out_f32 = y; out_f16 = fp16(scale * y).
+// TR applies H_n^T = H_k^T (x) H_{2^m} (the Sylvester factor is symmetric).
+template <int K, int LOGM, typename TIn, bool TR>
 __global__ __launch_bounds__(threads_for(K << LOGM)) void hadamard_quant_kernel(const TIn *__restrict__ g, float inv_s,
                                                             int8_t *__restrict__ out,
-                                                            float *__restrict__ out_f32) {
+                                                            float *__restrict__ out_f32,
+                                                            __half *__restrict__ out_f16) {
   static_assert(LOGM >= 4, "the last pass owns the low four index bits");
   constexpr int n = K << LOGM;
   constexpr int HT = threads_for(n);
@@ -194,8 +217,8 @@ __global__ __launch_bounds__(threads_for(K << LOGM)) void hadamard_quant_kernel(
   const size_t r = blockIdx.x;
   const TIn *src = g + r * n;
 
-  if constexpr (sizeof(TIn) == 2 && K > 1 && LOGM >= 5) {
-    order_k_load_mfma<K, LOGM, HT>(src, row);
+  if constexpr (sizeof(TIn) <= 2 && K > 1 && LOGM >= 5) {
+    order_k_load_mfma<K, LOGM, HT, TIn, TR>(src, row);
   } else {
     for (int i = threadIdx.x * 8; i < n; i += HT * 8) {
       float *dst = row + pad(i);
@@ -209,13 +232,18 @@ __global__ __launch_bounds__(threads_for(K << LOGM)) void hadamard_quant_kernel(
                                                        __half2float(in.h[2]), __half2float(in.h[3]));
         *reinterpret_cast<float4 *>(dst + 4) = make_float4(__half2float(in.h[4]), __half2float(in.h[5]),
                                                            __half2float(in.h[6]), __half2float(in.h[7]));
+      } else if constexpr (sizeof(TIn) == 1) {
+        const uint2 in = *reinterpret_cast<const uint2 *>(src + i);
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          dst[e] = static_cast<float>(static_cast<int>(static_cast<int8_t>((e < 4 ? in.x : in.y) >> (8 * (e & 3)))));
       } else {
         *reinterpret_cast<float4 *>(dst) = *reinterpret_cast<const float4 *>(src + i);
         *reinterpret_cast<float4 *>(dst + 4) = *reinterpret_cast<const float4 *>(src + i + 4);
       }
     }
     __syncthreads();
-    order_k_pass<K, HT>(row, LOGM);
+    order_k_pass<K, HT, TR>(row, LOGM);
   }
 
   // index bits [4, LOGM) in up to three passes of at most 5 bits, high bits first
@@ -255,30 +283,42 @@ __global__ __launch_bounds__(threads_for(K << LOGM)) void hadamard_quant_kernel(
       for (int q = 0; q < 4; ++q)
         reinterpret_cast<float4 *>(o)[q] = make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
     }
+    if (out_f16) {
+      union {
+        uint4 u[2];
+        __half h[16];
+      } o;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) o.h[e] = __float2half_rn(v[e] * inv_s);
+      uint4 *dst = reinterpret_cast<uint4 *>(out_f16 + r * n + (size_t)w * 16);
+      dst[0] = o.u[0];
+      dst[1] = o.u[1];
+    }
   }
 }
 
-template <int K, int LOGM, typename TIn>
-int run(const TIn *g, int M, float inv_s, int8_t *out, float *out_f32, hipStream_t st) {
+template <int K, int LOGM, typename TIn, bool TR>
+int run(const TIn *g, int M, float inv_s, int8_t *out, float *out_f32, __half *out_f16, hipStream_t st) {
   constexpr int n = K << LOGM;
   constexpr size_t lds = (size_t)(n + n / 4) * sizeof(float);
   static bool attr_set = false;
   if (lds > 64 * 1024 && !attr_set) {
-    QUAMBA_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&hadamard_quant_kernel<K, LOGM, TIn>),
+    QUAMBA_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&hadamard_quant_kernel<K, LOGM, TIn, TR>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     attr_set = true;
   }
-  hipLaunchKernelGGL((hadamard_quant_kernel<K, LOGM, TIn>), dim3(M), dim3(threads_for(n)), lds, st, g, inv_s, out, out_f32);
+  hipLaunchKernelGGL((hadamard_quant_kernel<K, LOGM, TIn, TR>), dim3(M), dim3(threads_for(n)), lds, st, g, inv_s, out,
+                     out_f32, out_f16);
   QUAMBA_LAUNCH_CHECK();
   return QUAMBA_OK;
 }
 
-template <int K, typename TIn>
-int dispatch_m(int m, const TIn *g, int M, float inv_s, int8_t *out, float *out_f32, hipStream_t st) {
+template <int K, typename TIn, bool TR>
+int dispatch_m(int m, const TIn *g, int M, float inv_s, int8_t *out, float *out_f32, __half *out_f16, hipStream_t st) {
   switch (m) {
 #define QUAMBA_CASE(LM) \
   case LM:              \
-    return run<K, LM, TIn>(g, M, inv_s, out, out_f32, st);
+    return run<K, LM, TIn, TR>(g, M, inv_s, out, out_f32, out_f16, st);
     QUAMBA_CASE(4)
     QUAMBA_CASE(5)
     QUAMBA_CASE(6)
@@ -326,31 +366,37 @@ bool hadamard_factor(int n, int *k, int *m) {
 }
 
 namespace {
-template <typename TIn>
-int dispatch_k(const TIn *g, int M, int n, float inv_s_y, int8_t *yH_q, float *yH_f32, hipStream_t st) {
+template <typename TIn, bool TR>
+int dispatch_k(const TIn *g, int M, int n, float inv_s_y, int8_t *yH_q, float *yH_f32, __half *y_f16, hipStream_t st) {
   int k = 0, m = 0;
   if (!hadamard_factor(n, &k, &m) || m < 4)
     return fail(QUAMBA_EUNSUPPORTED, "hadamard: n=%d is not k*2^m with k in (1,12,20) and m >= 4", n);
   if (M == 0) return QUAMBA_OK;
   switch (k) {
     case 1:
-      return dispatch_m<1, TIn>(m, g, M, inv_s_y, yH_q, yH_f32, st);
+      return dispatch_m<1, TIn, false>(m, g, M, inv_s_y, yH_q, yH_f32, y_f16, st);  // H_{2^m} is symmetric
     case 12:
-      return dispatch_m<12, TIn>(m, g, M, inv_s_y, yH_q, yH_f32, st);
+      return dispatch_m<12, TIn, TR>(m, g, M, inv_s_y, yH_q, yH_f32, y_f16, st);
     default:
-      return dispatch_m<20, TIn>(m, g, M, inv_s_y, yH_q, yH_f32, st);
+      return dispatch_m<20, TIn, TR>(m, g, M, inv_s_y, yH_q, yH_f32, y_f16, st);
   }
 }
 }  // namespace
 
 int launch_hadamard_quant(const __half *g, int M, int n, float inv_s_y, int8_t *yH_q, float *yH_f32,
                           hipStream_t st) {
-  return dispatch_k<__half>(g, M, n, inv_s_y, yH_q, yH_f32, st);
+  return dispatch_k<__half, false>(g, M, n, inv_s_y, yH_q, yH_f32, nullptr, st);
 }
 
 // fp32 rows in, fp32 rows out, no quantization (used by calibration)
 int launch_hadamard_f32(const float *x, int M, int n, float *y, hipStream_t st) {
-  return dispatch_k<float>(x, M, n, 1.f, nullptr, y, st);
+  return dispatch_k<float, false>(x, M, n, 1.f, nullptr, y, nullptr, st);
+}
+
+// Backward transform of quantized codes (Appendix H, the comparison variant's scan input):
+// x_hat = fp16(scale * H_n^T xH_q).  The integer sums are exact in fp32 for n * 128 < 2^24.
+int launch_hadamard_inverse(const int8_t *xH_q, int M, int n, float scale, __half *x_hat, hipStream_t st) {
+  return dispatch_k<int8_t, true>(xH_q, M, n, scale, nullptr, nullptr, x_hat, st);
 }
 
 }  // namespace quamba

@@ -66,6 +66,7 @@ struct Dev {
   int lddl, R;
   float m_dt;
   int8_t *dt_out;
+  const __half *x_f16;  // scan input in half precision instead of s_x * x_q (comparison variant)
 };
 
 // Dequantize B (and C) of tokens [row0, row0+cnt) into LDS as fp32 [TB][16].
@@ -89,7 +90,7 @@ __device__ __forceinline__ void stage_bc(const Dev &p, size_t row0, int cnt, flo
 // The int8 x / dt / z bytes of the next TS tokens are fetched into registers while the
 // current TS tokens are computed, so no load latency sits on the recurrence.
 // FUSE_DT (pass 1 only): dt_q is not read but computed from dt_low and W_dt, and written out.
-template <bool OUTPUT, bool FUSE_DT>
+template <bool OUTPUT, bool FUSE_DT, bool XF16 = false>
 __global__ __launch_bounds__(SCAN_THREADS) void scan_chunk_kernel(Dev p) {
   static_assert(!(OUTPUT && FUSE_DT), "dt_q is produced by pass 1");
   __shared__ __attribute__((aligned(16))) float sB[TB][NS];
@@ -131,7 +132,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_chunk_kernel(Dev p) {
   const unsigned ud = static_cast<unsigned>(dd);
   const size_t tok0 = seq0 + t0;
   const int nt = t1 - t0;
-  const auto rx = buffer_over(p.x_q + tok0 * p.Di, nt * p.Di);
+  const auto rx = XF16 ? buffer_over(p.x_f16 + tok0 * p.Di, nt * p.Di * 2) : buffer_over(p.x_q + tok0 * p.Di, nt * p.Di);
   const auto rdt = FUSE_DT ? rx : buffer_over(p.dt_q + tok0 * p.Di, nt * p.Di);
   const auto rz = OUTPUT ? buffer_over(p.z_q + tok0 * p.ldz, (nt - 1) * p.ldz + p.Di) : rx;
   const auto rg = OUTPUT ? buffer_over(p.g16 + tok0 * p.Di, nt * p.Di * 2) : rx;
@@ -197,7 +198,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_chunk_kernel(Dev p) {
     for (int i = 0; i < TS; ++i) {
       // clamp: tokens past the chunk are loaded but never used
       const int row = min(t + i, t1 - 1) - t0;
-      r.x[i] = buffer_load_i8(rx, ud, row * p.Di);
+      r.x[i] = XF16 ? static_cast<int>(buffer_load_u16(rx, 2 * ud, row * p.Di * 2)) : buffer_load_i8(rx, ud, row * p.Di);
       if (!FUSE_DT) r.dt[i] = buffer_load_i8(rdt, ud, row * p.Di);  // fused: read from the LDS tile
       if (OUTPUT) r.z[i] = buffer_load_i8(rz, ud, row * p.ldz);
     }
@@ -206,7 +207,8 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_chunk_kernel(Dev p) {
 #pragma unroll
     for (int i = 0; i < TS; ++i) {
       if (t + i < t1) {
-        const float xv = p.s_x * static_cast<float>(r.x[i]);
+        const float xv = XF16 ? __half2float(__ushort_as_half(static_cast<unsigned short>(r.x[i])))
+                              : p.s_x * static_cast<float>(r.x[i]);
         const int dtq = FUSE_DT ? static_cast<int>(sDT[wave][tl + i][lane]) : r.dt[i];
         const float dt = softplus_f(p.s_dt * static_cast<float>(dtq) + bias);
         const float u = dt * xv;
@@ -317,7 +319,8 @@ __global__ __launch_bounds__(256) void scan_step_kernel(Dev p, float *__restrict
   const unsigned aw = *reinterpret_cast<const unsigned *>(p.A_q + (size_t)d * NS + 4 * q);
   const unsigned bw = *reinterpret_cast<const unsigned *>(p.B_q + (size_t)b * p.ldbc + 4 * q);
   const unsigned cw = *reinterpret_cast<const unsigned *>(p.C_q + (size_t)b * p.ldbc + 4 * q);
-  const float xv = p.s_x * static_cast<float>(p.x_q[(size_t)b * p.Di + d]);
+  const float xv = p.x_f16 ? __half2float(p.x_f16[(size_t)b * p.Di + d])
+                           : p.s_x * static_cast<float>(p.x_q[(size_t)b * p.Di + d]);
   int dtq;
   if (FUSE_DT) {
     const int8_t *wrow = p.W_dt + (size_t)d * p.R;
@@ -370,6 +373,7 @@ Dev make_dev(const ScanArgs &a) {
   p.L = a.L; p.Di = a.Di; p.g16 = a.g16; p.y_f32 = a.y_f32;
   p.dtlow_q = a.dtlow_q; p.W_dt = a.W_dt; p.lddl = a.lddl; p.R = a.R; p.m_dt = a.m_dt; p.dt_out = a.dt_out;
   if (a.dtlow_q && a.dt_out) p.dt_q = a.dt_out;
+  p.x_f16 = a.x_f16;
   return p;
 }
 
@@ -427,7 +431,12 @@ int launch_scan_prefill(const ScanArgs &a, void *ws, size_t ws_bytes, hipStream_
         !aligned(a.dtlow_q, 16) || !aligned(a.W_dt, 16) || !aligned(a.dt_out, 4))
       return fail(QUAMBA_EUNSUPPORTED, "scan: fused dt_proj needs dt_rank and lddl multiples of 16, Di a multiple "
                                        "of 4, 16-byte aligned dt_low and W_dt");
-    hipLaunchKernelGGL((scan_chunk_kernel<false, true>), grid, dim3(SCAN_THREADS), 0, st, p);
+    if (a.x_f16)
+      hipLaunchKernelGGL((scan_chunk_kernel<false, true, true>), grid, dim3(SCAN_THREADS), 0, st, p);
+    else
+      hipLaunchKernelGGL((scan_chunk_kernel<false, true>), grid, dim3(SCAN_THREADS), 0, st, p);
+  } else if (a.x_f16) {
+    hipLaunchKernelGGL((scan_chunk_kernel<false, false, true>), grid, dim3(SCAN_THREADS), 0, st, p);
   } else {
     hipLaunchKernelGGL((scan_chunk_kernel<false, false>), grid, dim3(SCAN_THREADS), 0, st, p);
   }
@@ -436,7 +445,10 @@ int launch_scan_prefill(const ScanArgs &a, void *ws, size_t ws_bytes, hipStream_
   hipLaunchKernelGGL(scan_carry_kernel, dim3((unsigned)((n2 + 255) / 256)), dim3(256), 0, st, p, a.ssm_state,
                      a.Bt);
   QUAMBA_LAUNCH_CHECK();
-  hipLaunchKernelGGL((scan_chunk_kernel<true, false>), grid, dim3(SCAN_THREADS), 0, st, p);
+  if (a.x_f16)
+    hipLaunchKernelGGL((scan_chunk_kernel<true, false, true>), grid, dim3(SCAN_THREADS), 0, st, p);
+  else
+    hipLaunchKernelGGL((scan_chunk_kernel<true, false>), grid, dim3(SCAN_THREADS), 0, st, p);
   QUAMBA_LAUNCH_CHECK();
   return QUAMBA_OK;
 }
