@@ -159,6 +159,68 @@ def bench_x_scale_rules(Q, W, torch, np, dev, to_dev, stream):
             "rules": res}
 
 
+def bench_hadx_variant(Q, W, torch, np, dev, to_dev, stream, quamba_prefill_ms, quamba_decode_us, steps):
+    """The comparison variant of Appendix H (forward Hadamard & quantize, backward Hadamard on the
+    scan-input path) next to the Quamba path: one c1 prefill step and one c2 decode step (batch 64),
+    same weights, same inputs.  The paper's whole-model table has it 1.18x (prefill, L = 512) and
+    1.29x (generation) slower than Quamba on its GPU."""
+    cfg, c2 = W.CONFIGS["c1"], W.CONFIGS["c2"]
+    Bt, L, Dm, Di, N, R = cfg.batch, cfg.seqlen, cfg.d_model, cfg.d_inner, cfg.d_state, cfg.dt_rank
+    NX = R + 2 * N
+    fw = {k: to_dev(v) for k, v in W.make_weights(cfg).items()}
+    calib = to_dev(W.make_calibration(cfg))
+    nb, Lc = calib.shape[:2]
+    shapes = {"W_in": (2 * Di, Dm), "conv_w": (Di, 4), "W_x": (NX, Di), "W_dt": (Di, R), "A": (Di, N), "D": (Di,),
+              "W_outH": (Dm, Di)}
+    qd = {k: torch.empty(v, dtype=torch.int8, device=dev) for k, v in shapes.items()}
+    qd["conv_b"] = torch.empty((Di,), dtype=torch.float32, device=dev)
+    qd["dt_bias"] = torch.empty((Di,), dtype=torch.float32, device=dev)
+    W_xH = torch.empty((NX, Di), dtype=torch.int8, device=dev)
+    cws = torch.empty(Q.quamba_calibrate_workspace_bytes(cfg, nb, Lc), dtype=torch.uint8, device=dev)
+    sc, hx = Q.quamba_calibrate_hadx(cfg, fw, calib, nb, Lc, 99.999, qd, W_xH, cws, stream)
+    del cws, fw
+    qs, dims = Q.make_qweights(qd), Q.make_dims(cfg)
+
+    u = to_dev(W.make_hidden(cfg))
+    out = torch.empty((Bt, L, Dm), dtype=torch.float16, device=dev)
+    ws = torch.empty(Q.quamba_hadx_workspace_bytes(cfg, Bt, L), dtype=torch.uint8, device=dev)
+
+    def timed(fn, n):
+        for _ in range(max(n // 5, 5)):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / n
+
+    pre = timed(lambda: Q.quamba_mixer_prefill_hadx(dims, qs, sc, hx, u, Bt, L, out, None, None, None, None, ws, stream),
+                steps)
+    # the two added kernels on their own
+    M = Bt * L
+    x16 = torch.empty((M, Di), dtype=torch.float16, device=dev).normal_()
+    xq = torch.empty((M, Di), dtype=torch.int8, device=dev)
+    fwd = timed(lambda: Q.quamba_hadamard_quant(x16, M, Di, hx.inv_s_xH, xq, None, stream), steps)
+    bwd = timed(lambda: Q.quamba_hadamard_inverse(xq, M, Di, hx.xhat_scale, x16, stream), steps)
+
+    Bd = c2.batch
+    ssm_np, cs_np = W.make_decode_state(c2)
+    dssm, dcs = to_dev(ssm_np), to_dev(cs_np)
+    ud = to_dev(W.make_hidden(c2, batch=Bd, seqlen=1)[:, 0, :])
+    dout = torch.empty((Bd, Dm), dtype=torch.float16, device=dev)
+    dws = torch.empty(Q.quamba_hadx_workspace_bytes(c2, Bd, 1), dtype=torch.uint8, device=dev)
+    dec = timed(lambda: Q.quamba_mixer_decode_hadx(dims, qs, sc, hx, ud, Bd, dout, dssm, dcs, None, None, dws, stream),
+                max(steps, 500))
+    return {"workload": "c1 prefill step and c2 decode step (batch 64) of the Appendix H variant, same shapes and inputs "
+                        "as the Quamba figures of this line",
+            "prefill_ms": round(pre * 1e3, 4), "prefill_vs_quamba": round(pre * 1e3 / quamba_prefill_ms, 3),
+            "decode_us": round(dec * 1e6, 2),
+            "decode_vs_quamba": round(dec * 1e6 / quamba_decode_us, 3) if quamba_decode_us else None,
+            "forward_hadamard_quant_us": round(fwd * 1e6, 2), "backward_hadamard_us": round(bwd * 1e6, 2),
+            "paper_ratio_whole_model": {"prefill_L512": round(56.87 / 48.24, 3), "generate": round(10.46 / 8.12, 3)}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -439,6 +501,12 @@ def main():
     if not args.no_model and args.workload == "c1":
         model = bench_model(args, Q, W, torch, np, dev, to_dev)
 
+    # ---- the comparison variant of Appendix H next to the Quamba path
+    hadx = None
+    if not args.no_model and args.workload == "c1":
+        hadx = bench_hadx_variant(Q, W, torch, np, dev, to_dev, stream, ms_per_step,
+                                  decode["us_per_step_eager"] if decode else None, min(args.steps, 200))
+
     # ---- choice of the clipping rule for the scan input (percentile sweep, clipping optimisation)
     x_rules = None
     if not args.no_model and args.workload == "c1":
@@ -488,6 +556,7 @@ def main():
         "decode": decode,
         "model": model,
         "x_scale_rules": x_rules,
+        "hadx_variant": hadx,
         "cpu_baseline": cpu,
     }
     print(json.dumps(line))

@@ -117,7 +117,8 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
   if (norm && !(decode && Bt <= 4)) return fail(QUAMBA_EINVAL, "fused block input needs decode with batch <= 4");
   if (Bt < 1 || L < 1) return fail(QUAMBA_EINVAL, "batch=%d, L=%d must be >= 1", Bt, L);
   if (decode && (!ssm_state || !conv_state)) return fail(QUAMBA_EINVAL, "decode needs ssm_state and conv_state");
-  if (hx && (!hx->W_xH || norm)) return fail(QUAMBA_EINVAL, "variant: W_xH is NULL");
+  if (hx && !hx->W_xH) return fail(QUAMBA_EINVAL, "variant: W_xH is NULL");
+  if (hx && norm) return fail(QUAMBA_EINVAL, "variant: the fused block input is not built for it");
   const Plan p = make_plan(d, Bt, L, hx != nullptr);
   if (!ws || ws_bytes < p.total) return fail(QUAMBA_EWORKSPACE, "workspace %zu < %zu", ws_bytes, p.total);
   if (!aligned(ws, 256) || !aligned(out, 8) || (u && !aligned(u, 16)) || (u_q_in && !aligned(u_q_in, 16)))
