@@ -32,6 +32,18 @@ SCAN_FLOP_PER_TD = 123.0     # 16 x (exp + 2 mul + 2 fma) + D*x + softplus + gat
 MEASURED_TRAFFIC_BYTES = {"c1": 90.7e6}
 
 
+def alloc_qweights(cfg, torch, dev):
+    """Empty device tensors for one layer's quantized weights (filled by the library's calibration)."""
+    Dm, Di, N, R = cfg.d_model, cfg.d_inner, cfg.d_state, cfg.dt_rank
+    NX = R + 2 * N
+    shapes = {"W_in": (2 * Di, Dm), "conv_w": (Di, 4), "W_x": (NX, Di), "W_dt": (Di, R), "A": (Di, N), "D": (Di,),
+              "W_outH": (Dm, Di)}
+    qd = {k: torch.empty(v, dtype=torch.int8, device=dev) for k, v in shapes.items()}
+    qd["conv_b"] = torch.empty((Di,), dtype=torch.float32, device=dev)
+    qd["dt_bias"] = torch.empty((Di,), dtype=torch.float32, device=dev)
+    return qd
+
+
 def bench_model(args, Q, W, torch, np, dev, to_dev):
     """Time to first token, time per output token (eager and HIP-graph replay) and time to last token of
     the Mamba-2.8B-shaped model: 64 quantized blocks, vocabulary 50280, random-init weights."""
@@ -53,11 +65,7 @@ def bench_model(args, Q, W, torch, np, dev, to_dev):
     norm_w, norm_f = W.make_norm_weights(cfg, nl)
     layers = []
     for l in range(nl):
-        qd = {"W_in": (2 * Di, Dm), "conv_w": (Di, 4), "W_x": (NX, Di), "W_dt": (Di, R), "A": (Di, N), "D": (Di,),
-              "W_outH": (Dm, Di)}
-        qd = {k: torch.empty(v, dtype=torch.int8, device=dev) for k, v in qd.items()}  # own memory per layer
-        qd["conv_b"] = torch.empty((Di,), dtype=torch.float32, device=dev)
-        qd["dt_bias"] = torch.empty((Di,), dtype=torch.float32, device=dev)
+        qd = alloc_qweights(cfg, torch, dev)  # own memory per layer
         nw = to_dev(norm_w[l])
         sc = Q.quamba_calibrate_block(cfg, distinct[l % nd], nw, 1e-5, res, out, nb, Lc, 99.999, qd, cws,
                                       torch.cuda.current_stream())
@@ -133,11 +141,7 @@ def bench_x_scale_rules(Q, W, torch, np, dev, to_dev, stream):
     calib = to_dev(W.make_calibration(cfg))
     nb, Lc = calib.shape[:2]
     u = to_dev(W.make_hidden(cfg, batch=1, seqlen=L, stream=5))
-    shapes = {"W_in": (2 * Di, Dm), "conv_w": (Di, 4), "W_x": (NX, Di), "W_dt": (Di, R), "A": (Di, N), "D": (Di,),
-              "W_outH": (Dm, Di)}
-    qd = {k: torch.empty(v, dtype=torch.int8, device=dev) for k, v in shapes.items()}
-    qd["conv_b"] = torch.empty((Di,), dtype=torch.float32, device=dev)
-    qd["dt_bias"] = torch.empty((Di,), dtype=torch.float32, device=dev)
+    qd = alloc_qweights(cfg, torch, dev)
     cws = torch.empty(max(Q.quamba_calibrate_workspace_bytes(cfg, nb, Lc), Q.quamba_calibrate_workspace_bytes(cfg, 1, L)),
                       dtype=torch.uint8, device=dev)
     ref = torch.empty((L, Dm), dtype=torch.float32, device=dev)
@@ -170,11 +174,7 @@ def bench_hadx_variant(Q, W, torch, np, dev, to_dev, stream, quamba_prefill_ms, 
     fw = {k: to_dev(v) for k, v in W.make_weights(cfg).items()}
     calib = to_dev(W.make_calibration(cfg))
     nb, Lc = calib.shape[:2]
-    shapes = {"W_in": (2 * Di, Dm), "conv_w": (Di, 4), "W_x": (NX, Di), "W_dt": (Di, R), "A": (Di, N), "D": (Di,),
-              "W_outH": (Dm, Di)}
-    qd = {k: torch.empty(v, dtype=torch.int8, device=dev) for k, v in shapes.items()}
-    qd["conv_b"] = torch.empty((Di,), dtype=torch.float32, device=dev)
-    qd["dt_bias"] = torch.empty((Di,), dtype=torch.float32, device=dev)
+    qd = alloc_qweights(cfg, torch, dev)
     W_xH = torch.empty((NX, Di), dtype=torch.int8, device=dev)
     cws = torch.empty(Q.quamba_calibrate_workspace_bytes(cfg, nb, Lc), dtype=torch.uint8, device=dev)
     sc, hx = Q.quamba_calibrate_hadx(cfg, fw, calib, nb, Lc, 99.999, qd, W_xH, cws, stream)
@@ -269,17 +269,7 @@ def main():
     w = W.make_weights(cfg)
     calib = W.make_calibration(cfg)
     fw = {k: to_dev(v) for k, v in w.items()}
-    qd = {
-        "W_in": torch.empty((2 * Di, Dm), dtype=torch.int8, device=dev),
-        "conv_w": torch.empty((Di, 4), dtype=torch.int8, device=dev),
-        "W_x": torch.empty((NX, Di), dtype=torch.int8, device=dev),
-        "W_dt": torch.empty((Di, R), dtype=torch.int8, device=dev),
-        "A": torch.empty((Di, N), dtype=torch.int8, device=dev),
-        "D": torch.empty((Di,), dtype=torch.int8, device=dev),
-        "W_outH": torch.empty((Dm, Di), dtype=torch.int8, device=dev),
-        "conv_b": torch.empty((Di,), dtype=torch.float32, device=dev),
-        "dt_bias": torch.empty((Di,), dtype=torch.float32, device=dev),
-    }
+    qd = alloc_qweights(cfg, torch, dev)
     nb, Lc = calib.shape[:2]
     cws = torch.empty(Q.quamba_calibrate_workspace_bytes(cfg, nb, Lc), dtype=torch.uint8, device=dev)
     sc = Q.quamba_calibrate(cfg, fw, to_dev(calib), nb, Lc, 99.999, qd, cws, stream)
