@@ -34,3 +34,4 @@ from .model import (embed, final_norm, lm_head, greedy, model_prefill, model_dec
                     model_generate)
 from .mamba_had import (calibrate_hadx, q_prefill_hadx, q_decode_hadx,  # noqa: F401
                         hadamard_inverse_dequant)
+from .x_asym import calibrate_xasym, q_prefill_xasym, q_decode_xasym, quantize_asym  # noqa: F401
