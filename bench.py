@@ -158,7 +158,33 @@ def bench_x_scale_rules(Q, W, torch, np, dev, to_dev, stream):
         err = (torch.linalg.vector_norm(out.reshape(L, Dm).double() - ref.double())
                / torch.linalg.vector_norm(ref.double())).item()
         res[name] = {"x_clip": round(sc.s_x * 127.0, 4), "rel_err": round(err, 5)}
-    return {"workload": "c1 shape, hidden input without outlier channels, 8 rows of the x half of W_in scaled by 8; "
+
+    # the asymmetric grid of Appendix K on the same data: error, and cost next to the symmetric path
+    def rel_err():
+        torch.cuda.synchronize()
+        return (torch.linalg.vector_norm(out.reshape(L, Dm).double() - ref.double())
+                / torch.linalg.vector_norm(ref.double())).item()
+
+    def timed(fn, n=100):
+        for _ in range(20):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / n
+
+    col_bias = torch.empty((NX,), dtype=torch.int32, device=dev)
+    sc, xa = Q.quamba_calibrate_xasym(cfg, fw, calib, nb, Lc, 99.999, qd, col_bias, cws, stream)
+    qs, dims = Q.make_qweights(qd), Q.make_dims(cfg)
+    run_asym = lambda: Q.quamba_mixer_prefill_xasym(dims, qs, sc, xa, u, 1, L, out, None, None, None, ws, stream)  # noqa: E731
+    run_sym = lambda: Q.quamba_mixer_prefill(dims, qs, sc, u, 1, L, out, None, None, None, ws, stream)  # noqa: E731
+    run_asym()
+    asym = {"x_step": round(xa.s_x, 6), "symmetric_x_step": round(sc.s_x, 6), "zero_point": int(xa.zero_point),
+            "rel_err": round(rel_err(), 5), "prefill_us": round(timed(run_asym) * 1e6, 1),
+            "symmetric_prefill_us": round(timed(run_sym) * 1e6, 1)}
+    return {"asymmetric_p99.999": asym, "workload": "c1 shape, hidden input without outlier channels, 8 rows of the x half of W_in scaled by 8; "
                         "calibrated on a seeded 4x256 batch, error over a fresh 1024-token sequence",
             "rules": res}
 

@@ -200,6 +200,34 @@ int quamba_mixer_decode_hadx(const quamba_dims *dims, const quamba_qweights *qw,
  * n = k 2^m as for quamba_hadamard_quant; pointers 16-byte aligned. */
 int quamba_hadamard_inverse(const int8_t *xH_q, int M, int n, float scale, quamba_half *x_hat, void *stream);
 
+/* ---- Asymmetric 8-bit grid with percentile clipping for the scan input x (Appendix K, "MinMax Asym.
+ * Per."): x is the output of SiLU, bounded below by about -0.28 and reaching far above, so an affine
+ * grid over [lo, hi] has about half the step of the symmetric one over [-hi, hi]; the price is a
+ * zero point in the operators that read x.  The paper gives no formulas; this reading:
+ *   lo = min(min x, 0), hi = the percentile maximum, s = (hi - lo) / 255, zp = clamp(rne(-128 - lo / s))
+ *   x_q = clamp(rne(fp32(x * (1/s)) + zp))  (conv epilogue);  x = s (x_q - zp)  (inside the scan)
+ *   x_proj: sums + col_bias[n], col_bias[n] = -zp * sum_k W_x_q[n, k], multipliers with s in place of s_x
+ * quamba_xasym: col_bias [dt_rank + 2 d_state] int32 is device memory provided by the caller (16-byte
+ * aligned), the scalars are host values.  Entry points as quamba_calibrate / quamba_mixer_prefill /
+ * quamba_mixer_decode, plus `xa`; same workspaces. */
+typedef struct quamba_xasym {
+  int32_t *col_bias;
+  int32_t zero_point;
+  float s_x, inv_s_x, m_x_dt, m_x_B, m_x_C;
+} quamba_xasym;
+int quamba_calibrate_xasym(const quamba_dims *dims, const quamba_fp_weights *w, const quamba_half *calib_u,
+                           int nb, int Lc, double x_percentile, quamba_qweights *out_q,
+                           quamba_scales *out_s /* host */, quamba_xasym *out_a /* host */, void *ws,
+                           size_t ws_bytes, void *stream);
+int quamba_mixer_prefill_xasym(const quamba_dims *dims, const quamba_qweights *qw, const quamba_scales *sc,
+                               const quamba_xasym *xa, const quamba_half *u, int Bt, int L, quamba_half *out,
+                               float *ssm_state, quamba_half *conv_state, const quamba_taps *taps, void *ws,
+                               size_t ws_bytes, void *stream);
+int quamba_mixer_decode_xasym(const quamba_dims *dims, const quamba_qweights *qw, const quamba_scales *sc,
+                              const quamba_xasym *xa, const quamba_half *u, int Bt, quamba_half *out,
+                              float *ssm_state, quamba_half *conv_state, const quamba_taps *taps, void *ws,
+                              size_t ws_bytes, void *stream);
+
 /* The unquantized mixer (Section 3.1: in_proj, causal conv + SiLU, selection, selective scan,
  * gate, out_proj) in fp32 from the fp32 master weights, each of the nb sequences of length L from
  * an empty history: u [nb, L, Dm] fp16 in, out [nb * L, Dm] fp32.  It is what calibration observes

@@ -22,6 +22,8 @@ __all__ = [
     "X_PERCENTILE", "X_MSE_CLIP", "quamba_calibrate_x_rule", "quamba_clip_search_workspace_bytes", "quamba_clip_search", "quamba_mixer_fp32",
     "Hadx", "HadxTaps", "HADX_FIELDS", "make_hadx", "hadx_to_dict", "quamba_calibrate_hadx", "quamba_hadx_workspace_bytes",
     "quamba_mixer_prefill_hadx", "quamba_mixer_decode_hadx", "quamba_hadamard_inverse",
+    "XAsym", "XASYM_FIELDS", "make_xasym", "xasym_to_dict", "quamba_calibrate_xasym", "quamba_mixer_prefill_xasym",
+    "quamba_mixer_decode_xasym",
 ]
 
 X_PERCENTILE, X_MSE_CLIP = 0, 1
@@ -80,6 +82,13 @@ class HadxTaps(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("x16", "xH_q", "xhat16")]
 
 
+XASYM_FIELDS = ("s_x", "inv_s_x", "m_x_dt", "m_x_B", "m_x_C")
+
+
+class XAsym(C.Structure):
+    _fields_ = [("col_bias", C.c_void_p), ("zero_point", C.c_int32)] + [(n, C.c_float) for n in XASYM_FIELDS]
+
+
 class Layer(C.Structure):
     _fields_ = [("q", QWeights), ("s", Scales), ("norm_w", C.c_void_p)]
 
@@ -130,6 +139,23 @@ def make_hadx(W_xH, values=None) -> Hadx:
 
 def hadx_to_dict(h: Hadx) -> dict:
     return {n: float(getattr(h, n)) for n in HADX_FIELDS}
+
+
+def make_xasym(col_bias, values=None) -> XAsym:
+    """XAsym struct over a device int32 tensor col_bias (keep it alive) and, optionally, a dict of the scalars."""
+    a = XAsym()
+    a.col_bias = col_bias.data_ptr()
+    if values is not None:
+        a.zero_point = int(values["zero_point"])
+        for n in XASYM_FIELDS:
+            setattr(a, n, float(values[n]))
+    return a
+
+
+def xasym_to_dict(a: XAsym) -> dict:
+    d = {n: float(getattr(a, n)) for n in XASYM_FIELDS}
+    d["zero_point"] = int(a.zero_point)
+    return d
 
 
 def make_qweights(src) -> QWeights:
@@ -249,6 +275,14 @@ def lib():
     for name in ("quamba_calibrate_hadx", "quamba_mixer_prefill_hadx", "quamba_mixer_decode_hadx",
                  "quamba_hadamard_inverse"):
         getattr(L, name).restype = C.c_int
+    L.quamba_calibrate_xasym.argtypes = [P(Dims), P(FpWeights), vp, i, i, C.c_double, P(QWeights), P(Scales), P(XAsym),
+                                         vp, sz, vp]
+    L.quamba_mixer_prefill_xasym.argtypes = [P(Dims), P(QWeights), P(Scales), P(XAsym), vp, i, i, vp, vp, vp, P(Taps),
+                                             vp, sz, vp]
+    L.quamba_mixer_decode_xasym.argtypes = [P(Dims), P(QWeights), P(Scales), P(XAsym), vp, i, vp, vp, vp, P(Taps),
+                                            vp, sz, vp]
+    for name in ("quamba_calibrate_xasym", "quamba_mixer_prefill_xasym", "quamba_mixer_decode_xasym"):
+        getattr(L, name).restype = C.c_int
     L.quamba_mixer_fp32.argtypes = [P(Dims), P(FpWeights), vp, i, i, vp, vp, sz, vp]
     for name in ("quamba_calibrate_x_rule", "quamba_clip_search", "quamba_mixer_fp32"):
         getattr(L, name).restype = C.c_int
@@ -343,6 +377,30 @@ def quamba_mixer_decode_hadx(dims, qw, sc, hx, u, Bt, out, ssm_state, conv_state
 
 def quamba_hadamard_inverse(xH_q, M, n, scale, x_hat, stream=None):
     _check(lib().quamba_hadamard_inverse(_ptr(xH_q), M, n, float(scale), _ptr(x_hat), _stream(stream)))
+
+
+def quamba_calibrate_xasym(dims, fp_weights, calib_u, nb, Lc, x_percentile, out_q, col_bias, ws, stream=None):
+    """Returns (Scales, XAsym); `out_q` and `col_bias` (preallocated device tensors) are written on the device."""
+    fw = _struct_of_ptrs(FpWeights, fp_weights)
+    oq = _struct_of_ptrs(QWeights, out_q)
+    sc, xa = Scales(), make_xasym(col_bias)
+    _check(lib().quamba_calibrate_xasym(C.byref(_dims(dims)), C.byref(fw), _ptr(calib_u), nb, Lc, float(x_percentile),
+                                        C.byref(oq), C.byref(sc), C.byref(xa), _ptr(ws), _nbytes(ws), _stream(stream)))
+    return sc, xa
+
+
+def quamba_mixer_prefill_xasym(dims, qw, sc, xa, u, Bt, L, out, ssm_state, conv_state, taps, ws, stream=None):
+    _check(lib().quamba_mixer_prefill_xasym(C.byref(_dims(dims)), C.byref(_struct_of_ptrs(QWeights, qw)),
+                                            C.byref(scales_from_dict(sc)), C.byref(xa), _ptr(u), Bt, L, _ptr(out),
+                                            _ptr(ssm_state), _ptr(conv_state), _taps(taps), _ptr(ws), _nbytes(ws),
+                                            _stream(stream)))
+
+
+def quamba_mixer_decode_xasym(dims, qw, sc, xa, u, Bt, out, ssm_state, conv_state, taps, ws, stream=None):
+    _check(lib().quamba_mixer_decode_xasym(C.byref(_dims(dims)), C.byref(_struct_of_ptrs(QWeights, qw)),
+                                           C.byref(scales_from_dict(sc)), C.byref(xa), _ptr(u), Bt, _ptr(out),
+                                           _ptr(ssm_state), _ptr(conv_state), _taps(taps), _ptr(ws), _nbytes(ws),
+                                           _stream(stream)))
 
 
 def quamba_clip_search_workspace_bytes() -> int:

@@ -10,12 +10,15 @@ namespace quamba {
 size_t calibrate_workspace_bytes(const quamba_dims *d, int nb, int Lc);
 int calibrate(const quamba_dims *d, const quamba_fp_weights *w, const __half *calib_u, int nb, int Lc,
               int x_rule, double x_percentile, quamba_qweights *oq, quamba_scales *os, void *ws, size_t ws_bytes,
-              hipStream_t st, float *out_f32);
+              hipStream_t st, float *out_f32, float *x_clip_out = nullptr);
 int fp_mixer(const quamba_dims *d, const quamba_fp_weights *w, const __half *u, int nb, int Lc, float *out,
              void *ws, size_t ws_bytes, hipStream_t st);
 int calibrate_hadx(const quamba_dims *d, const quamba_fp_weights *w, const __half *calib_u, int nb, int Lc,
                    double x_percentile, quamba_qweights *oq, quamba_scales *os, quamba_hadx *oh, void *ws,
                    size_t ws_bytes, hipStream_t st);
+int calibrate_xasym(const quamba_dims *d, const quamba_fp_weights *w, const __half *calib_u, int nb, int Lc,
+                    double x_percentile, quamba_qweights *oq, quamba_scales *os, quamba_xasym *oa, void *ws,
+                    size_t ws_bytes, hipStream_t st);
 size_t clip_search_workspace_bytes();
 int clip_search(const float *x, size_t n, int bits, int max_iters, double *clip_out, int *iters_out, void *ws,
                 size_t ws_bytes, hipStream_t st);
@@ -110,7 +113,8 @@ int tap_copy(void *dst, const void *src, size_t bytes, hipStream_t st) {
 int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scales *sc, const __half *u,
               const int8_t *u_q_in, int Bt, int L, bool decode, __half *out, float *ssm_state,
               __half *conv_state, const quamba_taps *taps, void *ws, size_t ws_bytes, hipStream_t st,
-              const NormIn *norm = nullptr, const quamba_hadx *hx = nullptr, const quamba_hadx_taps *hx_taps = nullptr) {
+              const NormIn *norm = nullptr, const quamba_hadx *hx = nullptr, const quamba_hadx_taps *hx_taps = nullptr,
+              const quamba_xasym *xa = nullptr) {
   QUAMBA_TRY(check_dims(d));
   QUAMBA_TRY(check_q(qw, sc));
   if ((!u && !u_q_in && !norm) || !out) return fail(QUAMBA_EINVAL, "input or output pointer is NULL");
@@ -118,7 +122,12 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
   if (Bt < 1 || L < 1) return fail(QUAMBA_EINVAL, "batch=%d, L=%d must be >= 1", Bt, L);
   if (decode && (!ssm_state || !conv_state)) return fail(QUAMBA_EINVAL, "decode needs ssm_state and conv_state");
   if (hx && !hx->W_xH) return fail(QUAMBA_EINVAL, "variant: W_xH is NULL");
-  if (hx && norm) return fail(QUAMBA_EINVAL, "variant: the fused block input is not built for it");
+  if (xa && (!xa->col_bias || !aligned(xa->col_bias, 16))) return fail(QUAMBA_EINVAL, "variant: col_bias is NULL or unaligned");
+  if ((hx || xa) && norm) return fail(QUAMBA_EINVAL, "variant: the fused block input is not built for it");
+  if (hx && xa) return fail(QUAMBA_EINVAL, "the two x variants exclude each other");
+  // scale, reciprocal and zero point of the scan input's grid
+  const float s_x = xa ? xa->s_x : sc->s_x, inv_s_x = xa ? xa->inv_s_x : sc->inv_s_x;
+  const int x_zp = xa ? xa->zero_point : 0;
   const Plan p = make_plan(d, Bt, L, hx != nullptr);
   if (!ws || ws_bytes < p.total) return fail(QUAMBA_EWORKSPACE, "workspace %zu < %zu", ws_bytes, p.total);
   if (!aligned(ws, 256) || !aligned(out, 8) || (u && !aligned(u, 16)) || (u_q_in && !aligned(u_q_in, 16)))
@@ -141,7 +150,7 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
   const quamba_taps &t = taps ? *taps : none;
 
   // Generation with a handful of sequences: [norm +] in_proj + conv step in one streaming kernel.
-  const bool few = decode && M <= 4 && Dm <= 8192 && g_fuse_decode && !hx;
+  const bool few = decode && M <= 4 && Dm <= 8192 && g_fuse_decode && !hx && !xa;
   // quantize the block input (Eq. 2)
   const int8_t *uq = u_q_in;
   if (!uq && !norm) {
@@ -173,10 +182,10 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
     // causal conv + SiLU + requantization with the percentile scale of x
     if (decode) {
       QUAMBA_TRY(launch_conv_step(xz_q, 2 * Di, qw->conv_w, qw->conv_b, Bt, Di, sc->s_cw, sc->s_xpre,
-                                  sc->inv_s_x, x_q, conv_state, st, x16));
+                                  inv_s_x, x_q, conv_state, st, x16, x_zp));
     } else {
-      QUAMBA_TRY(launch_conv_prefill(xz_q, 2 * Di, qw->conv_w, qw->conv_b, Bt, L, Di, sc->m_conv, sc->inv_s_x,
-                                     sc->s_xpre, x_q, conv_state, st, x16));
+      QUAMBA_TRY(launch_conv_prefill(xz_q, 2 * Di, qw->conv_w, qw->conv_b, Bt, L, Di, sc->m_conv, inv_s_x,
+                                     sc->s_xpre, x_q, conv_state, st, x16, x_zp));
     }
   }
   if (hx) {  // forward Hadamard & quantize: x_q now holds the codes of H_n x
@@ -187,8 +196,9 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
   QUAMBA_TRY(tap_copy(t.x_q, x_q, (size_t)M * Di, st));
   // x_proj: columns dt_low | B | C, each with its own output scale
   {
-    GemmEpilogue e{dbc_q, nullptr, t.acc_x, NX, R, R + N, hx ? hx->m_xh_dt : sc->m_x_dt, hx ? hx->m_xh_B : sc->m_x_B,
-                   hx ? hx->m_xh_C : sc->m_x_C};
+    GemmEpilogue e{dbc_q, nullptr, t.acc_x, NX, R, R + N, hx ? hx->m_xh_dt : (xa ? xa->m_x_dt : sc->m_x_dt),
+                   hx ? hx->m_xh_B : (xa ? xa->m_x_B : sc->m_x_B), hx ? hx->m_xh_C : (xa ? xa->m_x_C : sc->m_x_C),
+                   xa ? xa->col_bias : nullptr};
     QUAMBA_TRY(launch_gemm_i8(x_q, Di, hx ? hx->W_xH : qw->W_x, Di, M, NX, Di, e, base + p.gemm, p.gemm_bytes, st));
     QUAMBA_TRY(tap_copy(t.dbc_q, dbc_q, (size_t)M * NX, st));
   }
@@ -212,7 +222,7 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
     a.x_q = x_q; a.dt_q = dt_q; a.z_q = xz_q + Di; a.ldz = 2 * Di;
     a.B_q = dbc_q + R; a.C_q = dbc_q + R + N; a.ldbc = NX;
     a.A_q = qw->A; a.D_q = qw->D; a.dt_bias = qw->dt_bias;
-    a.s_x = sc->s_x; a.s_dt = sc->s_dt; a.s_z = sc->s_z; a.s_B = sc->s_B; a.s_C = sc->s_C;
+    a.s_x = s_x; a.x_zero_point = x_zp; a.s_dt = sc->s_dt; a.s_z = sc->s_z; a.s_B = sc->s_B; a.s_C = sc->s_C;
     a.s_A = sc->s_A; a.s_D = sc->s_D;
     a.Bt = Bt; a.L = L; a.Di = Di; a.g16 = g16; a.y_f32 = t.y_f32; a.ssm_state = ssm_state;
     a.x_f16 = x16;
@@ -542,6 +552,34 @@ int quamba_calibrate_hadx(const quamba_dims *dims, const quamba_fp_weights *w, c
   if (!calib_u || !out_h || !out_h->W_xH) return fail(QUAMBA_EINVAL, "calibrate: NULL pointer");
   return calibrate_hadx(dims, w, reinterpret_cast<const __half *>(calib_u), nb, Lc, x_percentile, out_q, out_s, out_h,
                         ws, ws_bytes, as_stream(stream));
+}
+
+int quamba_calibrate_xasym(const quamba_dims *dims, const quamba_fp_weights *w, const quamba_half *calib_u, int nb,
+                           int Lc, double x_percentile, quamba_qweights *out_q, quamba_scales *out_s,
+                           quamba_xasym *out_a, void *ws, size_t ws_bytes, void *stream) {
+  QUAMBA_TRY(check_calibrate_args(dims, w, out_q, out_s, ws, nb, Lc, x_percentile));
+  if (!calib_u || !out_a || !out_a->col_bias) return fail(QUAMBA_EINVAL, "calibrate: NULL pointer");
+  return calibrate_xasym(dims, w, reinterpret_cast<const __half *>(calib_u), nb, Lc, x_percentile, out_q, out_s, out_a,
+                         ws, ws_bytes, as_stream(stream));
+}
+
+int quamba_mixer_prefill_xasym(const quamba_dims *dims, const quamba_qweights *qw, const quamba_scales *sc,
+                               const quamba_xasym *xa, const quamba_half *u, int Bt, int L, quamba_half *out,
+                               float *ssm_state, quamba_half *conv_state, const quamba_taps *taps, void *ws,
+                               size_t ws_bytes, void *stream) {
+  if (!u || !xa) return fail(QUAMBA_EINVAL, "u or xa is NULL");
+  return run_mixer(dims, qw, sc, reinterpret_cast<const __half *>(u), nullptr, Bt, L, false,
+                   reinterpret_cast<__half *>(out), ssm_state, reinterpret_cast<__half *>(conv_state), taps, ws, ws_bytes,
+                   as_stream(stream), nullptr, nullptr, nullptr, xa);
+}
+
+int quamba_mixer_decode_xasym(const quamba_dims *dims, const quamba_qweights *qw, const quamba_scales *sc,
+                              const quamba_xasym *xa, const quamba_half *u, int Bt, quamba_half *out, float *ssm_state,
+                              quamba_half *conv_state, const quamba_taps *taps, void *ws, size_t ws_bytes, void *stream) {
+  if (!u || !xa) return fail(QUAMBA_EINVAL, "u or xa is NULL");
+  return run_mixer(dims, qw, sc, reinterpret_cast<const __half *>(u), nullptr, Bt, 1, true,
+                   reinterpret_cast<__half *>(out), ssm_state, reinterpret_cast<__half *>(conv_state), taps, ws, ws_bytes,
+                   as_stream(stream), nullptr, nullptr, nullptr, xa);
 }
 
 size_t quamba_hadx_workspace_bytes(const quamba_dims *dims, int batch, int L) {

@@ -273,6 +273,28 @@ __global__ void copy_f32_kernel(const float *x, float *y, size_t n) {
   if (i < n) y[i] = x[i];
 }
 
+// max(0, -min x) over x[0, n), as the bit pattern of a non-negative float
+__global__ __launch_bounds__(256) void negmax_kernel(const float *__restrict__ x, size_t n, unsigned *slot) {
+  float m = 0.f;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) m = fmaxf(m, -x[i]);
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+  if ((threadIdx.x & 63) == 0) atomicMax(slot, __float_as_uint(m));
+}
+
+// out[r] = factor * sum_k w[r, k] (int32; |sum| <= 128 K): one workgroup per row
+__global__ __launch_bounds__(256) void scaled_rowsum_i8_kernel(const int8_t *__restrict__ w, int K, int factor,
+                                                               int32_t *__restrict__ out) {
+  int acc = 0;
+  for (int k = threadIdx.x; k < K; k += 256) acc += w[(size_t)blockIdx.x * K + k];
+  __shared__ int part[4];
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) out[blockIdx.x] = factor * (part[0] + part[1] + part[2] + part[3]);
+}
+
 inline unsigned nblk(size_t n) { return (unsigned)((n + 255) / 256); }
 
 struct CalPlan {
@@ -384,7 +406,7 @@ int fp_mixer(const quamba_dims *d, const quamba_fp_weights *w, const __half *u, 
 
 int calibrate(const quamba_dims *d, const quamba_fp_weights *w, const __half *calib_u, int nb, int Lc,
               int x_rule, double x_percentile, quamba_qweights *oq, quamba_scales *os, void *ws, size_t ws_bytes,
-              hipStream_t st, float *out_f32);
+              hipStream_t st, float *out_f32, float *x_clip_out = nullptr);
 
 namespace {
 // res[row] += out[row]; u[row] = res[row] / sqrt(mean(res[row]^2) + eps) * w   (fp32; one workgroup per row)
@@ -427,7 +449,7 @@ int calibrate_block(const quamba_dims *d, const quamba_fp_weights *w, const __ha
 // g W_out^T, which feeds the next block of a stack.
 int calibrate(const quamba_dims *d, const quamba_fp_weights *w, const __half *calib_u, int nb, int Lc,
               int x_rule, double x_percentile, quamba_qweights *oq, quamba_scales *os, void *ws, size_t ws_bytes,
-              hipStream_t st, float *out_f32) {
+              hipStream_t st, float *out_f32, float *x_clip_out) {
   const CalPlan p = cal_plan(d, nb, Lc);
   if (ws_bytes < p.total) return fail(QUAMBA_EWORKSPACE, "calibrate: workspace %zu < %zu", ws_bytes, p.total);
   const int Dm = d->d_model, Di = d->d_inner, N = d->d_state, R = d->dt_rank, NX = R + 2 * N;
@@ -498,6 +520,7 @@ int calibrate(const quamba_dims *d, const quamba_fp_weights *w, const __half *ca
   std::memcpy(&xp, &prefix, 4);
   }
 
+  if (x_clip_out) *x_clip_out = xp;  // the clipping value of x before it becomes a scale
   auto sc_of = [](float m) { return m > 0.f ? (float)((double)m / 127.0) : 1.0f; };
   quamba_scales s{};
   s.s_u = sc_of(mx[S_U]); s.s_xpre = sc_of(mx[S_XPRE]); s.s_z = sc_of(mx[S_Z]); s.s_x = sc_of(xp);
@@ -573,6 +596,43 @@ int calibrate_hadx(const quamba_dims *d, const quamba_fp_weights *w, const __hal
   oh->xhat_scale = (float)(a / (double)Di);
   const size_t nw = (size_t)NX * Di;
   hipLaunchKernelGGL(quantize_f32_kernel, dim3(nblk(nw)), dim3(256), 0, st, b.woh, oh->W_xH, nw, (float)(1.0 / c));
+  QUAMBA_LAUNCH_CHECK();
+  QUAMBA_HIP(hipStreamSynchronize(st));
+  return QUAMBA_OK;
+}
+
+// Calibration with an asymmetric grid for the scan input (Appendix K): Quamba's calibration, then
+// lo = min(min x, 0), hi = the percentile maximum, s = (hi - lo) / 255, zero point
+// clamp(rne(-128 - lo / s)), and the x_proj column term -zp * rowsum(W_x_q).
+int calibrate_xasym(const quamba_dims *d, const quamba_fp_weights *w, const __half *calib_u, int nb, int Lc,
+                    double x_percentile, quamba_qweights *oq, quamba_scales *os, quamba_xasym *oa, void *ws,
+                    size_t ws_bytes, hipStream_t st) {
+  int rc;
+  float hi = 0.f;
+  if ((rc = calibrate(d, w, calib_u, nb, Lc, QUAMBA_X_PERCENTILE, x_percentile, oq, os, ws, ws_bytes, st, nullptr, &hi)))
+    return rc;
+  const CalPlan p = cal_plan(d, nb, Lc);
+  const CalBufs b = carve(p, ws);
+  const int Di = d->d_inner, NX = d->dt_rank + 2 * d->d_state;
+  const size_t nx = (size_t)nb * Lc * Di;
+  hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(256), 0, st, b.slots, (size_t)32, 0u);
+  hipLaunchKernelGGL(negmax_kernel, dim3((unsigned)std::min<size_t>((nx + 255) / 256, 2048)), dim3(256), 0, st, b.x, nx,
+                     b.slots);
+  QUAMBA_LAUNCH_CHECK();
+  float neg;
+  QUAMBA_HIP(hipMemcpyAsync(&neg, b.slots, sizeof(neg), hipMemcpyDeviceToHost, st));
+  QUAMBA_HIP(hipStreamSynchronize(st));
+  const double lo = -(double)neg, span = (double)hi - lo;
+  const float s = span > 0.0 ? (float)(span / 255.0) : 1.0f;
+  int zp = (int)std::nearbyint(-128.0 - lo / (double)s);
+  zp = std::min(127, std::max(-128, zp));
+  oa->s_x = s;
+  oa->inv_s_x = (float)(1.0 / (double)s);
+  oa->zero_point = zp;
+  oa->m_x_dt = (float)((double)s * (double)os->s_Wx / (double)os->s_dtl);
+  oa->m_x_B = (float)((double)s * (double)os->s_Wx / (double)os->s_B);
+  oa->m_x_C = (float)((double)s * (double)os->s_Wx / (double)os->s_C);
+  hipLaunchKernelGGL(scaled_rowsum_i8_kernel, dim3(NX), dim3(256), 0, st, oq->W_x, Di, -zp, oa->col_bias);
   QUAMBA_LAUNCH_CHECK();
   QUAMBA_HIP(hipStreamSynchronize(st));
   return QUAMBA_OK;

@@ -46,6 +46,9 @@ struct GemmEpilogue {
   int ldo;
   int e0, e1;
   float m0, m1, m2;
+  // optional int32 term per output column [N], added to the sums before the multiplier (the
+  // zero-point correction of an asymmetric input grid); 16-byte aligned; the `acc` tap stays raw
+  const int32_t *col_bias;
 };
 
 // `ws` (may be NULL) lets skinny problems split K; gemm_workspace_bytes is the most they use.
@@ -57,11 +60,12 @@ int launch_quantize_f16(const __half *x, int8_t *q, size_t n, float inv_s, hipSt
 
 int launch_conv_prefill(const int8_t *xpre_q, int ldx, const int8_t *w_q, const float *conv_b,
                         int Bt, int L, int Di, float m_conv, float inv_s_x, float s_xpre,
-                        int8_t *x_q, __half *conv_state, hipStream_t st, __half *x16 = nullptr);
+                        int8_t *x_q, __half *conv_state, hipStream_t st, __half *x16 = nullptr,
+                        int x_zero_point = 0);
 
 int launch_conv_step(const int8_t *xpre_q, int ldx, const int8_t *w_q, const float *conv_b, int Bt,
                      int Di, float s_cw, float s_xpre, float inv_s_x, int8_t *x_q,
-                     __half *conv_state, hipStream_t st, __half *x16 = nullptr);
+                     __half *conv_state, hipStream_t st, __half *x16 = nullptr, int x_zero_point = 0);
 
 int launch_add_rmsnorm_quant(const __half *x_out, __half *res, const __half *weight, float eps,
                              float inv_s, int8_t *u_q, int M, int Dm, hipStream_t st);
@@ -84,6 +88,8 @@ struct ScanArgs {
   // optional: the scan input given in half precision [Bt*L, Di] instead of s_x * x_q
   // (the Appendix H comparison variant); x_q and s_x are then ignored
   const __half *x_f16;
+  // zero point of an asymmetric x grid (Appendix K): x = s_x (x_q - x_zero_point); 0 = symmetric
+  int x_zero_point;
 };
 
 size_t scan_workspace_bytes(int Bt, int L, int Di);

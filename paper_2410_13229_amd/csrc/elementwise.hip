@@ -51,13 +51,16 @@ __device__ __forceinline__ float silu_fast(float v) {
   return v * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-v * 1.44269504088896340736f));
 }
 
-// F16OUT (the Appendix H comparison variant): the SiLU output is stored in half precision into
-// x16 instead of being quantized into xq.
-template <bool F16OUT>
+// OUT_F16 (the Appendix H comparison variant): the SiLU output is stored in half precision into
+// x16 instead of being quantized into xq.  OUT_ASYM (Appendix K): codes on an asymmetric grid,
+// clamp(rne(v / s + zero point)).
+enum ConvOut { OUT_SYM, OUT_F16, OUT_ASYM };
+template <ConvOut MODE>
 __global__ __launch_bounds__(256) void conv_prefill_kernel(
     const int8_t *__restrict__ xpre, int ldx, const int8_t *__restrict__ wq,
     const float *__restrict__ bias, int L, int Di, float m_conv, float inv_s_x, float s_xpre,
-    int8_t *__restrict__ xq, __half *__restrict__ x16, __half *__restrict__ conv_state) {
+    int8_t *__restrict__ xq, __half *__restrict__ x16, float x_zp, __half *__restrict__ conv_state) {
+  constexpr bool F16OUT = MODE == OUT_F16;
   const int c4 = blockIdx.x * 256 + threadIdx.x;  // channel group
   if (c4 * 4 >= Di) return;
   const int d0 = c4 * 4;
@@ -94,6 +97,7 @@ __global__ __launch_bounds__(256) void conv_prefill_kernel(
         const int a = __builtin_amdgcn_sdot4((int)taps[c], wword[c], 0, false);
         const float v = __fadd_rn(__fmul_rn(static_cast<float>(a), m_conv), bb[c]);
         sv[c] = F16OUT ? silu_fast(v) : silu_fast(v) * inv_s_x;
+        if constexpr (MODE == OUT_ASYM) sv[c] = __fadd_rn(sv[c], x_zp);
       }
       if constexpr (F16OUT)
         *reinterpret_cast<uint2 *>(x16 + ((size_t)b * L + t0 + i) * Di + d0) = pack_f16x4(sv[0], sv[1], sv[2], sv[3]);
@@ -128,7 +132,7 @@ __global__ __launch_bounds__(256) void conv_step_kernel(const int8_t *__restrict
                                                         const float *__restrict__ bias, int Bt, int Di,
                                                         float s_cw, float s_xpre, float inv_s_x,
                                                         int8_t *__restrict__ xq, __half *__restrict__ x16,
-                                                        __half *__restrict__ conv_state) {
+                                                        float x_zp, __half *__restrict__ conv_state) {
   const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;  // (b, channel group of 4)
   const int groups = Di / 4;
   if (idx >= (size_t)Bt * groups) return;
@@ -141,8 +145,12 @@ __global__ __launch_bounds__(256) void conv_step_kernel(const int8_t *__restrict
     conv_step4_values(xin, wq + (size_t)d0 * 4, bias + d0, cs, s_cw, s_xpre, sv);
     *reinterpret_cast<uint2 *>(x16 + (size_t)b * Di + d0) = pack_f16x4(sv[0], sv[1], sv[2], sv[3]);
   } else {
+    float sv[4];
+    conv_step4_values(xin, wq + (size_t)d0 * 4, bias + d0, cs, s_cw, s_xpre, sv);
+    // x_zp = 0 is the symmetric grid: adding it changes nothing
     *reinterpret_cast<unsigned *>(xq + (size_t)b * Di + d0) =
-        conv_step4(xin, wq + (size_t)d0 * 4, bias + d0, cs, s_cw, s_xpre, inv_s_x);
+        pack_q8x4(__fadd_rn(sv[0] * inv_s_x, x_zp), __fadd_rn(sv[1] * inv_s_x, x_zp), __fadd_rn(sv[2] * inv_s_x, x_zp),
+                  __fadd_rn(sv[3] * inv_s_x, x_zp));
   }
 }
 
@@ -221,24 +229,28 @@ int launch_quantize_f16(const __half *x, int8_t *q, size_t n, float inv_s, hipSt
 
 int launch_conv_prefill(const int8_t *xpre_q, int ldx, const int8_t *w_q, const float *conv_b, int Bt,
                         int L, int Di, float m_conv, float inv_s_x, float s_xpre, int8_t *x_q,
-                        __half *conv_state, hipStream_t st, __half *x16) {
+                        __half *conv_state, hipStream_t st, __half *x16, int x_zero_point) {
   dim3 grid((Di / 4 + 255) / 256, (L + CONV_TT - 1) / CONV_TT, Bt);
+  const float zp = static_cast<float>(x_zero_point);
   if (x16)
-    hipLaunchKernelGGL(conv_prefill_kernel<true>, grid, dim3(256), 0, st, xpre_q, ldx, w_q, conv_b, L, Di,
-                       m_conv, inv_s_x, s_xpre, x_q, x16, conv_state);
+    hipLaunchKernelGGL(conv_prefill_kernel<OUT_F16>, grid, dim3(256), 0, st, xpre_q, ldx, w_q, conv_b, L, Di,
+                       m_conv, inv_s_x, s_xpre, x_q, x16, zp, conv_state);
+  else if (x_zero_point != 0)
+    hipLaunchKernelGGL(conv_prefill_kernel<OUT_ASYM>, grid, dim3(256), 0, st, xpre_q, ldx, w_q, conv_b, L, Di,
+                       m_conv, inv_s_x, s_xpre, x_q, x16, zp, conv_state);
   else
-    hipLaunchKernelGGL(conv_prefill_kernel<false>, grid, dim3(256), 0, st, xpre_q, ldx, w_q, conv_b, L, Di,
-                       m_conv, inv_s_x, s_xpre, x_q, x16, conv_state);
+    hipLaunchKernelGGL(conv_prefill_kernel<OUT_SYM>, grid, dim3(256), 0, st, xpre_q, ldx, w_q, conv_b, L, Di,
+                       m_conv, inv_s_x, s_xpre, x_q, x16, zp, conv_state);
   QUAMBA_LAUNCH_CHECK();
   return QUAMBA_OK;
 }
 
 int launch_conv_step(const int8_t *xpre_q, int ldx, const int8_t *w_q, const float *conv_b, int Bt,
                      int Di, float s_cw, float s_xpre, float inv_s_x, int8_t *x_q, __half *conv_state,
-                     hipStream_t st, __half *x16) {
+                     hipStream_t st, __half *x16, int x_zero_point) {
   const size_t n = (size_t)Bt * (Di / 4);
   hipLaunchKernelGGL(conv_step_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, xpre_q, ldx,
-                     w_q, conv_b, Bt, Di, s_cw, s_xpre, inv_s_x, x_q, x16, conv_state);
+                     w_q, conv_b, Bt, Di, s_cw, s_xpre, inv_s_x, x_q, x16, static_cast<float>(x_zero_point), conv_state);
   QUAMBA_LAUNCH_CHECK();
   return QUAMBA_OK;
 }

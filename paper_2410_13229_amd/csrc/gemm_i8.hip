@@ -40,10 +40,16 @@ __device__ __forceinline__ int swzk(int row, int chunk) {
 
 // Epilogue for four consecutive columns gn..gn+3 of row gm.  The column ranges end on multiples
 // of 4, so one multiplier serves the group.
-__device__ __forceinline__ void emit4(const GemmEpilogue &epi, int gm, int gn, int N, const int (&a)[4]) {
+__device__ __forceinline__ void emit4(const GemmEpilogue &epi, int gm, int gn, int N, const int (&raw)[4]) {
   if (epi.acc) {
-    v4i v = {a[0], a[1], a[2], a[3]};
+    v4i v = {raw[0], raw[1], raw[2], raw[3]};
     *reinterpret_cast<v4i *>(epi.acc + (size_t)gm * N + gn) = v;
+  }
+  int a[4] = {raw[0], raw[1], raw[2], raw[3]};
+  if (epi.col_bias) {
+    const v4i b = *reinterpret_cast<const v4i *>(epi.col_bias + gn);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) a[e] += b[e];
   }
   const float m = gn < epi.e0 ? epi.m0 : (gn < epi.e1 ? epi.m1 : epi.m2);
   if (epi.out_i8) {
@@ -108,7 +114,12 @@ __device__ __forceinline__ void store_tiles_rows(const v16i (&acc)[TN][TM], int 
       for (int g = 0; g < 4; ++g) {
         const int col = i * 32 + 8 * g + 4 * (lane >> 5);
         const int gn = n_base + col;
-        const int a[4] = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+        int a[4] = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+        if (epi.col_bias && gn < N) {
+          const v4i b = *reinterpret_cast<const v4i *>(epi.col_bias + gn);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) a[e] += b[e];
+        }
         const float m = gn < epi.e0 ? epi.m0 : (gn < epi.e1 ? epi.m1 : epi.m2);
         if (f16) {
           union {

@@ -67,6 +67,7 @@ struct Dev {
   float m_dt;
   int8_t *dt_out;
   const __half *x_f16;  // scan input in half precision instead of s_x * x_q (comparison variant)
+  float x_off;          // -s_x * zero point of an asymmetric x grid: x = s_x x_q + x_off (0 = symmetric)
 };
 
 // Dequantize B (and C) of tokens [row0, row0+cnt) into LDS as fp32 [TB][16].
@@ -208,7 +209,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_chunk_kernel(Dev p) {
     for (int i = 0; i < TS; ++i) {
       if (t + i < t1) {
         const float xv = XF16 ? __half2float(__ushort_as_half(static_cast<unsigned short>(r.x[i])))
-                              : p.s_x * static_cast<float>(r.x[i]);
+                              : __builtin_fmaf(p.s_x, static_cast<float>(r.x[i]), p.x_off);
         const int dtq = FUSE_DT ? static_cast<int>(sDT[wave][tl + i][lane]) : r.dt[i];
         const float dt = softplus_f(p.s_dt * static_cast<float>(dtq) + bias);
         const float u = dt * xv;
@@ -320,7 +321,7 @@ __global__ __launch_bounds__(256) void scan_step_kernel(Dev p, float *__restrict
   const unsigned bw = *reinterpret_cast<const unsigned *>(p.B_q + (size_t)b * p.ldbc + 4 * q);
   const unsigned cw = *reinterpret_cast<const unsigned *>(p.C_q + (size_t)b * p.ldbc + 4 * q);
   const float xv = p.x_f16 ? __half2float(p.x_f16[(size_t)b * p.Di + d])
-                           : p.s_x * static_cast<float>(p.x_q[(size_t)b * p.Di + d]);
+                           : __builtin_fmaf(p.s_x, static_cast<float>(p.x_q[(size_t)b * p.Di + d]), p.x_off);
   int dtq;
   if (FUSE_DT) {
     const int8_t *wrow = p.W_dt + (size_t)d * p.R;
@@ -374,6 +375,7 @@ Dev make_dev(const ScanArgs &a) {
   p.dtlow_q = a.dtlow_q; p.W_dt = a.W_dt; p.lddl = a.lddl; p.R = a.R; p.m_dt = a.m_dt; p.dt_out = a.dt_out;
   if (a.dtlow_q && a.dt_out) p.dt_q = a.dt_out;
   p.x_f16 = a.x_f16;
+  p.x_off = -a.s_x * static_cast<float>(a.x_zero_point);  // -0.f for the symmetric grid: adds nothing
   return p;
 }
 
