@@ -29,7 +29,7 @@ SCAN_FLOP_PER_TD = 123.0     # 16 x (exp + 2 mul + 2 fma) + D*x + softplus + gat
 # HBM bytes per launch of the dominant kernel (in_proj GEMM, c1) from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE runs of `bench.py --probe`, scaled by a plain device copy in the same run
 # (profiles/in_proj_gemm_c1_hbm_traffic.txt).  None until measured for a workload.
-MEASURED_TRAFFIC_BYTES = {"c1": 90.7e6}
+MEASURED_TRAFFIC_BYTES = {"c1": 89.6e6}
 
 
 def alloc_qweights(cfg, torch, dev):
@@ -256,6 +256,9 @@ def main():
     ap.add_argument("--decode-steps", type=int, default=1000)
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle (cpu_baseline) leg")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-two-streams", action="store_true",
+                    help="skip the extra figure with independent steps on two streams (keeps a kernel trace of the "
+                         "run free of overlapped launches)")
     ap.add_argument("--no-model", action="store_true", help="skip the whole-model shell (64-layer 2.8B) timings")
     ap.add_argument("--model-layers", type=int, default=64)
     ap.add_argument("--model-distinct", type=int, default=4,
@@ -339,7 +342,7 @@ def main():
     # sequences may overlap (one step's GEMMs run on the matrix cores under another's scan passes on
     # the vector units).  Extra figure; `value` above is the one-stream, one-step-at-a-time rate.
     two_streams = None
-    if not args.no_decode:
+    if not args.no_two_streams:
         lanes = [(stream, out, ws)]
         lanes.append((torch.cuda.Stream(), torch.empty_like(out), torch.empty_like(ws)))
 
