@@ -19,6 +19,9 @@
  *     synchronise the stream to hand the scales back in host memory, and graph-replayed
  *     generation (quamba_model_generate with use_graph), which waits for its last replay and
  *     lets the HIP runtime allocate what its graph objects need.
+ *   - the library keeps no state between calls: calls that share no output, state or workspace
+ *     buffer may be in flight on different streams at once (independent sequences overlap well:
+ *     one call's projections use the matrix cores while another's scan uses the vector units).
  *   - fp16 tensors are IEEE binary16 (quamba_half = raw 16-bit storage).
  *   - tensors are dense row-major with the last index fastest; weights are [out, in].
  *   - notation: Dm = d_model, Di = d_inner, N = d_state (16), R = dt_rank, W = d_conv (4),
