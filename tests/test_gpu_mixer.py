@@ -384,6 +384,37 @@ def test_x_scale_rules_rank_as_in_the_oracle():
     assert err_g["mse"] <= 1.05 * min(err_g[99.0], err_g[99.99], err_g[100.0])
 
 
+def test_two_calls_in_flight_on_two_streams():
+    """Calls that share no output, state or workspace may overlap on different streams: each must
+    give what it gives alone."""
+    cfg = W.CONFIGS["c0"]
+    w, qw, sc = oracle_setup(cfg)
+    qd = qweights_to_dev(qw)
+    us = [dev(W.make_hidden(cfg, batch=2, seqlen=300, stream=40 + i)) for i in range(2)]
+    alone = []
+    for u in us:
+        out = empty((2, 300, cfg.d_model), torch.float16)
+        ssm = torch.zeros((2, cfg.d_inner, cfg.d_state), dtype=torch.float32, device="cuda:0")
+        Q.quamba_mixer_prefill(cfg, qd, sc, u, 2, 300, out, ssm, None, None, workspace(Q.quamba_workspace_bytes(cfg, 2, 300)))
+        torch.cuda.synchronize()
+        alone.append((host(out), host(ssm)))
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    outs = [empty((2, 300, cfg.d_model), torch.float16) for _ in range(2)]
+    ssms = [torch.zeros((2, cfg.d_inner, cfg.d_state), dtype=torch.float32, device="cuda:0") for _ in range(2)]
+    wss = [workspace(Q.quamba_workspace_bytes(cfg, 2, 300)) for _ in range(2)]
+    torch.cuda.synchronize()
+    for rep in range(6):  # several rounds so that the two streams really interleave
+        for i in range(2):
+            with torch.cuda.stream(streams[i]):
+                if rep:
+                    ssms[i].zero_()  # h0 = 0 again, ordered on the call's own stream
+                Q.quamba_mixer_prefill(cfg, qd, sc, us[i], 2, 300, outs[i], ssms[i], None, None, wss[i], streams[i])
+    torch.cuda.synchronize()
+    for i in range(2):
+        assert np.array_equal(host(outs[i]).view(np.uint16), alone[i][0].view(np.uint16))
+        assert np.array_equal(host(ssms[i]), alone[i][1])
+
+
 def test_decode_steps_replayed_from_a_hip_graph():
     """The decode call enqueues kernel launches only, so a caller may capture it.  Several replays,
     with eager work and synchronisations in between, must each reproduce the eager result bit for bit."""
