@@ -680,6 +680,11 @@ int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, i
     // K = 8192 or with many more tiles the split-K / single-pass 64 x 64 form stays ahead).
     const long tiles_32 = (long)((M + 63) / 64) * ((N + 31) / 32);
     if (k128 && tiles_32 >= 192 && tiles_32 <= 512 && K <= 6144) kind = 7;
+    // Very many rows and an N that 160-wide tiles cover without waste: the 128 x 160 tiles with two
+    // K groups (N = 320, K = 8192, 16384 tokens: 56 vs 80 us; at 8192 tokens and below the 64 x 64
+    // tiles are ahead again).
+    const int n160 = (N + 159) / 160 * 160;
+    if (k128 && M >= 16384 && N * 10 >= n160 * 9) kind = 6;
   }
   else if (k128 && M >= 256 && N >= 640)
     kind = tiles_256 >= 192 ? 4 : (tiles_128 < 192 ? 5 : (tiles_128 <= 384 ? 6 : 2));  // few big tiles: 64x64 ones
@@ -695,7 +700,9 @@ int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, i
   }
   // deep K in whole 256-byte slices: half as many barriers for the same bytes
   if ((K % 256) == 0 && kind == 6) kind = 8;
-  if ((K % 256) == 0 && kind == 5 && M > 64) kind = 9;  // (decode-sized M measured better with 128-byte slices)
+  // (decode-sized M measured better with 128-byte slices, and so do outputs with so many 64 x 64
+  // tiles that K is not split over the grid: there the deeper ring of the 128-byte form wins)
+  if ((K % 256) == 0 && kind == 5 && M > 64 && (long)((M + 63) / 64) * ((N + 63) / 64) <= 256) kind = 9;
   if (g_gemm_variant >= 0 && g_gemm_variant <= 10 &&
       (g_gemm_variant < 2 || (g_gemm_variant == 3 && k64) || (g_gemm_variant != 3 && k128)))
     kind = g_gemm_variant;
