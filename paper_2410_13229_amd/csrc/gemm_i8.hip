@@ -700,9 +700,10 @@ int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, i
   }
   // deep K in whole 256-byte slices: half as many barriers for the same bytes
   if ((K % 256) == 0 && kind == 6) kind = 8;
-  // (decode-sized M measured better with 128-byte slices, and so do outputs with so many 64 x 64
-  // tiles that K is not split over the grid: there the deeper ring of the 128-byte form wins)
-  if ((K % 256) == 0 && kind == 5 && M > 64 && (long)((M + 63) / 64) * ((N + 63) / 64) <= 256) kind = 9;
+  // (decode-sized M measured better with 128-byte slices, and so do skinny outputs, N <= 512, with so
+  // many 64 x 64 tiles that K is not split over the grid: there the deeper ring of the 128-byte form wins)
+  const bool skinny_unsplit = N <= 512 && (long)((M + 63) / 64) * ((N + 63) / 64) > 256;
+  if ((K % 256) == 0 && kind == 5 && M > 64 && !skinny_unsplit) kind = 9;
   if (g_gemm_variant >= 0 && g_gemm_variant <= 10 &&
       (g_gemm_variant < 2 || (g_gemm_variant == 3 && k64) || (g_gemm_variant != 3 && k128)))
     kind = g_gemm_variant;
