@@ -127,6 +127,7 @@ __global__ __launch_bounds__(256) void conv_prefill_kernel(
 }
 
 // ------------------------------------------------------------------ conv, decode step
+template <ConvOut MODE>
 __global__ __launch_bounds__(256) void conv_step_kernel(const int8_t *__restrict__ xpre, int ldx,
                                                         const int8_t *__restrict__ wq,
                                                         const float *__restrict__ bias, int Bt, int Di,
@@ -140,17 +141,18 @@ __global__ __launch_bounds__(256) void conv_step_kernel(const int8_t *__restrict
   const int d0 = static_cast<int>(idx % groups) * 4;
   const unsigned xin = *reinterpret_cast<const unsigned *>(xpre + (size_t)b * ldx + d0);
   __half *cs = conv_state + ((size_t)b * Di + d0) * 3;
-  if (x16) {  // half-precision output, no quantizer
-    float sv[4];
-    conv_step4_values(xin, wq + (size_t)d0 * 4, bias + d0, cs, s_cw, s_xpre, sv);
-    *reinterpret_cast<uint2 *>(x16 + (size_t)b * Di + d0) = pack_f16x4(sv[0], sv[1], sv[2], sv[3]);
+  if constexpr (MODE == OUT_SYM) {
+    *reinterpret_cast<unsigned *>(xq + (size_t)b * Di + d0) =
+        conv_step4(xin, wq + (size_t)d0 * 4, bias + d0, cs, s_cw, s_xpre, inv_s_x);
   } else {
     float sv[4];
     conv_step4_values(xin, wq + (size_t)d0 * 4, bias + d0, cs, s_cw, s_xpre, sv);
-    // x_zp = 0 is the symmetric grid: adding it changes nothing
-    *reinterpret_cast<unsigned *>(xq + (size_t)b * Di + d0) =
-        pack_q8x4(__fadd_rn(sv[0] * inv_s_x, x_zp), __fadd_rn(sv[1] * inv_s_x, x_zp), __fadd_rn(sv[2] * inv_s_x, x_zp),
-                  __fadd_rn(sv[3] * inv_s_x, x_zp));
+    if constexpr (MODE == OUT_F16)  // half-precision output, no quantizer
+      *reinterpret_cast<uint2 *>(x16 + (size_t)b * Di + d0) = pack_f16x4(sv[0], sv[1], sv[2], sv[3]);
+    else
+      *reinterpret_cast<unsigned *>(xq + (size_t)b * Di + d0) =
+          pack_q8x4(__fadd_rn(sv[0] * inv_s_x, x_zp), __fadd_rn(sv[1] * inv_s_x, x_zp),
+                    __fadd_rn(sv[2] * inv_s_x, x_zp), __fadd_rn(sv[3] * inv_s_x, x_zp));
   }
 }
 
@@ -249,8 +251,17 @@ int launch_conv_step(const int8_t *xpre_q, int ldx, const int8_t *w_q, const flo
                      int Di, float s_cw, float s_xpre, float inv_s_x, int8_t *x_q, __half *conv_state,
                      hipStream_t st, __half *x16, int x_zero_point) {
   const size_t n = (size_t)Bt * (Di / 4);
-  hipLaunchKernelGGL(conv_step_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, xpre_q, ldx,
-                     w_q, conv_b, Bt, Di, s_cw, s_xpre, inv_s_x, x_q, x16, static_cast<float>(x_zero_point), conv_state);
+  const dim3 grid((unsigned)((n + 255) / 256));
+  const float zp = static_cast<float>(x_zero_point);
+  if (x16)
+    hipLaunchKernelGGL(conv_step_kernel<OUT_F16>, grid, dim3(256), 0, st, xpre_q, ldx, w_q, conv_b, Bt, Di, s_cw,
+                       s_xpre, inv_s_x, x_q, x16, zp, conv_state);
+  else if (x_zero_point != 0)
+    hipLaunchKernelGGL(conv_step_kernel<OUT_ASYM>, grid, dim3(256), 0, st, xpre_q, ldx, w_q, conv_b, Bt, Di, s_cw,
+                       s_xpre, inv_s_x, x_q, x16, zp, conv_state);
+  else
+    hipLaunchKernelGGL(conv_step_kernel<OUT_SYM>, grid, dim3(256), 0, st, xpre_q, ldx, w_q, conv_b, Bt, Di, s_cw,
+                       s_xpre, inv_s_x, x_q, x16, zp, conv_state);
   QUAMBA_LAUNCH_CHECK();
   return QUAMBA_OK;
 }

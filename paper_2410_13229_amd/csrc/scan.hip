@@ -305,7 +305,7 @@ __global__ __launch_bounds__(256) void scan_carry_kernel(Dev p, float *__restric
 // 4 lanes per channel, each owning 4 of the 16 states as one float4.  FUSE_DT: the step also forms
 // its own dt code, dt_q = q(W_dt[d, :] . dt_low[b, :], m_dt) (dt_proj, K = dt_rank): the four lanes of
 // a channel share the 16-byte pieces of the two rows and add their parts with two shuffles.
-template <bool FUSE_DT>
+template <bool FUSE_DT, bool XF16 = false>
 __global__ __launch_bounds__(256) void scan_step_kernel(Dev p, float *__restrict__ ssm_state, int Bt) {
   const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;  // (b, d, quad)
   const size_t total = (size_t)Bt * p.Di * 4;
@@ -320,8 +320,10 @@ __global__ __launch_bounds__(256) void scan_step_kernel(Dev p, float *__restrict
   const unsigned aw = *reinterpret_cast<const unsigned *>(p.A_q + (size_t)d * NS + 4 * q);
   const unsigned bw = *reinterpret_cast<const unsigned *>(p.B_q + (size_t)b * p.ldbc + 4 * q);
   const unsigned cw = *reinterpret_cast<const unsigned *>(p.C_q + (size_t)b * p.ldbc + 4 * q);
-  const float xv = p.x_f16 ? __half2float(p.x_f16[(size_t)b * p.Di + d])
-                           : __builtin_fmaf(p.s_x, static_cast<float>(p.x_q[(size_t)b * p.Di + d]), p.x_off);
+  // (a compile-time choice: a run-time test of the pointer would put this load behind a branch and
+  // cost the step one more memory round trip)
+  const float xv = XF16 ? __half2float(p.x_f16[(size_t)b * p.Di + d])
+                        : __builtin_fmaf(p.s_x, static_cast<float>(p.x_q[(size_t)b * p.Di + d]), p.x_off);
   int dtq;
   if (FUSE_DT) {
     const int8_t *wrow = p.W_dt + (size_t)d * p.R;
@@ -463,10 +465,17 @@ int launch_scan_step(const ScanArgs &a, hipStream_t st) {
     if (!a.W_dt || a.R < 16 || a.R % 16 || a.lddl % 16 || a.lddl < a.R || !aligned(a.dtlow_q, 16) || !aligned(a.W_dt, 16))
       return fail(QUAMBA_EUNSUPPORTED, "scan_step: fused dt_proj needs dt_rank and lddl multiples of 16 and 16-byte "
                                        "aligned dt_low and W_dt");
-    hipLaunchKernelGGL(scan_step_kernel<true>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, a.ssm_state,
-                       a.Bt);
+    if (a.x_f16)
+      hipLaunchKernelGGL((scan_step_kernel<true, true>), dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p,
+                         a.ssm_state, a.Bt);
+    else
+      hipLaunchKernelGGL((scan_step_kernel<true>), dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, a.ssm_state,
+                         a.Bt);
+  } else if (a.x_f16) {
+    hipLaunchKernelGGL((scan_step_kernel<false, true>), dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p,
+                       a.ssm_state, a.Bt);
   } else {
-    hipLaunchKernelGGL(scan_step_kernel<false>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, a.ssm_state,
+    hipLaunchKernelGGL((scan_step_kernel<false>), dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, a.ssm_state,
                        a.Bt);
   }
   QUAMBA_LAUNCH_CHECK();
