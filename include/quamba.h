@@ -22,6 +22,9 @@
  *   - the library keeps no state between calls: calls that share no output, state or workspace
  *     buffer may be in flight on different streams at once (independent sequences overlap well:
  *     one call's projections use the matrix cores while another's scan uses the vector units).
+ *   - alignment: workspaces 256 bytes; weights, conv_b, fp16 / int8 activations and ssm_state 16
+ *     bytes; conv_state and fp16 outputs 8 bytes (what any allocator returns; a view that starts
+ *     inside a tensor may not qualify and is refused with QUAMBA_EINVAL).
  *   - fp16 tensors are IEEE binary16 (quamba_half = raw 16-bit storage).
  *   - tensors are dense row-major with the last index fastest; weights are [out, in].
  *   - notation: Dm = d_model, Di = d_inner, N = d_state (16), R = dt_rank, W = d_conv (4),

@@ -93,6 +93,11 @@ int check_q(const quamba_qweights *qw, const quamba_scales *sc) {
   if (!qw->W_in || !qw->conv_w || !qw->W_x || !qw->W_dt || !qw->A || !qw->D || !qw->W_outH || !qw->conv_b ||
       !qw->dt_bias)
     return fail(QUAMBA_EINVAL, "a quantized weight pointer is NULL");
+  // the kernels read weights and biases in 16-byte pieces
+  for (const void *p : {(const void *)qw->W_in, (const void *)qw->conv_w, (const void *)qw->W_x, (const void *)qw->W_dt,
+                        (const void *)qw->A, (const void *)qw->W_outH, (const void *)qw->conv_b})
+    if (!aligned(p, 16)) return fail(QUAMBA_EINVAL, "quantized weights and conv_b must be 16-byte aligned");
+  if (!aligned(qw->dt_bias, 4)) return fail(QUAMBA_EINVAL, "dt_bias must be 4-byte aligned");
   return QUAMBA_OK;
 }
 
@@ -121,7 +126,9 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
   if (norm && !(decode && Bt <= 4)) return fail(QUAMBA_EINVAL, "fused block input needs decode with batch <= 4");
   if (Bt < 1 || L < 1) return fail(QUAMBA_EINVAL, "batch=%d, L=%d must be >= 1", Bt, L);
   if (decode && (!ssm_state || !conv_state)) return fail(QUAMBA_EINVAL, "decode needs ssm_state and conv_state");
-  if (hx && !hx->W_xH) return fail(QUAMBA_EINVAL, "variant: W_xH is NULL");
+  if (hx && (!hx->W_xH || !aligned(hx->W_xH, 16))) return fail(QUAMBA_EINVAL, "variant: W_xH is NULL or not 16-byte aligned");
+  if ((ssm_state && !aligned(ssm_state, 16)) || (conv_state && !aligned(conv_state, 8)))
+    return fail(QUAMBA_EINVAL, "ssm_state must be 16-byte aligned, conv_state 8-byte");
   if (xa && (!xa->col_bias || !aligned(xa->col_bias, 16))) return fail(QUAMBA_EINVAL, "variant: col_bias is NULL or unaligned");
   if ((hx || xa) && norm) return fail(QUAMBA_EINVAL, "variant: the fused block input is not built for it");
   if (hx && xa) return fail(QUAMBA_EINVAL, "the two x variants exclude each other");

@@ -384,6 +384,28 @@ def test_x_scale_rules_rank_as_in_the_oracle():
     assert err_g["mse"] <= 1.05 * min(err_g[99.0], err_g[99.99], err_g[100.0])
 
 
+def test_misaligned_weights_and_states_are_refused():
+    """The kernels read weights in 16-byte pieces and the states in 16- / 8-byte pieces: a pointer
+    that does not allow it is an argument error, not a fault."""
+    cfg = W.tiny_config(name="tm", d_model=64, d_inner=128, dt_rank=16, config_id=88)
+    w, qw, sc = oracle_setup(cfg)
+    u = dev(W.make_hidden(cfg, batch=1, seqlen=8))
+    out = empty((1, 8, cfg.d_model), torch.float16)
+    ws = workspace(Q.quamba_workspace_bytes(cfg, 1, 8))
+    for key in ("W_in", "W_x", "W_outH", "conv_w"):
+        qd = qweights_to_dev(qw)
+        shifted = torch.zeros(qd[key].numel() + 16, dtype=torch.int8, device="cuda:0")
+        shifted[1:1 + qd[key].numel()] = qd[key].reshape(-1)
+        qd[key] = shifted[1:1 + qd[key].numel()]  # one byte off a 16-byte boundary
+        with pytest.raises(Q.QuambaError):
+            Q.quamba_mixer_prefill(cfg, qd, sc, u, 1, 8, out, None, None, None, ws)
+    qd = qweights_to_dev(qw)
+    ssm = torch.zeros(cfg.d_inner * cfg.d_state + 4, dtype=torch.float32, device="cuda:0")[1:1 + cfg.d_inner * cfg.d_state]
+    with pytest.raises(Q.QuambaError):
+        Q.quamba_mixer_prefill(cfg, qd, sc, u, 1, 8, out, ssm, None, None, ws)
+    Q.quamba_mixer_prefill(cfg, qd, sc, u, 1, 8, out, None, None, None, ws)  # the aligned call still works
+
+
 def test_two_calls_in_flight_on_two_streams():
     """Calls that share no output, state or workspace may overlap on different streams: each must
     give what it gives alone."""
