@@ -103,8 +103,9 @@ __device__ __forceinline__ uint2 pack_f16x4(float v0, float v1, float v2, float 
 
 // Buffer descriptor over [base, base + bytes).  An access takes a scalar byte offset plus a 32-bit
 // lane offset, so its address costs no vector arithmetic (a 64-bit vector address is a quarter-rate
-// multiply-add per access); bytes past the end read as zero and are not written.  `base` must be
-// wave-uniform and bytes < 2^31.
+// multiply-add per access); a lane offset past the end reads as zero and is not written (the range
+// test looks at the lane offset only), so a lane is switched off by an offset >= bytes and a whole
+// output by bytes = 0.  `base` must be wave-uniform and bytes < 2^31.
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t buffer_over(const void *base, int bytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, bytes, 0x00020000);
 }
@@ -113,6 +114,9 @@ __device__ __forceinline__ int buffer_load_i8(__amdgpu_buffer_rsrc_t r, unsigned
 }
 __device__ __forceinline__ unsigned buffer_load_u16(__amdgpu_buffer_rsrc_t r, unsigned lane_off, int wave_off) {
   return __builtin_amdgcn_raw_buffer_load_b16(r, lane_off, wave_off, 0);
+}
+__device__ __forceinline__ void buffer_store_f32(__amdgpu_buffer_rsrc_t r, unsigned lane_off, int wave_off, float v) {
+  __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), r, lane_off, wave_off, 0);
 }
 __device__ __forceinline__ void buffer_store_f16(__amdgpu_buffer_rsrc_t r, unsigned lane_off, int wave_off, float v) {
   __builtin_amdgcn_raw_buffer_store_b16(__half_as_ushort(__float2half_rn(v)), r, lane_off, wave_off, 0);

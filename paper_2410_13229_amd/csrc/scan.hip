@@ -140,6 +140,9 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_chunk_kernel(Dev p) {
   const auto rdt = FUSE_DT ? rx : buffer_over(p.dt_q + tok0 * p.Di, nt * p.Di);
   const auto rz = OUTPUT ? buffer_over(p.z_q + tok0 * p.ldz, (nt - 1) * p.ldz + p.Di) : rx;
   const auto rg = OUTPUT ? buffer_over(p.g16 + tok0 * p.Di, nt * p.Di * 2) : rx;
+  // the optional fp32 copy of the output: an empty descriptor drops every store when it is not asked for
+  const auto ry = (OUTPUT && p.y_f32) ? buffer_over(p.y_f32 + tok0 * p.Di, nt * p.Di * 4) : buffer_over(p.x_q, 0);
+  const unsigned ud_out = live ? ud : 0x0fffffffu;  // lanes past the last channel store nothing
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -207,10 +210,8 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_chunk_kernel(Dev p) {
       if (OUTPUT) r.z[i] = buffer_load_i8(rz, ud, row * p.ldz);
     }
   };
-  auto compute = [&](const Regs &r, int t, int tl) {  // t: token index, tl: index inside the LDS block
-#pragma unroll
-    for (int i = 0; i < TS; ++i) {
-      if (t + i < t1) {
+  auto token = [&](const Regs &r, int i, int t, int tl) {  // t: token index, tl: index inside the LDS block
+      {
         const float xv = XF16 ? __half2float(__ushort_as_half(static_cast<unsigned short>(r.x[i])))
                               : __builtin_fmaf(p.s_x, static_cast<float>(r.x[i]), p.x_off);
         const int dtq = FUSE_DT ? static_cast<int>(sDT[wave][tl + i][lane]) : r.dt[i];
@@ -226,12 +227,21 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_chunk_kernel(Dev p) {
         if (OUTPUT) {
           y += Dv * xv;
           const float g = silu_gate(y, p.s_z * static_cast<float>(r.z[i]));
-          if (live) {
-            buffer_store_f16(rg, 2 * ud, (t + i - t0) * p.Di * 2, g);
-            if (p.y_f32) p.y_f32[(seq0 + t + i) * p.Di + d] = g;
-          }
+          buffer_store_f16(rg, 2 * ud_out, (t + i - t0) * p.Di * 2, g);
+          buffer_store_f32(ry, 4 * ud_out, (t + i - t0) * p.Di * 4, g);
         }
       }
+  };
+  // Whole groups of TS tokens run without per-token range tests, as one straight block the
+  // scheduler can interleave; only the ragged end of a sequence takes the tested form.
+  auto compute = [&](const Regs &r, int t, int tl) {
+    if (t + TS <= t1) {
+#pragma unroll
+      for (int i = 0; i < TS; ++i) token(r, i, t, tl);
+    } else {
+#pragma unroll
+      for (int i = 0; i < TS; ++i)
+        if (t + i < t1) token(r, i, t, tl);
     }
   };
 
@@ -427,7 +437,7 @@ int launch_scan_prefill(const ScanArgs &a, void *ws, size_t ws_bytes, hipStream_
     return fail(QUAMBA_EWORKSPACE, "scan: workspace %zu < %zu", ws_bytes, scan_workspace_bytes(a.Bt, a.L, a.Di));
   Dev p = make_dev(a);
   choose_chunks(a.Bt, a.L, a.Di, &p.T, &p.nchunks);
-  if ((long long)p.T * std::max(a.ldz, 2 * a.Di) > 0x7fffffffLL)  // the kernels' 32-bit offsets inside a chunk
+  if ((long long)p.T * std::max(a.ldz, (a.y_f32 ? 4 : 2) * a.Di) > 0x7fffffffLL)  // 32-bit offsets inside a chunk
     return fail(QUAMBA_EUNSUPPORTED, "scan: a chunk of %d tokens x %d channels exceeds 2^31 bytes", p.T, a.Di);
   p.hloc = static_cast<float *>(ws);
   p.ssum = reinterpret_cast<float *>(static_cast<char *>(ws) +
