@@ -215,8 +215,9 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
   }
   // dt_proj on the dt_low columns.  In prefill the scan's first pass computes dt_q itself when
   // the shapes allow and the raw dt_proj sums are not asked for; otherwise it is a GEMM.
-  // (generation: only with few sequences, each of which re-reads the W_dt rows; prefill: L > 1)
-  const bool fuse_dt = g_fuse_dt && (decode ? M <= 16 : L > 1) && !t.acc_dt && R >= 16 && R % 16 == 0 && NX % 16 == 0 && Di % 4 == 0 &&
+  // (generation: up to 16 sequences each re-read the W_dt rows; beyond that a workgroup keeps its rows
+  // in registers over 8 sequences, which needs dt_rank <= 256; prefill: L > 1)
+  const bool fuse_dt = g_fuse_dt && (decode ? (M <= 16 || R <= 256) : L > 1) && !t.acc_dt && R >= 16 && R % 16 == 0 && NX % 16 == 0 && Di % 4 == 0 &&
                        aligned(qw->W_dt, 16);
   if (!fuse_dt) {
     GemmEpilogue e{dt_q, nullptr, t.acc_dt, Di, Di, Di, sc->m_dt, sc->m_dt, sc->m_dt};

@@ -224,6 +224,16 @@ def test_decode_c2_shape(fused_dt):
     _decode_steps(cfg, cfg.batch, 3, qw, sc, fused_dt=fused_dt)
 
 
+@pytest.mark.parametrize("Bt,di,rk", [(19, 32, 16), (33, 192, 80)])
+def test_decode_many_sequences_ragged(Bt, di, rk):
+    """Above 16 sequences the scan step walks groups of four sequences per workgroup with the W_dt rows in
+    registers: a batch that is not a multiple of four, channels that do not fill the last workgroup, and a
+    dt_rank that leaves the last 64-byte piece partly empty."""
+    cfg = W.tiny_config(name="tdm", d_model=64, d_inner=di, dt_rank=rk, batch=Bt, seqlen=1, config_id=97)
+    w, qw, sc = oracle_setup(cfg, randomize_bias=True, gain=4.0)
+    _decode_steps(cfg, Bt, 3, qw, sc, fused_dt=True)
+
+
 @pytest.mark.parametrize("Bt", [1, 2, 5, 8])
 def test_decode_few_sequences_2p8b_width(Bt):
     """Generation with a handful of sequences takes the streaming (no matrix tile) projections."""
