@@ -181,13 +181,18 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
     QUAMBA_TRY(tap_copy(t.xz_q, xz_q, (size_t)M * 2 * Di, st));
   } else {
     // in_proj: columns [0, Di) -> x_pre, [Di, 2Di) -> z
+    // (generation: where the GEMM's epilogue can carry it, the conv step rides along: a kernel less)
+    const bool conv_in_gemm = decode && !hx && !xa && g_fuse_decode && Di % 4 == 0 &&
+                              gemm_fuses_conv_step(M, 2 * Di, Dm, base + p.gemm, p.gemm_bytes);
     {
       GemmEpilogue e{xz_q, nullptr, t.acc_in, 2 * Di, Di, 2 * Di, sc->m_in_x, sc->m_in_z, sc->m_in_z};
+      if (conv_in_gemm) e.conv = ConvStepEpi{x_q, qw->conv_w, qw->conv_b, conv_state, sc->s_cw, sc->s_xpre, inv_s_x};
       QUAMBA_TRY(launch_gemm_i8(uq, Dm, qw->W_in, Dm, M, 2 * Di, Dm, e, base + p.gemm, p.gemm_bytes, st));
       QUAMBA_TRY(tap_copy(t.xz_q, xz_q, (size_t)M * 2 * Di, st));
     }
     // causal conv + SiLU + requantization with the percentile scale of x
-    if (decode) {
+    if (conv_in_gemm) {
+    } else if (decode) {
       QUAMBA_TRY(launch_conv_step(xz_q, 2 * Di, qw->conv_w, qw->conv_b, Bt, Di, sc->s_cw, sc->s_xpre,
                                   inv_s_x, x_q, conv_state, st, x16, x_zp));
     } else {

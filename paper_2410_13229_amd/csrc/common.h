@@ -39,6 +39,19 @@ bool hadamard_factor(int n, int *k, int *m);
 // ---- internal launchers (one per .hip file); all enqueue on `st` and return a QUAMBA_* code
 namespace quamba {
 
+// Optional tail of a generation-step in_proj (Section 4.3 fuses operators to save launches): the
+// output columns below `e0` are the conv input of one token per row, and the epilogue, besides
+// storing them, runs the conv step on each group of four (window of row m, channel n at
+// state[(m e0 + n) 3], shifted in place) and writes the codes of x to x_q [M, e0].  Off when
+// `state` is NULL.
+struct ConvStepEpi {
+  int8_t *x_q;
+  const int8_t *w_q;   // [e0, 4]
+  const float *bias;   // [e0]
+  __half *state;       // [M, e0, 3]
+  float s_cw, s_xpre, inv_s_x;
+};
+
 struct GemmEpilogue {
   int8_t *out_i8;
   __half *out_f16;
@@ -49,7 +62,12 @@ struct GemmEpilogue {
   // optional int32 term per output column [N], added to the sums before the multiplier (the
   // zero-point correction of an asymmetric input grid); 16-byte aligned; the `acc` tap stays raw
   const int32_t *col_bias;
+  ConvStepEpi conv;  // only where gemm_fuses_conv_step says so
 };
+
+// Whether launch_gemm_i8 on this shape ends in an epilogue that can carry the conv step (the
+// 64 x 32 tiles of a wide generation-step output, or the reduce kernel of a split K).
+bool gemm_fuses_conv_step(int M, int N, int K, const void *ws, size_t ws_bytes);
 
 // `ws` (may be NULL) lets skinny problems split K; gemm_workspace_bytes is the most they use.
 size_t gemm_workspace_bytes(int M, int N);

@@ -48,37 +48,52 @@ __device__ __forceinline__ unsigned requant_pack4(const int (&a)[4], float m) {
 // the window then shifts by one.  `xin`: the four new int8 codes; `cs`: 12 fp16 of state
 // (channel-major, oldest first), updated in place.  Returns the four int8 output codes.
 // conv_step4_values leaves SiLU(conv) of the four channels in sv; conv_step4 quantizes them.
-__device__ __forceinline__ void conv_step4_values(unsigned xin, const int8_t *wq4, const float *bias4, __half *cs,
-                                                  float s_cw, float s_xpre, float (&sv)[4]) {
-  const uint4 wv = *reinterpret_cast<const uint4 *>(wq4);
+struct ConvWindow4 {  // the fp16 windows of four adjacent channels: 12 halves, channel-major, oldest first
+  uint2 u[3];
+};
+__device__ __forceinline__ void conv_step4_core(unsigned xin, const uint4 &wv, const float4 &bv, ConvWindow4 &win,
+                                                float s_cw, float s_xpre, float (&sv)[4]) {
   const unsigned wword[4] = {wv.x, wv.y, wv.z, wv.w};
-  const float4 bv = *reinterpret_cast<const float4 *>(bias4);
   const float bb[4] = {bv.x, bv.y, bv.z, bv.w};
   union {
     uint2 u[3];
     __half h[12];
   } st;
-  st.u[0] = reinterpret_cast<const uint2 *>(cs)[0];
-  st.u[1] = reinterpret_cast<const uint2 *>(cs)[1];
-  st.u[2] = reinterpret_cast<const uint2 *>(cs)[2];
+  st.u[0] = win.u[0];
+  st.u[1] = win.u[1];
+  st.u[2] = win.u[2];
 #pragma unroll
   for (int c = 0; c < 4; ++c) {
     const float xn = __fmul_rn(s_xpre, static_cast<float>(static_cast<int8_t>(xin >> (8 * c))));
-    const float win[4] = {__half2float(st.h[3 * c]), __half2float(st.h[3 * c + 1]), __half2float(st.h[3 * c + 2]), xn};
+    const float w4[4] = {__half2float(st.h[3 * c]), __half2float(st.h[3 * c + 1]), __half2float(st.h[3 * c + 2]), xn};
     float v = bb[c];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const float wj = __fmul_rn(s_cw, static_cast<float>(static_cast<int8_t>(wword[c] >> (8 * j))));
-      v = __fadd_rn(v, __fmul_rn(wj, win[j]));
+      v = __fadd_rn(v, __fmul_rn(wj, w4[j]));
     }
     sv[c] = v / (1.f + __builtin_amdgcn_exp2f(-v * 1.44269504088896340736f));
     st.h[3 * c] = st.h[3 * c + 1];
     st.h[3 * c + 1] = st.h[3 * c + 2];
     st.h[3 * c + 2] = __float2half_rn(xn);
   }
-  reinterpret_cast<uint2 *>(cs)[0] = st.u[0];
-  reinterpret_cast<uint2 *>(cs)[1] = st.u[1];
-  reinterpret_cast<uint2 *>(cs)[2] = st.u[2];
+  win.u[0] = st.u[0];
+  win.u[1] = st.u[1];
+  win.u[2] = st.u[2];
+}
+
+__device__ __forceinline__ void conv_step4_values(unsigned xin, const int8_t *wq4, const float *bias4, __half *cs,
+                                                  float s_cw, float s_xpre, float (&sv)[4]) {
+  const uint4 wv = *reinterpret_cast<const uint4 *>(wq4);
+  const float4 bv = *reinterpret_cast<const float4 *>(bias4);
+  ConvWindow4 win;
+  win.u[0] = reinterpret_cast<const uint2 *>(cs)[0];
+  win.u[1] = reinterpret_cast<const uint2 *>(cs)[1];
+  win.u[2] = reinterpret_cast<const uint2 *>(cs)[2];
+  conv_step4_core(xin, wv, bv, win, s_cw, s_xpre, sv);
+  reinterpret_cast<uint2 *>(cs)[0] = win.u[0];
+  reinterpret_cast<uint2 *>(cs)[1] = win.u[1];
+  reinterpret_cast<uint2 *>(cs)[2] = win.u[2];
 }
 
 __device__ __forceinline__ unsigned conv_step4(unsigned xin, const int8_t *wq4, const float *bias4, __half *cs,

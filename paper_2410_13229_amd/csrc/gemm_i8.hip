@@ -40,6 +40,15 @@ __device__ __forceinline__ int swzk(int row, int chunk) {
 
 // Epilogue for four consecutive columns gn..gn+3 of row gm.  The column ranges end on multiples
 // of 4, so one multiplier serves the group.
+// The conv step on the four x_pre codes `xin` of row gm, channels gn..gn+3.
+__device__ __forceinline__ void conv_emit(const GemmEpilogue &epi, int gm, int gn, unsigned xin) {
+  const size_t at = (size_t)gm * epi.e0 + gn;
+  const unsigned xq = conv_step4(xin, epi.conv.w_q + (size_t)gn * 4, epi.conv.bias + gn, epi.conv.state + at * 3,
+                                 epi.conv.s_cw, epi.conv.s_xpre, epi.conv.inv_s_x);
+  *reinterpret_cast<unsigned *>(epi.conv.x_q + at) = xq;
+}
+
+template <bool CONV = false>
 __device__ __forceinline__ void emit4(const GemmEpilogue &epi, int gm, int gn, int N, const int (&raw)[4]) {
   if (epi.acc) {
     v4i v = {raw[0], raw[1], raw[2], raw[3]};
@@ -53,7 +62,10 @@ __device__ __forceinline__ void emit4(const GemmEpilogue &epi, int gm, int gn, i
   }
   const float m = gn < epi.e0 ? epi.m0 : (gn < epi.e1 ? epi.m1 : epi.m2);
   if (epi.out_i8) {
-    *reinterpret_cast<unsigned *>(epi.out_i8 + (size_t)gm * epi.ldo + gn) = requant_pack4(a, m);
+    const unsigned word = requant_pack4(a, m);
+    *reinterpret_cast<unsigned *>(epi.out_i8 + (size_t)gm * epi.ldo + gn) = word;
+    if constexpr (CONV)
+      if (gn < epi.e0) conv_emit(epi, gm, gn, word);
   } else if (epi.out_f16) {
     union {
       __half h[4];
@@ -68,7 +80,7 @@ __device__ __forceinline__ void emit4(const GemmEpilogue &epi, int gm, int gn, i
 // Register r of lane l in MFMA tile (i, j) holds
 //   column n = n_base + i*32 + 8*(r/4) + 4*(l/32) + r%4,   row m = m_base + j*32 + l%32.
 // `partial` != nullptr: split-K launch, raw sums go to partial[M, N].
-template <int TM, int TN>
+template <int TM, int TN, bool CONV = false>
 __device__ __forceinline__ void store_tiles(const v16i (&acc)[TN][TM], int m_base, int n_base, int lane,
                                             int M, int N, const GemmEpilogue &epi, int32_t *partial) {
 #pragma unroll
@@ -86,7 +98,7 @@ __device__ __forceinline__ void store_tiles(const v16i (&acc)[TN][TM], int m_bas
           v4i v = {a[0], a[1], a[2], a[3]};
           *reinterpret_cast<v4i *>(partial + (size_t)gm * N + gn) = v;
         } else {
-          emit4(epi, gm, gn, N, a);
+          emit4<CONV>(epi, gm, gn, N, a);
         }
       }
     }
@@ -98,7 +110,7 @@ __device__ __forceinline__ void store_tiles(const v16i (&acc)[TN][TM], int m_bas
 // wave-level store covers whole runs of a row instead of 8-byte pieces of 32 different rows.
 // Needs N, ldo and the output base aligned to 16 bytes; `scratch` is this wave's region of
 // TM*32 * (TN*32 * sizeof(element) + 16) bytes, free of other use (callers barrier before).
-template <int TM, int TN>
+template <int TM, int TN, bool CONV = false>
 __device__ __forceinline__ void store_tiles_rows(const v16i (&acc)[TN][TM], int m_base, int n_base, int lane,
                                                  int M, int N, const GemmEpilogue &epi, int8_t *scratch) {
   const bool f16 = epi.out_f16 != nullptr;
@@ -148,13 +160,52 @@ __device__ __forceinline__ void store_tiles_rows(const v16i (&acc)[TN][TM], int 
       *reinterpret_cast<v4i *>(out + ((size_t)gm * epi.ldo + gcol) * esz) = v;
     }
   }
+  if constexpr (CONV) {
+    // conv step on the x_pre columns, from the staged codes: consecutive lanes take consecutive
+    // groups of four channels of one row, so the 24-byte windows they touch are adjacent.  All
+    // windows, weights and biases of the wave's block are requested before the first is used.
+    constexpr int GPR = TN * 8;            // groups per block row (int8 output)
+    constexpr int IT = TM * 32 * GPR / 64;  // groups per lane
+    ConvWindow4 win[IT];
+    uint4 wv[IT];
+    float4 bv[IT];
+    bool on[IT];
+    size_t at[IT];
+#pragma unroll
+    for (int it = 0; it < IT; ++it) {
+      const int q = lane + 64 * it;
+      const int row = q / GPR, cg = q % GPR;
+      const int gm = m_base + row, gn = n_base + cg * 4;
+      on[it] = gm < M && gn < N && gn < epi.e0;
+      const int cm = on[it] ? gm : 0, cn = on[it] ? gn : 0;  // off: a valid address, loaded, never stored
+      at[it] = (size_t)cm * epi.e0 + cn;
+      const uint2 *cs = reinterpret_cast<const uint2 *>(epi.conv.state + at[it] * 3);
+      win[it].u[0] = cs[0];
+      win[it].u[1] = cs[1];
+      win[it].u[2] = cs[2];
+      wv[it] = *reinterpret_cast<const uint4 *>(epi.conv.w_q + (size_t)cn * 4);
+      bv[it] = *reinterpret_cast<const float4 *>(epi.conv.bias + cn);
+    }
+#pragma unroll
+    for (int it = 0; it < IT; ++it) {
+      const int q = lane + 64 * it;
+      const int row = q / GPR, cg = q % GPR;
+      float sv[4];
+      conv_step4_core(*reinterpret_cast<const unsigned *>(scratch + row * pitch + cg * 4), wv[it], bv[it], win[it],
+                      epi.conv.s_cw, epi.conv.s_xpre, sv);
+      if (on[it]) {
+        uint2 *cs = reinterpret_cast<uint2 *>(epi.conv.state + at[it] * 3);
+        cs[0] = win[it].u[0];
+        cs[1] = win[it].u[1];
+        cs[2] = win[it].u[2];
+        *reinterpret_cast<unsigned *>(epi.conv.x_q + at[it]) =
+            pack_q8x4(sv[0] * epi.conv.inv_s_x, sv[1] * epi.conv.inv_s_x, sv[2] * epi.conv.inv_s_x, sv[3] * epi.conv.inv_s_x);
+      }
+    }
+  }
 }
 
-// Picks the epilogue: row-major staged stores when alignment allows and no raw accumulators are
-// requested, direct per-lane stores otherwise.
-// `scratch` is this wave's private LDS region of `scratch_bytes`; with BARRIER the workgroup
-// first agrees that the operand tiles living there are dead (every wave must then call this).
-template <int TM, int TN, bool BARRIER>
+template <int TM, int TN, bool BARRIER, bool CONV = false>
 __device__ __forceinline__ void finish(const v16i (&acc)[TN][TM], int m_base, int n_base, int lane,
                                        int M, int N, const GemmEpilogue &epi, int32_t *partial,
                                        int8_t *scratch, int scratch_bytes) {
@@ -166,9 +217,9 @@ __device__ __forceinline__ void finish(const v16i (&acc)[TN][TM], int m_base, in
                        (base % 16) == 0 && region <= scratch_bytes;
   if (rows_ok) {
     if (BARRIER) __syncthreads();
-    store_tiles_rows<TM, TN>(acc, m_base, n_base, lane, M, N, epi, scratch);
+    store_tiles_rows<TM, TN, CONV>(acc, m_base, n_base, lane, M, N, epi, scratch);
   } else {
-    store_tiles<TM, TN>(acc, m_base, n_base, lane, M, N, epi, partial);
+    store_tiles<TM, TN, CONV>(acc, m_base, n_base, lane, M, N, epi, partial);
   }
 }
 
@@ -317,7 +368,7 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t *__restrict__
 // Rows past M or N are clamped to the last valid row: they are loaded and multiplied but never
 // stored.
 // ------------------------------------------------------------------------------------------
-template <int BM, int BN, int WGM, int WGN, int S, int BKB, int OCC, int KG = 1, bool PIPE = false>
+template <int BM, int BN, int WGM, int WGN, int S, int BKB, int OCC, int KG = 1, bool PIPE = false, bool CONV = false>
 __global__ __launch_bounds__(64 * WGM * WGN * KG, OCC) void gemm_i8_dma_kernel(const int8_t *__restrict__ A, int lda,
                                                                const int8_t *__restrict__ Wt, int ldw,
                                                                int M, int N, int K, GemmEpilogue epi,
@@ -490,11 +541,11 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG, OCC) void gemm_i8_dma_kernel(c
             for (int e = 0; e < 4; ++e) acc[i][j][4 * g + e] += v[e];
           }
     }
-    finish<TM, TN, false>(acc, m0 + wm * WM, n0 + wn * WN, lane, M, N, epi,
-                          ks.partial ? ks.partial + (size_t)blockIdx.y * M * N : nullptr, ring + wtile * PART, PART);
+    finish<TM, TN, false, CONV>(acc, m0 + wm * WM, n0 + wn * WN, lane, M, N, epi,
+                                ks.partial ? ks.partial + (size_t)blockIdx.y * M * N : nullptr, ring + wtile * PART, PART);
   } else {
     constexpr int REGION = S * STAGE / NW / 16 * 16;
-    finish<TM, TN, true>(acc, m0 + wm * WM, n0 + wn * WN, lane, M, N, epi,
+    finish<TM, TN, true, CONV>(acc, m0 + wm * WM, n0 + wn * WN, lane, M, N, epi,
                          ks.partial ? ks.partial + (size_t)blockIdx.y * M * N : nullptr, ring + wave * REGION, REGION);
   }
 }
@@ -577,6 +628,7 @@ __global__ __launch_bounds__(256) void gemv_i8_kernel(const int8_t *__restrict__
 }
 
 // Sum of the split-K partials + epilogue; one thread per group of four columns.
+template <bool CONV>
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const int32_t *__restrict__ partial, int splits,
                                                             int M, int N, GemmEpilogue epi) {
   const size_t g = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -599,22 +651,22 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const int32_t *__res
     a[2] += v[s][2];
     a[3] += v[s][3];
   }
-  emit4(epi, gm, gn, N, a);
+  emit4<CONV>(epi, gm, gn, N, a);
 }
 
-template <int BM, int BN, int WGM, int WGN, int S, int BKB, int OCC, int KG = 1, bool PIPE = false>
+template <int BM, int BN, int WGM, int WGN, int S, int BKB, int OCC, int KG = 1, bool PIPE = false, bool CONV = false>
 int run_dma(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, int N, int K,
             const GemmEpilogue &epi, int splits, const KSplit &ks, hipStream_t st) {
   constexpr size_t lds = (size_t)S * (BM + BN) * BKB;
   static bool attr_set = false;
   if (!attr_set) {
     QUAMBA_HIP(hipFuncSetAttribute(
-        reinterpret_cast<const void *>(&gemm_i8_dma_kernel<BM, BN, WGM, WGN, S, BKB, OCC, KG, PIPE>),
+        reinterpret_cast<const void *>(&gemm_i8_dma_kernel<BM, BN, WGM, WGN, S, BKB, OCC, KG, PIPE, CONV>),
         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     attr_set = true;
   }
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-  hipLaunchKernelGGL((gemm_i8_dma_kernel<BM, BN, WGM, WGN, S, BKB, OCC, KG, PIPE>), dim3(tiles_m * tiles_n, splits),
+  hipLaunchKernelGGL((gemm_i8_dma_kernel<BM, BN, WGM, WGN, S, BKB, OCC, KG, PIPE, CONV>), dim3(tiles_m * tiles_n, splits),
                      dim3(64 * WGM * WGN * KG), lds, st, A, lda, Wt, ldw, M, N, K, epi, tiles_m, tiles_n, ks);
   QUAMBA_LAUNCH_CHECK();
   return QUAMBA_OK;
@@ -633,15 +685,12 @@ int run_reg(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, int N, i
 int g_gemm_variant = -1;  // tuning hook: >= 0 forces a kernel configuration
 int g_gemv_max_rows = 4;  // the few-row streaming kernel serves M up to this (tuning hook; at most 4)
 
-}  // namespace
+struct GemmChoice {
+  bool gemv;  // the few-row streaming kernel
+  int kind, splits, slices_per_split;
+};
 
-size_t gemm_workspace_bytes(int M, int N) {
-  // room for up to 8 int32 partial copies of a skinny output
-  return (size_t)8 * M * N * sizeof(int32_t);
-}
-
-int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, int N, int K,
-                   const GemmEpilogue &epi, void *ws, size_t ws_bytes, hipStream_t st) {
+GemmChoice choose_gemm(int M, int N, int K, const void *ws, size_t ws_bytes) {
   const bool k64 = (K % 64) == 0, k128 = (K % 128) == 0;
   // which kernel:
   //   0 = reg 64x64            1 = reg 128x128
@@ -656,17 +705,7 @@ int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, i
   //   10 = 4 with 256 x 256 tiles (eight waves of 64 x 128), for N that 320-wide tiles fit badly
   //   7 = dma 64x32, two K groups of 2 waves, ring of 4: decode-sized M with a wide output gets a
   //       tile per CU without splitting K over the grid (no second kernel)
-  if (M <= g_gemv_max_rows && g_gemm_variant < 0 && (size_t)4 * K <= 64 * 1024) {
-    const size_t lds = (size_t)(M <= 1 ? 1 : (M <= 2 ? 2 : 4)) * K;
-    if (M <= 1)
-      hipLaunchKernelGGL(gemv_i8_kernel<1>, dim3(N / 4), dim3(256), lds, st, A, lda, Wt, ldw, M, N, K, epi);
-    else if (M <= 2)
-      hipLaunchKernelGGL(gemv_i8_kernel<2>, dim3(N / 4), dim3(256), lds, st, A, lda, Wt, ldw, M, N, K, epi);
-    else
-      hipLaunchKernelGGL(gemv_i8_kernel<4>, dim3(N / 4), dim3(256), lds, st, A, lda, Wt, ldw, M, N, K, epi);
-    QUAMBA_LAUNCH_CHECK();
-    return QUAMBA_OK;
-  }
+  if (M <= g_gemv_max_rows && g_gemm_variant < 0 && (size_t)4 * K <= 64 * 1024) return GemmChoice{true, 0, 1, 0};
   int kind;
   const long tiles_256 = (long)((M + 255) / 256) * ((N + 319) / 320);
   const long tiles_128 = (long)((M + 127) / 128) * ((N + 159) / 160);
@@ -719,9 +758,41 @@ int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, i
     while (want > 1 && (nslices / want < 4 || (size_t)want * M * N * sizeof(int32_t) > ws_bytes)) --want;
     if (want > 1) splits = want;
   }
-  KSplit ks{(nslices + splits - 1) / splits, nullptr};
-  splits = (nslices + ks.slices_per_split - 1) / ks.slices_per_split;
-  if (splits > 1) ks.partial = static_cast<int32_t *>(ws);
+  const int per = (nslices + splits - 1) / splits;
+  return GemmChoice{false, kind, (nslices + per - 1) / per, per};
+}
+
+}  // namespace
+
+size_t gemm_workspace_bytes(int M, int N) {
+  // room for up to 8 int32 partial copies of a skinny output
+  return (size_t)8 * M * N * sizeof(int32_t);
+}
+
+bool gemm_fuses_conv_step(int M, int N, int K, const void *ws, size_t ws_bytes) {
+  const GemmChoice c = choose_gemm(M, N, K, ws, ws_bytes);
+  return !c.gemv && (c.kind == 7 || c.splits > 1);
+}
+
+int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, int N, int K,
+                   const GemmEpilogue &epi, void *ws, size_t ws_bytes, hipStream_t st) {
+  const GemmChoice c = choose_gemm(M, N, K, ws, ws_bytes);
+  const bool conv = epi.conv.state != nullptr;
+  if (conv && (c.gemv || !(c.kind == 7 || c.splits > 1) || !epi.out_i8 || epi.e0 % 4 != 0))
+    return fail(QUAMBA_EUNSUPPORTED, "gemm: this shape (M=%d N=%d K=%d) has no epilogue that carries the conv step", M, N, K);
+  if (c.gemv) {
+    const size_t lds = (size_t)(M <= 1 ? 1 : (M <= 2 ? 2 : 4)) * K;
+    if (M <= 1)
+      hipLaunchKernelGGL(gemv_i8_kernel<1>, dim3(N / 4), dim3(256), lds, st, A, lda, Wt, ldw, M, N, K, epi);
+    else if (M <= 2)
+      hipLaunchKernelGGL(gemv_i8_kernel<2>, dim3(N / 4), dim3(256), lds, st, A, lda, Wt, ldw, M, N, K, epi);
+    else
+      hipLaunchKernelGGL(gemv_i8_kernel<4>, dim3(N / 4), dim3(256), lds, st, A, lda, Wt, ldw, M, N, K, epi);
+    QUAMBA_LAUNCH_CHECK();
+    return QUAMBA_OK;
+  }
+  const int kind = c.kind, splits = c.splits;
+  KSplit ks{c.slices_per_split, splits > 1 ? static_cast<int32_t *>(ws) : nullptr};
 
   int rc;
   switch (kind) {
@@ -731,7 +802,10 @@ int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, i
     case 5: rc = run_dma<64, 64, 2, 2, 3, 128, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
     case 4: rc = run_dma<256, 320, 4, 2, 2, 128, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
     case 6: rc = run_dma<128, 160, 4, 1, 3, 128, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
-    case 7: rc = run_dma<64, 32, 2, 1, 4, 128, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
+    case 7:
+      rc = conv ? run_dma<64, 32, 2, 1, 4, 128, 2, 2, false, true>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st)
+                : run_dma<64, 32, 2, 1, 4, 128, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st);
+      break;
     case 8: rc = run_dma<128, 160, 4, 1, 2, 256, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
     case 9: rc = run_dma<64, 64, 2, 2, 2, 256, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
     case 10: rc = run_dma<256, 256, 4, 2, 2, 128, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
@@ -739,8 +813,12 @@ int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, i
   }
   if (rc != QUAMBA_OK || splits == 1) return rc;
   const size_t groups = (size_t)M * (N / 4);
-  hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, st, ks.partial,
-                     splits, M, N, epi);
+  if (conv)
+    hipLaunchKernelGGL(splitk_reduce_kernel<true>, dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, st, ks.partial,
+                       splits, M, N, epi);
+  else
+    hipLaunchKernelGGL(splitk_reduce_kernel<false>, dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, st, ks.partial,
+                       splits, M, N, epi);
   QUAMBA_LAUNCH_CHECK();
   return QUAMBA_OK;
 }

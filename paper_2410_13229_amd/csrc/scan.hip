@@ -365,12 +365,13 @@ __global__ __launch_bounds__(256) void scan_step_kernel(Dev p, float *__restrict
     const float a2 = static_cast<float>(static_cast<int8_t>(aw >> (8 * j))) * (p.s_A * LOG2E);
     const float Bv = p.s_B * static_cast<float>(static_cast<int8_t>(bw >> (8 * j)));
     const float Cv = p.s_C * static_cast<float>(static_cast<int8_t>(cw >> (8 * j)));
-    h[j] = exp2_fast(dt * a2) * h[j] + u * Bv;
-    y += Cv * h[j];
+    // (explicit fused multiply-adds: both step kernels must round alike whatever the compiler contracts)
+    h[j] = __builtin_fmaf(exp2_fast(dt * a2), h[j], u * Bv);
+    y = __builtin_fmaf(Cv, h[j], y);
   }
   y += __shfl_xor(y, 1);
   y += __shfl_xor(y, 2);
-  y += p.s_D * static_cast<float>(p.D_q[d]) * xv;
+  y = __builtin_fmaf(p.s_D * static_cast<float>(p.D_q[d]), xv, y);
   const float g = silu_gate(y, zv);
   if (live) {
     reinterpret_cast<float4 *>(ssm_state)[id] = make_float4(h[0], h[1], h[2], h[3]);
@@ -450,12 +451,12 @@ __global__ __launch_bounds__(256) void scan_step_batch_kernel(Dev p, float *__re
     for (int j = 0; j < 4; ++j) {
       const float Bv = p.s_B * static_cast<float>(static_cast<int8_t>(bw[i] >> (8 * j)));
       const float Cv = p.s_C * static_cast<float>(static_cast<int8_t>(cw[i] >> (8 * j)));
-      h[j] = exp2_fast(dt * a2[j]) * h[j] + u * Bv;
-      y += Cv * h[j];
+      h[j] = __builtin_fmaf(exp2_fast(dt * a2[j]), h[j], u * Bv);
+      y = __builtin_fmaf(Cv, h[j], y);
     }
     y += __shfl_xor(y, 1);
     y += __shfl_xor(y, 2);
-    y += Dv * xv[i];
+    y = __builtin_fmaf(Dv, xv[i], y);
     const float g = silu_gate(y, zv[i]);
     if (on) {
       reinterpret_cast<float4 *>(ssm_state)[(b * p.Di + d) * 4 + q] = make_float4(h[0], h[1], h[2], h[3]);

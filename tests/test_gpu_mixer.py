@@ -224,6 +224,32 @@ def test_decode_c2_shape(fused_dt):
     _decode_steps(cfg, cfg.batch, 3, qw, sc, fused_dt=fused_dt)
 
 
+@pytest.mark.parametrize("name,Bt", [("c2", 64), ("c2", 24), ("tiny", 6)])
+def test_decode_without_taps_is_the_tapped_step(name, Bt):
+    """The intermediates are checked link by link in the tapped runs above; without taps the step takes
+    the faster epilogues (row-staged stores, the conv step inside in_proj's epilogue from staged codes).
+    Both must leave exactly the same output and states."""
+    cfg = W.CONFIGS[name] if name != "tiny" else W.tiny_config(name="tdn", d_model=1024, d_inner=256, dt_rank=16,
+                                                                 batch=Bt, seqlen=1, config_id=98)
+    w, qw, sc = oracle_setup(cfg)
+    qd = qweights_to_dev(qw)
+    ssm_np, cs_np = W.make_decode_state(cfg, batch=Bt)
+    ws = workspace(Q.quamba_workspace_bytes(cfg, Bt, 1))
+    from gpu_util import TAP_SHAPES
+    res = []
+    for taps in (make_taps(cfg, Bt, None), make_taps(cfg, Bt, [n for n in TAP_SHAPES if n != "acc_dt"]), None):
+        ssm, cs = dev(ssm_np), dev(cs_np)
+        out = empty((Bt, cfg.d_model), torch.float16)
+        for s in range(2):
+            u = W.make_hidden(cfg, batch=Bt, seqlen=1, stream=300 + s)
+            Q.quamba_mixer_decode(cfg, qd, sc, dev(u[:, 0]), Bt, out, ssm, cs, taps, ws)
+        res.append((host(out), host(ssm), host(cs)))
+    for r in res[1:]:
+        assert np.array_equal(r[0].view(np.uint16), res[0][0].view(np.uint16))
+        assert np.array_equal(r[1].view(np.uint32), res[0][1].view(np.uint32))
+        assert np.array_equal(r[2].view(np.uint16), res[0][2].view(np.uint16))
+
+
 @pytest.mark.parametrize("Bt,di,rk", [(19, 32, 16), (33, 192, 80)])
 def test_decode_many_sequences_ragged(Bt, di, rk):
     """Above 16 sequences the scan step walks groups of four sequences per workgroup with the W_dt rows in
