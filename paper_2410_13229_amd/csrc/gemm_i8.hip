@@ -683,6 +683,7 @@ int run_reg(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, int N, i
 }
 
 int g_gemm_variant = -1;  // tuning hook: >= 0 forces a kernel configuration
+int g_gemm_split = 0;     // tuning hook: > 1 forces a K split over the grid
 int g_gemv_max_rows = 4;  // the few-row streaming kernel serves M up to this (tuning hook; at most 4)
 
 struct GemmChoice {
@@ -741,8 +742,12 @@ GemmChoice choose_gemm(int M, int N, int K, const void *ws, size_t ws_bytes) {
   if ((K % 256) == 0 && kind == 6) kind = 8;
   // (decode-sized M measured better with 128-byte slices, and so do skinny outputs, N <= 512, with so
   // many 64 x 64 tiles that K is not split over the grid: there the deeper ring of the 128-byte form wins)
-  const bool skinny_unsplit = N <= 512 && (long)((M + 63) / 64) * ((N + 63) / 64) > 256;
-  if ((K % 256) == 0 && kind == 5 && M > 64 && !skinny_unsplit) kind = 9;
+  // and so do outputs of more than 512 tiles: the 128-byte form fits three workgroups on a CU, the
+  // 256-byte form two, so beyond 512 tiles it needs a second round (1024 x 2560 x 5120: 28.8 against
+  // 32.7 us; 256 x 10240 x 2560: 15.3 against 18.2 us)
+  const long tiles64 = (long)((M + 63) / 64) * ((N + 63) / 64);
+  const bool skinny_unsplit = N <= 512 && tiles64 > 256;
+  if ((K % 256) == 0 && kind == 5 && M > 64 && !skinny_unsplit && tiles64 <= 512) kind = 9;
   if (g_gemm_variant >= 0 && g_gemm_variant <= 10 &&
       (g_gemm_variant < 2 || (g_gemm_variant == 3 && k64) || (g_gemm_variant != 3 && k128)))
     kind = g_gemm_variant;
@@ -758,6 +763,7 @@ GemmChoice choose_gemm(int M, int N, int K, const void *ws, size_t ws_bytes) {
     while (want > 1 && (nslices / want < 4 || (size_t)want * M * N * sizeof(int32_t) > ws_bytes)) --want;
     if (want > 1) splits = want;
   }
+  if (g_gemm_split > 1 && ws != nullptr && (size_t)g_gemm_split * M * N * sizeof(int32_t) <= ws_bytes) splits = g_gemm_split;
   const int per = (nslices + splits - 1) / splits;
   return GemmChoice{false, kind, (nslices + per - 1) / per, per};
 }
@@ -826,4 +832,5 @@ int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, i
 }  // namespace quamba
 
 extern "C" void quamba_debug_set_gemm_variant(int v) { quamba::g_gemm_variant = v; }
+extern "C" void quamba_debug_set_gemm_split(int v) { quamba::g_gemm_split = v; }
 extern "C" void quamba_debug_set_gemv_max_rows(int v) { quamba::g_gemv_max_rows = v < 4 ? v : 4; }
