@@ -35,3 +35,5 @@ from .model import (embed, final_norm, lm_head, greedy, model_prefill, model_dec
 from .mamba_had import (calibrate_hadx, q_prefill_hadx, q_decode_hadx,  # noqa: F401
                         hadamard_inverse_dequant)
 from .x_asym import calibrate_xasym, q_prefill_xasym, q_decode_xasym, quantize_asym  # noqa: F401
+from .x_formats import (calibrate_xfmt, q_prefill_xfmt, q_decode_xfmt, encode_e4m3, decode_e4m3,  # noqa: F401
+                        encode_log2, decode_log2)
