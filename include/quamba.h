@@ -234,6 +234,53 @@ int quamba_mixer_decode_xasym(const quamba_dims *dims, const quamba_qweights *qw
                               float *ssm_state, quamba_half *conv_state, const quamba_taps *taps, void *ws,
                               size_t ws_bytes, void *stream);
 
+/* ---- Non-uniform 8-bit formats for the scan input x (Appendix K: row "MinMax Sym. Log2", and the E4M3
+ * float its last paragraph names).  The appendix reports log2 as slightly better than Quamba's grid but
+ * without a matrix-multiply form on the frameworks it used; here x_proj has one: every decoded value and
+ * every int8 weight code is exact in bfloat16, so x_proj runs on the bf16 matrix units with fp32 sums.
+ * The paper gives no formulas; this reading (t = fp32(x) * fp32(1/s), one multiply):
+ *   QUAMBA_XFMT_LOG2  s = max|x| over the calibration batch; t = f 2^E, 1 <= f < 2, goes to 2^k with
+ *                     k = E + (f >= fp32(sqrt 2)); code = sign bit | e, e = -k in 0..126 (t > 1 saturates
+ *                     at e = 0), 127 = zero (also anything below 2^-126.5);  x = sign s 2^-e
+ *   QUAMBA_XFMT_E4M3  1-4-3 bits, bias 7, subnormals m 2^-9, largest finite value 448, no infinities, the
+ *                     two not-a-number codes never produced; s = max^p(|x|) / 448; t goes to the nearest
+ *                     value, ties to the even mantissa, saturating at +-448;  x = s value(code)
+ *   x_proj: acc[n] = sum_k W_x_q[n, k] value(code_k) (fp32 sums in a fixed order: K is cut in equal
+ *           ranges whose sums are added in ascending order); outputs clamp(rne(acc * m)), m = s s_Wx / s_out
+ * quamba_xfmt: W_x_bf16 [dt_rank + 2 d_state, d_inner] is device memory provided by the caller (16-byte
+ * aligned) and written by the calibration: the int8 codes of W_x as bfloat16 bit patterns; the scalars
+ * are host values.  Entry points as quamba_calibrate / quamba_mixer_prefill / quamba_mixer_decode, plus
+ * `xf`; same workspaces.  taps->x_q receives the code bytes, taps->acc_x the fp32 sums (as bit patterns
+ * in the int32 buffer); d_inner must be a multiple of 16 and dt_rank + 2 d_state at most 320. */
+#define QUAMBA_XFMT_E4M3 1
+#define QUAMBA_XFMT_LOG2 2
+typedef struct quamba_xfmt {
+  uint16_t *W_x_bf16;
+  int32_t format;
+  float s_x, inv_s_x, m_x_dt, m_x_B, m_x_C;
+} quamba_xfmt;
+int quamba_calibrate_xfmt(const quamba_dims *dims, const quamba_fp_weights *w, const quamba_half *calib_u,
+                          int nb, int Lc, int format, double x_percentile, quamba_qweights *out_q,
+                          quamba_scales *out_s /* host */, quamba_xfmt *out_f /* host */, void *ws,
+                          size_t ws_bytes, void *stream);
+int quamba_mixer_prefill_xfmt(const quamba_dims *dims, const quamba_qweights *qw, const quamba_scales *sc,
+                              const quamba_xfmt *xf, const quamba_half *u, int Bt, int L, quamba_half *out,
+                              float *ssm_state, quamba_half *conv_state, const quamba_taps *taps, void *ws,
+                              size_t ws_bytes, void *stream);
+int quamba_mixer_decode_xfmt(const quamba_dims *dims, const quamba_qweights *qw, const quamba_scales *sc,
+                             const quamba_xfmt *xf, const quamba_half *u, int Bt, quamba_half *out,
+                             float *ssm_state, quamba_half *conv_state, const quamba_taps *taps, void *ws,
+                             size_t ws_bytes, void *stream);
+/* Stages of the variant.  quamba_x_encode: codes[i] = encode(fp32(v[i]) * inv_s) for n fp32 values.
+ * quamba_xfmt_proj: out_q [M, N] int8 = clamp(rne(acc * m)) with acc as above over x_code [M, K] and
+ * W_bf16 [N, K]; columns [0, e0) use m[0], [e0, e1) m[1], [e1, N) m[2] (multiples of 4); acc_f32 [M, N]
+ * (may be NULL) receives the sums; ws: quamba_gemm_workspace_bytes(M, N, K) bytes, 256-byte aligned.
+ * K a multiple of 16, N a multiple of 4 and at most 320; pointers 16-byte aligned. */
+int quamba_x_encode(int format, const float *v, size_t n, float inv_s, uint8_t *codes, void *stream);
+int quamba_xfmt_proj(int format, const uint8_t *x_code, int M, int N, int K, const uint16_t *W_bf16, int e0, int e1,
+                     const float *m /* host, 3 */, int8_t *out_q, float *acc_f32, void *ws, size_t ws_bytes,
+                     void *stream);
+
 /* The unquantized mixer (Section 3.1: in_proj, causal conv + SiLU, selection, selective scan,
  * gate, out_proj) in fp32 from the fp32 master weights, each of the nb sequences of length L from
  * an empty history: u [nb, L, Dm] fp16 in, out [nb * L, Dm] fp32.  It is what calibration observes

@@ -24,6 +24,8 @@ __all__ = [
     "quamba_mixer_prefill_hadx", "quamba_mixer_decode_hadx", "quamba_hadamard_inverse",
     "XAsym", "XASYM_FIELDS", "make_xasym", "xasym_to_dict", "quamba_calibrate_xasym", "quamba_mixer_prefill_xasym",
     "quamba_mixer_decode_xasym",
+    "XFmt", "XFMT_FIELDS", "XFMT_E4M3", "XFMT_LOG2", "make_xfmt", "xfmt_to_dict", "quamba_calibrate_xfmt",
+    "quamba_mixer_prefill_xfmt", "quamba_mixer_decode_xfmt", "quamba_x_encode", "quamba_xfmt_proj",
 ]
 
 X_PERCENTILE, X_MSE_CLIP = 0, 1
@@ -87,6 +89,14 @@ XASYM_FIELDS = ("s_x", "inv_s_x", "m_x_dt", "m_x_B", "m_x_C")
 
 class XAsym(C.Structure):
     _fields_ = [("col_bias", C.c_void_p), ("zero_point", C.c_int32)] + [(n, C.c_float) for n in XASYM_FIELDS]
+
+
+XFMT_FIELDS = ("s_x", "inv_s_x", "m_x_dt", "m_x_B", "m_x_C")
+XFMT_E4M3, XFMT_LOG2 = 1, 2
+
+
+class XFmt(C.Structure):
+    _fields_ = [("W_x_bf16", C.c_void_p), ("format", C.c_int32)] + [(n, C.c_float) for n in XFMT_FIELDS]
 
 
 class Layer(C.Structure):
@@ -155,6 +165,23 @@ def make_xasym(col_bias, values=None) -> XAsym:
 def xasym_to_dict(a: XAsym) -> dict:
     d = {n: float(getattr(a, n)) for n in XASYM_FIELDS}
     d["zero_point"] = int(a.zero_point)
+    return d
+
+
+def make_xfmt(W_x_bf16, values=None) -> XFmt:
+    """XFmt struct over a device int16 tensor W_x_bf16 (keep it alive) and, optionally, a dict of the scalars."""
+    a = XFmt()
+    a.W_x_bf16 = W_x_bf16.data_ptr()
+    if values is not None:
+        a.format = int(values["format"])
+        for n in XFMT_FIELDS:
+            setattr(a, n, float(values[n]))
+    return a
+
+
+def xfmt_to_dict(a: XFmt) -> dict:
+    d = {n: float(getattr(a, n)) for n in XFMT_FIELDS}
+    d["format"] = int(a.format)
     return d
 
 
@@ -283,6 +310,17 @@ def lib():
                                             vp, sz, vp]
     for name in ("quamba_calibrate_xasym", "quamba_mixer_prefill_xasym", "quamba_mixer_decode_xasym"):
         getattr(L, name).restype = C.c_int
+    L.quamba_calibrate_xfmt.argtypes = [P(Dims), P(FpWeights), vp, i, i, i, C.c_double, P(QWeights), P(Scales), P(XFmt),
+                                        vp, sz, vp]
+    L.quamba_mixer_prefill_xfmt.argtypes = [P(Dims), P(QWeights), P(Scales), P(XFmt), vp, i, i, vp, vp, vp, P(Taps),
+                                            vp, sz, vp]
+    L.quamba_mixer_decode_xfmt.argtypes = [P(Dims), P(QWeights), P(Scales), P(XFmt), vp, i, vp, vp, vp, P(Taps),
+                                           vp, sz, vp]
+    L.quamba_x_encode.argtypes = [i, vp, sz, f, vp, vp]
+    L.quamba_xfmt_proj.argtypes = [i, vp, i, i, i, vp, i, i, P(C.c_float), vp, vp, vp, sz, vp]
+    for name in ("quamba_calibrate_xfmt", "quamba_mixer_prefill_xfmt", "quamba_mixer_decode_xfmt", "quamba_x_encode",
+                 "quamba_xfmt_proj"):
+        getattr(L, name).restype = C.c_int
     L.quamba_mixer_fp32.argtypes = [P(Dims), P(FpWeights), vp, i, i, vp, vp, sz, vp]
     for name in ("quamba_calibrate_x_rule", "quamba_clip_search", "quamba_mixer_fp32"):
         getattr(L, name).restype = C.c_int
@@ -401,6 +439,41 @@ def quamba_mixer_decode_xasym(dims, qw, sc, xa, u, Bt, out, ssm_state, conv_stat
                                            C.byref(scales_from_dict(sc)), C.byref(xa), _ptr(u), Bt, _ptr(out),
                                            _ptr(ssm_state), _ptr(conv_state), _taps(taps), _ptr(ws), _nbytes(ws),
                                            _stream(stream)))
+
+
+def quamba_calibrate_xfmt(dims, fp_weights, calib_u, nb, Lc, fmt, x_percentile, out_q, W_x_bf16, ws, stream=None):
+    """Returns (Scales, XFmt); `out_q` and `W_x_bf16` (preallocated device tensors) are written on the device."""
+    fw = _struct_of_ptrs(FpWeights, fp_weights)
+    oq = _struct_of_ptrs(QWeights, out_q)
+    sc, xf = Scales(), make_xfmt(W_x_bf16)
+    _check(lib().quamba_calibrate_xfmt(C.byref(_dims(dims)), C.byref(fw), _ptr(calib_u), nb, Lc, int(fmt),
+                                       float(x_percentile), C.byref(oq), C.byref(sc), C.byref(xf), _ptr(ws),
+                                       _nbytes(ws), _stream(stream)))
+    return sc, xf
+
+
+def quamba_mixer_prefill_xfmt(dims, qw, sc, xf, u, Bt, L, out, ssm_state, conv_state, taps, ws, stream=None):
+    _check(lib().quamba_mixer_prefill_xfmt(C.byref(_dims(dims)), C.byref(_struct_of_ptrs(QWeights, qw)),
+                                           C.byref(scales_from_dict(sc)), C.byref(xf), _ptr(u), Bt, L, _ptr(out),
+                                           _ptr(ssm_state), _ptr(conv_state), _taps(taps), _ptr(ws), _nbytes(ws),
+                                           _stream(stream)))
+
+
+def quamba_mixer_decode_xfmt(dims, qw, sc, xf, u, Bt, out, ssm_state, conv_state, taps, ws, stream=None):
+    _check(lib().quamba_mixer_decode_xfmt(C.byref(_dims(dims)), C.byref(_struct_of_ptrs(QWeights, qw)),
+                                          C.byref(scales_from_dict(sc)), C.byref(xf), _ptr(u), Bt, _ptr(out),
+                                          _ptr(ssm_state), _ptr(conv_state), _taps(taps), _ptr(ws), _nbytes(ws),
+                                          _stream(stream)))
+
+
+def quamba_x_encode(fmt, v, n, inv_s, codes, stream=None):
+    _check(lib().quamba_x_encode(int(fmt), _ptr(v), n, float(inv_s), _ptr(codes), _stream(stream)))
+
+
+def quamba_xfmt_proj(fmt, x_code, M, N, K, W_bf16, e0, e1, mult, out_q, acc_f32, ws=None, stream=None):
+    m = (C.c_float * 3)(*[float(v) for v in mult])
+    _check(lib().quamba_xfmt_proj(int(fmt), _ptr(x_code), M, N, K, _ptr(W_bf16), e0, e1, m, _ptr(out_q), _ptr(acc_f32),
+                                  _ptr(ws), _nbytes(ws), _stream(stream)))
 
 
 def quamba_clip_search_workspace_bytes() -> int:

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libquamba.so")
-SOURCES = ["api.hip", "gemm_i8.hip", "elementwise.hip", "scan.hip", "hadamard.hip", "calibrate.hip", "model.hip", "decode_fused.hip"]
+SOURCES = ["api.hip", "gemm_i8.hip", "elementwise.hip", "scan.hip", "hadamard.hip", "calibrate.hip", "model.hip", "decode_fused.hip", "gemm_xfmt.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + os.path.join(ROOT, "include"),
          "-I" + CSRC, "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

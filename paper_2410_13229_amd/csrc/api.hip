@@ -19,6 +19,9 @@ int calibrate_hadx(const quamba_dims *d, const quamba_fp_weights *w, const __hal
 int calibrate_xasym(const quamba_dims *d, const quamba_fp_weights *w, const __half *calib_u, int nb, int Lc,
                     double x_percentile, quamba_qweights *oq, quamba_scales *os, quamba_xasym *oa, void *ws,
                     size_t ws_bytes, hipStream_t st);
+int calibrate_xfmt(const quamba_dims *d, const quamba_fp_weights *w, const __half *calib_u, int nb, int Lc, int format,
+                   double x_percentile, quamba_qweights *oq, quamba_scales *os, quamba_xfmt *of, void *ws,
+                   size_t ws_bytes, hipStream_t st);
 size_t clip_search_workspace_bytes();
 int clip_search(const float *x, size_t n, int bits, int max_iters, double *clip_out, int *iters_out, void *ws,
                 size_t ws_bytes, hipStream_t st);
@@ -119,7 +122,7 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
               const int8_t *u_q_in, int Bt, int L, bool decode, __half *out, float *ssm_state,
               __half *conv_state, const quamba_taps *taps, void *ws, size_t ws_bytes, hipStream_t st,
               const NormIn *norm = nullptr, const quamba_hadx *hx = nullptr, const quamba_hadx_taps *hx_taps = nullptr,
-              const quamba_xasym *xa = nullptr) {
+              const quamba_xasym *xa = nullptr, const quamba_xfmt *xf = nullptr) {
   QUAMBA_TRY(check_dims(d));
   QUAMBA_TRY(check_q(qw, sc));
   if ((!u && !u_q_in && !norm) || !out) return fail(QUAMBA_EINVAL, "input or output pointer is NULL");
@@ -131,9 +134,18 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
     return fail(QUAMBA_EINVAL, "ssm_state must be 16-byte aligned, conv_state 8-byte");
   if (xa && (!xa->col_bias || !aligned(xa->col_bias, 16))) return fail(QUAMBA_EINVAL, "variant: col_bias is NULL or unaligned");
   if ((hx || xa) && norm) return fail(QUAMBA_EINVAL, "variant: the fused block input is not built for it");
-  if (hx && xa) return fail(QUAMBA_EINVAL, "the two x variants exclude each other");
+  if ((hx != nullptr) + (xa != nullptr) + (xf != nullptr) > 1) return fail(QUAMBA_EINVAL, "the x variants exclude each other");
+  if (xf && norm) return fail(QUAMBA_EINVAL, "variant: the fused block input is not built for it");
+  if (xf && (xf->format != QUAMBA_XFMT_E4M3 && xf->format != QUAMBA_XFMT_LOG2))
+    return fail(QUAMBA_EINVAL, "variant: unknown x format %d", xf->format);
+  if (xf && (!xf->W_x_bf16 || !aligned(xf->W_x_bf16, 16))) return fail(QUAMBA_EINVAL, "variant: W_x_bf16 is NULL or unaligned");
+  if (xf && (d->d_inner % 16 != 0 || d->dt_rank + 2 * d->d_state > 320 || (d->dt_rank + 2 * d->d_state) % 4 != 0 ||
+             d->dt_rank % 4 != 0 || d->d_state % 4 != 0))
+    return fail(QUAMBA_EUNSUPPORTED, "variant: d_inner must be a multiple of 16, dt_rank and d_state multiples of 4, "
+                                     "dt_rank + 2 d_state at most 320");
   // scale, reciprocal and zero point of the scan input's grid
-  const float s_x = xa ? xa->s_x : sc->s_x, inv_s_x = xa ? xa->inv_s_x : sc->inv_s_x;
+  const float s_x = xa ? xa->s_x : (xf ? xf->s_x : sc->s_x), inv_s_x = xa ? xa->inv_s_x : (xf ? xf->inv_s_x : sc->inv_s_x);
+  const int x_format = xf ? xf->format : 0;
   const int x_zp = xa ? xa->zero_point : 0;
   const Plan p = make_plan(d, Bt, L, hx != nullptr);
   if (!ws || ws_bytes < p.total) return fail(QUAMBA_EWORKSPACE, "workspace %zu < %zu", ws_bytes, p.total);
@@ -157,7 +169,7 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
   const quamba_taps &t = taps ? *taps : none;
 
   // Generation with a handful of sequences: [norm +] in_proj + conv step in one streaming kernel.
-  const bool few = decode && M <= 4 && Dm <= 8192 && g_fuse_decode && !hx && !xa;
+  const bool few = decode && M <= 4 && Dm <= 8192 && g_fuse_decode && !hx && !xa && !xf;
   // quantize the block input (Eq. 2)
   const int8_t *uq = u_q_in;
   if (!uq && !norm) {
@@ -182,7 +194,7 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
   } else {
     // in_proj: columns [0, Di) -> x_pre, [Di, 2Di) -> z
     // (generation: where the GEMM's epilogue can carry it, the conv step rides along: a kernel less)
-    const bool conv_in_gemm = decode && !hx && !xa && g_fuse_decode && Di % 4 == 0 &&
+    const bool conv_in_gemm = decode && !hx && !xa && !xf && g_fuse_decode && Di % 4 == 0 &&
                               gemm_fuses_conv_step(M, 2 * Di, Dm, base + p.gemm, p.gemm_bytes);
     {
       GemmEpilogue e{xz_q, nullptr, t.acc_in, 2 * Di, Di, 2 * Di, sc->m_in_x, sc->m_in_z, sc->m_in_z};
@@ -194,10 +206,10 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
     if (conv_in_gemm) {
     } else if (decode) {
       QUAMBA_TRY(launch_conv_step(xz_q, 2 * Di, qw->conv_w, qw->conv_b, Bt, Di, sc->s_cw, sc->s_xpre,
-                                  inv_s_x, x_q, conv_state, st, x16, x_zp));
+                                  inv_s_x, x_q, conv_state, st, x16, x_zp, x_format));
     } else {
       QUAMBA_TRY(launch_conv_prefill(xz_q, 2 * Di, qw->conv_w, qw->conv_b, Bt, L, Di, sc->m_conv, inv_s_x,
-                                     sc->s_xpre, x_q, conv_state, st, x16, x_zp));
+                                     sc->s_xpre, x_q, conv_state, st, x16, x_zp, x_format));
     }
   }
   if (hx) {  // forward Hadamard & quantize: x_q now holds the codes of H_n x
@@ -207,7 +219,12 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
   }
   QUAMBA_TRY(tap_copy(t.x_q, x_q, (size_t)M * Di, st));
   // x_proj: columns dt_low | B | C, each with its own output scale
-  {
+  if (xf) {  // codes of a non-uniform format: bf16 matrix units on the decoded values, fp32 sums
+    QUAMBA_TRY(launch_xfmt_proj(xf->format, reinterpret_cast<const uint8_t *>(x_q), M, NX, Di, xf->W_x_bf16, R, R + N,
+                                xf->m_x_dt, xf->m_x_B, xf->m_x_C, dbc_q, reinterpret_cast<float *>(t.acc_x),
+                                base + p.gemm, p.gemm_bytes, st));
+    QUAMBA_TRY(tap_copy(t.dbc_q, dbc_q, (size_t)M * NX, st));
+  } else {
     GemmEpilogue e{dbc_q, nullptr, t.acc_x, NX, R, R + N, hx ? hx->m_xh_dt : (xa ? xa->m_x_dt : sc->m_x_dt),
                    hx ? hx->m_xh_B : (xa ? xa->m_x_B : sc->m_x_B), hx ? hx->m_xh_C : (xa ? xa->m_x_C : sc->m_x_C),
                    xa ? xa->col_bias : nullptr};
@@ -239,6 +256,7 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
     a.s_A = sc->s_A; a.s_D = sc->s_D;
     a.Bt = Bt; a.L = L; a.Di = Di; a.g16 = g16; a.y_f32 = t.y_f32; a.ssm_state = ssm_state;
     a.x_f16 = x16;
+    a.x_format = x_format;
     if (fuse_dt) {  // decode writes the dt codes only when they are asked for as a tap
       a.dtlow_q = dbc_q; a.lddl = NX; a.W_dt = qw->W_dt; a.R = R; a.m_dt = sc->m_dt;
       a.dt_out = (decode && !t.dt_q) ? nullptr : dt_q;
@@ -593,6 +611,48 @@ int quamba_mixer_decode_xasym(const quamba_dims *dims, const quamba_qweights *qw
   return run_mixer(dims, qw, sc, reinterpret_cast<const __half *>(u), nullptr, Bt, 1, true,
                    reinterpret_cast<__half *>(out), ssm_state, reinterpret_cast<__half *>(conv_state), taps, ws, ws_bytes,
                    as_stream(stream), nullptr, nullptr, nullptr, xa);
+}
+
+int quamba_calibrate_xfmt(const quamba_dims *dims, const quamba_fp_weights *w, const quamba_half *calib_u, int nb,
+                          int Lc, int format, double x_percentile, quamba_qweights *out_q, quamba_scales *out_s,
+                          quamba_xfmt *out_f, void *ws, size_t ws_bytes, void *stream) {
+  QUAMBA_TRY(check_calibrate_args(dims, w, out_q, out_s, ws, nb, Lc, x_percentile));
+  if (!calib_u || !out_f || !out_f->W_x_bf16 || !aligned(out_f->W_x_bf16, 16))
+    return fail(QUAMBA_EINVAL, "calibrate: NULL pointer or unaligned W_x_bf16");
+  if (format != QUAMBA_XFMT_E4M3 && format != QUAMBA_XFMT_LOG2) return fail(QUAMBA_EINVAL, "calibrate: unknown x format %d", format);
+  return calibrate_xfmt(dims, w, reinterpret_cast<const __half *>(calib_u), nb, Lc, format, x_percentile, out_q, out_s,
+                        out_f, ws, ws_bytes, as_stream(stream));
+}
+
+int quamba_mixer_prefill_xfmt(const quamba_dims *dims, const quamba_qweights *qw, const quamba_scales *sc,
+                              const quamba_xfmt *xf, const quamba_half *u, int Bt, int L, quamba_half *out,
+                              float *ssm_state, quamba_half *conv_state, const quamba_taps *taps, void *ws,
+                              size_t ws_bytes, void *stream) {
+  if (!xf) return fail(QUAMBA_EINVAL, "variant: xf is NULL");
+  return run_mixer(dims, qw, sc, reinterpret_cast<const __half *>(u), nullptr, Bt, L, false, reinterpret_cast<__half *>(out),
+                   ssm_state, reinterpret_cast<__half *>(conv_state), taps, ws, ws_bytes, as_stream(stream), nullptr,
+                   nullptr, nullptr, nullptr, xf);
+}
+
+int quamba_mixer_decode_xfmt(const quamba_dims *dims, const quamba_qweights *qw, const quamba_scales *sc,
+                             const quamba_xfmt *xf, const quamba_half *u, int Bt, quamba_half *out, float *ssm_state,
+                             quamba_half *conv_state, const quamba_taps *taps, void *ws, size_t ws_bytes, void *stream) {
+  if (!xf) return fail(QUAMBA_EINVAL, "variant: xf is NULL");
+  return run_mixer(dims, qw, sc, reinterpret_cast<const __half *>(u), nullptr, Bt, 1, true, reinterpret_cast<__half *>(out),
+                   ssm_state, reinterpret_cast<__half *>(conv_state), taps, ws, ws_bytes, as_stream(stream), nullptr,
+                   nullptr, nullptr, nullptr, xf);
+}
+
+int quamba_x_encode(int format, const float *v, size_t n, float inv_s, uint8_t *codes, void *stream) {
+  return launch_x_encode(format, v, n, inv_s, codes, as_stream(stream));
+}
+
+int quamba_xfmt_proj(int format, const uint8_t *x_code, int M, int N, int K, const uint16_t *W_bf16, int e0, int e1,
+                     const float *m, int8_t *out_q, float *acc_f32, void *ws, size_t ws_bytes, void *stream) {
+  if (!m) return fail(QUAMBA_EINVAL, "xfmt_proj: NULL multipliers");
+  if (e0 < 0 || e1 < e0 || e1 > N) return fail(QUAMBA_EINVAL, "xfmt_proj: column ranges e0=%d e1=%d N=%d", e0, e1, N);
+  return launch_xfmt_proj(format, x_code, M, N, K, W_bf16, e0, e1, m[0], m[1], m[2], out_q, acc_f32, ws, ws_bytes,
+                          as_stream(stream));
 }
 
 size_t quamba_hadx_workspace_bytes(const quamba_dims *dims, int batch, int L) {

@@ -638,4 +638,40 @@ int calibrate_xasym(const quamba_dims *d, const quamba_fp_weights *w, const __ha
   return QUAMBA_OK;
 }
 
+// Calibration with a non-uniform 8-bit format for the scan input (Appendix K): Quamba's calibration,
+// then the format's scale (log2: the maximum of |x| over the batch; E4M3: the percentile maximum
+// over 448), the multipliers with it, and the int8 codes of W_x as bfloat16 for the matrix units.
+int calibrate_xfmt(const quamba_dims *d, const quamba_fp_weights *w, const __half *calib_u, int nb, int Lc, int format,
+                   double x_percentile, quamba_qweights *oq, quamba_scales *os, quamba_xfmt *of, void *ws,
+                   size_t ws_bytes, hipStream_t st) {
+  int rc;
+  float hi = 0.f;
+  if ((rc = calibrate(d, w, calib_u, nb, Lc, QUAMBA_X_PERCENTILE, x_percentile, oq, os, ws, ws_bytes, st, nullptr, &hi)))
+    return rc;
+  const CalPlan p = cal_plan(d, nb, Lc);
+  const CalBufs b = carve(p, ws);
+  const int Di = d->d_inner, NX = d->dt_rank + 2 * d->d_state;
+  float s;
+  if (format == QUAMBA_XFMT_E4M3) {
+    s = hi > 0.f ? (float)((double)hi / 448.0) : 1.0f;
+  } else {
+    hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(256), 0, st, b.slots, (size_t)32, 0u);
+    QUAMBA_LAUNCH_CHECK();
+    if ((rc = absmax(b.x, (size_t)nb * Lc, Di, 0, Di, b.slots + 0, st))) return rc;
+    float mx;
+    QUAMBA_HIP(hipMemcpyAsync(&mx, b.slots, sizeof(mx), hipMemcpyDeviceToHost, st));
+    QUAMBA_HIP(hipStreamSynchronize(st));
+    s = mx > 0.f ? mx : 1.0f;
+  }
+  of->format = format;
+  of->s_x = s;
+  of->inv_s_x = (float)(1.0 / (double)s);
+  of->m_x_dt = (float)((double)s * (double)os->s_Wx / (double)os->s_dtl);
+  of->m_x_B = (float)((double)s * (double)os->s_Wx / (double)os->s_B);
+  of->m_x_C = (float)((double)s * (double)os->s_Wx / (double)os->s_C);
+  if ((rc = launch_i8_to_bf16(oq->W_x, (size_t)NX * Di, of->W_x_bf16, st))) return rc;
+  QUAMBA_HIP(hipStreamSynchronize(st));
+  return QUAMBA_OK;
+}
+
 }  // namespace quamba

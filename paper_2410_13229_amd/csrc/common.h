@@ -79,11 +79,19 @@ int launch_quantize_f16(const __half *x, int8_t *q, size_t n, float inv_s, hipSt
 int launch_conv_prefill(const int8_t *xpre_q, int ldx, const int8_t *w_q, const float *conv_b,
                         int Bt, int L, int Di, float m_conv, float inv_s_x, float s_xpre,
                         int8_t *x_q, __half *conv_state, hipStream_t st, __half *x16 = nullptr,
-                        int x_zero_point = 0);
+                        int x_zero_point = 0, int x_format = 0);
 
 int launch_conv_step(const int8_t *xpre_q, int ldx, const int8_t *w_q, const float *conv_b, int Bt,
                      int Di, float s_cw, float s_xpre, float inv_s_x, int8_t *x_q,
-                     __half *conv_state, hipStream_t st, __half *x16 = nullptr, int x_zero_point = 0);
+                     __half *conv_state, hipStream_t st, __half *x16 = nullptr, int x_zero_point = 0,
+                     int x_format = 0);
+
+// x_proj on one-byte codes of a non-uniform format, the encoder as a stage, and the bf16 copy of int8 weight codes
+int launch_xfmt_proj(int format, const uint8_t *x_code, int M, int N, int K, const uint16_t *W_bf16, int e0, int e1,
+                     float m0, float m1, float m2, int8_t *out_q, float *acc_f32, void *ws, size_t ws_bytes,
+                     hipStream_t st);
+int launch_x_encode(int format, const float *v, size_t n, float inv_s, uint8_t *codes, hipStream_t st);
+int launch_i8_to_bf16(const int8_t *q, size_t n, uint16_t *out, hipStream_t st);
 
 int launch_add_rmsnorm_quant(const __half *x_out, __half *res, const __half *weight, float eps,
                              float inv_s, int8_t *u_q, int M, int Dm, hipStream_t st);
@@ -108,6 +116,8 @@ struct ScanArgs {
   const __half *x_f16;
   // zero point of an asymmetric x grid (Appendix K): x = s_x (x_q - x_zero_point); 0 = symmetric
   int x_zero_point;
+  // QUAMBA_XFMT_E4M3 / QUAMBA_XFMT_LOG2: x_q holds one-byte codes of that format, x = s_x * value(code); 0 = the grid above
+  int x_format;
 };
 
 size_t scan_workspace_bytes(int Bt, int L, int Di);

@@ -103,6 +103,55 @@ __device__ __forceinline__ unsigned conv_step4(unsigned xin, const int8_t *wq4, 
   return pack_q8x4(sv[0] * inv_s_x, sv[1] * inv_s_x, sv[2] * inv_s_x, sv[3] * inv_s_x);
 }
 
+// ---- non-uniform 8-bit formats of the scan input (Appendix K: log2, and the E4M3 float it names) ----
+// E4M3 (1-4-3 bits, bias 7, subnormals m 2^-9, largest finite value 448 = 0x7e, no infinities):
+// nearest representable value of t, ties to the even mantissa, saturating; the sign bit of t is kept.
+__device__ __forceinline__ unsigned encode_e4m3(float t) {
+  const unsigned tb = __float_as_uint(t);
+  const float a = fminf(__uint_as_float(tb & 0x7fffffffu), 448.f);
+  int E = static_cast<int>(__float_as_uint(a) >> 23) - 127;
+  E = E < -6 ? -6 : E;  // below the smallest normal the subnormal spacing 2^-9 holds
+  // a / 2^(E-3): an exact scaling by a power of two, then round to nearest even
+  int q = static_cast<int>(__builtin_rintf(a * __uint_as_float(static_cast<unsigned>(130 - E) << 23)));
+  if (q == 16) {  // rounded up into the next binade
+    q = 8;
+    ++E;
+  }
+  unsigned field = q >= 8 ? ((static_cast<unsigned>(E + 7) << 3) | static_cast<unsigned>(q - 8)) : static_cast<unsigned>(q);
+  field = field > 0x7eu ? 0x7eu : field;
+  return field | ((tb >> 24) & 0x80u);
+}
+__device__ __forceinline__ float decode_e4m3(unsigned c) {
+  const unsigned mag = c & 0x7fu;
+  const float normal = __uint_as_float((mag << 20) + 0x3c000000u);  // exponent field + 120, mantissa in the top bits
+  const float sub = static_cast<float>(mag) * 0.001953125f;          // m 2^-9
+  return __uint_as_float(__float_as_uint(mag < 8u ? sub : normal) | ((c & 0x80u) << 24));
+}
+// log2: t = f 2^E with 1 <= f < 2 goes to 2^k, k = E + (f >= fp32(sqrt 2)) (nearest in the log domain);
+// code = sign bit | e with e = -k in 0..126 (larger t saturates at e = 0), 127 for zero and for
+// anything below 2^-126.5.  Integer work on the bits of t, so subnormal t needs no care elsewhere.
+__device__ __forceinline__ unsigned encode_log2(float t) {
+  const unsigned tb = __float_as_uint(t);
+  const unsigned ab = tb & 0x7fffffffu;
+  const int ef = static_cast<int>(ab >> 23);
+  const unsigned man = ab & 0x7fffffu;
+  int k;
+  if (ef != 0) {
+    k = ef - 127 + (man >= 0x3504f3u ? 1 : 0);
+  } else {  // subnormal: only [2^-127 sqrt 2, 2^-126) still reaches e = 126
+    k = (man >= 0x5a827au) ? -126 : -200;  // man 2^-149 >= 2^-127 fp32(sqrt 2), i.e. man >= 0xb504f3 / 2 rounded up
+  }
+  int e = -k;
+  const bool zero = ab == 0u || e > 126;
+  e = e < 0 ? 0 : e;
+  return zero ? 127u : (static_cast<unsigned>(e) | ((tb >> 24) & 0x80u));
+}
+__device__ __forceinline__ float decode_log2(unsigned c) {
+  const unsigned e = c & 0x7fu;
+  const unsigned bits = e == 127u ? 0u : ((127u - e) << 23);
+  return __uint_as_float(bits | ((c & 0x80u) << 24));
+}
+
 // four floats -> four fp16 in one 8-byte word
 __device__ __forceinline__ uint2 pack_f16x4(float v0, float v1, float v2, float v3) {
   union {

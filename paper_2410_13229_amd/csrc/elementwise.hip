@@ -52,8 +52,17 @@ __device__ __forceinline__ float silu_fast(float v) {
 
 // OUT_F16 (the Appendix H comparison variant): the SiLU output is stored in half precision into
 // x16 instead of being quantized into xq.  OUT_ASYM (Appendix K): codes on an asymmetric grid,
-// clamp(rne(v / s + zero point)).
-enum ConvOut { OUT_SYM, OUT_F16, OUT_ASYM };
+// clamp(rne(v / s + zero point)).  OUT_E4M3 / OUT_LOG2 (Appendix K): one-byte codes of v / s in that format.
+enum ConvOut { OUT_SYM, OUT_F16, OUT_ASYM, OUT_E4M3, OUT_LOG2 };
+template <ConvOut MODE>
+__device__ __forceinline__ unsigned conv_pack4(const float (&sv)[4]) {
+  if constexpr (MODE == OUT_E4M3)
+    return encode_e4m3(sv[0]) | (encode_e4m3(sv[1]) << 8) | (encode_e4m3(sv[2]) << 16) | (encode_e4m3(sv[3]) << 24);
+  else if constexpr (MODE == OUT_LOG2)
+    return encode_log2(sv[0]) | (encode_log2(sv[1]) << 8) | (encode_log2(sv[2]) << 16) | (encode_log2(sv[3]) << 24);
+  else
+    return pack_q8x4(sv[0], sv[1], sv[2], sv[3]);
+}
 template <ConvOut MODE, int CONV_TT>
 __global__ __launch_bounds__(256) void conv_prefill_kernel(
     const int8_t *__restrict__ xpre, int ldx, const int8_t *__restrict__ wq,
@@ -101,7 +110,7 @@ __global__ __launch_bounds__(256) void conv_prefill_kernel(
       if constexpr (F16OUT)
         *reinterpret_cast<uint2 *>(x16 + ((size_t)b * L + t0 + i) * Di + d0) = pack_f16x4(sv[0], sv[1], sv[2], sv[3]);
       else
-        *reinterpret_cast<unsigned *>(dst + (size_t)(t0 + i) * Di) = pack_q8x4(sv[0], sv[1], sv[2], sv[3]);
+        *reinterpret_cast<unsigned *>(dst + (size_t)(t0 + i) * Di) = conv_pack4<MODE>(sv);
     }
   }
   // the tile holding the sequence end also emits the carried window [L-3, L-2, L-1]
@@ -146,12 +155,16 @@ __global__ __launch_bounds__(256) void conv_step_kernel(const int8_t *__restrict
   } else {
     float sv[4];
     conv_step4_values(xin, wq + (size_t)d0 * 4, bias + d0, cs, s_cw, s_xpre, sv);
-    if constexpr (MODE == OUT_F16)  // half-precision output, no quantizer
+    if constexpr (MODE == OUT_F16) {  // half-precision output, no quantizer
       *reinterpret_cast<uint2 *>(x16 + (size_t)b * Di + d0) = pack_f16x4(sv[0], sv[1], sv[2], sv[3]);
-    else
+    } else if constexpr (MODE == OUT_ASYM) {
       *reinterpret_cast<unsigned *>(xq + (size_t)b * Di + d0) =
           pack_q8x4(__fadd_rn(sv[0] * inv_s_x, x_zp), __fadd_rn(sv[1] * inv_s_x, x_zp),
                     __fadd_rn(sv[2] * inv_s_x, x_zp), __fadd_rn(sv[3] * inv_s_x, x_zp));
+    } else {
+      const float tv[4] = {sv[0] * inv_s_x, sv[1] * inv_s_x, sv[2] * inv_s_x, sv[3] * inv_s_x};
+      *reinterpret_cast<unsigned *>(xq + (size_t)b * Di + d0) = conv_pack4<MODE>(tv);
+    }
   }
 }
 
@@ -232,10 +245,16 @@ namespace {
 template <int TT>
 void conv_prefill_launch(const int8_t *xpre_q, int ldx, const int8_t *w_q, const float *conv_b, int Bt, int L, int Di,
                          float m_conv, float inv_s_x, float s_xpre, int8_t *x_q, __half *conv_state, hipStream_t st,
-                         __half *x16, int x_zero_point) {
+                         __half *x16, int x_zero_point, int x_format) {
   dim3 grid((Di / 4 + 255) / 256, (L + TT - 1) / TT, Bt);
   const float zp = static_cast<float>(x_zero_point);
-  if (x16)
+  if (x_format == QUAMBA_XFMT_E4M3)
+    hipLaunchKernelGGL((conv_prefill_kernel<OUT_E4M3, TT>), grid, dim3(256), 0, st, xpre_q, ldx, w_q, conv_b, L, Di,
+                       m_conv, inv_s_x, s_xpre, x_q, x16, zp, conv_state);
+  else if (x_format == QUAMBA_XFMT_LOG2)
+    hipLaunchKernelGGL((conv_prefill_kernel<OUT_LOG2, TT>), grid, dim3(256), 0, st, xpre_q, ldx, w_q, conv_b, L, Di,
+                       m_conv, inv_s_x, s_xpre, x_q, x16, zp, conv_state);
+  else if (x16)
     hipLaunchKernelGGL((conv_prefill_kernel<OUT_F16, TT>), grid, dim3(256), 0, st, xpre_q, ldx, w_q, conv_b, L, Di,
                        m_conv, inv_s_x, s_xpre, x_q, x16, zp, conv_state);
   else if (x_zero_point != 0)
@@ -249,7 +268,7 @@ void conv_prefill_launch(const int8_t *xpre_q, int ldx, const int8_t *w_q, const
 
 int launch_conv_prefill(const int8_t *xpre_q, int ldx, const int8_t *w_q, const float *conv_b, int Bt,
                         int L, int Di, float m_conv, float inv_s_x, float s_xpre, int8_t *x_q,
-                        __half *conv_state, hipStream_t st, __half *x16, int x_zero_point) {
+                        __half *conv_state, hipStream_t st, __half *x16, int x_zero_point, int x_format) {
   // Tokens per thread: 8 re-reads the least of the 3-token window and is best when the launch has
   // many waves per SIMD anyway or is tiny; in between (about 4 to 16 M elements, 2048 tokens of the
   // 2.8B shape) 4 gives twice the waves and is 0.5 us faster (measured 8.9 vs 9.4 us; 47.5 vs 46.3 us
@@ -257,21 +276,27 @@ int launch_conv_prefill(const int8_t *xpre_q, int ldx, const int8_t *w_q, const 
   const size_t elems = (size_t)Bt * L * Di;
   if (elems >= ((size_t)4 << 20) && elems <= ((size_t)16 << 20))
     conv_prefill_launch<4>(xpre_q, ldx, w_q, conv_b, Bt, L, Di, m_conv, inv_s_x, s_xpre, x_q, conv_state, st, x16,
-                           x_zero_point);
+                           x_zero_point, x_format);
   else
     conv_prefill_launch<8>(xpre_q, ldx, w_q, conv_b, Bt, L, Di, m_conv, inv_s_x, s_xpre, x_q, conv_state, st, x16,
-                           x_zero_point);
+                           x_zero_point, x_format);
   QUAMBA_LAUNCH_CHECK();
   return QUAMBA_OK;
 }
 
 int launch_conv_step(const int8_t *xpre_q, int ldx, const int8_t *w_q, const float *conv_b, int Bt,
                      int Di, float s_cw, float s_xpre, float inv_s_x, int8_t *x_q, __half *conv_state,
-                     hipStream_t st, __half *x16, int x_zero_point) {
+                     hipStream_t st, __half *x16, int x_zero_point, int x_format) {
   const size_t n = (size_t)Bt * (Di / 4);
   const dim3 grid((unsigned)((n + 255) / 256));
   const float zp = static_cast<float>(x_zero_point);
-  if (x16)
+  if (x_format == QUAMBA_XFMT_E4M3)
+    hipLaunchKernelGGL(conv_step_kernel<OUT_E4M3>, grid, dim3(256), 0, st, xpre_q, ldx, w_q, conv_b, Bt, Di, s_cw,
+                       s_xpre, inv_s_x, x_q, x16, zp, conv_state);
+  else if (x_format == QUAMBA_XFMT_LOG2)
+    hipLaunchKernelGGL(conv_step_kernel<OUT_LOG2>, grid, dim3(256), 0, st, xpre_q, ldx, w_q, conv_b, Bt, Di, s_cw,
+                       s_xpre, inv_s_x, x_q, x16, zp, conv_state);
+  else if (x16)
     hipLaunchKernelGGL(conv_step_kernel<OUT_F16>, grid, dim3(256), 0, st, xpre_q, ldx, w_q, conv_b, Bt, Di, s_cw,
                        s_xpre, inv_s_x, x_q, x16, zp, conv_state);
   else if (x_zero_point != 0)

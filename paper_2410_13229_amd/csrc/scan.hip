@@ -73,6 +73,18 @@ struct Dev {
   float x_off;          // -s_x * zero point of an asymmetric x grid: x = s_x x_q + x_off (0 = symmetric)
 };
 
+// How the scan reads x: int8 codes on a uniform grid (s_x x_q + x_off), half precision values (the
+// Appendix H comparison variant), or one-byte codes of a non-uniform format (Appendix K).
+enum XMode { X_I8 = 0, X_F16 = 1, X_E4M3 = 2, X_LOG2 = 3 };
+// raw: the sign-extended code byte, or the 16 bits of the half
+template <int XM>
+__device__ __forceinline__ float x_value(const Dev &p, int raw) {
+  if constexpr (XM == X_F16) return __half2float(__ushort_as_half(static_cast<unsigned short>(raw)));
+  else if constexpr (XM == X_E4M3) return p.s_x * decode_e4m3(static_cast<unsigned>(raw) & 0xffu);
+  else if constexpr (XM == X_LOG2) return p.s_x * decode_log2(static_cast<unsigned>(raw) & 0xffu);
+  else return __builtin_fmaf(p.s_x, static_cast<float>(raw), p.x_off);
+}
+
 // Dequantize B (and C) of tokens [row0, row0+cnt) into LDS as fp32 [TB][16].
 template <bool WITH_C>
 __device__ __forceinline__ void stage_bc(const Dev &p, size_t row0, int cnt, float (*sB)[NS],
@@ -94,7 +106,7 @@ __device__ __forceinline__ void stage_bc(const Dev &p, size_t row0, int cnt, flo
 // The int8 x / dt / z bytes of the next TS tokens are fetched into registers while the
 // current TS tokens are computed, so no load latency sits on the recurrence.
 // FUSE_DT (pass 1 only): dt_q is not read but computed from dt_low and W_dt, and written out.
-template <bool OUTPUT, bool FUSE_DT, bool XF16 = false>
+template <bool OUTPUT, bool FUSE_DT, int XM = X_I8>
 __global__ __launch_bounds__(SCAN_THREADS) void scan_chunk_kernel(Dev p) {
   static_assert(!(OUTPUT && FUSE_DT), "dt_q is produced by pass 1");
   __shared__ __attribute__((aligned(16))) float sB[TB][NS];
@@ -136,7 +148,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_chunk_kernel(Dev p) {
   const unsigned ud = static_cast<unsigned>(dd);
   const size_t tok0 = seq0 + t0;
   const int nt = t1 - t0;
-  const auto rx = XF16 ? buffer_over(p.x_f16 + tok0 * p.Di, nt * p.Di * 2) : buffer_over(p.x_q + tok0 * p.Di, nt * p.Di);
+  const auto rx = XM == X_F16 ? buffer_over(p.x_f16 + tok0 * p.Di, nt * p.Di * 2) : buffer_over(p.x_q + tok0 * p.Di, nt * p.Di);
   const auto rdt = FUSE_DT ? rx : buffer_over(p.dt_q + tok0 * p.Di, nt * p.Di);
   const auto rz = OUTPUT ? buffer_over(p.z_q + tok0 * p.ldz, (nt - 1) * p.ldz + p.Di) : rx;
   const auto rg = OUTPUT ? buffer_over(p.g16 + tok0 * p.Di, nt * p.Di * 2) : rx;
@@ -205,15 +217,14 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_chunk_kernel(Dev p) {
     for (int i = 0; i < TS; ++i) {
       // clamp: tokens past the chunk are loaded but never used
       const int row = min(t + i, t1 - 1) - t0;
-      r.x[i] = XF16 ? static_cast<int>(buffer_load_u16(rx, 2 * ud, row * p.Di * 2)) : buffer_load_i8(rx, ud, row * p.Di);
+      r.x[i] = XM == X_F16 ? static_cast<int>(buffer_load_u16(rx, 2 * ud, row * p.Di * 2)) : buffer_load_i8(rx, ud, row * p.Di);
       if (!FUSE_DT) r.dt[i] = buffer_load_i8(rdt, ud, row * p.Di);  // fused: read from the LDS tile
       if (OUTPUT) r.z[i] = buffer_load_i8(rz, ud, row * p.ldz);
     }
   };
   auto token = [&](const Regs &r, int i, int t, int tl) {  // t: token index, tl: index inside the LDS block
       {
-        const float xv = XF16 ? __half2float(__ushort_as_half(static_cast<unsigned short>(r.x[i])))
-                              : __builtin_fmaf(p.s_x, static_cast<float>(r.x[i]), p.x_off);
+        const float xv = x_value<XM>(p, r.x[i]);
         const int dtq = FUSE_DT ? static_cast<int>(sDT[wave][tl + i][lane]) : r.dt[i];
         const float dt = softplus_f(p.s_dt * static_cast<float>(dtq) + bias);
         const float u = dt * xv;
@@ -318,7 +329,7 @@ __global__ __launch_bounds__(256) void scan_carry_kernel(Dev p, float *__restric
 // 4 lanes per channel, each owning 4 of the 16 states as one float4.  FUSE_DT: the step also forms
 // its own dt code, dt_q = q(W_dt[d, :] . dt_low[b, :], m_dt) (dt_proj, K = dt_rank): the four lanes of
 // a channel share the 16-byte pieces of the two rows and add their parts with two shuffles.
-template <bool FUSE_DT, bool XF16 = false>
+template <bool FUSE_DT, int XM = X_I8>
 __global__ __launch_bounds__(256) void scan_step_kernel(Dev p, float *__restrict__ ssm_state, int Bt) {
   const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;  // (b, d, quad)
   const size_t total = (size_t)Bt * p.Di * 4;
@@ -335,8 +346,8 @@ __global__ __launch_bounds__(256) void scan_step_kernel(Dev p, float *__restrict
   const unsigned cw = *reinterpret_cast<const unsigned *>(p.C_q + (size_t)b * p.ldbc + 4 * q);
   // (a compile-time choice: a run-time test of the pointer would put this load behind a branch and
   // cost the step one more memory round trip)
-  const float xv = XF16 ? __half2float(p.x_f16[(size_t)b * p.Di + d])
-                        : __builtin_fmaf(p.s_x, static_cast<float>(p.x_q[(size_t)b * p.Di + d]), p.x_off);
+  const float xv = x_value<XM>(p, XM == X_F16 ? static_cast<int>(__half_as_ushort(p.x_f16[(size_t)b * p.Di + d]))
+                                               : static_cast<int>(p.x_q[(size_t)b * p.Di + d]));
   int dtq;
   if (FUSE_DT) {
     const int8_t *wrow = p.W_dt + (size_t)d * p.R;
@@ -388,7 +399,7 @@ __global__ __launch_bounds__(256) void scan_step_kernel(Dev p, float *__restrict
 // code loads of the BB sequences are requested before the first dot product.  BB = 4 (measured at
 // 2.8B, batch 64: step 47.5 us with the separate dt_proj GEMM, 44.6 us with BB = 4 or 2, 47.4 us
 // with BB = 8, whose 183 registers leave two waves per SIMD and nothing to overlap the loads with).
-template <bool XF16, int BB, int NP>
+template <int XM, int BB, int NP>
 __global__ __launch_bounds__(256) void scan_step_batch_kernel(Dev p, float *__restrict__ ssm_state, int Bt) {
   const int q = threadIdx.x & 3;
   const int d = blockIdx.x * 64 + (threadIdx.x >> 2);
@@ -420,8 +431,8 @@ __global__ __launch_bounds__(256) void scan_step_batch_kernel(Dev p, float *__re
     hv[i] = reinterpret_cast<const float4 *>(ssm_state)[(b * p.Di + dd) * 4 + q];
     bw[i] = *reinterpret_cast<const unsigned *>(p.B_q + b * p.ldbc + 4 * q);
     cw[i] = *reinterpret_cast<const unsigned *>(p.C_q + b * p.ldbc + 4 * q);
-    xv[i] = XF16 ? __half2float(p.x_f16[b * p.Di + dd])
-                 : __builtin_fmaf(p.s_x, static_cast<float>(p.x_q[b * p.Di + dd]), p.x_off);
+    xv[i] = x_value<XM>(p, XM == X_F16 ? static_cast<int>(__half_as_ushort(p.x_f16[b * p.Di + dd]))
+                                       : static_cast<int>(p.x_q[b * p.Di + dd]));
     zv[i] = p.s_z * static_cast<float>(p.z_q[b * p.ldz + dd]);
 #pragma unroll
     for (int j = 0; j < NP; ++j) {
@@ -530,29 +541,35 @@ int launch_scan_prefill(const ScanArgs &a, void *ws, size_t ws_bytes, hipStream_
   p.ssum = reinterpret_cast<float *>(static_cast<char *>(ws) +
                                      align_up((size_t)a.Bt * p.nchunks * a.Di * NS * sizeof(float), 256));
   dim3 grid((a.Di + SCAN_THREADS - 1) / SCAN_THREADS, p.nchunks, a.Bt);
+  const int xm = a.x_f16 ? X_F16 : (a.x_format == QUAMBA_XFMT_E4M3 ? X_E4M3 : (a.x_format == QUAMBA_XFMT_LOG2 ? X_LOG2 : X_I8));
+#define QUAMBA_XM_SWITCH(CALL) \
+  switch (xm) {                \
+    case X_F16: CALL(X_F16); break;   \
+    case X_E4M3: CALL(X_E4M3); break; \
+    case X_LOG2: CALL(X_LOG2); break; \
+    default: CALL(X_I8); break;       \
+  }
   if (a.dtlow_q) {
     if (!a.W_dt || !a.dt_out || a.R < 16 || a.R % 16 || a.lddl % 16 || a.lddl < a.R || a.Di % 4 ||
         !aligned(a.dtlow_q, 16) || !aligned(a.W_dt, 16) || !aligned(a.dt_out, 4))
       return fail(QUAMBA_EUNSUPPORTED, "scan: fused dt_proj needs dt_rank and lddl multiples of 16, Di a multiple "
                                        "of 4, 16-byte aligned dt_low and W_dt");
-    if (a.x_f16)
-      hipLaunchKernelGGL((scan_chunk_kernel<false, true, true>), grid, dim3(SCAN_THREADS), 0, st, p);
-    else
-      hipLaunchKernelGGL((scan_chunk_kernel<false, true>), grid, dim3(SCAN_THREADS), 0, st, p);
-  } else if (a.x_f16) {
-    hipLaunchKernelGGL((scan_chunk_kernel<false, false, true>), grid, dim3(SCAN_THREADS), 0, st, p);
+#define QUAMBA_PASS1F(XMV) hipLaunchKernelGGL((scan_chunk_kernel<false, true, XMV>), grid, dim3(SCAN_THREADS), 0, st, p)
+    QUAMBA_XM_SWITCH(QUAMBA_PASS1F)
+#undef QUAMBA_PASS1F
   } else {
-    hipLaunchKernelGGL((scan_chunk_kernel<false, false>), grid, dim3(SCAN_THREADS), 0, st, p);
+#define QUAMBA_PASS1(XMV) hipLaunchKernelGGL((scan_chunk_kernel<false, false, XMV>), grid, dim3(SCAN_THREADS), 0, st, p)
+    QUAMBA_XM_SWITCH(QUAMBA_PASS1)
+#undef QUAMBA_PASS1
   }
   QUAMBA_LAUNCH_CHECK();
   const size_t n2 = (size_t)a.Bt * a.Di * NS;
   hipLaunchKernelGGL(scan_carry_kernel, dim3((unsigned)((n2 + 255) / 256)), dim3(256), 0, st, p, a.ssm_state,
                      a.Bt);
   QUAMBA_LAUNCH_CHECK();
-  if (a.x_f16)
-    hipLaunchKernelGGL((scan_chunk_kernel<true, false, true>), grid, dim3(SCAN_THREADS), 0, st, p);
-  else
-    hipLaunchKernelGGL((scan_chunk_kernel<true, false>), grid, dim3(SCAN_THREADS), 0, st, p);
+#define QUAMBA_PASS3(XMV) hipLaunchKernelGGL((scan_chunk_kernel<true, false, XMV>), grid, dim3(SCAN_THREADS), 0, st, p)
+  QUAMBA_XM_SWITCH(QUAMBA_PASS3)
+#undef QUAMBA_PASS3
   QUAMBA_LAUNCH_CHECK();
   return QUAMBA_OK;
 }
@@ -560,6 +577,7 @@ int launch_scan_prefill(const ScanArgs &a, void *ws, size_t ws_bytes, hipStream_
 int launch_scan_step(const ScanArgs &a, hipStream_t st) {
   Dev p = make_dev(a);
   p.L = 1;
+  const int xm = a.x_f16 ? X_F16 : (a.x_format == QUAMBA_XFMT_E4M3 ? X_E4M3 : (a.x_format == QUAMBA_XFMT_LOG2 ? X_LOG2 : X_I8));
   const size_t n = (size_t)a.Bt * a.Di * 4;
   if (a.dtlow_q) {
     if (!a.W_dt || a.R < 16 || a.R % 16 || a.lddl % 16 || a.lddl < a.R || !aligned(a.dtlow_q, 16) || !aligned(a.W_dt, 16))
@@ -569,31 +587,31 @@ int launch_scan_step(const ScanArgs &a, hipStream_t st) {
     const int np = (a.R + 63) / 64;
     if (a.Bt > 16 && np <= 4) {  // many sequences: keep the W_dt rows in registers over BB of them
       const dim3 grid((unsigned)((a.Di + 63) / 64), (unsigned)((a.Bt + BB - 1) / BB));
-#define QUAMBA_STEP_BATCH(XF, NPV) \
-  hipLaunchKernelGGL((scan_step_batch_kernel<XF, BB, NPV>), grid, dim3(256), 0, st, p, a.ssm_state, a.Bt)
-      if (a.x_f16) {
-        if (np == 1) QUAMBA_STEP_BATCH(true, 1); else if (np == 2) QUAMBA_STEP_BATCH(true, 2);
-        else if (np == 3) QUAMBA_STEP_BATCH(true, 3); else QUAMBA_STEP_BATCH(true, 4);
-      } else {
-        if (np == 1) QUAMBA_STEP_BATCH(false, 1); else if (np == 2) QUAMBA_STEP_BATCH(false, 2);
-        else if (np == 3) QUAMBA_STEP_BATCH(false, 3); else QUAMBA_STEP_BATCH(false, 4);
-      }
+#define QUAMBA_STEP_BATCH(XMV)                                                                                        \
+  do {                                                                                                                \
+    if (np == 1) hipLaunchKernelGGL((scan_step_batch_kernel<XMV, BB, 1>), grid, dim3(256), 0, st, p, a.ssm_state, a.Bt);      \
+    else if (np == 2) hipLaunchKernelGGL((scan_step_batch_kernel<XMV, BB, 2>), grid, dim3(256), 0, st, p, a.ssm_state, a.Bt); \
+    else if (np == 3) hipLaunchKernelGGL((scan_step_batch_kernel<XMV, BB, 3>), grid, dim3(256), 0, st, p, a.ssm_state, a.Bt); \
+    else hipLaunchKernelGGL((scan_step_batch_kernel<XMV, BB, 4>), grid, dim3(256), 0, st, p, a.ssm_state, a.Bt);              \
+  } while (0)
+      QUAMBA_XM_SWITCH(QUAMBA_STEP_BATCH)
 #undef QUAMBA_STEP_BATCH
-    } else if (a.x_f16)
-      hipLaunchKernelGGL((scan_step_kernel<true, true>), dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p,
-                         a.ssm_state, a.Bt);
-    else
-      hipLaunchKernelGGL((scan_step_kernel<true>), dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, a.ssm_state,
-                         a.Bt);
-  } else if (a.x_f16) {
-    hipLaunchKernelGGL((scan_step_kernel<false, true>), dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p,
-                       a.ssm_state, a.Bt);
+    } else {
+#define QUAMBA_STEPF(XMV) \
+  hipLaunchKernelGGL((scan_step_kernel<true, XMV>), dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, a.ssm_state, a.Bt)
+      QUAMBA_XM_SWITCH(QUAMBA_STEPF)
+#undef QUAMBA_STEPF
+    }
   } else {
-    hipLaunchKernelGGL((scan_step_kernel<false>), dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, a.ssm_state,
-                       a.Bt);
+#define QUAMBA_STEP(XMV) \
+  hipLaunchKernelGGL((scan_step_kernel<false, XMV>), dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, a.ssm_state, a.Bt)
+    QUAMBA_XM_SWITCH(QUAMBA_STEP)
+#undef QUAMBA_STEP
   }
   QUAMBA_LAUNCH_CHECK();
   return QUAMBA_OK;
 }
+
+#undef QUAMBA_XM_SWITCH
 
 }  // namespace quamba
