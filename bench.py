@@ -184,7 +184,18 @@ def bench_x_scale_rules(Q, W, torch, np, dev, to_dev, stream):
     asym = {"x_step": round(xa.s_x, 6), "symmetric_x_step": round(sc.s_x, 6), "zero_point": int(xa.zero_point),
             "rel_err": round(rel_err(), 5), "prefill_us": round(timed(run_asym) * 1e6, 1),
             "symmetric_prefill_us": round(timed(run_sym) * 1e6, 1)}
-    return {"asymmetric_p99.999": asym, "workload": "c1 shape, hidden input without outlier channels, 8 rows of the x half of W_in scaled by 8; "
+    # the non-uniform formats of Appendix K (log2, E4M3) on the same data; their x_proj runs on the bf16
+    # matrix units, the codes are decoded inside the scan
+    formats = {}
+    wb = torch.empty((NX, Di), dtype=torch.int16, device=dev)
+    for name, fid in (("e4m3_p99.999", Q.XFMT_E4M3), ("log2_max", Q.XFMT_LOG2)):
+        scf, xf = Q.quamba_calibrate_xfmt(cfg, fw, calib, nb, Lc, fid, 99.999, qd, wb, cws, stream)
+        run_f = lambda: Q.quamba_mixer_prefill_xfmt(dims, qs, scf, xf, u, 1, L, out, None, None, None, ws, stream)  # noqa: E731
+        run_f()
+        formats[name] = {"x_scale": round(xf.s_x, 6), "rel_err": round(rel_err(), 5),
+                         "prefill_us": round(timed(run_f) * 1e6, 1)}
+    formats["symmetric_prefill_us"] = asym["symmetric_prefill_us"]
+    return {"asymmetric_p99.999": asym, "formats": formats, "workload": "c1 shape, hidden input without outlier channels, 8 rows of the x half of W_in scaled by 8; "
                         "calibrated on a seeded 4x256 batch, error over a fresh 1024-token sequence",
             "rules": res}
 

@@ -247,11 +247,13 @@ int quamba_mixer_decode_xasym(const quamba_dims *dims, const quamba_qweights *qw
  *                     value, ties to the even mantissa, saturating at +-448;  x = s value(code)
  *   x_proj: acc[n] = sum_k W_x_q[n, k] value(code_k) (fp32 sums in a fixed order: K is cut in equal
  *           ranges whose sums are added in ascending order); outputs clamp(rne(acc * m)), m = s s_Wx / s_out
- * quamba_xfmt: W_x_bf16 [dt_rank + 2 d_state, d_inner] is device memory provided by the caller (16-byte
- * aligned) and written by the calibration: the int8 codes of W_x as bfloat16 bit patterns; the scalars
- * are host values.  Entry points as quamba_calibrate / quamba_mixer_prefill / quamba_mixer_decode, plus
+ * quamba_xfmt: W_x_bf16, (dt_rank + 2 d_state) * d_inner 16-bit words of device memory provided by the caller
+ * (16-byte aligned) and written by the calibration: the int8 codes of W_x as bfloat16 bit patterns, in the
+ * order the matrix unit consumes them, with N = dt_rank + 2 d_state:
+ *   W_x_bf16[(s N + n) 16 + 8 h + j] = bf16(W_x_q[n, 32 (s / 2) + 16 h + 8 (s % 2) + j]),  s < d_inner / 16, h < 2, j < 8
+ * the scalars are host values.  Entry points as quamba_calibrate / quamba_mixer_prefill / quamba_mixer_decode, plus
  * `xf`; same workspaces.  taps->x_q receives the code bytes, taps->acc_x the fp32 sums (as bit patterns
- * in the int32 buffer); d_inner must be a multiple of 16 and dt_rank + 2 d_state at most 320. */
+ * in the int32 buffer); d_inner must be a multiple of 32 and dt_rank + 2 d_state at most 320. */
 #define QUAMBA_XFMT_E4M3 1
 #define QUAMBA_XFMT_LOG2 2
 typedef struct quamba_xfmt {
@@ -273,9 +275,9 @@ int quamba_mixer_decode_xfmt(const quamba_dims *dims, const quamba_qweights *qw,
                              size_t ws_bytes, void *stream);
 /* Stages of the variant.  quamba_x_encode: codes[i] = encode(fp32(v[i]) * inv_s) for n fp32 values.
  * quamba_xfmt_proj: out_q [M, N] int8 = clamp(rne(acc * m)) with acc as above over x_code [M, K] and
- * W_bf16 [N, K]; columns [0, e0) use m[0], [e0, e1) m[1], [e1, N) m[2] (multiples of 4); acc_f32 [M, N]
+ * W_bf16 (N * K words in the order above); columns [0, e0) use m[0], [e0, e1) m[1], [e1, N) m[2] (multiples of 4); acc_f32 [M, N]
  * (may be NULL) receives the sums; ws: quamba_gemm_workspace_bytes(M, N, K) bytes, 256-byte aligned.
- * K a multiple of 16, N a multiple of 4 and at most 320; pointers 16-byte aligned. */
+ * K a multiple of 32, N a multiple of 4 and at most 320; pointers 16-byte aligned. */
 int quamba_x_encode(int format, const float *v, size_t n, float inv_s, uint8_t *codes, void *stream);
 int quamba_xfmt_proj(int format, const uint8_t *x_code, int M, int N, int K, const uint16_t *W_bf16, int e0, int e1,
                      const float *m /* host, 3 */, int8_t *out_q, float *acc_f32, void *ws, size_t ws_bytes,

@@ -139,9 +139,9 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
   if (xf && (xf->format != QUAMBA_XFMT_E4M3 && xf->format != QUAMBA_XFMT_LOG2))
     return fail(QUAMBA_EINVAL, "variant: unknown x format %d", xf->format);
   if (xf && (!xf->W_x_bf16 || !aligned(xf->W_x_bf16, 16))) return fail(QUAMBA_EINVAL, "variant: W_x_bf16 is NULL or unaligned");
-  if (xf && (d->d_inner % 16 != 0 || d->dt_rank + 2 * d->d_state > 320 || (d->dt_rank + 2 * d->d_state) % 4 != 0 ||
+  if (xf && (d->d_inner % 32 != 0 || d->dt_rank + 2 * d->d_state > 320 || (d->dt_rank + 2 * d->d_state) % 4 != 0 ||
              d->dt_rank % 4 != 0 || d->d_state % 4 != 0))
-    return fail(QUAMBA_EUNSUPPORTED, "variant: d_inner must be a multiple of 16, dt_rank and d_state multiples of 4, "
+    return fail(QUAMBA_EUNSUPPORTED, "variant: d_inner must be a multiple of 32, dt_rank and d_state multiples of 4, "
                                      "dt_rank + 2 d_state at most 320");
   // scale, reciprocal and zero point of the scan input's grid
   const float s_x = xa ? xa->s_x : (xf ? xf->s_x : sc->s_x), inv_s_x = xa ? xa->inv_s_x : (xf ? xf->inv_s_x : sc->inv_s_x);

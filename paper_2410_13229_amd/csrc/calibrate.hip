@@ -669,7 +669,7 @@ int calibrate_xfmt(const quamba_dims *d, const quamba_fp_weights *w, const __hal
   of->m_x_dt = (float)((double)s * (double)os->s_Wx / (double)os->s_dtl);
   of->m_x_B = (float)((double)s * (double)os->s_Wx / (double)os->s_B);
   of->m_x_C = (float)((double)s * (double)os->s_Wx / (double)os->s_C);
-  if ((rc = launch_i8_to_bf16(oq->W_x, (size_t)NX * Di, of->W_x_bf16, st))) return rc;
+  if ((rc = launch_i8_to_bf16(oq->W_x, NX, Di, of->W_x_bf16, st))) return rc;
   QUAMBA_HIP(hipStreamSynchronize(st));
   return QUAMBA_OK;
 }

@@ -91,7 +91,7 @@ int launch_xfmt_proj(int format, const uint8_t *x_code, int M, int N, int K, con
                      float m0, float m1, float m2, int8_t *out_q, float *acc_f32, void *ws, size_t ws_bytes,
                      hipStream_t st);
 int launch_x_encode(int format, const float *v, size_t n, float inv_s, uint8_t *codes, hipStream_t st);
-int launch_i8_to_bf16(const int8_t *q, size_t n, uint16_t *out, hipStream_t st);
+int launch_i8_to_bf16(const int8_t *q, int N, int K, uint16_t *out, hipStream_t st);
 
 int launch_add_rmsnorm_quant(const __half *x_out, __half *res, const __half *weight, float eps,
                              float inv_s, int8_t *u_q, int M, int Dm, hipStream_t st);

@@ -26,7 +26,14 @@ def _order_index(fmt, code):
 
 
 def _bf16_bits(w_q):
-    return (np.asarray(w_q).astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)
+    """int8 codes [N, K] -> bfloat16 bit patterns in the order the header documents:
+    out[(s N + n) 16 + 8 h + j] = W[n, 32 (s // 2) + 16 h + 8 (s % 2) + j]."""
+    w = np.asarray(w_q)
+    N, K = w.shape
+    bits = (w.astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)
+    s, h, j = np.meshgrid(np.arange(K // 16), np.arange(2), np.arange(8), indexing="ij")
+    k = (32 * (s // 2) + 16 * h + 8 * (s % 2) + j).reshape(K // 16, 16)           # [s, 8 h + j] -> k
+    return np.ascontiguousarray(bits[:, k].transpose(1, 0, 2)).reshape(N, K)      # [s, n, p], kept 2-D for the allocators
 
 
 def _encode_on_gpu(fmt, v, inv_s):
@@ -58,7 +65,7 @@ def test_encoder_bit_exact(fmt):
 
 @pytest.mark.parametrize("fmt", XF.FORMATS)
 @pytest.mark.parametrize("M,N,K", [(1, 48, 64), (37, 80, 192), (64, 192, 5120), (200, 192, 5120), (2048, 192, 5120),
-                                   (70, 288, 1024), (5, 320, 16)])
+                                   (4100, 192, 1024), (70, 288, 1024), (5, 320, 32), (33, 192, 352)])
 def test_xfmt_proj_against_the_float64_product(fmt, M, N, K):
     rng = np.random.default_rng(M + N + K)
     t = (rng.standard_normal((M, K)) * np.exp(rng.standard_normal((M, K)))).astype(np.float32)
@@ -87,7 +94,7 @@ def test_xfmt_proj_rejects_bad_arguments():
     codes = torch.zeros((4, 64), dtype=torch.uint8, device="cuda:0")
     Wb = torch.zeros((8, 64), dtype=torch.int16, device="cuda:0")
     out = torch.zeros((4, 8), dtype=torch.int8, device="cuda:0")
-    for kw in (dict(fmt=7), dict(N=6), dict(K=40), dict(N=324)):
+    for kw in (dict(fmt=7), dict(N=6), dict(K=48), dict(N=324)):
         a = dict(fmt=Q.XFMT_LOG2, N=8, K=64)
         a.update(kw)
         with pytest.raises(Q.QuambaError):
