@@ -37,3 +37,4 @@ from .mamba_had import (calibrate_hadx, q_prefill_hadx, q_decode_hadx,  # noqa: 
 from .x_asym import calibrate_xasym, q_prefill_xasym, q_decode_xasym, quantize_asym  # noqa: F401
 from .x_formats import (calibrate_xfmt, q_prefill_xfmt, q_decode_xfmt, encode_e4m3, decode_e4m3,  # noqa: F401
                         encode_log2, decode_log2)
+from .x_dynamic import q_prefill_xdyn, q_decode_xdyn, dynamic_scale, dynamic_multipliers  # noqa: F401
