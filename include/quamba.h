@@ -283,6 +283,28 @@ int quamba_xfmt_proj(int format, const uint8_t *x_code, int M, int N, int K, con
                      const float *m /* host, 3 */, int8_t *out_q, float *acc_f32, void *ws, size_t ws_bytes,
                      void *stream);
 
+/* ---- Dynamic 8-bit quantization of the scan input x (Appendix K, row "Dynamic / MinMax Sym."): the scale
+ * of x is not calibrated but taken from the values of the call (all sequences and tokens it processes):
+ *   x16 = fp16(SiLU(conv)),  s = max|x16| / 127 (1 if that is 0),  x_q = clamp(rne(fp32(x16) * (1 / s)))
+ *   x_proj outputs clamp(rne(acc * m)), m = (s * s_Wx) / s_out;  x = s x_q inside the scan
+ * every division and product a single correctly rounded fp32 operation, formed on the device by each reader
+ * from one word holding max|x16|: no host round trip, and the whole step stays a fixed launch sequence.
+ * The appendix's point is the price: three small kernels more than the static path (maximum, quantization,
+ * requantization of the x_proj sums) and the conv output kept in half precision between them.
+ * qw / sc come from quamba_calibrate (its s_x is not used).  s_x_out (device, one float, may be NULL)
+ * receives the scale the call used, x16_out (device [Bt*L, d_inner] fp16, may be NULL) the half-precision
+ * x; taps as for quamba_mixer_prefill (acc_x: the raw x_proj sums).  ws: quamba_xdyn_workspace_bytes.
+ * d_inner must be a multiple of 8. */
+size_t quamba_xdyn_workspace_bytes(const quamba_dims *dims, int batch, int L);
+int quamba_mixer_prefill_xdyn(const quamba_dims *dims, const quamba_qweights *qw, const quamba_scales *sc,
+                              const quamba_half *u, int Bt, int L, quamba_half *out, float *ssm_state,
+                              quamba_half *conv_state, const quamba_taps *taps, float *s_x_out, quamba_half *x16_out,
+                              void *ws, size_t ws_bytes, void *stream);
+int quamba_mixer_decode_xdyn(const quamba_dims *dims, const quamba_qweights *qw, const quamba_scales *sc,
+                             const quamba_half *u, int Bt, quamba_half *out, float *ssm_state, quamba_half *conv_state,
+                             const quamba_taps *taps, float *s_x_out, quamba_half *x16_out, void *ws, size_t ws_bytes,
+                             void *stream);
+
 /* The unquantized mixer (Section 3.1: in_proj, causal conv + SiLU, selection, selective scan,
  * gate, out_proj) in fp32 from the fp32 master weights, each of the nb sequences of length L from
  * an empty history: u [nb, L, Dm] fp16 in, out [nb * L, Dm] fp32.  It is what calibration observes

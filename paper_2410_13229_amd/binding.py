@@ -26,6 +26,7 @@ __all__ = [
     "quamba_mixer_decode_xasym",
     "XFmt", "XFMT_FIELDS", "XFMT_E4M3", "XFMT_LOG2", "make_xfmt", "xfmt_to_dict", "quamba_calibrate_xfmt",
     "quamba_mixer_prefill_xfmt", "quamba_mixer_decode_xfmt", "quamba_x_encode", "quamba_xfmt_proj",
+    "quamba_xdyn_workspace_bytes", "quamba_mixer_prefill_xdyn", "quamba_mixer_decode_xdyn",
 ]
 
 X_PERCENTILE, X_MSE_CLIP = 0, 1
@@ -321,6 +322,12 @@ def lib():
     for name in ("quamba_calibrate_xfmt", "quamba_mixer_prefill_xfmt", "quamba_mixer_decode_xfmt", "quamba_x_encode",
                  "quamba_xfmt_proj"):
         getattr(L, name).restype = C.c_int
+    L.quamba_xdyn_workspace_bytes.restype = sz
+    L.quamba_xdyn_workspace_bytes.argtypes = [P(Dims), i, i]
+    L.quamba_mixer_prefill_xdyn.argtypes = [P(Dims), P(QWeights), P(Scales), vp, i, i, vp, vp, vp, P(Taps), vp, vp, vp, sz, vp]
+    L.quamba_mixer_decode_xdyn.argtypes = [P(Dims), P(QWeights), P(Scales), vp, i, vp, vp, vp, P(Taps), vp, vp, vp, sz, vp]
+    for name in ("quamba_mixer_prefill_xdyn", "quamba_mixer_decode_xdyn"):
+        getattr(L, name).restype = C.c_int
     L.quamba_mixer_fp32.argtypes = [P(Dims), P(FpWeights), vp, i, i, vp, vp, sz, vp]
     for name in ("quamba_calibrate_x_rule", "quamba_clip_search", "quamba_mixer_fp32"):
         getattr(L, name).restype = C.c_int
@@ -464,6 +471,24 @@ def quamba_mixer_decode_xfmt(dims, qw, sc, xf, u, Bt, out, ssm_state, conv_state
                                           C.byref(scales_from_dict(sc)), C.byref(xf), _ptr(u), Bt, _ptr(out),
                                           _ptr(ssm_state), _ptr(conv_state), _taps(taps), _ptr(ws), _nbytes(ws),
                                           _stream(stream)))
+
+
+def quamba_xdyn_workspace_bytes(dims, batch, L) -> int:
+    return int(lib().quamba_xdyn_workspace_bytes(C.byref(_dims(dims)), batch, L))
+
+
+def quamba_mixer_prefill_xdyn(dims, qw, sc, u, Bt, L, out, ssm_state, conv_state, taps, s_x_out, x16_out, ws, stream=None):
+    _check(lib().quamba_mixer_prefill_xdyn(C.byref(_dims(dims)), C.byref(_struct_of_ptrs(QWeights, qw)),
+                                           C.byref(scales_from_dict(sc)), _ptr(u), Bt, L, _ptr(out), _ptr(ssm_state),
+                                           _ptr(conv_state), _taps(taps), _ptr(s_x_out), _ptr(x16_out), _ptr(ws),
+                                           _nbytes(ws), _stream(stream)))
+
+
+def quamba_mixer_decode_xdyn(dims, qw, sc, u, Bt, out, ssm_state, conv_state, taps, s_x_out, x16_out, ws, stream=None):
+    _check(lib().quamba_mixer_decode_xdyn(C.byref(_dims(dims)), C.byref(_struct_of_ptrs(QWeights, qw)),
+                                          C.byref(scales_from_dict(sc)), _ptr(u), Bt, _ptr(out), _ptr(ssm_state),
+                                          _ptr(conv_state), _taps(taps), _ptr(s_x_out), _ptr(x16_out), _ptr(ws),
+                                          _nbytes(ws), _stream(stream)))
 
 
 def quamba_x_encode(fmt, v, n, inv_s, codes, stream=None):

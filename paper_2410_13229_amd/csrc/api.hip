@@ -57,11 +57,12 @@ int check_dims(const quamba_dims *d) {
 
 // Workspace carving, shared by the size query and the launches.
 struct Plan {
-  size_t u_q, xz_q, x_q, dbc_q, dt_q, g16, gH_q, scan, gemm, gemm_bytes, x16, total;
+  size_t u_q, xz_q, x_q, dbc_q, dt_q, g16, gH_q, scan, gemm, gemm_bytes, x16, acc_x, slot, total;
 };
 
 // hadx: the Appendix H comparison variant also keeps the scan input in half precision
-Plan make_plan(const quamba_dims *d, int Bt, int L, bool hadx = false) {
+// dyn: the dynamic-scale variant of Appendix K also keeps x in half precision, the raw x_proj sums and one word for max|x|
+Plan make_plan(const quamba_dims *d, int Bt, int L, bool hadx = false, bool dyn = false) {
   const size_t M = (size_t)Bt * L;
   const size_t nx = d->dt_rank + 2 * d->d_state;
   Plan p{};
@@ -83,7 +84,9 @@ Plan make_plan(const quamba_dims *d, int Bt, int L, bool hadx = false) {
   const size_t widest = M <= 64 ? (size_t)2 * d->d_inner : nx;
   p.gemm_bytes = gemm_workspace_bytes((int)M, (int)widest);
   p.gemm = take(p.gemm_bytes);
-  p.x16 = take(hadx ? M * d->d_inner * sizeof(__half) : 0);
+  p.x16 = take((hadx || dyn) ? M * d->d_inner * sizeof(__half) : 0);
+  p.acc_x = take(dyn ? M * nx * sizeof(int32_t) : 0);
+  p.slot = take(dyn ? 256 : 0);
   p.total = off;
   return p;
 }
@@ -115,6 +118,12 @@ int tap_copy(void *dst, const void *src, size_t bytes, hipStream_t st) {
   return QUAMBA_OK;
 }
 
+// The dynamic-scale variant of Appendix K: where the caller wants the call's scale and the half-precision x (both optional).
+struct DynX {
+  float *s_x_out;
+  __half *x16_out;
+};
+
 // Steps shared by prefill (L >= 1, fresh conv history) and decode (L == 1, carried state).
 // `norm` (generation with at most 4 sequences only): the block input is not given but formed inside
 // the first kernel from the previous block's output and the residual stream.
@@ -122,7 +131,7 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
               const int8_t *u_q_in, int Bt, int L, bool decode, __half *out, float *ssm_state,
               __half *conv_state, const quamba_taps *taps, void *ws, size_t ws_bytes, hipStream_t st,
               const NormIn *norm = nullptr, const quamba_hadx *hx = nullptr, const quamba_hadx_taps *hx_taps = nullptr,
-              const quamba_xasym *xa = nullptr, const quamba_xfmt *xf = nullptr) {
+              const quamba_xasym *xa = nullptr, const quamba_xfmt *xf = nullptr, const DynX *dyn = nullptr) {
   QUAMBA_TRY(check_dims(d));
   QUAMBA_TRY(check_q(qw, sc));
   if ((!u && !u_q_in && !norm) || !out) return fail(QUAMBA_EINVAL, "input or output pointer is NULL");
@@ -134,7 +143,11 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
     return fail(QUAMBA_EINVAL, "ssm_state must be 16-byte aligned, conv_state 8-byte");
   if (xa && (!xa->col_bias || !aligned(xa->col_bias, 16))) return fail(QUAMBA_EINVAL, "variant: col_bias is NULL or unaligned");
   if ((hx || xa) && norm) return fail(QUAMBA_EINVAL, "variant: the fused block input is not built for it");
-  if ((hx != nullptr) + (xa != nullptr) + (xf != nullptr) > 1) return fail(QUAMBA_EINVAL, "the x variants exclude each other");
+  if ((hx != nullptr) + (xa != nullptr) + (xf != nullptr) + (dyn != nullptr) > 1)
+    return fail(QUAMBA_EINVAL, "the x variants exclude each other");
+  if (dyn && norm) return fail(QUAMBA_EINVAL, "variant: the fused block input is not built for it");
+  if (dyn && (d->d_inner % 8 != 0 || (d->dt_rank + 2 * d->d_state) % 4 != 0 || d->dt_rank % 4 != 0 || d->d_state % 4 != 0))
+    return fail(QUAMBA_EUNSUPPORTED, "variant: d_inner must be a multiple of 8, dt_rank and d_state multiples of 4");
   if (xf && norm) return fail(QUAMBA_EINVAL, "variant: the fused block input is not built for it");
   if (xf && (xf->format != QUAMBA_XFMT_E4M3 && xf->format != QUAMBA_XFMT_LOG2))
     return fail(QUAMBA_EINVAL, "variant: unknown x format %d", xf->format);
@@ -147,7 +160,7 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
   const float s_x = xa ? xa->s_x : (xf ? xf->s_x : sc->s_x), inv_s_x = xa ? xa->inv_s_x : (xf ? xf->inv_s_x : sc->inv_s_x);
   const int x_format = xf ? xf->format : 0;
   const int x_zp = xa ? xa->zero_point : 0;
-  const Plan p = make_plan(d, Bt, L, hx != nullptr);
+  const Plan p = make_plan(d, Bt, L, hx != nullptr, dyn != nullptr);
   if (!ws || ws_bytes < p.total) return fail(QUAMBA_EWORKSPACE, "workspace %zu < %zu", ws_bytes, p.total);
   if (!aligned(ws, 256) || !aligned(out, 8) || (u && !aligned(u, 16)) || (u_q_in && !aligned(u_q_in, 16)))
     return fail(QUAMBA_EINVAL, "workspace must be 256-byte aligned, u 16-byte, out 8-byte");
@@ -162,14 +175,16 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
   int8_t *dt_q = reinterpret_cast<int8_t *>(base + p.dt_q);
   __half *g16 = reinterpret_cast<__half *>(base + p.g16);
   int8_t *gH_q = reinterpret_cast<int8_t *>(base + p.gH_q);
-  __half *x16 = hx ? reinterpret_cast<__half *>(base + p.x16) : nullptr;
+  __half *x16 = (hx || dyn) ? reinterpret_cast<__half *>(base + p.x16) : nullptr;
+  unsigned *slot = dyn ? reinterpret_cast<unsigned *>(base + p.slot) : nullptr;
+  int32_t *acc_x = dyn ? reinterpret_cast<int32_t *>(base + p.acc_x) : nullptr;
   const quamba_hadx_taps hnone{};
   const quamba_hadx_taps &ht = hx_taps ? *hx_taps : hnone;
   const quamba_taps none{};
   const quamba_taps &t = taps ? *taps : none;
 
   // Generation with a handful of sequences: [norm +] in_proj + conv step in one streaming kernel.
-  const bool few = decode && M <= 4 && Dm <= 8192 && g_fuse_decode && !hx && !xa && !xf;
+  const bool few = decode && M <= 4 && Dm <= 8192 && g_fuse_decode && !hx && !xa && !xf && !dyn;
   // quantize the block input (Eq. 2)
   const int8_t *uq = u_q_in;
   if (!uq && !norm) {
@@ -194,7 +209,7 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
   } else {
     // in_proj: columns [0, Di) -> x_pre, [Di, 2Di) -> z
     // (generation: where the GEMM's epilogue can carry it, the conv step rides along: a kernel less)
-    const bool conv_in_gemm = decode && !hx && !xa && !xf && g_fuse_decode && Di % 4 == 0 &&
+    const bool conv_in_gemm = decode && !hx && !xa && !xf && !dyn && g_fuse_decode && Di % 4 == 0 &&
                               gemm_fuses_conv_step(M, 2 * Di, Dm, base + p.gemm, p.gemm_bytes);
     {
       GemmEpilogue e{xz_q, nullptr, t.acc_in, 2 * Di, Di, 2 * Di, sc->m_in_x, sc->m_in_z, sc->m_in_z};
@@ -212,6 +227,12 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
                                      sc->s_xpre, x_q, conv_state, st, x16, x_zp, x_format));
     }
   }
+  if (dyn) {  // the scale of x from this call's own values, then the codes
+    QUAMBA_TRY(launch_dyn_absmax_f16(x16, (size_t)M * Di, slot, st));
+    QUAMBA_TRY(launch_quantize_f16_dyn(x16, x_q, (size_t)M * Di, slot, st));
+    if (dyn->s_x_out) QUAMBA_TRY(launch_dyn_export(slot, dyn->s_x_out, st));
+    QUAMBA_TRY(tap_copy(dyn->x16_out, x16, (size_t)M * Di * sizeof(__half), st));
+  }
   if (hx) {  // forward Hadamard & quantize: x_q now holds the codes of H_n x
     QUAMBA_TRY(tap_copy(ht.x16, x16, (size_t)M * Di * sizeof(__half), st));
     QUAMBA_TRY(launch_hadamard_quant(x16, M, Di, hx->inv_s_xH, x_q, nullptr, st));
@@ -223,6 +244,12 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
     QUAMBA_TRY(launch_xfmt_proj(xf->format, reinterpret_cast<const uint8_t *>(x_q), M, NX, Di, xf->W_x_bf16, R, R + N,
                                 xf->m_x_dt, xf->m_x_B, xf->m_x_C, dbc_q, reinterpret_cast<float *>(t.acc_x),
                                 base + p.gemm, p.gemm_bytes, st));
+    QUAMBA_TRY(tap_copy(t.dbc_q, dbc_q, (size_t)M * NX, st));
+  } else if (dyn) {  // raw sums, then the requantization with multipliers formed on the device from the call's scale
+    GemmEpilogue e{nullptr, nullptr, acc_x, NX, R, R + N, 1.f, 1.f, 1.f};
+    QUAMBA_TRY(launch_gemm_i8(x_q, Di, qw->W_x, Di, M, NX, Di, e, base + p.gemm, p.gemm_bytes, st));
+    QUAMBA_TRY(launch_requant_dyn(acc_x, dbc_q, M, NX, R, R + N, slot, sc->s_Wx, sc->s_dtl, sc->s_B, sc->s_C, st));
+    QUAMBA_TRY(tap_copy(t.acc_x, acc_x, (size_t)M * NX * sizeof(int32_t), st));
     QUAMBA_TRY(tap_copy(t.dbc_q, dbc_q, (size_t)M * NX, st));
   } else {
     GemmEpilogue e{dbc_q, nullptr, t.acc_x, NX, R, R + N, hx ? hx->m_xh_dt : (xa ? xa->m_x_dt : sc->m_x_dt),
@@ -255,8 +282,9 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
     a.s_x = s_x; a.x_zero_point = x_zp; a.s_dt = sc->s_dt; a.s_z = sc->s_z; a.s_B = sc->s_B; a.s_C = sc->s_C;
     a.s_A = sc->s_A; a.s_D = sc->s_D;
     a.Bt = Bt; a.L = L; a.Di = Di; a.g16 = g16; a.y_f32 = t.y_f32; a.ssm_state = ssm_state;
-    a.x_f16 = x16;
+    a.x_f16 = dyn ? nullptr : x16;
     a.x_format = x_format;
+    a.s_x_slot = slot;
     if (fuse_dt) {  // decode writes the dt codes only when they are asked for as a tap
       a.dtlow_q = dbc_q; a.lddl = NX; a.W_dt = qw->W_dt; a.R = R; a.m_dt = sc->m_dt;
       a.dt_out = (decode && !t.dt_q) ? nullptr : dt_q;
@@ -653,6 +681,31 @@ int quamba_xfmt_proj(int format, const uint8_t *x_code, int M, int N, int K, con
   if (e0 < 0 || e1 < e0 || e1 > N) return fail(QUAMBA_EINVAL, "xfmt_proj: column ranges e0=%d e1=%d N=%d", e0, e1, N);
   return launch_xfmt_proj(format, x_code, M, N, K, W_bf16, e0, e1, m[0], m[1], m[2], out_q, acc_f32, ws, ws_bytes,
                           as_stream(stream));
+}
+
+size_t quamba_xdyn_workspace_bytes(const quamba_dims *dims, int batch, int L) {
+  if (check_dims(dims) != QUAMBA_OK || batch < 1 || L < 1) return 0;
+  return make_plan(dims, batch, L, false, true).total;
+}
+
+int quamba_mixer_prefill_xdyn(const quamba_dims *dims, const quamba_qweights *qw, const quamba_scales *sc,
+                              const quamba_half *u, int Bt, int L, quamba_half *out, float *ssm_state,
+                              quamba_half *conv_state, const quamba_taps *taps, float *s_x_out, quamba_half *x16_out,
+                              void *ws, size_t ws_bytes, void *stream) {
+  const DynX dyn{s_x_out, reinterpret_cast<__half *>(x16_out)};
+  return run_mixer(dims, qw, sc, reinterpret_cast<const __half *>(u), nullptr, Bt, L, false, reinterpret_cast<__half *>(out),
+                   ssm_state, reinterpret_cast<__half *>(conv_state), taps, ws, ws_bytes, as_stream(stream), nullptr,
+                   nullptr, nullptr, nullptr, nullptr, &dyn);
+}
+
+int quamba_mixer_decode_xdyn(const quamba_dims *dims, const quamba_qweights *qw, const quamba_scales *sc,
+                             const quamba_half *u, int Bt, quamba_half *out, float *ssm_state, quamba_half *conv_state,
+                             const quamba_taps *taps, float *s_x_out, quamba_half *x16_out, void *ws, size_t ws_bytes,
+                             void *stream) {
+  const DynX dyn{s_x_out, reinterpret_cast<__half *>(x16_out)};
+  return run_mixer(dims, qw, sc, reinterpret_cast<const __half *>(u), nullptr, Bt, 1, true, reinterpret_cast<__half *>(out),
+                   ssm_state, reinterpret_cast<__half *>(conv_state), taps, ws, ws_bytes, as_stream(stream), nullptr,
+                   nullptr, nullptr, nullptr, nullptr, &dyn);
 }
 
 size_t quamba_hadx_workspace_bytes(const quamba_dims *dims, int batch, int L) {

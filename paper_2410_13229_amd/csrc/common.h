@@ -93,6 +93,13 @@ int launch_xfmt_proj(int format, const uint8_t *x_code, int M, int N, int K, con
 int launch_x_encode(int format, const float *v, size_t n, float inv_s, uint8_t *codes, hipStream_t st);
 int launch_i8_to_bf16(const int8_t *q, int N, int K, uint16_t *out, hipStream_t st);
 
+// per-call scale of the scan input: *slot = bits of max|x16|; readers derive the scale from it
+int launch_dyn_absmax_f16(const __half *x, size_t n, unsigned *slot, hipStream_t st);
+int launch_quantize_f16_dyn(const __half *x, int8_t *q, size_t n, const unsigned *slot, hipStream_t st);
+int launch_requant_dyn(const int32_t *acc, int8_t *out, int M, int N, int e0, int e1, const unsigned *slot, float s_W,
+                       float so0, float so1, float so2, hipStream_t st);
+int launch_dyn_export(const unsigned *slot, float *out, hipStream_t st);
+
 int launch_add_rmsnorm_quant(const __half *x_out, __half *res, const __half *weight, float eps,
                              float inv_s, int8_t *u_q, int M, int Dm, hipStream_t st);
 
@@ -118,6 +125,8 @@ struct ScanArgs {
   int x_zero_point;
   // QUAMBA_XFMT_E4M3 / QUAMBA_XFMT_LOG2: x_q holds one-byte codes of that format, x = s_x * value(code); 0 = the grid above
   int x_format;
+  // optional: the scale of x is not s_x but derived from this device word (bits of the call's max|x|)
+  const unsigned *s_x_slot;
 };
 
 size_t scan_workspace_bytes(int Bt, int L, int Di);

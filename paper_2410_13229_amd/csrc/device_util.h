@@ -152,6 +152,19 @@ __device__ __forceinline__ float decode_log2(unsigned c) {
   return __uint_as_float(bits | ((c & 0x80u) << 24));
 }
 
+// ---- per-call scale of the scan input (Appendix K, dynamic row).  One device word holds the bits of
+// max|x| of the call; every reader derives what it needs from it with the same correctly rounded
+// operations, so all of them (and the CPU check) agree bit for bit:
+//   s = max / 127 (1 if max is 0),  1 / s,  multiplier = (s * s_W) / s_out
+__device__ __forceinline__ float dyn_scale(const unsigned *slot) {
+  const float mx = __uint_as_float(*slot);
+  return mx > 0.f ? __fdiv_rn(mx, 127.f) : 1.f;
+}
+__device__ __forceinline__ float dyn_inv_scale(const unsigned *slot) { return __fdiv_rn(1.f, dyn_scale(slot)); }
+__device__ __forceinline__ float dyn_multiplier(const unsigned *slot, float s_W, float s_out) {
+  return __fdiv_rn(__fmul_rn(dyn_scale(slot), s_W), s_out);
+}
+
 // four floats -> four fp16 in one 8-byte word
 __device__ __forceinline__ uint2 pack_f16x4(float v0, float v1, float v2, float v3) {
   union {

@@ -3,6 +3,8 @@
 // convolution"), and the fused residual add + RMSNorm + quantization (Section 4.3 "Fused
 // RMSNorm").  Every kernel reads and writes each byte once, with 4- to 16-byte accesses per
 // lane that are contiguous across the wavefront.
+#include <algorithm>
+
 #include "common.h"
 #include "device_util.h"
 
@@ -231,7 +233,108 @@ __global__ __launch_bounds__(256) void add_rmsnorm_quant_kernel(const __half *__
   }
 }
 
+// ------------------------------------------------------------------ per-call scale of x (Appendix K, dynamic row)
+__global__ __launch_bounds__(64) void dyn_reset_kernel(unsigned *slot) {
+  if (threadIdx.x == 0) *slot = 0u;
+}
+
+// max|x| over n halves -> *slot (bits of a non-negative float order like unsigned integers)
+__global__ __launch_bounds__(256) void absmax_f16_kernel(const __half *__restrict__ x, size_t n, unsigned *__restrict__ slot) {
+  float m = 0.f;
+  const size_t stride = (size_t)gridDim.x * 256 * 8;
+  for (size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 8; i < n; i += stride) {
+    if (i + 8 <= n) {
+      union {
+        uint4 u;
+        __half h[8];
+      } v;
+      v.u = *reinterpret_cast<const uint4 *>(x + i);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) m = fmaxf(m, fabsf(__half2float(v.h[e])));
+    } else {
+      for (size_t j = i; j < n; ++j) m = fmaxf(m, fabsf(__half2float(x[j])));
+    }
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+  __shared__ float part[4];
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) atomicMax(slot, __float_as_uint(fmaxf(fmaxf(part[0], part[1]), fmaxf(part[2], part[3]))));
+}
+
+// x_q = clamp(rne(fp32(x16) * (1 / s))) with the call's scale
+__global__ __launch_bounds__(256) void quantize_f16_dyn_kernel(const __half *__restrict__ x, int8_t *__restrict__ q, size_t n,
+                                                               const unsigned *__restrict__ slot) {
+  const float inv_s = dyn_inv_scale(slot);
+  const size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 8;
+  if (i >= n) return;
+  if (i + 8 <= n) {
+    union {
+      uint4 u;
+      __half h[8];
+    } in;
+    in.u = *reinterpret_cast<const uint4 *>(x + i);
+    float v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = __half2float(in.h[e]) * inv_s;
+    *reinterpret_cast<uint2 *>(q + i) = make_uint2(pack_q8x4(v[0], v[1], v[2], v[3]), pack_q8x4(v[4], v[5], v[6], v[7]));
+  } else {
+    for (size_t j = i; j < n; ++j) q[j] = static_cast<int8_t>(q8(__half2float(x[j]) * inv_s));
+  }
+}
+
+// x_proj sums [M, N] int32 -> int8 codes, the multipliers formed from the call's scale:
+// columns [0, e0) (s s_W) / so0, [e0, e1) (s s_W) / so1, [e1, N) (s s_W) / so2
+__global__ __launch_bounds__(256) void requant_dyn_kernel(const int32_t *__restrict__ acc, int8_t *__restrict__ out, size_t groups,
+                                                          int N, int e0, int e1, const unsigned *__restrict__ slot, float s_W,
+                                                          float so0, float so1, float so2) {
+  const size_t g = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (g >= groups) return;
+  const int gn = static_cast<int>(g % (N / 4)) * 4;
+  const float m = dyn_multiplier(slot, s_W, gn < e0 ? so0 : (gn < e1 ? so1 : so2));
+  const v4i a = *reinterpret_cast<const v4i *>(acc + g * 4);
+  const int r[4] = {a[0], a[1], a[2], a[3]};
+  *reinterpret_cast<unsigned *>(out + g * 4) = requant_pack4(r, m);
+}
+
+// *out = the scale the call used (for callers that want to see it)
+__global__ __launch_bounds__(64) void dyn_export_kernel(const unsigned *slot, float *out) {
+  if (threadIdx.x == 0) *out = dyn_scale(slot);
+}
+
 }  // namespace
+
+int launch_dyn_absmax_f16(const __half *x, size_t n, unsigned *slot, hipStream_t st) {
+  hipLaunchKernelGGL(dyn_reset_kernel, dim3(1), dim3(64), 0, st, slot);
+  const size_t blocks = std::min<size_t>((n + 2047) / 2048, 1024);
+  hipLaunchKernelGGL(absmax_f16_kernel, dim3((unsigned)(blocks ? blocks : 1)), dim3(256), 0, st, x, n, slot);
+  QUAMBA_LAUNCH_CHECK();
+  return QUAMBA_OK;
+}
+
+int launch_quantize_f16_dyn(const __half *x, int8_t *q, size_t n, const unsigned *slot, hipStream_t st) {
+  if (n == 0) return QUAMBA_OK;
+  hipLaunchKernelGGL(quantize_f16_dyn_kernel, dim3((unsigned)((n + 2047) / 2048)), dim3(256), 0, st, x, q, n, slot);
+  QUAMBA_LAUNCH_CHECK();
+  return QUAMBA_OK;
+}
+
+int launch_requant_dyn(const int32_t *acc, int8_t *out, int M, int N, int e0, int e1, const unsigned *slot, float s_W,
+                       float so0, float so1, float so2, hipStream_t st) {
+  const size_t groups = (size_t)M * (N / 4);
+  if (groups == 0) return QUAMBA_OK;
+  hipLaunchKernelGGL(requant_dyn_kernel, dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, st, acc, out, groups, N, e0, e1,
+                     slot, s_W, so0, so1, so2);
+  QUAMBA_LAUNCH_CHECK();
+  return QUAMBA_OK;
+}
+
+int launch_dyn_export(const unsigned *slot, float *out, hipStream_t st) {
+  hipLaunchKernelGGL(dyn_export_kernel, dim3(1), dim3(64), 0, st, slot, out);
+  QUAMBA_LAUNCH_CHECK();
+  return QUAMBA_OK;
+}
 
 int launch_quantize_f16(const __half *x, int8_t *q, size_t n, float inv_s, hipStream_t st) {
   if (n == 0) return QUAMBA_OK;

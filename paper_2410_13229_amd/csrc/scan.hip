@@ -71,18 +71,26 @@ struct Dev {
   int8_t *dt_out;
   const __half *x_f16;  // scan input in half precision instead of s_x * x_q (comparison variant)
   float x_off;          // -s_x * zero point of an asymmetric x grid: x = s_x x_q + x_off (0 = symmetric)
+  const unsigned *s_x_slot;  // bits of the call's max|x| when the scale of x is dynamic
 };
 
 // How the scan reads x: int8 codes on a uniform grid (s_x x_q + x_off), half precision values (the
 // Appendix H comparison variant), or one-byte codes of a non-uniform format (Appendix K).
-enum XMode { X_I8 = 0, X_F16 = 1, X_E4M3 = 2, X_LOG2 = 3 };
-// raw: the sign-extended code byte, or the 16 bits of the half
+// X_I8DYN: the uniform grid with a scale derived in the kernel from the call's max|x| (Appendix K, dynamic row).
+enum XMode { X_I8 = 0, X_F16 = 1, X_E4M3 = 2, X_LOG2 = 3, X_I8DYN = 4 };
 template <int XM>
-__device__ __forceinline__ float x_value(const Dev &p, int raw) {
+__device__ __forceinline__ float x_scale(const Dev &p) {
+  if constexpr (XM == X_I8DYN) return dyn_scale(p.s_x_slot);
+  else return p.s_x;
+}
+// raw: the sign-extended code byte, or the 16 bits of the half; sx: x_scale<XM>(p)
+template <int XM>
+__device__ __forceinline__ float x_value(const Dev &p, int raw, float sx) {
   if constexpr (XM == X_F16) return __half2float(__ushort_as_half(static_cast<unsigned short>(raw)));
-  else if constexpr (XM == X_E4M3) return p.s_x * decode_e4m3(static_cast<unsigned>(raw) & 0xffu);
-  else if constexpr (XM == X_LOG2) return p.s_x * decode_log2(static_cast<unsigned>(raw) & 0xffu);
-  else return __builtin_fmaf(p.s_x, static_cast<float>(raw), p.x_off);
+  else if constexpr (XM == X_E4M3) return sx * decode_e4m3(static_cast<unsigned>(raw) & 0xffu);
+  else if constexpr (XM == X_LOG2) return sx * decode_log2(static_cast<unsigned>(raw) & 0xffu);
+  else if constexpr (XM == X_I8DYN) return sx * static_cast<float>(raw);
+  else return __builtin_fmaf(sx, static_cast<float>(raw), p.x_off);
 }
 
 // Dequantize B (and C) of tokens [row0, row0+cnt) into LDS as fp32 [TB][16].
@@ -141,6 +149,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_chunk_kernel(Dev p) {
   }
   const float bias = p.dt_bias[dd];
   const float Dv = OUTPUT ? p.s_D * static_cast<float>(p.D_q[dd]) : 0.f;
+  const float sx = x_scale<XM>(p);
   float sdt = 0.f;
   const size_t seq0 = (size_t)b * p.L;
   // x / dt / z / g of this chunk behind buffer descriptors: row offsets are scalar, the lane adds
@@ -224,7 +233,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_chunk_kernel(Dev p) {
   };
   auto token = [&](const Regs &r, int i, int t, int tl) {  // t: token index, tl: index inside the LDS block
       {
-        const float xv = x_value<XM>(p, r.x[i]);
+        const float xv = x_value<XM>(p, r.x[i], sx);
         const int dtq = FUSE_DT ? static_cast<int>(sDT[wave][tl + i][lane]) : r.dt[i];
         const float dt = softplus_f(p.s_dt * static_cast<float>(dtq) + bias);
         const float u = dt * xv;
@@ -347,7 +356,7 @@ __global__ __launch_bounds__(256) void scan_step_kernel(Dev p, float *__restrict
   // (a compile-time choice: a run-time test of the pointer would put this load behind a branch and
   // cost the step one more memory round trip)
   const float xv = x_value<XM>(p, XM == X_F16 ? static_cast<int>(__half_as_ushort(p.x_f16[(size_t)b * p.Di + d]))
-                                               : static_cast<int>(p.x_q[(size_t)b * p.Di + d]));
+                                               : static_cast<int>(p.x_q[(size_t)b * p.Di + d]), x_scale<XM>(p));
   int dtq;
   if (FUSE_DT) {
     const int8_t *wrow = p.W_dt + (size_t)d * p.R;
@@ -417,6 +426,7 @@ __global__ __launch_bounds__(256) void scan_step_batch_kernel(Dev p, float *__re
   const unsigned aw = *reinterpret_cast<const unsigned *>(p.A_q + (size_t)dd * NS + 4 * q);
   const float bias = p.dt_bias[dd];
   const float Dv = p.s_D * static_cast<float>(p.D_q[dd]);
+  const float sx = x_scale<XM>(p);
   float a2[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) a2[j] = static_cast<float>(static_cast<int8_t>(aw >> (8 * j))) * (p.s_A * LOG2E);
@@ -432,7 +442,7 @@ __global__ __launch_bounds__(256) void scan_step_batch_kernel(Dev p, float *__re
     bw[i] = *reinterpret_cast<const unsigned *>(p.B_q + b * p.ldbc + 4 * q);
     cw[i] = *reinterpret_cast<const unsigned *>(p.C_q + b * p.ldbc + 4 * q);
     xv[i] = x_value<XM>(p, XM == X_F16 ? static_cast<int>(__half_as_ushort(p.x_f16[b * p.Di + dd]))
-                                       : static_cast<int>(p.x_q[b * p.Di + dd]));
+                                       : static_cast<int>(p.x_q[b * p.Di + dd]), sx);
     zv[i] = p.s_z * static_cast<float>(p.z_q[b * p.ldz + dd]);
 #pragma unroll
     for (int j = 0; j < NP; ++j) {
@@ -488,6 +498,7 @@ Dev make_dev(const ScanArgs &a) {
   p.dtlow_q = a.dtlow_q; p.W_dt = a.W_dt; p.lddl = a.lddl; p.R = a.R; p.m_dt = a.m_dt; p.dt_out = a.dt_out;
   if (a.dtlow_q && a.dt_out) p.dt_q = a.dt_out;
   p.x_f16 = a.x_f16;
+  p.s_x_slot = a.s_x_slot;
   p.x_off = -a.s_x * static_cast<float>(a.x_zero_point);  // -0.f for the symmetric grid: adds nothing
   return p;
 }
@@ -541,12 +552,13 @@ int launch_scan_prefill(const ScanArgs &a, void *ws, size_t ws_bytes, hipStream_
   p.ssum = reinterpret_cast<float *>(static_cast<char *>(ws) +
                                      align_up((size_t)a.Bt * p.nchunks * a.Di * NS * sizeof(float), 256));
   dim3 grid((a.Di + SCAN_THREADS - 1) / SCAN_THREADS, p.nchunks, a.Bt);
-  const int xm = a.x_f16 ? X_F16 : (a.x_format == QUAMBA_XFMT_E4M3 ? X_E4M3 : (a.x_format == QUAMBA_XFMT_LOG2 ? X_LOG2 : X_I8));
+  const int xm = a.x_f16 ? X_F16 : (a.s_x_slot ? X_I8DYN : (a.x_format == QUAMBA_XFMT_E4M3 ? X_E4M3 : (a.x_format == QUAMBA_XFMT_LOG2 ? X_LOG2 : X_I8)));
 #define QUAMBA_XM_SWITCH(CALL) \
   switch (xm) {                \
     case X_F16: CALL(X_F16); break;   \
     case X_E4M3: CALL(X_E4M3); break; \
     case X_LOG2: CALL(X_LOG2); break; \
+    case X_I8DYN: CALL(X_I8DYN); break; \
     default: CALL(X_I8); break;       \
   }
   if (a.dtlow_q) {
@@ -577,7 +589,7 @@ int launch_scan_prefill(const ScanArgs &a, void *ws, size_t ws_bytes, hipStream_
 int launch_scan_step(const ScanArgs &a, hipStream_t st) {
   Dev p = make_dev(a);
   p.L = 1;
-  const int xm = a.x_f16 ? X_F16 : (a.x_format == QUAMBA_XFMT_E4M3 ? X_E4M3 : (a.x_format == QUAMBA_XFMT_LOG2 ? X_LOG2 : X_I8));
+  const int xm = a.x_f16 ? X_F16 : (a.s_x_slot ? X_I8DYN : (a.x_format == QUAMBA_XFMT_E4M3 ? X_E4M3 : (a.x_format == QUAMBA_XFMT_LOG2 ? X_LOG2 : X_I8)));
   const size_t n = (size_t)a.Bt * a.Di * 4;
   if (a.dtlow_q) {
     if (!a.W_dt || a.R < 16 || a.R % 16 || a.lddl % 16 || a.lddl < a.R || !aligned(a.dtlow_q, 16) || !aligned(a.W_dt, 16))
