@@ -194,6 +194,14 @@ def bench_x_scale_rules(Q, W, torch, np, dev, to_dev, stream):
         run_f()
         formats[name] = {"x_scale": round(xf.s_x, 6), "rel_err": round(rel_err(), 5),
                          "prefill_us": round(timed(run_f) * 1e6, 1)}
+    # the dynamic row of the same appendix: the scale of x from the call's own values (Quamba's calibration otherwise)
+    scd_ = Q.quamba_calibrate(cfg, fw, calib, nb, Lc, 99.999, qd, cws, stream)
+    wsd = torch.empty(Q.quamba_xdyn_workspace_bytes(cfg, 1, L), dtype=torch.uint8, device=dev)
+    s_dyn = torch.zeros(1, dtype=torch.float32, device=dev)
+    run_d = lambda: Q.quamba_mixer_prefill_xdyn(dims, qs, scd_, u, 1, L, out, None, None, None, s_dyn, None, wsd, stream)  # noqa: E731
+    run_d()
+    formats["dynamic_max"] = {"x_scale": round(float(s_dyn.item()), 6), "rel_err": round(rel_err(), 5),
+                              "prefill_us": round(timed(run_d) * 1e6, 1)}
     formats["symmetric_prefill_us"] = asym["symmetric_prefill_us"]
     return {"asymmetric_p99.999": asym, "formats": formats, "workload": "c1 shape, hidden input without outlier channels, 8 rows of the x half of W_in scaled by 8; "
                         "calibrated on a seeded 4x256 batch, error over a fresh 1024-token sequence",
