@@ -307,7 +307,8 @@ __global__ __launch_bounds__(64) void dyn_export_kernel(const unsigned *slot, fl
 
 int launch_dyn_absmax_f16(const __half *x, size_t n, unsigned *slot, hipStream_t st) {
   hipLaunchKernelGGL(dyn_reset_kernel, dim3(1), dim3(64), 0, st, slot);
-  const size_t blocks = std::min<size_t>((n + 2047) / 2048, 1024);
+  // (few blocks: every block ends in one atomic on the same word, and those serialise)
+  const size_t blocks = std::min<size_t>((n + 2047) / 2048, 256);
   hipLaunchKernelGGL(absmax_f16_kernel, dim3((unsigned)(blocks ? blocks : 1)), dim3(256), 0, st, x, n, slot);
   QUAMBA_LAUNCH_CHECK();
   return QUAMBA_OK;
