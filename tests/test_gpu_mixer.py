@@ -473,23 +473,31 @@ def test_two_calls_in_flight_on_two_streams():
         assert np.array_equal(host(ssms[i]), alone[i][1])
 
 
-def test_decode_steps_replayed_from_a_hip_graph():
+@pytest.mark.parametrize("path", ["static", "dynamic_x"])
+def test_decode_steps_replayed_from_a_hip_graph(path):
     """The decode call enqueues kernel launches only, so a caller may capture it.  Several replays,
-    with eager work and synchronisations in between, must each reproduce the eager result bit for bit."""
+    with eager work and synchronisations in between, must each reproduce the eager result bit for bit.
+    (dynamic_x: the variant that forms the scale of x on the device; its word for the maximum is cleared
+    by a kernel, so it captures as well.)"""
     cfg = W.tiny_config(name="tg", d_model=64, d_inner=128, dt_rank=16, batch=3, seqlen=1, config_id=89)
     w, qw, sc = oracle_setup(cfg, randomize_bias=True, gain=4.0)
     qd = qweights_to_dev(qw)
     Bt, nsteps = 3, 4
     us = dev(np.stack([W.make_hidden(cfg, batch=Bt, seqlen=1, stream=300 + s)[:, 0] for s in range(nsteps)]))
     ssm0_np, cs0_np = W.make_decode_state(cfg, batch=Bt)
-    ws = workspace(Q.quamba_workspace_bytes(cfg, Bt, 1))
+    dyn = path == "dynamic_x"
+    ws = workspace(Q.quamba_xdyn_workspace_bytes(cfg, Bt, 1) if dyn else Q.quamba_workspace_bytes(cfg, Bt, 1))
     outs = empty((nsteps, Bt, cfg.d_model), torch.float16)
     ssm, cs = dev(ssm0_np), dev(cs0_np)
     qs, scs, dims = Q.make_qweights(qd), Q.scales_from_dict(sc), Q.make_dims(cfg)
 
     def steps():
         for s in range(nsteps):
-            Q.quamba_mixer_decode(dims, qs, scs, us[s], Bt, outs[s], ssm, cs, None, ws, torch.cuda.current_stream())
+            if dyn:
+                Q.quamba_mixer_decode_xdyn(dims, qs, scs, us[s], Bt, outs[s], ssm, cs, None, None, None, ws,
+                                           torch.cuda.current_stream())
+            else:
+                Q.quamba_mixer_decode(dims, qs, scs, us[s], Bt, outs[s], ssm, cs, None, ws, torch.cuda.current_stream())
 
     steps()  # eager reference (also the warm-up that sets kernel attributes outside the capture)
     ref_out, ref_ssm, ref_cs = host(outs).copy(), host(ssm).copy(), host(cs).copy()
