@@ -591,6 +591,7 @@ int quamba_hadamard_quant(const quamba_half *g, int M, int n, float inv_s_y, int
                           void *stream) {
   if (!g || !yH_q) return fail(QUAMBA_EINVAL, "NULL pointer");
   if (M < 0 || n <= 0) return fail(QUAMBA_EINVAL, "hadamard: M=%d n=%d", M, n);
+  if (M == 0) return QUAMBA_OK;
   if (!aligned(g, 16) || !aligned(yH_q, 16) || (yH_f32 && !aligned(yH_f32, 16)))
     return fail(QUAMBA_EINVAL, "hadamard: buffers must be 16-byte aligned");
   return launch_hadamard_quant(reinterpret_cast<const __half *>(g), M, n, inv_s_y, yH_q, yH_f32,
@@ -600,6 +601,7 @@ int quamba_hadamard_quant(const quamba_half *g, int M, int n, float inv_s_y, int
 int quamba_hadamard_inverse(const int8_t *xH_q, int M, int n, float scale, quamba_half *x_hat, void *stream) {
   if (!xH_q || !x_hat) return fail(QUAMBA_EINVAL, "NULL pointer");
   if (M < 0 || n <= 0) return fail(QUAMBA_EINVAL, "hadamard: M=%d n=%d", M, n);
+  if (M == 0) return QUAMBA_OK;
   if (!aligned(xH_q, 16) || !aligned(x_hat, 16)) return fail(QUAMBA_EINVAL, "hadamard: buffers must be 16-byte aligned");
   return launch_hadamard_inverse(xH_q, M, n, scale, reinterpret_cast<__half *>(x_hat), as_stream(stream));
 }

@@ -326,3 +326,27 @@ def test_clip_search_degenerate_and_errors():
             Q.quamba_clip_search(x, bad.get("n", 10), bad.get("bits", 8), bad.get("iters", 4), ws)
     with pytest.raises(Q.QuambaError):
         Q.quamba_clip_search(x, 10, 8, 4, workspace(256))
+
+
+def test_empty_inputs_are_no_ops_and_an_empty_mixer_call_is_a_clear_error():
+    """Zero rows or zero elements: the stage entry points return without touching their outputs;
+    the mixer, whose shapes come from (batch, L), refuses batch or L below 1."""
+    canary = torch.full((64,), 7, dtype=torch.int8, device="cuda:0")
+    half = torch.zeros((64,), dtype=torch.float16, device="cuda:0")
+    Q.quamba_quantize_f16(half, canary, 0, 1.0)
+    Q.quamba_hadamard_quant(half, 0, 64, 1.0, canary, None)
+    Q.quamba_add_rmsnorm_quant(half, half.clone(), half, 1e-5, 1.0, canary, 0, 64)
+    w = torch.zeros((64, 64), dtype=torch.int8, device="cuda:0")
+    Q.quamba_gemm_i8(w, 64, w, 64, 0, 64, 64, 64, 64, [1.0, 1.0, 1.0], canary, None, 64, None, None)
+    Q.quamba_x_encode(Q.XFMT_LOG2, torch.zeros(4, device="cuda:0"), 0, 1.0, canary.view(torch.uint8))
+    assert np.all(host(canary) == 7)
+    cfg = W.tiny_config(name="te", d_model=64, d_inner=128, dt_rank=16, config_id=93)
+    w_, qw, sc = oracle_setup(cfg)
+    from gpu_util import qweights_to_dev
+    qd = qweights_to_dev(qw)
+    out = empty((1, 1, cfg.d_model), torch.float16)
+    ws = workspace(Q.quamba_workspace_bytes(cfg, 1, 1))
+    for Bt, L in ((0, 4), (1, 0)):
+        with pytest.raises(Q.QuambaError):
+            Q.quamba_mixer_prefill(cfg, qd, sc, half, Bt, L, out, None, None, None, ws)
+    assert Q.quamba_workspace_bytes(cfg, 0, 4) == 0
