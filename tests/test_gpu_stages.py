@@ -36,7 +36,25 @@ GEMM_SHAPES = [
     (1100, 14000, 256, 0), (1500, 5408, 128, 0), (4000, 4096, 128, 0),  # the last: 256 x 256 tiles
     # few rows (generation): the streaming kernel without matrix tiles
     (1, 10240, 2560, 0), (4, 2560, 5120, 0), (8, 192, 5120, 0), (3, 5120, 160, 32), (2, 12, 48, 0), (7, 768, 1536, 0),
+    # more than 512 tiles of 64 x 64 with deep K (the 128-byte-slice form), as in the 1024- and 256-token prefills
+    (1024, 2560, 5120, 0), (256, 10240, 2560, 0),
 ]
+
+
+def _random_gemm_shapes(count, seed=2024):
+    """Seeded shapes inside the documented limits (K a multiple of 16, N of 4): every kernel choice has
+    ragged neighbours among them."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(count):
+        M = int(rng.choice([rng.integers(1, 9), rng.integers(9, 80), rng.integers(80, 400)]))
+        N = 4 * int(rng.choice([rng.integers(1, 20), rng.integers(20, 120), rng.integers(120, 360)]))
+        K = 16 * int(rng.choice([rng.integers(1, 8), rng.integers(8, 40), rng.integers(40, 96)]))
+        out.append((M, N, K, int(rng.choice([0, 16, 48]))))
+    return out
+
+
+GEMM_SHAPES += _random_gemm_shapes(28)
 
 
 @pytest.mark.parametrize("M,N,K,pad", GEMM_SHAPES)
