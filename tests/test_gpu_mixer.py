@@ -95,7 +95,10 @@ def end_to_end(r, ref, name):
 
 
 @pytest.mark.parametrize("Bt,L,dm,di,rk", [(2, 37, 64, 128, 16), (1, 5, 96, 192, 16), (3, 130, 160, 320, 32),
-                                            (2, 1, 64, 128, 16)])  # the last: a prefill of one token
+                                            (2, 1, 64, 128, 16),  # a prefill of one token
+                                            # fewer channels than a workgroup, a ragged last chunk, the order-12 factor
+                                            # with a wider dt_rank, five sequences
+                                            (5, 257, 48, 32, 16), (1, 513, 128, 384, 48), (2, 64, 32, 640, 64)])
 def test_prefill_tiny(Bt, L, dm, di, rk):
     cfg = W.tiny_config(name=f"t{di}", d_model=dm, d_inner=di, dt_rank=rk, batch=Bt, seqlen=L, config_id=91 + di)
     w, qw, sc = oracle_setup(cfg, randomize_bias=True, gain=4.0)
