@@ -706,12 +706,15 @@ GemmChoice choose_gemm(int M, int N, int K, const void *ws, size_t ws_bytes) {
   //   10 = 4 with 256 x 256 tiles (eight waves of 64 x 128), for N that 320-wide tiles fit badly
   //   7 = dma 64x32, two K groups of 2 waves, ring of 4: decode-sized M with a wide output gets a
   //       tile per CU without splitting K over the grid (no second kernel)
+  //   11 = dma 64x64, two K groups of 4 waves, 256-byte slices, ring of 3: the same job when K is a
+  //       multiple of 256; half as many workgroups re-read the activation rows (64 x 10240 x 2560:
+  //       7.5 against 8.0 us, 64 x 16384 x 4096: 13.6 against 14.6 us)
   if (M <= g_gemv_max_rows && g_gemm_variant < 0 && (size_t)4 * K <= 64 * 1024) return GemmChoice{true, 0, 1, 0};
   int kind;
   const long tiles_256 = (long)((M + 255) / 256) * ((N + 319) / 320);
   const long tiles_128 = (long)((M + 127) / 128) * ((N + 159) / 160);
   if (M <= 64)
-    kind = k128 ? ((N + 31) / 32 >= 256 ? 7 : 5) : (k64 ? 3 : 0);
+    kind = k128 ? ((N + 31) / 32 >= 256 ? ((K % 256) == 0 ? 11 : 7) : 5) : (k64 ? 3 : 0);
   else if (N <= 512) {
     kind = k128 ? 5 : (k64 ? 3 : 0);
     // A skinny output with about one 64 x 32 tile per CU and a moderately deep K: those tiles with
@@ -748,13 +751,14 @@ GemmChoice choose_gemm(int M, int N, int K, const void *ws, size_t ws_bytes) {
   const long tiles64 = (long)((M + 63) / 64) * ((N + 63) / 64);
   const bool skinny_unsplit = N <= 512 && tiles64 > 256;
   if ((K % 256) == 0 && kind == 5 && M > 64 && !skinny_unsplit && tiles64 <= 512) kind = 9;
-  if (g_gemm_variant >= 0 && g_gemm_variant <= 10 &&
-      (g_gemm_variant < 2 || (g_gemm_variant == 3 && k64) || (g_gemm_variant != 3 && k128)))
+  if (g_gemm_variant >= 0 && g_gemm_variant <= 11 &&
+      (g_gemm_variant < 2 || (g_gemm_variant == 3 && k64) || (g_gemm_variant != 3 && k128)) &&
+      (g_gemm_variant != 11 || (K % 256) == 0))
     kind = g_gemm_variant;
 
   // split K when the output has too few tiles to fill 256 CUs and K is deep
   int splits = 1;
-  const int slice = (kind == 8 || kind == 9) ? 256 : ((kind == 2 || kind >= 4) ? 128 : 64);
+  const int slice = (kind == 8 || kind == 9 || kind == 11) ? 256 : ((kind == 2 || kind >= 4) ? 128 : 64);
   const int nslices = (K + slice - 1) / slice;
   if ((kind == 0 || kind == 3 || kind == 5 || kind == 9) && ws != nullptr) {
     const int tiles = ((M + 63) / 64) * ((N + 63) / 64);
@@ -777,14 +781,14 @@ size_t gemm_workspace_bytes(int M, int N) {
 
 bool gemm_fuses_conv_step(int M, int N, int K, const void *ws, size_t ws_bytes) {
   const GemmChoice c = choose_gemm(M, N, K, ws, ws_bytes);
-  return !c.gemv && (c.kind == 7 || c.splits > 1);
+  return !c.gemv && (c.kind == 7 || c.kind == 11 || c.splits > 1);
 }
 
 int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, int N, int K,
                    const GemmEpilogue &epi, void *ws, size_t ws_bytes, hipStream_t st) {
   const GemmChoice c = choose_gemm(M, N, K, ws, ws_bytes);
   const bool conv = epi.conv.state != nullptr;
-  if (conv && (c.gemv || !(c.kind == 7 || c.splits > 1) || !epi.out_i8 || epi.e0 % 4 != 0))
+  if (conv && (c.gemv || !(c.kind == 7 || c.kind == 11 || c.splits > 1) || !epi.out_i8 || epi.e0 % 4 != 0))
     return fail(QUAMBA_EUNSUPPORTED, "gemm: this shape (M=%d N=%d K=%d) has no epilogue that carries the conv step", M, N, K);
   if (c.gemv) {
     const size_t lds = (size_t)(M <= 1 ? 1 : (M <= 2 ? 2 : 4)) * K;
@@ -811,6 +815,10 @@ int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, i
     case 7:
       rc = conv ? run_dma<64, 32, 2, 1, 4, 128, 2, 2, false, true>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st)
                 : run_dma<64, 32, 2, 1, 4, 128, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st);
+      break;
+    case 11:
+      rc = conv ? run_dma<64, 64, 2, 2, 3, 256, 2, 2, false, true>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st)
+                : run_dma<64, 64, 2, 2, 3, 256, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st);
       break;
     case 8: rc = run_dma<128, 160, 4, 1, 2, 256, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
     case 9: rc = run_dma<64, 64, 2, 2, 2, 256, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
