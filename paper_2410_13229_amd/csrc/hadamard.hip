@@ -203,20 +203,13 @@ __device__ __forceinline__ void radix_pass(float *row, int n, int s) {
   }
 }
 
-// Outputs (any may be null): out = int8 codes of scale * y; out_f32 = y; out_f16 = fp16(scale * y).
-// TR applies H_n^T = H_k^T (x) H_{2^m} (the Sylvester factor is symmetric).
+// One row of n = K 2^LOGM values from global memory through every pass but the last, left in LDS
+// (padded fp32 layout); ends with a barrier.
 template <int K, int LOGM, typename TIn, bool TR>
-__global__ __launch_bounds__(threads_for(K << LOGM)) void hadamard_quant_kernel(const TIn *__restrict__ g, float inv_s,
-                                                            int8_t *__restrict__ out,
-                                                            float *__restrict__ out_f32,
-                                                            __half *__restrict__ out_f16) {
+__device__ __forceinline__ void transform_row(const TIn *__restrict__ src, float *row) {
   static_assert(LOGM >= 4, "the last pass owns the low four index bits");
   constexpr int n = K << LOGM;
   constexpr int HT = threads_for(n);
-  extern __shared__ __attribute__((aligned(16))) float row[];
-  const size_t r = blockIdx.x;
-  const TIn *src = g + r * n;
-
   if constexpr (sizeof(TIn) <= 2 && K > 1 && LOGM >= 5) {
     order_k_load_mfma<K, LOGM, HT, TIn, TR>(src, row);
   } else {
@@ -256,20 +249,39 @@ __global__ __launch_bounds__(threads_for(K << LOGM)) void hadamard_quant_kernel(
   radix_pass<R0, HT>(row, n, LOGM - R0);
   radix_pass<R1, HT>(row, n, LOGM - R0 - R1);
   radix_pass<R2, HT>(row, n, 4);
+}
+
+// last pass of item w: bits [0, 4) of elements [16 w, 16 w + 16)
+__device__ __forceinline__ void last_pass(const float *row, int w, float (&v)[16]) {
+  const float *p = row + pad(w * 16);
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const float4 f = reinterpret_cast<const float4 *>(p)[q];
+    v[4 * q] = f.x;
+    v[4 * q + 1] = f.y;
+    v[4 * q + 2] = f.z;
+    v[4 * q + 3] = f.w;
+  }
+  butterflies<4>(v);
+}
+
+// Outputs (any may be null): out = int8 codes of scale * y; out_f32 = y; out_f16 = fp16(scale * y).
+// TR applies H_n^T = H_k^T (x) H_{2^m} (the Sylvester factor is symmetric).
+template <int K, int LOGM, typename TIn, bool TR>
+__global__ __launch_bounds__(threads_for(K << LOGM)) void hadamard_quant_kernel(const TIn *__restrict__ g, float inv_s,
+                                                            int8_t *__restrict__ out,
+                                                            float *__restrict__ out_f32,
+                                                            __half *__restrict__ out_f16) {
+  constexpr int n = K << LOGM;
+  constexpr int HT = threads_for(n);
+  extern __shared__ __attribute__((aligned(16))) float row[];
+  const size_t r = blockIdx.x;
+  transform_row<K, LOGM, TIn, TR>(g + r * n, row);
 
   // last pass: bits [0, 4), fused with scale / round / clamp / pack
   for (int w = threadIdx.x; w < n / 16; w += HT) {
     float v[16];
-    const float *p = row + pad(w * 16);
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const float4 f = reinterpret_cast<const float4 *>(p)[q];
-      v[4 * q] = f.x;
-      v[4 * q + 1] = f.y;
-      v[4 * q + 2] = f.z;
-      v[4 * q + 3] = f.w;
-    }
-    butterflies<4>(v);
+    last_pass(row, w, v);
     if (out) {
       unsigned pk[4];
 #pragma unroll
@@ -294,6 +306,59 @@ __global__ __launch_bounds__(threads_for(K << LOGM)) void hadamard_quant_kernel(
       dst[0] = o.u[0];
       dst[1] = o.u[1];
     }
+  }
+}
+
+// Generation with one sequence: Hadamard + quantization + out_proj in one launch.  Two launches of a
+// few microseconds each, almost all of it latency, become one: every workgroup owns OC output
+// columns, asks for its pieces of their weight rows first (one 16-byte piece per thread and column:
+// n / 16 threads), transforms the single row itself while they arrive (redundantly: the row is 10 KB
+// and stays in the cache), and multiplies the 16 codes each thread ends up holding with exactly the
+// weight pieces it asked for.  The codes are the stand-alone kernel's bit for bit (same passes, same
+// order); workgroup 0 also stores them.  out[n] = fp16(acc[n] * m_out).
+constexpr int OC = 16;  // output columns per workgroup (8: +2 %, 4: +3 %, 32: +12 % on the 64-block step)
+
+template <int K, int LOGM>
+__global__ __launch_bounds__(threads_for(K << LOGM)) void hadamard_out_proj_kernel(
+    const __half *__restrict__ g, float inv_s, const int8_t *__restrict__ W, int Dm, float m_out,
+    __half *__restrict__ out, int8_t *__restrict__ codes_out) {
+  constexpr int n = K << LOGM;
+  constexpr int HT = threads_for(n);
+  static_assert(HT == n / 16, "one item per thread");
+  extern __shared__ __attribute__((aligned(16))) float row[];
+  __shared__ int red[HT / 64][OC];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n0 = blockIdx.x * OC;
+  v4i wv[OC];
+#pragma unroll
+  for (int j = 0; j < OC; ++j)  // the clamp only bounds the address of a ragged last group
+    wv[j] = *reinterpret_cast<const v4i *>(W + (size_t)min(n0 + j, Dm - 1) * n + (size_t)tid * 16);
+  transform_row<K, LOGM, __half, false>(g, row);
+  float v[16];
+  last_pass(row, tid, v);
+  v4i c;
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+    c[q] = static_cast<int>(pack_q8x4(v[4 * q] * inv_s, v[4 * q + 1] * inv_s, v[4 * q + 2] * inv_s, v[4 * q + 3] * inv_s));
+  if (blockIdx.x == 0 && codes_out) *reinterpret_cast<v4i *>(codes_out + (size_t)tid * 16) = c;
+  int acc[OC];
+#pragma unroll
+  for (int j = 0; j < OC; ++j) {
+    acc[j] = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) acc[j] = __builtin_amdgcn_sdot4(c[e], wv[j][e], acc[j], false);
+    acc[j] = wave_sum(acc[j]);
+  }
+  if (lane == 0) {
+#pragma unroll
+    for (int j = 0; j < OC; ++j) red[wave][j] = acc[j];
+  }
+  __syncthreads();
+  if (tid < OC && n0 + tid < Dm) {
+    int a = 0;
+#pragma unroll
+    for (int w = 0; w < HT / 64; ++w) a += red[w][tid];
+    out[n0 + tid] = __float2half_rn(static_cast<float>(a) * m_out);
   }
 }
 
@@ -386,6 +451,42 @@ int dispatch_k(const TIn *g, int M, int n, float inv_s_y, int8_t *yH_q, float *y
 int launch_hadamard_quant(const __half *g, int M, int n, float inv_s_y, int8_t *yH_q, float *yH_f32,
                           hipStream_t st) {
   return dispatch_k<__half, false>(g, M, n, inv_s_y, yH_q, yH_f32, nullptr, st);
+}
+
+namespace {
+template <int K, int LOGM>
+int run_out_proj(const __half *g, float inv_s, const int8_t *W, int Dm, float m_out, __half *out, int8_t *codes,
+                 hipStream_t st) {
+  constexpr int n = K << LOGM;
+  constexpr size_t lds = (size_t)(n + n / 4) * sizeof(float);
+  static_assert(lds <= 64 * 1024, "fits the default dynamic LDS limit");
+  hipLaunchKernelGGL((hadamard_out_proj_kernel<K, LOGM>), dim3((Dm + OC - 1) / OC), dim3(threads_for(n)), lds, st, g, inv_s,
+                     W, Dm, m_out, out, codes);
+  QUAMBA_LAUNCH_CHECK();
+  return QUAMBA_OK;
+}
+}  // namespace
+
+// orders for which one thread per 16 elements is a whole number of waves and the row fits 64 KB of LDS
+bool hadamard_fuses_out_proj(int n, int Dm) {
+  int k = 0, m = 0;
+  if (Dm < 1 || !hadamard_factor(n, &k, &m)) return false;
+  return (k == 1 && m >= 10 && m <= 13) || (k == 12 && m >= 8 && m <= 10) || (k == 20 && m >= 8 && m <= 9);
+}
+
+// One row: out[0, Dm) = fp16(m_out * W codes(H_n g)), codes as launch_hadamard_quant's (stored to codes if given)
+int launch_hadamard_out_proj(const __half *g, int n, float inv_s_y, const int8_t *W, int Dm, float m_out, __half *out,
+                             int8_t *codes, hipStream_t st) {
+  if (!hadamard_fuses_out_proj(n, Dm)) return fail(QUAMBA_EUNSUPPORTED, "hadamard + out_proj: n=%d Dm=%d", n, Dm);
+  int k = 0, m = 0;
+  hadamard_factor(n, &k, &m);
+#define QUAMBA_CASE(KK, LM) \
+  if (k == KK && m == LM) return run_out_proj<KK, LM>(g, inv_s_y, W, Dm, m_out, out, codes, st);
+  QUAMBA_CASE(1, 10) QUAMBA_CASE(1, 11) QUAMBA_CASE(1, 12) QUAMBA_CASE(1, 13)
+  QUAMBA_CASE(12, 8) QUAMBA_CASE(12, 9) QUAMBA_CASE(12, 10)
+  QUAMBA_CASE(20, 8) QUAMBA_CASE(20, 9)
+#undef QUAMBA_CASE
+  return fail(QUAMBA_EUNSUPPORTED, "hadamard + out_proj: n=%d", n);
 }
 
 // fp32 rows in, fp32 rows out, no quantization (used by calibration)
