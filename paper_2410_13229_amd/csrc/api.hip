@@ -298,9 +298,9 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
     QUAMBA_TRY(tap_copy(t.g16, g16, (size_t)M * Di * sizeof(__half), st));
   }
   // Hadamard transform + quantization (Eq. 3)
-  // (generation with one sequence: both ride in the out_proj launch; same codes, same sums)
-  if (decode && M == 1 && g_fuse_decode && !t.gH_f32 && !t.acc_out && hadamard_fuses_out_proj(Di, Dm)) {
-    QUAMBA_TRY(launch_hadamard_out_proj(g16, Di, sc->inv_s_y, qw->W_outH, Dm, sc->m_out, out, gH_q, st));
+  // (generation with up to three sequences: both ride in the out_proj launch; same codes, same sums)
+  if (decode && M <= 3 && g_fuse_decode && !t.gH_f32 && !t.acc_out && hadamard_fuses_out_proj(Di, Dm)) {
+    QUAMBA_TRY(launch_hadamard_out_proj(g16, M, Di, sc->inv_s_y, qw->W_outH, Dm, sc->m_out, out, gH_q, st));
     QUAMBA_TRY(tap_copy(t.gH_q, gH_q, (size_t)M * Di, st));
     return QUAMBA_OK;
   }

@@ -137,8 +137,8 @@ int launch_hadamard_quant(const __half *g, int M, int n, float inv_s_y, int8_t *
                           hipStream_t st);
 // x_hat = fp16(scale * H_n^T xH_q): the backward transform of the Appendix H comparison variant
 bool hadamard_fuses_out_proj(int n, int Dm);
-int launch_hadamard_out_proj(const __half *g, int n, float inv_s_y, const int8_t *W, int Dm, float m_out, __half *out,
-                             int8_t *codes, hipStream_t st);
+int launch_hadamard_out_proj(const __half *g, int M, int n, float inv_s_y, const int8_t *W, int Dm, float m_out,
+                             __half *out, int8_t *codes, hipStream_t st);
 int launch_hadamard_inverse(const int8_t *xH_q, int M, int n, float scale, __half *x_hat, hipStream_t st);
 
 // generation with M <= 4 rows: [add + RMSNorm + quant] -> in_proj -> conv step in one kernel.

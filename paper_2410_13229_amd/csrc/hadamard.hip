@@ -309,18 +309,18 @@ __global__ __launch_bounds__(threads_for(K << LOGM)) void hadamard_quant_kernel(
   }
 }
 
-// Generation with one sequence: Hadamard + quantization + out_proj in one launch.  Two launches of a
-// few microseconds each, almost all of it latency, become one: every workgroup owns OC output
-// columns, asks for its pieces of their weight rows first (one 16-byte piece per thread and column:
-// n / 16 threads), transforms the single row itself while they arrive (redundantly: the row is 10 KB
+// Generation with up to three sequences: Hadamard + quantization + out_proj in one launch.  Two launches
+// of a few microseconds each, almost all of it latency, become one: every workgroup owns one row and OC
+// output columns, asks for its pieces of their weight rows first (one 16-byte piece per thread and column:
+// n / 16 threads), transforms its row itself while they arrive (redundantly: the row is 10 KB
 // and stays in the cache), and multiplies the 16 codes each thread ends up holding with exactly the
 // weight pieces it asked for.  The codes are the stand-alone kernel's bit for bit (same passes, same
-// order); workgroup 0 also stores them.  out[n] = fp16(acc[n] * m_out).
+// order); the workgroups of column group 0 also store them.  out[r, n] = fp16(acc[r, n] * m_out).
 constexpr int OC = 16;  // output columns per workgroup (8: +2 %, 4: +3 %, 32: +12 % on the 64-block step)
 
 template <int K, int LOGM>
 __global__ __launch_bounds__(threads_for(K << LOGM)) void hadamard_out_proj_kernel(
-    const __half *__restrict__ g, float inv_s, const int8_t *__restrict__ W, int Dm, float m_out,
+    const __half *__restrict__ g, int M, float inv_s, const int8_t *__restrict__ W, int Dm, float m_out,
     __half *__restrict__ out, int8_t *__restrict__ codes_out) {
   constexpr int n = K << LOGM;
   constexpr int HT = threads_for(n);
@@ -328,37 +328,45 @@ __global__ __launch_bounds__(threads_for(K << LOGM)) void hadamard_out_proj_kern
   extern __shared__ __attribute__((aligned(16))) float row[];
   __shared__ int red[HT / 64][OC];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int n0 = blockIdx.x * OC;
+  // One workgroup per (row, column group).  Workgroups go to the 8 XCDs round-robin by index, so the
+  // M workgroups of a column group are spaced 8 apart: same L2, launched together, one HBM read.
+  const int ncg = gridDim.x / M, bid = blockIdx.x;
+  int cg, r;
+  if (ncg % 8 == 0) {
+    const int slot = bid >> 3;
+    r = slot % M;
+    cg = (slot / M) * 8 + (bid & 7);
+  } else {
+    r = bid % M;
+    cg = bid / M;
+  }
+  const int n0 = cg * OC;
   v4i wv[OC];
 #pragma unroll
   for (int j = 0; j < OC; ++j)  // the clamp only bounds the address of a ragged last group
     wv[j] = *reinterpret_cast<const v4i *>(W + (size_t)min(n0 + j, Dm - 1) * n + (size_t)tid * 16);
-  transform_row<K, LOGM, __half, false>(g, row);
+  transform_row<K, LOGM, __half, false>(g + (size_t)r * n, row);
   float v[16];
   last_pass(row, tid, v);
   v4i c;
 #pragma unroll
   for (int q = 0; q < 4; ++q)
     c[q] = static_cast<int>(pack_q8x4(v[4 * q] * inv_s, v[4 * q + 1] * inv_s, v[4 * q + 2] * inv_s, v[4 * q + 3] * inv_s));
-  if (blockIdx.x == 0 && codes_out) *reinterpret_cast<v4i *>(codes_out + (size_t)tid * 16) = c;
-  int acc[OC];
+  if (cg == 0 && codes_out) *reinterpret_cast<v4i *>(codes_out + (size_t)r * n + (size_t)tid * 16) = c;
 #pragma unroll
   for (int j = 0; j < OC; ++j) {
-    acc[j] = 0;
+    int acc = 0;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) acc[j] = __builtin_amdgcn_sdot4(c[e], wv[j][e], acc[j], false);
-    acc[j] = wave_sum(acc[j]);
-  }
-  if (lane == 0) {
-#pragma unroll
-    for (int j = 0; j < OC; ++j) red[wave][j] = acc[j];
+    for (int e = 0; e < 4; ++e) acc = __builtin_amdgcn_sdot4(c[e], wv[j][e], acc, false);
+    acc = wave_sum(acc);
+    if (lane == 0) red[wave][j] = acc;
   }
   __syncthreads();
   if (tid < OC && n0 + tid < Dm) {
     int a = 0;
 #pragma unroll
     for (int w = 0; w < HT / 64; ++w) a += red[w][tid];
-    out[n0 + tid] = __float2half_rn(static_cast<float>(a) * m_out);
+    out[(size_t)r * Dm + n0 + tid] = __float2half_rn(static_cast<float>(a) * m_out);
   }
 }
 
@@ -455,13 +463,13 @@ int launch_hadamard_quant(const __half *g, int M, int n, float inv_s_y, int8_t *
 
 namespace {
 template <int K, int LOGM>
-int run_out_proj(const __half *g, float inv_s, const int8_t *W, int Dm, float m_out, __half *out, int8_t *codes,
+int run_out_proj(const __half *g, int M, float inv_s, const int8_t *W, int Dm, float m_out, __half *out, int8_t *codes,
                  hipStream_t st) {
   constexpr int n = K << LOGM;
   constexpr size_t lds = (size_t)(n + n / 4) * sizeof(float);
   static_assert(lds <= 64 * 1024, "fits the default dynamic LDS limit");
-  hipLaunchKernelGGL((hadamard_out_proj_kernel<K, LOGM>), dim3((Dm + OC - 1) / OC), dim3(threads_for(n)), lds, st, g, inv_s,
-                     W, Dm, m_out, out, codes);
+  hipLaunchKernelGGL((hadamard_out_proj_kernel<K, LOGM>), dim3((Dm + OC - 1) / OC * M), dim3(threads_for(n)), lds, st, g, M,
+                     inv_s, W, Dm, m_out, out, codes);
   QUAMBA_LAUNCH_CHECK();
   return QUAMBA_OK;
 }
@@ -474,14 +482,16 @@ bool hadamard_fuses_out_proj(int n, int Dm) {
   return (k == 1 && m >= 10 && m <= 13) || (k == 12 && m >= 8 && m <= 10) || (k == 20 && m >= 8 && m <= 9);
 }
 
-// One row: out[0, Dm) = fp16(m_out * W codes(H_n g)), codes as launch_hadamard_quant's (stored to codes if given)
-int launch_hadamard_out_proj(const __half *g, int n, float inv_s_y, const int8_t *W, int Dm, float m_out, __half *out,
-                             int8_t *codes, hipStream_t st) {
+// M rows (a few: with four the separate kernels are faster, and two rows per workgroup, the transforms one
+// after the other, cost 5-9 us more than they save): out[r, 0..Dm) = fp16(m_out * W codes(H_n g[r])), codes as launch_hadamard_quant's (stored to codes if given)
+int launch_hadamard_out_proj(const __half *g, int M, int n, float inv_s_y, const int8_t *W, int Dm, float m_out,
+                             __half *out, int8_t *codes, hipStream_t st) {
+  if (M < 1 || M > 64) return fail(QUAMBA_EINVAL, "hadamard + out_proj: M=%d", M);
   if (!hadamard_fuses_out_proj(n, Dm)) return fail(QUAMBA_EUNSUPPORTED, "hadamard + out_proj: n=%d Dm=%d", n, Dm);
   int k = 0, m = 0;
   hadamard_factor(n, &k, &m);
 #define QUAMBA_CASE(KK, LM) \
-  if (k == KK && m == LM) return run_out_proj<KK, LM>(g, inv_s_y, W, Dm, m_out, out, codes, st);
+  if (k == KK && m == LM) return run_out_proj<KK, LM>(g, M, inv_s_y, W, Dm, m_out, out, codes, st);
   QUAMBA_CASE(1, 10) QUAMBA_CASE(1, 11) QUAMBA_CASE(1, 12) QUAMBA_CASE(1, 13)
   QUAMBA_CASE(12, 8) QUAMBA_CASE(12, 9) QUAMBA_CASE(12, 10)
   QUAMBA_CASE(20, 8) QUAMBA_CASE(20, 9)

@@ -253,25 +253,28 @@ def test_decode_without_taps_is_the_tapped_step(name, Bt):
         assert np.array_equal(r[2].view(np.uint16), res[0][2].view(np.uint16))
 
 
-@pytest.mark.parametrize("dm,di", [(2560, 5120), (208, 1024), (64, 2048), (144, 3072), (48, 10240)])
-def test_decode_one_sequence_fused_tail_is_the_tapped_step(dm, di):
-    """One sequence without taps: the Hadamard transform and its quantization run inside the out_proj
-    launch (orders 2^m, 12 * 2^m and 20 * 2^m).  The
-    tapped run, checked against the oracle link by link, takes the separate kernels; outputs, states
-    and the transformed codes must be the same bits."""
-    cfg = W.tiny_config(name="t1", d_model=dm, d_inner=di, dt_rank=16, batch=1, seqlen=1, config_id=96)
+@pytest.mark.parametrize("dm,di,Bt", [(2560, 5120, 1), (2560, 5120, 3), (208, 1024, 3), (128, 1024, 2), (64, 2048, 2),
+                                      (144, 3072, 3), (48, 10240, 1), (2560, 5120, 4)])
+def test_decode_few_sequences_fused_tail_is_the_tapped_step(dm, di, Bt):
+    """Up to three sequences without taps: the Hadamard transform and its quantization run inside the
+    out_proj launch (orders 2^m, 12 * 2^m and 20 * 2^m; numbers of column groups that are and are not
+    multiples of 8, which picks the workgroup-to-tile mapping; four sequences take the separate kernels
+    again).  The tapped run, checked against the
+    oracle link by link, takes the separate kernels; outputs, states and the transformed codes must
+    be the same bits."""
+    cfg = W.tiny_config(name="t1", d_model=dm, d_inner=di, dt_rank=16, batch=Bt, seqlen=1, config_id=96)
     w, qw, sc = oracle_setup(cfg, randomize_bias=True, gain=4.0)
-    _decode_steps(cfg, 1, 2, qw, sc, fused_dt=True)
+    _decode_steps(cfg, Bt, 2, qw, sc, fused_dt=True)
     qd = qweights_to_dev(qw)
-    ssm_np, cs_np = W.make_decode_state(cfg, batch=1)
-    ws = workspace(Q.quamba_workspace_bytes(cfg, 1, 1))
+    ssm_np, cs_np = W.make_decode_state(cfg, batch=Bt)
+    ws = workspace(Q.quamba_workspace_bytes(cfg, Bt, 1))
     res = []
-    for taps in (make_taps(cfg, 1, None), make_taps(cfg, 1, ["gH_q"]), None):
+    for taps in (make_taps(cfg, Bt, None), make_taps(cfg, Bt, ["gH_q"]), None):
         ssm, cs = dev(ssm_np), dev(cs_np)
-        out = empty((1, cfg.d_model), torch.float16)
+        out = empty((Bt, cfg.d_model), torch.float16)
         for s in range(2):
-            u = W.make_hidden(cfg, batch=1, seqlen=1, stream=310 + s)
-            Q.quamba_mixer_decode(cfg, qd, sc, dev(u[:, 0]), 1, out, ssm, cs, taps, ws)
+            u = W.make_hidden(cfg, batch=Bt, seqlen=1, stream=310 + s)
+            Q.quamba_mixer_decode(cfg, qd, sc, dev(u[:, 0]), Bt, out, ssm, cs, taps, ws)
         res.append((host(out), host(ssm), host(cs), None if taps is None else host(taps["gH_q"])))
     for r in res[1:]:
         assert np.array_equal(r[0].view(np.uint16), res[0][0].view(np.uint16))
