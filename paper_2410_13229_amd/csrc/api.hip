@@ -239,6 +239,16 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
     QUAMBA_TRY(tap_copy(ht.xH_q, x_q, (size_t)M * Di, st));
   }
   QUAMBA_TRY(tap_copy(t.x_q, x_q, (size_t)M * Di, st));
+  // dt_proj on the dt_low columns.  In prefill the scan's first pass computes dt_q itself when
+  // the shapes allow and the raw dt_proj sums are not asked for; otherwise it is a GEMM.
+  // (generation: up to 16 sequences each re-read the W_dt rows; beyond that a workgroup keeps its rows
+  // in registers over 8 sequences, which needs dt_rank <= 256; prefill: L > 1)
+  const bool fuse_dt = g_fuse_dt && (decode ? (M <= 16 || R <= 256) : L > 1) && !t.acc_dt && R >= 16 && R % 16 == 0 && NX % 16 == 0 && Di % 4 == 0 &&
+                       aligned(qw->W_dt, 16);
+  // Generation with many sequences: x_proj splits K over the grid; the scan step that follows adds up the
+  // partial sums of its own sequences (192 columns each) instead of a reduce kernel in between.
+  bool dbc_part = false;
+  int x_splits = 1;
   // x_proj: columns dt_low | B | C, each with its own output scale
   if (xf) {  // codes of a non-uniform format: bf16 matrix units on the decoded values, fp32 sums
     QUAMBA_TRY(launch_xfmt_proj(xf->format, reinterpret_cast<const uint8_t *>(x_q), M, NX, Di, xf->W_x_bf16, R, R + N,
@@ -255,6 +265,10 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
     GemmEpilogue e{dbc_q, nullptr, t.acc_x, NX, R, R + N, hx ? hx->m_xh_dt : (xa ? xa->m_x_dt : sc->m_x_dt),
                    hx ? hx->m_xh_B : (xa ? xa->m_x_B : sc->m_x_B), hx ? hx->m_xh_C : (xa ? xa->m_x_C : sc->m_x_C),
                    xa ? xa->col_bias : nullptr};
+    x_splits = gemm_splits(M, NX, Di, base + p.gemm, p.gemm_bytes);
+    dbc_part = decode && fuse_dt && g_fuse_decode && M > 16 && R <= 256 && !xa && !t.dbc_q && !t.acc_x && x_splits > 1 &&
+               x_splits <= 8;
+    e.defer_reduce = dbc_part;
     QUAMBA_TRY(launch_gemm_i8(x_q, Di, hx ? hx->W_xH : qw->W_x, Di, M, NX, Di, e, base + p.gemm, p.gemm_bytes, st));
     QUAMBA_TRY(tap_copy(t.dbc_q, dbc_q, (size_t)M * NX, st));
   }
@@ -262,12 +276,6 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
     QUAMBA_TRY(launch_hadamard_inverse(x_q, M, Di, hx->xhat_scale, x16, st));
     QUAMBA_TRY(tap_copy(ht.xhat16, x16, (size_t)M * Di * sizeof(__half), st));
   }
-  // dt_proj on the dt_low columns.  In prefill the scan's first pass computes dt_q itself when
-  // the shapes allow and the raw dt_proj sums are not asked for; otherwise it is a GEMM.
-  // (generation: up to 16 sequences each re-read the W_dt rows; beyond that a workgroup keeps its rows
-  // in registers over 8 sequences, which needs dt_rank <= 256; prefill: L > 1)
-  const bool fuse_dt = g_fuse_dt && (decode ? (M <= 16 || R <= 256) : L > 1) && !t.acc_dt && R >= 16 && R % 16 == 0 && NX % 16 == 0 && Di % 4 == 0 &&
-                       aligned(qw->W_dt, 16);
   if (!fuse_dt) {
     GemmEpilogue e{dt_q, nullptr, t.acc_dt, Di, Di, Di, sc->m_dt, sc->m_dt, sc->m_dt};
     QUAMBA_TRY(launch_gemm_i8(dbc_q, NX, qw->W_dt, R, M, Di, R, e, base + p.gemm, p.gemm_bytes, st));
@@ -288,6 +296,10 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
     if (fuse_dt) {  // decode writes the dt codes only when they are asked for as a tap
       a.dtlow_q = dbc_q; a.lddl = NX; a.W_dt = qw->W_dt; a.R = R; a.m_dt = sc->m_dt;
       a.dt_out = (decode && !t.dt_q) ? nullptr : dt_q;
+    }
+    if (dbc_part) {
+      a.dbc_part = reinterpret_cast<const int32_t *>(base + p.gemm); a.dbc_splits = x_splits;
+      a.m_x_dt = hx ? hx->m_xh_dt : sc->m_x_dt; a.m_x_B = hx ? hx->m_xh_B : sc->m_x_B; a.m_x_C = hx ? hx->m_xh_C : sc->m_x_C;
     }
     if (decode) {
       QUAMBA_TRY(launch_scan_step(a, st));

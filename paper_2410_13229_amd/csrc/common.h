@@ -63,6 +63,9 @@ struct GemmEpilogue {
   // zero-point correction of an asymmetric input grid); 16-byte aligned; the `acc` tap stays raw
   const int32_t *col_bias;
   ConvStepEpi conv;  // only where gemm_fuses_conv_step says so
+  // K split over the grid (gemm_splits > 1): leave the raw partial sums [splits][M][N] at the start of
+  // the workspace and launch no reduce kernel; the consumer adds them up and applies the multipliers
+  bool defer_reduce;
 };
 
 // Whether launch_gemm_i8 on this shape ends in an epilogue that can carry the conv step (the
@@ -71,6 +74,8 @@ bool gemm_fuses_conv_step(int M, int N, int K, const void *ws, size_t ws_bytes);
 
 // `ws` (may be NULL) lets skinny problems split K; gemm_workspace_bytes is the most they use.
 size_t gemm_workspace_bytes(int M, int N);
+// Into how many K ranges launch_gemm_i8 splits this shape over the grid (1: not split).
+int gemm_splits(int M, int N, int K, const void *ws, size_t ws_bytes);
 int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, int N, int K,
                    const GemmEpilogue &epi, void *ws, size_t ws_bytes, hipStream_t st);
 
@@ -127,6 +132,13 @@ struct ScanArgs {
   int x_format;
   // optional: the scale of x is not s_x but derived from this device word (bits of the call's max|x|)
   const unsigned *s_x_slot;
+  // optional (generation with more than 16 sequences and the fused dt_proj only): x_proj's raw sums
+  // as dbc_splits (<= 8) partial results [dbc_splits][Bt][R + 2 d_state] of a K split; the step adds
+  // them up and requantizes the dt_low | B | C columns itself with these multipliers;
+  // dtlow_q, B_q, C_q are then ignored
+  const int32_t *dbc_part;
+  int dbc_splits;
+  float m_x_dt, m_x_B, m_x_C;
 };
 
 size_t scan_workspace_bytes(int Bt, int L, int Di);

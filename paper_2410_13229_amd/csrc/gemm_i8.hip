@@ -781,6 +781,11 @@ size_t gemm_workspace_bytes(int M, int N) {
   return (size_t)8 * M * N * sizeof(int32_t);
 }
 
+int gemm_splits(int M, int N, int K, const void *ws, size_t ws_bytes) {
+  const GemmChoice c = choose_gemm(M, N, K, ws, ws_bytes);
+  return c.gemv ? 1 : c.splits;
+}
+
 bool gemm_fuses_conv_step(int M, int N, int K, const void *ws, size_t ws_bytes) {
   const GemmChoice c = choose_gemm(M, N, K, ws, ws_bytes);
   return !c.gemv && (c.kind == 7 || c.kind == 11 || c.splits > 1);
@@ -827,7 +832,7 @@ int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, i
     case 10: rc = run_dma<256, 256, 4, 2, 2, 128, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
     default: rc = run_reg<128, 128, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
   }
-  if (rc != QUAMBA_OK || splits == 1) return rc;
+  if (rc != QUAMBA_OK || splits == 1 || epi.defer_reduce) return rc;
   const size_t groups = (size_t)M * (N / 4);
   if (conv)
     hipLaunchKernelGGL(splitk_reduce_kernel<true>, dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, st, ks.partial,

@@ -72,6 +72,9 @@ struct Dev {
   const __half *x_f16;  // scan input in half precision instead of s_x * x_q (comparison variant)
   float x_off;          // -s_x * zero point of an asymmetric x grid: x = s_x x_q + x_off (0 = symmetric)
   const unsigned *s_x_slot;  // bits of the call's max|x| when the scale of x is dynamic
+  const int32_t *dbc_part;   // generation: x_proj's sums as dbc_splits partial results [dbc_splits][Bt][R + 2 NS]
+  int dbc_splits;
+  float m_x_dt, m_x_B, m_x_C;
 };
 
 // How the scan reads x: int8 codes on a uniform grid (s_x x_q + x_off), half precision values (the
@@ -408,8 +411,13 @@ __global__ __launch_bounds__(256) void scan_step_kernel(Dev p, float *__restrict
 // code loads of the BB sequences are requested before the first dot product.  BB = 4 (measured at
 // 2.8B, batch 64: step 47.5 us with the separate dt_proj GEMM, 44.6 us with BB = 4 or 2, 47.4 us
 // with BB = 8, whose 183 registers leave two waves per SIMD and nothing to overlap the loads with).
-template <int XM, int BB, int NP>
+// PART: x_proj's K was split over the grid and its reduce kernel left out; the workgroup adds up the
+// partial sums of its BB sequences (R + 32 columns each) and requantizes them into LDS first, after
+// its weight pieces are requested.  Integer sums: the codes are the reduce kernel's bit for bit.
+template <int XM, int BB, int NP, bool PART>
 __global__ __launch_bounds__(256) void scan_step_batch_kernel(Dev p, float *__restrict__ ssm_state, int Bt) {
+  constexpr int LDP = NP * 64 + 2 * NS;  // R <= 64 NP
+  __shared__ __attribute__((aligned(16))) int8_t dbc[PART ? BB : 1][LDP];
   const int q = threadIdx.x & 3;
   const int d = blockIdx.x * 64 + (threadIdx.x >> 2);
   const bool live = d < p.Di;
@@ -439,16 +447,49 @@ __global__ __launch_bounds__(256) void scan_step_batch_kernel(Dev p, float *__re
   for (int i = 0; i < BB; ++i) {
     const size_t b = static_cast<size_t>(min(b0 + i, Bt - 1));  // past the batch: loaded again, never stored
     hv[i] = reinterpret_cast<const float4 *>(ssm_state)[(b * p.Di + dd) * 4 + q];
-    bw[i] = *reinterpret_cast<const unsigned *>(p.B_q + b * p.ldbc + 4 * q);
-    cw[i] = *reinterpret_cast<const unsigned *>(p.C_q + b * p.ldbc + 4 * q);
     xv[i] = x_value<XM>(p, XM == X_F16 ? static_cast<int>(__half_as_ushort(p.x_f16[b * p.Di + dd]))
                                        : static_cast<int>(p.x_q[b * p.Di + dd]), sx);
     zv[i] = p.s_z * static_cast<float>(p.z_q[b * p.ldz + dd]);
+  }
+  if constexpr (PART) {
+    const int NX = p.R + 2 * NS, per_row = NX / 4;
+    for (int g = threadIdx.x; g < BB * per_row; g += 256) {
+      const int i = g / per_row, gn = (g % per_row) * 4;
+      const size_t b = static_cast<size_t>(min(b0 + i, Bt - 1));
+      v4i v[8];
+#pragma unroll
+      for (int s = 0; s < 8; ++s) {
+        v[s] = v4i{0, 0, 0, 0};
+        if (s < p.dbc_splits) v[s] = *reinterpret_cast<const v4i *>(p.dbc_part + ((size_t)s * Bt + b) * NX + gn);
+      }
+      int sum[4] = {0, 0, 0, 0};
+#pragma unroll
+      for (int s = 0; s < 8; ++s)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) sum[e] += v[s][e];
+      const float m = gn < p.R ? p.m_x_dt : (gn < p.R + NS ? p.m_x_B : p.m_x_C);
+      *reinterpret_cast<unsigned *>(&dbc[i][gn]) = requant_pack4(sum, m);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < BB; ++i) {
+    const size_t b = static_cast<size_t>(min(b0 + i, Bt - 1));
+    if constexpr (PART) {
+      bw[i] = *reinterpret_cast<const unsigned *>(&dbc[i][p.R + 4 * q]);
+      cw[i] = *reinterpret_cast<const unsigned *>(&dbc[i][p.R + NS + 4 * q]);
+    } else {
+      bw[i] = *reinterpret_cast<const unsigned *>(p.B_q + b * p.ldbc + 4 * q);
+      cw[i] = *reinterpret_cast<const unsigned *>(p.C_q + b * p.ldbc + 4 * q);
+    }
 #pragma unroll
     for (int j = 0; j < NP; ++j) {
       const int kc = 16 * q + 64 * j;
       a[i][j] = v4i{0, 0, 0, 0};
-      if (kc < p.R) a[i][j] = *reinterpret_cast<const v4i *>(p.dtlow_q + b * p.lddl + kc);
+      if (kc < p.R) {
+        if constexpr (PART) a[i][j] = *reinterpret_cast<const v4i *>(&dbc[i][kc]);
+        else a[i][j] = *reinterpret_cast<const v4i *>(p.dtlow_q + b * p.lddl + kc);
+      }
     }
   }
 #pragma unroll
@@ -499,6 +540,7 @@ Dev make_dev(const ScanArgs &a) {
   if (a.dtlow_q && a.dt_out) p.dt_q = a.dt_out;
   p.x_f16 = a.x_f16;
   p.s_x_slot = a.s_x_slot;
+  p.dbc_part = a.dbc_part; p.dbc_splits = a.dbc_splits; p.m_x_dt = a.m_x_dt; p.m_x_B = a.m_x_B; p.m_x_C = a.m_x_C;
   p.x_off = -a.s_x * static_cast<float>(a.x_zero_point);  // -0.f for the symmetric grid: adds nothing
   return p;
 }
@@ -587,6 +629,9 @@ int launch_scan_prefill(const ScanArgs &a, void *ws, size_t ws_bytes, hipStream_
 }
 
 int launch_scan_step(const ScanArgs &a, hipStream_t st) {
+  if (a.dbc_part && (!a.dtlow_q || a.Bt <= 16 || a.R > 256 || a.dbc_splits < 1 || a.dbc_splits > 8 || !aligned(a.dbc_part, 16)))
+    return fail(QUAMBA_EUNSUPPORTED, "scan_step: partial x_proj sums need the fused dt_proj, more than 16 sequences, "
+                                     "dt_rank <= 256 and at most 8 partial results");
   Dev p = make_dev(a);
   p.L = 1;
   const int xm = a.x_f16 ? X_F16 : (a.s_x_slot ? X_I8DYN : (a.x_format == QUAMBA_XFMT_E4M3 ? X_E4M3 : (a.x_format == QUAMBA_XFMT_LOG2 ? X_LOG2 : X_I8)));
@@ -599,15 +644,21 @@ int launch_scan_step(const ScanArgs &a, hipStream_t st) {
     const int np = (a.R + 63) / 64;
     if (a.Bt > 16 && np <= 4) {  // many sequences: keep the W_dt rows in registers over BB of them
       const dim3 grid((unsigned)((a.Di + 63) / 64), (unsigned)((a.Bt + BB - 1) / BB));
-#define QUAMBA_STEP_BATCH(XMV)                                                                                        \
+#define QUAMBA_STEP_BATCH_NP(XMV, NPV)                                                                                  \
   do {                                                                                                                \
-    if (np == 1) hipLaunchKernelGGL((scan_step_batch_kernel<XMV, BB, 1>), grid, dim3(256), 0, st, p, a.ssm_state, a.Bt);      \
-    else if (np == 2) hipLaunchKernelGGL((scan_step_batch_kernel<XMV, BB, 2>), grid, dim3(256), 0, st, p, a.ssm_state, a.Bt); \
-    else if (np == 3) hipLaunchKernelGGL((scan_step_batch_kernel<XMV, BB, 3>), grid, dim3(256), 0, st, p, a.ssm_state, a.Bt); \
-    else hipLaunchKernelGGL((scan_step_batch_kernel<XMV, BB, 4>), grid, dim3(256), 0, st, p, a.ssm_state, a.Bt);              \
+    if (a.dbc_part) hipLaunchKernelGGL((scan_step_batch_kernel<XMV, BB, NPV, true>), grid, dim3(256), 0, st, p, a.ssm_state, a.Bt); \
+    else hipLaunchKernelGGL((scan_step_batch_kernel<XMV, BB, NPV, false>), grid, dim3(256), 0, st, p, a.ssm_state, a.Bt);          \
+  } while (0)
+#define QUAMBA_STEP_BATCH(XMV)                      \
+  do {                                              \
+    if (np == 1) QUAMBA_STEP_BATCH_NP(XMV, 1);      \
+    else if (np == 2) QUAMBA_STEP_BATCH_NP(XMV, 2); \
+    else if (np == 3) QUAMBA_STEP_BATCH_NP(XMV, 3); \
+    else QUAMBA_STEP_BATCH_NP(XMV, 4);              \
   } while (0)
       QUAMBA_XM_SWITCH(QUAMBA_STEP_BATCH)
 #undef QUAMBA_STEP_BATCH
+#undef QUAMBA_STEP_BATCH_NP
     } else {
 #define QUAMBA_STEPF(XMV) \
   hipLaunchKernelGGL((scan_step_kernel<true, XMV>), dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, a.ssm_state, a.Bt)
