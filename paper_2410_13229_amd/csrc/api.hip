@@ -131,7 +131,9 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
               const int8_t *u_q_in, int Bt, int L, bool decode, __half *out, float *ssm_state,
               __half *conv_state, const quamba_taps *taps, void *ws, size_t ws_bytes, hipStream_t st,
               const NormIn *norm = nullptr, const quamba_hadx *hx = nullptr, const quamba_hadx_taps *hx_taps = nullptr,
-              const quamba_xasym *xa = nullptr, const quamba_xfmt *xf = nullptr, const DynX *dyn = nullptr) {
+              const quamba_xasym *xa = nullptr, const quamba_xfmt *xf = nullptr, const DynX *dyn = nullptr,
+              OutPartial *defer_out = nullptr) {
+  if (defer_out) defer_out->splits = 1;
   QUAMBA_TRY(check_dims(d));
   QUAMBA_TRY(check_q(qw, sc));
   if ((!u && !u_q_in && !norm) || !out) return fail(QUAMBA_EINVAL, "input or output pointer is NULL");
@@ -321,6 +323,13 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
   // out_proj with the folded weight, fp16 out; the multiplier carries s_y s_WoutH / n
   {
     GemmEpilogue e{nullptr, out, t.acc_out, Dm, Dm, Dm, sc->m_out, sc->m_out, sc->m_out};
+    if (defer_out && defer_out->want && decode && g_fuse_decode && !t.acc_out) {
+      const int splits = gemm_splits(M, Dm, Di, base + p.gemm, p.gemm_bytes);
+      if (splits > 1 && splits <= 8) {
+        e.defer_reduce = true;
+        *defer_out = OutPartial{true, splits, reinterpret_cast<const int32_t *>(base + p.gemm), sc->m_out};
+      }
+    }
     QUAMBA_TRY(launch_gemm_i8(gH_q, Di, qw->W_outH, Di, M, Dm, Di, e, base + p.gemm, p.gemm_bytes, st));
   }
   return QUAMBA_OK;
@@ -350,8 +359,9 @@ size_t mixer_workspace_bytes(const quamba_dims *d, int Bt, int L) { return make_
 
 int mixer_run_q(const quamba_dims *d, const quamba_qweights *qw, const quamba_scales *sc, const int8_t *u_q, int Bt,
                 int L, bool decode, __half *out, float *ssm_state, __half *conv_state, void *ws, size_t ws_bytes,
-                hipStream_t st) {
-  return run_mixer(d, qw, sc, nullptr, u_q, Bt, L, decode, out, ssm_state, conv_state, nullptr, ws, ws_bytes, st);
+                hipStream_t st, OutPartial *defer_out) {
+  return run_mixer(d, qw, sc, nullptr, u_q, Bt, L, decode, out, ssm_state, conv_state, nullptr, ws, ws_bytes, st,
+                   nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, defer_out);
 }
 
 int mixer_decode_norm(const quamba_dims *d, const quamba_qweights *qw, const quamba_scales *sc, const NormIn &norm,

@@ -107,6 +107,9 @@ int launch_dyn_export(const unsigned *slot, float *out, hipStream_t st);
 
 int launch_add_rmsnorm_quant(const __half *x_out, __half *res, const __half *weight, float eps,
                              float inv_s, int8_t *u_q, int M, int Dm, hipStream_t st);
+// the same with x_out given as `splits` (<= 8) int32 partial sums [splits][M][Dm]: x_out = fp16(m_out * their sum)
+int launch_add_rmsnorm_quant_partial(const int32_t *partial, int splits, float m_out, __half *res, const __half *weight,
+                                     float eps, float inv_s, int8_t *u_q, int M, int Dm, hipStream_t st);
 
 struct ScanArgs {
   const int8_t *x_q, *dt_q, *z_q, *B_q, *C_q, *A_q, *D_q;
@@ -178,9 +181,19 @@ int launch_decode_in(const DecodeInArgs &a, hipStream_t st);
 // one quantized mixer on already quantized input (prefill: fresh conv history; decode: L == 1 on
 // carried states), its workspace size, and the dimension check of the entry points
 size_t mixer_workspace_bytes(const quamba_dims *d, int Bt, int L);
+// out_proj's result left as the partial sums of a K split (generation in a stack of blocks: the next
+// block's add + RMSNorm + quantization adds them up, which saves the reduce kernel).  The caller sets
+// `want`; the mixer sets splits (1: `out` was written as usual), partial [splits][M][d_model] (inside
+// the mixer's workspace: valid until the next mixer call on it) and the multiplier of the sums.
+struct OutPartial {
+  bool want;
+  int splits;
+  const int32_t *partial;
+  float m_out;
+};
 int mixer_run_q(const quamba_dims *d, const quamba_qweights *qw, const quamba_scales *sc, const int8_t *u_q, int Bt,
                 int L, bool decode, __half *out, float *ssm_state, __half *conv_state, void *ws, size_t ws_bytes,
-                hipStream_t st);
+                hipStream_t st, OutPartial *defer_out = nullptr);
 int check_model_dims(const quamba_dims *d);
 
 // generation with at most 4 sequences: the block's own residual add + RMSNorm + quantization runs

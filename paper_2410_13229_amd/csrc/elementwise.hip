@@ -175,11 +175,16 @@ __global__ __launch_bounds__(256) void conv_step_kernel(const int8_t *__restrict
 // the reduction and the normalisation, so the row is read once.
 constexpr int RMS_MAX_PER_THREAD = 4;  // groups of 8 halves per thread: Dm <= 8192
 
+// PART: x_out is not stored but given as the int32 partial sums of a GEMM whose K was split over the
+// grid, [splits][rows][Dm]: x_out = fp16(m_out * sum), the rounding the reduce kernel would have done.
+template <bool PART>
 __global__ __launch_bounds__(256) void add_rmsnorm_quant_kernel(const __half *__restrict__ x_out,
                                                                 __half *__restrict__ res,
                                                                 const __half *__restrict__ weight,
                                                                 float eps, float inv_s,
-                                                                int8_t *__restrict__ u_q, int Dm) {
+                                                                int8_t *__restrict__ u_q, int Dm,
+                                                                const int32_t *__restrict__ partial, int splits,
+                                                                float m_out) {
   const size_t row = blockIdx.x;
   const int ngroups = Dm / 8;
   float vals[RMS_MAX_PER_THREAD][8];
@@ -192,7 +197,28 @@ __global__ __launch_bounds__(256) void add_rmsnorm_quant_kernel(const __half *__
         uint4 u;
         __half h[8];
       } a, r;
-      a.u = *reinterpret_cast<const uint4 *>(x_out + row * Dm + (size_t)g * 8);
+      if constexpr (PART) {
+        const size_t rows = gridDim.x;
+        v4i v[8][2];
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+          v[s][0] = v[s][1] = v4i{0, 0, 0, 0};
+          if (s < splits) {
+            const v4i *src = reinterpret_cast<const v4i *>(partial + ((size_t)s * rows + row) * Dm + (size_t)g * 8);
+            v[s][0] = src[0];
+            v[s][1] = src[1];
+          }
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          int sum = 0;
+#pragma unroll
+          for (int s = 0; s < 8; ++s) sum += v[s][e >> 2][e & 3];
+          a.h[e] = __float2half_rn(static_cast<float>(sum) * m_out);
+        }
+      } else {
+        a.u = *reinterpret_cast<const uint4 *>(x_out + row * Dm + (size_t)g * 8);
+      }
       r.u = *reinterpret_cast<const uint4 *>(res + row * Dm + (size_t)g * 8);
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
@@ -418,8 +444,21 @@ int launch_add_rmsnorm_quant(const __half *x_out, __half *res, const __half *wei
   if (Dm % 8 != 0 || Dm > 8 * 256 * RMS_MAX_PER_THREAD)
     return fail(QUAMBA_EUNSUPPORTED, "add_rmsnorm_quant: d_model=%d must be a multiple of 8 and <= %d", Dm,
                 8 * 256 * RMS_MAX_PER_THREAD);
-  hipLaunchKernelGGL(add_rmsnorm_quant_kernel, dim3(M), dim3(256), 0, st, x_out, res, weight, eps, inv_s,
-                     u_q, Dm);
+  hipLaunchKernelGGL(add_rmsnorm_quant_kernel<false>, dim3(M), dim3(256), 0, st, x_out, res, weight, eps, inv_s,
+                     u_q, Dm, nullptr, 0, 0.f);
+  QUAMBA_LAUNCH_CHECK();
+  return QUAMBA_OK;
+}
+
+int launch_add_rmsnorm_quant_partial(const int32_t *partial, int splits, float m_out, __half *res, const __half *weight,
+                                     float eps, float inv_s, int8_t *u_q, int M, int Dm, hipStream_t st) {
+  if (Dm % 8 != 0 || Dm > 8 * 256 * RMS_MAX_PER_THREAD)
+    return fail(QUAMBA_EUNSUPPORTED, "add_rmsnorm_quant: d_model=%d must be a multiple of 8 and <= %d", Dm,
+                8 * 256 * RMS_MAX_PER_THREAD);
+  if (!partial || splits < 1 || splits > 8 || !aligned(partial, 16))
+    return fail(QUAMBA_EINVAL, "add_rmsnorm_quant: %d partial sums", splits);
+  hipLaunchKernelGGL(add_rmsnorm_quant_kernel<true>, dim3(M), dim3(256), 0, st, nullptr, res, weight, eps, inv_s, u_q,
+                     Dm, partial, splits, m_out);
   QUAMBA_LAUNCH_CHECK();
   return QUAMBA_OK;
 }

@@ -366,6 +366,9 @@ int run_model(const quamba_model *m, const int32_t *tokens, int Bt, int L, bool 
   // kernel, which reads one residual buffer and writes the other
   const bool fused = decode && mixer_decode_norm_available(&m->dims, Bt);
   __half *res_other = reinterpret_cast<__half *>(base + c.res2);
+  // generation with more sequences: where out_proj splits K over the grid, the next block's add + norm +
+  // quantization adds up the partial sums (the last block's output is stored as usual for the final norm)
+  OutPartial prev{false, 1, nullptr, 0.f};
   for (int l = 0; l < m->n_layers; ++l) {
     const quamba_layer &ly = m->layers[l];
     float *ssm = ssm_states + (size_t)l * Bt * Di * N;
@@ -378,10 +381,17 @@ int run_model(const quamba_model *m, const int32_t *tokens, int Bt, int L, bool 
       res = res_other;
       res_other = tmp;
     } else {
-      rc = launch_add_rmsnorm_quant(out, res, reinterpret_cast<const __half *>(ly.norm_w), m->eps, ly.s.inv_s_u,
-                                    u_q, M, Dm, st);
+      if (prev.splits > 1)
+        rc = launch_add_rmsnorm_quant_partial(prev.partial, prev.splits, prev.m_out, res,
+                                              reinterpret_cast<const __half *>(ly.norm_w), m->eps, ly.s.inv_s_u, u_q, M,
+                                              Dm, st);
+      else
+        rc = launch_add_rmsnorm_quant(out, res, reinterpret_cast<const __half *>(ly.norm_w), m->eps, ly.s.inv_s_u,
+                                      u_q, M, Dm, st);
       if (rc != QUAMBA_OK) return rc;
-      rc = mixer_run_q(&m->dims, &ly.q, &ly.s, u_q, Bt, L, decode, out, ssm, cs, base + c.mixer, c.mixer_bytes, st);
+      prev = OutPartial{decode && l + 1 < m->n_layers, 1, nullptr, 0.f};
+      rc = mixer_run_q(&m->dims, &ly.q, &ly.s, u_q, Bt, L, decode, out, ssm, cs, base + c.mixer, c.mixer_bytes, st,
+                       &prev);
     }
     if (rc != QUAMBA_OK) return rc;
   }

@@ -204,6 +204,39 @@ def test_few_sequence_generation_kernels_match_the_general_path(Bt, d_model, d_i
         assert (ca.view(np.uint16) != cb.view(np.uint16)).mean() <= 2e-3
 
 
+@pytest.mark.parametrize("Bt,d_model,d_inner", [(24, 256, 512), (64, 256, 512), (7, 512, 1024)])
+def test_many_sequence_generation_fusions_are_the_general_path_bit_for_bit(Bt, d_model, d_inner):
+    """With more than 4 sequences the projections whose K is split over the grid hand their partial sums to
+    the kernel that follows (x_proj to the scan step, out_proj to the next block's add + norm + quantization)
+    instead of a reduce kernel.  Integer sums, the same roundings: logits, states and tokens must be the same
+    bits as with the separate kernels."""
+    nlayers, vocab = 3, 128
+    cfg, om, gm = _tiny_model(nlayers, 103, vocab, d_model=d_model, d_inner=d_inner)
+    prompt = W.make_tokens(cfg, vocab, batch=Bt, seqlen=5)
+    wsp = workspace(Q.quamba_model_workspace_bytes(gm, Bt, 5))
+    wsd = workspace(Q.quamba_model_workspace_bytes(gm, Bt, 1))
+    res = []
+    try:
+        for fuse in (1, 0):
+            Q.lib().quamba_debug_set_fuse_decode(fuse)
+            ssm, cs = _states(cfg, nlayers, Bt)
+            nxt = empty((Bt,), torch.int32)
+            Q.quamba_model_prefill(gm, dev(prompt), Bt, 5, None, nxt, ssm, cs, wsp)
+            logits = empty((Bt, vocab), torch.float32)
+            steps = []
+            for _ in range(3):
+                Q.quamba_model_decode(gm, nxt, Bt, logits, nxt, ssm, cs, wsd)
+                steps.append((host(logits).copy(), host(ssm).copy(), host(cs).copy(), host(nxt).copy()))
+            res.append(steps)
+    finally:
+        Q.lib().quamba_debug_set_fuse_decode(1)
+    for (la, sa, ca, ta), (lb, sb, cb, tb) in zip(*res):
+        assert np.array_equal(la.view(np.uint32), lb.view(np.uint32))
+        assert np.array_equal(sa.view(np.uint32), sb.view(np.uint32))
+        assert np.array_equal(ca.view(np.uint16), cb.view(np.uint16))
+        assert np.array_equal(ta, tb)
+
+
 def test_model_rejects_bad_arguments():
     cfg, om, gm = _tiny_model(1, 100, 97)
     ws = workspace(Q.quamba_model_workspace_bytes(gm, 1, 4))
