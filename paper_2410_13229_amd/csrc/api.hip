@@ -247,7 +247,7 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
   // in registers over 8 sequences, which needs dt_rank <= 256; prefill: L > 1)
   const bool fuse_dt = g_fuse_dt && (decode ? (M <= 16 || R <= 256) : L > 1) && !t.acc_dt && R >= 16 && R % 16 == 0 && NX % 16 == 0 && Di % 4 == 0 &&
                        aligned(qw->W_dt, 16);
-  // Generation with many sequences: x_proj splits K over the grid; the scan step that follows adds up the
+  // Generation with more than a few sequences: x_proj splits K over the grid; the scan step that follows adds up the
   // partial sums of its own sequences (192 columns each) instead of a reduce kernel in between.
   bool dbc_part = false;
   int x_splits = 1;
@@ -268,7 +268,7 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
                    hx ? hx->m_xh_B : (xa ? xa->m_x_B : sc->m_x_B), hx ? hx->m_xh_C : (xa ? xa->m_x_C : sc->m_x_C),
                    xa ? xa->col_bias : nullptr};
     x_splits = gemm_splits(M, NX, Di, base + p.gemm, p.gemm_bytes);
-    dbc_part = decode && fuse_dt && g_fuse_decode && M > 16 && R <= 256 && !xa && !t.dbc_q && !t.acc_x && x_splits > 1 &&
+    dbc_part = decode && fuse_dt && g_fuse_decode && R <= 256 && !xa && !t.dbc_q && !t.acc_x && x_splits > 1 &&
                x_splits <= 8;
     e.defer_reduce = dbc_part;
     QUAMBA_TRY(launch_gemm_i8(x_q, Di, hx ? hx->W_xH : qw->W_x, Di, M, NX, Di, e, base + p.gemm, p.gemm_bytes, st));

@@ -135,7 +135,7 @@ struct ScanArgs {
   int x_format;
   // optional: the scale of x is not s_x but derived from this device word (bits of the call's max|x|)
   const unsigned *s_x_slot;
-  // optional (generation with more than 16 sequences and the fused dt_proj only): x_proj's raw sums
+  // optional (generation with the fused dt_proj only): x_proj's raw sums
   // as dbc_splits (<= 8) partial results [dbc_splits][Bt][R + 2 d_state] of a K split; the step adds
   // them up and requantizes the dt_low | B | C columns itself with these multipliers;
   // dtlow_q, B_q, C_q are then ignored

@@ -629,9 +629,9 @@ int launch_scan_prefill(const ScanArgs &a, void *ws, size_t ws_bytes, hipStream_
 }
 
 int launch_scan_step(const ScanArgs &a, hipStream_t st) {
-  if (a.dbc_part && (!a.dtlow_q || a.Bt <= 16 || a.R > 256 || a.dbc_splits < 1 || a.dbc_splits > 8 || !aligned(a.dbc_part, 16)))
-    return fail(QUAMBA_EUNSUPPORTED, "scan_step: partial x_proj sums need the fused dt_proj, more than 16 sequences, "
-                                     "dt_rank <= 256 and at most 8 partial results");
+  if (a.dbc_part && (!a.dtlow_q || a.R > 256 || a.dbc_splits < 1 || a.dbc_splits > 8 || !aligned(a.dbc_part, 16)))
+    return fail(QUAMBA_EUNSUPPORTED, "scan_step: partial x_proj sums need the fused dt_proj, dt_rank <= 256 and at most 8 "
+                                     "partial results");
   Dev p = make_dev(a);
   p.L = 1;
   const int xm = a.x_f16 ? X_F16 : (a.s_x_slot ? X_I8DYN : (a.x_format == QUAMBA_XFMT_E4M3 ? X_E4M3 : (a.x_format == QUAMBA_XFMT_LOG2 ? X_LOG2 : X_I8)));
@@ -642,7 +642,18 @@ int launch_scan_step(const ScanArgs &a, hipStream_t st) {
                                        "aligned dt_low and W_dt");
     constexpr int BB = 4;
     const int np = (a.R + 63) / 64;
-    if (a.Bt > 16 && np <= 4) {  // many sequences: keep the W_dt rows in registers over BB of them
+    if (a.dbc_part && a.Bt <= 16) {  // a workgroup per sequence and 64 channels, as the kernel below, plus the sums
+      const dim3 grid((unsigned)((a.Di + 63) / 64), (unsigned)a.Bt);
+#define QUAMBA_STEP_ONE(XMV)                                                                                                 \
+  do {                                                                                                                       \
+    if (np == 1) hipLaunchKernelGGL((scan_step_batch_kernel<XMV, 1, 1, true>), grid, dim3(256), 0, st, p, a.ssm_state, a.Bt);      \
+    else if (np == 2) hipLaunchKernelGGL((scan_step_batch_kernel<XMV, 1, 2, true>), grid, dim3(256), 0, st, p, a.ssm_state, a.Bt); \
+    else if (np == 3) hipLaunchKernelGGL((scan_step_batch_kernel<XMV, 1, 3, true>), grid, dim3(256), 0, st, p, a.ssm_state, a.Bt); \
+    else hipLaunchKernelGGL((scan_step_batch_kernel<XMV, 1, 4, true>), grid, dim3(256), 0, st, p, a.ssm_state, a.Bt);              \
+  } while (0)
+      QUAMBA_XM_SWITCH(QUAMBA_STEP_ONE)
+#undef QUAMBA_STEP_ONE
+    } else if (a.Bt > 16 && np <= 4) {  // many sequences: keep the W_dt rows in registers over BB of them
       const dim3 grid((unsigned)((a.Di + 63) / 64), (unsigned)((a.Bt + BB - 1) / BB));
 #define QUAMBA_STEP_BATCH_NP(XMV, NPV)                                                                                  \
   do {                                                                                                                \

@@ -227,7 +227,7 @@ def test_decode_c2_shape(fused_dt):
     _decode_steps(cfg, cfg.batch, 3, qw, sc, fused_dt=fused_dt)
 
 
-@pytest.mark.parametrize("name,Bt", [("c2", 64), ("c2", 24), ("tiny", 6)])
+@pytest.mark.parametrize("name,Bt", [("c2", 64), ("c2", 24), ("c2", 16), ("c2", 7), ("tiny", 6)])
 def test_decode_without_taps_is_the_tapped_step(name, Bt):
     """The intermediates are checked link by link in the tapped runs above; without taps the step takes
     the faster epilogues (row-staged stores, the conv step inside in_proj's epilogue from staged codes).
