@@ -68,6 +68,9 @@ struct GemmEpilogue {
   bool defer_reduce;
 };
 
+// generation takes the few-row streaming kernels up to this many sequences (at most 4)
+extern int g_gemv_max_rows;
+
 // Whether launch_gemm_i8 on this shape ends in an epilogue that can carry the conv step (the
 // 64 x 32 tiles of a wide generation-step output, or the reduce kernel of a split K).
 bool gemm_fuses_conv_step(int M, int N, int K, const void *ws, size_t ws_bytes);

@@ -684,7 +684,6 @@ int run_reg(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, int N, i
 
 int g_gemm_variant = -1;  // tuning hook: >= 0 forces a kernel configuration
 int g_gemm_split = 0;     // tuning hook: > 1 forces a K split over the grid
-int g_gemv_max_rows = 4;  // the few-row streaming kernel serves M up to this (tuning hook; at most 4)
 
 struct GemmChoice {
   bool gemv;  // the few-row streaming kernel
@@ -776,6 +775,8 @@ GemmChoice choose_gemm(int M, int N, int K, const void *ws, size_t ws_bytes) {
 
 }  // namespace
 
+int g_gemv_max_rows = 2;  // the few-row streaming kernels serve M up to this (tuning hook; at most 4)
+
 size_t gemm_workspace_bytes(int M, int N) {
   // room for up to 8 int32 partial copies of a skinny output
   return (size_t)8 * M * N * sizeof(int32_t);
@@ -848,4 +849,4 @@ int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, i
 
 extern "C" void quamba_debug_set_gemm_variant(int v) { quamba::g_gemm_variant = v; }
 extern "C" void quamba_debug_set_gemm_split(int v) { quamba::g_gemm_split = v; }
-extern "C" void quamba_debug_set_gemv_max_rows(int v) { quamba::g_gemv_max_rows = v < 4 ? v : 4; }
+extern "C" void quamba_debug_set_gemv_max_rows(int v) { quamba::g_gemv_max_rows = v < 0 ? 2 : (v < 4 ? v : 4); }

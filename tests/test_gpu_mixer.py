@@ -293,12 +293,26 @@ def test_decode_many_sequences_ragged(Bt, di, rk):
     _decode_steps(cfg, Bt, 3, qw, sc, fused_dt=True)
 
 
-@pytest.mark.parametrize("Bt", [1, 2, 5, 8])
+@pytest.mark.parametrize("Bt", [1, 2, 3, 4, 5, 8])
 def test_decode_few_sequences_2p8b_width(Bt):
-    """Generation with a handful of sequences takes the streaming (no matrix tile) projections."""
+    """Generation with one or two sequences takes the streaming (no matrix tile) projections, more take
+    matrix tiles."""
     cfg = W.CONFIGS["c2"]
     w, qw, sc = oracle_setup(cfg)
     _decode_steps(cfg, Bt, 2, qw, sc, fused_dt=(Bt % 2 == 1))
+
+
+@pytest.mark.parametrize("Bt", [3, 4])
+def test_decode_streaming_kernels_up_to_four_sequences(Bt):
+    """The streaming kernels serve up to four sequences (by default they are used up to two, where they are
+    the faster form): the same checks with the threshold raised."""
+    cfg = W.CONFIGS["c2"]
+    w, qw, sc = oracle_setup(cfg)
+    try:
+        Q.lib().quamba_debug_set_gemv_max_rows(4)
+        _decode_steps(cfg, Bt, 2, qw, sc, fused_dt=(Bt % 2 == 1))
+    finally:
+        Q.lib().quamba_debug_set_gemv_max_rows(-1)
 
 
 def test_prefill_then_decode_handoff():

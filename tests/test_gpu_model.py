@@ -185,6 +185,7 @@ def test_few_sequence_generation_kernels_match_the_general_path(Bt, d_model, d_i
     wsd = workspace(Q.quamba_model_workspace_bytes(gm, Bt, 1))
     res = []
     try:
+        Q.lib().quamba_debug_set_gemv_max_rows(4)  # the few-row kernels up to the 4 rows they serve (default: 2)
         for fuse in (1, 0):
             Q.lib().quamba_debug_set_fuse_decode(fuse)
             ssm, cs = _states(cfg, nlayers, Bt)
@@ -198,6 +199,7 @@ def test_few_sequence_generation_kernels_match_the_general_path(Bt, d_model, d_i
             res.append(steps)
     finally:
         Q.lib().quamba_debug_set_fuse_decode(1)
+        Q.lib().quamba_debug_set_gemv_max_rows(-1)
     for (la, sa, ca), (lb, sb, cb) in zip(*res):
         assert rel_err(la, lb) <= 2e-2
         assert rel_err(sa, sb) <= 2e-2
