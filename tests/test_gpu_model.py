@@ -206,9 +206,9 @@ def test_few_sequence_generation_kernels_match_the_general_path(Bt, d_model, d_i
         assert (ca.view(np.uint16) != cb.view(np.uint16)).mean() <= 2e-3
 
 
-@pytest.mark.parametrize("Bt,d_model,d_inner", [(24, 256, 512), (64, 256, 512), (7, 512, 1024)])
+@pytest.mark.parametrize("Bt,d_model,d_inner", [(24, 256, 512), (64, 256, 512), (7, 512, 1024), (3, 256, 512), (4, 512, 1024)])
 def test_many_sequence_generation_fusions_are_the_general_path_bit_for_bit(Bt, d_model, d_inner):
-    """With more than 4 sequences the projections whose K is split over the grid hand their partial sums to
+    """With more than 2 sequences the projections whose K is split over the grid hand their partial sums to
     the kernel that follows (x_proj to the scan step, out_proj to the next block's add + norm + quantization)
     instead of a reduce kernel.  Integer sums, the same roundings: logits, states and tokens must be the same
     bits as with the separate kernels."""
