@@ -16,7 +16,8 @@ Pins (tests/test_oracle_*.py): Hadamard orthogonality and the Sylvester closed f
 fold identity of the output projection, quantizer error bound / saturation / idempotence,
 nearest-rank percentile vs a sort, integer GEMM vs int64 loops, conv vs an explicit
 Toeplitz product and causality, scan vs cumulative sum / unrolled sum / chunk splitting /
-the LTI error bound of Theorem 4.1; the model shell: final norm closed form, head of a one-hot
+the LTI error bound of Theorem 4.1; the fused residual add + RMSNorm + quantizer vs its closed form
+on constant rows (graded weight; eps inside the root); the model shell: final norm closed form, head of a one-hot
 vector, and generation by carried state against re-running the prefill on the grown sequence.
 
 parity unpinned: the end-to-end numbers of ``q_prefill`` / ``q_decode`` (the paper prints

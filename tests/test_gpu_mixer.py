@@ -35,7 +35,8 @@ def check_chain(cfg, qw, sc, u, r, h0=None, rows=None, chans=None, decode_state=
     assert np.array_equal(r["u_q"][rs], u_q)
     # S1 in_proj
     acc = O.int_matmul(r["u_q"][rs], qw["W_in"])
-    assert np.array_equal(r["acc_in"][rs], acc)
+    if "acc_in" in r:  # the raw sums are absent when the run took the row-staged epilogues (as an untapped call does)
+        assert np.array_equal(r["acc_in"][rs], acc)
     assert np.array_equal(r["xz_q"][rs, :Di], O.requant_acc(acc[:, :Di], sc["m_in_x"]))
     assert np.array_equal(r["xz_q"][rs, Di:], O.requant_acc(acc[:, Di:], sc["m_in_z"]))
     # S2 conv
@@ -51,7 +52,8 @@ def check_chain(cfg, qw, sc, u, r, h0=None, rows=None, chans=None, decode_state=
     stats["x_q_flip"] = float((got != want).mean())
     # S3 x_proj
     acc = O.int_matmul(r["x_q"][rs], qw["W_x"])
-    assert np.array_equal(r["acc_x"][rs], acc)
+    if "acc_x" in r:
+        assert np.array_equal(r["acc_x"][rs], acc)
     assert np.array_equal(r["dbc_q"][rs, :R], O.requant_acc(acc[:, :R], sc["m_x_dt"]))
     assert np.array_equal(r["dbc_q"][rs, R:R + N], O.requant_acc(acc[:, R:R + N], sc["m_x_B"]))
     assert np.array_equal(r["dbc_q"][rs, R + N:], O.requant_acc(acc[:, R + N:], sc["m_x_C"]))
@@ -67,20 +69,23 @@ def check_chain(cfg, qw, sc, u, r, h0=None, rows=None, chans=None, decode_state=
                                      xz3[:, :, Di + cs], dbc3[..., R:R + N], dbc3[..., R + N:], qw["A"][cs],
                                      qw["D"][cs], qw["dt_bias"][cs], sc, None if hh is None else hh[:, cs])
     assert np.isfinite(g16_ref.astype(np.float32)).all(), "workload overflows fp16: not a valid parity case"
-    stats["scan_err"] = rel_err(r["y_f32"].reshape(Bt, L, Di)[:, :, cs], g_ref)
-    assert stats["scan_err"] <= 1e-3
+    if "y_f32" in r:
+        stats["scan_err"] = rel_err(r["y_f32"].reshape(Bt, L, Di)[:, :, cs], g_ref)
+        assert stats["scan_err"] <= 1e-3
     assert rel_err(r["g16"].reshape(Bt, L, Di)[:, :, cs].astype(np.float64), g_ref) <= 1e-3
     if "h" in r:
         assert rel_err(r["h"][:, cs], h_ref) <= 1e-3
     # S6 Hadamard + quant
     gH_ref, gHq_ref = O.q_hadamard_quant(r["g16"][rs], sc)
-    stats["had_err"] = rel_err(r["gH_f32"][rs], gH_ref)
-    assert stats["had_err"] <= 1e-5
+    if "gH_f32" in r:
+        stats["had_err"] = rel_err(r["gH_f32"][rs], gH_ref)
+        assert stats["had_err"] <= 1e-5
     assert_lsb(r["gH_q"][rs], gHq_ref, "gH_q")
     stats["gH_q_flip"] = float((r["gH_q"][rs] != gHq_ref).mean())
     # S7 out_proj
     acc, out = O.q_out_proj(r["gH_q"][rs], qw["W_outH"], sc)
-    assert np.array_equal(r["acc_out"][rs], acc)
+    if "acc_out" in r:
+        assert np.array_equal(r["acc_out"][rs], acc)
     assert np.array_equal(r["out"].reshape(M, Dm)[rs].view(np.uint16), out.view(np.uint16))
     return stats
 
@@ -182,6 +187,44 @@ def test_prefill_c3_layer_shape_sampled():
     rows, chans = _sampled(cfg, cfg.batch, cfg.seqlen, 3)
     st = check_chain(cfg, qw, sc, u, r, h0=h0, rows=rows, chans=chans)
     print("c3-layer", st)
+
+
+
+# Taps that are copies of the library's own intermediate buffers: asking for them changes no kernel,
+# so a run with them launches exactly what a call without taps (the call the benchmark times) launches:
+# the row-staged GEMM epilogues and dt_proj inside the scan's first pass.
+COPY_TAPS = ["u_q", "xz_q", "x_q", "dbc_q", "dt_q", "g16", "gH_q"]
+
+
+@pytest.mark.parametrize("name", ["c1", "c3", "c4"])
+def test_prefill_untapped_path_at_full_size(name):
+    """The path `bench.py` times, at the configured shapes: (i) with the copy taps only, every link against
+    the oracle (all rows at c1, sampled rows and channels at c3 / c4); (ii) with no taps at all: output and
+    states are the same bits as (i); (iii) c1: the output against the oracle's own end-to-end run."""
+    cfg = W.CONFIGS[name]
+    w, qw, sc = oracle_setup(cfg)
+    u = W.make_hidden(cfg)
+    h0 = None
+    if name == "c3":
+        h0 = (np.random.default_rng(8).standard_normal((cfg.batch, cfg.d_inner, 16)) * 0.1).astype(np.float32)
+    qd = qweights_to_dev(qw)
+    r = run_prefill(cfg, qd, sc, u, h0=h0, tap_names=COPY_TAPS)
+    rows, chans = (None, None) if name == "c1" else _sampled(cfg, cfg.batch, cfg.seqlen, 11)
+    st = check_chain(cfg, qw, sc, u, r, h0=h0, rows=rows, chans=chans)
+    r0 = run_prefill(cfg, qd, sc, u, h0=h0, taps=False)
+    assert np.array_equal(r0["out"].view(np.uint16), r["out"].view(np.uint16))
+    assert np.array_equal(r0["h"].view(np.uint32), r["h"].view(np.uint32))
+    assert np.array_equal(r0["conv_state"].view(np.uint16), r["conv_state"].view(np.uint16))
+    # the float taps switch on one more store in the scan and the Hadamard kernel, nothing else
+    r1 = run_prefill(cfg, qd, sc, u, h0=h0, tap_names=COPY_TAPS + ["y_f32", "gH_f32"])
+    check_chain(cfg, qw, sc, u, r1, h0=h0, rows=rows, chans=chans)
+    assert np.array_equal(r1["out"].view(np.uint16), r["out"].view(np.uint16))
+    if name == "c1":
+        ref = O.q_prefill(qw, sc, u)
+        e = end_to_end(r0, ref, name)
+        assert rel_err(r0["h"], ref["h"]) <= 2e-2
+        assert np.array_equal(r0["conv_state"].view(np.uint16), ref["conv_state"].view(np.uint16))
+        print(name, st, "end-to-end", e)
 
 
 def _decode_steps(cfg, Bt, steps, qw, sc, check_every=1, fused_dt=False):

@@ -38,6 +38,9 @@ GEMM_SHAPES = [
     (1, 10240, 2560, 0), (4, 2560, 5120, 0), (8, 192, 5120, 0), (3, 5120, 160, 32), (2, 12, 48, 0), (7, 768, 1536, 0),
     # more than 512 tiles of 64 x 64 with deep K (the 128-byte-slice form), as in the 1024- and 256-token prefills
     (1024, 2560, 5120, 0), (256, 10240, 2560, 0),
+    # in_proj and out_proj of the 2.8B layer at 2048 tokens, exactly as the benchmark launches them: 256 x 320
+    # tiles over a ring that wraps 20 times, and 128 x 160 tiles with two K groups and 256-byte slices
+    (2048, 10240, 2560, 0), (2048, 2560, 5120, 0),
 ]
 
 
@@ -101,6 +104,42 @@ def test_gemm_acc_and_requant_bit_exact(M, N, K, pad):
     goth = host(outh)
     assert np.array_equal(goth[:, :N].view(np.uint16), want_h.view(np.uint16))
     assert not goth[:, N:].any()
+
+
+@pytest.mark.parametrize("M,N,K", [(16384, 10240, 2560), (16384, 2560, 5120),  # the 2.8B layer at 4 x 4096 tokens
+                                   (16384, 16384, 4096), (16384, 4096, 8192),  # the Jamba-shaped layer at 16384 tokens
+                                   (16384, 320, 8192), (16384, 8192, 256)])    # its x_proj and dt_proj
+def test_gemm_large_shapes_sampled_rows(M, N, K):
+    """The big projections at their full sizes: raw sums and both epilogues on sampled rows against the oracle
+    (which computes those rows one by one), and the row-staged epilogue (no raw sums asked for) against the
+    direct one on every element."""
+    rng = np.random.default_rng(M + N * 3 + K)
+    A = rng.integers(-128, 128, (M, K), dtype=np.int8)
+    Wt = rng.integers(-128, 128, (N, K), dtype=np.int8)
+    A[0] = -128
+    Wt[0] = -128
+    rows = np.unique(np.concatenate([[0, 1, 255, 256, M // 2, M - 257, M - 1], rng.integers(0, M, 57)]))
+    acc_ref = O.int_matmul(A[rows], Wt)
+    e0, e1 = (N // 4) // 4 * 4, (N // 2) // 4 * 4
+    mult = np.array([3.1e-5, 7.7e-5, 1.9e-4], dtype=np.float32) * np.float32(5120.0 / K)
+    want = np.concatenate([O.requant_acc(acc_ref[:, :e0], mult[0]), O.requant_acc(acc_ref[:, e0:e1], mult[1]),
+                           O.requant_acc(acc_ref[:, e1:], mult[2])], axis=1)
+    dA, dW, drows = dev(A), dev(Wt), dev(rows)
+    ws = workspace(Q.quamba_gemm_workspace_bytes(M, N, K))
+    acc = empty((M, N), torch.int32)
+    out = torch.zeros((M, N), dtype=torch.int8, device="cuda:0")
+    Q.quamba_gemm_i8(dA, K, dW, K, M, N, K, e0, e1, mult, out, None, N, acc, ws)
+    assert np.array_equal(host(acc[drows]), acc_ref)
+    assert np.array_equal(host(out[drows]), want)
+    del acc
+    out3 = torch.zeros((M, N), dtype=torch.int8, device="cuda:0")
+    Q.quamba_gemm_i8(dA, K, dW, K, M, N, K, e0, e1, mult, out3, None, N, None, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out3)
+    outh = torch.zeros((M, N), dtype=torch.float16, device="cuda:0")
+    Q.quamba_gemm_i8(dA, K, dW, K, M, N, K, N, N, mult, None, outh, N, None, ws)
+    want_h = (acc_ref.astype(np.float32) * mult[0]).astype(np.float16)
+    assert np.array_equal(host(outh[drows]).view(np.uint16), want_h.view(np.uint16))
 
 
 def test_gemm_rejects_bad_arguments():
@@ -195,7 +234,9 @@ def test_scan_prefill(Bt, L, Di, with_h0):
 
 @pytest.mark.parametrize("Bt,L,Di,R,with_h0", [(1, 1, 64, 16, False), (2, 45, 128, 48, True), (1, 300, 320, 160, False),
                                                 (3, 67, 192, 32, True), (1, 1000, 256, 256, True),
-                                                (1, 256, 1536, 48, False), (1, 130, 100, 80, False)])
+                                                (1, 256, 1536, 48, False), (1, 130, 100, 80, False),
+                                                # the 2.8B layer at 2048 tokens and the Jamba-shaped one at 4096
+                                                (1, 2048, 5120, 160, False), (1, 4096, 8192, 256, True)])
 def test_scan_prefill_with_fused_dt_proj(Bt, L, Di, R, with_h0):
     """dt_q computed inside the scan's first pass: bit-exact codes, same scan tolerances."""
     rng = np.random.default_rng(L * 17 + Di + R)

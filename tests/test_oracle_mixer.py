@@ -331,3 +331,43 @@ def test_add_rmsnorm_quant():
                                 (r.astype(np.float32) * 4).astype(np.float16), wt,
                                 np.float32(127.0 / 4.0), eps=0.0)
     assert np.abs(q2.astype(int) - q.astype(int)).max() <= 1
+
+
+def test_add_rmsnorm_quant_closed_form_places_weight_and_eps():
+    """Section 4.3 "Fused RMSNorm", written out for rows whose sum is a constant c: RMSNorm gives
+    w_j c / sqrt(c^2 + eps) in column j, so the codes are q(w_j c / sqrt(c^2 + eps) / s).  A graded
+    weight pins the weight multiply (position and per-column use); a small c makes eps matter: with
+    c^2 = eps the factor is 1/sqrt(2), with eps outside the root it would be 1/(1 + sqrt(eps)/|c|) = 1/2,
+    without eps 1."""
+    Dm = 64
+    w = np.linspace(0.5, 1.5, Dm).astype(np.float16)
+    inv_s = np.float32(127.0 / 2.0)
+    # |c| = 3: eps is negligible, the weight is not
+    half = np.full((2, Dm), 1.5, dtype=np.float16)
+    half[1] = -1.5
+    q, res = O.add_rmsnorm_quant(half, half, w, inv_s, eps=1e-5)
+    assert np.array_equal(res, (half * 2).astype(np.float16))
+    y = w.astype(np.float64) * 3.0 / np.sqrt(9.0 + 1e-5)
+    want = np.clip(np.rint((y.astype(np.float32) * inv_s)), -128, 127).astype(np.int8)
+    assert np.array_equal(q[0], want) and np.array_equal(q[1], -want)
+    assert len(np.unique(q[0])) > 30  # the weight really grades the row
+    # c^2 = eps exactly (c = 2^-6, eps = 2^-12): the three placements of eps give three different rows
+    c, eps = 2.0 ** -6, 2.0 ** -12
+    a = np.full((1, Dm), c, dtype=np.float16)
+    q, res = O.add_rmsnorm_quant(a, np.zeros_like(a), w, inv_s, eps=eps)
+    inside = np.rint((w.astype(np.float64) / np.sqrt(2.0)).astype(np.float32) * inv_s).astype(np.int8)
+    outside = np.rint((w.astype(np.float64) / 2.0).astype(np.float32) * inv_s).astype(np.int8)
+    absent = np.rint(w.astype(np.float32) * inv_s).astype(np.int8)
+    assert np.array_equal(q[0], inside)
+    assert not np.array_equal(inside, outside) and not np.array_equal(inside, absent)
+    # a non-constant row against the definition written out element by element in plain Python
+    rng = np.random.default_rng(3)
+    xo = rng.standard_normal((1, 8)).astype(np.float16)
+    xr = rng.standard_normal((1, 8)).astype(np.float16)
+    w8 = np.linspace(0.25, 2.0, 8).astype(np.float16)
+    q, res = O.add_rmsnorm_quant(xo, xr, w8, np.float32(127.0 / 6.0), eps=1e-5)
+    ssum = [float(np.float16(np.float32(xo[0, j]) + np.float32(xr[0, j]))) for j in range(8)]
+    ms = sum(v * v for v in ssum) / 8.0
+    for j in range(8):
+        yj = np.float32(ssum[j] / (ms + 1e-5) ** 0.5 * float(w8[j]))
+        assert q[0, j] == int(np.clip(np.rint(yj * np.float32(127.0 / 6.0)), -128, 127))
