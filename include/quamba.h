@@ -358,6 +358,22 @@ int quamba_mixer_decode_q(const quamba_dims *dims, const quamba_qweights *qw,
                           quamba_half *out, float *ssm_state, quamba_half *conv_state,
                           const quamba_taps *taps, void *ws, size_t ws_bytes, void *stream);
 
+/* quamba_mixer_decode for callers that cannot allocate device memory and have no workspace to pass:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same step,
+ * same kernels, same results bit for bit; the scratch is a buffer of QUAMBA_NOALLOC_SCRATCH_BYTES built
+ * into the library's device image (every GPU the library runs on holds it until the process ends).
+ * The call allocates and frees nothing.  A step that needs more than the buffer (quamba_workspace_bytes(dims,
+ * Bt, 1) > QUAMBA_NOALLOC_SCRATCH_BYTES; the 2.8B layer fits up to 128 sequences) is refused with
+ * QUAMBA_EWORKSPACE.  The device that `stream` belongs to must be current.  All calls on one GPU share
+ * that GPU's buffer: calls that overlap on one GPU (different streams or threads) race; nothing in the
+ * buffer has to start at zero, every step overwrites what it reads.  The first call on a device looks
+ * the buffer's address up (not a stream operation: make one call before capturing a graph). */
+#define QUAMBA_NOALLOC_SCRATCH_BYTES (48u << 20)
+int quamba_mixer_decode_noalloc(const quamba_dims *dims, const quamba_qweights *qw,
+                                const quamba_scales *sc /* host */, const quamba_half *u, int Bt,
+                                quamba_half *out, float *ssm_state, quamba_half *conv_state,
+                                const quamba_taps *taps, void *stream);
+
 /* Fused residual add + RMSNorm + static quantization between blocks (Section 4.3 "Fused
  * RMSNorm"): res <- fp16(x_out + res) in place; u_q = q(RMSNorm(res) * weight, 1/s) with
  * the norm taken in fp32 over the stored fp16 residual.

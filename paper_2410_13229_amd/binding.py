@@ -14,7 +14,7 @@ __all__ = [
     "SCALE_FIELDS", "scales_from_dict", "scales_to_dict", "make_qweights", "make_dims",
     "quamba_last_error", "quamba_workspace_bytes", "quamba_calibrate_workspace_bytes",
     "quamba_calibrate", "quamba_mixer_prefill", "quamba_mixer_prefill_q", "quamba_mixer_decode",
-    "quamba_mixer_decode_q", "quamba_add_rmsnorm_quant", "quamba_quantize_f16", "quamba_gemm_i8",
+    "quamba_mixer_decode_q", "quamba_mixer_decode_noalloc", "quamba_add_rmsnorm_quant", "quamba_quantize_f16", "quamba_gemm_i8",
     "quamba_gemm_workspace_bytes", "quamba_conv_silu_quant", "quamba_conv_step", "quamba_scan_workspace_bytes",
     "quamba_scan_prefill", "quamba_scan_prefill_dtproj", "quamba_scan_step", "quamba_hadamard_quant",
     "Layer", "Model", "make_model", "quamba_model_workspace_bytes", "quamba_model_prefill", "quamba_model_decode",
@@ -257,6 +257,7 @@ def lib():
     dec = [P(Dims), P(QWeights), P(Scales), vp, i, vp, vp, vp, P(Taps), vp, sz, vp]
     L.quamba_mixer_decode.argtypes = dec
     L.quamba_mixer_decode_q.argtypes = dec
+    L.quamba_mixer_decode_noalloc.argtypes = [P(Dims), P(QWeights), P(Scales), vp, i, vp, vp, vp, P(Taps), vp]
     L.quamba_add_rmsnorm_quant.argtypes = [vp, vp, vp, f, f, vp, i, i, vp]
     L.quamba_quantize_f16.argtypes = [vp, vp, sz, f, vp]
     L.quamba_gemm_i8.argtypes = [vp, i, vp, i, i, i, i, i, i, P(C.c_float), vp, vp, i, vp, vp, sz, vp]
@@ -332,7 +333,8 @@ def lib():
     for name in ("quamba_calibrate_x_rule", "quamba_clip_search", "quamba_mixer_fp32"):
         getattr(L, name).restype = C.c_int
     for name in ("quamba_calibrate", "quamba_mixer_prefill", "quamba_mixer_prefill_q", "quamba_mixer_decode",
-                 "quamba_mixer_decode_q", "quamba_add_rmsnorm_quant", "quamba_quantize_f16", "quamba_gemm_i8",
+                 "quamba_mixer_decode_q", "quamba_mixer_decode_noalloc", "quamba_add_rmsnorm_quant",
+                 "quamba_quantize_f16", "quamba_gemm_i8",
                  "quamba_conv_silu_quant", "quamba_conv_step", "quamba_scan_prefill", "quamba_scan_step",
                  "quamba_scan_prefill_dtproj", "quamba_hadamard_quant"):
         getattr(L, name).restype = C.c_int
@@ -535,6 +537,12 @@ def quamba_mixer_decode(dims, qw, sc, u, Bt, out, ssm_state, conv_state, taps, w
     _check(lib().quamba_mixer_decode(C.byref(_dims(dims)), C.byref(_struct_of_ptrs(QWeights, qw)),
                                      C.byref(scales_from_dict(sc)), _ptr(u), Bt, _ptr(out), _ptr(ssm_state),
                                      _ptr(conv_state), _taps(taps), _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def quamba_mixer_decode_noalloc(dims, qw, sc, u, Bt, out, ssm_state, conv_state, taps, stream=None):
+    _check(lib().quamba_mixer_decode_noalloc(C.byref(_dims(dims)), C.byref(_struct_of_ptrs(QWeights, qw)),
+                                             C.byref(scales_from_dict(sc)), _ptr(u), Bt, _ptr(out), _ptr(ssm_state),
+                                             _ptr(conv_state), _taps(taps), _stream(stream)))
 
 
 def quamba_mixer_decode_q(dims, qw, sc, u_q, Bt, out, ssm_state, conv_state, taps, ws, stream=None):

@@ -1,8 +1,14 @@
 // C-ABI entry points: argument checks, workspace carving and the order of kernel launches of
 // the quantized mixer (Sections 4.2 and 4.3).  No arithmetic of the method lives here.
 #include <cstring>
+#include <mutex>
 
 #include "common.h"
+
+// Scratch of quamba_mixer_decode_noalloc: the workspace of one generation step, held by every GPU the
+// library runs on until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress; kernels and copies get the per-device address kept in g_scratch_ptr.
+static __device__ __align__(256) unsigned char scratch[QUAMBA_NOALLOC_SCRATCH_BYTES];
 
 namespace quamba {
 
@@ -766,6 +772,48 @@ int quamba_mixer_decode_hadx(const quamba_dims *dims, const quamba_qweights *qw,
 }
 
 }  // extern "C"
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices] = {};  // address of `scratch` on each device, resolved on first use
+
+// Address of the current device's copy of `scratch` (each GPU has its own, at its own address).
+int scratch_of_current_device(void **out) {
+  int dev = -1;
+  QUAMBA_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(QUAMBA_EUNSUPPORTED, "device index %d outside [0, %d)", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    QUAMBA_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p || !aligned(p, 256)) return fail(QUAMBA_EHIP, "scratch symbol resolved to %p", p);
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return QUAMBA_OK;
+}
+
+}  // namespace
+
+extern "C" int quamba_mixer_decode_noalloc(const quamba_dims *dims, const quamba_qweights *qw, const quamba_scales *sc,
+                                           const quamba_half *u, int Bt, quamba_half *out, float *ssm_state,
+                                           quamba_half *conv_state, const quamba_taps *taps, void *stream) {
+  if (!u) return fail(QUAMBA_EINVAL, "u is NULL");
+  QUAMBA_TRY(check_dims(dims));
+  if (Bt < 1) return fail(QUAMBA_EINVAL, "batch=%d must be >= 1", Bt);
+  const size_t need = make_plan(dims, Bt, 1).total;
+  if (need > sizeof(scratch))
+    return fail(QUAMBA_EWORKSPACE, "decode_noalloc: a step of %d sequences at d_model=%d d_inner=%d needs %zu bytes of "
+                                   "scratch, the built-in buffer holds %zu; use quamba_mixer_decode with a workspace",
+                Bt, dims->d_model, dims->d_inner, need, sizeof(scratch));
+  void *ws = nullptr;
+  QUAMBA_TRY(scratch_of_current_device(&ws));
+  return run_mixer(dims, qw, sc, reinterpret_cast<const __half *>(u), nullptr, Bt, 1, true,
+                   reinterpret_cast<__half *>(out), ssm_state, reinterpret_cast<__half *>(conv_state), taps, ws,
+                   sizeof(scratch), as_stream(stream));
+}
 
 extern "C" void quamba_debug_set_fuse_dt(int v) { quamba::g_fuse_dt = v; }
 extern "C" void quamba_debug_set_fuse_decode(int v) { quamba::g_fuse_decode = v; }
