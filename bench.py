@@ -482,7 +482,11 @@ def main():
     dom = max(single, key=lambda k: single[k]["us"])
     roof = {k: stages[dom][k] for k in ("bound", "achieved", "peak", "unit", "frac")}
     roof.update({"kernel": dom, "us_per_launch": stages[dom]["us"],
-                 "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name)})
+                 "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
+                 "traffic_source": "stored counter figure, not measured in this run: rocprofv3 --pmc FETCH_SIZE / "
+                                   "WRITE_SIZE of `bench.py --probe`, scaled by a plain copy "
+                                   "(profiles/in_proj_gemm_c1_hbm_traffic.txt)"
+                                   if MEASURED_TRAFFIC_BYTES.get(cfg.name) else None})
 
     # ---- decode: batch 64, consecutive steps on carried state, distinct seeded inputs
     decode = None
@@ -598,6 +602,23 @@ def main():
         cpu = {"value": round(reps * Bt * Ls / csec, 1), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
                "sample": f"{reps} oracle q_prefill calls over {Ls}-token sequences of the same workload "
                          f"({csec:.1f} s wall; BLAS matmuls threaded, the recurrence is single-threaded numpy)"}
+        if decode is not None:
+            # the generation leg: 20 consecutive oracle steps of the batch-64 workload on carried states (the GPU
+            # figure above is the mean of 1000; the oracle's per-step cost does not depend on the step index)
+            c2 = W.CONFIGS["c2"]
+            o_ssm, o_cs = W.make_decode_state(c2)
+            dsteps, dsec_cpu = 20, 0.0
+            for s_i in range(dsteps + 1):
+                ui = W.make_hidden(c2, batch=c2.batch, seqlen=1, stream=500 + s_i)[:, 0]
+                t0 = time.perf_counter()
+                r_i = O.q_decode(qw_np, scd, ui, o_ssm, o_cs)
+                if s_i > 0:  # the first call warms the BLAS threads up
+                    dsec_cpu += time.perf_counter() - t0
+                o_ssm, o_cs = r_i["h"], r_i["conv_state"]
+            cpu["decode"] = {"value": round(dsec_cpu / dsteps * 1e6, 1), "unit": "us/step", "cores": int(cores),
+                             "kind": "oracle",
+                             "sample": f"{dsteps} consecutive oracle q_decode steps at batch {c2.batch} on carried "
+                                       f"states ({dsec_cpu:.1f} s wall), after one warm-up step"}
 
     line = {
         "metric": "w8a8_mamba_mixer_prefill_tokens_per_s",
