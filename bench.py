@@ -32,6 +32,46 @@ SCAN_FLOP_PER_TD = 123.0     # 16 x (exp + 2 mul + 2 fma) + D*x + softplus + gat
 MEASURED_TRAFFIC_BYTES = {"c1": 89.6e6}
 
 
+def instruction_rates(Q, torch, np, dev, stream):
+    """Issue rates of the instruction classes the roofline statements rest on, from register-only loops on
+    every SIMD at once (256 CUs x 4 SIMDs x 1, 2 or 4 waves).  Per probe: instructions per second and SIMD,
+    and cycles per instruction with the clock taken from the fp32 FMA probe of the same occupancy (a wave64
+    FMA occupies a 16-lane SIMD for 4 cycles); the matrix probes report POP/s (65536 operations per
+    v_mfma_i32_32x32x32_i8) and the fraction of the published 5.0 POP/s."""
+    probes = [("fma_f32", Q.PROBE_FMA_F32, 40000), ("exp_f32", Q.PROBE_EXP_F32, 20000),
+              ("scan_state_update", Q.PROBE_SCAN_MIX, 8000), ("mfma_i8_zero_operands", Q.PROBE_MFMA_I8, 20000),
+              ("mfma_i8_random_operands", Q.PROBE_MFMA_I8_RANDOM, 20000)]
+    out = {"probe": "register-only loops, 256 CUs x 4 SIMDs", "rates": {}}
+    rng = np.random.default_rng(241013229)
+    for wps in (1, 2, 4):
+        ws = torch.zeros(Q.quamba_probe_workspace_bytes(wps), dtype=torch.uint8, device=dev)
+        ws[:4096] = torch.from_numpy(rng.integers(0, 256, 4096, dtype=np.uint8)).to(dev)
+        res = {}
+        for name, pid, iters in probes:
+            for _ in range(3):
+                n = Q.quamba_probe_rate(pid, wps, iters, ws, stream)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            reps = 5
+            e0.record(stream)
+            for _ in range(reps):
+                Q.quamba_probe_rate(pid, wps, iters, ws, stream)
+            e1.record(stream)
+            e1.synchronize()
+            sec = e0.elapsed_time(e1) * 1e-3 / reps
+            res[name] = {"instr_per_s_per_simd": n / sec / 1024.0, "us_per_launch": round(sec * 1e6, 1)}
+        clock = 4.0 * res["fma_f32"]["instr_per_s_per_simd"]  # Hz, if the FMA probe issues every 4 cycles
+        for name, r in res.items():
+            r["cycles_per_instr"] = round(clock / r["instr_per_s_per_simd"], 2)
+            if name.startswith("mfma"):
+                r["POP_per_s"] = round(r["instr_per_s_per_simd"] * 1024 * 65536 / 1e15, 3)
+                r["frac_of_5_POPs"] = round(r["POP_per_s"] / 5.0, 3)
+            r["instr_per_s_per_simd"] = round(r["instr_per_s_per_simd"] / 1e6, 1)
+        res["clock_GHz_from_fma"] = round(clock / 1e9, 3)
+        out["rates"][f"{wps}_waves_per_simd"] = res
+    out["units"] = {"instr_per_s_per_simd": "1e6 / s", "scan_state_update": "one update = mul, exp, mul, fma, fma"}
+    return out
+
+
 def alloc_qweights(cfg, torch, dev):
     """Empty device tensors for one layer's quantized weights (filled by the library's calibration)."""
     Dm, Di, N, R = cfg.d_model, cfg.d_inner, cfg.d_state, cfg.dt_rank
@@ -285,6 +325,9 @@ def main():
     ap.add_argument("--model-distinct", type=int, default=4,
                     help="distinct random-init layers generated on the host; the stack cycles through copies of "
                          "them, every layer in device memory of its own")
+    ap.add_argument("--rates", action="store_true",
+                    help="instruction-rate probes (fp32 FMA, v_exp_f32, the scan's state update, int8 MFMA with zero and "
+                         "with random operands) instead of the benchmark; one JSON line")
     ap.add_argument("--probe", action="store_true",
                     help="counter-collection mode: a plain 256 MiB device copy (calibration) and 20 launches "
                          "of each stage, nothing else")
@@ -305,6 +348,10 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     stream = torch.cuda.current_stream()
+
+    if args.rates:
+        print(json.dumps(instruction_rates(Q, torch, np, dev, stream)))
+        return
 
     cfg = W.CONFIGS[args.workload]
     Bt, L = cfg.batch, cfg.seqlen

@@ -19,9 +19,13 @@
  *     synchronise the stream to hand the scales back in host memory, and graph-replayed
  *     generation (quamba_model_generate with use_graph), which waits for its last replay and
  *     lets the HIP runtime allocate what its graph objects need.
- *   - the library keeps no state between calls: calls that share no output, state or workspace
- *     buffer may be in flight on different streams at once (independent sequences overlap well:
- *     one call's projections use the matrix cores while another's scan uses the vector units).
+ *   - calls that share no output, state or workspace buffer may be in flight on different
+ *     streams (and from different host threads) at once; independent sequences overlap well: one
+ *     call's projections use the matrix cores while another's scan uses the vector units.  What the
+ *     library keeps between calls: the process-wide tuning hooks at the end of this file (defaults =
+ *     the measured choices; only tests and tuning runs touch them), the per-device scratch buffer of
+ *     quamba_mixer_decode_noalloc (its calls on one GPU must not overlap), and the one-time
+ *     per-device set-up of kernel attributes.
  *   - alignment: workspaces 256 bytes; weights, conv_b, fp16 / int8 activations and ssm_state 16
  *     bytes; conv_state and fp16 outputs 8 bytes (what any allocator returns; a view that starts
  *     inside a tensor may not qualify and is refused with QUAMBA_EINVAL).
@@ -431,6 +435,11 @@ int quamba_conv_step(const int8_t *xpre_q, int ldx, const int8_t *w_q, const flo
  * ldbc (columns of the x_proj output); A_q [Di, 16]; D_q [Di]; dt_bias [Di] fp32.
  *   g16   [Bt*L, Di] fp16 out          y_f32 (may be NULL) same shape, value before rounding
  *   ssm_state [Bt, Di, 16] fp32 in/out (NULL: zeros in, nothing out)
+ * Range of g16: the fp32 value is converted with round-to-nearest-even and NOT saturated: a gated output
+ * beyond the largest finite half (|g| >= 65520) becomes +-infinity, as the IEEE conversion defines (the
+ * recurrent state stays fp32 and is not affected).  The Hadamard stage then turns the whole token row into
+ * infinities / NaNs and its int8 codes are unspecified, so static scales must leave that margin: with the
+ * paper's observation of output outliers of a few hundred (Appendix I, J) the margin is two orders of magnitude.
  * quamba_scan_prefill runs a chunked three-pass scan over L; it needs
  * quamba_scan_workspace_bytes(Bt, L, Di) bytes of workspace.  quamba_scan_step is L = 1. */
 size_t quamba_scan_workspace_bytes(int Bt, int L, int Di);
@@ -548,6 +557,52 @@ int quamba_model_generate(const quamba_model *model, const int32_t *first_tokens
                           int n_new, int32_t *tokens_out, float *ssm_states,
                           quamba_half *conv_states, void *ws, size_t ws_bytes, int use_graph,
                           void *stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Diagnostics: instruction-rate probes behind the roofline statements (no part of the method).
+ * A probe is one kernel of register-only loops on every SIMD of the chip (256 CUs x 4 SIMDs x
+ * waves_per_simd waves, `iters` rounds); the caller times the launch and divides:
+ *   QUAMBA_PROBE_FMA_F32          8 independent v_fma_f32 per round
+ *   QUAMBA_PROBE_EXP_F32          8 independent v_exp_f32 per round (the decay factor of Eq. 1)
+ *   QUAMBA_PROBE_SCAN_MIX         8 state updates of Eq. 1 per round: multiply, exponential, multiply,
+ *                                 two multiply-adds each
+ *   QUAMBA_PROBE_MFMA_I8          4 independent v_mfma_i32_32x32x32_i8 per round, all-zero operands
+ *   QUAMBA_PROBE_MFMA_I8_RANDOM   the same with the caller's operands: the first 4096 bytes of `ws`
+ *                                 (4 operand registers x 64 lanes x 16 int8), e.g. seeded random codes
+ * *instr_per_call (host) receives the number of counted instructions (state updates for SCAN_MIX,
+ * 65536 integer operations per MFMA) of the launch.  Workspace: quamba_probe_workspace_bytes. */
+#define QUAMBA_PROBE_FMA_F32 0
+#define QUAMBA_PROBE_EXP_F32 1
+#define QUAMBA_PROBE_SCAN_MIX 2
+#define QUAMBA_PROBE_MFMA_I8 3
+#define QUAMBA_PROBE_MFMA_I8_RANDOM 4
+size_t quamba_probe_workspace_bytes(int waves_per_simd);
+int quamba_probe_rate(int probe, int waves_per_simd, int iters, double *instr_per_call /* host */,
+                      void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Tuning hooks: process-wide switches that choose between kernels which compute the same
+ * thing; tests use them to run the non-default forms, tuning runs to compare them.  Each is
+ * one atomic word that a call reads once at its start, so a call is consistent in itself; a
+ * hook changed while calls are in flight applies to whichever calls start after it.  Results
+ * do not depend on them beyond what the tests of the alternative forms state (bit-identical,
+ * except where a row's sum of squares is accumulated in another order).
+ *   quamba_debug_set_gemm_variant(v)   v >= 0 forces GEMM kernel configuration v (0..11) where the
+ *                                      shape allows it; -1 = chosen per shape (default)
+ *   quamba_debug_set_gemm_split(v)     v > 1 forces a K split into v ranges over the grid; 0 = default
+ *   quamba_debug_set_gemv_max_rows(v)  generation takes the few-row streaming kernels up to v
+ *                                      sequences (0..4); negative = default (2)
+ *   quamba_debug_set_fuse_dt(v)        0: dt_proj always as a GEMM of its own; 1 = default (inside
+ *                                      the scan where the shape allows and acc_dt is not tapped)
+ *   quamba_debug_set_fuse_decode(v)    0: generation without the fused epilogues and hand-overs
+ *                                      (conv step in in_proj, split-K sums added up by the consumer,
+ *                                      Hadamard inside out_proj, fused few-sequence kernels); 1 = default
+ * ------------------------------------------------------------------------------------- */
+void quamba_debug_set_gemm_variant(int v);
+void quamba_debug_set_gemm_split(int v);
+void quamba_debug_set_gemv_max_rows(int v);
+void quamba_debug_set_fuse_dt(int v);
+void quamba_debug_set_fuse_decode(int v);
 
 #ifdef __cplusplus
 }

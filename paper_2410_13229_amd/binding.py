@@ -27,6 +27,10 @@ __all__ = [
     "XFmt", "XFMT_FIELDS", "XFMT_E4M3", "XFMT_LOG2", "make_xfmt", "xfmt_to_dict", "quamba_calibrate_xfmt",
     "quamba_mixer_prefill_xfmt", "quamba_mixer_decode_xfmt", "quamba_x_encode", "quamba_xfmt_proj",
     "quamba_xdyn_workspace_bytes", "quamba_mixer_prefill_xdyn", "quamba_mixer_decode_xdyn",
+    "quamba_debug_set_gemm_variant", "quamba_debug_set_gemm_split", "quamba_debug_set_gemv_max_rows",
+    "quamba_debug_set_fuse_dt", "quamba_debug_set_fuse_decode",
+    "PROBE_FMA_F32", "PROBE_EXP_F32", "PROBE_SCAN_MIX", "PROBE_MFMA_I8", "PROBE_MFMA_I8_RANDOM",
+    "quamba_probe_workspace_bytes", "quamba_probe_rate",
 ]
 
 X_PERCENTILE, X_MSE_CLIP = 0, 1
@@ -338,6 +342,14 @@ def lib():
                  "quamba_conv_silu_quant", "quamba_conv_step", "quamba_scan_prefill", "quamba_scan_step",
                  "quamba_scan_prefill_dtproj", "quamba_hadamard_quant"):
         getattr(L, name).restype = C.c_int
+    for name in ("quamba_debug_set_gemm_variant", "quamba_debug_set_gemm_split", "quamba_debug_set_gemv_max_rows",
+                 "quamba_debug_set_fuse_dt", "quamba_debug_set_fuse_decode"):
+        getattr(L, name).argtypes = [i]
+        getattr(L, name).restype = None
+    L.quamba_probe_workspace_bytes.restype = sz
+    L.quamba_probe_workspace_bytes.argtypes = [i]
+    L.quamba_probe_rate.restype = C.c_int
+    L.quamba_probe_rate.argtypes = [i, i, i, P(C.c_double), vp, sz, vp]
     _LIB = L
     return L
 
@@ -661,3 +673,40 @@ def quamba_calibrate_block(dims, fp_weights, norm_w, eps, res, out, nb, Lc, x_pe
                                         nb, Lc, float(x_percentile), C.byref(oq), C.byref(sc), _ptr(ws), _nbytes(ws),
                                         _stream(stream)))
     return sc
+
+
+# ---- tuning hooks (process-wide switches between kernels that compute the same thing)
+def quamba_debug_set_gemm_variant(v):
+    lib().quamba_debug_set_gemm_variant(int(v))
+
+
+def quamba_debug_set_gemm_split(v):
+    lib().quamba_debug_set_gemm_split(int(v))
+
+
+def quamba_debug_set_gemv_max_rows(v):
+    lib().quamba_debug_set_gemv_max_rows(int(v))
+
+
+def quamba_debug_set_fuse_dt(v):
+    lib().quamba_debug_set_fuse_dt(int(v))
+
+
+def quamba_debug_set_fuse_decode(v):
+    lib().quamba_debug_set_fuse_decode(int(v))
+
+
+# ---- diagnostics: instruction-rate probes
+PROBE_FMA_F32, PROBE_EXP_F32, PROBE_SCAN_MIX, PROBE_MFMA_I8, PROBE_MFMA_I8_RANDOM = 0, 1, 2, 3, 4
+
+
+def quamba_probe_workspace_bytes(waves_per_simd) -> int:
+    return int(lib().quamba_probe_workspace_bytes(int(waves_per_simd)))
+
+
+def quamba_probe_rate(probe, waves_per_simd, iters, ws, stream=None) -> float:
+    """Enqueues one probe launch; returns the number of counted instructions of that launch."""
+    n = C.c_double(0.0)
+    _check(lib().quamba_probe_rate(int(probe), int(waves_per_simd), int(iters), C.byref(n), _ptr(ws), _nbytes(ws),
+                                   _stream(stream)))
+    return n.value

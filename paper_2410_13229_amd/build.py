@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libquamba.so")
-SOURCES = ["api.hip", "gemm_i8.hip", "elementwise.hip", "scan.hip", "hadamard.hip", "calibrate.hip", "model.hip", "decode_fused.hip", "gemm_xfmt.hip"]
+SOURCES = ["api.hip", "gemm_i8.hip", "elementwise.hip", "scan.hip", "hadamard.hip", "calibrate.hip", "model.hip", "decode_fused.hip", "gemm_xfmt.hip", "microbench.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + os.path.join(ROOT, "include"),
          "-I" + CSRC, "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -62,7 +62,7 @@ def build(verbose: bool = False) -> str:
         src, obj = pair
         return _run([HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj])
 
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
+    with ThreadPoolExecutor(max_workers=min(10, len(SOURCES))) as ex:
         for msg in ex.map(one, zip(SOURCES, objs)):
             if verbose and msg.strip():
                 print(msg, file=sys.stderr)

@@ -1,5 +1,6 @@
 // C-ABI entry points: argument checks, workspace carving and the order of kernel launches of
 // the quantized mixer (Sections 4.2 and 4.3).  No arithmetic of the method lives here.
+#include <atomic>
 #include <cstring>
 #include <mutex>
 
@@ -97,8 +98,9 @@ Plan make_plan(const quamba_dims *d, int Bt, int L, bool hadx = false, bool dyn 
   return p;
 }
 
-int g_fuse_dt = 1;      // tuning hook
-int g_fuse_decode = 1;  // tuning hook
+// Tuning hooks (process-wide; every call reads each of them once, at its start).
+std::atomic<int> g_fuse_dt_hook{1};
+std::atomic<int> g_fuse_decode_hook{1};
 
 int check_q(const quamba_qweights *qw, const quamba_scales *sc) {
   if (!qw || !sc) return fail(QUAMBA_EINVAL, "qweights or scales is NULL");
@@ -140,6 +142,9 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
               const quamba_xasym *xa = nullptr, const quamba_xfmt *xf = nullptr, const DynX *dyn = nullptr,
               OutPartial *defer_out = nullptr) {
   if (defer_out) defer_out->splits = 1;
+  const int g_fuse_dt = g_fuse_dt_hook.load(std::memory_order_relaxed);
+  const int g_fuse_decode = g_fuse_decode_hook.load(std::memory_order_relaxed);
+  const int g_gemv_max_rows = gemv_max_rows();
   QUAMBA_TRY(check_dims(d));
   QUAMBA_TRY(check_q(qw, sc));
   if ((!u && !u_q_in && !norm) || !out) return fail(QUAMBA_EINVAL, "input or output pointer is NULL");
@@ -195,6 +200,7 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
   // (the kernels serve up to 4; from 3 on the matrix-tile path with its fused epilogues is ahead:
   // 64 blocks at the 2.8B shape, 2.13 against 2.21 ms per step with 3 sequences, 2.30 against 2.45 with 4).
   const bool few = decode && M <= g_gemv_max_rows && Dm <= 8192 && g_fuse_decode && !hx && !xa && !xf && !dyn;
+  if (norm && !few) return fail(QUAMBA_EINVAL, "fused block input: the few-sequence kernels do not serve this call");
   // quantize the block input (Eq. 2)
   const int8_t *uq = u_q_in;
   if (!uq && !norm) {
@@ -219,12 +225,13 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
   } else {
     // in_proj: columns [0, Di) -> x_pre, [Di, 2Di) -> z
     // (generation: where the GEMM's epilogue can carry it, the conv step rides along: a kernel less)
+    const GemmPlan in_plan = gemm_plan(M, 2 * Di, Dm, base + p.gemm, p.gemm_bytes);
     const bool conv_in_gemm = decode && !hx && !xa && !xf && !dyn && g_fuse_decode && Di % 4 == 0 &&
-                              gemm_fuses_conv_step(M, 2 * Di, Dm, base + p.gemm, p.gemm_bytes);
+                              in_plan.fuses_conv_step();
     {
       GemmEpilogue e{xz_q, nullptr, t.acc_in, 2 * Di, Di, 2 * Di, sc->m_in_x, sc->m_in_z, sc->m_in_z};
       if (conv_in_gemm) e.conv = ConvStepEpi{x_q, qw->conv_w, qw->conv_b, conv_state, sc->s_cw, sc->s_xpre, inv_s_x};
-      QUAMBA_TRY(launch_gemm_i8(uq, Dm, qw->W_in, Dm, M, 2 * Di, Dm, e, base + p.gemm, p.gemm_bytes, st));
+      QUAMBA_TRY(launch_gemm_i8(uq, Dm, qw->W_in, Dm, M, 2 * Di, Dm, e, base + p.gemm, p.gemm_bytes, st, &in_plan));
       QUAMBA_TRY(tap_copy(t.xz_q, xz_q, (size_t)M * 2 * Di, st));
     }
     // causal conv + SiLU + requantization with the percentile scale of x
@@ -275,11 +282,12 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
     GemmEpilogue e{dbc_q, nullptr, t.acc_x, NX, R, R + N, hx ? hx->m_xh_dt : (xa ? xa->m_x_dt : sc->m_x_dt),
                    hx ? hx->m_xh_B : (xa ? xa->m_x_B : sc->m_x_B), hx ? hx->m_xh_C : (xa ? xa->m_x_C : sc->m_x_C),
                    xa ? xa->col_bias : nullptr};
-    x_splits = gemm_splits(M, NX, Di, base + p.gemm, p.gemm_bytes);
+    const GemmPlan x_plan = gemm_plan(M, NX, Di, base + p.gemm, p.gemm_bytes);
+    x_splits = x_plan.k_splits();
     dbc_part = decode && fuse_dt && g_fuse_decode && R <= 256 && !xa && !t.dbc_q && !t.acc_x && x_splits > 1 &&
                x_splits <= 8;
     e.defer_reduce = dbc_part;
-    QUAMBA_TRY(launch_gemm_i8(x_q, Di, hx ? hx->W_xH : qw->W_x, Di, M, NX, Di, e, base + p.gemm, p.gemm_bytes, st));
+    QUAMBA_TRY(launch_gemm_i8(x_q, Di, hx ? hx->W_xH : qw->W_x, Di, M, NX, Di, e, base + p.gemm, p.gemm_bytes, st, &x_plan));
     QUAMBA_TRY(tap_copy(t.dbc_q, dbc_q, (size_t)M * NX, st));
   }
   if (hx) {  // backward Hadamard: the scan's x, half precision, over the conv output that is no longer needed
@@ -331,14 +339,15 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
   // out_proj with the folded weight, fp16 out; the multiplier carries s_y s_WoutH / n
   {
     GemmEpilogue e{nullptr, out, t.acc_out, Dm, Dm, Dm, sc->m_out, sc->m_out, sc->m_out};
+    const GemmPlan out_plan = gemm_plan(M, Dm, Di, base + p.gemm, p.gemm_bytes);
     if (defer_out && defer_out->want && decode && g_fuse_decode && !t.acc_out) {
-      const int splits = gemm_splits(M, Dm, Di, base + p.gemm, p.gemm_bytes);
+      const int splits = out_plan.k_splits();
       if (splits > 1 && splits <= 8) {
         e.defer_reduce = true;
         *defer_out = OutPartial{true, splits, reinterpret_cast<const int32_t *>(base + p.gemm), sc->m_out};
       }
     }
-    QUAMBA_TRY(launch_gemm_i8(gH_q, Di, qw->W_outH, Di, M, Dm, Di, e, base + p.gemm, p.gemm_bytes, st));
+    QUAMBA_TRY(launch_gemm_i8(gH_q, Di, qw->W_outH, Di, M, Dm, Di, e, base + p.gemm, p.gemm_bytes, st, &out_plan));
   }
   return QUAMBA_OK;
 }
@@ -379,7 +388,9 @@ int mixer_decode_norm(const quamba_dims *d, const quamba_qweights *qw, const qua
                    &norm);
 }
 
-bool mixer_decode_norm_available(const quamba_dims *d, int Bt) { return g_fuse_decode && Bt <= g_gemv_max_rows && d->d_model <= 8192; }
+bool mixer_decode_norm_available(const quamba_dims *d, int Bt) {
+  return g_fuse_decode_hook.load(std::memory_order_relaxed) && Bt <= gemv_max_rows() && d->d_model <= 8192;
+}
 
 int check_model_dims(const quamba_dims *d) { return check_dims(d); }
 
@@ -815,5 +826,5 @@ extern "C" int quamba_mixer_decode_noalloc(const quamba_dims *dims, const quamba
                    sizeof(scratch), as_stream(stream));
 }
 
-extern "C" void quamba_debug_set_fuse_dt(int v) { quamba::g_fuse_dt = v; }
-extern "C" void quamba_debug_set_fuse_decode(int v) { quamba::g_fuse_decode = v; }
+extern "C" void quamba_debug_set_fuse_dt(int v) { quamba::g_fuse_dt_hook.store(v); }
+extern "C" void quamba_debug_set_fuse_decode(int v) { quamba::g_fuse_decode_hook.store(v); }

@@ -68,19 +68,28 @@ struct GemmEpilogue {
   bool defer_reduce;
 };
 
-// generation takes the few-row streaming kernels up to this many sequences (at most 4)
-extern int g_gemv_max_rows;
+// generation takes the few-row streaming kernels up to this many sequences (at most 4); tuning hook
+int gemv_max_rows();
 
-// Whether launch_gemm_i8 on this shape ends in an epilogue that can carry the conv step (the
-// 64 x 32 tiles of a wide generation-step output, or the reduce kernel of a split K).
-bool gemm_fuses_conv_step(int M, int N, int K, const void *ws, size_t ws_bytes);
+// Which kernel launch_gemm_i8 runs for a shape and how it splits K over the grid.  A caller whose
+// own launches depend on that (who adds up the partial sums, where the conv step runs) asks once
+// and hands the same plan to launch_gemm_i8, so the two cannot disagree.
+struct GemmPlan {
+  bool gemv;  // the few-row streaming kernel
+  int kind, splits, slices_per_split;
+  // the launch ends in an epilogue that can carry the conv step (the 64 x 32 / two-K-group 64 x 64
+  // tiles of a wide generation-step output, or the reduce kernel of a split K)
+  bool fuses_conv_step() const { return !gemv && (kind == 7 || kind == 11 || splits > 1); }
+  int k_splits() const { return gemv ? 1 : splits; }
+};
+GemmPlan gemm_plan(int M, int N, int K, const void *ws, size_t ws_bytes);
 
 // `ws` (may be NULL) lets skinny problems split K; gemm_workspace_bytes is the most they use.
 size_t gemm_workspace_bytes(int M, int N);
-// Into how many K ranges launch_gemm_i8 splits this shape over the grid (1: not split).
-int gemm_splits(int M, int N, int K, const void *ws, size_t ws_bytes);
+// `plan`: the result of gemm_plan for the same shape and workspace (NULL: chosen here).
 int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, int N, int K,
-                   const GemmEpilogue &epi, void *ws, size_t ws_bytes, hipStream_t st);
+                   const GemmEpilogue &epi, void *ws, size_t ws_bytes, hipStream_t st,
+                   const GemmPlan *plan = nullptr);
 
 int launch_quantize_f16(const __half *x, int8_t *q, size_t n, float inv_s, hipStream_t st);
 

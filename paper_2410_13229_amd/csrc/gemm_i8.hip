@@ -20,6 +20,8 @@
 // Skinny problems (few output tiles, deep K) are split along K over grid.y; the int32 partial
 // sums go to a workspace and a second kernel adds them and applies the epilogue (integer
 // addition, so the result does not depend on the order).
+#include <atomic>
+
 #include "common.h"
 #include "device_util.h"
 
@@ -658,12 +660,17 @@ template <int BM, int BN, int WGM, int WGN, int S, int BKB, int OCC, int KG = 1,
 int run_dma(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, int N, int K,
             const GemmEpilogue &epi, int splits, const KSplit &ks, hipStream_t st) {
   constexpr size_t lds = (size_t)S * (BM + BN) * BKB;
-  static bool attr_set = false;
-  if (!attr_set) {
+  // the attribute is per device: one bit per device index, set after the first successful call there
+  // (two threads racing here both set it, which is harmless)
+  static std::atomic<unsigned long long> attr_set{0};
+  int dev = 0;
+  QUAMBA_HIP(hipGetDevice(&dev));
+  const unsigned long long bit = 1ull << (dev & 63);
+  if (!(attr_set.load(std::memory_order_acquire) & bit)) {
     QUAMBA_HIP(hipFuncSetAttribute(
         reinterpret_cast<const void *>(&gemm_i8_dma_kernel<BM, BN, WGM, WGN, S, BKB, OCC, KG, PIPE, CONV>),
         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    attr_set = true;
+    attr_set.fetch_or(bit, std::memory_order_release);
   }
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   hipLaunchKernelGGL((gemm_i8_dma_kernel<BM, BN, WGM, WGN, S, BKB, OCC, KG, PIPE, CONV>), dim3(tiles_m * tiles_n, splits),
@@ -682,15 +689,17 @@ int run_reg(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, int N, i
   return QUAMBA_OK;
 }
 
-int g_gemm_variant = -1;  // tuning hook: >= 0 forces a kernel configuration
-int g_gemm_split = 0;     // tuning hook: > 1 forces a K split over the grid
+// Tuning hooks (process-wide; read once per plan).
+std::atomic<int> g_gemm_variant{-1};  // >= 0 forces a kernel configuration
+std::atomic<int> g_gemm_split{0};     // > 1 forces a K split over the grid
+std::atomic<int> g_gemv_max_rows{2};  // the few-row streaming kernels serve M up to this (at most 4)
 
-struct GemmChoice {
-  bool gemv;  // the few-row streaming kernel
-  int kind, splits, slices_per_split;
-};
+using GemmChoice = GemmPlan;
 
 GemmChoice choose_gemm(int M, int N, int K, const void *ws, size_t ws_bytes) {
+  const int g_gemm_variant = quamba::g_gemm_variant.load(std::memory_order_relaxed);
+  const int g_gemm_split = quamba::g_gemm_split.load(std::memory_order_relaxed);
+  const int g_gemv_max_rows = quamba::g_gemv_max_rows.load(std::memory_order_relaxed);
   const bool k64 = (K % 64) == 0, k128 = (K % 128) == 0;
   // which kernel:
   //   0 = reg 64x64            1 = reg 128x128
@@ -708,7 +717,10 @@ GemmChoice choose_gemm(int M, int N, int K, const void *ws, size_t ws_bytes) {
   //   11 = dma 64x64, two K groups of 4 waves, 256-byte slices, ring of 3: the same job when K is a
   //       multiple of 256; half as many workgroups re-read the activation rows (64 x 10240 x 2560:
   //       7.5 against 8.0 us, 64 x 16384 x 4096: 13.6 against 14.6 us)
-  if (M <= g_gemv_max_rows && g_gemm_variant < 0 && (size_t)4 * K <= 64 * 1024) return GemmChoice{true, 0, 1, 0};
+  // the streaming kernel keeps its rows in LDS: rows x K bytes next to a static array of rows x 64 bytes
+  const size_t gemv_rows = M <= 1 ? 1 : (M <= 2 ? 2 : 4);
+  if (M <= g_gemv_max_rows && g_gemm_variant < 0 && gemv_rows * K + gemv_rows * 64 <= 64 * 1024)
+    return GemmChoice{true, 0, 1, 0};
   int kind;
   const long tiles_256 = (long)((M + 255) / 256) * ((N + 319) / 320);
   const long tiles_128 = (long)((M + 127) / 128) * ((N + 159) / 160);
@@ -750,6 +762,7 @@ GemmChoice choose_gemm(int M, int N, int K, const void *ws, size_t ws_bytes) {
   const long tiles64 = (long)((M + 63) / 64) * ((N + 63) / 64);
   const bool skinny_unsplit = N <= 512 && tiles64 > 256;
   if ((K % 256) == 0 && kind == 5 && M > 64 && !skinny_unsplit && tiles64 <= 512) kind = 9;
+  if (g_gemm_variant >= 12 && g_gemm_variant <= 15 && k64) kind = g_gemm_variant;  // experimental forms
   if (g_gemm_variant >= 0 && g_gemm_variant <= 11 &&
       (g_gemm_variant < 2 || (g_gemm_variant == 3 && k64) || (g_gemm_variant != 3 && k128)) &&
       (g_gemm_variant != 11 || (K % 256) == 0))
@@ -757,7 +770,7 @@ GemmChoice choose_gemm(int M, int N, int K, const void *ws, size_t ws_bytes) {
 
   // split K when the output has too few tiles to fill 256 CUs and K is deep
   int splits = 1;
-  const int slice = (kind == 8 || kind == 9 || kind == 11) ? 256 : ((kind == 2 || kind >= 4) ? 128 : 64);
+  const int slice = (kind == 8 || kind == 9 || kind == 11) ? 256 : (kind >= 12 ? 64 : ((kind == 2 || kind >= 4) ? 128 : 64));
   const int nslices = (K + slice - 1) / slice;
   if ((kind == 0 || kind == 3 || kind == 5 || kind == 9) && ws != nullptr) {
     const int tiles = ((M + 63) / 64) * ((N + 63) / 64);
@@ -775,26 +788,20 @@ GemmChoice choose_gemm(int M, int N, int K, const void *ws, size_t ws_bytes) {
 
 }  // namespace
 
-int g_gemv_max_rows = 2;  // the few-row streaming kernels serve M up to this (tuning hook; at most 4)
+int gemv_max_rows() { return g_gemv_max_rows.load(std::memory_order_relaxed); }
 
 size_t gemm_workspace_bytes(int M, int N) {
   // room for up to 8 int32 partial copies of a skinny output
   return (size_t)8 * M * N * sizeof(int32_t);
 }
 
-int gemm_splits(int M, int N, int K, const void *ws, size_t ws_bytes) {
-  const GemmChoice c = choose_gemm(M, N, K, ws, ws_bytes);
-  return c.gemv ? 1 : c.splits;
-}
-
-bool gemm_fuses_conv_step(int M, int N, int K, const void *ws, size_t ws_bytes) {
-  const GemmChoice c = choose_gemm(M, N, K, ws, ws_bytes);
-  return !c.gemv && (c.kind == 7 || c.kind == 11 || c.splits > 1);
-}
+GemmPlan gemm_plan(int M, int N, int K, const void *ws, size_t ws_bytes) { return choose_gemm(M, N, K, ws, ws_bytes); }
 
 int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, int N, int K,
-                   const GemmEpilogue &epi, void *ws, size_t ws_bytes, hipStream_t st) {
-  const GemmChoice c = choose_gemm(M, N, K, ws, ws_bytes);
+                   const GemmEpilogue &epi, void *ws, size_t ws_bytes, hipStream_t st, const GemmPlan *plan) {
+  const GemmChoice c = plan ? *plan : choose_gemm(M, N, K, ws, ws_bytes);
+  if (c.splits > 1 && (!ws || (size_t)c.splits * M * N * sizeof(int32_t) > ws_bytes))
+    return fail(QUAMBA_EWORKSPACE, "gemm: %d K ranges of a %d x %d output do not fit the workspace", c.splits, M, N);
   const bool conv = epi.conv.state != nullptr;
   if (conv && (c.gemv || !(c.kind == 7 || c.kind == 11 || c.splits > 1) || !epi.out_i8 || epi.e0 % 4 != 0))
     return fail(QUAMBA_EUNSUPPORTED, "gemm: this shape (M=%d N=%d K=%d) has no epilogue that carries the conv step", M, N, K);
@@ -831,6 +838,10 @@ int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, i
     case 8: rc = run_dma<128, 160, 4, 1, 2, 256, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
     case 9: rc = run_dma<64, 64, 2, 2, 2, 256, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
     case 10: rc = run_dma<256, 256, 4, 2, 2, 128, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
+    case 12: rc = run_dma<256, 320, 4, 2, 4, 64, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
+    case 13: rc = run_dma<256, 160, 4, 1, 3, 64, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
+    case 14: rc = run_dma<256, 256, 4, 2, 4, 64, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
+    case 15: rc = run_dma<256, 320, 4, 2, 3, 64, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
     default: rc = run_reg<128, 128, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
   }
   if (rc != QUAMBA_OK || splits == 1 || epi.defer_reduce) return rc;
@@ -847,6 +858,6 @@ int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, i
 
 }  // namespace quamba
 
-extern "C" void quamba_debug_set_gemm_variant(int v) { quamba::g_gemm_variant = v; }
-extern "C" void quamba_debug_set_gemm_split(int v) { quamba::g_gemm_split = v; }
-extern "C" void quamba_debug_set_gemv_max_rows(int v) { quamba::g_gemv_max_rows = v < 0 ? 2 : (v < 4 ? v : 4); }
+extern "C" void quamba_debug_set_gemm_variant(int v) { quamba::g_gemm_variant.store(v); }
+extern "C" void quamba_debug_set_gemm_split(int v) { quamba::g_gemm_split.store(v); }
+extern "C" void quamba_debug_set_gemv_max_rows(int v) { quamba::g_gemv_max_rows.store(v < 0 ? 2 : (v < 4 ? v : 4)); }

@@ -401,10 +401,10 @@ def test_decode_streaming_kernels_up_to_four_sequences(Bt):
     cfg = W.CONFIGS["c2"]
     w, qw, sc = oracle_setup(cfg)
     try:
-        Q.lib().quamba_debug_set_gemv_max_rows(4)
+        Q.quamba_debug_set_gemv_max_rows(4)
         _decode_steps(cfg, Bt, 2, qw, sc, fused_dt=(Bt % 2 == 1))
     finally:
-        Q.lib().quamba_debug_set_gemv_max_rows(-1)
+        Q.quamba_debug_set_gemv_max_rows(-1)
 
 
 def test_prefill_then_decode_handoff():

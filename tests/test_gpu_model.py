@@ -185,9 +185,9 @@ def test_few_sequence_generation_kernels_match_the_general_path(Bt, d_model, d_i
     wsd = workspace(Q.quamba_model_workspace_bytes(gm, Bt, 1))
     res = []
     try:
-        Q.lib().quamba_debug_set_gemv_max_rows(4)  # the few-row kernels up to the 4 rows they serve (default: 2)
+        Q.quamba_debug_set_gemv_max_rows(4)  # the few-row kernels up to the 4 rows they serve (default: 2)
         for fuse in (1, 0):
-            Q.lib().quamba_debug_set_fuse_decode(fuse)
+            Q.quamba_debug_set_fuse_decode(fuse)
             ssm, cs = _states(cfg, nlayers, Bt)
             nxt = empty((Bt,), torch.int32)
             Q.quamba_model_prefill(gm, dev(prompt), Bt, 9, None, nxt, ssm, cs, wsp)
@@ -198,8 +198,8 @@ def test_few_sequence_generation_kernels_match_the_general_path(Bt, d_model, d_i
                 steps.append((host(logits).copy(), host(ssm).copy(), host(cs).copy()))
             res.append(steps)
     finally:
-        Q.lib().quamba_debug_set_fuse_decode(1)
-        Q.lib().quamba_debug_set_gemv_max_rows(-1)
+        Q.quamba_debug_set_fuse_decode(1)
+        Q.quamba_debug_set_gemv_max_rows(-1)
     for (la, sa, ca), (lb, sb, cb) in zip(*res):
         assert rel_err(la, lb) <= 2e-2
         assert rel_err(sa, sb) <= 2e-2
@@ -220,7 +220,7 @@ def test_many_sequence_generation_fusions_are_the_general_path_bit_for_bit(Bt, d
     res = []
     try:
         for fuse in (1, 0):
-            Q.lib().quamba_debug_set_fuse_decode(fuse)
+            Q.quamba_debug_set_fuse_decode(fuse)
             ssm, cs = _states(cfg, nlayers, Bt)
             nxt = empty((Bt,), torch.int32)
             Q.quamba_model_prefill(gm, dev(prompt), Bt, 5, None, nxt, ssm, cs, wsp)
@@ -231,7 +231,7 @@ def test_many_sequence_generation_fusions_are_the_general_path_bit_for_bit(Bt, d
                 steps.append((host(logits).copy(), host(ssm).copy(), host(cs).copy(), host(nxt).copy()))
             res.append(steps)
     finally:
-        Q.lib().quamba_debug_set_fuse_decode(1)
+        Q.quamba_debug_set_fuse_decode(1)
     for (la, sa, ca, ta), (lb, sb, cb, tb) in zip(*res):
         assert np.array_equal(la.view(np.uint32), lb.view(np.uint32))
         assert np.array_equal(sa.view(np.uint32), sb.view(np.uint32))

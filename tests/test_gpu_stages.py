@@ -41,6 +41,9 @@ GEMM_SHAPES = [
     # in_proj and out_proj of the 2.8B layer at 2048 tokens, exactly as the benchmark launches them: 256 x 320
     # tiles over a ring that wraps 20 times, and 128 x 160 tiles with two K groups and 256-byte slices
     (2048, 10240, 2560, 0), (2048, 2560, 5120, 0),
+    # few rows with the deepest K whose rows still fit the streaming kernel's LDS (2 rows) and one that no
+    # longer does (3 rows: matrix tiles)
+    (2, 64, 16384, 0), (3, 64, 16384, 0),
 ]
 
 
@@ -282,6 +285,47 @@ def test_scan_prefill_with_fused_dt_proj_rejects_odd_rank():
                                      dbc[..., 48:], 64, dev(A), dev(D), dev(bias), full, Bt, L, Di,
                                      empty((Bt, L, Di), torch.float16), None, None, ws)
 
+
+
+@pytest.mark.parametrize("prefill", [False, True])
+def test_scan_output_at_the_edge_of_half_precision(prefill):
+    """The gated scan output is rounded to half precision once (Section 4.2: the quantized SSM "outputs half
+    precision"): values up to the largest finite half (65504) come out finite and equal to the oracle's, values
+    beyond it become infinities of the right sign on both sides (IEEE conversion, no saturation)."""
+    Bt, L, Di, R = 2, (5 if prefill else 1), 64, 48
+    rng = np.random.default_rng(7)
+    sc, x, dt, xz, dbc, A, D, bias = _scan_inputs(rng, Bt, L, Di)
+    # y = D x with D = 1 (B = C = 0 switch the state off), gate SiLU(40) = 40: g = 40 * 13 * x_q
+    sc = dict(sc, s_x=np.float32(13.0), s_D=np.float32(1 / 127), s_z=np.float32(40 / 127))
+    dbc[...] = 0
+    D[:] = 127
+    xz[..., Di:] = 127
+    x[...] = rng.integers(-120, 121, x.shape)
+    x[:, :, 0], x[:, :, 1], x[:, :, 2], x[:, :, 3] = 125, -125, 127, -127   # 65000, -65000, 66040, -66040
+    x[:, :, 4], x[:, :, 5] = 126, -126                                        # 65520: the tie that rounds to infinity
+    with np.errstate(over="ignore"):
+        g_ref, g16_ref, h_ref = O.q_scan(x, dt, xz[..., Di:], dbc[..., R:R + 16], dbc[..., R + 16:], A, D, bias, sc, None)
+    assert np.isinf(g16_ref[:, :, 2]).all() and np.isinf(g16_ref[:, :, 3]).all() and np.isfinite(g16_ref[:, :, :2]).all()
+    full = dict(sc)
+    for k in Q.SCALE_FIELDS:
+        full.setdefault(k, 1.0)
+    dxz, ddbc = dev(xz), dev(dbc)
+    g16 = empty((Bt, L, Di), torch.float16)
+    ssm = torch.zeros((Bt, Di, 16), dtype=torch.float32, device="cuda:0")
+    if prefill:
+        ws = workspace(Q.quamba_scan_workspace_bytes(Bt, L, Di))
+        Q.quamba_scan_prefill(dev(x), dev(dt), dxz[..., Di:], 2 * Di, ddbc[..., R:], ddbc[..., R + 16:], dbc.shape[-1],
+                              dev(A), dev(D), dev(bias), full, Bt, L, Di, g16, None, ssm, ws)
+    else:
+        Q.quamba_scan_step(dev(x[:, 0]), dev(dt[:, 0]), dxz[:, 0, Di:], 2 * Di, ddbc[:, 0, R:], ddbc[:, 0, R + 16:],
+                           dbc.shape[-1], dev(A), dev(D), dev(bias), full, Bt, Di, g16, None, ssm)
+    got = host(g16).reshape(Bt, L, Di)
+    fin = np.isfinite(g16_ref)
+    fin[:, :, 4:6] = False  # the exact tie may fall either way in fp32 against fp64: not compared
+    assert np.isfinite(got[fin]).all()
+    assert rel_err(got[fin].astype(np.float64), g_ref[fin]) <= 1e-3
+    assert np.array_equal(got[:, :, 2:4], g16_ref[:, :, 2:4])  # +inf / -inf
+    assert np.abs(got[:, :, :2].astype(np.float64)).min() >= 64960
 
 @pytest.mark.parametrize("Bt,Di", [(1, 64), (7, 192), (64, 5120)])
 def test_scan_step(Bt, Di):
