@@ -23,7 +23,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA, published
-FP32_ALU_PEAK_TFLOPS = 78.6  # 256 CU x 4 SIMD x 16 lanes x 2 flop x 2.4 GHz (packed fp32 is compiled out)
+FP32_ALU_PEAK_TFLOPS = 157.3  # MI355X fp32 vector, published; `bench.py --rates` measures 0.87 of it with plain v_fma_f32
 SCAN_FLOP_PER_TD = 123.0     # 16 x (exp + 2 mul + 2 fma) + D*x + softplus + gate, per (token, channel)
 
 # HBM bytes per launch of the dominant kernel (in_proj GEMM, c1) from rocprofv3 --pmc FETCH_SIZE /
@@ -34,16 +34,19 @@ MEASURED_TRAFFIC_BYTES = {"c1": 89.6e6}
 
 def instruction_rates(Q, torch, np, dev, stream):
     """Issue rates of the instruction classes the roofline statements rest on, from register-only loops on
-    every SIMD at once (256 CUs x 4 SIMDs x 1, 2 or 4 waves).  Per probe: instructions per second and SIMD,
-    and cycles per instruction with the clock taken from the fp32 FMA probe of the same occupancy (a wave64
-    FMA occupies a 16-lane SIMD for 4 cycles); the matrix probes report POP/s (65536 operations per
+    every SIMD at once (256 CUs x 4 SIMDs x 2, 4 or 8 waves).  Per probe: instructions per second and SIMD,
+    and cycles per instruction with the shader clock the probe itself measured (shader-clock ticks over
+    constant-rate-clock ticks of its first wave); the matrix probes report POP/s (65536 operations per
     v_mfma_i32_32x32x32_i8) and the fraction of the published 5.0 POP/s."""
-    probes = [("fma_f32", Q.PROBE_FMA_F32, 40000), ("exp_f32", Q.PROBE_EXP_F32, 20000),
-              ("scan_state_update", Q.PROBE_SCAN_MIX, 8000), ("mfma_i8_zero_operands", Q.PROBE_MFMA_I8, 20000),
+    probes = [("fma_f32", Q.PROBE_FMA_F32, 40000), ("mul_f32", Q.PROBE_MUL_F32, 40000),
+              ("exp_f32", Q.PROBE_EXP_F32, 20000), ("fma_exp_independent", Q.PROBE_FMA_EXP_INDEP, 20000),
+              ("scan_state_update", Q.PROBE_SCAN_MIX, 8000), ("scan_state_update_no_exp", Q.PROBE_MIX_NOEXP, 8000),
+              ("scan_state_update_exp_grouped", Q.PROBE_MIX_GROUPED, 8000), ("mfma_i8_zero_operands", Q.PROBE_MFMA_I8, 20000),
               ("mfma_i8_random_operands", Q.PROBE_MFMA_I8_RANDOM, 20000)]
     out = {"probe": "register-only loops, 256 CUs x 4 SIMDs", "rates": {}}
     rng = np.random.default_rng(241013229)
-    for wps in (1, 2, 4):
+    wall_hz = 1e8  # the constant-rate clock of this part ticks at 100 MHz
+    for wps in (2, 4, 8):
         ws = torch.zeros(Q.quamba_probe_workspace_bytes(wps), dtype=torch.uint8, device=dev)
         ws[:4096] = torch.from_numpy(rng.integers(0, 256, 4096, dtype=np.uint8)).to(dev)
         res = {}
@@ -58,15 +61,16 @@ def instruction_rates(Q, torch, np, dev, stream):
             e1.record(stream)
             e1.synchronize()
             sec = e0.elapsed_time(e1) * 1e-3 / reps
-            res[name] = {"instr_per_s_per_simd": n / sec / 1024.0, "us_per_launch": round(sec * 1e6, 1)}
-        clock = 4.0 * res["fma_f32"]["instr_per_s_per_simd"]  # Hz, if the FMA probe issues every 4 cycles
+            ticks = ws[4096:4112].view(torch.int64).cpu().numpy()
+            clock = float(ticks[0]) / max(float(ticks[1]), 1.0) * wall_hz  # shader clock during this probe
+            res[name] = {"instr_per_s_per_simd": n / sec / 1024.0, "us_per_launch": round(sec * 1e6, 1),
+                         "shader_clock_GHz": round(clock / 1e9, 3)}
         for name, r in res.items():
-            r["cycles_per_instr"] = round(clock / r["instr_per_s_per_simd"], 2)
+            r["cycles_per_instr"] = round(r["shader_clock_GHz"] * 1e9 / r["instr_per_s_per_simd"], 2)
             if name.startswith("mfma"):
                 r["POP_per_s"] = round(r["instr_per_s_per_simd"] * 1024 * 65536 / 1e15, 3)
                 r["frac_of_5_POPs"] = round(r["POP_per_s"] / 5.0, 3)
             r["instr_per_s_per_simd"] = round(r["instr_per_s_per_simd"] / 1e6, 1)
-        res["clock_GHz_from_fma"] = round(clock / 1e9, 3)
         out["rates"][f"{wps}_waves_per_simd"] = res
     out["units"] = {"instr_per_s_per_simd": "1e6 / s", "scan_state_update": "one update = mul, exp, mul, fma, fma"}
     return out

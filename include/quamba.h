@@ -570,12 +570,19 @@ int quamba_model_generate(const quamba_model *model, const int32_t *first_tokens
  *   QUAMBA_PROBE_MFMA_I8_RANDOM   the same with the caller's operands: the first 4096 bytes of `ws`
  *                                 (4 operand registers x 64 lanes x 16 int8), e.g. seeded random codes
  * *instr_per_call (host) receives the number of counted instructions (state updates for SCAN_MIX,
- * 65536 integer operations per MFMA) of the launch.  Workspace: quamba_probe_workspace_bytes. */
+ * 65536 integer operations per MFMA) of the launch.  Workspace: quamba_probe_workspace_bytes; after the
+ * launch its bytes [4096, 4112) hold two uint64: the ticks of the shader clock and of the constant-rate
+ * clock between the start and the end of the first wave (their ratio times the constant rate is the
+ * shader clock the probe ran at). */
 #define QUAMBA_PROBE_FMA_F32 0
 #define QUAMBA_PROBE_EXP_F32 1
 #define QUAMBA_PROBE_SCAN_MIX 2
 #define QUAMBA_PROBE_MFMA_I8 3
 #define QUAMBA_PROBE_MFMA_I8_RANDOM 4
+#define QUAMBA_PROBE_MUL_F32 5        /* 8 independent v_mul_f32 per round */
+#define QUAMBA_PROBE_FMA_EXP_INDEP 6  /* 4 v_fma_f32 and 4 v_exp_f32 per round, all independent */
+#define QUAMBA_PROBE_MIX_NOEXP 7      /* SCAN_MIX with a multiply-add in the exponential's place */
+#define QUAMBA_PROBE_MIX_GROUPED 8    /* SCAN_MIX with the 8 exponentials of a round issued as one run */
 size_t quamba_probe_workspace_bytes(int waves_per_simd);
 int quamba_probe_rate(int probe, int waves_per_simd, int iters, double *instr_per_call /* host */,
                       void *ws, size_t ws_bytes, void *stream);

@@ -30,6 +30,7 @@ __all__ = [
     "quamba_debug_set_gemm_variant", "quamba_debug_set_gemm_split", "quamba_debug_set_gemv_max_rows",
     "quamba_debug_set_fuse_dt", "quamba_debug_set_fuse_decode",
     "PROBE_FMA_F32", "PROBE_EXP_F32", "PROBE_SCAN_MIX", "PROBE_MFMA_I8", "PROBE_MFMA_I8_RANDOM",
+    "PROBE_MUL_F32", "PROBE_FMA_EXP_INDEP", "PROBE_MIX_NOEXP", "PROBE_MIX_GROUPED",
     "quamba_probe_workspace_bytes", "quamba_probe_rate",
 ]
 
@@ -698,6 +699,7 @@ def quamba_debug_set_fuse_decode(v):
 
 # ---- diagnostics: instruction-rate probes
 PROBE_FMA_F32, PROBE_EXP_F32, PROBE_SCAN_MIX, PROBE_MFMA_I8, PROBE_MFMA_I8_RANDOM = 0, 1, 2, 3, 4
+PROBE_MUL_F32, PROBE_FMA_EXP_INDEP, PROBE_MIX_NOEXP, PROBE_MIX_GROUPED = 5, 6, 7, 8
 
 
 def quamba_probe_workspace_bytes(waves_per_simd) -> int:

@@ -762,7 +762,6 @@ GemmChoice choose_gemm(int M, int N, int K, const void *ws, size_t ws_bytes) {
   const long tiles64 = (long)((M + 63) / 64) * ((N + 63) / 64);
   const bool skinny_unsplit = N <= 512 && tiles64 > 256;
   if ((K % 256) == 0 && kind == 5 && M > 64 && !skinny_unsplit && tiles64 <= 512) kind = 9;
-  if (g_gemm_variant >= 12 && g_gemm_variant <= 15 && k64) kind = g_gemm_variant;  // experimental forms
   if (g_gemm_variant >= 0 && g_gemm_variant <= 11 &&
       (g_gemm_variant < 2 || (g_gemm_variant == 3 && k64) || (g_gemm_variant != 3 && k128)) &&
       (g_gemm_variant != 11 || (K % 256) == 0))
@@ -770,7 +769,7 @@ GemmChoice choose_gemm(int M, int N, int K, const void *ws, size_t ws_bytes) {
 
   // split K when the output has too few tiles to fill 256 CUs and K is deep
   int splits = 1;
-  const int slice = (kind == 8 || kind == 9 || kind == 11) ? 256 : (kind >= 12 ? 64 : ((kind == 2 || kind >= 4) ? 128 : 64));
+  const int slice = (kind == 8 || kind == 9 || kind == 11) ? 256 : ((kind == 2 || kind >= 4) ? 128 : 64);
   const int nslices = (K + slice - 1) / slice;
   if ((kind == 0 || kind == 3 || kind == 5 || kind == 9) && ws != nullptr) {
     const int tiles = ((M + 63) / 64) * ((N + 63) / 64);
@@ -838,10 +837,6 @@ int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, i
     case 8: rc = run_dma<128, 160, 4, 1, 2, 256, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
     case 9: rc = run_dma<64, 64, 2, 2, 2, 256, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
     case 10: rc = run_dma<256, 256, 4, 2, 2, 128, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
-    case 12: rc = run_dma<256, 320, 4, 2, 4, 64, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
-    case 13: rc = run_dma<256, 160, 4, 1, 3, 64, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
-    case 14: rc = run_dma<256, 256, 4, 2, 4, 64, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
-    case 15: rc = run_dma<256, 320, 4, 2, 3, 64, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
     default: rc = run_reg<128, 128, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
   }
   if (rc != QUAMBA_OK || splits == 1 || epi.defer_reduce) return rc;

@@ -211,7 +211,8 @@ def _scan_inputs(rng, Bt, L, Di, N=16):
 
 
 @pytest.mark.parametrize("Bt,L,Di,with_h0", [(1, 1, 64, False), (2, 45, 128, True), (1, 300, 320, False),
-                                              (3, 67, 192, True), (1, 1000, 256, True), (1, 256, 1536, False)])
+                                              (3, 67, 192, True), (1, 1000, 256, True), (1, 256, 1536, False),
+                                              (2, 131, 1100, True), (1, 2048, 5120, True)])
 def test_scan_prefill(Bt, L, Di, with_h0):
     rng = np.random.default_rng(L * 31 + Di)
     sc, x, dt, xz, dbc, A, D, bias = _scan_inputs(rng, Bt, L, Di)
