@@ -714,6 +714,10 @@ GemmChoice choose_gemm(int M, int N, int K, const void *ws, size_t ws_bytes) {
   //   10 = 4 with 256 x 256 tiles (eight waves of 64 x 128), for N that 320-wide tiles fit badly
   //   7 = dma 64x32, two K groups of 2 waves, ring of 4: decode-sized M with a wide output gets a
   //       tile per CU without splitting K over the grid (no second kernel)
+  //   12 = 7 with four K groups of 2 waves and 256-byte slices, ring of 3 (K a multiple of 256): half the
+  //       barriers and twice the waves per tile for the skinny output of a prefill (2048 x 192 x 5120: 8.3 against
+  //       10.1 us; with a deeper ring of 128-byte slices, 6 to 12 stages, the time does not move: the loop is bound
+  //       by the per-slice barrier and the latency of one round of fragment reads, not by bytes in flight)
   //   11 = dma 64x64, two K groups of 4 waves, 256-byte slices, ring of 3: the same job when K is a
   //       multiple of 256; half as many workgroups re-read the activation rows (64 x 10240 x 2560:
   //       7.5 against 8.0 us, 64 x 16384 x 4096: 13.6 against 14.6 us)
@@ -733,7 +737,7 @@ GemmChoice choose_gemm(int M, int N, int K, const void *ws, size_t ws_bytes) {
     // (measured at N = 192, K = 5120: 10.2 vs 12.5 us at M = 2048, 12.4 vs 15.1 at 4096; at
     // K = 8192 or with many more tiles the split-K / single-pass 64 x 64 form stays ahead).
     const long tiles_32 = (long)((M + 63) / 64) * ((N + 31) / 32);
-    if (k128 && tiles_32 >= 192 && tiles_32 <= 512 && K <= 6144) kind = 7;
+    if (k128 && tiles_32 >= 192 && tiles_32 <= 512 && K <= 6144) kind = (K % 256) == 0 ? 12 : 7;
     // Very many rows and an N that 160-wide tiles cover without waste: the 128 x 160 tiles with two
     // K groups (N = 320, K = 8192, 16384 tokens: 56 vs 80 us; at 8192 tokens and below the 64 x 64
     // tiles are ahead again).
@@ -762,6 +766,7 @@ GemmChoice choose_gemm(int M, int N, int K, const void *ws, size_t ws_bytes) {
   const long tiles64 = (long)((M + 63) / 64) * ((N + 63) / 64);
   const bool skinny_unsplit = N <= 512 && tiles64 > 256;
   if ((K % 256) == 0 && kind == 5 && M > 64 && !skinny_unsplit && tiles64 <= 512) kind = 9;
+  if (g_gemm_variant == 12 && (K % 256) == 0) kind = 12;
   if (g_gemm_variant >= 0 && g_gemm_variant <= 11 &&
       (g_gemm_variant < 2 || (g_gemm_variant == 3 && k64) || (g_gemm_variant != 3 && k128)) &&
       (g_gemm_variant != 11 || (K % 256) == 0))
@@ -769,7 +774,7 @@ GemmChoice choose_gemm(int M, int N, int K, const void *ws, size_t ws_bytes) {
 
   // split K when the output has too few tiles to fill 256 CUs and K is deep
   int splits = 1;
-  const int slice = (kind == 8 || kind == 9 || kind == 11) ? 256 : ((kind == 2 || kind >= 4) ? 128 : 64);
+  const int slice = (kind == 8 || kind == 9 || kind == 11 || kind == 12) ? 256 : ((kind == 2 || kind >= 4) ? 128 : 64);
   const int nslices = (K + slice - 1) / slice;
   if ((kind == 0 || kind == 3 || kind == 5 || kind == 9) && ws != nullptr) {
     const int tiles = ((M + 63) / 64) * ((N + 63) / 64);
@@ -837,6 +842,7 @@ int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, i
     case 8: rc = run_dma<128, 160, 4, 1, 2, 256, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
     case 9: rc = run_dma<64, 64, 2, 2, 2, 256, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
     case 10: rc = run_dma<256, 256, 4, 2, 2, 128, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
+    case 12: rc = run_dma<64, 32, 2, 1, 3, 256, 2, 4>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
     default: rc = run_reg<128, 128, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
   }
   if (rc != QUAMBA_OK || splits == 1 || epi.defer_reduce) return rc;

@@ -157,7 +157,9 @@ def test_gemm_rejects_bad_arguments():
 
 
 # ------------------------------------------------------------------ conv
-@pytest.mark.parametrize("Bt,L,Di", [(1, 1, 64), (2, 3, 128), (3, 37, 192), (1, 256, 1536), (2, 100, 5120)])
+@pytest.mark.parametrize("Bt,L,Di", [(1, 1, 64), (2, 3, 128), (3, 37, 192), (1, 256, 1536), (2, 100, 5120),
+                                     (2, 21, 36), (1, 7, 100),  # channel counts that only the 4-channel form serves
+                                     (1, 2048, 5120), (3, 1000, 208)])
 def test_conv_prefill(Bt, L, Di):
     rng = np.random.default_rng(Bt * 1000 + L)
     ldx = 2 * Di
