@@ -16,6 +16,8 @@
 // The last pass covers the lowest four index bits, so every work item ends with 16 adjacent
 // outputs, which it scales, rounds, clamps and stores as one 16-byte word.  The LDS row is
 // padded by 4 floats every 16 so that this 16-byte-per-lane pass is bank-conflict free.
+#include <atomic>
+
 #include "common.h"
 #include "device_util.h"
 
@@ -374,11 +376,16 @@ template <int K, int LOGM, typename TIn, bool TR>
 int run(const TIn *g, int M, float inv_s, int8_t *out, float *out_f32, __half *out_f16, hipStream_t st) {
   constexpr int n = K << LOGM;
   constexpr size_t lds = (size_t)(n + n / 4) * sizeof(float);
-  static bool attr_set = false;
-  if (lds > 64 * 1024 && !attr_set) {
-    QUAMBA_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&hadamard_quant_kernel<K, LOGM, TIn, TR>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    attr_set = true;
+  if (lds > 64 * 1024) {  // the attribute is per device: one bit per device index
+    static std::atomic<unsigned long long> attr_set{0};
+    int dev = 0;
+    QUAMBA_HIP(hipGetDevice(&dev));
+    const unsigned long long bit = 1ull << (dev & 63);
+    if (!(attr_set.load(std::memory_order_acquire) & bit)) {
+      QUAMBA_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&hadamard_quant_kernel<K, LOGM, TIn, TR>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+      attr_set.fetch_or(bit, std::memory_order_release);
+    }
   }
   hipLaunchKernelGGL((hadamard_quant_kernel<K, LOGM, TIn, TR>), dim3(M), dim3(threads_for(n)), lds, st, g, inv_s, out,
                      out_f32, out_f16);
