@@ -604,12 +604,16 @@ int quamba_probe_rate(int probe, int waves_per_simd, int iters, double *instr_pe
  *   quamba_debug_set_fuse_decode(v)    0: generation without the fused epilogues and hand-overs
  *                                      (conv step in in_proj, split-K sums added up by the consumer,
  *                                      Hadamard inside out_proj, fused few-sequence kernels); 1 = default
+ *   quamba_debug_set_scan_variant(v)   prefill scan: 1 = always the three-pass chunked form, 2 = one sweep per
+ *                                      sequence wherever its layout rules hold, 0 = default (the cheaper of
+ *                                      the two by the library's estimate for the shape)
  * ------------------------------------------------------------------------------------- */
 void quamba_debug_set_gemm_variant(int v);
 void quamba_debug_set_gemm_split(int v);
 void quamba_debug_set_gemv_max_rows(int v);
 void quamba_debug_set_fuse_dt(int v);
 void quamba_debug_set_fuse_decode(int v);
+void quamba_debug_set_scan_variant(int v);
 
 #ifdef __cplusplus
 }

@@ -28,7 +28,7 @@ __all__ = [
     "quamba_mixer_prefill_xfmt", "quamba_mixer_decode_xfmt", "quamba_x_encode", "quamba_xfmt_proj",
     "quamba_xdyn_workspace_bytes", "quamba_mixer_prefill_xdyn", "quamba_mixer_decode_xdyn",
     "quamba_debug_set_gemm_variant", "quamba_debug_set_gemm_split", "quamba_debug_set_gemv_max_rows",
-    "quamba_debug_set_fuse_dt", "quamba_debug_set_fuse_decode",
+    "quamba_debug_set_fuse_dt", "quamba_debug_set_fuse_decode", "quamba_debug_set_scan_variant",
     "PROBE_FMA_F32", "PROBE_EXP_F32", "PROBE_SCAN_MIX", "PROBE_MFMA_I8", "PROBE_MFMA_I8_RANDOM",
     "PROBE_MUL_F32", "PROBE_FMA_EXP_INDEP", "PROBE_MIX_NOEXP", "PROBE_MIX_GROUPED",
     "quamba_probe_workspace_bytes", "quamba_probe_rate",
@@ -344,7 +344,7 @@ def lib():
                  "quamba_scan_prefill_dtproj", "quamba_hadamard_quant"):
         getattr(L, name).restype = C.c_int
     for name in ("quamba_debug_set_gemm_variant", "quamba_debug_set_gemm_split", "quamba_debug_set_gemv_max_rows",
-                 "quamba_debug_set_fuse_dt", "quamba_debug_set_fuse_decode"):
+                 "quamba_debug_set_fuse_dt", "quamba_debug_set_fuse_decode", "quamba_debug_set_scan_variant"):
         getattr(L, name).argtypes = [i]
         getattr(L, name).restype = None
     L.quamba_probe_workspace_bytes.restype = sz
@@ -695,6 +695,10 @@ def quamba_debug_set_fuse_dt(v):
 
 def quamba_debug_set_fuse_decode(v):
     lib().quamba_debug_set_fuse_decode(int(v))
+
+
+def quamba_debug_set_scan_variant(v):
+    lib().quamba_debug_set_scan_variant(int(v))
 
 
 # ---- diagnostics: instruction-rate probes

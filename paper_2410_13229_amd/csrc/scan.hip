@@ -22,6 +22,9 @@
 // launches): dt_q = q(W_dt dt_low) is a K = dt_rank contraction, a handful of MFMAs per
 // (32-token, 64-channel) tile, which each wave runs for its own channels before it walks the
 // tokens.  The codes go through a wave-private LDS tile to the lanes and to dt_q for pass 3.
+#include <atomic>
+#include <cmath>
+
 #include "common.h"
 #include "device_util.h"
 
@@ -337,6 +340,217 @@ __global__ __launch_bounds__(256) void scan_carry_kernel(Dev p, float *__restric
   if (ssm_state) ssm_state[idx] = h;
 }
 
+// ---------------------------------------------------------------- prefill: one sweep per sequence
+// The chunked form pays for its parallelism over L with every exponential twice (pass 1 and pass 3).
+// When sequences x channels alone give several waves per SIMD, one sweep over each whole sequence is
+// cheaper.  A lane owns two of the 16 states of one channel (8 lanes per channel, 8 channels per wave,
+// 32 per workgroup), so the recurrence of a (channel, state pair) is serial in a lane and everything
+// else is spread over lanes:
+//   * the work per (token, channel) - dt code (MFMA tile of the fused dt_proj), softplus, x, z - is done
+//     once, a 16-token x 32-channel tile per wave and superblock of 64 tokens, and handed to the lanes of
+//     the recurrence through LDS as (dt, dt x), D x and the z code; B and C go there as (B0, B1, C0, C1)
+//     per state pair.  The global loads of superblock k + 1 are issued before the recurrence over
+//     superblock k and consumed after it.
+//   * the partial sums C h of 8 tokens are added across the 8 lanes of a channel with a transposing
+//     butterfly (3 DPP steps, 21 instructions for 8 tokens), which leaves lane j with token j's sum:
+//     it gates, rounds and stores that one value.
+// Tokens past the end of the sequence enter as dt = 0, dt x = 0: they leave the state as it is.
+constexpr int SW_CH = 32;      // channels per workgroup
+constexpr int SW_SB = 64;      // tokens per superblock: one 16-token tile per wave
+constexpr int SW_THREADS = 256;
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+
+// NK: k steps of 64 the dt_proj contraction may take (dt_rank <= 64 NK); 0: dt_q is read, not computed.
+template <int NK, int XM>
+__global__ __launch_bounds__(SW_THREADS, 3) void scan_sweep_kernel(Dev p, float *__restrict__ ssm_state) {
+  constexpr bool FUSE_DT = NK > 0;
+  constexpr int NKR = FUSE_DT ? NK : 1;
+  __shared__ __attribute__((aligned(16))) float2 sDU[SW_SB][SW_CH + 1];  // (dt, dt x); odd pitch: a tile's token rows on different banks
+  __shared__ __attribute__((aligned(16))) float4 sBC[SW_SB][NS / 2];     // (B[2g], B[2g+1], C[2g], C[2g+1])
+  __shared__ float sDX[SW_SB][SW_CH + 1];                                 // D x
+  __shared__ __attribute__((aligned(4))) int8_t sZ[SW_SB][SW_CH + 4];    // z code
+  // Workgroups go to the 8 XCDs round-robin by index: give one XCD consecutive channel blocks, so the
+  // blocks that share 128-byte lines of x, z and g share an L2.
+  const int nblk = p.Di / SW_CH;
+  const int bx = blockIdx.x;
+  const int cb = (nblk % 8 == 0) ? (bx & 7) * (nblk >> 3) + (bx >> 3) : bx;
+  const int b = blockIdx.y;
+  const int ch0 = cb * SW_CH;
+  const size_t seq0 = (size_t)b * p.L;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+  // ---- recurrence role: channel chl of the workgroup, states 2 ng and 2 ng + 1
+  const int ng = lane & 7, chl = 8 * wave + (lane >> 3), chg = ch0 + chl;
+  float a20, a21, h0 = 0.f, h1 = 0.f;
+  {
+    const unsigned short aw = *reinterpret_cast<const unsigned short *>(p.A_q + (size_t)chg * NS + 2 * ng);
+    a20 = static_cast<float>(static_cast<int8_t>(aw & 0xff)) * (p.s_A * LOG2E);
+    a21 = static_cast<float>(static_cast<int8_t>(aw >> 8)) * (p.s_A * LOG2E);
+    if (ssm_state) {
+      const float2 hv = *reinterpret_cast<const float2 *>(ssm_state + ((size_t)b * p.Di + chg) * NS + 2 * ng);
+      h0 = hv.x;
+      h1 = hv.y;
+    }
+  }
+  const bool up4 = (ng & 4) != 0, up2 = (ng & 2) != 0, up1 = (ng & 1) != 0;
+
+  // ---- tile role (v_mfma_i32_16x16x64_i8, weights as the A operand): token row lane % 16 of the wave's
+  // 16-token tile; register r of result m is channel 16 m + 4 (lane / 16) + r of the workgroup.  Both
+  // operands take the 16 bytes at k = 64 s + 16 (lane / 16) of their row.
+  const int tokl = lane & 15, kq = lane >> 4;
+  float bias_r[8], Dv_r[8];
+#pragma unroll
+  for (int r = 0; r < 8; ++r) {
+    const int c = ch0 + 16 * (r >> 2) + 4 * kq + (r & 3);
+    bias_r[r] = p.dt_bias[c];
+    Dv_r[r] = p.s_D * static_cast<float>(p.D_q[c]);
+  }
+  v4i wfrag[2][NKR];
+#pragma unroll
+  for (int m = 0; m < 2; ++m)
+#pragma unroll
+    for (int s = 0; s < NKR; ++s) {
+      wfrag[m][s] = v4i{0, 0, 0, 0};
+      if constexpr (FUSE_DT) {
+        const int kc = 64 * s + 16 * kq;
+        if (kc < p.R) wfrag[m][s] = *reinterpret_cast<const v4i *>(p.W_dt + (size_t)(ch0 + 16 * m + tokl) * p.R + kc);
+      }
+    }
+  const float sx = x_scale<XM>(p);
+
+  struct Pre {
+    v4i a[NKR];
+    unsigned x[2], z[2], dtc[2];
+    unsigned bq, cq;
+  };
+  auto issue = [&](Pre &r, int sb) {
+    const size_t row = seq0 + min(sb * SW_SB + 16 * wave + tokl, p.L - 1);  // clamped rows are zeroed in produce
+#pragma unroll
+    for (int s = 0; s < NKR; ++s) {
+      r.a[s] = v4i{0, 0, 0, 0};
+      if constexpr (FUSE_DT) {
+        const int kc = 64 * s + 16 * kq;
+        if (kc < p.R) r.a[s] = *reinterpret_cast<const v4i *>(p.dtlow_q + row * p.lddl + kc);
+      }
+    }
+#pragma unroll
+    for (int m = 0; m < 2; ++m) {
+      const int c = ch0 + 16 * m + 4 * kq;
+      r.x[m] = *reinterpret_cast<const unsigned *>(p.x_q + row * p.Di + c);
+      r.z[m] = *reinterpret_cast<const unsigned *>(p.z_q + row * p.ldz + c);
+      r.dtc[m] = FUSE_DT ? 0u : *reinterpret_cast<const unsigned *>(p.dt_q + row * p.Di + c);
+    }
+    // B and C of token tid / 4, states 4 (tid % 4) .. + 4
+    const size_t rowb = seq0 + min(sb * SW_SB + (tid >> 2), p.L - 1);
+    r.bq = *reinterpret_cast<const unsigned *>(p.B_q + rowb * p.ldbc + 4 * (tid & 3));
+    r.cq = *reinterpret_cast<const unsigned *>(p.C_q + rowb * p.ldbc + 4 * (tid & 3));
+  };
+  auto produce = [&](const Pre &r, int sb) {
+    const int tl = 16 * wave + tokl;
+    const int tok = sb * SW_SB + tl;
+    const bool valid = tok < p.L;
+#pragma unroll
+    for (int m = 0; m < 2; ++m) {
+      unsigned pk;
+      if constexpr (FUSE_DT) {
+        v4i acc = {0, 0, 0, 0};
+#pragma unroll
+        for (int s = 0; s < NKR; ++s) acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(wfrag[m][s], r.a[s], acc, 0, 0, 0);
+        const int a4[4] = {acc[0], acc[1], acc[2], acc[3]};
+        pk = requant_pack4(a4, p.m_dt);
+        if (valid) *reinterpret_cast<unsigned *>(p.dt_out + (seq0 + tok) * p.Di + ch0 + 16 * m + 4 * kq) = pk;
+      } else {
+        pk = r.dtc[m];
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int c = 16 * m + 4 * kq + i, idx = 4 * m + i;
+        const int dtq = static_cast<int>(static_cast<int8_t>(pk >> (8 * i)));
+        const int xr = static_cast<int>(static_cast<int8_t>(r.x[m] >> (8 * i)));
+        float dt = softplus_f(p.s_dt * static_cast<float>(dtq) + bias_r[idx]);
+        const float xv = x_value<XM>(p, xr, sx);
+        float u = dt * xv, dx = Dv_r[idx] * xv;
+        if (!valid) dt = u = dx = 0.f;
+        sDU[tl][c] = make_float2(dt, u);
+        sDX[tl][c] = dx;
+      }
+      *reinterpret_cast<unsigned *>(&sZ[tl][16 * m + 4 * kq]) = valid ? r.z[m] : 0u;
+    }
+    const int quarter = tid & 3, tb = tid >> 2;
+    const bool validb = sb * SW_SB + tb < p.L;
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      float4 v;
+      v.x = p.s_B * static_cast<float>(static_cast<int8_t>(r.bq >> (16 * q)));
+      v.y = p.s_B * static_cast<float>(static_cast<int8_t>(r.bq >> (16 * q + 8)));
+      v.z = p.s_C * static_cast<float>(static_cast<int8_t>(r.cq >> (16 * q)));
+      v.w = p.s_C * static_cast<float>(static_cast<int8_t>(r.cq >> (16 * q + 8)));
+      if (!validb) v = make_float4(0.f, 0.f, 0.f, 0.f);
+      sBC[tb][2 * quarter + q] = v;
+    }
+  };
+
+  const bool want_f32 = p.y_f32 != nullptr;
+  auto group = [&](int g, int tok0) {  // tok0: index in the sequence of the group's first token
+    float yp[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float2 du = sDU[8 * g + j][chl];
+      const float4 bc = sBC[8 * g + j][ng];
+      const float e0 = exp2_fast(du.x * a20), e1 = exp2_fast(du.x * a21);
+      h0 = __builtin_fmaf(e0, h0, du.y * bc.x);
+      h1 = __builtin_fmaf(e1, h1, du.y * bc.y);
+      yp[j] = __builtin_fmaf(bc.w, h1, bc.z * h0);
+    }
+    const float dx = sDX[8 * g + ng][chl];
+    const float zv = p.s_z * static_cast<float>(sZ[8 * g + ng][chl]);
+    // lanes 0-3 of a channel keep tokens 0-3 and take their partner's (lane 7 - i) sums for them, lanes 4-7
+    // the same for tokens 4-7; then pairs of tokens inside quads, then single tokens
+    float q4[4], q2[2];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const float keep = up4 ? yp[4 + k] : yp[k], send = up4 ? yp[k] : yp[4 + k];
+      q4[k] = keep + dpp_f<0x141>(send);  // row_half_mirror
+    }
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+      const float keep = up2 ? q4[2 + k] : q4[k], send = up2 ? q4[k] : q4[2 + k];
+      q2[k] = keep + dpp_f<0x4E>(send);  // quad_perm [2, 3, 0, 1]
+    }
+    const float keep = up1 ? q2[1] : q2[0], send = up1 ? q2[0] : q2[1];
+    const float y = keep + dpp_f<0xB1>(send) + dx;  // quad_perm [1, 0, 3, 2]
+    const float gv = silu_gate(y, zv);
+    const int tok = tok0 + ng;
+    if (tok < p.L) {
+      const size_t o = (seq0 + tok) * p.Di + chg;
+      p.g16[o] = __float2half_rn(gv);
+      if (want_f32) p.y_f32[o] = gv;
+    }
+  };
+
+  const int nsb = (p.L + SW_SB - 1) / SW_SB;
+  Pre pre;
+  issue(pre, 0);
+  produce(pre, 0);
+  __syncthreads();
+  for (int sb = 0; sb < nsb; ++sb) {
+    const bool more = sb + 1 < nsb;
+    if (more) issue(pre, sb + 1);
+    const int ngroups = (min(SW_SB, p.L - sb * SW_SB) + 7) >> 3;
+    for (int g = 0; g < ngroups; ++g) group(g, sb * SW_SB + 8 * g);
+    __syncthreads();  // every wave is done reading this superblock
+    if (more) produce(pre, sb + 1);
+    __syncthreads();
+  }
+  if (ssm_state)
+    *reinterpret_cast<float2 *>(ssm_state + ((size_t)b * p.Di + chg) * NS + 2 * ng) = make_float2(h0, h1);
+}
+
 // ---------------------------------------------------------------- decode: one step
 // 4 lanes per channel, each owning 4 of the 16 states as one float4.  FUSE_DT: the step also forms
 // its own dt code, dt_q = q(W_dt[d, :] . dt_low[b, :], m_dt) (dt_proj, K = dt_rank): the four lanes of
@@ -552,6 +766,14 @@ Dev make_dev(const ScanArgs &a) {
 // never shorter than 16 tokens.
 void choose_chunks(int Bt, int L, int Di, int *T, int *nchunks) {
   const long per_chunk = (long)Bt * ((Di + SCAN_THREADS - 1) / SCAN_THREADS);
+  // Plenty of workgroups even at one staging block of B / C per chunk: 64-token chunks measure 4-6 % faster
+  // than the longer ones the rule below would take (three workgroups are resident per CU, so many short
+  // ones fill the tail better, and a chunk of exactly one staging block has no ragged second block).
+  if (per_chunk * ((L + TB - 1) / TB) >= 1280) {
+    *T = TB;
+    *nchunks = (L + TB - 1) / TB;
+    return;
+  }
   const int max_chunks = (L + 15) / 16;
   int best_n = max_chunks > 0 ? max_chunks : 1;
   for (int n = 1; n <= max_chunks; ++n) {
@@ -583,10 +805,72 @@ size_t scan_workspace_bytes(int Bt, int L, int Di) {
   return hloc + ssum;
 }
 
+// 0: the cheaper form by the estimate below, 1: always chunked, 2: one sweep wherever its layout rules hold
+std::atomic<int> g_scan_variant_hook{0};
+
+namespace {
+
+int scan_x_mode(const ScanArgs &a) {
+  return a.x_f16 ? X_F16 : (a.s_x_slot ? X_I8DYN : (a.x_format == QUAMBA_XFMT_E4M3 ? X_E4M3 : (a.x_format == QUAMBA_XFMT_LOG2 ? X_LOG2 : X_I8)));
+}
+
+// The sweep reads x, z and dt four channels at a time, B and C four states at a time and the state as pairs.
+bool sweep_layout_ok(const ScanArgs &a) {
+  if (a.x_f16 || a.L < 1 || a.Bt < 1 || a.Bt > 65535 || a.Di % SW_CH) return false;
+  if (!aligned(a.x_q, 4) || !aligned(a.z_q, 4) || a.ldz % 4 || !aligned(a.B_q, 4) || !aligned(a.C_q, 4) || a.ldbc % 4 ||
+      !aligned(a.A_q, 2) || (a.ssm_state && !aligned(a.ssm_state, 8)))
+    return false;
+  if (a.dtlow_q)
+    return a.W_dt && a.dt_out && a.R >= 16 && a.R <= 256 && a.R % 16 == 0 && a.lddl % 16 == 0 && a.lddl >= a.R &&
+           aligned(a.dtlow_q, 16) && aligned(a.W_dt, 16) && aligned(a.dt_out, 4);
+  return aligned(a.dt_q, 4);
+}
+
+// Which form is faster, from fits to measured times (microseconds; W = workgroups of the sweep = Bt * Di / 32,
+// k = workgroups per CU):
+//   sweep    3 + L * s(k): a wave alone on its SIMD walks a token in 78 ns (its own latencies: one instruction
+//            per 5.4 clocks); two per SIMD 98 ns; from three on the SIMD is busy, 40 ns per token and wave
+//   chunked  18 + L * (W / 256) * c: three launches and the carry, then 69 ns per token and 32-channel block
+//            of a CU (58 ns once the chip is full): every exponential is taken twice
+// so the sweep takes the short sequences and the batches, the chunked form a long single sequence.
+bool sweep_is_cheaper(const ScanArgs &a) {
+  const double W = (double)a.Bt * (a.Di / SW_CH);
+  const int k = (int)std::ceil(W / 256.0);
+  const double s = k <= 1 ? 0.078 : (k == 2 ? 0.098 : 0.040 * k);
+  const double sweep = 3.0 + a.L * s;
+  const double chunked = 18.0 + (double)a.L * (W / 256.0) * (W <= 320 ? 0.069 : 0.058);
+  return sweep < chunked;
+}
+
+template <int NK, int XM>
+int run_sweep(const Dev &p, const ScanArgs &a, hipStream_t st) {
+  hipLaunchKernelGGL((scan_sweep_kernel<NK, XM>), dim3(a.Di / SW_CH, a.Bt), dim3(SW_THREADS), 0, st, p, a.ssm_state);
+  QUAMBA_LAUNCH_CHECK();
+  return QUAMBA_OK;
+}
+
+template <int XM>
+int dispatch_sweep(const Dev &p, const ScanArgs &a, hipStream_t st) {
+  if (!a.dtlow_q) return run_sweep<0, XM>(p, a, st);
+  if (a.R <= 192) return run_sweep<3, XM>(p, a, st);
+  return run_sweep<4, XM>(p, a, st);
+}
+
+}  // namespace
+
 int launch_scan_prefill(const ScanArgs &a, void *ws, size_t ws_bytes, hipStream_t st) {
   if (ws_bytes < scan_workspace_bytes(a.Bt, a.L, a.Di))
     return fail(QUAMBA_EWORKSPACE, "scan: workspace %zu < %zu", ws_bytes, scan_workspace_bytes(a.Bt, a.L, a.Di));
   Dev p = make_dev(a);
+  const int variant = g_scan_variant_hook.load(std::memory_order_relaxed);
+  if (variant != 1 && sweep_layout_ok(a) && (variant == 2 || sweep_is_cheaper(a))) {
+    switch (scan_x_mode(a)) {
+      case X_E4M3: return dispatch_sweep<X_E4M3>(p, a, st);
+      case X_LOG2: return dispatch_sweep<X_LOG2>(p, a, st);
+      case X_I8DYN: return dispatch_sweep<X_I8DYN>(p, a, st);
+      default: return dispatch_sweep<X_I8>(p, a, st);
+    }
+  }
   choose_chunks(a.Bt, a.L, a.Di, &p.T, &p.nchunks);
   if ((long long)p.T * std::max(a.ldz, (a.y_f32 ? 4 : 2) * a.Di) > 0x7fffffffLL)  // 32-bit offsets inside a chunk
     return fail(QUAMBA_EUNSUPPORTED, "scan: a chunk of %d tokens x %d channels exceeds 2^31 bytes", p.T, a.Di);
@@ -594,7 +878,7 @@ int launch_scan_prefill(const ScanArgs &a, void *ws, size_t ws_bytes, hipStream_
   p.ssum = reinterpret_cast<float *>(static_cast<char *>(ws) +
                                      align_up((size_t)a.Bt * p.nchunks * a.Di * NS * sizeof(float), 256));
   dim3 grid((a.Di + SCAN_THREADS - 1) / SCAN_THREADS, p.nchunks, a.Bt);
-  const int xm = a.x_f16 ? X_F16 : (a.s_x_slot ? X_I8DYN : (a.x_format == QUAMBA_XFMT_E4M3 ? X_E4M3 : (a.x_format == QUAMBA_XFMT_LOG2 ? X_LOG2 : X_I8)));
+  const int xm = scan_x_mode(a);
 #define QUAMBA_XM_SWITCH(CALL) \
   switch (xm) {                \
     case X_F16: CALL(X_F16); break;   \
@@ -634,7 +918,7 @@ int launch_scan_step(const ScanArgs &a, hipStream_t st) {
                                      "partial results");
   Dev p = make_dev(a);
   p.L = 1;
-  const int xm = a.x_f16 ? X_F16 : (a.s_x_slot ? X_I8DYN : (a.x_format == QUAMBA_XFMT_E4M3 ? X_E4M3 : (a.x_format == QUAMBA_XFMT_LOG2 ? X_LOG2 : X_I8)));
+  const int xm = scan_x_mode(a);
   const size_t n = (size_t)a.Bt * a.Di * 4;
   if (a.dtlow_q) {
     if (!a.W_dt || a.R < 16 || a.R % 16 || a.lddl % 16 || a.lddl < a.R || !aligned(a.dtlow_q, 16) || !aligned(a.W_dt, 16))
@@ -689,3 +973,5 @@ int launch_scan_step(const ScanArgs &a, hipStream_t st) {
 #undef QUAMBA_XM_SWITCH
 
 }  // namespace quamba
+
+extern "C" void quamba_debug_set_scan_variant(int v) { quamba::g_scan_variant_hook.store(v); }

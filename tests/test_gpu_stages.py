@@ -212,10 +212,20 @@ def _scan_inputs(rng, Bt, L, Di, N=16):
     return sc, x, dt, xz, dbc, A, D, bias
 
 
+@pytest.fixture(params=["chunked", "sweep"])
+def scan_variant(request):
+    """Both forms of the prefill scan: three chunked passes, and one sweep per sequence (taken wherever its
+    layout rules hold: channel counts that are not multiples of 32 run the chunked form under either setting)."""
+    Q.quamba_debug_set_scan_variant({"chunked": 1, "sweep": 2}[request.param])
+    yield request.param
+    Q.quamba_debug_set_scan_variant(0)
+
+
 @pytest.mark.parametrize("Bt,L,Di,with_h0", [(1, 1, 64, False), (2, 45, 128, True), (1, 300, 320, False),
                                               (3, 67, 192, True), (1, 1000, 256, True), (1, 256, 1536, False),
-                                              (2, 131, 1100, True), (1, 2048, 5120, True)])
-def test_scan_prefill(Bt, L, Di, with_h0):
+                                              (2, 131, 1100, True), (1, 2048, 5120, True), (2, 129, 64, True),
+                                              (1, 128, 96, False), (2, 8, 32, True)])
+def test_scan_prefill(Bt, L, Di, with_h0, scan_variant):
     rng = np.random.default_rng(L * 31 + Di)
     sc, x, dt, xz, dbc, A, D, bias = _scan_inputs(rng, Bt, L, Di)
     R = 48
@@ -243,7 +253,7 @@ def test_scan_prefill(Bt, L, Di, with_h0):
                                                 (1, 256, 1536, 48, False), (1, 130, 100, 80, False),
                                                 # the 2.8B layer at 2048 tokens and the Jamba-shaped one at 4096
                                                 (1, 2048, 5120, 160, False), (1, 4096, 8192, 256, True)])
-def test_scan_prefill_with_fused_dt_proj(Bt, L, Di, R, with_h0):
+def test_scan_prefill_with_fused_dt_proj(Bt, L, Di, R, with_h0, scan_variant):
     """dt_q computed inside the scan's first pass: bit-exact codes, same scan tolerances."""
     rng = np.random.default_rng(L * 17 + Di + R)
     sc, x, _, xz, _, A, D, bias = _scan_inputs(rng, Bt, L, Di)
@@ -291,7 +301,7 @@ def test_scan_prefill_with_fused_dt_proj_rejects_odd_rank():
 
 
 @pytest.mark.parametrize("prefill", [False, True])
-def test_scan_output_at_the_edge_of_half_precision(prefill):
+def test_scan_output_at_the_edge_of_half_precision(prefill, scan_variant):
     """The gated scan output is rounded to half precision once (Section 4.2: the quantized SSM "outputs half
     precision"): values up to the largest finite half (65504) come out finite and equal to the oracle's, values
     beyond it become infinities of the right sign on both sides (IEEE conversion, no saturation)."""
