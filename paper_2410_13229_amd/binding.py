@@ -246,6 +246,10 @@ def lib():
     path = lib_path()
     if not os.path.exists(path):
         raise QuambaError(-100, f"{path} not found: build it with `python -m paper_2410_13229_amd.build`")
+    try:  # a process that also uses PyTorch must end up with one HIP runtime: PyTorch's, loaded first
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     L = C.CDLL(path)
     vp, i, f, sz = C.c_void_p, C.c_int, C.c_float, C.c_size_t
     P = C.POINTER
