@@ -365,8 +365,12 @@ __device__ __forceinline__ float dpp_f(float v) {
 }
 
 // NK: k steps of 64 the dt_proj contraction may take (dt_rank <= 64 NK); 0: dt_q is read, not computed.
-template <int NK, int XM>
-__global__ __launch_bounds__(SW_THREADS, 3) void scan_sweep_kernel(Dev p, float *__restrict__ ssm_state) {
+// LAT: the form for one or two workgroups per CU, where a wave has its SIMD (almost) to itself and nothing but
+// its own instruction order hides latencies: the LDS reads of group g + 1 are in flight under group g, the 16
+// exponentials of a group are issued ahead of the two recurrence chains that consume them, and the gate of
+// group g - 1 (a serial chain with two transcendentals) is spread between them.
+template <int NK, int XM, bool LAT>
+__global__ __launch_bounds__(SW_THREADS, LAT ? 1 : 3) void scan_sweep_kernel(Dev p, float *__restrict__ ssm_state) {
   constexpr bool FUSE_DT = NK > 0;
   constexpr int NKR = FUSE_DT ? NK : 1;
   __shared__ __attribute__((aligned(16))) float2 sDU[SW_SB][SW_CH + 1];  // (dt, dt x); odd pitch: a tile's token rows on different banks
@@ -495,7 +499,16 @@ __global__ __launch_bounds__(SW_THREADS, 3) void scan_sweep_kernel(Dev p, float 
     }
   };
 
-  const bool want_f32 = p.y_f32 != nullptr;
+  // outputs of this sequence behind buffer descriptors: a lane stores at 32-bit offset (token * Di + channel) and a
+  // token past the end becomes an offset past the end, which the range test drops (no branch around the store);
+  // the optional fp32 copy is an empty descriptor when it is not asked for
+  const auto rg = buffer_over(p.g16 + seq0 * p.Di, p.L * p.Di * 2);
+  const auto ry = p.y_f32 ? buffer_over(p.y_f32 + seq0 * p.Di, p.L * p.Di * 4) : buffer_over(p.x_q, 0);
+  auto store_g = [&](int tok, float gv) {
+    const unsigned e = tok >= 0 && tok < p.L ? static_cast<unsigned>(tok * p.Di + chg) : 0x1fffffffu;
+    buffer_store_f16(rg, 2 * e, 0, gv);
+    buffer_store_f32(ry, 4 * e, 0, gv);
+  };
   auto group = [&](int g, int tok0) {  // tok0: index in the sequence of the group's first token
     float yp[8];
 #pragma unroll
@@ -524,13 +537,75 @@ __global__ __launch_bounds__(SW_THREADS, 3) void scan_sweep_kernel(Dev p, float 
     }
     const float keep = up1 ? q2[1] : q2[0], send = up1 ? q2[0] : q2[1];
     const float y = keep + dpp_f<0xB1>(send) + dx;  // quad_perm [1, 0, 3, 2]
-    const float gv = silu_gate(y, zv);
-    const int tok = tok0 + ng;
-    if (tok < p.L) {
-      const size_t o = (seq0 + tok) * p.Di + chg;
-      p.g16[o] = __float2half_rn(gv);
-      if (want_f32) p.y_f32[o] = gv;
+    store_g(tok0 + ng, silu_gate(y, zv));
+  };
+
+  // ---- the latency-ordered form of the same group
+  struct Rec {
+    float2 du[8];
+    float4 bc[8];
+    float dx;
+    int z;
+  };
+  auto load = [&](Rec &r, int g) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      r.du[j] = sDU[8 * g + j][chl];
+      r.bc[j] = sBC[8 * g + j][ng];
     }
+    r.dx = sDX[8 * g + ng][chl];
+    r.z = static_cast<int>(sZ[8 * g + ng][chl]);
+  };
+  struct Pending {  // a group whose sums are complete and whose gate is still to be applied
+    float y, zs;
+    int tok;
+  };
+  auto group_lat = [&](const Rec &r, int tok0, Pending &pend) {
+    float e0[8], e1[8], ub0[8], ub1[8];
+    float gt = 0.f, gy = pend.y, gz = pend.zs;
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float m0 = r.du[j].x * a20, m1 = r.du[j].x * a21;
+      e0[j] = exp2_fast(m0);
+      ub0[j] = r.du[j].y * r.bc[j].x;
+      e1[j] = exp2_fast(m1);
+      ub1[j] = r.du[j].y * r.bc[j].y;
+      // the previous group's gate, one step per token of this one
+      if (j == 0) gt = exp2_fast(-gz * LOG2E);
+      if (j == 2) gt = 1.f + gt;
+      if (j == 4) gt = __builtin_amdgcn_rcpf(gt);
+      if (j == 6) gy = gy * gz * gt;
+    }
+    store_g(pend.tok, gy);
+    __builtin_amdgcn_sched_barrier(0);
+    float yp[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      h0 = __builtin_fmaf(e0[j], h0, ub0[j]);
+      h1 = __builtin_fmaf(e1[j], h1, ub1[j]);
+      yp[j] = __builtin_fmaf(r.bc[j].w, h1, r.bc[j].z * h0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    float q4[4], q2[2];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const float keep = up4 ? yp[4 + k] : yp[k], send = up4 ? yp[k] : yp[4 + k];
+      q4[k] = keep + dpp_f<0x141>(send);
+    }
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+      const float keep = up2 ? q4[2 + k] : q4[k], send = up2 ? q4[k] : q4[2 + k];
+      q2[k] = keep + dpp_f<0x4E>(send);
+    }
+    const float keep = up1 ? q2[1] : q2[0], send = up1 ? q2[0] : q2[1];
+    pend.y = keep + dpp_f<0xB1>(send) + r.dx;
+    pend.zs = p.s_z * static_cast<float>(r.z);
+    pend.tok = tok0 + ng;
+  };
+  auto flush = [&](Pending &pend) {  // the gate of the last group of a superblock
+    store_g(pend.tok, silu_gate(pend.y, pend.zs));
+    pend.tok = -1;
   };
 
   const int nsb = (p.L + SW_SB - 1) / SW_SB;
@@ -542,7 +617,20 @@ __global__ __launch_bounds__(SW_THREADS, 3) void scan_sweep_kernel(Dev p, float 
     const bool more = sb + 1 < nsb;
     if (more) issue(pre, sb + 1);
     const int ngroups = (min(SW_SB, p.L - sb * SW_SB) + 7) >> 3;
-    for (int g = 0; g < ngroups; ++g) group(g, sb * SW_SB + 8 * g);
+    if constexpr (LAT) {
+      Rec ra, rb;
+      Pending pend{0.f, 0.f, -1};
+      load(ra, 0);
+      for (int g = 0; g < ngroups; g += 2) {
+        if (g + 1 < ngroups) load(rb, g + 1);
+        group_lat(ra, sb * SW_SB + 8 * g, pend);
+        if (g + 2 < ngroups) load(ra, g + 2);
+        if (g + 1 < ngroups) group_lat(rb, sb * SW_SB + 8 * g + 8, pend);
+      }
+      flush(pend);
+    } else {
+      for (int g = 0; g < ngroups; ++g) group(g, sb * SW_SB + 8 * g);
+    }
     __syncthreads();  // every wave is done reading this superblock
     if (more) produce(pre, sb + 1);
     __syncthreads();
@@ -817,6 +905,7 @@ int scan_x_mode(const ScanArgs &a) {
 // The sweep reads x, z and dt four channels at a time, B and C four states at a time and the state as pairs.
 bool sweep_layout_ok(const ScanArgs &a) {
   if (a.x_f16 || a.L < 1 || a.Bt < 1 || a.Bt > 65535 || a.Di % SW_CH) return false;
+  if ((long long)a.L * a.Di * 4 >= 0x7fffffffLL) return false;  // 32-bit byte offsets inside one sequence's outputs
   if (!aligned(a.x_q, 4) || !aligned(a.z_q, 4) || a.ldz % 4 || !aligned(a.B_q, 4) || !aligned(a.C_q, 4) || a.ldbc % 4 ||
       !aligned(a.A_q, 2) || (a.ssm_state && !aligned(a.ssm_state, 8)))
     return false;
@@ -828,32 +917,42 @@ bool sweep_layout_ok(const ScanArgs &a) {
 
 // Which form is faster, from fits to measured times (microseconds; W = workgroups of the sweep = Bt * Di / 32,
 // k = workgroups per CU):
-//   sweep    3 + L * s(k): a wave alone on its SIMD walks a token in 78 ns (its own latencies: one instruction
-//            per 5.4 clocks); two per SIMD 98 ns; from three on the SIMD is busy, 40 ns per token and wave
-//   chunked  18 + L * (W / 256) * c: three launches and the carry, then 69 ns per token and 32-channel block
-//            of a CU (58 ns once the chip is full): every exponential is taken twice
+//   sweep    3.6 + L * s(k): a wave alone on its SIMD walks a token in 65 ns (a lone wave issues one instruction
+//            of any kind per 5.4 clocks, and a token costs it about 27); two per SIMD 98 ns; from three on the
+//            SIMD is busy, 40 ns per token and wave
+//   chunked  30 + L * (W / 256) * 52 ns: three launches and the carry, every exponential taken twice
 // so the sweep takes the short sequences and the batches, the chunked form a long single sequence.
 bool sweep_is_cheaper(const ScanArgs &a) {
   const double W = (double)a.Bt * (a.Di / SW_CH);
   const int k = (int)std::ceil(W / 256.0);
-  const double s = k <= 1 ? 0.078 : (k == 2 ? 0.098 : 0.040 * k);
-  const double sweep = 3.0 + a.L * s;
-  const double chunked = 18.0 + (double)a.L * (W / 256.0) * (W <= 320 ? 0.069 : 0.058);
+  const double s = k <= 1 ? 0.0645 : (k == 2 ? 0.098 : 0.040 * k);
+  const double sweep = 3.6 + a.L * s;
+  const double chunked = 30.0 + (double)a.L * (W / 256.0) * 0.052;
   return sweep < chunked;
 }
 
-template <int NK, int XM>
+template <int NK, int XM, bool LAT>
 int run_sweep(const Dev &p, const ScanArgs &a, hipStream_t st) {
-  hipLaunchKernelGGL((scan_sweep_kernel<NK, XM>), dim3(a.Di / SW_CH, a.Bt), dim3(SW_THREADS), 0, st, p, a.ssm_state);
+  hipLaunchKernelGGL((scan_sweep_kernel<NK, XM, LAT>), dim3(a.Di / SW_CH, a.Bt), dim3(SW_THREADS), 0, st, p, a.ssm_state);
   QUAMBA_LAUNCH_CHECK();
   return QUAMBA_OK;
 }
 
+// lat: at most one workgroup per CU, where the latency-ordered form pays: 10-15 % (with two per CU it
+// measures the same as the plain form); compiled for int8 x on the calibrated grid only
 template <int XM>
 int dispatch_sweep(const Dev &p, const ScanArgs &a, hipStream_t st) {
-  if (!a.dtlow_q) return run_sweep<0, XM>(p, a, st);
-  if (a.R <= 192) return run_sweep<3, XM>(p, a, st);
-  return run_sweep<4, XM>(p, a, st);
+  const bool lat = XM == X_I8 && (long)a.Bt * (a.Di / SW_CH) <= 256;
+  if constexpr (XM == X_I8) {
+    if (lat) {
+      if (!a.dtlow_q) return run_sweep<0, XM, true>(p, a, st);
+      if (a.R <= 192) return run_sweep<3, XM, true>(p, a, st);
+      return run_sweep<4, XM, true>(p, a, st);
+    }
+  }
+  if (!a.dtlow_q) return run_sweep<0, XM, false>(p, a, st);
+  if (a.R <= 192) return run_sweep<3, XM, false>(p, a, st);
+  return run_sweep<4, XM, false>(p, a, st);
 }
 
 }  // namespace

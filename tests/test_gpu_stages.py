@@ -224,7 +224,8 @@ def scan_variant(request):
 @pytest.mark.parametrize("Bt,L,Di,with_h0", [(1, 1, 64, False), (2, 45, 128, True), (1, 300, 320, False),
                                               (3, 67, 192, True), (1, 1000, 256, True), (1, 256, 1536, False),
                                               (2, 131, 1100, True), (1, 2048, 5120, True), (2, 129, 64, True),
-                                              (1, 128, 96, False), (2, 8, 32, True)])
+                                              (1, 128, 96, False), (2, 8, 32, True),
+                                              (9, 40, 1024, True)])  # more than one workgroup per CU in the sweep
 def test_scan_prefill(Bt, L, Di, with_h0, scan_variant):
     rng = np.random.default_rng(L * 31 + Di)
     sc, x, dt, xz, dbc, A, D, bias = _scan_inputs(rng, Bt, L, Di)
@@ -252,7 +253,8 @@ def test_scan_prefill(Bt, L, Di, with_h0, scan_variant):
                                                 (3, 67, 192, 32, True), (1, 1000, 256, 256, True),
                                                 (1, 256, 1536, 48, False), (1, 130, 100, 80, False),
                                                 # the 2.8B layer at 2048 tokens and the Jamba-shaped one at 4096
-                                                (1, 2048, 5120, 160, False), (1, 4096, 8192, 256, True)])
+                                                (1, 2048, 5120, 160, False), (1, 4096, 8192, 256, True),
+                                                (9, 70, 1024, 64, True)])  # more than one sweep workgroup per CU
 def test_scan_prefill_with_fused_dt_proj(Bt, L, Di, R, with_h0, scan_variant):
     """dt_q computed inside the scan's first pass: bit-exact codes, same scan tolerances."""
     rng = np.random.default_rng(L * 17 + Di + R)
