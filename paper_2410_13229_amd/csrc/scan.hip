@@ -16,6 +16,8 @@
 //   pass 2  per (channel, n): walk the chunks in order, h_start[c+1] = P_c h_start[c] + h_loc[c]
 //           with P_c = exp(A * sum_c dt); emits the start state of every chunk and h_L
 //   pass 3  per (chunk, channel): rerun the chunk from its true start state and emit g
+// Where sequences x channels alone fill the SIMDs (batches, and any sequence short enough that the three
+// launches dominate) prefill instead walks each sequence once, two states per lane: scan_sweep_kernel below.
 // Decode is a single recurrence step with 4 lanes per channel (float4 state access).
 //
 // Pass 1 can also produce dt_q itself (Section 4.3 fuses operators to save memory traffic and
