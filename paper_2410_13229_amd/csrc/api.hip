@@ -339,8 +339,9 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
   // out_proj with the folded weight, fp16 out; the multiplier carries s_y s_WoutH / n
   {
     GemmEpilogue e{nullptr, out, t.acc_out, Dm, Dm, Dm, sc->m_out, sc->m_out, sc->m_out};
-    const GemmPlan out_plan = gemm_plan(M, Dm, Di, base + p.gemm, p.gemm_bytes);
-    if (defer_out && defer_out->want && decode && g_fuse_decode && !t.acc_out) {
+    const bool can_defer = defer_out && defer_out->want && decode && g_fuse_decode && !t.acc_out;
+    const GemmPlan out_plan = gemm_plan(M, Dm, Di, base + p.gemm, p.gemm_bytes, decode && g_fuse_decode && !can_defer);
+    if (can_defer) {
       const int splits = out_plan.k_splits();
       if (splits > 1 && splits <= 8) {
         e.defer_reduce = true;

@@ -82,7 +82,9 @@ struct GemmPlan {
   bool fuses_conv_step() const { return !gemv && (kind == 7 || kind == 11 || splits > 1); }
   int k_splits() const { return gemv ? 1 : splits; }
 };
-GemmPlan gemm_plan(int M, int N, int K, const void *ws, size_t ws_bytes);
+// single_pass: the caller needs the finished output from this call (nobody downstream adds up partial sums of a
+// split K), so a form that covers K inside one launch is preferred where it is faster than GEMM + reduce.
+GemmPlan gemm_plan(int M, int N, int K, const void *ws, size_t ws_bytes, bool single_pass = false);
 
 // `ws` (may be NULL) lets skinny problems split K; gemm_workspace_bytes is the most they use.
 size_t gemm_workspace_bytes(int M, int N);

@@ -696,7 +696,7 @@ std::atomic<int> g_gemv_max_rows{2};  // the few-row streaming kernels serve M u
 
 using GemmChoice = GemmPlan;
 
-GemmChoice choose_gemm(int M, int N, int K, const void *ws, size_t ws_bytes) {
+GemmChoice choose_gemm(int M, int N, int K, const void *ws, size_t ws_bytes, bool single_pass = false) {
   const int g_gemm_variant = quamba::g_gemm_variant.load(std::memory_order_relaxed);
   const int g_gemm_split = quamba::g_gemm_split.load(std::memory_order_relaxed);
   const int g_gemv_max_rows = quamba::g_gemv_max_rows.load(std::memory_order_relaxed);
@@ -718,6 +718,10 @@ GemmChoice choose_gemm(int M, int N, int K, const void *ws, size_t ws_bytes) {
   //       barriers and twice the waves per tile for the skinny output of a prefill (2048 x 192 x 5120: 8.3 against
   //       10.1 us; with a deeper ring of 128-byte slices, 6 to 12 stages, the time does not move: the loop is bound
   //       by the per-slice barrier and the latency of one round of fragment reads, not by bytes in flight)
+  //   13 = dma 32x32, four K groups of one wave, 256-byte slices, ring of 3: a generation-step output of 64 to 512
+  //       such tiles whose K would otherwise be split over the grid, when nobody downstream can take the partial
+  //       sums (`single_pass`): one launch instead of GEMM + reduce (64 x 2560 x 5120: 7.4 against 9.0 us, 16 rows:
+  //       6.6 against 8.0; two K groups with a ring of 4: 8.8; at K = 8192 the split form stays ahead, 11.0 against 11.3)
   //   11 = dma 64x64, two K groups of 4 waves, 256-byte slices, ring of 3: the same job when K is a
   //       multiple of 256; half as many workgroups re-read the activation rows (64 x 10240 x 2560:
   //       7.5 against 8.0 us, 64 x 16384 x 4096: 13.6 against 14.6 us)
@@ -766,7 +770,11 @@ GemmChoice choose_gemm(int M, int N, int K, const void *ws, size_t ws_bytes) {
   const long tiles64 = (long)((M + 63) / 64) * ((N + 63) / 64);
   const bool skinny_unsplit = N <= 512 && tiles64 > 256;
   if ((K % 256) == 0 && kind == 5 && M > 64 && !skinny_unsplit && tiles64 <= 512) kind = 9;
-  if (g_gemm_variant == 12 && (K % 256) == 0) kind = 12;
+  if (single_pass && M <= 64 && (K % 256) == 0 && K <= 6144 && (kind == 5 || kind == 9)) {
+    const long tiles_s = (long)((M + 31) / 32) * ((N + 31) / 32);
+    if (tiles_s >= 64 && tiles_s <= 512) kind = 13;
+  }
+  if ((g_gemm_variant == 12 || g_gemm_variant == 13) && (K % 256) == 0) kind = g_gemm_variant;
   if (g_gemm_variant >= 0 && g_gemm_variant <= 11 &&
       (g_gemm_variant < 2 || (g_gemm_variant == 3 && k64) || (g_gemm_variant != 3 && k128)) &&
       (g_gemm_variant != 11 || (K % 256) == 0))
@@ -774,7 +782,7 @@ GemmChoice choose_gemm(int M, int N, int K, const void *ws, size_t ws_bytes) {
 
   // split K when the output has too few tiles to fill 256 CUs and K is deep
   int splits = 1;
-  const int slice = (kind == 8 || kind == 9 || kind == 11 || kind == 12) ? 256 : ((kind == 2 || kind >= 4) ? 128 : 64);
+  const int slice = (kind == 8 || kind == 9 || kind == 11 || kind == 12 || kind == 13) ? 256 : ((kind == 2 || kind >= 4) ? 128 : 64);
   const int nslices = (K + slice - 1) / slice;
   if ((kind == 0 || kind == 3 || kind == 5 || kind == 9) && ws != nullptr) {
     const int tiles = ((M + 63) / 64) * ((N + 63) / 64);
@@ -799,7 +807,9 @@ size_t gemm_workspace_bytes(int M, int N) {
   return (size_t)8 * M * N * sizeof(int32_t);
 }
 
-GemmPlan gemm_plan(int M, int N, int K, const void *ws, size_t ws_bytes) { return choose_gemm(M, N, K, ws, ws_bytes); }
+GemmPlan gemm_plan(int M, int N, int K, const void *ws, size_t ws_bytes, bool single_pass) {
+  return choose_gemm(M, N, K, ws, ws_bytes, single_pass);
+}
 
 int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, int N, int K,
                    const GemmEpilogue &epi, void *ws, size_t ws_bytes, hipStream_t st, const GemmPlan *plan) {
@@ -843,6 +853,7 @@ int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, i
     case 9: rc = run_dma<64, 64, 2, 2, 2, 256, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
     case 10: rc = run_dma<256, 256, 4, 2, 2, 128, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
     case 12: rc = run_dma<64, 32, 2, 1, 3, 256, 2, 4>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
+    case 13: rc = run_dma<32, 32, 1, 1, 3, 256, 2, 4>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
     default: rc = run_reg<128, 128, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
   }
   if (rc != QUAMBA_OK || splits == 1 || epi.defer_reduce) return rc;
