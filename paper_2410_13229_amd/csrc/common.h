@@ -77,9 +77,9 @@ int gemv_max_rows();
 struct GemmPlan {
   bool gemv;  // the few-row streaming kernel
   int kind, splits, slices_per_split;
-  // the launch ends in an epilogue that can carry the conv step (the 64 x 32 / two-K-group 64 x 64
+  // the launch ends in an epilogue that can carry the conv step (the 64 x 32, 32 x 32 and two-K-group 64 x 64
   // tiles of a wide generation-step output, or the reduce kernel of a split K)
-  bool fuses_conv_step() const { return !gemv && (kind == 7 || kind == 11 || splits > 1); }
+  bool fuses_conv_step() const { return !gemv && (kind == 7 || kind == 11 || kind == 13 || splits > 1); }
   int k_splits() const { return gemv ? 1 : splits; }
 };
 // single_pass: the caller needs the finished output from this call (nobody downstream adds up partial sums of a

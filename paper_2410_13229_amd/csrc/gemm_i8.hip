@@ -721,7 +721,9 @@ GemmChoice choose_gemm(int M, int N, int K, const void *ws, size_t ws_bytes, boo
   //   13 = dma 32x32, four K groups of one wave, 256-byte slices, ring of 3: a generation-step output of 64 to 512
   //       such tiles whose K would otherwise be split over the grid, when nobody downstream can take the partial
   //       sums (`single_pass`): one launch instead of GEMM + reduce (64 x 2560 x 5120: 7.4 against 9.0 us, 16 rows:
-  //       6.6 against 8.0; two K groups with a ring of 4: 8.8; at K = 8192 the split form stays ahead, 11.0 against 11.3)
+  //       6.6 against 8.0; two K groups with a ring of 4: 8.8; at K = 8192 the split form stays ahead, 11.0 against 11.3);
+  //       also the wide output of a step with at most 32 sequences, where one row of tiles covers them
+  //       (4 to 32 x 10240 x 2560: 5.9-6.2 against 7.3-7.5 us for the 64 x 64 form)
   //   11 = dma 64x64, two K groups of 4 waves, 256-byte slices, ring of 3: the same job when K is a
   //       multiple of 256; half as many workgroups re-read the activation rows (64 x 10240 x 2560:
   //       7.5 against 8.0 us, 64 x 16384 x 4096: 13.6 against 14.6 us)
@@ -733,7 +735,8 @@ GemmChoice choose_gemm(int M, int N, int K, const void *ws, size_t ws_bytes, boo
   const long tiles_256 = (long)((M + 255) / 256) * ((N + 319) / 320);
   const long tiles_128 = (long)((M + 127) / 128) * ((N + 159) / 160);
   if (M <= 64)
-    kind = k128 ? ((N + 31) / 32 >= 256 ? ((K % 256) == 0 ? 11 : 7) : 5) : (k64 ? 3 : 0);
+    kind = k128 ? ((N + 31) / 32 >= 256 ? ((K % 256) == 0 ? (M <= 32 && (N + 31) / 32 <= 512 && K <= 6144 ? 13 : 11) : 7) : 5)
+                : (k64 ? 3 : 0);
   else if (N <= 512) {
     kind = k128 ? 5 : (k64 ? 3 : 0);
     // A skinny output with about one 64 x 32 tile per CU and a moderately deep K: those tiles with
@@ -817,7 +820,7 @@ int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, i
   if (c.splits > 1 && (!ws || (size_t)c.splits * M * N * sizeof(int32_t) > ws_bytes))
     return fail(QUAMBA_EWORKSPACE, "gemm: %d K ranges of a %d x %d output do not fit the workspace", c.splits, M, N);
   const bool conv = epi.conv.state != nullptr;
-  if (conv && (c.gemv || !(c.kind == 7 || c.kind == 11 || c.splits > 1) || !epi.out_i8 || epi.e0 % 4 != 0))
+  if (conv && (c.gemv || !(c.kind == 7 || c.kind == 11 || c.kind == 13 || c.splits > 1) || !epi.out_i8 || epi.e0 % 4 != 0))
     return fail(QUAMBA_EUNSUPPORTED, "gemm: this shape (M=%d N=%d K=%d) has no epilogue that carries the conv step", M, N, K);
   if (c.gemv) {
     const size_t lds = (size_t)(M <= 1 ? 1 : (M <= 2 ? 2 : 4)) * K;
@@ -853,7 +856,10 @@ int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, i
     case 9: rc = run_dma<64, 64, 2, 2, 2, 256, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
     case 10: rc = run_dma<256, 256, 4, 2, 2, 128, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
     case 12: rc = run_dma<64, 32, 2, 1, 3, 256, 2, 4>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
-    case 13: rc = run_dma<32, 32, 1, 1, 3, 256, 2, 4>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
+    case 13:
+      rc = conv ? run_dma<32, 32, 1, 1, 3, 256, 2, 4, false, true>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st)
+                : run_dma<32, 32, 1, 1, 3, 256, 2, 4>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st);
+      break;
     default: rc = run_reg<128, 128, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, splits, ks, st); break;
   }
   if (rc != QUAMBA_OK || splits == 1 || epi.defer_reduce) return rc;
