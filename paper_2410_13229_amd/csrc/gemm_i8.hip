@@ -745,14 +745,19 @@ GemmChoice choose_gemm(int M, int N, int K, const void *ws, size_t ws_bytes, boo
     // K = 8192 or with many more tiles the split-K / single-pass 64 x 64 form stays ahead).
     const long tiles_32 = (long)((M + 63) / 64) * ((N + 31) / 32);
     if (k128 && tiles_32 >= 192 && tiles_32 <= 512 && K <= 6144) kind = (K % 256) == 0 ? 12 : 7;
+    // up to 400 tiles of 32 x 32, four K groups of one wave: 7.9 us at 2048 tokens, 6.9-7.1 at 96 to 1024 (the
+    // 64 x 64 form: 8.4-11.0)
+    if ((K % 256) == 0 && K <= 6144 && (long)((M + 31) / 32) * ((N + 31) / 32) <= 400) kind = 13;
     // Very many rows and an N that 160-wide tiles cover without waste: the 128 x 160 tiles with two
     // K groups (N = 320, K = 8192, 16384 tokens: 56 vs 80 us; at 8192 tokens and below the 64 x 64
     // tiles are ahead again).
     const int n160 = (N + 159) / 160 * 160;
     if (k128 && M >= 16384 && N * 10 >= n160 * 9) kind = 6;
   }
-  else if (k128 && M >= 256 && N >= 640)
-    kind = tiles_256 >= 192 ? 4 : (tiles_128 < 192 ? 5 : (tiles_128 <= 384 ? 6 : 2));  // few big tiles: 64x64 ones
+  else if (k128)
+    // few big tiles: 64x64 ones; up to one 128 x 160 tile per CU: two K groups; up to two: two workgroups per CU
+    // (768 x 10240 x 2560, 384 tiles: 32.0 against 41.1 us for the two-K-group form, which needs a second round)
+    kind = tiles_256 >= 192 ? 4 : (tiles_128 < 192 ? 5 : (tiles_128 <= 256 ? 6 : 2));
   else
     kind = 1;
   if (kind == 4) {
@@ -773,6 +778,14 @@ GemmChoice choose_gemm(int M, int N, int K, const void *ws, size_t ws_bytes, boo
   const long tiles64 = (long)((M + 63) / 64) * ((N + 63) / 64);
   const bool skinny_unsplit = N <= 512 && tiles64 > 256;
   if ((K % 256) == 0 && kind == 5 && M > 64 && !skinny_unsplit && tiles64 <= 512) kind = 9;
+  // More than 64 rows and still few tiles (short prompts, generation with 65 to 256 sequences): the 32 x 32 tiles
+  // with four K groups cover K in one launch and fill the chip where the 64 x 64 ones would split K or leave CUs
+  // idle (96 to 256 x 2560 x 5120: 7.2-13.0 against 10.3-14.6 us; from about 700 such tiles on the 64 x 64 form is
+  // ahead again: 384 x 2560 x 5120 18.2 against 13.1).
+  if (M > 64 && (K % 256) == 0 && K <= 6144 && (kind == 5 || kind == 9)) {
+    const long tiles_s = (long)((M + 31) / 32) * ((N + 31) / 32);
+    if (N > 512 && tiles_s <= 700) kind = 13;
+  }
   if (single_pass && M <= 64 && (K % 256) == 0 && K <= 6144 && (kind == 5 || kind == 9)) {
     const long tiles_s = (long)((M + 31) / 32) * ((N + 31) / 32);
     if (tiles_s >= 64 && tiles_s <= 512) kind = 13;

@@ -44,6 +44,9 @@ GEMM_SHAPES = [
     # few rows with the deepest K whose rows still fit the streaming kernel's LDS (2 rows) and one that no
     # longer does (3 rows: matrix tiles)
     (2, 64, 16384, 0), (3, 64, 16384, 0),
+    # 65 to 255 rows (short prompts, generation with many sequences) at the 2.8B widths: 32 x 32 tiles with four K
+    # groups for the narrower outputs, 64 x 64 tiles for the wide one
+    (128, 2560, 5120, 0), (200, 10240, 2560, 0), (96, 192, 5120, 0), (255, 2560, 5120, 16),
 ]
 
 
