@@ -282,10 +282,11 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
     GemmEpilogue e{dbc_q, nullptr, t.acc_x, NX, R, R + N, hx ? hx->m_xh_dt : (xa ? xa->m_x_dt : sc->m_x_dt),
                    hx ? hx->m_xh_B : (xa ? xa->m_x_B : sc->m_x_B), hx ? hx->m_xh_C : (xa ? xa->m_x_C : sc->m_x_C),
                    xa ? xa->col_bias : nullptr};
-    const GemmPlan x_plan = gemm_plan(M, NX, Di, base + p.gemm, p.gemm_bytes);
+    // the scan step can add up the partial sums of a split K itself: then the split form is the one wanted
+    const bool x_can_defer = decode && fuse_dt && g_fuse_decode && R <= 256 && !xa && !t.dbc_q && !t.acc_x;
+    const GemmPlan x_plan = gemm_plan(M, NX, Di, base + p.gemm, p.gemm_bytes, x_can_defer);
     x_splits = x_plan.k_splits();
-    dbc_part = decode && fuse_dt && g_fuse_decode && R <= 256 && !xa && !t.dbc_q && !t.acc_x && x_splits > 1 &&
-               x_splits <= 8;
+    dbc_part = x_can_defer && x_splits > 1 && x_splits <= 8;
     e.defer_reduce = dbc_part;
     QUAMBA_TRY(launch_gemm_i8(x_q, Di, hx ? hx->W_xH : qw->W_x, Di, M, NX, Di, e, base + p.gemm, p.gemm_bytes, st, &x_plan));
     QUAMBA_TRY(tap_copy(t.dbc_q, dbc_q, (size_t)M * NX, st));
@@ -340,7 +341,7 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
   {
     GemmEpilogue e{nullptr, out, t.acc_out, Dm, Dm, Dm, sc->m_out, sc->m_out, sc->m_out};
     const bool can_defer = defer_out && defer_out->want && decode && g_fuse_decode && !t.acc_out;
-    const GemmPlan out_plan = gemm_plan(M, Dm, Di, base + p.gemm, p.gemm_bytes, decode && g_fuse_decode && !can_defer);
+    const GemmPlan out_plan = gemm_plan(M, Dm, Di, base + p.gemm, p.gemm_bytes, can_defer);
     if (can_defer) {
       const int splits = out_plan.k_splits();
       if (splits > 1 && splits <= 8) {

@@ -82,9 +82,9 @@ struct GemmPlan {
   bool fuses_conv_step() const { return !gemv && (kind == 7 || kind == 11 || kind == 13 || splits > 1); }
   int k_splits() const { return gemv ? 1 : splits; }
 };
-// single_pass: the caller needs the finished output from this call (nobody downstream adds up partial sums of a
-// split K), so a form that covers K inside one launch is preferred where it is faster than GEMM + reduce.
-GemmPlan gemm_plan(int M, int N, int K, const void *ws, size_t ws_bytes, bool single_pass = false);
+// partials_wanted: the caller adds up the partial sums of a split K itself (deferred reduce), so the split form is
+// kept where a form that covers K inside one launch would otherwise replace GEMM + reduce kernel.
+GemmPlan gemm_plan(int M, int N, int K, const void *ws, size_t ws_bytes, bool partials_wanted = false);
 
 // `ws` (may be NULL) lets skinny problems split K; gemm_workspace_bytes is the most they use.
 size_t gemm_workspace_bytes(int M, int N);

@@ -696,7 +696,7 @@ std::atomic<int> g_gemv_max_rows{2};  // the few-row streaming kernels serve M u
 
 using GemmChoice = GemmPlan;
 
-GemmChoice choose_gemm(int M, int N, int K, const void *ws, size_t ws_bytes, bool single_pass = false) {
+GemmChoice choose_gemm(int M, int N, int K, const void *ws, size_t ws_bytes, bool partials_wanted = false) {
   const int g_gemm_variant = quamba::g_gemm_variant.load(std::memory_order_relaxed);
   const int g_gemm_split = quamba::g_gemm_split.load(std::memory_order_relaxed);
   const int g_gemv_max_rows = quamba::g_gemv_max_rows.load(std::memory_order_relaxed);
@@ -719,8 +719,8 @@ GemmChoice choose_gemm(int M, int N, int K, const void *ws, size_t ws_bytes, boo
   //       10.1 us; with a deeper ring of 128-byte slices, 6 to 12 stages, the time does not move: the loop is bound
   //       by the per-slice barrier and the latency of one round of fragment reads, not by bytes in flight)
   //   13 = dma 32x32, four K groups of one wave, 256-byte slices, ring of 3: a generation-step output of 64 to 512
-  //       such tiles whose K would otherwise be split over the grid, when nobody downstream can take the partial
-  //       sums (`single_pass`): one launch instead of GEMM + reduce (64 x 2560 x 5120: 7.4 against 9.0 us, 16 rows:
+  //       such tiles whose K would otherwise be split over the grid, unless the caller takes the partial sums
+  //       itself (`partials_wanted`): one launch instead of GEMM + reduce (64 x 2560 x 5120: 7.4 against 9.0 us, 16 rows:
   //       6.6 against 8.0; two K groups with a ring of 4: 8.8; at K = 8192 the split form stays ahead, 11.0 against 11.3);
   //       also the wide output of a step with at most 32 sequences, where one row of tiles covers them
   //       (4 to 32 x 10240 x 2560: 5.9-6.2 against 7.3-7.5 us for the 64 x 64 form)
@@ -744,10 +744,10 @@ GemmChoice choose_gemm(int M, int N, int K, const void *ws, size_t ws_bytes, boo
     // (measured at N = 192, K = 5120: 10.2 vs 12.5 us at M = 2048, 12.4 vs 15.1 at 4096; at
     // K = 8192 or with many more tiles the split-K / single-pass 64 x 64 form stays ahead).
     const long tiles_32 = (long)((M + 63) / 64) * ((N + 31) / 32);
-    if (k128 && tiles_32 >= 192 && tiles_32 <= 512 && K <= 6144) kind = (K % 256) == 0 ? 12 : 7;
+    if (k128 && tiles_32 >= 192 && tiles_32 <= 512 && K <= 8192) kind = (K % 256) == 0 ? 12 : 7;
     // up to 400 tiles of 32 x 32, four K groups of one wave: 7.9 us at 2048 tokens, 6.9-7.1 at 96 to 1024 (the
     // 64 x 64 form: 8.4-11.0)
-    if ((K % 256) == 0 && K <= 6144 && (long)((M + 31) / 32) * ((N + 31) / 32) <= 400) kind = 13;
+    if ((K % 256) == 0 && K <= 8192 && (long)((M + 31) / 32) * ((N + 31) / 32) <= 400) kind = 13;
     // Very many rows and an N that 160-wide tiles cover without waste: the 128 x 160 tiles with two
     // K groups (N = 320, K = 8192, 16384 tokens: 56 vs 80 us; at 8192 tokens and below the 64 x 64
     // tiles are ahead again).
@@ -780,16 +780,24 @@ GemmChoice choose_gemm(int M, int N, int K, const void *ws, size_t ws_bytes, boo
   if ((K % 256) == 0 && kind == 5 && M > 64 && !skinny_unsplit && tiles64 <= 512) kind = 9;
   // More than 64 rows and still few tiles (short prompts, generation with 65 to 256 sequences): the 32 x 32 tiles
   // with four K groups cover K in one launch and fill the chip where the 64 x 64 ones would split K or leave CUs
-  // idle (96 to 256 x 2560 x 5120: 7.2-13.0 against 10.3-14.6 us; from about 700 such tiles on the 64 x 64 form is
-  // ahead again: 384 x 2560 x 5120 18.2 against 13.1).
-  if (M > 64 && (K % 256) == 0 && K <= 6144 && (kind == 5 || kind == 9)) {
+  // idle (96 to 192 x 2560 x 5120: 7.2-9.8 against 10.3-12.4 us; from about 520 such tiles on the 64 x 64 forms are
+  // ahead again: 384 x 2560 x 5120 18.2 against 12.7).
+  if (M > 64 && (K % 256) == 0 && K <= 8192 && (kind == 5 || kind == 9)) {
     const long tiles_s = (long)((M + 31) / 32) * ((N + 31) / 32);
-    if (N > 512 && tiles_s <= 700) kind = 13;
+    if (N > 512 && tiles_s <= 520) kind = 13;
   }
-  if (single_pass && M <= 64 && (K % 256) == 0 && K <= 6144 && (kind == 5 || kind == 9)) {
+  // At most 64 rows: the same tiles instead of 64 x 64 tiles with K split over the grid + reduce kernel, unless
+  // the caller takes the partial sums itself (3 to 64 x 2560 x 5120: 6.8-7.3 against 8.4-9.2 us, x 192: 6.9-7.0
+  // against 8.4-8.8)
+  if (!partials_wanted && M <= 64 && (K % 256) == 0 && K <= 6144 && (kind == 5 || kind == 9)) {
     const long tiles_s = (long)((M + 31) / 32) * ((N + 31) / 32);
-    if (tiles_s >= 64 && tiles_s <= 512) kind = 13;
+    if (tiles_s <= 512) kind = 13;
   }
+  // 129 to 256 tiles of 64 x 64 with deep K: two K groups per tile instead of K split over the grid
+  // (256 / 384 x 2560 x 5120: 12.1 / 12.7 against 13.3 / 14.1 us; 3072 / 4096 x 192 x 5120: 12.3 against 14.1 / 13.3)
+  if (M > 64 && (K % 256) == 0 && K <= 8192 && (kind == 5 || kind == 9 || kind == 12) && tiles64 > 128 && tiles64 <= 256 &&
+      (long)((M + 31) / 32) * ((N + 31) / 32) > (N <= 512 ? 400 : 520))
+    kind = 11;
   if ((g_gemm_variant == 12 || g_gemm_variant == 13) && (K % 256) == 0) kind = g_gemm_variant;
   if (g_gemm_variant >= 0 && g_gemm_variant <= 11 &&
       (g_gemm_variant < 2 || (g_gemm_variant == 3 && k64) || (g_gemm_variant != 3 && k128)) &&
@@ -823,8 +831,8 @@ size_t gemm_workspace_bytes(int M, int N) {
   return (size_t)8 * M * N * sizeof(int32_t);
 }
 
-GemmPlan gemm_plan(int M, int N, int K, const void *ws, size_t ws_bytes, bool single_pass) {
-  return choose_gemm(M, N, K, ws, ws_bytes, single_pass);
+GemmPlan gemm_plan(int M, int N, int K, const void *ws, size_t ws_bytes, bool partials_wanted) {
+  return choose_gemm(M, N, K, ws, ws_bytes, partials_wanted);
 }
 
 int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, int N, int K,
