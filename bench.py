@@ -135,7 +135,7 @@ def bench_model(args, Q, W, torch, np, dev, to_dev):
     ssm = torch.empty((nl, 64, Di, N), dtype=torch.float32, device=dev)
     cs = torch.empty((nl, 64, Di, 3), dtype=torch.float16, device=dev)
     with torch.cuda.stream(stream):
-        for L in (512, 1024, 2048):
+        for L in (128, 512, 1024, 2048):
             tok = to_dev(W.make_tokens(cfg, vocab, batch=1, seqlen=L))
             ws = torch.empty(Q.quamba_model_workspace_bytes(m, 1, L), dtype=torch.uint8, device=dev)
             sec = wall(lambda: Q.quamba_model_prefill(m, tok, 1, L, None, first, ssm, cs, ws, stream), 10)
