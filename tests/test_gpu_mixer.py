@@ -319,7 +319,7 @@ def test_decode_c2_200_consecutive_steps(capsys):
     assert np.isfinite(host(ssm)).all()
 
 
-@pytest.mark.parametrize("name,Bt", [("c2", 64), ("c2", 24), ("c2", 16), ("c2", 7), ("tiny", 6)])
+@pytest.mark.parametrize("name,Bt", [("c2", 64), ("c2", 24), ("c2", 16), ("c2", 7), ("tiny", 6), ("c2", 100)])
 def test_decode_without_taps_is_the_tapped_step(name, Bt):
     """The intermediates are checked link by link in the tapped runs above; without taps the step takes
     the faster epilogues (row-staged stores, the conv step inside in_proj's epilogue from staged codes).
@@ -389,6 +389,15 @@ def test_decode_many_sequences_ragged(Bt, di, rk):
 def test_decode_few_sequences_2p8b_width(Bt):
     """Generation with one or two sequences takes the streaming (no matrix tile) projections, more take
     matrix tiles."""
+    cfg = W.CONFIGS["c2"]
+    w, qw, sc = oracle_setup(cfg)
+    _decode_steps(cfg, Bt, 2, qw, sc, fused_dt=(Bt % 2 == 1))
+
+
+@pytest.mark.parametrize("Bt", [65, 130])
+def test_decode_more_than_64_sequences_2p8b_width(Bt):
+    """Beyond 64 sequences the projections leave the generation tile forms (in_proj no longer carries the conv
+    step, the planner takes its prefill rules): same link-by-link checks, with and without the fused dt_proj."""
     cfg = W.CONFIGS["c2"]
     w, qw, sc = oracle_setup(cfg)
     _decode_steps(cfg, Bt, 2, qw, sc, fused_dt=(Bt % 2 == 1))
