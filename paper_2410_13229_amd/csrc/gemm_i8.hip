@@ -746,8 +746,9 @@ GemmChoice choose_gemm(int M, int N, int K, const void *ws, size_t ws_bytes, boo
     const long tiles_32 = (long)((M + 63) / 64) * ((N + 31) / 32);
     if (k128 && tiles_32 >= 192 && tiles_32 <= 512 && K <= 8192) kind = (K % 256) == 0 ? 12 : 7;
     // up to 400 tiles of 32 x 32, four K groups of one wave: 7.9 us at 2048 tokens, 6.9-7.1 at 96 to 1024 (the
-    // 64 x 64 form: 8.4-11.0)
-    if ((K % 256) == 0 && K <= 8192 && (long)((M + 31) / 32) * ((N + 31) / 32) <= 400) kind = 13;
+    // 64 x 64 form: 8.4-11.0); a generation step whose scan adds up the partial sums keeps the split form (96
+    // sequences: 4.1 us for the GEMM against 8.3 in one launch)
+    if (!partials_wanted && (K % 256) == 0 && K <= 8192 && (long)((M + 31) / 32) * ((N + 31) / 32) <= 400) kind = 13;
     // Very many rows and an N that 160-wide tiles cover without waste: the 128 x 160 tiles with two
     // K groups (N = 320, K = 8192, 16384 tokens: 56 vs 80 us; at 8192 tokens and below the 64 x 64
     // tiles are ahead again).
@@ -782,7 +783,7 @@ GemmChoice choose_gemm(int M, int N, int K, const void *ws, size_t ws_bytes, boo
   // with four K groups cover K in one launch and fill the chip where the 64 x 64 ones would split K or leave CUs
   // idle (96 to 192 x 2560 x 5120: 7.2-9.8 against 10.3-12.4 us; from about 520 such tiles on the 64 x 64 forms are
   // ahead again: 384 x 2560 x 5120 18.2 against 12.7).
-  if (M > 64 && (K % 256) == 0 && K <= 8192 && (kind == 5 || kind == 9)) {
+  if (!partials_wanted && M > 64 && (K % 256) == 0 && K <= 8192 && (kind == 5 || kind == 9)) {
     const long tiles_s = (long)((M + 31) / 32) * ((N + 31) / 32);
     if (N > 512 && tiles_s <= 520) kind = 13;
   }
