@@ -755,20 +755,30 @@ GemmChoice choose_gemm(int M, int N, int K, const void *ws, size_t ws_bytes, boo
     const int n160 = (N + 159) / 160 * 160;
     if (k128 && M >= 16384 && N * 10 >= n160 * 9) kind = 6;
   }
-  else if (k128)
-    // few big tiles: 64x64 ones; up to one 128 x 160 tile per CU: two K groups; up to two: two workgroups per CU
-    // (768 x 10240 x 2560, 384 tiles: 32.0 against 41.1 us for the two-K-group form, which needs a second round)
-    kind = tiles_256 >= 192 ? 4 : (tiles_128 < 192 ? 5 : (tiles_128 <= 256 ? 6 : 2));
-  else
+  else if (k128 && tiles_128 < 192)
+    kind = 5;  // few big tiles: 64 x 64 ones
+  else if (k128) {
+    // Four forms compete for the large outputs; which is fastest depends on how the tile count fills rounds of
+    // 256 CUs, so each is priced as rounds x operations per tile / the rate one resident workgroup sustains
+    // (measured with the chip full: 256 x 320 tiles 8.7 TOP/s, 256 x 256 8.3, 128 x 160 with two K groups 5.8,
+    // all one workgroup per CU; 128 x 160 with two workgroups per CU 3.44 each, and a last round that leaves
+    // them alone on their CUs runs in 0.6 of a tile time).  1280 x 10240 x 2560: 39.4 us with the 256 x 256
+    // tiles this picks (200 tiles, one round) against 54.0 with 128 x 160 (640 tiles); 5120 x 2560 x 5120:
+    // 80.1 against 91.7; 2560 x 4096 x 8192: 108.9 against 135.4.
+    auto rounds1 = [](long t) { return (double)((t + 255) / 256); };
+    const long t4 = tiles_256, t10 = (long)((M + 255) / 256) * ((N + 255) / 256), t2 = tiles_128;
+    const double e4 = rounds1(t4) * (256.0 * 320.0) / 8.7;
+    const double e10 = rounds1(t10) * (256.0 * 256.0) / 8.3;
+    const double e6 = rounds1(t2) * (128.0 * 160.0) / 5.8;
+    const long r2 = t2 % 512;
+    const double e2 = ((double)(t2 / 512) + (r2 == 0 ? 0.0 : (r2 <= 256 ? 0.6 : 1.0))) * (128.0 * 160.0) / 3.44;
+    kind = 4;
+    double best = e4;
+    if (e10 < best * 0.97) { kind = 10; best = e10; }
+    if (e6 < best * 0.97) { kind = 6; best = e6; }
+    if (e2 < best * 0.97) { kind = 2; best = e2; }
+  } else
     kind = 1;
-  if (kind == 4) {
-    // 256 x 256 tiles instead when they fill the rounds of 256 CUs (and the N edge) clearly better
-    auto fill = [&](int bn) {
-      const long tn = (N + bn - 1) / bn, t = (long)((M + 255) / 256) * tn;
-      return (double)t / (double)((t + 255) / 256 * 256) * (double)N / (double)(tn * bn);
-    };
-    if (fill(256) > fill(320) + 0.05) kind = 10;
-  }
   // deep K in whole 256-byte slices: half as many barriers for the same bytes
   if ((K % 256) == 0 && kind == 6) kind = 8;
   // (decode-sized M measured better with 128-byte slices, and so do skinny outputs, N <= 512, with so
