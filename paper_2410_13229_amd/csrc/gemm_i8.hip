@@ -696,6 +696,54 @@ std::atomic<int> g_gemv_max_rows{2};  // the few-row streaming kernels serve M u
 
 using GemmChoice = GemmPlan;
 
+// The four tile forms of a large output, priced in output elements per unit rate (times 2 K / 10^6: microseconds).
+struct LargePrice {
+  int kind;
+  double units;
+};
+LargePrice price_large(int M, int N) {
+  auto rounds1 = [](long t) { return (double)((t + 255) / 256); };
+  const long t4 = (long)((M + 255) / 256) * ((N + 319) / 320), t10 = (long)((M + 255) / 256) * ((N + 255) / 256);
+  const long t2 = (long)((M + 127) / 128) * ((N + 159) / 160);
+  const double e4 = rounds1(t4) * (256.0 * 320.0) / 8.7;
+  const double e10 = rounds1(t10) * (256.0 * 256.0) / 8.3;
+  const double e6 = rounds1(t2) * (128.0 * 160.0) / 5.8;
+  const long r2 = t2 % 512;
+  const double e2 = ((double)(t2 / 512) + (r2 == 0 ? 0.0 : (r2 <= 256 ? 0.6 : 1.0))) * (128.0 * 160.0) / 3.44;
+  LargePrice p{4, e4};
+  if (e10 < p.units * 0.97) p = LargePrice{10, e10};
+  if (e6 < p.units * 0.97) p = LargePrice{6, e6};
+  if (e2 < p.units * 0.97) p = LargePrice{2, e2};
+  return p;
+}
+
+// Microseconds a row range of the output costs: the large forms by the prices above, smaller outputs by a fit to
+// the slower of their measured rates (8 us + operations at 1.2 POP/s: a pessimistic price keeps the split to cases
+// where the second part is small).
+double price_rows_us(int M, int N, int K) {
+  const long tiles_128 = (long)((M + 127) / 128) * ((N + 159) / 160);
+  if (tiles_128 >= 192) return price_large(M, N).units * 2.0 * K * 1e-6;
+  return 8.0 + 2.0 * M * N * (double)K / 1.2e9;
+}
+
+// Rows [0, Mb) and [Mb, M) as two launches when the first then fills whole rounds of CUs and the rest is cheap:
+// returns Mb, or 0 to keep one launch.  (2304 x 10240 x 2560: 2048 rows in one round of 256 x 320 tiles plus 256
+// rows, instead of two rounds of 256 x 256 tiles.)
+int row_split(int M, int N, int K) {
+  if (M < 512 || (long)((M + 127) / 128) * ((N + 159) / 160) < 192) return 0;
+  const double whole = price_rows_us(M, N, K);
+  double best = whole * 0.92;
+  int at = 0;
+  for (int Mb = (M - 1) / 256 * 256; Mb >= 256 && Mb >= M - 2048; Mb -= 256) {
+    const double two = price_rows_us(Mb, N, K) + price_rows_us(M - Mb, N, K) + 3.0;
+    if (two < best) {
+      best = two;
+      at = Mb;
+    }
+  }
+  return at;
+}
+
 GemmChoice choose_gemm(int M, int N, int K, const void *ws, size_t ws_bytes, bool partials_wanted = false) {
   const int g_gemm_variant = quamba::g_gemm_variant.load(std::memory_order_relaxed);
   const int g_gemm_split = quamba::g_gemm_split.load(std::memory_order_relaxed);
@@ -765,18 +813,7 @@ GemmChoice choose_gemm(int M, int N, int K, const void *ws, size_t ws_bytes, boo
     // them alone on their CUs runs in 0.6 of a tile time).  1280 x 10240 x 2560: 39.4 us with the 256 x 256
     // tiles this picks (200 tiles, one round) against 54.0 with 128 x 160 (640 tiles); 5120 x 2560 x 5120:
     // 80.1 against 91.7; 2560 x 4096 x 8192: 108.9 against 135.4.
-    auto rounds1 = [](long t) { return (double)((t + 255) / 256); };
-    const long t4 = tiles_256, t10 = (long)((M + 255) / 256) * ((N + 255) / 256), t2 = tiles_128;
-    const double e4 = rounds1(t4) * (256.0 * 320.0) / 8.7;
-    const double e10 = rounds1(t10) * (256.0 * 256.0) / 8.3;
-    const double e6 = rounds1(t2) * (128.0 * 160.0) / 5.8;
-    const long r2 = t2 % 512;
-    const double e2 = ((double)(t2 / 512) + (r2 == 0 ? 0.0 : (r2 <= 256 ? 0.6 : 1.0))) * (128.0 * 160.0) / 3.44;
-    kind = 4;
-    double best = e4;
-    if (e10 < best * 0.97) { kind = 10; best = e10; }
-    if (e6 < best * 0.97) { kind = 6; best = e6; }
-    if (e2 < best * 0.97) { kind = 2; best = e2; }
+    kind = price_large(M, N).kind;
   } else
     kind = 1;
   // deep K in whole 256-byte slices: half as many barriers for the same bytes
@@ -848,6 +885,18 @@ GemmPlan gemm_plan(int M, int N, int K, const void *ws, size_t ws_bytes, bool pa
 
 int launch_gemm_i8(const int8_t *A, int lda, const int8_t *Wt, int ldw, int M, int N, int K,
                    const GemmEpilogue &epi, void *ws, size_t ws_bytes, hipStream_t st, const GemmPlan *plan) {
+  const bool conv_in = epi.conv.state != nullptr;
+  if (!conv_in && !epi.defer_reduce && g_gemm_variant.load(std::memory_order_relaxed) < 0 && (K % 128) == 0 && N > 512) {
+    if (const int Mb = row_split(M, N, K)) {
+      GemmEpilogue rest = epi;
+      if (rest.out_i8) rest.out_i8 += (size_t)Mb * epi.ldo;
+      if (rest.out_f16) rest.out_f16 += (size_t)Mb * epi.ldo;
+      if (rest.acc) rest.acc += (size_t)Mb * N;
+      const int rc = launch_gemm_i8(A, lda, Wt, ldw, Mb, N, K, epi, ws, ws_bytes, st, nullptr);
+      if (rc != QUAMBA_OK) return rc;
+      return launch_gemm_i8(A + (size_t)Mb * lda, lda, Wt, ldw, M - Mb, N, K, rest, ws, ws_bytes, st, nullptr);
+    }
+  }
   const GemmChoice c = plan ? *plan : choose_gemm(M, N, K, ws, ws_bytes);
   if (c.splits > 1 && (!ws || (size_t)c.splits * M * N * sizeof(int32_t) > ws_bytes))
     return fail(QUAMBA_EWORKSPACE, "gemm: %d K ranges of a %d x %d output do not fit the workspace", c.splits, M, N);

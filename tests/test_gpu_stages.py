@@ -114,7 +114,10 @@ def test_gemm_acc_and_requant_bit_exact(M, N, K, pad):
 
 @pytest.mark.parametrize("M,N,K", [(16384, 10240, 2560), (16384, 2560, 5120),  # the 2.8B layer at 4 x 4096 tokens
                                    (16384, 16384, 4096), (16384, 4096, 8192),  # the Jamba-shaped layer at 16384 tokens
-                                   (16384, 320, 8192), (16384, 8192, 256)])    # its x_proj and dt_proj
+                                   (16384, 320, 8192), (16384, 8192, 256),     # its x_proj and dt_proj
+                                   # row counts that leave a nearly empty last round of tiles: the launcher runs the
+                                   # rows that fill whole rounds and the rest as two launches
+                                   (2304, 10240, 2560), (2049, 10240, 2560), (2600, 2560, 5120), (4500, 4096, 8192)])
 def test_gemm_large_shapes_sampled_rows(M, N, K):
     """The big projections at their full sizes: raw sums and both epilogues on sampled rows against the oracle
     (which computes those rows one by one), and the row-staged epilogue (no raw sums asked for) against the
@@ -124,7 +127,8 @@ def test_gemm_large_shapes_sampled_rows(M, N, K):
     Wt = rng.integers(-128, 128, (N, K), dtype=np.int8)
     A[0] = -128
     Wt[0] = -128
-    rows = np.unique(np.concatenate([[0, 1, 255, 256, M // 2, M - 257, M - 1], rng.integers(0, M, 57)]))
+    rows = np.unique(np.concatenate([[0, 1, 255, 256, M // 2, M - 257, M - 1], rng.integers(0, M, 57),
+                                     [r for r in (2047, 2048, 2049, 2303, 2559, 2560, 4095, 4096) if r < M]]))
     acc_ref = O.int_matmul(A[rows], Wt)
     e0, e1 = (N // 4) // 4 * 4, (N // 2) // 4 * 4
     mult = np.array([3.1e-5, 7.7e-5, 1.9e-4], dtype=np.float32) * np.float32(5120.0 / K)
