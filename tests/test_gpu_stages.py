@@ -112,7 +112,16 @@ def test_gemm_acc_and_requant_bit_exact(M, N, K, pad):
     assert not goth[:, N:].any()
 
 
-@pytest.mark.parametrize("M,N,K", [(16384, 10240, 2560), (16384, 2560, 5120),  # the 2.8B layer at 4 x 4096 tokens
+def _random_large_gemm_shapes(count, seed=77):
+    """Seeded row counts between the benchmark's sizes at the model widths: whatever tile form, row split and
+    K split the planner takes for them must give the oracle's numbers."""
+    rng = np.random.default_rng(seed)
+    widths = [(10240, 2560), (2560, 5120), (192, 5120), (16384, 4096), (4096, 8192), (3072, 768)]
+    return [(int(rng.integers(400, 7000)),) + widths[i % len(widths)] for i in range(count)]
+
+
+@pytest.mark.parametrize("M,N,K", _random_large_gemm_shapes(12) + [
+                                   (16384, 10240, 2560), (16384, 2560, 5120),  # the 2.8B layer at 4 x 4096 tokens
                                    (16384, 16384, 4096), (16384, 4096, 8192),  # the Jamba-shaped layer at 16384 tokens
                                    (16384, 320, 8192), (16384, 8192, 256),     # its x_proj and dt_proj
                                    # row counts that leave a nearly empty last round of tiles: the launcher runs the
@@ -128,7 +137,8 @@ def test_gemm_large_shapes_sampled_rows(M, N, K):
     A[0] = -128
     Wt[0] = -128
     rows = np.unique(np.concatenate([[0, 1, 255, 256, M // 2, M - 257, M - 1], rng.integers(0, M, 57),
-                                     [r for r in (2047, 2048, 2049, 2303, 2559, 2560, 4095, 4096) if r < M]]))
+                                     np.array([r for r in (2047, 2048, 2049, 2303, 2559, 2560, 4095, 4096) if r < M],
+                                              dtype=np.int64)]).astype(np.int64))
     acc_ref = O.int_matmul(A[rows], Wt)
     e0, e1 = (N // 4) // 4 * 4, (N // 2) // 4 * 4
     mult = np.array([3.1e-5, 7.7e-5, 1.9e-4], dtype=np.float32) * np.float32(5120.0 / K)
