@@ -594,8 +594,9 @@ int quamba_probe_rate(int probe, int waves_per_simd, int iters, double *instr_pe
  * hook changed while calls are in flight applies to whichever calls start after it.  Results
  * do not depend on them beyond what the tests of the alternative forms state (bit-identical,
  * except where a row's sum of squares is accumulated in another order).
- *   quamba_debug_set_gemm_variant(v)   v >= 0 forces GEMM kernel configuration v (0..11) where the
- *                                      shape allows it; -1 = chosen per shape (default)
+ *   quamba_debug_set_gemm_variant(v)   v >= 0 forces GEMM kernel configuration v (0..13) where the
+ *                                      shape allows it, and switches the launcher's row split off;
+ *                                      -1 = chosen per shape (default)
  *   quamba_debug_set_gemm_split(v)     v > 1 forces a K split into v ranges over the grid; 0 = default
  *   quamba_debug_set_gemv_max_rows(v)  generation takes the few-row streaming kernels up to v
  *                                      sequences (0..4); negative = default (2)
