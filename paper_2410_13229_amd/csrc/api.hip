@@ -140,7 +140,7 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
               __half *conv_state, const quamba_taps *taps, void *ws, size_t ws_bytes, hipStream_t st,
               const NormIn *norm = nullptr, const quamba_hadx *hx = nullptr, const quamba_hadx_taps *hx_taps = nullptr,
               const quamba_xasym *xa = nullptr, const quamba_xfmt *xf = nullptr, const DynX *dyn = nullptr,
-              OutPartial *defer_out = nullptr) {
+              OutPartial *defer_out = nullptr, const quamba_qweights *next_qw = nullptr) {
   if (defer_out) defer_out->splits = 1;
   const int g_fuse_dt = g_fuse_dt_hook.load(std::memory_order_relaxed);
   const int g_fuse_decode = g_fuse_decode_hook.load(std::memory_order_relaxed);
@@ -323,6 +323,11 @@ int run_mixer(const quamba_dims *d, const quamba_qweights *qw, const quamba_scal
     if (decode) {
       QUAMBA_TRY(launch_scan_step(a, st));
     } else {
+      if (next_qw) {  // a stack of blocks: warm the cache with the weights that come next
+        a.warm_ptr[0] = qw->W_outH; a.warm_bytes[0] = (size_t)Dm * Di;
+        a.warm_ptr[1] = next_qw->W_in; a.warm_bytes[1] = (size_t)2 * Di * Dm;
+        a.warm_ptr[2] = next_qw->W_x; a.warm_bytes[2] = (size_t)NX * Di;
+      }
       QUAMBA_TRY(launch_scan_prefill(a, base + p.scan, p.total - p.scan, st));
     }
     if (fuse_dt) QUAMBA_TRY(tap_copy(t.dt_q, dt_q, (size_t)M * Di, st));
@@ -378,9 +383,9 @@ size_t mixer_workspace_bytes(const quamba_dims *d, int Bt, int L) { return make_
 
 int mixer_run_q(const quamba_dims *d, const quamba_qweights *qw, const quamba_scales *sc, const int8_t *u_q, int Bt,
                 int L, bool decode, __half *out, float *ssm_state, __half *conv_state, void *ws, size_t ws_bytes,
-                hipStream_t st, OutPartial *defer_out) {
+                hipStream_t st, OutPartial *defer_out, const quamba_qweights *next_qw) {
   return run_mixer(d, qw, sc, nullptr, u_q, Bt, L, decode, out, ssm_state, conv_state, nullptr, ws, ws_bytes, st,
-                   nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, defer_out);
+                   nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, defer_out, next_qw);
 }
 
 int mixer_decode_norm(const quamba_dims *d, const quamba_qweights *qw, const quamba_scales *sc, const NormIn &norm,

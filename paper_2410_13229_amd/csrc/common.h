@@ -156,6 +156,11 @@ struct ScanArgs {
   const int32_t *dbc_part;
   int dbc_splits;
   float m_x_dt, m_x_B, m_x_C;
+  // prefill only, optional: memory the kernels after the scan will read (the weights of the next projections).
+  // The scan is bound by its arithmetic and leaves the memory idle, so a few extra workgroups of its launch read
+  // these ranges (16-byte aligned) and thereby bring them into the last-level cache; nothing is written
+  const void *warm_ptr[3];
+  size_t warm_bytes[3];
 };
 
 size_t scan_workspace_bytes(int Bt, int L, int Di);
@@ -207,7 +212,9 @@ struct OutPartial {
 };
 int mixer_run_q(const quamba_dims *d, const quamba_qweights *qw, const quamba_scales *sc, const int8_t *u_q, int Bt,
                 int L, bool decode, __half *out, float *ssm_state, __half *conv_state, void *ws, size_t ws_bytes,
-                hipStream_t st, OutPartial *defer_out = nullptr);
+                hipStream_t st, OutPartial *defer_out = nullptr, const quamba_qweights *next_qw = nullptr);
+// next_qw (prefill, optional): the weights of the block that runs after this one; its in_proj and x_proj weights
+// and this block's out_proj weights are read into the last-level cache under the scan (ScanArgs::warm_ptr)
 int check_model_dims(const quamba_dims *d);
 
 // generation with at most 4 sequences: the block's own residual add + RMSNorm + quantization runs

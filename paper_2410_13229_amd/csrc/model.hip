@@ -391,7 +391,7 @@ int run_model(const quamba_model *m, const int32_t *tokens, int Bt, int L, bool 
       if (rc != QUAMBA_OK) return rc;
       prev = OutPartial{decode && l + 1 < m->n_layers, 1, nullptr, 0.f};
       rc = mixer_run_q(&m->dims, &ly.q, &ly.s, u_q, Bt, L, decode, out, ssm, cs, base + c.mixer, c.mixer_bytes, st,
-                       &prev);
+                       &prev, (!decode && l + 1 < m->n_layers) ? &m->layers[l + 1].q : nullptr);
     }
     if (rc != QUAMBA_OK) return rc;
   }
