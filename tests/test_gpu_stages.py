@@ -277,7 +277,10 @@ def scan_variant(request):
                                               (3, 67, 192, True), (1, 1000, 256, True), (1, 256, 1536, False),
                                               (2, 131, 1100, True), (1, 2048, 5120, True), (2, 129, 64, True),
                                               (1, 128, 96, False), (2, 8, 32, True),
-                                              (9, 40, 1024, True)])  # more than one workgroup per CU in the sweep
+                                              (9, 40, 1024, True),  # more than one workgroup per CU in the sweep
+                                              # sequence ends on either side of the sweep's 64-token superblocks and 8-token groups
+                                              (5, 65, 64, True), (1, 63, 32, False), (3, 127, 96, True), (2, 64, 64, False),
+                                              (1, 71, 160, True)])
 def test_scan_prefill(Bt, L, Di, with_h0, scan_variant):
     rng = np.random.default_rng(L * 31 + Di)
     sc, x, dt, xz, dbc, A, D, bias = _scan_inputs(rng, Bt, L, Di)
