@@ -199,4 +199,35 @@ __device__ __forceinline__ void buffer_store_f16(__amdgpu_buffer_rsrc_t r, unsig
   __builtin_amdgcn_raw_buffer_store_b16(__half_as_ushort(__float2half_rn(v)), r, lane_off, wave_off, 0);
 }
 
+// ---- read-ahead: workgroups appended to a launch that is not bound by memory read ranges the following kernels
+// will need (the weights of the next projections), so that the lines wait in the last-level cache.  Plain loads,
+// 16 per thread in flight; nothing is written, the sum only keeps the loads alive.
+struct WarmRanges {
+  const uint4 *ptr[3];
+  unsigned n16[3];  // length in 16-byte words
+  int blocks;       // workgroups of the launch that do this (0: none)
+};
+__device__ __forceinline__ void warm_read(const WarmRanges &w, int part, int nparts) {
+  unsigned acc = 0;
+  const size_t step = (size_t)nparts * blockDim.x;
+#pragma unroll
+  for (int r = 0; r < 3; ++r) {
+    const uint4 *q = w.ptr[r];
+    const size_t n = w.n16[r];
+    size_t i = (size_t)part * blockDim.x + threadIdx.x;
+    for (; i + 15 * step < n; i += 16 * step) {
+      uint4 v[16];
+#pragma unroll
+      for (int j = 0; j < 16; ++j) v[j] = q[i + j * step];
+#pragma unroll
+      for (int j = 0; j < 16; ++j) acc ^= v[j].x ^ v[j].y ^ v[j].z ^ v[j].w;
+    }
+    for (; i < n; i += step) {
+      const uint4 v = q[i];
+      acc ^= v.x ^ v.y ^ v.z ^ v.w;
+    }
+  }
+  asm volatile("" ::"v"(acc));
+}
+
 }  // namespace quamba

@@ -80,9 +80,7 @@ struct Dev {
   const int32_t *dbc_part;   // generation: x_proj's sums as dbc_splits partial results [dbc_splits][Bt][R + 2 NS]
   int dbc_splits;
   float m_x_dt, m_x_B, m_x_C;
-  const uint4 *warm_ptr[3];  // ranges to read into the cache beside the scan (16-byte words), see warm_ranges
-  unsigned warm_n16[3];
-  int warm_blocks;           // extra workgroups along grid.x that do it (0: none)
+  WarmRanges warm;  // ranges that extra workgroups along grid.x read into the cache beside the scan
 };
 
 // How the scan reads x: int8 codes on a uniform grid (s_x x_q + x_off), half precision values (the
@@ -102,33 +100,6 @@ __device__ __forceinline__ float x_value(const Dev &p, int raw, float sx) {
   else if constexpr (XM == X_LOG2) return sx * decode_log2(static_cast<unsigned>(raw) & 0xffu);
   else if constexpr (XM == X_I8DYN) return sx * static_cast<float>(raw);
   else return __builtin_fmaf(sx, static_cast<float>(raw), p.x_off);
-}
-
-// Workgroups appended to a prefill launch read memory that the kernels after the scan will need (the weights of the
-// next projections): the scan keeps the vector units busy and leaves the memory system idle, so the reads are free
-// and the lines wait in the last-level cache.  part / nparts: this workgroup's share; 16 loads of 16 bytes in
-// flight per thread.  Nothing is written; the sum only keeps the loads alive.
-__device__ __forceinline__ void warm_ranges(const Dev &p, int part, int nparts) {
-  unsigned acc = 0;
-#pragma unroll
-  for (int r = 0; r < 3; ++r) {
-    const uint4 *q = p.warm_ptr[r];
-    const size_t n = p.warm_n16[r];
-    const size_t step = (size_t)nparts * 256;
-    size_t i = (size_t)part * 256 + threadIdx.x;
-    for (; i + 15 * step < n; i += 16 * step) {
-      uint4 v[16];
-#pragma unroll
-      for (int j = 0; j < 16; ++j) v[j] = q[i + j * step];
-#pragma unroll
-      for (int j = 0; j < 16; ++j) acc ^= v[j].x ^ v[j].y ^ v[j].z ^ v[j].w;
-    }
-    for (; i < n; i += step) {
-      const uint4 v = q[i];
-      acc ^= v.x ^ v.y ^ v.z ^ v.w;
-    }
-  }
-  asm volatile("" ::"v"(acc));
 }
 
 // Dequantize B (and C) of tokens [row0, row0+cnt) into LDS as fp32 [TB][16].
@@ -158,11 +129,11 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_chunk_kernel(Dev p) {
   __shared__ __attribute__((aligned(16))) float sB[TB][NS];
   __shared__ __attribute__((aligned(16))) float sC[OUTPUT ? TB : 1][NS];
   __shared__ __attribute__((aligned(16))) int8_t sDT[FUSE_DT ? SCAN_THREADS / 64 : 1][FUSE_DT ? TB : 1][DT_LD];
-  if constexpr (OUTPUT) {  // the last warm_blocks workgroups along x only read ahead (whole workgroups: no barrier is skipped)
-    const int real = gridDim.x - p.warm_blocks;
+  if constexpr (OUTPUT) {  // the last workgroups along x only read ahead (whole workgroups: no barrier is skipped)
+    const int real = gridDim.x - p.warm.blocks;
     if ((int)blockIdx.x >= real) {
       const int per = gridDim.y * gridDim.z;
-      warm_ranges(p, (blockIdx.x - real) * per + blockIdx.z * gridDim.y + blockIdx.y, p.warm_blocks * per);
+      warm_read(p.warm, (blockIdx.x - real) * per + blockIdx.z * gridDim.y + blockIdx.y, p.warm.blocks * per);
       return;
     }
   }
@@ -422,7 +393,7 @@ __global__ __launch_bounds__(SW_THREADS, LAT ? 1 : 3) void scan_sweep_kernel(Dev
   const int nblk = p.Di / SW_CH;
   const int bx = blockIdx.x;
   if (bx >= nblk) {  // appended workgroups only read ahead
-    warm_ranges(p, (bx - nblk) * gridDim.y + blockIdx.y, p.warm_blocks * gridDim.y);
+    warm_read(p.warm, (bx - nblk) * gridDim.y + blockIdx.y, p.warm.blocks * gridDim.y);
     return;
   }
   const int cb = (nblk % 8 == 0) ? (bx & 7) * (nblk >> 3) + (bx >> 3) : bx;
@@ -890,10 +861,10 @@ Dev make_dev(const ScanArgs &a) {
   p.x_off = -a.s_x * static_cast<float>(a.x_zero_point);  // -0.f for the symmetric grid: adds nothing
   for (int r = 0; r < 3; ++r) {
     const bool on = a.warm_ptr[r] && aligned(a.warm_ptr[r], 16);
-    p.warm_ptr[r] = on ? static_cast<const uint4 *>(a.warm_ptr[r]) : nullptr;
-    p.warm_n16[r] = on ? static_cast<unsigned>(std::min<size_t>(a.warm_bytes[r] / 16, 0xffffffffu)) : 0u;
+    p.warm.ptr[r] = on ? static_cast<const uint4 *>(a.warm_ptr[r]) : nullptr;
+    p.warm.n16[r] = on ? static_cast<unsigned>(std::min<size_t>(a.warm_bytes[r] / 16, 0xffffffffu)) : 0u;
   }
-  p.warm_blocks = 0;
+  p.warm.blocks = 0;
   return p;
 }
 
@@ -984,8 +955,8 @@ bool sweep_is_cheaper(const ScanArgs &a) {
 template <int NK, int XM, bool LAT>
 int run_sweep(const Dev &p, const ScanArgs &a, hipStream_t st) {
   Dev q = p;
-  if (q.warm_n16[0] || q.warm_n16[1] || q.warm_n16[2]) q.warm_blocks = std::max(1, 96 / a.Bt);  // about 96 workgroups in all
-  hipLaunchKernelGGL((scan_sweep_kernel<NK, XM, LAT>), dim3(a.Di / SW_CH + q.warm_blocks, a.Bt), dim3(SW_THREADS), 0, st, q,
+  if (q.warm.n16[0] || q.warm.n16[1] || q.warm.n16[2]) q.warm.blocks = std::max(1, 96 / a.Bt);  // about 96 workgroups in all
+  hipLaunchKernelGGL((scan_sweep_kernel<NK, XM, LAT>), dim3(a.Di / SW_CH + q.warm.blocks, a.Bt), dim3(SW_THREADS), 0, st, q,
                      a.ssm_state);
   QUAMBA_LAUNCH_CHECK();
   return QUAMBA_OK;
@@ -1058,9 +1029,9 @@ int launch_scan_prefill(const ScanArgs &a, void *ws, size_t ws_bytes, hipStream_
                      a.Bt);
   QUAMBA_LAUNCH_CHECK();
   dim3 grid3 = grid;
-  if (p.warm_n16[0] || p.warm_n16[1] || p.warm_n16[2]) {  // about 128 workgroups that read ahead
-    p.warm_blocks = std::max(1, (int)(128 / ((long)p.nchunks * a.Bt)));
-    grid3.x += p.warm_blocks;
+  if (p.warm.n16[0] || p.warm.n16[1] || p.warm.n16[2]) {  // about 128 workgroups that read ahead
+    p.warm.blocks = std::max(1, (int)(128 / ((long)p.nchunks * a.Bt)));
+    grid3.x += p.warm.blocks;
   }
 #define QUAMBA_PASS3(XMV) hipLaunchKernelGGL((scan_chunk_kernel<true, false, XMV>), grid3, dim3(SCAN_THREADS), 0, st, p)
   QUAMBA_XM_SWITCH(QUAMBA_PASS3)
