@@ -17,11 +17,6 @@ __device__ __forceinline__ int q8(float v) {
   return static_cast<int>(v);
 }
 
-__device__ __forceinline__ float silu_f(float v) {
-  // v / (1 + exp(-v)) with the hardware exp2
-  return v / (1.f + __builtin_amdgcn_exp2f(-v * 1.44269504088896340736f));
-}
-
 // ------------------------------------------------------------------ quantize fp16 -> int8
 __global__ __launch_bounds__(256) void quantize_f16_kernel(const __half *__restrict__ x,
                                                            int8_t *__restrict__ q, size_t n,

@@ -745,9 +745,9 @@ int row_split(int M, int N, int K) {
 }
 
 GemmChoice choose_gemm(int M, int N, int K, const void *ws, size_t ws_bytes, bool partials_wanted = false) {
-  const int g_gemm_variant = quamba::g_gemm_variant.load(std::memory_order_relaxed);
-  const int g_gemm_split = quamba::g_gemm_split.load(std::memory_order_relaxed);
-  const int g_gemv_max_rows = quamba::g_gemv_max_rows.load(std::memory_order_relaxed);
+  const int forced_kind = quamba::g_gemm_variant.load(std::memory_order_relaxed);
+  const int forced_split = quamba::g_gemm_split.load(std::memory_order_relaxed);
+  const int max_gemv_rows = quamba::g_gemv_max_rows.load(std::memory_order_relaxed);
   const bool k64 = (K % 64) == 0, k128 = (K % 128) == 0;
   // which kernel:
   //   0 = reg 64x64            1 = reg 128x128
@@ -777,10 +777,9 @@ GemmChoice choose_gemm(int M, int N, int K, const void *ws, size_t ws_bytes, boo
   //       7.5 against 8.0 us, 64 x 16384 x 4096: 13.6 against 14.6 us)
   // the streaming kernel keeps its rows in LDS: rows x K bytes next to a static array of rows x 64 bytes
   const size_t gemv_rows = M <= 1 ? 1 : (M <= 2 ? 2 : 4);
-  if (M <= g_gemv_max_rows && g_gemm_variant < 0 && gemv_rows * K + gemv_rows * 64 <= 64 * 1024)
+  if (M <= max_gemv_rows && forced_kind < 0 && gemv_rows * K + gemv_rows * 64 <= 64 * 1024)
     return GemmChoice{true, 0, 1, 0};
   int kind;
-  const long tiles_256 = (long)((M + 255) / 256) * ((N + 319) / 320);
   const long tiles_128 = (long)((M + 127) / 128) * ((N + 159) / 160);
   if (M <= 64)
     kind = k128 ? ((N + 31) / 32 >= 256 ? ((K % 256) == 0 ? (M <= 32 && (N + 31) / 32 <= 512 && K <= 6144 ? 13 : 11) : 7) : 5)
@@ -846,11 +845,11 @@ GemmChoice choose_gemm(int M, int N, int K, const void *ws, size_t ws_bytes, boo
   if (M > 64 && (K % 256) == 0 && K <= 8192 && (kind == 5 || kind == 9 || kind == 12) && tiles64 > 128 && tiles64 <= 256 &&
       (long)((M + 31) / 32) * ((N + 31) / 32) > (N <= 512 ? 400 : 520))
     kind = 11;
-  if ((g_gemm_variant == 12 || g_gemm_variant == 13) && (K % 256) == 0) kind = g_gemm_variant;
-  if (g_gemm_variant >= 0 && g_gemm_variant <= 11 &&
-      (g_gemm_variant < 2 || (g_gemm_variant == 3 && k64) || (g_gemm_variant != 3 && k128)) &&
-      (g_gemm_variant != 11 || (K % 256) == 0))
-    kind = g_gemm_variant;
+  if ((forced_kind == 12 || forced_kind == 13) && (K % 256) == 0) kind = forced_kind;
+  if (forced_kind >= 0 && forced_kind <= 11 &&
+      (forced_kind < 2 || (forced_kind == 3 && k64) || (forced_kind != 3 && k128)) &&
+      (forced_kind != 11 || (K % 256) == 0))
+    kind = forced_kind;
 
   // split K when the output has too few tiles to fill 256 CUs and K is deep
   int splits = 1;
@@ -865,7 +864,7 @@ GemmChoice choose_gemm(int M, int N, int K, const void *ws, size_t ws_bytes, boo
     while (want > 1 && (nslices / want < 4 || (size_t)want * M * N * sizeof(int32_t) > ws_bytes)) --want;
     if (want > 1) splits = want;
   }
-  if (g_gemm_split > 1 && ws != nullptr && (size_t)g_gemm_split * M * N * sizeof(int32_t) <= ws_bytes) splits = g_gemm_split;
+  if (forced_split > 1 && ws != nullptr && (size_t)forced_split * M * N * sizeof(int32_t) <= ws_bytes) splits = forced_split;
   const int per = (nslices + splits - 1) / splits;
   return GemmChoice{false, kind, (nslices + per - 1) / per, per};
 }

@@ -233,7 +233,7 @@ __global__ __launch_bounds__(256) void argmax_partials_kernel(const float *__res
   si[threadIdx.x] = bi;
   __syncthreads();
   for (int off = 128; off > 0; off >>= 1) {
-    if (threadIdx.x < off) {
+    if ((int)threadIdx.x < off) {
       const float ob = sb[threadIdx.x + off];
       const int oi = si[threadIdx.x + off];
       if (ob > sb[threadIdx.x] || (ob == sb[threadIdx.x] && oi < si[threadIdx.x])) {
@@ -273,7 +273,7 @@ __global__ __launch_bounds__(256) void argmax_kernel(const float *__restrict__ l
   si[threadIdx.x] = bi;
   __syncthreads();
   for (int off = 128; off > 0; off >>= 1) {
-    if (threadIdx.x < off) {
+    if ((int)threadIdx.x < off) {
       const float ob = sb[threadIdx.x + off];
       const int oi = si[threadIdx.x + off];
       if (ob > sb[threadIdx.x] || (ob == sb[threadIdx.x] && oi < si[threadIdx.x])) {
