@@ -119,10 +119,13 @@ __device__ __forceinline__ void store_tiles_rows(const v16i (&acc)[TN][TM], int 
   const int esz = f16 ? 2 : 1;
   const int rowb = TN * 32 * esz;  // bytes per block row
   const int pitch = rowb + 16;     // staged rows sit 16 bytes further apart: fewer lanes per LDS bank
+  const int cpr = rowb / 16;  // 16-byte chunks per block row
+  int8_t *out = f16 ? reinterpret_cast<int8_t *>(epi.out_f16) : epi.out_i8;
+  // one band of 32 rows at a time: its global stores are under way while the next band is requantized
 #pragma unroll
-  for (int i = 0; i < TN; ++i) {
+  for (int j = 0; j < TM; ++j) {
 #pragma unroll
-    for (int j = 0; j < TM; ++j) {
+    for (int i = 0; i < TN; ++i) {
       const int row = j * 32 + (lane & 31);
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
@@ -148,18 +151,15 @@ __device__ __forceinline__ void store_tiles_rows(const v16i (&acc)[TN][TM], int 
         }
       }
     }
-  }
-  // the region is private to this wave: its own LDS writes are ordered before its reads
-  const int cpr = rowb / 16;  // 16-byte chunks per block row
-  const int total = TM * 32 * cpr;
-  int8_t *out = f16 ? reinterpret_cast<int8_t *>(epi.out_f16) : epi.out_i8;
-  for (int q = lane; q < total; q += 64) {
-    const int row = q / cpr, cc = q % cpr;
-    const int gm = m_base + row;
-    const int gcol = n_base + cc * (16 / esz);
-    if (gm < M && gcol < N) {
-      const v4i v = *reinterpret_cast<const v4i *>(scratch + row * pitch + cc * 16);
-      *reinterpret_cast<v4i *>(out + ((size_t)gm * epi.ldo + gcol) * esz) = v;
+    // the region is private to this wave: its own LDS writes are ordered before its reads
+    for (int q = lane; q < 32 * cpr; q += 64) {
+      const int row = j * 32 + q / cpr, cc = q % cpr;
+      const int gm = m_base + row;
+      const int gcol = n_base + cc * (16 / esz);
+      if (gm < M && gcol < N) {
+        const v4i v = *reinterpret_cast<const v4i *>(scratch + row * pitch + cc * 16);
+        *reinterpret_cast<v4i *>(out + ((size_t)gm * epi.ldo + gcol) * esz) = v;
+      }
     }
   }
   if constexpr (CONV) {
