@@ -492,21 +492,88 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG, OCC) void gemm_i8_dma_kernel(c
   // s_waitcnt immediate for "vmcnt <= n, nothing else waited for" (gfx9 encoding: vmcnt in
   // bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8)
 #define QUAMBA_VMCNT(n) (((n) & 0xF) | ((((n) >> 4) & 0x3) << 14) | (0x7 << 4) | (0xF << 8))
+  // the same with lgkmcnt = 0 as well (LDS reads of this wave finished)
+#define QUAMBA_VMCNT_LGKM0(n) (((n) & 0xF) | ((((n) >> 4) & 0x3) << 14) | (0x7 << 4))
+  if constexpr (S == 2 && !PIPE) {
+    // Ring of two: the barrier of a slice sits in front of its last sub-slice instead of in front of its first.
+    // By then a wave holds the last fragments of the slice in registers, so behind the barrier it has products to
+    // issue at once, and the first fragments of the next slice (certified by the same barrier) and the loads of
+    // the slice after that travel under them.  With the barrier in front of a slice every wave starts the slice
+    // by asking for fragments, and the matrix pipes idle until they arrive.
+    constexpr int NSUB = BKB / 32 / KG;
+    static_assert(NSUB >= 2, "a slice has a last sub-slice of its own");
+    auto frags = [&](int stage, int sub, v4i (&fa)[TM], v4i (&fw)[TN]) {
+      const int8_t *la = ring + stage * STAGE;
+      const int8_t *lw = la + BM * BKB;
+      const int chunk = (sub * KG + kg) * 2 + (lane >> 5);
 #pragma unroll
-  for (int s = 0; s < S - 1; ++s)
-    if (s < nk) issue(s, s);
-  int stage = 0;
-  for (int kt = 0; kt < nk; ++kt) {
-    if (kt + S - 2 < nk)
-      __builtin_amdgcn_s_waitcnt(QUAMBA_VMCNT((S - 2) * NI));  // slices kt+1 .. kt+S-2 may be in flight
-    else
-      __builtin_amdgcn_s_waitcnt(QUAMBA_VMCNT(0));             // tail: fewer slices were issued
-    __builtin_amdgcn_s_barrier();
-    if (kt + S - 1 < nk) issue(stage == 0 ? S - 1 : stage - 1, kt + S - 1);
-    compute(stage);
-    stage = (stage + 1 == S) ? 0 : stage + 1;
+      for (int j = 0; j < TM; ++j)
+        fa[j] = *reinterpret_cast<const v4i *>(la + swzk<BKB>(wm * WM + j * 32 + (lane & 31), chunk));
+#pragma unroll
+      for (int i = 0; i < TN; ++i)
+        fw[i] = *reinterpret_cast<const v4i *>(lw + swzk<BKB>(wn * WN + i * 32 + (lane & 31), chunk));
+    };
+    auto mma = [&](const v4i (&fa)[TM], const v4i (&fw)[TN]) {
+#pragma unroll
+      for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[i], fa[j], acc[i][j], 0, 0, 0);
+    };
+    v4i pa[TM], pw[TN];  // first fragments of the slice about to start
+    if (nk > 0) {
+      issue(0, 0);
+      __builtin_amdgcn_s_waitcnt(QUAMBA_VMCNT(0));
+      __builtin_amdgcn_s_barrier();
+      if (nk > 1) issue(1, 1);
+      frags(0, 0, pa, pw);
+    }
+    for (int kt = 0; kt + 1 < nk; ++kt) {
+      const int cur = kt & 1;
+      v4i fa[TM], fw[TN];
+      mma(pa, pw);
+#pragma unroll
+      for (int sub = 1; sub + 1 < NSUB; ++sub) {
+        frags(cur, sub, fa, fw);
+        mma(fa, fw);
+      }
+      frags(cur, NSUB - 1, fa, fw);
+      // this wave's loads of slice kt + 1 have landed and its reads of this slice are done: behind the barrier
+      // that holds for every wave
+      __builtin_amdgcn_s_waitcnt(QUAMBA_VMCNT_LGKM0(0));
+      __builtin_amdgcn_s_barrier();
+      if (kt + 2 < nk) issue(cur, kt + 2);
+      frags(cur ^ 1, 0, pa, pw);
+      mma(fa, fw);
+    }
+    if (nk > 0) {  // the last slice (its own code: a join with the loop body would make the products above wait for pa, pw)
+      const int cur = (nk - 1) & 1;
+      v4i fa[TM], fw[TN];
+      mma(pa, pw);
+#pragma unroll
+      for (int sub = 1; sub < NSUB; ++sub) {
+        frags(cur, sub, fa, fw);
+        mma(fa, fw);
+      }
+    }
+  } else {
+#pragma unroll
+    for (int s = 0; s < S - 1; ++s)
+      if (s < nk) issue(s, s);
+    int stage = 0;
+    for (int kt = 0; kt < nk; ++kt) {
+      if (kt + S - 2 < nk)
+        __builtin_amdgcn_s_waitcnt(QUAMBA_VMCNT((S - 2) * NI));  // slices kt+1 .. kt+S-2 may be in flight
+      else
+        __builtin_amdgcn_s_waitcnt(QUAMBA_VMCNT(0));             // tail: fewer slices were issued
+      __builtin_amdgcn_s_barrier();
+      if (kt + S - 1 < nk) issue(stage == 0 ? S - 1 : stage - 1, kt + S - 1);
+      compute(stage);
+      stage = (stage + 1 == S) ? 0 : stage + 1;
+    }
   }
 #undef QUAMBA_VMCNT
+#undef QUAMBA_VMCNT_LGKM0
 
   if constexpr (KG > 1) {
     // groups 1 .. KG-1 park their sums lane-major (16 bytes per lane and register quad:
