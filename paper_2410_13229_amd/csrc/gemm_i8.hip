@@ -542,8 +542,9 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG, OCC) void gemm_i8_dma_kernel(c
       // that holds for every wave
       __builtin_amdgcn_s_waitcnt(QUAMBA_VMCNT_LGKM0(0));
       __builtin_amdgcn_s_barrier();
-      if (kt + 2 < nk) issue(cur, kt + 2);
       frags(cur ^ 1, 0, pa, pw);
+      __builtin_amdgcn_sched_barrier(0);  // the requests first: the products below are what covers their latency
+      if (kt + 2 < nk) issue(cur, kt + 2);
       mma(fa, fw);
     }
     if (nk > 0) {  // the last slice (its own code: a join with the loop body would make the products above wait for pa, pw)
