@@ -916,7 +916,7 @@ GemmChoice choose_gemm(int M, int N, int K, const void *ws, size_t ws_bytes, boo
   if ((forced_kind == 12 || forced_kind == 13) && (K % 256) == 0) kind = forced_kind;
   if (forced_kind >= 0 && forced_kind <= 11 &&
       (forced_kind < 2 || (forced_kind == 3 && k64) || (forced_kind != 3 && k128)) &&
-      (forced_kind != 11 || (K % 256) == 0))
+      ((forced_kind != 8 && forced_kind != 9 && forced_kind != 11) || (K % 256) == 0))  // their slices are 256 bytes
     kind = forced_kind;
 
   // split K when the output has too few tiles to fill 256 CUs and K is deep

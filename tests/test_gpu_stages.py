@@ -197,6 +197,42 @@ def test_gemm_generation_step_kinds_forced(kind, M, N, K):
     assert np.array_equal(host(outh).view(np.uint16), want_h.view(np.uint16))
 
 
+@pytest.mark.parametrize("kind", [2, 4, 8, 9, 10])
+@pytest.mark.parametrize("M,N,K", [(300, 700, 256), (130, 164, 512), (257, 332, 768), (40, 64, 1280)])
+def test_gemm_ring_of_two_kinds_forced(kind, M, N, K):
+    """The tile forms with a ring of two stages (256 x 320, 256 x 256, 128 x 160 with and without K groups, 64 x 64
+    with 256-byte slices) keep their per-slice barrier in front of the last sub-slice and run the last slice in a
+    copy of the loop body; forced onto ragged shapes whose K is one, two, three, five or ten slices: raw sums, codes
+    and the half-precision epilogue against the oracle."""
+    rng = np.random.default_rng(kind * 977 + M + N + K)
+    A = rng.integers(-128, 128, (M, K), dtype=np.int8)
+    Wt = rng.integers(-128, 128, (N, K), dtype=np.int8)
+    A[-1] = -128
+    Wt[-1] = -128
+    acc_ref = O.int_matmul(A, Wt)
+    mult = np.array([3.1e-5, 7.7e-5, 1.9e-4], dtype=np.float32) * np.float32(5120.0 / K)
+    e0, e1 = (N // 4) // 4 * 4, (N // 2) // 4 * 4
+    want = np.concatenate([O.requant_acc(acc_ref[:, :e0], mult[0]), O.requant_acc(acc_ref[:, e0:e1], mult[1]),
+                           O.requant_acc(acc_ref[:, e1:], mult[2])], axis=1)
+    dA, dW = dev(A), dev(Wt)
+    Q.quamba_debug_set_gemm_variant(kind)
+    try:
+        acc = empty((M, N), torch.int32)
+        out = torch.zeros((M, N), dtype=torch.int8, device="cuda:0")
+        Q.quamba_gemm_i8(dA, K, dW, K, M, N, K, e0, e1, mult, out, None, N, acc)
+        out2 = torch.zeros((M, N), dtype=torch.int8, device="cuda:0")
+        Q.quamba_gemm_i8(dA, K, dW, K, M, N, K, e0, e1, mult, out2, None, N, None)  # row-staged epilogue
+        outh = torch.zeros((M, N), dtype=torch.float16, device="cuda:0")
+        Q.quamba_gemm_i8(dA, K, dW, K, M, N, K, N, N, mult, None, outh, N, None)
+    finally:
+        Q.quamba_debug_set_gemm_variant(-1)
+    assert np.array_equal(host(acc), acc_ref)
+    assert np.array_equal(host(out), want)
+    assert torch.equal(out, out2)
+    want_h = (acc_ref.astype(np.float32) * mult[0]).astype(np.float16)
+    assert np.array_equal(host(outh).view(np.uint16), want_h.view(np.uint16))
+
+
 def test_gemm_rejects_bad_arguments():
     a = torch.zeros((16, 32), dtype=torch.int8, device="cuda:0")
     o = torch.zeros((16, 16), dtype=torch.int8, device="cuda:0")
