@@ -39,6 +39,7 @@ constexpr int NS = 16;       // d_state
 constexpr int TB = 64;       // tokens of B/C staged in LDS at a time
 constexpr int SCAN_THREADS = 256;
 constexpr int DT_LD = 68;    // row pitch (bytes) of the LDS tile of dt codes: 17 words, odd
+constexpr int W_PITCH_MAX = 176;  // the fused dt_proj stages its operand rows in LDS when dt_rank + 16 fits this pitch
 
 __device__ __forceinline__ float exp2_fast(float v) { return __builtin_amdgcn_exp2f(v); }
 
@@ -102,19 +103,31 @@ __device__ __forceinline__ float x_value(const Dev &p, int raw, float sx) {
   else return __builtin_fmaf(sx, static_cast<float>(raw), p.x_off);
 }
 
-// Dequantize B (and C) of tokens [row0, row0+cnt) into LDS as fp32 [TB][16].
+// B (and C) codes of tokens [row0, row0+cnt) -> fp32 [TB][16] in LDS, in two steps so that the loads can be
+// requested ahead of other work: bc_load asks for this thread's TB * 16 / 256 codes, bc_park dequantizes and stores.
+constexpr int BC_PER = TB * NS / SCAN_THREADS;
+struct BCRegs {
+  int b[BC_PER], c[BC_PER];
+};
 template <bool WITH_C>
-__device__ __forceinline__ void stage_bc(const Dev &p, size_t row0, int cnt, float (*sB)[NS],
-                                         float (*sC)[NS]) {
-  for (int i = threadIdx.x; i < TB * NS; i += SCAN_THREADS) {
+__device__ __forceinline__ void bc_load(const Dev &p, size_t row0, int cnt, BCRegs &r) {
+#pragma unroll
+  for (int k = 0; k < BC_PER; ++k) {
+    const int i = threadIdx.x + k * SCAN_THREADS;
+    const int tt = min(i >> 4, cnt - 1), n = i & 15;  // past the block: loaded again, parked as zero
+    r.b[k] = p.B_q[(row0 + tt) * p.ldbc + n];
+    r.c[k] = WITH_C ? p.C_q[(row0 + tt) * p.ldbc + n] : 0;
+  }
+}
+template <bool WITH_C>
+__device__ __forceinline__ void bc_park(const Dev &p, int cnt, const BCRegs &r, float (*sB)[NS], float (*sC)[NS]) {
+#pragma unroll
+  for (int k = 0; k < BC_PER; ++k) {
+    const int i = threadIdx.x + k * SCAN_THREADS;
     const int tt = i >> 4, n = i & 15;
-    float b = 0.f, c = 0.f;
-    if (tt < cnt) {
-      b = p.s_B * static_cast<float>(p.B_q[(row0 + tt) * p.ldbc + n]);
-      if (WITH_C) c = p.s_C * static_cast<float>(p.C_q[(row0 + tt) * p.ldbc + n]);
-    }
-    sB[tt][n] = b;
-    if (WITH_C) sC[tt][n] = c;
+    const bool on = tt < cnt;
+    sB[tt][n] = on ? p.s_B * static_cast<float>(r.b[k]) : 0.f;
+    if (WITH_C) sC[tt][n] = on ? p.s_C * static_cast<float>(r.c[k]) : 0.f;
   }
 }
 
@@ -129,6 +142,8 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_chunk_kernel(Dev p) {
   __shared__ __attribute__((aligned(16))) float sB[TB][NS];
   __shared__ __attribute__((aligned(16))) float sC[OUTPUT ? TB : 1][NS];
   __shared__ __attribute__((aligned(16))) int8_t sDT[FUSE_DT ? SCAN_THREADS / 64 : 1][FUSE_DT ? TB : 1][DT_LD];
+  __shared__ __attribute__((aligned(16))) int8_t sW[FUSE_DT ? SCAN_THREADS / 64 : 1][FUSE_DT ? 32 * W_PITCH_MAX : 16];
+  __shared__ __attribute__((aligned(16))) int8_t sA[FUSE_DT ? 32 * W_PITCH_MAX : 16];
   if constexpr (OUTPUT) {  // the last workgroups along x only read ahead (whole workgroups: no barrier is skipped)
     const int real = gridDim.x - p.warm.blocks;
     if ((int)blockIdx.x >= real) {
@@ -188,42 +203,116 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_chunk_kernel(Dev p) {
   // its LDS tile.  MFMA operands come straight from global memory (every fragment is used once):
   // lane l supplies 16 bytes of k at offset 32 s + 16 (l / 32) of weight row / token row l % 32;
   // register r of tile i then holds channel 32 i + 8 (r / 4) + 4 (l / 32) + r % 4 of token l % 32.
+  // Operand rows: a lane of the MFMA layout wants 16 bytes of one row, so a wave-level load straight from global memory
+  // touches 32 rows = 32 cache lines for 1 KB (measured at 2.8B width: 2.7 us of the pass).  Where the rows fit
+  // (R + 16 <= W_PITCH_MAX, whole workgroups of channels) they are read as whole rows instead - the 32 weight rows of a
+  // tile are 32 R contiguous bytes, 64 / (R / 16) rows per wave-level load, parked in the wave's own LDS region; the
+  // 32 token rows once per workgroup, shared by its four waves - and read back from LDS as fragments.
+  const int cpr = p.R >> 4;  // 16-byte pieces per row
+  const bool w_staged = FUSE_DT && p.R + 16 <= W_PITCH_MAX && (p.Di % SCAN_THREADS) == 0;
+  const int w_r0 = w_staged ? lane / cpr : 0, w_col = lane - w_r0 * cpr, w_rows = w_staged ? 64 / cpr : 1;
+  constexpr int W_LOADS = 6;  // 32 rows at 6 or more rows per load (R <= 160: 64 lanes hold 6 rows of 10 pieces)
+  constexpr int A_LOADS = 2;  // 32 rows of at most 10 pieces over 256 threads
   auto dt_tile = [&](int tok0, int row0) {
     const int dw0 = blockIdx.x * SCAN_THREADS + wave * 64;
-    const int8_t *arow = p.dtlow_q + (seq0 + min(tok0 + (lane & 31), t1 - 1)) * p.lddl;
-    const int8_t *w0 = p.W_dt + (size_t)min(dw0 + (lane & 31), p.Di - 1) * p.R;
-    const int8_t *w1 = p.W_dt + (size_t)min(dw0 + 32 + (lane & 31), p.Di - 1) * p.R;
     const int koff = 16 * (lane >> 5);
-    v16i acc[2];
-#pragma unroll
-    for (int r = 0; r < 16; ++r) acc[0][r] = acc[1][r] = 0;
-    constexpr int PH = 3;  // k steps whose operands are in flight together
-    for (int s0 = 0; s0 * 32 < p.R; s0 += PH) {
-      v4i fa[PH], fw0[PH], fw1[PH];
-#pragma unroll
-      for (int j = 0; j < PH; ++j) {
-        const int kc = 32 * (s0 + j) + koff;
-        fa[j] = fw0[j] = fw1[j] = v4i{0, 0, 0, 0};
-        if (kc < p.R) {  // R is a multiple of 16: a 16-byte piece is all in or all out
-          fa[j] = *reinterpret_cast<const v4i *>(arow + kc);
-          fw0[j] = *reinterpret_cast<const v4i *>(w0 + kc);
-          fw1[j] = *reinterpret_cast<const v4i *>(w1 + kc);
-        }
-      }
-#pragma unroll
-      for (int j = 0; j < PH; ++j) {
-        acc[0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw0[j], fa[j], acc[0], 0, 0, 0);
-        acc[1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw1[j], fa[j], acc[1], 0, 0, 0);
-      }
-    }
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
+    // codes of tile i: register r of lane l is channel 32 i + 8 (r / 4) + 4 (l / 32) + r % 4 of token l % 32
+    auto emit = [&](const v16i &acc, int i) {
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        const int a[4] = {acc[i][4 * g], acc[i][4 * g + 1], acc[i][4 * g + 2], acc[i][4 * g + 3]};
+        const int a[4] = {acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]};
         *reinterpret_cast<unsigned *>(&sDT[wave][row0 + (lane & 31)][32 * i + 8 * g + 4 * (lane >> 5)]) =
             requant_pack4(a, p.m_dt);
       }
+    };
+    if (w_staged) {
+      const int pitch = p.R + 16;
+      int8_t *lw = sW[wave];
+      v4i wv[W_LOADS], av[A_LOADS];
+      int a_at[A_LOADS];  // LDS offset of this thread's piece of the token rows, -1: none
+      auto w_load = [&](int i) {
+#pragma unroll
+        for (int g = 0; g < W_LOADS; ++g) {
+          const int row = g * w_rows + w_r0;
+          wv[g] = v4i{0, 0, 0, 0};
+          if (w_r0 < w_rows && row < 32)
+            wv[g] = *reinterpret_cast<const v4i *>(p.W_dt + (size_t)(dw0 + 32 * i + row) * p.R + 16 * w_col);
+        }
+      };
+      auto w_park = [&]() {
+#pragma unroll
+        for (int g = 0; g < W_LOADS; ++g) {
+          const int row = g * w_rows + w_r0;
+          if (w_r0 < w_rows && row < 32) *reinterpret_cast<v4i *>(lw + row * pitch + 16 * w_col) = wv[g];
+        }
+      };
+#pragma unroll
+      for (int k = 0; k < A_LOADS; ++k) {
+        const int c = static_cast<int>(threadIdx.x) + SCAN_THREADS * k;
+        const int row = c / cpr, col = c - row * cpr;
+        a_at[k] = -1;
+        av[k] = v4i{0, 0, 0, 0};
+        if (row < 32) {
+          a_at[k] = row * pitch + 16 * col;
+          av[k] = *reinterpret_cast<const v4i *>(p.dtlow_q + (seq0 + min(tok0 + row, t1 - 1)) * p.lddl + 16 * col);
+        }
+      }
+      w_load(0);
+      __syncthreads();  // the token rows of the previous tile have been read by every wave
+#pragma unroll
+      for (int k = 0; k < A_LOADS; ++k)
+        if (a_at[k] >= 0) *reinterpret_cast<v4i *>(sA + a_at[k]) = av[k];
+      w_park();
+      __builtin_amdgcn_sched_barrier(0);  // keeps the loads below from being hoisted over the stores: one set of registers
+      w_load(1);  // the second tile's rows travel under the first tile's products
+      __builtin_amdgcn_sched_barrier(0);
+      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        if (i == 1) w_park();  // the wave's own region, its LDS accesses execute in order: no barrier
+        v16i acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0;
+        for (int k0 = 0; k0 < p.R; k0 += 32) {
+          // a lane whose half lies past R (R an odd multiple of 16) multiplies zeros
+          v4i fw = v4i{0, 0, 0, 0}, fa = v4i{0, 0, 0, 0};
+          if (k0 + koff < p.R) {
+            fw = *reinterpret_cast<const v4i *>(lw + (lane & 31) * pitch + k0 + koff);
+            fa = *reinterpret_cast<const v4i *>(sA + (lane & 31) * pitch + k0 + koff);
+          }
+          acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw, fa, acc, 0, 0, 0);
+        }
+        emit(acc, i);
+        __builtin_amdgcn_sched_barrier(0);  // one accumulator tile at a time
+      }
+      return;
+    }
+    {  // operands straight from global memory, the two 32-channel tiles one after the other
+      const int8_t *arow = p.dtlow_q + (seq0 + min(tok0 + (lane & 31), t1 - 1)) * p.lddl;
+#pragma nounroll
+      for (int i = 0; i < 2; ++i) {
+        const int8_t *wrow = p.W_dt + (size_t)min(dw0 + 32 * i + (lane & 31), p.Di - 1) * p.R;
+        v16i acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0;
+        constexpr int PH = 3;  // k steps whose operands are in flight together
+        for (int s0 = 0; s0 * 32 < p.R; s0 += PH) {
+          v4i fa[PH], fw[PH];
+#pragma unroll
+          for (int j = 0; j < PH; ++j) {
+            const int kc = 32 * (s0 + j) + koff;
+            fa[j] = fw[j] = v4i{0, 0, 0, 0};
+            if (kc < p.R) {  // R is a multiple of 16: a 16-byte piece is all in or all out
+              fa[j] = *reinterpret_cast<const v4i *>(arow + kc);
+              fw[j] = *reinterpret_cast<const v4i *>(wrow + kc);
+            }
+          }
+#pragma unroll
+          for (int j = 0; j < PH; ++j) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[j], fa[j], acc, 0, 0, 0);
+        }
+        emit(acc, i);
+      }
+    }
   };
   // rows [0, cnt) of the wave's tile -> dt_q (64 contiguous bytes per token)
   auto dt_store = [&](int tb, int cnt) {
@@ -285,14 +374,21 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_chunk_kernel(Dev p) {
   for (int tb = t0; tb < t1; tb += TB) {
     const int cnt = min(TB, t1 - tb);
     Regs ra, rb;
+    // the loads of the block's start are requested together: B / C codes and the first TS tokens
+    BCRegs bc;
+    if (!FUSE_DT) {
+      bc_load<OUTPUT>(p, seq0 + tb, cnt, bc);
+      fetch(ra, tb);
+    }
     if (FUSE_DT) {  // the tile is private to the wave: its LDS accesses execute in order
       dt_tile(tb, 0);
       if (cnt > 32) dt_tile(tb + 32, 32);
       dt_store(tb, cnt);
+      bc_load<OUTPUT>(p, seq0 + tb, cnt, bc);  // (behind the tile: in front of it they cost it a wave per SIMD in registers)
+      fetch(ra, tb);
     }
-    fetch(ra, tb);
     __syncthreads();
-    stage_bc<OUTPUT>(p, seq0 + tb, cnt, sB, sC);
+    bc_park<OUTPUT>(p, cnt, bc, sB, sC);
     __syncthreads();
     for (int ts = 0; ts < cnt; ts += 2 * TS) {
       if (ts + TS < cnt) fetch(rb, tb + ts + TS);

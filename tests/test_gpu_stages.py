@@ -345,7 +345,10 @@ def test_scan_prefill(Bt, L, Di, with_h0, scan_variant):
                                                 (1, 256, 1536, 48, False), (1, 130, 100, 80, False),
                                                 # the 2.8B layer at 2048 tokens and the Jamba-shaped one at 4096
                                                 (1, 2048, 5120, 160, False), (1, 4096, 8192, 256, True),
-                                                (9, 70, 1024, 64, True)])  # more than one sweep workgroup per CU
+                                                (9, 70, 1024, 64, True),  # more than one sweep workgroup per CU
+                                                # whole workgroups of channels and dt_rank <= 160: the chunked pass stages its
+                                                # dt_proj operands in LDS (one piece per row, an odd number of pieces, nine)
+                                                (2, 200, 256, 16, True), (1, 333, 512, 80, False), (1, 97, 768, 144, True)])
 def test_scan_prefill_with_fused_dt_proj(Bt, L, Di, R, with_h0, scan_variant):
     """dt_q computed inside the scan's first pass: bit-exact codes, same scan tolerances."""
     rng = np.random.default_rng(L * 17 + Di + R)
