@@ -895,13 +895,12 @@ __global__ __launch_bounds__(256) void scan_step_batch_kernel(Dev p, float *__re
       bw[i] = *reinterpret_cast<const unsigned *>(p.B_q + b * p.ldbc + 4 * q);
       cw[i] = *reinterpret_cast<const unsigned *>(p.C_q + b * p.ldbc + 4 * q);
     }
+    if constexpr (!PART) {
 #pragma unroll
-    for (int j = 0; j < NP; ++j) {
-      const int kc = 16 * q + 64 * j;
-      a[i][j] = v4i{0, 0, 0, 0};
-      if (kc < p.R) {
-        if constexpr (PART) a[i][j] = *reinterpret_cast<const v4i *>(&dbc[i][kc]);
-        else a[i][j] = *reinterpret_cast<const v4i *>(p.dtlow_q + b * p.lddl + kc);
+      for (int j = 0; j < NP; ++j) {
+        const int kc = 16 * q + 64 * j;
+        a[i][j] = v4i{0, 0, 0, 0};
+        if (kc < p.R) a[i][j] = *reinterpret_cast<const v4i *>(p.dtlow_q + b * p.lddl + kc);
       }
     }
   }
@@ -909,6 +908,14 @@ __global__ __launch_bounds__(256) void scan_step_batch_kernel(Dev p, float *__re
   for (int i = 0; i < BB; ++i) {
     const size_t b = static_cast<size_t>(b0 + i);
     const bool on = live && b0 + i < Bt;
+    if constexpr (PART) {  // out of LDS just before use: held for all BB sequences at once they cost a wave per SIMD
+#pragma unroll
+      for (int j = 0; j < NP; ++j) {
+        const int kc = 16 * q + 64 * j;
+        a[i][j] = v4i{0, 0, 0, 0};
+        if (kc < p.R) a[i][j] = *reinterpret_cast<const v4i *>(&dbc[i][kc]);
+      }
+    }
     int acc = 0;
 #pragma unroll
     for (int j = 0; j < NP; ++j)
